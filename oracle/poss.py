@@ -1,0 +1,163 @@
+"""The PosS round: draft a tree with position specialists, verify it with the target,
+accept greedily, commit (oracle; test infrastructure only).
+
+State after prefill / after every round: committed tokens x_0..x_t, target features
+f_0..f_{t-1} and target keys/values of positions 0..t-1.  x_t (the root of the next
+tree) has no feature yet: it is the token the target chose last.
+
+Draft position i (0-based; depth d = i+1) is served by specialist ceil((i+1)/n)
+(Eq. 7).  The specialist at depth d sees the pair sequence of Eq. 9:
+[x_1; f_0] .. [x_t; f_{t-1}] with target features, then the drafted pairs
+[token(v); f^(S)(parent(v))] along the path to the node it expands.  Pair [x_j; .]
+has drafter sequence index j-1.  This file applies each specialist to that whole
+sequence afresh (no cache): the HIP library's per-specialist key/value caches and
+catch-up passes (section 3.3, overhead (1)) must reproduce it.
+"""
+import numpy as np
+
+from .model import (target_rows, head, causal_allowed, empty_kv, specialist_pass,
+                    specialist_index)
+from .numerics import log_softmax
+from .tree import TreeBuilder, Tree, accept_walk, AcceptStats
+
+
+def topk_lowest_id(row, k):
+    """Indices of the k largest entries, ordered by (value descending, index ascending)."""
+    row = np.asarray(row)
+    order = np.lexsort((np.arange(row.size), -row))
+    return order[:k]
+
+
+class PossOracle:
+    def __init__(self, W, cfg, act=None):
+        self.W, self.cfg, self.act = W, cfg, act
+        self.tokens, self.feats, self.kv = [], [], empty_kv(cfg)
+        self.stats = AcceptStats(cfg.depth)
+        self.margins = []                 # decision gaps seen so far (screening / near-tie accounting)
+        self.last = {}
+
+    # ------------------------------------------------------------------ prefill
+    @property
+    def t(self):
+        return len(self.tokens) - 1
+
+    def prefill(self, prompt):
+        """Causal target pass over the prompt; x_P = greedy token after the prompt."""
+        cfg, P = self.cfg, len(prompt)
+        f, kv = target_rows(self.W, cfg, prompt, np.arange(P), empty_kv(cfg),
+                            causal_allowed(0, P), self.act)
+        logits = head(self.W, cfg, f[-1:], self.act)[0]
+        self._note_margin(logits)
+        self.tokens = [int(x) for x in prompt] + [int(np.argmax(logits))]
+        self.feats = [f[i] for i in range(P)]
+        self.kv = kv
+        return self.tokens[-1]
+
+    def _note_margin(self, logits):
+        top2 = np.partition(np.asarray(logits), -2)[-2:]
+        self.margins.append(float(top2[1] - top2[0]))
+
+    # ------------------------------------------------------------------ draft
+    def draft_tree(self):
+        cfg, W, t = self.cfg, self.W, self.t
+        k, L = cfg.top_k, cfg.depth
+        n, S = cfg.positions_per_specialist, cfg.n_specialists
+        # committed pairs [x_j ; f_{j-1}], j = 1..t, drafter index j-1
+        seq_tok = list(self.tokens[1:t + 1])
+        seq_feat = [self.feats[j - 1] for j in range(1, t + 1)]
+        seq_pos = list(range(t))
+        row_of = {}                      # pool index of an expanded node -> its row in seq_*
+        fhat = {}                        # pool index (-1 = root) -> drafted feature
+        tb = TreeBuilder(k, L, cfg.total_tokens)
+        dbg_logp = []
+        for d in range(1, L + 1):
+            s = specialist_index(d - 1, n, S)
+            front = tb.frontier()
+            if d == 1:
+                q_rows = [t - 1]                                   # the root pair [x_t ; f_{t-1}]
+                allowed = np.ones((1, t), dtype=bool)
+            else:
+                for v in front:
+                    row_of[v] = len(seq_tok)
+                    seq_tok.append(tb.token[v])
+                    seq_feat.append(fhat[tb.parent[v]])
+                    seq_pos.append(t - 1 + tb.depth[v])
+                q_rows = [row_of[v] for v in front]
+                allowed = np.zeros((len(front), len(seq_tok)), dtype=bool)
+                allowed[:, :t] = True
+                for r, v in enumerate(front):
+                    u = v
+                    while u != -1:                                 # v itself and its drafted ancestors
+                        allowed[r, row_of[u]] = True
+                        u = tb.parent[u]
+            out = specialist_pass(W, cfg, s, seq_tok, np.stack(seq_feat), seq_pos, allowed,
+                                  q_rows, self.act)
+            for r, v in enumerate(front):
+                fhat[v] = out[r]
+            logits = head(W, cfg, out, self.act).astype(np.float32)
+            logp = log_softmax(logits.astype(np.float64)).astype(np.float32)
+            ids = np.zeros((len(front), k), dtype=np.int64)
+            lp = np.zeros((len(front), k), dtype=np.float32)
+            for r in range(len(front)):
+                order = topk_lowest_id(logits[r], k + 1)
+                ids[r], lp[r] = order[:k], logp[r, order[:k]]
+                gaps = -np.diff(logits[r, order].astype(np.float64))
+                self.margins.append(float(gaps.min()))
+            n_before = len(tb.token)
+            tb.push(ids, lp)
+            if d < L:                    # order inside the kept frontier fixes the next candidate order
+                lvl = sorted(range(n_before, len(tb.token)), key=lambda i: (-float(tb.score[i]), i))
+                sc = np.array([float(tb.score[i]) for i in lvl[:k + 1]])
+                if len(sc) > 1:
+                    self.margins.append(float((-np.diff(sc)).min()))
+            dbg_logp.append((ids, lp))
+        tree = tb.finalize(t)
+        tree.token[0] = self.tokens[t]
+        self.margins += tb.margins
+        self.last["builder"], self.last["topk"] = tb, dbg_logp
+        return tree
+
+    # ------------------------------------------------------------------ verify
+    def verify_tree(self, tree):
+        """One target pass over all tree rows (section 2.1, second phase).
+        Returns (greedy token after each node, logits, features)."""
+        cfg, t = self.cfg, self.t
+        if tree.pos is None:
+            tree.finish(t)
+        F, new_kv = target_rows(self.W, cfg, tree.token, tree.pos, self.kv, tree.allowed(t), self.act)
+        logits = head(self.W, cfg, F, self.act)
+        g = [int(np.argmax(logits[i])) for i in range(tree.n)]
+        self.last.update(tree=tree, F=F, new_kv=new_kv, logits=logits, g=g)
+        return g, logits, F
+
+    # ------------------------------------------------------------------ accept + commit
+    def accept_and_commit(self, path=None, bonus=None):
+        """Walk, then append the accepted rows' features and keys/values and the new tokens.
+        A caller in lock-step may impose (path, bonus)."""
+        tree, F, new_kv, g = (self.last[x] for x in ("tree", "F", "new_kv", "g"))
+        if path is None:
+            path, bonus = accept_walk(tree.token, tree.parent, g)
+        for node in path:
+            self._note_margin(self.last["logits"][node])
+        m = len(path) - 1
+        for node in path:
+            self.feats.append(F[node])
+        self.kv = [(np.concatenate([kc, kn[path]], axis=0), np.concatenate([vc, vn[path]], axis=0))
+                   for (kc, vc), (kn, vn) in zip(self.kv, new_kv)]
+        self.tokens += [tree.token[p] for p in path[1:]] + [int(bonus)]
+        self.stats.add(m)
+        return list(path), m, int(bonus)
+
+    # ------------------------------------------------------------------ whole run
+    def generate(self, prompt, n_new, record=None):
+        """prefill + rounds until n_new new tokens exist; the stream is cut to exactly n_new
+        (a last round that overshoots still counts fully in the statistics)."""
+        P = len(prompt)
+        self.prefill(prompt)
+        while len(self.tokens) - P < n_new:
+            tree = self.draft_tree()
+            g, _, _ = self.verify_tree(tree)
+            path, m, bonus = self.accept_and_commit()
+            if record is not None:
+                record.append(dict(tree=tree, g=g, path=path, m=m, bonus=bonus))
+        return self.tokens[:P + n_new]

@@ -1,0 +1,164 @@
+"""The oracle's speculative round against the plain definition (vanilla greedy decoding),
+Eq. 6, and the special cases where the outcome is known in advance."""
+import numpy as np
+import pytest
+
+from synth import get_config, make_weights, make_prompt
+from synth.gen import to_storage
+from oracle.model import Weights, target_full, head, specialist_pass
+from oracle.greedy import greedy_decode
+from oracle.poss import PossOracle, topk_lowest_id
+from oracle.tree import accept_bruteforce, Tree
+
+
+def _setup(name, **kw):
+    cfg = get_config(name, **kw)
+    return cfg, Weights(cfg, make_weights(cfg))
+
+
+@pytest.mark.parametrize("name,n_prompt,n_new", [("c0_tiny_f32", 64, 32), ("t_tiny_f32_6x1", 33, 12)])
+def test_lossless_against_vanilla_greedy(name, n_prompt, n_new):
+    cfg, W = _setup(name)
+    prompt = make_prompt(cfg, n=n_prompt)
+    ref = greedy_decode(W, cfg, prompt, n_new)
+    o = PossOracle(W, cfg)
+    rec = []
+    out = o.generate(prompt, n_new, record=rec)
+    assert out == ref
+    # every round: walk == brute force, accepted set is a root path, bookkeeping adds up
+    for r in rec:
+        tr = r["tree"]
+        assert accept_bruteforce(tr.token, tr.parent, r["g"])[0] == r["path"]
+        assert tr.n == cfg.total_tokens + 1 and max(tr.depth) <= cfg.depth
+    assert o.stats.rounds == len(rec)
+    assert o.stats.committed == len(o.tokens) - n_prompt - 1
+    assert len(o.feats) == o.t == len(o.kv[0][0])
+
+
+def test_lossless_with_injected_trees_of_every_accept_length():
+    """Trees that contain the true continuation to depth m must accept exactly m."""
+    cfg, W = _setup("c0_tiny_f32")
+    prompt = make_prompt(cfg, n=20)
+    L = cfg.depth
+    ref = greedy_decode(W, cfg, prompt, L + 3)
+    y = ref[len(prompt):]                      # y[0] is the token prefill emits
+    for m in range(L + 1):
+        o = PossOracle(W, cfg)
+        assert o.prefill(prompt) == y[0]
+        # chain of the m true tokens, a wrong token after it, plus a decoy branch at the root
+        wrong = lambda tok: (tok + 1) % cfg.vocab
+        token, parent = [y[0]], [-1]
+        token.append(wrong(y[1])); parent.append(0)
+        for j in range(1, m + 1):
+            token.append(y[j]); parent.append(0 if j == 1 else len(token) - 2)
+        last = len(token) - 1 if m else 0
+        token.append(wrong(y[m + 1])); parent.append(last)
+        g, logits, F = o.verify_tree(Tree(token, parent))
+        path, mm, bonus = o.accept_and_commit()
+        assert mm == m and bonus == y[m + 1]
+        assert [token[p] for p in path[1:]] == y[1:m + 1]
+        assert o.tokens == list(prompt) + y[:m + 2]
+        # Eq. 6: Head of the target feature of a committed position is the target's own
+        # next-token distribution: compare with a plain causal pass over the committed text
+        f_full, logits_full = target_full(W, cfg, o.tokens[:-1])
+        assert np.allclose(np.stack(o.feats), f_full, rtol=1e-9, atol=1e-11)
+        assert np.allclose(logits[path], logits_full[len(prompt):], rtol=1e-9, atol=1e-11)
+
+
+def test_depth_one_uses_target_features_only():
+    """Eq. 2 at k = 1 is Eq. 1: the first draft distribution is Head of specialist 1 applied to
+    the committed [x_j ; f^(T)_{j-1}] pairs, and the root's children are its top-k."""
+    cfg, W = _setup("c0_tiny_f32")
+    prompt = make_prompt(cfg, n=17)
+    o = PossOracle(W, cfg)
+    o.prefill(prompt)
+    tree = o.draft_tree()
+    t = o.t
+    out = specialist_pass(W, cfg, 0, o.tokens[1:t + 1], np.stack(o.feats[:t]), np.arange(t),
+                          np.ones((1, t), bool), [t - 1])
+    logits = head(W, cfg, out)[0]
+    want = topk_lowest_id(logits.astype(np.float32), cfg.top_k).tolist()
+    tb = o.last["builder"]
+    assert tb.token[:cfg.top_k] == want
+    kids = [tree.token[i] for i in range(1, tree.n) if tree.parent[i] == 0]
+    assert set(kids) <= set(want)
+
+
+def _perfect_drafter_weights(cfg):
+    """Target reduced to a per-token map and every specialist made a copy of it.  The head is
+    scaled up so that the next-token distributions are peaked: then the greedy chain has the
+    highest cumulative score at every depth and cannot fall out of the width-k frontier."""
+    from synth.gen import to_float64
+    st = make_weights(cfg)
+    st["lm_head"] = to_storage(100.0 * to_float64(st["lm_head"], cfg.dtype), cfg.dtype)
+    z = lambda a: to_storage(np.zeros(a.shape), cfg.dtype)
+    d = cfg.d_model
+    for l in range(cfg.n_layers):
+        st[f"layer{l}.wo"] = z(st[f"layer{l}.wo"])                  # attention adds nothing
+        if l > 0:
+            st[f"layer{l}.w_down"] = z(st[f"layer{l}.w_down"])      # later layers are the identity
+    for s in range(cfg.n_specialists):
+        fc = np.zeros((d, 2 * d)); fc[:, :d] = np.eye(d)            # picks the embedding half of [x ; f]
+        st[f"spec{s}.fc_w"] = to_storage(fc, cfg.dtype)
+        st[f"spec{s}.fc_b"] = z(st[f"spec{s}.fc_b"])
+        for nm in ("attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "w_gate", "w_up", "w_down"):
+            st[f"spec{s}.{nm}"] = st[f"layer0.{nm}"].copy()
+    return st
+
+
+def test_perfect_drafter_accepts_full_depth():
+    cfg = get_config("c0_tiny_f32")
+    W = Weights(cfg, _perfect_drafter_weights(cfg))
+    prompt = make_prompt(cfg, n=16)
+    o = PossOracle(W, cfg)
+    rec = []
+    out = o.generate(prompt, 3 * (cfg.depth + 1), record=rec)
+    assert out == greedy_decode(W, cfg, prompt, 3 * (cfg.depth + 1))
+    assert [r["m"] for r in rec] == [cfg.depth] * 3
+    assert o.stats.tau_acc == cfg.depth and o.stats.tau_gen == cfg.depth + 1
+    assert all(o.stats.pos_acc(i) == 1.0 for i in range(2, cfg.depth + 1))
+    assert o.stats.p_accept(1) == 1.0
+
+
+def test_random_drafter_accepts_almost_nothing():
+    cfg, W = _setup("c0_tiny_f32")
+    o = PossOracle(W, cfg)
+    o.generate(make_prompt(cfg, n=32), 12)
+    assert o.stats.tau_acc < 0.5 and 1.0 <= o.stats.tau_gen < 1.5
+
+
+def test_identical_specialists_equal_single_draft_model():
+    """A single draft model is the limit n -> infinity (appendix D): S copies of one specialist
+    must draft exactly what S = 1 drafts."""
+    cfg3 = get_config("c0_tiny_f32")
+    st = make_weights(cfg3)
+    for s in (1, 2):
+        for k in list(st):
+            if k.startswith("spec0."):
+                st[k.replace("spec0.", f"spec{s}.")] = st[k].copy()
+    cfg1 = cfg3.with_(n_specialists=1, positions_per_specialist=cfg3.depth)
+    prompt = make_prompt(cfg3, n=25)
+    a, b = PossOracle(Weights(cfg3, st), cfg3), PossOracle(Weights(cfg1, st), cfg1)
+    a.prefill(prompt); b.prefill(prompt)
+    ta, tb = a.draft_tree(), b.draft_tree()
+    assert ta.token == tb.token and ta.parent == tb.parent
+    assert np.array_equal(np.array(ta.score), np.array(tb.score))
+    # and distinct specialists really are dispatched by depth: different weights, different tree
+    c = PossOracle(Weights(cfg3, make_weights(cfg3)), cfg3)
+    c.prefill(prompt)
+    tc = c.draft_tree()
+    assert [tc.token[i] for i in range(1, tc.n) if tc.depth[i] == 1] == \
+           [ta.token[i] for i in range(1, ta.n) if ta.depth[i] == 1]      # specialist 1 is shared
+    assert tc.token != ta.token                                            # deeper levels differ
+
+
+def test_mixed_precision_mode_is_lossless_too():
+    cfg = get_config("c0_tiny_f32", dtype=1)
+    W = Weights(cfg, make_weights(cfg))
+    prompt = make_prompt(cfg, n=24)
+    ref = greedy_decode(W, cfg, prompt, 10, act=1)
+    assert PossOracle(W, cfg, act=1).generate(prompt, 10) == ref
+    # rounding the activations moves the logits by about the bf16 step, not more
+    _, exact = target_full(W, cfg, prompt)
+    _, mixed = target_full(W, cfg, prompt, act=1)
+    assert 1e-5 < np.abs(exact - mixed).max() < 2e-2
