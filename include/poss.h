@@ -1,0 +1,194 @@
+/* poss.h - C ABI of the MI355X (gfx950) PosS draft-and-verify library.
+ *
+ * One round of position-specialist speculative decoding (arXiv 2506.03566) at
+ * batch 1 under greedy verification:
+ *
+ *   poss_load -> poss_prefill -> ( poss_draft_tree -> poss_verify_tree
+ *                                  -> poss_accept_and_commit )*
+ *
+ * Every step runs in hand-written HIP kernels of this library.  All pointers
+ * are plain addresses; each argument says whether it is HOST or DEVICE memory.
+ * The library never allocates device memory: weights, the workspace and the
+ * stream belong to the caller.  Calls enqueue work on the stream given to
+ * poss_load and block only to hand back their (small) host outputs.
+ *
+ * Every function returning int returns POSS_OK (0) or a negative POSS_E_*
+ * code; a failing call leaves the context as it was and poss_last_error()
+ * describes the failure.  Calls on one context must not overlap.
+ *
+ * Notation (paper): target model theta_T with last-layer hidden state
+ * ("feature") f^(T); S position specialists theta_S^1..S, each serving n draft
+ * positions (PosS-n); prediction depth L; tree width k; N draft tokens kept
+ * per round; t = index of the last committed token x_t (the tree root).
+ */
+#ifndef POSS_H
+#define POSS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define POSS_OK             0
+#define POSS_E_INVALID_ARG -1   /* null pointer, shape the kernels do not support     */
+#define POSS_E_BAD_STATE   -2   /* call out of order                                  */
+#define POSS_E_CAPACITY    -3   /* sequence, tree or workspace larger than configured */
+#define POSS_E_BAD_TREE    -4   /* caller-supplied tree is not a valid draft tree     */
+#define POSS_E_HIP         -5   /* a HIP runtime call failed                          */
+
+#define POSS_DTYPE_F32  0
+#define POSS_DTYPE_BF16 1
+#define POSS_DTYPE_F16  2
+
+#define POSS_MAX_ROWS   128     /* rows one pass can carry: tree rows, prefill chunk  */
+#define POSS_MASK_WORDS 2       /* 64-bit words of one ancestor mask                  */
+#define POSS_MAX_DEPTH  16
+
+typedef struct poss_ctx poss_ctx;           /* opaque; created by poss_load, host memory */
+
+/* Shapes.  Target: Llama-style decoder (section 4.1 "Target Models").  Drafter:
+ * n_specialists layers of the target's layer shape, each preceded by an fc
+ * projection 2*d_model -> d_model over [token embedding ; feature] (section 2.2,
+ * Eq. 1; section 3.2).  Draft position i (0-based) is served by specialist
+ * min(i / positions_per_specialist, n_specialists - 1)  (Eq. 7; the clamp is this
+ * library's reading for depths beyond S*n).  Tree: section 4.1 "Implementations"
+ * (width = top_k, depth, total_tokens = draft nodes kept, root not counted).
+ * dtype is the storage type of weights, GEMM operands and KV caches; accumulation,
+ * the residual stream, softmax, norms and logits are float32. */
+typedef struct poss_config {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float   rms_eps, rope_theta;
+    int32_t dtype;                           /* POSS_DTYPE_*                               */
+    int32_t n_specialists, positions_per_specialist, fc_bias;
+    int32_t top_k, depth, total_tokens;
+    int32_t max_seq;                         /* capacity in committed tokens (multiple of kv_page_tokens) */
+    int32_t kv_page_tokens;                  /* tokens per KV page: 32, 64 or 128           */
+    int32_t kv_page_order;                   /* 0: pages in order; 1: physical pages reversed (layout tests) */
+} poss_config;
+
+/* Weights: DEVICE pointers to row-major [out, in] tensors of `dtype`.
+ * layer[l*9 + j], j = attn_norm[d], wq[Hq*dh,d], wk[Hkv*dh,d], wv[Hkv*dh,d], wo[d,Hq*dh],
+ *                     mlp_norm[d], w_gate[F,d], w_up[F,d], w_down[d,F].
+ * spec[s*11 + j], j = fc_w[d,2d] (input columns ordered [embedding ; feature]), fc_b[d],
+ *                     then the 9 layer tensors.  The arrays of pointers are HOST memory.
+ * poss_load repacks everything into the workspace; the caller may free its copies after. */
+typedef struct poss_weights {
+    const void *embed;        /* [vocab, d]  token embedding, shared by target and drafter */
+    const void *lm_head;      /* [vocab, d]  shared LM head (section 2.2)                  */
+    const void *final_norm;   /* [d]         final RMSNorm gain (part of Head)             */
+    const void *const *layer;
+    const void *const *spec;
+} poss_weights;
+
+/* A draft tree in HOST memory, arrays of capacity >= total_tokens + 1 owned by the caller.
+ * Node 0 is the root x_t.  parent[0] = -1, parent[i] < i.  pos[i] = t + depth[i].
+ * mask[i*POSS_MASK_WORDS + w]: bit j of the concatenated words is set iff node j is node i
+ * or an ancestor of it.  score[i]: sum of drafter log-probabilities on the path (0 for the
+ * root).  As input to poss_verify_tree only n_nodes, token[1..] and parent are read. */
+typedef struct poss_tree {
+    int32_t   n_nodes;
+    int32_t  *token, *parent, *depth, *pos;
+    uint64_t *mask;
+    float    *score;
+} poss_tree;
+
+/* Acceptance statistics (section 3.1): c[i] = rounds that accepted at least i draft tokens,
+ * so P(A_i) = c[i]/rounds, pos-acc_i = c[i]/c[i-1] (Eq. 3), and the mean number of accepted
+ * draft tokens per round is sum_i c[i] / rounds (Eq. 4 summed over k).  Times are HIP-event
+ * milliseconds summed over rounds. */
+typedef struct poss_stats {
+    int64_t rounds, committed_tokens;
+    int64_t c[POSS_MAX_DEPTH + 1];
+    double  ms_draft, ms_verify, ms_commit;
+} poss_stats;
+
+/* Bytes of DEVICE workspace poss_load needs for this configuration (0 if it is invalid). */
+size_t poss_workspace_bytes(const poss_config *cfg);
+
+/* Create a context.  cfg, w: HOST structs (w's tensors DEVICE).  workspace: DEVICE memory of
+ * at least poss_workspace_bytes(cfg) bytes, 256-byte aligned, owned by the caller and kept
+ * alive until poss_free.  hip_stream: a hipStream_t (NULL = default stream).  *out receives
+ * the context.  Repacks the weights into MFMA operand order and zeroes the KV caches. */
+int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace,
+              size_t workspace_bytes, void *hip_stream, poss_ctx **out);
+
+/* Forget the sequence (back to the state after poss_load); statistics are cleared. */
+int poss_reset(poss_ctx *ctx);
+
+/* Causal target pass over the prompt (HOST int32 ids, 1 <= n_prompt, n_prompt + 1 <= max_seq),
+ * then every specialist's keys/values for the pairs [x_j ; f_{j-1}], j = 1..n_prompt-1
+ * (section 3.3: specialists do not share a cache).  *first_token_out = x_P, the target's greedy
+ * token after the prompt; it becomes the root of the first tree. */
+int poss_prefill(poss_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out);
+
+/* Draft phase (section 6.2): `depth` specialist passes expand the tree level by level; the
+ * total_tokens best candidates by cumulative log-probability form the tree.  out (HOST, may be
+ * NULL) receives it; it also stays on the device for poss_verify_tree(ctx, NULL, ..). */
+int poss_draft_tree(poss_ctx *ctx, poss_tree *out);
+
+/* Verification phase (section 2.1): one target pass over all tree rows with tree position ids
+ * and the ancestor mask.  tree: HOST, or NULL for the tree drafted last.  argmax_out (HOST,
+ * int32[n_nodes], may be NULL): the target's greedy token after each node, lowest id on ties.
+ * logits_out (DEVICE float32 [n_nodes, vocab], may be NULL) and feat_out (DEVICE float32
+ * [n_nodes, d_model], may be NULL) receive Head(f) and f of every row (Eq. 6). */
+int poss_verify_tree(poss_ctx *ctx, const poss_tree *tree, int32_t *argmax_out,
+                     void *logits_out, void *feat_out);
+
+/* Greedy acceptance (section 2.1, section 3.1: A_i subset of A_{i-1}) and commit.  Walks from
+ * the root to the child whose token equals the target's greedy token, as long as there is one;
+ * moves the accepted rows' keys/values to positions t.., keeps their features for the next
+ * draft, appends the accepted tokens and the bonus token (the target's choice after the last
+ * accepted node).  All outputs HOST, any may be NULL: path_idx_out[depth+1] node indices starting
+ * with 0; *n_accepted_out = m; committed_out[depth+1] the m+1 new tokens; *n_committed_out = m+1. */
+int poss_accept_and_commit(poss_ctx *ctx, int32_t *path_idx_out, int32_t *n_accepted_out,
+                           int32_t *committed_out, int32_t *n_committed_out);
+
+int poss_get_stats(poss_ctx *ctx, poss_stats *out);
+/* Number of committed tokens (prompt included); tokens_out (HOST, may be NULL) of capacity cap. */
+int poss_get_tokens(poss_ctx *ctx, int32_t *tokens_out, int32_t cap, int32_t *n_out);
+const char *poss_last_error(poss_ctx *ctx);       /* ctx may be NULL: last poss_load error */
+void poss_free(poss_ctx *ctx);
+
+/* ---- instrumentation -------------------------------------------------------------------- */
+
+/* Per-kernel timing of the weight-streaming GEMM (the kernel that carries the round's bytes).
+ * enable != 0: every launch is bracketed by HIP events on the library's stream (slows the round
+ * slightly: use a pass of its own).  poss_gemm_profile sums the launches since the last call:
+ * count, milliseconds, and algorithmic bytes (each launch's weight matrix once, in storage
+ * dtype). */
+int poss_profile_gemm(poss_ctx *ctx, int32_t enable);
+int poss_gemm_profile(poss_ctx *ctx, int64_t *launches, double *ms, double *weight_bytes);
+
+/* Tuning knobs for sweeps: target number of workgroups per GEMM launch (0 = default). */
+int poss_set_tuning(poss_ctx *ctx, int32_t gemm_target_workgroups, int32_t attn_keys_per_split);
+
+/* ---- test hooks (same kernels, inputs injected) ----------------------------------------- */
+
+/* Tree builder alone: ids/logp are HOST arrays [depth][top_k][top_k]: for the pass at depth
+ * d (0-based index d-1) and frontier row r, the top_k child tokens in rank order and their
+ * float32 log-probabilities (at depth 1 only row 0 is read).  Needs a prefilled context (for
+ * t); does not touch the drafter caches. */
+int poss_debug_build_tree(poss_ctx *ctx, const int32_t *ids, const float *logp, poss_tree *out);
+
+/* Copy target residual streams of the last target pass: DEVICE float32
+ * [n_layers + 1][rows][d_model] (entry l = input of layer l; last = features). */
+int poss_debug_set_taps(poss_ctx *ctx, void *taps_dev_or_null);
+
+/* Read keys/values of logical slots [slot0, slot0+n) of one cache into HOST float32 arrays
+ * [n][n_kv_heads][head_dim].  which = -1: target layer `layer`; which = s >= 0: specialist s. */
+int poss_debug_read_kv(poss_ctx *ctx, int32_t which, int32_t layer, int32_t slot0, int32_t n,
+                       float *k_out, float *v_out);
+
+/* Y[M, N] (DEVICE float32) = X[M, K] . W[N, K]^T through the library's GEMM path; X and W DEVICE
+ * row-major of `dtype`; scratch DEVICE of at least poss_debug_gemm_scratch_bytes bytes. */
+size_t poss_debug_gemm_scratch_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K);
+int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_t M, int32_t N,
+                    int32_t K, int32_t target_workgroups, void *scratch, void *hip_stream,
+                    int32_t repeats, float *ms_per_launch_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POSS_H */

@@ -1,0 +1,821 @@
+// Host side of the C ABI (include/poss.h): context, workspace carving, weight repacking, the pass
+// schedules of prefill / draft / verify / accept-and-commit.  No arithmetic of the method happens
+// here: every step is a kernel launch on the caller's stream.
+#include "../../include/poss.h"
+#include "common.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+using namespace poss;
+
+namespace {
+
+char g_load_error[512] = "";
+
+struct LayerW { const void *attn_norm, *wqkv, *wo, *mlp_norm, *wgu, *wdown; };
+struct SpecW  { const void *fc_w, *fc_b; LayerW layer; };
+
+// Bump allocator over the caller's workspace; with base == nullptr it only measures.
+struct Arena {
+    char *base; size_t off = 0;
+    explicit Arena(void *b) : base(static_cast<char *>(b)) {}
+    void *take(size_t bytes) {
+        off = (off + 255) / 256 * 256;
+        void *p = base ? base + off : nullptr;
+        off += bytes;
+        return p;
+    }
+    template <typename T> T *take_n(size_t n) { return static_cast<T *>(take(n * sizeof(T))); }
+};
+
+enum { ST_LOADED = 0, ST_READY = 1, ST_VERIFIED = 2 };
+constexpr int PROFILE_EVENTS = 1024;
+
+}  // namespace
+
+struct poss_ctx {
+    poss_config cfg;
+    ModelDims md;
+    hipStream_t st;
+    char err[512];
+    // weights (workspace)
+    const void *embed, *lm_head, *final_norm;
+    std::vector<LayerW> layers;
+    std::vector<SpecW> specs;
+    // caches
+    int cache_slots, n_pages;
+    int32_t *page_table;
+    std::vector<KVCache> target_kv, spec_kv;
+    KVCache *target_kv_dev;
+    size_t cache_bytes_each;
+    // activations
+    float *h, *part, *logits, *feats, *fhat[2], *topk_scratch, *taps_user;
+    void *u, *xin, *q, *attn_out, *act;
+    AttnScratch attn_sc;
+    int32_t *row_pos, *row_slot, *tree_slot;
+    uint64_t *row_mask;
+    TreeDev td;
+    int32_t *tokens_dev, *argmax_dev, *walk_dev;
+    void *feat_stash, *xin_tmp;
+    double *inv_freq;
+    // host state
+    int state, t, tree_ready, tree_n;
+    std::vector<int32_t> tokens;
+    std::vector<int> spec_len, spec_tmp_depth;
+    poss_stats stats;
+    void *pinned; size_t pinned_bytes;
+    hipEvent_t ev0, ev1;
+    int gemm_target_wgs, attn_keys_per_split;
+    // gemm profiling
+    int prof_on, prof_n;
+    hipEvent_t prof_ev[2 * PROFILE_EVENTS];
+    double prof_bytes;
+    int64_t prof_launches; double prof_ms;
+};
+
+namespace {
+
+int fail(poss_ctx *c, int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(c ? c->err : g_load_error, 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(c, call)                                                                        \
+    do {                                                                                        \
+        hipError_t e_ = (call);                                                                 \
+        if (e_ != hipSuccess) return fail(c, POSS_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+const char *check_config(const poss_config &c) {
+    if (c.n_layers < 1 || c.d_model < 8 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.d_ffn < 8 || c.vocab < 2)
+        return "non-positive model dimension";
+    if (c.dtype < 0 || c.dtype > 2) return "dtype must be 0 (f32), 1 (bf16) or 2 (f16)";
+    if (c.n_q_heads % c.n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
+    if (c.dtype != POSS_DTYPE_F32 && c.head_dim != 64 && c.head_dim != 128)
+        return "16-bit kernels support head_dim 64 or 128";
+    if (c.head_dim < 2 || c.head_dim > 256 || (c.head_dim & 1)) return "head_dim must be even and <= 256";
+    if (c.dtype != POSS_DTYPE_F32 && ((c.d_model % 8) || (c.d_ffn % 8))) return "16-bit kernels need d_model, d_ffn multiples of 8";
+    if (c.n_specialists < 1 || c.positions_per_specialist < 1) return "need at least one specialist and one position each";
+    if (c.top_k < 1 || c.top_k > 16 || c.top_k >= c.vocab) return "top_k must be in 1..16 and below vocab";
+    if (c.depth < 1 || c.depth > POSS_MAX_DEPTH) return "depth must be in 1..16";
+    const int pool = c.top_k + (c.depth - 1) * c.top_k * c.top_k;
+    if (c.total_tokens < 1 || c.total_tokens + 1 > POSS_MAX_ROWS) return "total_tokens must be in 1..127";
+    if (c.total_tokens > pool) return "total_tokens exceeds the candidate pool k + (depth-1) k^2";
+    if (pool > 2048) return "candidate pool too large";
+    if ((c.depth - 1) * c.top_k > 64 * POSS_MASK_WORDS) return "(depth-1)*top_k must fit the 128-bit ancestor mask";
+    if (c.top_k + (c.depth + 1) + (c.depth - 1) * c.top_k > POSS_MAX_ROWS) return "a specialist pass would exceed 128 rows";
+    if (c.kv_page_tokens != 32 && c.kv_page_tokens != 64 && c.kv_page_tokens != 128) return "kv_page_tokens must be 32, 64 or 128";
+    if (c.max_seq < 2 || c.max_seq % c.kv_page_tokens) return "max_seq must be a positive multiple of kv_page_tokens";
+    if (c.kv_page_order < 0 || c.kv_page_order > 1) return "kv_page_order must be 0 or 1";
+    if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return "rms_eps / rope_theta out of range";
+    return nullptr;
+}
+
+size_t esize(const poss_config &c) { return dtype_size(c.dtype); }
+
+// Lays every buffer out in the arena (measuring when it has no base) and, if ctx != nullptr,
+// records the addresses.  Weight destinations are returned through ctx as well.
+struct WeightSlots {
+    void *embed, *lm_head, *final_norm;
+    std::vector<void *> layer;   // [n_layers][6]: attn_norm, wqkv, wo, mlp_norm, wgu, wdown
+    std::vector<void *> spec;    // [S][8]: fc_w, fc_b, then the 6
+};
+
+size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
+    const int dt = c.dtype;
+    const size_t es = esize(c);
+    const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kd = c.n_kv_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
+    const int tw = 0;
+    auto layer_slots = [&](std::vector<void *> &out) {
+        out.push_back(a.take(d * es));
+        out.push_back(a.take(packed_elems(dt, qd + 2 * kd, d) * es));
+        out.push_back(a.take(packed_elems(dt, d, qd) * es));
+        out.push_back(a.take(d * es));
+        out.push_back(a.take(packed_elems(dt, 2 * F, d) * es));
+        out.push_back(a.take(packed_elems(dt, d, F) * es));
+    };
+    WeightSlots local;
+    WeightSlots &w = ws ? *ws : local;
+    w.embed = a.take((size_t)V * d * es);
+    w.lm_head = a.take(packed_elems(dt, V, d) * es);
+    w.final_norm = a.take(d * es);
+    for (int l = 0; l < c.n_layers; ++l) layer_slots(w.layer);
+    for (int s = 0; s < c.n_specialists; ++s) {
+        w.spec.push_back(a.take(packed_elems(dt, d, 2 * d) * es));
+        w.spec.push_back(a.take(d * es));
+        layer_slots(w.spec);
+    }
+    // caches
+    const int P = c.kv_page_tokens;
+    const int slots = round_up(c.max_seq + MAX_ROWS, P), pages = slots / P;
+    const size_t cache_each = (size_t)pages * c.n_kv_heads * P * c.head_dim * es;
+    int32_t *pt = a.take_n<int32_t>(pages);
+    std::vector<void *> kvp;
+    for (int i = 0; i < 2 * (c.n_layers + c.n_specialists); ++i) kvp.push_back(a.take(cache_each));
+    KVCache *kv_dev = a.take_n<KVCache>(c.n_layers);
+    // activations
+    const int R = MAX_ROWS;
+    size_t part_floats = 0;
+    const int shapes[6][2] = {{qd + 2 * kd, d}, {d, qd}, {2 * F, d}, {d, F}, {d, 2 * d}, {V, d}};
+    for (int i = 0; i < 5; ++i) {
+        // split count does not depend on M; planes are at most R rows
+        GemmShape g = gemm_plan(dt, R, shapes[i][0], shapes[i][1], 4096);   // upper bound on splits
+        const size_t f = (size_t)g.S * R * g.Npad;
+        if (f > part_floats) part_floats = f;
+    }
+    float *h = a.take_n<float>((size_t)R * d);
+    float *part = a.take_n<float>(part_floats);
+    float *logits = a.take_n<float>((size_t)R * gemm_npad(V));
+    float *feats = a.take_n<float>((size_t)R * d);
+    float *fhat0 = a.take_n<float>((size_t)16 * d), *fhat1 = a.take_n<float>((size_t)16 * d);
+    float *topk_scr = a.take_n<float>(topk_scratch_floats(16, V));
+    void *u = a.take((size_t)R * d * es), *xin = a.take((size_t)R * 2 * d * es);
+    void *q = a.take((size_t)R * qd * es), *ao = a.take((size_t)R * qd * es), *act = a.take((size_t)R * F * es);
+    const int G = c.n_q_heads / c.n_kv_heads;
+    const int rho_pad = round_up(R * G, 16);
+    const int max_splits = attention_splits(slots, 128);
+    float *ao_part = a.take_n<float>((size_t)max_splits * c.n_kv_heads * rho_pad * c.head_dim);
+    float *ml_part = a.take_n<float>((size_t)max_splits * c.n_kv_heads * rho_pad * 2);
+    int32_t *row_pos = a.take_n<int32_t>(R), *row_slot = a.take_n<int32_t>(R), *tree_slot = a.take_n<int32_t>(R);
+    uint64_t *row_mask = a.take_n<uint64_t>((size_t)R * MASK_WORDS);
+    // tree
+    const int k = c.top_k, L = c.depth, pool = k + (L - 1) * k * k;
+    TreeDev td;
+    td.pool_token = a.take_n<int32_t>(pool); td.pool_parent = a.take_n<int32_t>(pool);
+    td.pool_depth = a.take_n<int32_t>(pool); td.pool_score = a.take_n<float>(pool);
+    td.fr_pool = a.take_n<int32_t>((L + 1) * k); td.fr_token = a.take_n<int32_t>((L + 1) * k);
+    td.fr_parent_rank = a.take_n<int32_t>((L + 1) * k); td.fr_score = a.take_n<float>((L + 1) * k);
+    td.fr_mask = a.take_n<uint64_t>((size_t)(L + 1) * k * MASK_WORDS);
+    td.topk_id = a.take_n<int32_t>(16 * 16); td.topk_logp = a.take_n<float>(16 * 16);
+    td.n_nodes = a.take_n<int32_t>(4); td.token = a.take_n<int32_t>(R); td.parent = a.take_n<int32_t>(R);
+    td.depth = a.take_n<int32_t>(R); td.pos = a.take_n<int32_t>(R);
+    td.mask = a.take_n<uint64_t>((size_t)R * MASK_WORDS); td.score = a.take_n<float>(R);
+    int32_t *tokens_dev = a.take_n<int32_t>(slots + 8);
+    int32_t *argmax_dev = a.take_n<int32_t>(R), *walk_dev = a.take_n<int32_t>(POSS_MAX_DEPTH + 4);
+    void *stash = a.take((size_t)slots * d * es);
+    void *xin_tmp = a.take((size_t)MAX_ROWS * 2 * d * es);
+    double *inv_freq = a.take_n<double>(c.head_dim / 2);
+    (void)tw;
+    if (ctx) {
+        ctx->cache_slots = slots; ctx->n_pages = pages; ctx->page_table = pt; ctx->cache_bytes_each = cache_each;
+        const int shift = P == 32 ? 5 : P == 64 ? 6 : 7;
+        for (int l = 0; l < c.n_layers; ++l) ctx->target_kv.push_back(KVCache{kvp[2 * l], kvp[2 * l + 1], pt, shift});
+        for (int s = 0; s < c.n_specialists; ++s)
+            ctx->spec_kv.push_back(KVCache{kvp[2 * (c.n_layers + s)], kvp[2 * (c.n_layers + s) + 1], pt, shift});
+        ctx->target_kv_dev = kv_dev;
+        ctx->h = h; ctx->part = part; ctx->logits = logits; ctx->feats = feats; ctx->fhat[0] = fhat0; ctx->fhat[1] = fhat1;
+        ctx->topk_scratch = topk_scr; ctx->u = u; ctx->xin = xin; ctx->q = q; ctx->attn_out = ao; ctx->act = act;
+        ctx->attn_sc = AttnScratch{ao_part, ml_part};
+        ctx->row_pos = row_pos; ctx->row_slot = row_slot; ctx->tree_slot = tree_slot; ctx->row_mask = row_mask;
+        ctx->td = td; ctx->tokens_dev = tokens_dev; ctx->argmax_dev = argmax_dev; ctx->walk_dev = walk_dev;
+        ctx->feat_stash = stash; ctx->xin_tmp = xin_tmp; ctx->inv_freq = inv_freq;
+    }
+    return a.off + 256;
+}
+
+// ------------------------------------------------------------------------------------------ GEMM wrapper
+GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int ldx, int M, float *part,
+                   bool single_split) {
+    GemmShape g = gemm_plan(c->md.dt, M, N, K, single_split ? 1 : c->gemm_target_wgs);
+    const bool prof = c->prof_on && c->prof_n < PROFILE_EVENTS;
+    if (prof) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->st);
+    launch_gemm(c->md.dt, g, Wp, X, ldx, part, c->st);
+    if (prof) {
+        (void)hipEventRecord(c->prof_ev[2 * c->prof_n + 1], c->st);
+        ++c->prof_n;
+        c->prof_bytes += (double)N * K * dtype_size(c->md.dt);
+    }
+    return g;
+}
+
+// One decoder layer on rows_all rows (all produce K/V) of which the first rows_q go through
+// attention and the MLP.  On entry c->u holds T(rmsnorm(h) * attn_norm); on exit c->h is updated and
+// c->u holds T(rmsnorm(h) * next_gain).
+void run_layer(poss_ctx *c, const LayerW &w, const KVCache &kv, int rows_all, int rows_q, const RowMeta &rm,
+               int n_prefix, int region_len, const void *next_gain, float *h_copy) {
+    const ModelDims &md = c->md;
+    const int qd = md.hq * md.dh, kd = md.hkv * md.dh;
+    GemmShape g = run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false);
+    launch_reduce_rope_kv(md, g, c->part, rows_all, rows_q, rm, c->inv_freq, c->q, kv, c->st);
+    if (rows_q == 0) return;
+    launch_attention(md, c->q, rows_q, rm, n_prefix, region_len, kv, c->attn_keys_per_split, c->attn_sc,
+                     c->attn_out, c->st);
+    g = run_gemm(c, w.wo, md.d, qd, c->attn_out, qd, rows_q, c->part, false);
+    launch_reduce_res_norm(md, g, c->part, rows_q, true, nullptr, w.mlp_norm, c->h, c->u, nullptr, c->st);
+    g = run_gemm(c, w.wgu, 2 * md.ffn, md.d, c->u, md.d, rows_q, c->part, false);
+    launch_reduce_silu(md, g, c->part, rows_q, c->act, c->st);
+    g = run_gemm(c, w.wdown, md.d, md.ffn, c->act, md.ffn, rows_q, c->part, false);
+    launch_reduce_res_norm(md, g, c->part, rows_q, true, nullptr, next_gain, c->h, c->u, h_copy, c->st);
+}
+
+// Target pass over `rows` rows whose tokens / metadata are on the device.  Leaves features in
+// c->feats and T(rmsnorm_final(features)) in c->u.
+void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowMeta &rm, int n_prefix,
+                    int region_len) {
+    const ModelDims &md = c->md;
+    launch_embed_norm(md, c->embed, tokens_dev, rows, c->layers[0].attn_norm, c->h, c->u, c->st);
+    const int nl = c->cfg.n_layers;
+    for (int l = 0; l < nl; ++l) {
+        if (c->taps_user)
+            launch_copy_rows_f32(c->h, md.d, c->taps_user + (size_t)l * rows * md.d, md.d, rows, md.d, c->st);
+        const void *next_gain = l + 1 < nl ? c->layers[l + 1].attn_norm : c->final_norm;
+        run_layer(c, c->layers[l], c->target_kv[l], rows, rows, rm, n_prefix, region_len, next_gain,
+                  l + 1 == nl ? c->feats : nullptr);
+    }
+    if (c->taps_user)
+        launch_copy_rows_f32(c->h, md.d, c->taps_user + (size_t)nl * rows * md.d, md.d, rows, md.d, c->st);
+}
+
+// logits[rows][Npad] = Head(features) for the rows whose final-normed activations are in c->u
+GemmShape run_head(poss_ctx *c, int rows) {
+    return run_gemm(c, c->lm_head, c->md.vocab, c->md.d, c->u, c->md.d, rows, c->logits, true);
+}
+
+__global__ void causal_meta_kernel(int n, int c0, int32_t *pos, int32_t *slot, uint64_t *mask) {
+    const int i = threadIdx.x;
+    if (i >= n) return;
+    pos[i] = c0 + i; slot[i] = c0 + i;
+    const int bits = i + 1;
+    mask[i * MASK_WORDS] = bits >= 64 ? ~0ull : ((1ull << bits) - 1);
+    mask[i * MASK_WORDS + 1] = bits <= 64 ? 0ull : (bits >= 128 ? ~0ull : ((1ull << (bits - 64)) - 1));
+}
+
+template <typename T>
+__global__ void stash_rows_kernel(const float *__restrict__ feats, int d, T *__restrict__ stash, int row0) {
+    const int r = blockIdx.x;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) stash[(size_t)(row0 + r) * d + i] = (T)feats[(size_t)r * d + i];
+}
+
+void stash_rows(poss_ctx *c, int rows, int row0) {
+    if (c->md.dt == DT_F32)
+        hipLaunchKernelGGL((stash_rows_kernel<float>), dim3(rows), dim3(256), 0, c->st, c->feats, c->md.d, (float *)c->feat_stash, row0);
+    else if (c->md.dt == DT_BF16)
+        hipLaunchKernelGGL((stash_rows_kernel<bf16_t>), dim3(rows), dim3(256), 0, c->st, c->feats, c->md.d, (bf16_t *)c->feat_stash, row0);
+    else
+        hipLaunchKernelGGL((stash_rows_kernel<f16_t>), dim3(rows), dim3(256), 0, c->st, c->feats, c->md.d, (f16_t *)c->feat_stash, row0);
+}
+
+uint64_t ones(int bits) { return bits <= 0 ? 0ull : bits >= 64 ? ~0ull : ((1ull << bits) - 1); }
+
+// One specialist pass over the rows of `plan` (the first rows_q of them full rows).
+void spec_pass(poss_ctx *c, int s, const DraftRowPlan &plan, int depth_index, int rows_q, int n_prefix,
+               int region_len, const float *fhat_prev, float *fhat_out) {
+    const ModelDims &md = c->md;
+    const SpecW &w = c->specs[s];
+    launch_draft_assemble(md, plan, depth_index, c->cfg.top_k, c->embed, c->tokens_dev, c->feat_stash, c->td,
+                          fhat_prev, c->xin_tmp, c->xin, c->row_pos, c->row_slot, c->row_mask, c->st);
+    GemmShape g = run_gemm(c, w.fc_w, md.d, 2 * md.d, c->xin, 2 * md.d, plan.n_rows, c->part, false);
+    launch_reduce_res_norm(md, g, c->part, plan.n_rows, false, c->cfg.fc_bias ? w.fc_b : nullptr, w.layer.attn_norm,
+                           c->h, c->u, nullptr, c->st);
+    RowMeta rm{c->row_pos, c->row_slot, c->row_mask};
+    run_layer(c, w.layer, c->spec_kv[s], plan.n_rows, rows_q, rm, n_prefix, region_len, c->final_norm, fhat_out);
+}
+
+// Keys/values of committed pairs [spec_len[s], upto) for specialist s, in chunks of MAX_ROWS rows.
+void spec_catchup(poss_ctx *c, int s, int upto) {
+    while (c->spec_len[s] < upto) {
+        const int i0 = c->spec_len[s], n = upto - i0 < MAX_ROWS ? upto - i0 : MAX_ROWS;
+        DraftRowPlan plan;
+        plan.n_rows = n; plan.mask0[0] = plan.mask0[1] = 0;
+        for (int r = 0; r < n; ++r) { plan.kind[r] = 0; plan.idx[r] = i0 + r; plan.slot[r] = i0 + r; plan.pos[r] = i0 + r; }
+        spec_pass(c, s, plan, 0, 0, 0, 0, nullptr, nullptr);
+        c->spec_len[s] = i0 + n;
+    }
+}
+
+int copy_tree_out(poss_ctx *c, poss_tree *out) {
+    const int n = c->tree_n;
+    out->n_nodes = n;
+    struct { void *dst; const void *src; size_t b; } cp[] = {
+        {out->token, c->td.token, n * sizeof(int32_t)}, {out->parent, c->td.parent, n * sizeof(int32_t)},
+        {out->depth, c->td.depth, n * sizeof(int32_t)}, {out->pos, c->td.pos, n * sizeof(int32_t)},
+        {out->mask, c->td.mask, (size_t)n * MASK_WORDS * sizeof(uint64_t)}, {out->score, c->td.score, n * sizeof(float)}};
+    for (auto &x : cp)
+        if (x.dst) HIP_TRY(c, hipMemcpyAsync(x.dst, x.src, x.b, hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    return POSS_OK;
+}
+
+void pack_layer(poss_ctx *c, const void *const *src, const std::vector<void *> &dst, size_t base) {
+    const poss_config &cf = c->cfg;
+    const int dt = cf.dtype, d = cf.d_model, qd = cf.n_q_heads * cf.head_dim, kd = cf.n_kv_heads * cf.head_dim, F = cf.d_ffn;
+    const size_t es = esize(cf);
+    (void)hipMemcpyAsync(dst[base + 0], src[0], d * es, hipMemcpyDeviceToDevice, c->st);
+    launch_pack(dt, PackSrc{{src[1], src[2], src[3]}, {qd, kd, kd}}, d, dst[base + 1], c->st);
+    launch_pack(dt, PackSrc{{src[4], nullptr, nullptr}, {d, 0, 0}}, qd, dst[base + 2], c->st);
+    (void)hipMemcpyAsync(dst[base + 3], src[5], d * es, hipMemcpyDeviceToDevice, c->st);
+    launch_pack(dt, PackSrc{{src[6], src[7], nullptr}, {F, F, 0}}, d, dst[base + 4], c->st);
+    launch_pack(dt, PackSrc{{src[8], nullptr, nullptr}, {d, 0, 0}}, F, dst[base + 5], c->st);
+}
+
+LayerW layer_view(const std::vector<void *> &v, size_t base) {
+    return LayerW{v[base], v[base + 1], v[base + 2], v[base + 3], v[base + 4], v[base + 5]};
+}
+
+void reset_sequence(poss_ctx *c) {
+    c->state = ST_LOADED; c->t = 0; c->tree_ready = 0; c->tree_n = 0;
+    c->tokens.clear();
+    for (auto &x : c->spec_len) x = 0;
+    for (auto &x : c->spec_tmp_depth) x = 0;
+    memset(&c->stats, 0, sizeof(c->stats));
+}
+
+}  // namespace
+
+// ============================================================================================ C ABI
+extern "C" {
+
+size_t poss_workspace_bytes(const poss_config *cfg) {
+    if (!cfg || check_config(*cfg)) return 0;
+    Arena a(nullptr);
+    return carve(*cfg, a, nullptr, nullptr);
+}
+
+int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, size_t workspace_bytes,
+              void *hip_stream, poss_ctx **out) {
+    if (!cfg || !w || !workspace || !out) return fail(nullptr, POSS_E_INVALID_ARG, "poss_load: null argument");
+    if (const char *why = check_config(*cfg)) return fail(nullptr, POSS_E_INVALID_ARG, "poss_load: %s", why);
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->layer || !w->spec)
+        return fail(nullptr, POSS_E_INVALID_ARG, "poss_load: null weight pointer");
+    for (int i = 0; i < cfg->n_layers * 9; ++i)
+        if (!w->layer[i]) return fail(nullptr, POSS_E_INVALID_ARG, "poss_load: null layer tensor %d", i);
+    for (int i = 0; i < cfg->n_specialists * 11; ++i)
+        if (!w->spec[i]) return fail(nullptr, POSS_E_INVALID_ARG, "poss_load: null specialist tensor %d", i);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(nullptr, POSS_E_INVALID_ARG, "poss_load: workspace not 256-byte aligned");
+    const size_t need = poss_workspace_bytes(cfg);
+    if (workspace_bytes < need)
+        return fail(nullptr, POSS_E_CAPACITY, "poss_load: workspace of %zu bytes, %zu needed", workspace_bytes, need);
+
+    poss_ctx *c = new (std::nothrow) poss_ctx();
+    if (!c) return fail(nullptr, POSS_E_INVALID_ARG, "poss_load: out of host memory");
+    c->cfg = *cfg;
+    c->md = ModelDims{cfg->d_model, cfg->n_q_heads, cfg->n_kv_heads, cfg->head_dim, cfg->d_ffn, cfg->vocab,
+                      cfg->rms_eps, cfg->rope_theta, cfg->dtype};
+    c->st = static_cast<hipStream_t>(hip_stream);
+    c->err[0] = 0;
+    c->taps_user = nullptr;
+    c->gemm_target_wgs = 0; c->attn_keys_per_split = 256;
+    c->prof_on = 0; c->prof_n = 0; c->prof_bytes = 0; c->prof_launches = 0; c->prof_ms = 0;
+    c->spec_len.assign(cfg->n_specialists, 0);
+    c->spec_tmp_depth.assign(cfg->n_specialists, 0);
+    Arena a(workspace);
+    WeightSlots ws;
+    carve(*cfg, a, c, &ws);
+
+    auto bail = [&](int code) { g_load_error[0] = 0; strncpy(g_load_error, c->err, 511); delete c; return code; };
+#define LOAD_TRY(call)                                                                    \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess) { fail(c, POSS_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); return bail(POSS_E_HIP); } \
+    } while (0)
+
+    const size_t es = esize(*cfg);
+    const int d = cfg->d_model, V = cfg->vocab;
+    // weights
+    LOAD_TRY(hipMemcpyAsync(ws.embed, w->embed, (size_t)V * d * es, hipMemcpyDeviceToDevice, c->st));
+    launch_pack(cfg->dtype, PackSrc{{w->lm_head, nullptr, nullptr}, {V, 0, 0}}, d, ws.lm_head, c->st);
+    LOAD_TRY(hipMemcpyAsync(ws.final_norm, w->final_norm, d * es, hipMemcpyDeviceToDevice, c->st));
+    c->embed = ws.embed; c->lm_head = ws.lm_head; c->final_norm = ws.final_norm;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        pack_layer(c, w->layer + (size_t)l * 9, ws.layer, (size_t)l * 6);
+        c->layers.push_back(layer_view(ws.layer, (size_t)l * 6));
+    }
+    for (int s = 0; s < cfg->n_specialists; ++s) {
+        const void *const *src = w->spec + (size_t)s * 11;
+        launch_pack(cfg->dtype, PackSrc{{src[0], nullptr, nullptr}, {d, 0, 0}}, 2 * d, ws.spec[(size_t)s * 8], c->st);
+        LOAD_TRY(hipMemcpyAsync(ws.spec[(size_t)s * 8 + 1], src[1], d * es, hipMemcpyDeviceToDevice, c->st));
+        pack_layer(c, src + 2, ws.spec, (size_t)s * 8 + 2);
+        c->specs.push_back(SpecW{ws.spec[(size_t)s * 8], ws.spec[(size_t)s * 8 + 1], layer_view(ws.spec, (size_t)s * 8 + 2)});
+    }
+    // caches: zero (attention may touch, masked, slots that were never written)
+    for (auto &kv : c->target_kv) { launch_fill_u32((uint32_t *)kv.k, c->cache_bytes_each / 4, 0, c->st); launch_fill_u32((uint32_t *)kv.vt, c->cache_bytes_each / 4, 0, c->st); }
+    for (auto &kv : c->spec_kv) { launch_fill_u32((uint32_t *)kv.k, c->cache_bytes_each / 4, 0, c->st); launch_fill_u32((uint32_t *)kv.vt, c->cache_bytes_each / 4, 0, c->st); }
+    // small host->device tables
+    c->pinned_bytes = 1 << 20;
+    LOAD_TRY(hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault));
+    {
+        char *p = static_cast<char *>(c->pinned);
+        int32_t *pt = reinterpret_cast<int32_t *>(p);
+        for (int i = 0; i < c->n_pages; ++i) pt[i] = cfg->kv_page_order == 1 ? c->n_pages - 1 - i : i;
+        LOAD_TRY(hipMemcpyAsync(c->page_table, pt, c->n_pages * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        p += round_up(c->n_pages * (int)sizeof(int32_t), 256);
+        double *fr = reinterpret_cast<double *>(p);
+        const int half = cfg->head_dim / 2;
+        for (int i = 0; i < half; ++i) fr[i] = pow((double)cfg->rope_theta, -2.0 * i / cfg->head_dim);
+        LOAD_TRY(hipMemcpyAsync(c->inv_freq, fr, half * sizeof(double), hipMemcpyHostToDevice, c->st));
+        p += round_up(half * (int)sizeof(double), 256);
+        KVCache *kvh = reinterpret_cast<KVCache *>(p);
+        for (int l = 0; l < cfg->n_layers; ++l) kvh[l] = c->target_kv[l];
+        LOAD_TRY(hipMemcpyAsync(c->target_kv_dev, kvh, cfg->n_layers * sizeof(KVCache), hipMemcpyHostToDevice, c->st));
+    }
+    LOAD_TRY(hipEventCreate(&c->ev0));
+    LOAD_TRY(hipEventCreate(&c->ev1));
+    for (int i = 0; i < 2 * PROFILE_EVENTS; ++i) LOAD_TRY(hipEventCreate(&c->prof_ev[i]));
+    LOAD_TRY(hipStreamSynchronize(c->st));
+    LOAD_TRY(hipGetLastError());
+#undef LOAD_TRY
+    reset_sequence(c);
+    *out = c;
+    return POSS_OK;
+}
+
+int poss_reset(poss_ctx *c) {
+    if (!c) return POSS_E_INVALID_ARG;
+    reset_sequence(c);
+    return POSS_OK;
+}
+
+void poss_free(poss_ctx *c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->st);
+    (void)hipEventDestroy(c->ev0);
+    (void)hipEventDestroy(c->ev1);
+    for (int i = 0; i < 2 * PROFILE_EVENTS; ++i) (void)hipEventDestroy(c->prof_ev[i]);
+    (void)hipHostFree(c->pinned);
+    delete c;
+}
+
+const char *poss_last_error(poss_ctx *c) { return c ? c->err : g_load_error; }
+
+int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (!prompt || n_prompt < 1) return fail(c, POSS_E_INVALID_ARG, "poss_prefill: empty prompt");
+    if (c->state != ST_LOADED) return fail(c, POSS_E_BAD_STATE, "poss_prefill: sequence already started (poss_reset first)");
+    if (n_prompt + 1 > c->cfg.max_seq) return fail(c, POSS_E_CAPACITY, "poss_prefill: prompt of %d tokens, max_seq %d", n_prompt, c->cfg.max_seq);
+    for (int i = 0; i < n_prompt; ++i)
+        if (prompt[i] < 0 || prompt[i] >= c->cfg.vocab) return fail(c, POSS_E_INVALID_ARG, "poss_prefill: token id %d out of range at %d", prompt[i], i);
+    const ModelDims &md = c->md;
+    int32_t *stage = static_cast<int32_t *>(c->pinned);
+    for (int c0 = 0; c0 < n_prompt; c0 += MAX_ROWS) {
+        const int rows = n_prompt - c0 < MAX_ROWS ? n_prompt - c0 : MAX_ROWS;
+        memcpy(stage, prompt + c0, rows * sizeof(int32_t));
+        HIP_TRY(c, hipMemcpyAsync(c->tokens_dev + c0, stage, rows * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        hipLaunchKernelGGL(causal_meta_kernel, dim3(1), dim3(MAX_ROWS), 0, c->st, rows, c0, c->row_pos, c->row_slot, c->row_mask);
+        RowMeta rm{c->row_pos, c->row_slot, c->row_mask};
+        target_forward(c, rows, c->tokens_dev + c0, rm, c0, rows);
+        stash_rows(c, rows, c0);
+        if (c0 + rows == n_prompt) {
+            // Head on the last row only: its normed activations sit at row rows-1 of c->u
+            const char *last = static_cast<const char *>(c->u) + (size_t)(rows - 1) * md.d * dtype_size(md.dt);
+            GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true);
+            launch_argmax(c->logits, g.Npad, 1, md.vocab, c->argmax_dev, c->st);
+            HIP_TRY(c, hipMemcpyAsync(c->tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
+        }
+        HIP_TRY(c, hipStreamSynchronize(c->st));          // the staging buffer is reused by the next chunk
+    }
+    int32_t first = 0;
+    HIP_TRY(c, hipMemcpy(&first, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToHost));
+    c->tokens.assign(prompt, prompt + n_prompt);
+    c->tokens.push_back(first);
+    c->t = n_prompt;
+    for (int s = 0; s < c->cfg.n_specialists; ++s) spec_catchup(c, s, c->t - 1);
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    HIP_TRY(c, hipGetLastError());
+    c->state = ST_READY; c->tree_ready = 0;
+    if (first_token_out) *first_token_out = first;
+    return POSS_OK;
+}
+
+int poss_draft_tree(poss_ctx *c, poss_tree *out) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_draft_tree: needs a prefilled context with no pending verification");
+    const poss_config &cf = c->cfg;
+    const int t = c->t, k = cf.top_k, L = cf.depth;
+    if (t + cf.total_tokens + 1 > c->cache_slots || t + L + 1 > cf.max_seq)
+        return fail(c, POSS_E_CAPACITY, "poss_draft_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
+    (void)hipEventRecord(c->ev0, c->st);
+    for (int s = 0; s < cf.n_specialists; ++s) {
+        c->spec_tmp_depth[s] = 0;
+        if (t - 1 - c->spec_len[s] > L) spec_catchup(c, s, t - 1);      // only after caller-supplied trees
+    }
+    for (int d = 1; d <= L; ++d) {
+        int s = (d - 1) / cf.positions_per_specialist;
+        if (s > cf.n_specialists - 1) s = cf.n_specialists - 1;
+        DraftRowPlan plan;
+        int n = 0, rows_q, n_prefix, region_len;
+        if (d == 1) {
+            // root pair [x_t ; f_{t-1}] first (the only row whose output is used), then the other
+            // pairs this specialist has not seen; all of them become committed cache entries
+            n_prefix = c->spec_len[s]; region_len = t - n_prefix; rows_q = 1;
+            plan.mask0[0] = ones(region_len); plan.mask0[1] = ones(region_len - 64);
+            plan.kind[n] = 0; plan.idx[n] = t - 1; plan.slot[n] = t - 1; plan.pos[n] = t - 1; ++n;
+            for (int i = n_prefix; i < t - 1; ++i) { plan.kind[n] = 0; plan.idx[n] = i; plan.slot[n] = i; plan.pos[n] = i; ++n; }
+        } else {
+            n_prefix = t; region_len = (d - 1) * k; rows_q = k;
+            plan.mask0[0] = plan.mask0[1] = 0;
+            for (int r = 0; r < k; ++r) { plan.kind[n] = 2; plan.idx[n] = r; plan.slot[n] = t + (d - 2) * k + r; plan.pos[n] = t - 1 + (d - 1); ++n; }
+            for (int i = c->spec_len[s]; i < t; ++i) { plan.kind[n] = 0; plan.idx[n] = i; plan.slot[n] = i; plan.pos[n] = i; ++n; }
+            for (int dl = c->spec_tmp_depth[s] + 1; dl <= d - 2; ++dl)
+                for (int r = 0; r < k; ++r) { plan.kind[n] = 1; plan.idx[n] = (dl - 1) * k + r; plan.slot[n] = t + (dl - 1) * k + r; plan.pos[n] = t - 1 + dl; ++n; }
+        }
+        plan.n_rows = n;
+        spec_pass(c, s, plan, d - 1, rows_q, n_prefix, region_len, c->fhat[(d - 1) & 1], c->fhat[d & 1]);
+        GemmShape g = run_head(c, rows_q);
+        launch_topk_logsoftmax(c->logits, g.Npad, rows_q, cf.vocab, k, c->topk_scratch, c->td.topk_id, c->td.topk_logp, c->st);
+        launch_tree_expand(c->td, d, k, L, rows_q, c->st);
+        c->spec_len[s] = t;
+        c->spec_tmp_depth[s] = d - 1;
+    }
+    launch_tree_finalize(c->td, k, L, cf.total_tokens, t, c->tokens_dev, c->st);
+    (void)hipEventRecord(c->ev1, c->st);
+    const int pool = k + (L - 1) * k * k;
+    c->tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
+    c->tree_ready = 1;
+    if (out) { int rc = copy_tree_out(c, out); if (rc) return rc; }
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    HIP_TRY(c, hipGetLastError());
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) c->stats.ms_draft += ms;
+    return POSS_OK;
+}
+
+int poss_debug_build_tree(poss_ctx *c, const int32_t *ids, const float *logp, poss_tree *out) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (!ids || !logp) return fail(c, POSS_E_INVALID_ARG, "poss_debug_build_tree: null argument");
+    if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_debug_build_tree: needs a prefilled context");
+    const poss_config &cf = c->cfg;
+    const int k = cf.top_k, L = cf.depth;
+    int32_t *sid = static_cast<int32_t *>(c->pinned);
+    float *slp = reinterpret_cast<float *>(sid + (size_t)L * k * k);
+    memcpy(sid, ids, (size_t)L * k * k * sizeof(int32_t));
+    memcpy(slp, logp, (size_t)L * k * k * sizeof(float));
+    for (int d = 1; d <= L; ++d) {
+        const int rows = d == 1 ? 1 : k;
+        HIP_TRY(c, hipMemcpyAsync(c->td.topk_id, sid + (size_t)(d - 1) * k * k, rows * k * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        HIP_TRY(c, hipMemcpyAsync(c->td.topk_logp, slp + (size_t)(d - 1) * k * k, rows * k * sizeof(float), hipMemcpyHostToDevice, c->st));
+        launch_tree_expand(c->td, d, k, L, rows, c->st);
+    }
+    launch_tree_finalize(c->td, k, L, cf.total_tokens, c->t, c->tokens_dev, c->st);
+    const int pool = k + (L - 1) * k * k;
+    c->tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
+    c->tree_ready = 1;
+    if (out) { int rc = copy_tree_out(c, out); if (rc) return rc; }
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    HIP_TRY(c, hipGetLastError());
+    return POSS_OK;
+}
+
+int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, void *logits_out, void *feat_out) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: needs a prefilled context with no pending verification");
+    const poss_config &cf = c->cfg;
+    const int t = c->t;
+    int n;
+    if (tree) {
+        n = tree->n_nodes;
+        if (n < 1 || n > cf.total_tokens + 1) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: %d nodes, capacity %d", n, cf.total_tokens + 1);
+        if (!tree->token || !tree->parent) return fail(c, POSS_E_INVALID_ARG, "poss_verify_tree: null tree arrays");
+        std::vector<int> depth(n, 0);
+        if (tree->parent[0] != -1) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: parent[0] must be -1");
+        for (int i = 1; i < n; ++i) {
+            const int p = tree->parent[i];
+            if (p < 0 || p >= i) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: parent[%d] = %d does not precede the node", i, p);
+            if (tree->token[i] < 0 || tree->token[i] >= cf.vocab) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: token[%d] out of range", i);
+            depth[i] = depth[p] + 1;
+            if (depth[i] > cf.depth) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: node %d deeper than depth %d", i, cf.depth);
+            for (int j = 1; j < i; ++j)
+                if (tree->parent[j] == p && tree->token[j] == tree->token[i])
+                    return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: siblings %d and %d carry the same token", j, i);
+        }
+    } else {
+        if (!c->tree_ready) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: no drafted tree");
+        n = c->tree_n;
+    }
+    if (t + n > c->cache_slots || t + cf.depth + 1 > cf.max_seq)
+        return fail(c, POSS_E_CAPACITY, "poss_verify_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
+    (void)hipEventRecord(c->ev0, c->st);
+    if (tree) {
+        int32_t *stage = static_cast<int32_t *>(c->pinned);
+        memcpy(stage, tree->token, n * sizeof(int32_t));
+        stage[0] = c->tokens[t];                                  // the root is always x_t
+        memcpy(stage + MAX_ROWS, tree->parent, n * sizeof(int32_t));
+        stage[2 * MAX_ROWS] = n;
+        HIP_TRY(c, hipMemcpyAsync(c->td.token, stage, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        HIP_TRY(c, hipMemcpyAsync(c->td.parent, stage + MAX_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        HIP_TRY(c, hipMemcpyAsync(c->td.n_nodes, stage + 2 * MAX_ROWS, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        launch_tree_upload_finish(n, t, c->td.token, c->td.parent, c->td.depth, c->td.pos, c->tree_slot, c->td.mask, c->st);
+        c->tree_n = n; c->tree_ready = 1;
+    } else {
+        launch_iota_slots(n, t, c->tree_slot, c->st);
+    }
+    RowMeta rm{c->td.pos, c->tree_slot, c->td.mask};
+    target_forward(c, n, c->td.token, rm, t, n);
+    GemmShape g = run_head(c, n);
+    launch_argmax(c->logits, g.Npad, n, cf.vocab, c->argmax_dev, c->st);
+    (void)hipEventRecord(c->ev1, c->st);
+    if (logits_out) launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
+    if (feat_out) launch_copy_rows_f32(c->feats, cf.d_model, static_cast<float *>(feat_out), cf.d_model, n, cf.d_model, c->st);
+    if (argmax_out) HIP_TRY(c, hipMemcpyAsync(argmax_out, c->argmax_dev, n * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    HIP_TRY(c, hipGetLastError());
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) c->stats.ms_verify += ms;
+    c->state = ST_VERIFIED;
+    return POSS_OK;
+}
+
+int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accepted_out, int32_t *committed_out,
+                           int32_t *n_committed_out) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (c->state != ST_VERIFIED) return fail(c, POSS_E_BAD_STATE, "poss_accept_and_commit: no verified tree");
+    const poss_config &cf = c->cfg;
+    const int t = c->t, L = cf.depth;
+    (void)hipEventRecord(c->ev0, c->st);
+    launch_accept_walk(c->td.token, c->td.parent, c->argmax_dev, c->td.n_nodes, L, c->walk_dev, c->st);
+    launch_commit(c->md, cf.n_layers, c->target_kv_dev, c->walk_dev, L, t, c->feats, c->feat_stash, c->tokens_dev,
+                  c->td.token, c->st);
+    (void)hipEventRecord(c->ev1, c->st);
+    int32_t *walk = static_cast<int32_t *>(c->pinned);
+    int32_t *toks = walk + 32;
+    HIP_TRY(c, hipMemcpyAsync(walk, c->walk_dev, (L + 3) * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipMemcpyAsync(toks, c->tokens_dev + t + 1, (L + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    HIP_TRY(c, hipGetLastError());
+    const int m = walk[0];
+    if (m < 0 || m > L) return fail(c, POSS_E_HIP, "poss_accept_and_commit: walk returned %d accepted tokens", m);
+    for (int j = 0; j <= m; ++j) c->tokens.push_back(toks[j]);
+    c->t = t + m + 1;
+    c->stats.rounds += 1;
+    c->stats.committed_tokens += m + 1;
+    for (int i = 1; i <= m; ++i) c->stats.c[i] += 1;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) c->stats.ms_commit += ms;
+    if (path_idx_out) for (int j = 0; j <= m; ++j) path_idx_out[j] = walk[2 + j];
+    if (n_accepted_out) *n_accepted_out = m;
+    if (committed_out) for (int j = 0; j <= m; ++j) committed_out[j] = toks[j];
+    if (n_committed_out) *n_committed_out = m + 1;
+    c->state = ST_READY; c->tree_ready = 0;
+    return POSS_OK;
+}
+
+int poss_get_stats(poss_ctx *c, poss_stats *out) {
+    if (!c || !out) return POSS_E_INVALID_ARG;
+    *out = c->stats;
+    return POSS_OK;
+}
+
+int poss_get_tokens(poss_ctx *c, int32_t *tokens_out, int32_t cap, int32_t *n_out) {
+    if (!c) return POSS_E_INVALID_ARG;
+    const int n = (int)c->tokens.size();
+    if (n_out) *n_out = n;
+    if (tokens_out) {
+        if (cap < n) return fail(c, POSS_E_CAPACITY, "poss_get_tokens: %d tokens, capacity %d", n, cap);
+        memcpy(tokens_out, c->tokens.data(), n * sizeof(int32_t));
+    }
+    return POSS_OK;
+}
+
+int poss_profile_gemm(poss_ctx *c, int32_t enable) {
+    if (!c) return POSS_E_INVALID_ARG;
+    c->prof_on = enable ? 1 : 0;
+    return POSS_OK;
+}
+
+int poss_gemm_profile(poss_ctx *c, int64_t *launches, double *ms, double *weight_bytes) {
+    if (!c) return POSS_E_INVALID_ARG;
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    double total = 0;
+    for (int i = 0; i < c->prof_n; ++i) {
+        float e = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&e, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+        total += e;
+    }
+    if (launches) *launches = c->prof_n;
+    if (ms) *ms = total;
+    if (weight_bytes) *weight_bytes = c->prof_bytes;
+    c->prof_n = 0; c->prof_bytes = 0;
+    return POSS_OK;
+}
+
+int poss_set_tuning(poss_ctx *c, int32_t gemm_target_workgroups, int32_t attn_keys_per_split) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (gemm_target_workgroups < 0 || gemm_target_workgroups > 4096) return fail(c, POSS_E_INVALID_ARG, "poss_set_tuning: workgroup target out of range");
+    if (attn_keys_per_split && (attn_keys_per_split < 128 || attn_keys_per_split % 32)) return fail(c, POSS_E_INVALID_ARG, "poss_set_tuning: keys per split must be a multiple of 32, >= 128");
+    c->gemm_target_wgs = gemm_target_workgroups;
+    if (attn_keys_per_split) c->attn_keys_per_split = attn_keys_per_split;
+    return POSS_OK;
+}
+
+int poss_debug_set_taps(poss_ctx *c, void *taps) {
+    if (!c) return POSS_E_INVALID_ARG;
+    c->taps_user = static_cast<float *>(taps);
+    return POSS_OK;
+}
+
+int poss_debug_read_kv(poss_ctx *c, int32_t which, int32_t layer, int32_t slot0, int32_t n, float *k_out, float *v_out) {
+    if (!c || !k_out || !v_out) return POSS_E_INVALID_ARG;
+    if (n < 1 || slot0 < 0 || slot0 + n > c->cache_slots) return fail(c, POSS_E_INVALID_ARG, "poss_debug_read_kv: slots out of range");
+    if (which >= c->cfg.n_specialists || (which < 0 && (layer < 0 || layer >= c->cfg.n_layers)))
+        return fail(c, POSS_E_INVALID_ARG, "poss_debug_read_kv: no such cache");
+    const KVCache &kv = which < 0 ? c->target_kv[layer] : c->spec_kv[which];
+    // stage through the partial-sum buffer (idle between calls)
+    const size_t per = (size_t)c->md.hkv * c->md.dh;
+    const int chunk = 64;
+    for (int i = 0; i < n; i += chunk) {
+        const int m = n - i < chunk ? n - i : chunk;
+        float *kd = c->part, *vd = c->part + (size_t)chunk * per;
+        launch_read_kv(c->md, kv, slot0 + i, m, kd, vd, c->st);
+        HIP_TRY(c, hipMemcpyAsync(k_out + (size_t)i * per, kd, m * per * sizeof(float), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(c, hipMemcpyAsync(v_out + (size_t)i * per, vd, m * per * sizeof(float), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(c, hipStreamSynchronize(c->st));
+    }
+    return POSS_OK;
+}
+
+__global__ void sum_planes_kernel(const float *__restrict__ part, int S, size_t plane, int Npad, int N, float *__restrict__ y) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x, m = blockIdx.y;
+    if (n >= N) return;
+    float a = 0.f;
+    for (int s = 0; s < S; ++s) a += part[(size_t)s * plane + (size_t)m * Npad + n];
+    y[(size_t)m * N + n] = a;
+}
+
+size_t poss_debug_gemm_scratch_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K) {
+    if (dtype < 0 || dtype > 2 || M < 1 || M > MAX_ROWS || N < 1 || K < 1) return 0;
+    GemmShape g = gemm_plan(dtype, M, N, K, 4096);
+    return (packed_elems(dtype, N, K) * dtype_size(dtype) + 255) / 256 * 256 +
+           (size_t)g.S * MAX_ROWS * g.Npad * sizeof(float) + 512;
+}
+
+int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_t M, int32_t N, int32_t K,
+                    int32_t target_workgroups, void *scratch, void *hip_stream, int32_t repeats,
+                    float *ms_per_launch_out) {
+    if (!x || !w || !y || !scratch) return fail(nullptr, POSS_E_INVALID_ARG, "poss_debug_gemm: null argument");
+    if (dtype < 0 || dtype > 2 || M < 1 || M > MAX_ROWS || N < 1 || K < 1 || repeats < 1)
+        return fail(nullptr, POSS_E_INVALID_ARG, "poss_debug_gemm: bad shape");
+    if (dtype != DT_F32 && (K % 8)) return fail(nullptr, POSS_E_INVALID_ARG, "poss_debug_gemm: K must be a multiple of 8");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    GemmShape g = gemm_plan(dtype, M, N, K, target_workgroups);
+    char *p = static_cast<char *>(scratch);
+    void *wp = p;
+    p += (packed_elems(dtype, N, K) * dtype_size(dtype) + 255) / 256 * 256;
+    float *part = reinterpret_cast<float *>(p);
+    launch_pack(dtype, PackSrc{{w, nullptr, nullptr}, {N, 0, 0}}, K, wp, st);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return fail(nullptr, POSS_E_HIP, "poss_debug_gemm: event creation failed");
+    launch_gemm(dtype, g, wp, x, K, part, st);
+    (void)hipEventRecord(e0, st);
+    for (int i = 0; i < repeats; ++i) launch_gemm(dtype, g, wp, x, K, part, st);
+    (void)hipEventRecord(e1, st);
+    hipLaunchKernelGGL(sum_planes_kernel, dim3((N + 255) / 256, M), dim3(256), 0, st, part, g.S, (size_t)g.Mpad * g.Npad, g.Npad, N, static_cast<float *>(y));
+    hipError_t e = hipStreamSynchronize(st);
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail(nullptr, POSS_E_HIP, "poss_debug_gemm: %s", hipGetErrorString(e));
+    if (ms_per_launch_out) *ms_per_launch_out = ms / repeats;
+    return POSS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,146 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace poss {
+
+typedef __bf16   bf16_t;
+typedef _Float16 f16_t;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+static inline size_t dtype_size(int dt) { return dt == DT_F32 ? 4 : 2; }
+
+// ---------------------------------------------------------------- GEMM geometry
+// Y[M, N] = X[M, K] . W[N, K]^T with M <= 128 rows: the weight matrix is streamed once.
+// 16-bit types use v_mfma_f32_16x16x32 with the activations as A (rows m) and the weights
+// as B (columns n).  Weights are repacked at load time into B-operand order:
+//   Wp[n_group][k_step][nt][lane][8],  n = (n_group*GEMM_NT + nt)*16 + lane%16,
+//                                       k = k_step*32 + (lane/16)*8 + j
+// so that one wave reads GEMM_NT KiB per k-step, contiguous and in k order.
+constexpr int GEMM_NT      = 2;                       // 16-column tiles per wave
+constexpr int GEMM_WPB     = 4;                       // waves per workgroup
+constexpr int GEMM_BLOCK_N = GEMM_NT * 16 * GEMM_WPB; // 128 columns per workgroup
+constexpr int GEMM_KSTEP   = 32;
+constexpr int GEMM_KCHUNK  = 256;                     // K is padded to this at pack time
+constexpr int MAX_ROWS     = 128;
+constexpr int MASK_WORDS   = 2;
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+static inline int gemm_npad(int n) { return round_up(n, GEMM_BLOCK_N); }
+static inline int gemm_kpad(int dt, int k) { return dt == DT_F32 ? k : round_up(k, GEMM_KCHUNK); }
+static inline size_t packed_elems(int dt, int n, int k) { return (size_t)gemm_npad(n) * gemm_kpad(dt, k); }
+
+struct GemmShape {
+    int M;          // real rows
+    int N, K;       // logical sizes
+    int Npad, Kpad; // padded sizes of the packed weight
+    int S;          // K splits; partial sums land in part[S][Mpad16][Npad]
+    int chunks_per_split;
+    int Mpad;       // rows rounded up to 16 (row stride of a partial plane is Npad)
+};
+GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs);
+// part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.
+void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
+                 hipStream_t st);
+
+struct PackSrc { const void *ptr[3]; int rows[3]; };  // up to three matrices stacked along N
+void launch_pack(int dt, const PackSrc &src, int K, void *dst, hipStream_t st);
+
+// ---------------------------------------------------------------- KV caches
+// K  : [phys_page][Hkv][P][dh]      (row per token)
+// Vt : [phys_page][Hkv][dh][P]      (tokens contiguous: the A operand of O^T = V^T P^T)
+struct KVCache {
+    void *k, *vt;
+    const int32_t *page_table;     // device: logical page -> physical page
+    int page_shift;                // log2(P)
+};
+
+struct ModelDims {
+    int d, hq, hkv, dh, ffn, vocab;
+    float eps, theta;
+    int dt;
+};
+
+// Per-row metadata of one pass, all DEVICE arrays.
+struct RowMeta {
+    const int32_t  *pos;    // rotary position
+    const int32_t  *slot;   // cache slot the row's key/value is written to
+    const uint64_t *mask;   // [rows][MASK_WORDS] visibility over region slots (bit j = slot region0 + j)
+};
+
+// ---------------------------------------------------------------- launchers: elementwise / reductions
+void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *tokens, int rows,
+                       const void *gain, float *h, void *u, hipStream_t st);
+// rows_q leading rows get a rotated query; all `rows` get key/value written into the cache
+void launch_reduce_rope_kv(const ModelDims &md, const GemmShape &g, const float *part, int rows,
+                           int rows_q, const RowMeta &rm, const double *inv_freq, void *q,
+                           const KVCache &kv, hipStream_t st);
+// h = (residual ? h : 0) + sum(part) + bias ; u = T(rmsnorm(h) * gain); optional fp32 copies of h
+void launch_reduce_res_norm(const ModelDims &md, const GemmShape &g, const float *part, int rows,
+                            bool residual, const void *bias, const void *gain, float *h, void *u,
+                            float *h_copy, hipStream_t st);
+void launch_reduce_silu(const ModelDims &md, const GemmShape &g, const float *part, int rows, void *act,
+                        hipStream_t st);
+void launch_argmax(const float *logits, int ld, int rows, int vocab, int32_t *out, hipStream_t st);
+void launch_copy_rows_f32(const float *src, int ld_src, float *dst, int ld_dst, int rows, int cols,
+                          hipStream_t st);
+
+// ---------------------------------------------------------------- attention
+struct AttnScratch { float *o; float *ml; };  // partial outputs [split][Hq][rows][dh], (m, l) pairs
+void launch_attention(const ModelDims &md, const void *q, int rows, const RowMeta &rm, int n_prefix,
+                      int region_len, const KVCache &kv, int keys_per_split, const AttnScratch &sc,
+                      void *out, hipStream_t st);
+
+// ---------------------------------------------------------------- draft-tree kernels
+struct TreeDev {            // device-resident tree state of one round
+    // candidate pool
+    int32_t *pool_token, *pool_parent, *pool_depth; float *pool_score;
+    // frontier of each depth: [depth][k]
+    int32_t *fr_pool, *fr_token, *fr_parent_rank; float *fr_score; uint64_t *fr_mask;
+    // per-pass top-k results [k rows][k]
+    int32_t *topk_id; float *topk_logp;
+    // final tree
+    int32_t *n_nodes, *token, *parent, *depth, *pos; uint64_t *mask; float *score;
+};
+size_t topk_scratch_floats(int rows, int vocab);
+void launch_topk_logsoftmax(const float *logits, int ld, int rows, int vocab, int k, float *seg_scratch,
+                            int32_t *out_id, float *out_logp, hipStream_t st);
+void launch_tree_expand(const TreeDev &td, int d, int k, int L, int rows, hipStream_t st);
+void launch_tree_finalize(const TreeDev &td, int k, int L, int n_keep, int t, const int32_t *tokens_dev,
+                          hipStream_t st);
+// rows of [embedding ; feature] pairs for one specialist pass
+struct DraftRowPlan {
+    int n_rows;
+    uint64_t mask0[MASK_WORDS];   // region mask given to rows of kind 0 and 1
+    int16_t kind[MAX_ROWS];       // 0: committed pair (idx = drafter index i); 1: stored frontier row
+                                  // (idx = temp row); 2: new frontier row (idx = rank in this depth)
+    int32_t idx[MAX_ROWS];
+    int32_t slot[MAX_ROWS];
+    int32_t pos[MAX_ROWS];
+};
+void launch_draft_assemble(const ModelDims &md, const DraftRowPlan &plan, int depth_index, int k,
+                           const void *embed, const int32_t *tokens_dev, const void *feat_stash,
+                           const TreeDev &td, const float *fhat_prev, void *xin_tmp, void *x_out,
+                           int32_t *pos_out, int32_t *slot_out, uint64_t *mask_out, hipStream_t st);
+
+// ---------------------------------------------------------------- accept + commit
+void launch_tree_upload_finish(int n, int t, const int32_t *token, const int32_t *parent, int32_t *depth,
+                               int32_t *pos, int32_t *slot, uint64_t *mask, hipStream_t st);
+void launch_iota_slots(int n, int t, int32_t *slot, hipStream_t st);
+// walk: [0] = m, [1] = bonus token, [2..2+m] = node indices of the accepted path
+void launch_accept_walk(const int32_t *token, const int32_t *parent, const int32_t *g, const int32_t *n_nodes,
+                        int max_path, int32_t *walk, hipStream_t st);
+void launch_commit(const ModelDims &md, int n_layers, const KVCache *caches_dev, const int32_t *walk, int max_path,
+                   int t, const float *feats, void *feat_stash, int32_t *tokens_dev, const int32_t *tree_token,
+                   hipStream_t st);
+
+void launch_read_kv(const ModelDims &md, const KVCache &kv, int slot0, int n, float *k_out, float *v_out,
+                    hipStream_t st);
+void launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
+int attention_splits(int total_keys, int keys_per_split);
+
+}  // namespace poss

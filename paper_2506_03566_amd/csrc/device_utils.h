@@ -1,0 +1,80 @@
+// Device-side helpers: storage conversions, block reductions, cache addressing.
+#pragma once
+#include "common.h"
+
+namespace poss {
+
+template <typename T> __device__ __forceinline__ float to_f(T v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f(float v) { return (T)v; }   // round to nearest even
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// Sum over a workgroup of up to 1024 threads, identical in every thread; fixed order.
+__device__ __forceinline__ float block_sum(float v, float *red /* >= 17 floats of LDS */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int i = 0; i < nw; ++i) s += red[i];
+        red[16] = s;
+    }
+    __syncthreads();
+    return red[16];
+}
+
+// (value, index) ordering used by every argmax / top-k here: larger value first, then lower index.
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
+    return (v > bv) || (v == bv && i < bi);
+}
+
+__device__ __forceinline__ void wave_argmax(float &v, int &i) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(v, o, 64);
+        const int oi = __shfl_xor(i, o, 64);
+        if (better(ov, oi, v, i)) { v = ov; i = oi; }
+    }
+}
+
+// Workgroup-wide argmax; result valid in every thread.  red_v/red_i: >= 17 entries of LDS each.
+__device__ __forceinline__ void block_argmax(float &v, int &i, float *red_v, int *red_i) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    wave_argmax(v, i);
+    __syncthreads();
+    if (lane == 0) { red_v[wave] = v; red_i[wave] = i; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float bv = red_v[0]; int bi = red_i[0];
+        for (int w = 1; w < nw; ++w)
+            if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
+        red_v[16] = bv; red_i[16] = bi;
+    }
+    __syncthreads();
+    v = red_v[16]; i = red_i[16];
+}
+
+// Element offsets into the paged caches.
+__device__ __forceinline__ size_t k_offset(const KVCache &kv, int slot, int head, int hkv, int dh) {
+    const int P = 1 << kv.page_shift;
+    const int pg = kv.page_table[slot >> kv.page_shift];
+    return ((size_t)(pg * hkv + head) * P + (slot & (P - 1))) * dh;
+}
+__device__ __forceinline__ size_t vt_offset(const KVCache &kv, int slot, int head, int hkv, int dh, int row) {
+    const int P = 1 << kv.page_shift;
+    const int pg = kv.page_table[slot >> kv.page_shift];
+    return ((size_t)(pg * hkv + head) * dh + row) * P + (slot & (P - 1));
+}
+
+}  // namespace poss

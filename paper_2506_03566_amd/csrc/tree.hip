@@ -1,0 +1,368 @@
+// Draft-tree kernels: log-softmax + top-k of the drafter's logits, level-by-level expansion with a
+// width-k frontier, final top-N rerank and tree emission (tree drafting with width / depth / total
+// tokens, section 4.1 "Implementations" of the paper), assembly of the [embedding ; feature] rows a
+// specialist consumes (Eq. 2 / Eq. 9), greedy acceptance walk and commit (section 2.1, 3.1).
+//
+// Ordering rules, identical everywhere: larger value first; ties to the lower token id (children of
+// one node) or the earlier candidate (anything else).  Candidate order = (depth, rank of the parent
+// in its frontier, rank of the child among its siblings).  Scores are float32 running sums of
+// log-probabilities.  All selection is by rank counting, so results do not depend on thread timing.
+#include "device_utils.h"
+
+namespace poss {
+
+// ------------------------------------------------------------------ top-k + log-sum-exp, stage 1
+// One workgroup per (segment of <= TOPK_SEG logits, row): segment maximum, sum of exp(l - max) and
+// the segment's k best (value, index).
+constexpr int TOPK_SEG = 2048;
+constexpr int TOPK_MAXK = 16;
+
+__global__ __launch_bounds__(256) void topk_seg_kernel(const float *__restrict__ logits, int ld, int vocab, int k,
+                                                       int n_seg, float *__restrict__ seg_out) {
+    __shared__ float vals[TOPK_SEG];
+    __shared__ float red_v[17];
+    __shared__ int red_i[17];
+    const int seg = blockIdx.x, row = blockIdx.y;
+    const int base = seg * TOPK_SEG, n = min(TOPK_SEG, vocab - base);
+    const float *src = logits + (size_t)row * ld + base;
+    float mx = -INFINITY;
+    for (int i = threadIdx.x; i < TOPK_SEG; i += blockDim.x) {
+        const float v = i < n ? src[i] : -INFINITY;
+        vals[i] = v;
+        mx = fmaxf(mx, v);
+    }
+    int dummy = 0;
+    {   // segment max via the argmax reduction (index irrelevant)
+        float v = mx; int i = threadIdx.x;
+        block_argmax(v, i, red_v, red_i);
+        mx = v; dummy = i;
+    }
+    (void)dummy;
+    float se = 0.f;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) se += expf(vals[i] - mx);
+    se = block_sum(se, red_v);
+    // record layout per (row, seg): [max, sumexp, k values, k indices(as float bits)]
+    float *rec = seg_out + ((size_t)row * n_seg + seg) * (2 + 2 * TOPK_MAXK);
+    if (threadIdx.x == 0) { rec[0] = mx; rec[1] = se; }
+    for (int j = 0; j < k; ++j) {
+        float bv = -INFINITY; int bi = 0x7fffffff;
+        for (int i = threadIdx.x; i < TOPK_SEG; i += blockDim.x) {
+            const float v = vals[i];
+            if (better(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+        block_argmax(bv, bi, red_v, red_i);
+        if (threadIdx.x == 0) {
+            rec[2 + j] = bv;
+            reinterpret_cast<int *>(rec)[2 + TOPK_MAXK + j] = (bi < TOPK_SEG && bv > -INFINITY) ? base + bi : 0x7fffffff;
+            if (bi < TOPK_SEG) vals[bi] = -INFINITY;
+        }
+        __syncthreads();
+    }
+}
+
+// stage 2: one workgroup per row merges the segments.
+__global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict__ seg_out, int n_seg, int k,
+                                                         int32_t *__restrict__ out_id, float *__restrict__ out_logp) {
+    extern __shared__ float cand[];                 // n_seg * k values, then n_seg * k ids
+    __shared__ float red_v[17];
+    __shared__ int red_i[17];
+    const int row = blockIdx.x, nc = n_seg * k;
+    int *cid = reinterpret_cast<int *>(cand + nc);
+    const float *recs = seg_out + (size_t)row * n_seg * (2 + 2 * TOPK_MAXK);
+    float mx = -INFINITY;
+    for (int s = threadIdx.x; s < n_seg; s += blockDim.x) mx = fmaxf(mx, recs[(size_t)s * (2 + 2 * TOPK_MAXK)]);
+    { float v = mx; int i = threadIdx.x; block_argmax(v, i, red_v, red_i); mx = v; }
+    float se = 0.f;
+    for (int s = threadIdx.x; s < n_seg; s += blockDim.x) {
+        const float *r = recs + (size_t)s * (2 + 2 * TOPK_MAXK);
+        se += r[1] * expf(r[0] - mx);
+    }
+    se = block_sum(se, red_v);
+    const float lse = mx + logf(se);
+    for (int c = threadIdx.x; c < nc; c += blockDim.x) {
+        const float *r = recs + (size_t)(c / k) * (2 + 2 * TOPK_MAXK);
+        cand[c] = r[2 + c % k];
+        cid[c] = reinterpret_cast<const int *>(r)[2 + TOPK_MAXK + c % k];
+    }
+    __syncthreads();
+    for (int j = 0; j < k; ++j) {
+        float bv = -INFINITY; int bi = 0x7fffffff, bc = -1;
+        for (int c = threadIdx.x; c < nc; c += blockDim.x)
+            if (better(cand[c], cid[c], bv, bi)) { bv = cand[c]; bi = cid[c]; bc = c; }
+        block_argmax(bv, bi, red_v, red_i);          // ids are unique, so (value, id) names one candidate
+        if (bc >= 0 && cid[bc] == bi && cand[bc] == bv) cand[bc] = -INFINITY;
+        if (threadIdx.x == 0) {
+            out_id[row * k + j] = bi;
+            out_logp[row * k + j] = bv - lse;
+        }
+        __syncthreads();
+    }
+}
+
+void launch_topk_logsoftmax(const float *logits, int ld, int rows, int vocab, int k, float *seg_scratch,
+                            int32_t *out_id, float *out_logp, hipStream_t st) {
+    const int n_seg = (vocab + TOPK_SEG - 1) / TOPK_SEG;
+    hipLaunchKernelGGL(topk_seg_kernel, dim3(n_seg, rows), dim3(256), 0, st, logits, ld, vocab, k, n_seg, seg_scratch);
+    hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(256), (size_t)n_seg * k * 8, st, seg_scratch, n_seg, k,
+                       out_id, out_logp);
+}
+
+size_t topk_scratch_floats(int rows, int vocab) {
+    return (size_t)rows * ((vocab + TOPK_SEG - 1) / TOPK_SEG) * (2 + 2 * TOPK_MAXK);
+}
+
+// ------------------------------------------------------------------ expansion of one depth
+// Children of the frontier of depth d-1 (the root for d = 1) join the candidate pool; unless d = L,
+// the k best of them become the frontier of depth d.  A frontier node's drafter row lives in temp
+// slot (d-1)*k + rank; fr_mask collects the temp slots of the node and its drafted ancestors.
+__global__ __launch_bounds__(256) void tree_expand_kernel(TreeDev td, int d, int k, int L, int rows) {
+    __shared__ float sc[256];
+    const int n_child = rows * k;
+    const int base = d == 1 ? 0 : k + (d - 2) * k * k;
+    const int tid = threadIdx.x;
+    if (tid < n_child) {
+        const int r = tid / k;
+        const float ps = d == 1 ? 0.f : td.fr_score[(d - 1) * k + r];
+        const float s = ps + td.topk_logp[tid];
+        sc[tid] = s;
+        td.pool_token[base + tid] = td.topk_id[tid];
+        td.pool_parent[base + tid] = d == 1 ? -1 : td.fr_pool[(d - 1) * k + r];
+        td.pool_depth[base + tid] = d;
+        td.pool_score[base + tid] = s;
+    }
+    __syncthreads();
+    if (d < L && tid < n_child) {
+        const float s = sc[tid];
+        int rank = 0;
+        for (int j = 0; j < n_child; ++j) rank += (sc[j] > s) || (sc[j] == s && j < tid);
+        if (rank < k) {
+            const int r = tid / k, o = d * k + rank;
+            td.fr_pool[o] = base + tid;
+            td.fr_token[o] = td.topk_id[tid];
+            td.fr_parent_rank[o] = r;
+            td.fr_score[o] = s;
+            const int bit = (d - 1) * k + rank;
+            uint64_t w0 = d == 1 ? 0ull : td.fr_mask[((d - 1) * k + r) * MASK_WORDS];
+            uint64_t w1 = d == 1 ? 0ull : td.fr_mask[((d - 1) * k + r) * MASK_WORDS + 1];
+            if (bit < 64) w0 |= 1ull << bit; else w1 |= 1ull << (bit - 64);
+            td.fr_mask[o * MASK_WORDS] = w0;
+            td.fr_mask[o * MASK_WORDS + 1] = w1;
+        }
+    }
+}
+
+void launch_tree_expand(const TreeDev &td, int d, int k, int L, int rows, hipStream_t st) {
+    hipLaunchKernelGGL(tree_expand_kernel, dim3(1), dim3(256), 0, st, td, d, k, L, rows);
+}
+
+// ------------------------------------------------------------------ rerank + emit
+// Keep the n_keep best candidates; order them as candidates are ordered (parents first); node 0 is
+// the root x_t.  pos = t + depth; mask = node and its ancestors; slot = t + node index.
+constexpr int POOL_MAX = 2048;
+__global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int pool_n, int n_keep, int t,
+                                                             const int32_t *__restrict__ tokens_dev) {
+    __shared__ float sc[POOL_MAX];
+    __shared__ int16_t new_idx[POOL_MAX];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < pool_n; i += blockDim.x) sc[i] = td.pool_score[i];
+    __syncthreads();
+    for (int i = tid; i < pool_n; i += blockDim.x) {
+        const float s = sc[i];
+        int rank = 0;
+        for (int j = 0; j < pool_n; ++j) rank += (sc[j] > s) || (sc[j] == s && j < i);
+        new_idx[i] = rank < n_keep ? 1 : 0;
+    }
+    __syncthreads();
+    if (tid == 0) {                                  // running count -> node index (pool_n <= 2048)
+        int c = 0;
+        for (int i = 0; i < pool_n; ++i) new_idx[i] = new_idx[i] ? (int16_t)(++c) : (int16_t)-1;
+        td.n_nodes[0] = c + 1;
+        td.token[0] = tokens_dev[t]; td.parent[0] = -1; td.depth[0] = 0; td.pos[0] = t; td.score[0] = 0.f;
+        td.mask[0] = 1ull; td.mask[1] = 0ull;
+    }
+    __syncthreads();
+    for (int i = tid; i < pool_n; i += blockDim.x) {
+        const int ni = new_idx[i];
+        if (ni < 0) continue;
+        const int pp = td.pool_parent[i];
+        td.token[ni] = td.pool_token[i];
+        td.parent[ni] = pp < 0 ? 0 : new_idx[pp];
+        td.depth[ni] = td.pool_depth[i];
+        td.pos[ni] = t + td.pool_depth[i];
+        td.score[ni] = sc[i];
+        uint64_t w0 = 1ull, w1 = 0ull;               // the root
+        for (int u = i; u >= 0; u = td.pool_parent[u]) {
+            const int b = new_idx[u];
+            if (b < 64) w0 |= 1ull << b; else w1 |= 1ull << (b - 64);
+        }
+        td.mask[ni * MASK_WORDS] = w0;
+        td.mask[ni * MASK_WORDS + 1] = w1;
+    }
+}
+
+void launch_tree_finalize(const TreeDev &td, int k, int L, int n_keep, int t, const int32_t *tokens_dev,
+                          hipStream_t st) {
+    const int pool_n = k + (L - 1) * k * k;
+    hipLaunchKernelGGL(tree_finalize_kernel, dim3(1), dim3(1024), 0, st, td, pool_n, n_keep < pool_n ? n_keep : pool_n,
+                       t, tokens_dev);
+}
+
+// ------------------------------------------------------------------ rows of one specialist pass
+template <typename T>
+__global__ __launch_bounds__(256) void draft_assemble_kernel(
+    DraftRowPlan plan, int depth_index, int k, int d_model, const T *__restrict__ embed,
+    const int32_t *__restrict__ tokens_dev, const T *__restrict__ feat_stash, TreeDev td,
+    const float *__restrict__ fhat_prev, T *__restrict__ xin_tmp, T *__restrict__ x_out,
+    int32_t *__restrict__ pos_out, int32_t *__restrict__ slot_out, uint64_t *__restrict__ mask_out) {
+    const int row = blockIdx.x, kind = plan.kind[row], idx = plan.idx[row];
+    T *dst = x_out + (size_t)row * 2 * d_model;
+    uint64_t w0 = plan.mask0[0], w1 = plan.mask0[1];
+    if (kind == 0) {                    // committed pair [x_{i+1} ; f_i]
+        const T *e = embed + (size_t)tokens_dev[idx + 1] * d_model, *f = feat_stash + (size_t)idx * d_model;
+        for (int i = threadIdx.x; i < d_model; i += blockDim.x) { dst[i] = e[i]; dst[d_model + i] = f[i]; }
+    } else if (kind == 1) {             // a frontier row of an earlier depth, as assembled then
+        const T *src = xin_tmp + (size_t)idx * 2 * d_model;
+        for (int i = threadIdx.x; i < 2 * d_model; i += blockDim.x) dst[i] = src[i];
+    } else {                            // new frontier row: [emb(token_v) ; drafted feature of parent(v)]
+        const int o = depth_index * k + idx;
+        const T *e = embed + (size_t)td.fr_token[o] * d_model;
+        const float *f = fhat_prev + (size_t)td.fr_parent_rank[o] * d_model;
+        T *keep = xin_tmp + (size_t)((depth_index - 1) * k + idx) * 2 * d_model;
+        for (int i = threadIdx.x; i < d_model; i += blockDim.x) {
+            const T ev = e[i], fv = from_f<T>(f[i]);
+            dst[i] = ev; dst[d_model + i] = fv;
+            keep[i] = ev; keep[d_model + i] = fv;
+        }
+        w0 = td.fr_mask[o * MASK_WORDS]; w1 = td.fr_mask[o * MASK_WORDS + 1];
+    }
+    if (threadIdx.x == 0) {
+        pos_out[row] = plan.pos[row];
+        slot_out[row] = plan.slot[row];
+        mask_out[row * MASK_WORDS] = w0;
+        mask_out[row * MASK_WORDS + 1] = w1;
+    }
+}
+
+void launch_draft_assemble(const ModelDims &md, const DraftRowPlan &plan, int depth_index, int k,
+                           const void *embed, const int32_t *tokens_dev, const void *feat_stash,
+                           const TreeDev &td, const float *fhat_prev, void *xin_tmp, void *x_out,
+                           int32_t *pos_out, int32_t *slot_out, uint64_t *mask_out, hipStream_t st) {
+#define POSS_ASM(T)                                                                                          \
+    hipLaunchKernelGGL((draft_assemble_kernel<T>), dim3(plan.n_rows), dim3(256), 0, st, plan, depth_index, k,   \
+                       md.d, static_cast<const T *>(embed), tokens_dev, static_cast<const T *>(feat_stash), td, \
+                       fhat_prev, static_cast<T *>(xin_tmp), static_cast<T *>(x_out), pos_out, slot_out, mask_out)
+    if (md.dt == DT_F32) POSS_ASM(float); else if (md.dt == DT_BF16) POSS_ASM(bf16_t); else POSS_ASM(f16_t);
+#undef POSS_ASM
+}
+
+// ------------------------------------------------------------------ caller-supplied tree -> depth/pos/slot/mask
+__global__ void tree_upload_finish_kernel(int n, int t, const int32_t *__restrict__ parent, int32_t *__restrict__ depth,
+                                          int32_t *__restrict__ pos, int32_t *__restrict__ slot,
+                                          uint64_t *__restrict__ mask) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint64_t w0 = 0ull, w1 = 0ull;
+    int dep = -1;
+    for (int u = i; u >= 0; u = parent[u]) {
+        if (u < 64) w0 |= 1ull << u; else w1 |= 1ull << (u - 64);
+        ++dep;
+    }
+    depth[i] = dep; pos[i] = t + dep; slot[i] = t + i;
+    mask[i * MASK_WORDS] = w0; mask[i * MASK_WORDS + 1] = w1;
+}
+
+void launch_tree_upload_finish(int n, int t, const int32_t *token, const int32_t *parent, int32_t *depth,
+                               int32_t *pos, int32_t *slot, uint64_t *mask, hipStream_t st) {
+    (void)token;
+    hipLaunchKernelGGL(tree_upload_finish_kernel, dim3(1), dim3(128), 0, st, n, t, parent, depth, pos, slot, mask);
+}
+
+__global__ void iota_slots_kernel(int n, int t, int32_t *slot) {
+    const int i = threadIdx.x;
+    if (i < n) slot[i] = t + i;
+}
+void launch_iota_slots(int n, int t, int32_t *slot, hipStream_t st) {
+    hipLaunchKernelGGL(iota_slots_kernel, dim3(1), dim3(128), 0, st, n, t, slot);
+}
+
+// ------------------------------------------------------------------ greedy acceptance walk
+// walk[0] = m (accepted draft tokens), walk[1] = bonus token, walk[2..2+m] = node indices of the path.
+__global__ __launch_bounds__(64) void accept_walk_kernel(const int32_t *__restrict__ token, const int32_t *__restrict__ parent,
+                                                         const int32_t *__restrict__ g, const int32_t *__restrict__ n_nodes,
+                                                         int max_path, int32_t *__restrict__ walk) {
+    const int lane = threadIdx.x, n = n_nodes[0];
+    int cur = 0, m = 0;
+    if (lane == 0) walk[2] = 0;
+    while (m < max_path) {
+        const int want = g[cur];
+        int found = 0x7fffffff;
+        for (int i = 1 + lane; i < n; i += 64)
+            if (parent[i] == cur && token[i] == want) found = min(found, i);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) found = min(found, __shfl_xor(found, o, 64));
+        if (found == 0x7fffffff) break;
+        cur = found; ++m;
+        if (lane == 0) walk[2 + m] = cur;
+    }
+    if (lane == 0) { walk[0] = m; walk[1] = g[cur]; }
+}
+
+void launch_accept_walk(const int32_t *token, const int32_t *parent, const int32_t *g, const int32_t *n_nodes,
+                        int max_path, int32_t *walk, hipStream_t st) {
+    hipLaunchKernelGGL(accept_walk_kernel, dim3(1), dim3(64), 0, st, token, parent, g, n_nodes, max_path, walk);
+}
+
+// ------------------------------------------------------------------ commit
+// Keys/values of the accepted rows move from slot t + path[j] to slot t + j.  A destination may be
+// another move's source, so each (layer, KV head) workgroup gathers everything, synchronises, scatters.
+template <typename T>
+__global__ __launch_bounds__(256) void commit_kv_kernel(const KVCache *__restrict__ caches, const int32_t *__restrict__ walk,
+                                                        int t, int hkv, int dh) {
+    extern __shared__ unsigned char smem[];
+    T *kbuf = reinterpret_cast<T *>(smem);
+    const int m = walk[0], n = (m + 1) * dh;
+    T *vbuf = kbuf + n;
+    const KVCache kv = caches[blockIdx.x];
+    const int head = blockIdx.y;
+    T *kc = static_cast<T *>(kv.k), *vc = static_cast<T *>(kv.vt);
+    for (int e = threadIdx.x; e < n; e += blockDim.x) {
+        const int j = e / dh, i = e % dh, src = t + walk[2 + j];
+        kbuf[e] = kc[k_offset(kv, src, head, hkv, dh) + i];
+        vbuf[e] = vc[vt_offset(kv, src, head, hkv, dh, i)];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < n; e += blockDim.x) {
+        const int j = e / dh, i = e % dh, dst = t + j;
+        kc[k_offset(kv, dst, head, hkv, dh) + i] = kbuf[e];
+        vc[vt_offset(kv, dst, head, hkv, dh, i)] = vbuf[e];
+    }
+}
+
+// Features of the accepted rows become f_{t+j}; accepted tokens and the bonus token join the stream.
+template <typename T>
+__global__ __launch_bounds__(256) void commit_misc_kernel(const int32_t *__restrict__ walk, int t, int d_model,
+                                                          const float *__restrict__ feats, T *__restrict__ feat_stash,
+                                                          int32_t *__restrict__ tokens_dev,
+                                                          const int32_t *__restrict__ tree_token) {
+    const int j = blockIdx.x, m = walk[0];
+    if (j > m) return;
+    const float *src = feats + (size_t)walk[2 + j] * d_model;
+    T *dst = feat_stash + (size_t)(t + j) * d_model;
+    for (int i = threadIdx.x; i < d_model; i += blockDim.x) dst[i] = from_f<T>(src[i]);
+    if (threadIdx.x == 0) tokens_dev[t + 1 + j] = j < m ? tree_token[walk[2 + j + 1]] : walk[1];
+}
+
+void launch_commit(const ModelDims &md, int n_layers, const KVCache *caches_dev, const int32_t *walk, int max_path,
+                   int t, const float *feats, void *feat_stash, int32_t *tokens_dev, const int32_t *tree_token,
+                   hipStream_t st) {
+    const size_t lds = (size_t)2 * (max_path + 1) * md.dh * dtype_size(md.dt);
+#define POSS_COMMIT(T)                                                                                             \
+    hipLaunchKernelGGL((commit_kv_kernel<T>), dim3(n_layers, md.hkv), dim3(256), lds, st, caches_dev, walk, t, md.hkv, \
+                       md.dh);                                                                                     \
+    hipLaunchKernelGGL((commit_misc_kernel<T>), dim3(max_path + 1), dim3(256), 0, st, walk, t, md.d, feats,           \
+                       static_cast<T *>(feat_stash), tokens_dev, tree_token)
+    if (md.dt == DT_F32) { POSS_COMMIT(float); } else if (md.dt == DT_BF16) { POSS_COMMIT(bf16_t); } else { POSS_COMMIT(f16_t); }
+#undef POSS_COMMIT
+}
+
+}  // namespace poss

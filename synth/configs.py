@@ -38,6 +38,7 @@ class ModelConfig:
     weight_seed: int = 2506
     prompt_seed: int = 3566
     norm_gain_jitter: float = 0.0    # 0 => RMSNorm gains are exactly 1
+    kv_page_order: int = 0           # physical page order of the KV caches (layout tests)
 
     @property
     def tree_rows(self):

@@ -16,3 +16,17 @@ def pytest_configure(config):
 def c0():
     from synth import get_config
     return get_config("c0_tiny_f32")
+
+
+def pytest_collection_modifyitems(config, items):
+    try:
+        import torch
+        ok = torch.cuda.is_available()
+    except Exception:
+        ok = False
+    if ok:
+        return
+    skip = pytest.mark.skip(reason="no GPU in this environment")
+    for item in items:
+        if "gpu" in item.keywords:
+            item.add_marker(skip)

@@ -48,7 +48,7 @@ def test_lossless_with_injected_trees_of_every_accept_length():
         # chain of the m true tokens, a wrong token after it, plus a decoy branch at the root
         wrong = lambda tok: (tok + 1) % cfg.vocab
         token, parent = [y[0]], [-1]
-        token.append(wrong(y[1])); parent.append(0)
+        token.append((y[1] + 2) % cfg.vocab); parent.append(0)
         for j in range(1, m + 1):
             token.append(y[j]); parent.append(0 if j == 1 else len(token) - 2)
         last = len(token) - 1 if m else 0
