@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the PosS draft-and-verify round on one MI355X.
+
+A "step" is one round: poss_draft_tree -> poss_verify_tree -> poss_accept_and_commit through the
+C ABI, on a synthetic random-init model of Llama-3-8B shape (3 specialists x 2 positions, tree
+width 10, depth 6, 60 draft tokens, 512-token uniform-random prompt), everything resident in HBM.
+Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "draft+verify round latency (ms), tokens/s and HBM GB/s, Llama-3-8B shape, bs=1"
+HBM_PEAK_GBPS = 8000.0
+
+
+def round_bytes(cfg, t, a):
+    """Algorithmic HBM bytes of one round: every weight of every GEMM once, plus the KV read."""
+    es = 4 if cfg.dtype == 0 else 2
+    d, qd, kd, F, V = cfg.d_model, cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim, cfg.d_ffn, cfg.vocab
+    layer = (qd + 2 * kd) * d + d * qd + 2 * F * d + d * F + 2 * d
+    head = V * d + d
+    target = cfg.n_layers * layer + head
+    draft = cfg.depth * (2 * d * d + d + layer + head)
+    kv_target = cfg.n_layers * t * 2 * kd
+    kv_draft = cfg.depth * t * 2 * kd
+    return es * (target + draft + kv_target + kv_draft)
+
+
+def cpu_baseline(cfg, seconds_hint=20.0):
+    """The CPU oracle timed on a bounded sample of the same round and scaled to a whole round:
+    one of the target's layers and its Head over the 61 tree rows at t = n_prompt, and one
+    specialist pass with its Head over top_k rows."""
+    import numpy as np
+    from synth import make_weights
+    from oracle.model import Weights, decoder_layer, head, specialist_pass
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    act = None if cfg.dtype == 0 else cfg.dtype
+    names = ["layer0.", "lm_head", "final_norm", "embed", "spec0."]
+    W = Weights(cfg, make_weights(cfg, names=names), cache=False)
+    rng = np.random.default_rng(0)
+    t, M, k = cfg.n_prompt, cfg.total_tokens + 1, cfg.top_k
+    h = rng.normal(size=(M, cfg.d_model))
+    kc = rng.normal(size=(t, cfg.n_kv_heads, cfg.head_dim))
+    vc = rng.normal(size=(t, cfg.n_kv_heads, cfg.head_dim))
+    allowed = np.ones((M, t + M), dtype=bool)
+    allowed[:, t:] = np.tril(np.ones((M, M), dtype=bool))
+    t0 = time.perf_counter()
+    f, _, _ = decoder_layer(W, "layer0.", cfg, h, np.arange(t, t + M), kc, vc, allowed, act)
+    t_layer = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    head(W, cfg, f, act)
+    t_head_v = time.perf_counter() - t0
+    n_seq = t + k
+    toks = rng.integers(0, cfg.vocab, size=n_seq)
+    feats = rng.normal(size=(n_seq, cfg.d_model))
+    al = np.ones((k, n_seq), dtype=bool)
+    t0 = time.perf_counter()
+    out = specialist_pass(W, cfg, 0, toks, feats, np.arange(n_seq), al, list(range(t, n_seq)), act)
+    t_spec = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    head(W, cfg, out, act)
+    t_head_d = time.perf_counter() - t0
+    round_s = cfg.n_layers * t_layer + t_head_v + cfg.depth * (t_spec + t_head_d)
+    return dict(value=1.0 / round_s, unit="tokens/s", cores=int(cores), kind="oracle",
+                sample=("oracle timed on 1 of %d target layers + Head over %d tree rows at t=%d, and 1 of %d "
+                        "specialist passes + Head over %d rows; scaled to a full round at 1 committed "
+                        "token per round; %.2f s measured, %.1f s per round extrapolated"
+                        % (cfg.n_layers, M, t, cfg.depth, k, t_layer + t_head_v + t_spec + t_head_d, round_s)),
+                ms_per_round=round_s * 1e3)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c1_llama3_8b_3x2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-wgs", type=int, default=0)
+    ap.add_argument("--attn-split", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2506_03566_amd as P
+    from synth import get_config, make_prompt
+    from synth.gpu import make_weights_on_device
+
+    cfg = get_config(args.config)
+    P.load_library()                                  # fail loudly if the HIP library is missing
+    t0 = time.perf_counter()
+    weights = make_weights_on_device(cfg)
+    t_gen = time.perf_counter() - t0
+    ctx = P.Poss(cfg, weights)
+    del weights
+    torch.cuda.empty_cache()
+    if args.gemm_wgs or args.attn_split:
+        ctx.set_tuning(args.gemm_wgs, args.attn_split)
+    prompt = make_prompt(cfg)
+    ctx.prefill(prompt)
+
+    def one_round():
+        ctx.draft_tree(want_tree=False)
+        ctx.verify_tree(None, want_argmax=False)
+        return ctx.accept_and_commit()
+
+    for _ in range(args.warmup):
+        one_round()
+    s0 = ctx.stats()
+    base = (s0.rounds, s0.committed_tokens, s0.ms_draft, s0.ms_verify, s0.ms_commit)
+    t_begin = len(ctx.tokens()) - 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_round()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    s1 = ctx.stats()
+    rounds = s1.rounds - base[0]
+    committed = s1.committed_tokens - base[1]
+    ms_round = wall * 1e3 / rounds
+    t_mid = t_begin + committed // 2
+    bytes_round = round_bytes(cfg, t_mid, 1)
+    gbps = bytes_round / (ms_round * 1e-3) / 1e9
+
+    # dominant kernel: the weight-streaming GEMM, timed per launch with HIP events on the library's stream
+    ctx.profile_gemm(True)
+    prof_rounds = min(3, args.steps)
+    for _ in range(prof_rounds):
+        one_round()
+    launches, gemm_ms, gemm_bytes = ctx.gemm_profile()
+    ctx.profile_gemm(False)
+    achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
+    roofline = dict(bound="hbm", kernel="gemm_stream_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS,
+                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4), traffic=None,
+                    launches_per_round=launches // max(prof_rounds, 1),
+                    avg_launch_us=round(gemm_ms * 1e3 / max(launches, 1), 2),
+                    weight_bytes_per_round=gemm_bytes / max(prof_rounds, 1))
+
+    out = dict(metric=METRIC, value=round(committed / wall, 2), unit="tokens/s", n_gpus=1, steps=rounds,
+               warmup=args.warmup, ms_per_step=round(ms_round, 4), higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype={0: "f32", 1: "bf16", 2: "f16"}[cfg.dtype], data="synthetic",
+               config=dict(workload=cfg.name, target_layers=cfg.n_layers, d_model=cfg.d_model, vocab=cfg.vocab,
+                           specialists=cfg.n_specialists, positions_per_specialist=cfg.positions_per_specialist,
+                           top_k=cfg.top_k, depth=cfg.depth, total_tokens=cfg.total_tokens,
+                           n_prompt=cfg.n_prompt, batch=1, t_at_timing=t_mid),
+               round_latency_ms=round(ms_round, 4), hbm_gbps=round(gbps, 1), hbm_frac=round(gbps / HBM_PEAK_GBPS, 4),
+               bytes_per_round=bytes_round, tau_gen=round(committed / rounds, 3),
+               phase_ms=dict(draft=round((s1.ms_draft - base[2]) / rounds, 4),
+                             verify=round((s1.ms_verify - base[3]) / rounds, 4),
+                             commit=round((s1.ms_commit - base[4]) / rounds, 4)),
+               setup_s=dict(weights=round(t_gen, 1)), roofline=roofline)
+    ctx.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
