@@ -55,7 +55,10 @@ struct poss_ctx {
     KVCache *target_kv_dev;
     size_t cache_bytes_each;
     // activations
-    float *h, *part, *logits, *feats, *fhat[2], *topk_scratch, *taps_user;
+    float *h, *part, *logits, *feats, *fhat[2], *topk_scratch, *taps_user, *ss;
+    unsigned *counters;
+    float2 *cs;
+    int ss_ld, n_counters;
     void *u, *xin, *q, *attn_out, *act;
     AttnScratch attn_sc;
     int32_t *row_pos, *row_slot, *tree_slot;
@@ -142,7 +145,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         out.push_back(a.take(packed_elems(dt, qd + 2 * kd, d) * es));
         out.push_back(a.take(packed_elems(dt, d, qd) * es));
         out.push_back(a.take(d * es));
-        out.push_back(a.take(packed_elems(dt, 2 * F, d) * es));
+        out.push_back(a.take(packed_elems(dt, gate_up_rows(F), d) * es));
         out.push_back(a.take(packed_elems(dt, d, F) * es));
     };
     WeightSlots local;
@@ -167,14 +170,20 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     // activations
     const int R = MAX_ROWS;
     size_t part_floats = 0;
-    const int shapes[6][2] = {{qd + 2 * kd, d}, {d, qd}, {2 * F, d}, {d, F}, {d, 2 * d}, {V, d}};
+    const int shapes[6][2] = {{qd + 2 * kd, d}, {d, qd}, {gate_up_rows(F), d}, {d, F}, {d, 2 * d}, {V, d}};
+    int max_tiles = 1;
     for (int i = 0; i < 5; ++i) {
         // split count does not depend on M; planes are at most R rows
         GemmShape g = gemm_plan(dt, R, shapes[i][0], shapes[i][1], 4096);   // upper bound on splits
         const size_t f = (size_t)g.S * R * g.Npad;
         if (f > part_floats) part_floats = f;
+        if (g.Npad / GEMM_BLOCK_N > max_tiles) max_tiles = g.Npad / GEMM_BLOCK_N;
     }
     float *h = a.take_n<float>((size_t)R * d);
+    const int ss_ld = gemm_npad(d) / GEMM_BLOCK_N;
+    float *ss = a.take_n<float>((size_t)R * ss_ld);
+    unsigned *counters = a.take_n<unsigned>(max_tiles);
+    float2 *cs = a.take_n<float2>((size_t)R * (c.head_dim / 2));
     float *part = a.take_n<float>(part_floats);
     float *logits = a.take_n<float>((size_t)R * gemm_npad(V));
     float *feats = a.take_n<float>((size_t)R * d);
@@ -214,6 +223,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         for (int s = 0; s < c.n_specialists; ++s)
             ctx->spec_kv.push_back(KVCache{kvp[2 * (c.n_layers + s)], kvp[2 * (c.n_layers + s) + 1], pt, shift});
         ctx->target_kv_dev = kv_dev;
+        ctx->ss = ss; ctx->ss_ld = ss_ld; ctx->counters = counters; ctx->cs = cs; ctx->n_counters = max_tiles;
         ctx->h = h; ctx->part = part; ctx->logits = logits; ctx->feats = feats; ctx->fhat[0] = fhat0; ctx->fhat[1] = fhat1;
         ctx->topk_scratch = topk_scr; ctx->u = u; ctx->xin = xin; ctx->q = q; ctx->attn_out = ao; ctx->act = act;
         ctx->attn_sc = AttnScratch{ao_part, ml_part};
@@ -226,11 +236,11 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
 
 // ------------------------------------------------------------------------------------------ GEMM wrapper
 GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int ldx, int M, float *part,
-                   bool single_split) {
+                   bool single_split, EpiArgs epi) {
     GemmShape g = gemm_plan(c->md.dt, M, N, K, single_split ? 1 : c->gemm_target_wgs);
     const bool prof = c->prof_on && c->prof_n < PROFILE_EVENTS;
     if (prof) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->st);
-    launch_gemm(c->md.dt, g, Wp, X, ldx, part, c->st);
+    launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->st);
     if (prof) {
         (void)hipEventRecord(c->prof_ev[2 * c->prof_n + 1], c->st);
         ++c->prof_n;
@@ -239,24 +249,38 @@ GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int
     return g;
 }
 
+EpiArgs epi_residual(poss_ctx *c, bool residual, const void *bias, float *h_copy) {
+    EpiArgs e{};
+    e.mode = EPI_RESIDUAL; e.h = c->h; e.bias = bias; e.residual = residual ? 1 : 0; e.h_copy = h_copy;
+    e.ss = c->ss; e.ss_ld = c->ss_ld;
+    return e;
+}
+
+void norm_rows(poss_ctx *c, int rows, const void *gain) {
+    launch_norm_apply(c->md, c->h, c->ss, c->ss_ld, gemm_npad(c->md.d) / GEMM_BLOCK_N, rows, gain, c->u, c->st);
+}
+
 // One decoder layer on rows_all rows (all produce K/V) of which the first rows_q go through
-// attention and the MLP.  On entry c->u holds T(rmsnorm(h) * attn_norm); on exit c->h is updated and
-// c->u holds T(rmsnorm(h) * next_gain).
+// attention and the MLP.  On entry c->u holds T(rmsnorm(h) * attn_norm) and c->cs the rotary table
+// of the rows; on exit c->h is updated and c->u holds T(rmsnorm(h) * next_gain).
 void run_layer(poss_ctx *c, const LayerW &w, const KVCache &kv, int rows_all, int rows_q, const RowMeta &rm,
                int n_prefix, int region_len, const void *next_gain, float *h_copy) {
     const ModelDims &md = c->md;
     const int qd = md.hq * md.dh, kd = md.hkv * md.dh;
-    GemmShape g = run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false);
-    launch_reduce_rope_kv(md, g, c->part, rows_all, rows_q, rm, c->inv_freq, c->q, kv, c->st);
+    EpiArgs e{};
+    e.mode = EPI_ROPE_KV; e.rows_q = rows_q; e.cs = c->cs; e.slot = rm.slot; e.q = c->q; e.kv = kv;
+    e.hq = md.hq; e.hkv = md.hkv; e.dh = md.dh;
+    run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false, e);
     if (rows_q == 0) return;
     launch_attention(md, c->q, rows_q, rm, n_prefix, region_len, kv, c->attn_keys_per_split, c->attn_sc,
                      c->attn_out, c->st);
-    g = run_gemm(c, w.wo, md.d, qd, c->attn_out, qd, rows_q, c->part, false);
-    launch_reduce_res_norm(md, g, c->part, rows_q, true, nullptr, w.mlp_norm, c->h, c->u, nullptr, c->st);
-    g = run_gemm(c, w.wgu, 2 * md.ffn, md.d, c->u, md.d, rows_q, c->part, false);
-    launch_reduce_silu(md, g, c->part, rows_q, c->act, c->st);
-    g = run_gemm(c, w.wdown, md.d, md.ffn, c->act, md.ffn, rows_q, c->part, false);
-    launch_reduce_res_norm(md, g, c->part, rows_q, true, nullptr, next_gain, c->h, c->u, h_copy, c->st);
+    run_gemm(c, w.wo, md.d, qd, c->attn_out, qd, rows_q, c->part, false, epi_residual(c, true, nullptr, nullptr));
+    norm_rows(c, rows_q, w.mlp_norm);
+    EpiArgs es{};
+    es.mode = EPI_SILU; es.act = c->act; es.F = md.ffn;
+    run_gemm(c, w.wgu, gate_up_rows(md.ffn), md.d, c->u, md.d, rows_q, c->part, false, es);
+    run_gemm(c, w.wdown, md.d, md.ffn, c->act, md.ffn, rows_q, c->part, false, epi_residual(c, true, nullptr, h_copy));
+    norm_rows(c, rows_q, next_gain);
 }
 
 // Target pass over `rows` rows whose tokens / metadata are on the device.  Leaves features in
@@ -264,6 +288,7 @@ void run_layer(poss_ctx *c, const LayerW &w, const KVCache &kv, int rows_all, in
 void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowMeta &rm, int n_prefix,
                     int region_len) {
     const ModelDims &md = c->md;
+    launch_rope_table(rm.pos, c->inv_freq, md.dh / 2, rows, c->cs, c->st);
     launch_embed_norm(md, c->embed, tokens_dev, rows, c->layers[0].attn_norm, c->h, c->u, c->st);
     const int nl = c->cfg.n_layers;
     for (int l = 0; l < nl; ++l) {
@@ -279,7 +304,9 @@ void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowM
 
 // logits[rows][Npad] = Head(features) for the rows whose final-normed activations are in c->u
 GemmShape run_head(poss_ctx *c, int rows) {
-    return run_gemm(c, c->lm_head, c->md.vocab, c->md.d, c->u, c->md.d, rows, c->logits, true);
+    EpiArgs e{};
+    e.mode = EPI_PLAIN;
+    return run_gemm(c, c->lm_head, c->md.vocab, c->md.d, c->u, c->md.d, rows, c->logits, true, e);
 }
 
 __global__ void causal_meta_kernel(int n, int c0, int32_t *pos, int32_t *slot, uint64_t *mask) {
@@ -315,9 +342,10 @@ void spec_pass(poss_ctx *c, int s, const DraftRowPlan &plan, int depth_index, in
     const SpecW &w = c->specs[s];
     launch_draft_assemble(md, plan, depth_index, c->cfg.top_k, c->embed, c->tokens_dev, c->feat_stash, c->td,
                           fhat_prev, c->xin_tmp, c->xin, c->row_pos, c->row_slot, c->row_mask, c->st);
-    GemmShape g = run_gemm(c, w.fc_w, md.d, 2 * md.d, c->xin, 2 * md.d, plan.n_rows, c->part, false);
-    launch_reduce_res_norm(md, g, c->part, plan.n_rows, false, c->cfg.fc_bias ? w.fc_b : nullptr, w.layer.attn_norm,
-                           c->h, c->u, nullptr, c->st);
+    launch_rope_table(c->row_pos, c->inv_freq, md.dh / 2, plan.n_rows, c->cs, c->st);
+    run_gemm(c, w.fc_w, md.d, 2 * md.d, c->xin, 2 * md.d, plan.n_rows, c->part, false,
+             epi_residual(c, false, c->cfg.fc_bias ? w.fc_b : nullptr, nullptr));
+    norm_rows(c, plan.n_rows, w.layer.attn_norm);
     RowMeta rm{c->row_pos, c->row_slot, c->row_mask};
     run_layer(c, w.layer, c->spec_kv[s], plan.n_rows, rows_q, rm, n_prefix, region_len, c->final_norm, fhat_out);
 }
@@ -355,7 +383,7 @@ void pack_layer(poss_ctx *c, const void *const *src, const std::vector<void *> &
     launch_pack(dt, PackSrc{{src[1], src[2], src[3]}, {qd, kd, kd}}, d, dst[base + 1], c->st);
     launch_pack(dt, PackSrc{{src[4], nullptr, nullptr}, {d, 0, 0}}, qd, dst[base + 2], c->st);
     (void)hipMemcpyAsync(dst[base + 3], src[5], d * es, hipMemcpyDeviceToDevice, c->st);
-    launch_pack(dt, PackSrc{{src[6], src[7], nullptr}, {F, F, 0}}, d, dst[base + 4], c->st);
+    launch_pack(dt, PackSrc{{src[6], src[7], nullptr}, {F, F, 0}, 1}, d, dst[base + 4], c->st);
     launch_pack(dt, PackSrc{{src[8], nullptr, nullptr}, {d, 0, 0}}, F, dst[base + 5], c->st);
 }
 
@@ -508,7 +536,9 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
         if (c0 + rows == n_prompt) {
             // Head on the last row only: its normed activations sit at row rows-1 of c->u
             const char *last = static_cast<const char *>(c->u) + (size_t)(rows - 1) * md.d * dtype_size(md.dt);
-            GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true);
+            EpiArgs pe{};
+            pe.mode = EPI_PLAIN;
+            GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true, pe);
             launch_argmax(c->logits, g.Npad, 1, md.vocab, c->argmax_dev, c->st);
             HIP_TRY(c, hipMemcpyAsync(c->tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
         }
@@ -785,7 +815,7 @@ size_t poss_debug_gemm_scratch_bytes(int32_t dtype, int32_t M, int32_t N, int32_
     if (dtype < 0 || dtype > 2 || M < 1 || M > MAX_ROWS || N < 1 || K < 1) return 0;
     GemmShape g = gemm_plan(dtype, M, N, K, 4096);
     return (packed_elems(dtype, N, K) * dtype_size(dtype) + 255) / 256 * 256 +
-           (size_t)g.S * MAX_ROWS * g.Npad * sizeof(float) + 512;
+           (size_t)g.S * MAX_ROWS * g.Npad * sizeof(float) + (size_t)(g.Npad / GEMM_BLOCK_N) * sizeof(unsigned) + 1024;
 }
 
 int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_t M, int32_t N, int32_t K,
@@ -801,14 +831,16 @@ int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_
     void *wp = p;
     p += (packed_elems(dtype, N, K) * dtype_size(dtype) + 255) / 256 * 256;
     float *part = reinterpret_cast<float *>(p);
+    p += ((size_t)g.S * MAX_ROWS * g.Npad * sizeof(float) + 255) / 256 * 256;
+    EpiArgs epi{};
+    epi.mode = EPI_PLAIN; epi.out = static_cast<float *>(y); epi.ld_out = N;
     launch_pack(dtype, PackSrc{{w, nullptr, nullptr}, {N, 0, 0}}, K, wp, st);
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return fail(nullptr, POSS_E_HIP, "poss_debug_gemm: event creation failed");
-    launch_gemm(dtype, g, wp, x, K, part, st);
+    launch_gemm(dtype, g, wp, x, K, part, epi, st);
     (void)hipEventRecord(e0, st);
-    for (int i = 0; i < repeats; ++i) launch_gemm(dtype, g, wp, x, K, part, st);
+    for (int i = 0; i < repeats; ++i) launch_gemm(dtype, g, wp, x, K, part, epi, st);
     (void)hipEventRecord(e1, st);
-    hipLaunchKernelGGL(sum_planes_kernel, dim3((N + 255) / 256, M), dim3(256), 0, st, part, g.S, (size_t)g.Mpad * g.Npad, g.Npad, N, static_cast<float *>(y));
     hipError_t e = hipStreamSynchronize(st);
     float ms = 0.f;
     (void)hipEventElapsedTime(&ms, e0, e1);

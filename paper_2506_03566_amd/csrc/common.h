@@ -38,17 +38,18 @@ struct GemmShape {
     int M;          // real rows
     int N, K;       // logical sizes
     int Npad, Kpad; // padded sizes of the packed weight
-    int S;          // K splits; partial sums land in part[S][Mpad16][Npad]
+    int S;          // K splits; partial sums land in part[S][Mpad][Npad]
     int chunks_per_split;
-    int Mpad;       // rows rounded up to 16 (row stride of a partial plane is Npad)
+    int Mpad;       // rows of one partial plane (row stride Npad)
 };
 GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs);
-// part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.
-void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 hipStream_t st);
 
-struct PackSrc { const void *ptr[3]; int rows[3]; };  // up to three matrices stacked along N
+struct PackSrc {
+    const void *ptr[3]; int rows[3];   // up to three matrices stacked along N
+    int interleave64;                  // 1: ptr[0]/ptr[1] alternate in groups of 64 rows (gate | up per 128-column tile)
+};
 void launch_pack(int dt, const PackSrc &src, int K, void *dst, hipStream_t st);
+static inline int gate_up_rows(int F) { return 2 * round_up(F, 64); }
 
 // ---------------------------------------------------------------- KV caches
 // K  : [phys_page][Hkv][P][dh]      (row per token)
@@ -72,19 +73,35 @@ struct RowMeta {
     const uint64_t *mask;   // [rows][MASK_WORDS] visibility over region slots (bit j = slot region0 + j)
 };
 
-// ---------------------------------------------------------------- launchers: elementwise / reductions
+// ---------------------------------------------------------------- GEMM with fused epilogue
+// The stream kernel writes split-K partial planes; an epilogue kernel with one workgroup per
+// 128-column tile sums them in split order and applies the fused operation.
+enum { EPI_PLAIN = 0, EPI_ROPE_KV = 1, EPI_RESIDUAL = 2, EPI_SILU = 3 };
+struct EpiArgs {
+    int mode;
+    // EPI_PLAIN: out[m][n] = sum (with out == nullptr and S == 1 plane 0 is the result, row stride Npad)
+    float *out; int ld_out;
+    // EPI_ROPE_KV: columns are [q heads | k heads | v heads]; rows < rows_q get a rotated query,
+    // every row its rotated key and its value written to cache slot slot[m]
+    int rows_q; const float2 *cs; const int32_t *slot; void *q; KVCache kv; int hq, hkv, dh;
+    // EPI_RESIDUAL: h[m][n] = sum + bias[n] + (residual ? h[m][n] : 0); h_copy likewise;
+    // ss[m][tile] = sum over the tile's columns of h^2 (RMSNorm partials)
+    float *h; const void *bias; int residual; float *h_copy; float *ss; int ss_ld;
+    // EPI_SILU: tile j holds gate[64j..64j+63] | up[64j..64j+63]; act[m][f] = T(silu(gate) * up)
+    void *act; int F;
+};
+// part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.
+void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
+                 const EpiArgs &epi, hipStream_t st);
+
+// ---------------------------------------------------------------- launchers: elementwise
 void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *tokens, int rows,
                        const void *gain, float *h, void *u, hipStream_t st);
-// rows_q leading rows get a rotated query; all `rows` get key/value written into the cache
-void launch_reduce_rope_kv(const ModelDims &md, const GemmShape &g, const float *part, int rows,
-                           int rows_q, const RowMeta &rm, const double *inv_freq, void *q,
-                           const KVCache &kv, hipStream_t st);
-// h = (residual ? h : 0) + sum(part) + bias ; u = T(rmsnorm(h) * gain); optional fp32 copies of h
-void launch_reduce_res_norm(const ModelDims &md, const GemmShape &g, const float *part, int rows,
-                            bool residual, const void *bias, const void *gain, float *h, void *u,
-                            float *h_copy, hipStream_t st);
-void launch_reduce_silu(const ModelDims &md, const GemmShape &g, const float *part, int rows, void *act,
-                        hipStream_t st);
+// u = T(h / sqrt(sum_tiles ss / d + eps) * gain)
+void launch_norm_apply(const ModelDims &md, const float *h, const float *ss, int ss_ld, int n_tiles, int rows,
+                       const void *gain, void *u, hipStream_t st);
+// cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)), angle formed in float64
+void launch_rope_table(const int32_t *pos, const double *inv_freq, int half, int rows, float2 *cs, hipStream_t st);
 void launch_argmax(const float *logits, int ld, int rows, int vocab, int32_t *out, hipStream_t st);
 void launch_copy_rows_f32(const float *src, int ld_src, float *dst, int ld_dst, int rows, int cols,
                           hipStream_t st);

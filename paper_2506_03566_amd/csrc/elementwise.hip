@@ -1,7 +1,6 @@
-// Consumers of the GEMM's split-K partial sums, fused with what follows each projection in a
-// Llama decoder layer: rotary embedding + KV-cache write, residual add + RMSNorm, SiLU * up,
-// plus embedding gather, argmax and row copies.  All arithmetic in float32; values become the
-// storage type only where they are the next GEMM's operand or a cache entry.
+// Small kernels around the GEMMs: embedding gather + first RMSNorm, RMSNorm application from the
+// GEMM epilogue's partial sums of squares, rotary table, argmax, row copies.  All arithmetic in
+// float32; values become the storage type only where they are the next GEMM's operand.
 #include "device_utils.h"
 
 namespace poss {
@@ -12,12 +11,6 @@ namespace poss {
         case DT_BF16: { using T = bf16_t; __VA_ARGS__; } break;              \
         default:      { using T = f16_t;  __VA_ARGS__; } break;              \
     }
-
-__device__ __forceinline__ float sum_parts(const float *part, size_t plane, int S, size_t idx) {
-    float a = part[idx];
-    for (int s = 1; s < S; ++s) a += part[(size_t)s * plane + idx];
-    return a;
-}
 
 // ------------------------------------------------------------------ h = emb[token]; u = T(rmsnorm(h) g)
 template <typename T>
@@ -46,113 +39,44 @@ void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *to
                                             static_cast<const T *>(gain), h, static_cast<T *>(u)));
 }
 
-// ------------------------------------------------------------------ QKV partials -> rotated q, cache writes
-// Rotary embedding pairs element i with i + dh/2 and turns pair i by pos * theta^(-2i/dh); the
-// angle is formed in float64 so that positions in the thousands keep float32-accurate sines.
+// ------------------------------------------------------------------ rotary table of one pass
+// cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)).  The angle is formed in float64 so positions in
+// the thousands keep float32-accurate sines; one table serves every layer of the pass.
+__global__ void rope_table_kernel(const int32_t *__restrict__ pos, const double *__restrict__ inv_freq, int half,
+                                  float2 *__restrict__ cs) {
+    const int m = blockIdx.x, i = threadIdx.x;
+    if (i >= half) return;
+    double s, c;
+    sincos((double)pos[m] * inv_freq[i], &s, &c);
+    cs[m * half + i] = make_float2((float)c, (float)s);
+}
+
+void launch_rope_table(const int32_t *pos, const double *inv_freq, int half, int rows, float2 *cs, hipStream_t st) {
+    hipLaunchKernelGGL(rope_table_kernel, dim3(rows), dim3(half < 64 ? 64 : half), 0, st, pos, inv_freq, half, cs);
+}
+
+// ------------------------------------------------------------------ u = T(rmsnorm(h) g) from tile partials
+// ss[m][tile] holds the sum of squares of 128 columns of h (written by the GEMM epilogue); every
+// workgroup re-adds the row's partials in tile order.
 template <typename T>
-__global__ __launch_bounds__(256) void reduce_rope_kv_kernel(
-    const float *__restrict__ part, size_t plane, int S, int Npad, int rows_q, const int32_t *__restrict__ pos,
-    const int32_t *__restrict__ slot, const double *__restrict__ inv_freq, int hq, int hkv, int dh,
-    T *__restrict__ q, KVCache kv) {
-    __shared__ float cs[128][2];
-    const int m = blockIdx.x, half = dh >> 1;
-    if ((int)threadIdx.x < half) {
-        double s, c;
-        sincos((double)pos[m] * inv_freq[threadIdx.x], &s, &c);
-        cs[threadIdx.x][0] = (float)c;
-        cs[threadIdx.x][1] = (float)s;
-    }
-    __syncthreads();
-    const size_t row0 = (size_t)m * Npad;
-    if (m < rows_q) {
-        for (int p = threadIdx.x; p < hq * half; p += blockDim.x) {
-            const int h = p / half, i = p % half;
-            const float x1 = sum_parts(part, plane, S, row0 + h * dh + i);
-            const float x2 = sum_parts(part, plane, S, row0 + h * dh + i + half);
-            const float c = cs[i][0], s = cs[i][1];
-            T *dst = q + ((size_t)m * hq + h) * dh;
-            dst[i] = from_f<T>(x1 * c - x2 * s);
-            dst[i + half] = from_f<T>(x2 * c + x1 * s);
-        }
-    }
-    const int sl = slot[m];
-    T *kc = static_cast<T *>(kv.k), *vc = static_cast<T *>(kv.vt);
-    for (int p = threadIdx.x; p < hkv * half; p += blockDim.x) {
-        const int h = p / half, i = p % half;
-        const size_t col = (size_t)hq * dh + h * dh + i;
-        const float x1 = sum_parts(part, plane, S, row0 + col);
-        const float x2 = sum_parts(part, plane, S, row0 + col + half);
-        const float c = cs[i][0], s = cs[i][1];
-        T *dst = kc + k_offset(kv, sl, h, hkv, dh);
-        dst[i] = from_f<T>(x1 * c - x2 * s);
-        dst[i + half] = from_f<T>(x2 * c + x1 * s);
-    }
-    for (int p = threadIdx.x; p < hkv * dh; p += blockDim.x) {
-        const int h = p / dh, i = p % dh;
-        const float x = sum_parts(part, plane, S, row0 + (size_t)(hq + hkv) * dh + p);
-        vc[vt_offset(kv, sl, h, hkv, dh, i)] = from_f<T>(x);
-    }
+__global__ __launch_bounds__(256) void norm_apply_kernel(const float *__restrict__ h, const float *__restrict__ ss,
+                                                         int ss_ld, int n_tiles, int d, float eps,
+                                                         const T *__restrict__ gain, T *__restrict__ u) {
+    const int m = blockIdx.y;
+    float tot = 0.f;
+    for (int i = 0; i < n_tiles; ++i) tot += ss[(size_t)m * ss_ld + i];
+    const float rs = 1.0f / sqrtf(tot / (float)d + eps);
+    const int c = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (c + j < d) u[(size_t)m * d + c + j] = from_f<T>(h[(size_t)m * d + c + j] * rs * to_f(gain[c + j]));
 }
 
-void launch_reduce_rope_kv(const ModelDims &md, const GemmShape &g, const float *part, int rows,
-                           int rows_q, const RowMeta &rm, const double *inv_freq, void *q,
-                           const KVCache &kv, hipStream_t st) {
-    const size_t plane = (size_t)g.Mpad * g.Npad;
-    POSS_DISPATCH(md.dt, hipLaunchKernelGGL((reduce_rope_kv_kernel<T>), dim3(rows), dim3(256), 0, st, part, plane,
-                                            g.S, g.Npad, rows_q, rm.pos, rm.slot, inv_freq, md.hq, md.hkv,
-                                            md.dh, static_cast<T *>(q), kv));
-}
-
-// ------------------------------------------------------------------ h (+)= sum(part) + bias ; u = T(rmsnorm(h) g)
-template <typename T>
-__global__ __launch_bounds__(256) void reduce_res_norm_kernel(
-    const float *__restrict__ part, size_t plane, int S, int Npad, int d, float eps, int residual,
-    const T *__restrict__ bias, const T *__restrict__ gain, float *__restrict__ h, T *__restrict__ u,
-    float *__restrict__ h_copy) {
-    __shared__ float red[17];
-    const int m = blockIdx.x;
-    float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += blockDim.x) {
-        float v = sum_parts(part, plane, S, (size_t)m * Npad + i);
-        if (bias) v += to_f(bias[i]);
-        if (residual) v += h[(size_t)m * d + i];
-        h[(size_t)m * d + i] = v;
-        if (h_copy) h_copy[(size_t)m * d + i] = v;
-        ss += v * v;
-    }
-    if (!gain) return;
-    ss = block_sum(ss, red);
-    const float rs = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += blockDim.x)
-        u[(size_t)m * d + i] = from_f<T>(h[(size_t)m * d + i] * rs * to_f(gain[i]));
-}
-
-void launch_reduce_res_norm(const ModelDims &md, const GemmShape &g, const float *part, int rows,
-                            bool residual, const void *bias, const void *gain, float *h, void *u,
-                            float *h_copy, hipStream_t st) {
-    const size_t plane = (size_t)g.Mpad * g.Npad;
-    POSS_DISPATCH(md.dt, hipLaunchKernelGGL((reduce_res_norm_kernel<T>), dim3(rows), dim3(256), 0, st, part, plane,
-                                            g.S, g.Npad, md.d, md.eps, residual ? 1 : 0,
-                                            static_cast<const T *>(bias), static_cast<const T *>(gain), h,
-                                            static_cast<T *>(u), h_copy));
-}
-
-// ------------------------------------------------------------------ act = T(silu(gate) * up)
-template <typename T>
-__global__ __launch_bounds__(256) void reduce_silu_kernel(const float *__restrict__ part, size_t plane, int S,
-                                                          int Npad, int F, T *__restrict__ act) {
-    const int f = blockIdx.x * blockDim.x + threadIdx.x, m = blockIdx.y;
-    if (f >= F) return;
-    const float g = sum_parts(part, plane, S, (size_t)m * Npad + f);
-    const float up = sum_parts(part, plane, S, (size_t)m * Npad + F + f);
-    act[(size_t)m * F + f] = from_f<T>(g / (1.0f + expf(-g)) * up);
-}
-
-void launch_reduce_silu(const ModelDims &md, const GemmShape &g, const float *part, int rows, void *act,
-                        hipStream_t st) {
-    const size_t plane = (size_t)g.Mpad * g.Npad;
-    POSS_DISPATCH(md.dt, hipLaunchKernelGGL((reduce_silu_kernel<T>), dim3((md.ffn + 255) / 256, rows), dim3(256), 0,
-                                            st, part, plane, g.S, g.Npad, md.ffn, static_cast<T *>(act)));
+void launch_norm_apply(const ModelDims &md, const float *h, const float *ss, int ss_ld, int n_tiles, int rows,
+                       const void *gain, void *u, hipStream_t st) {
+    dim3 grid((md.d + 1023) / 1024, rows);
+    POSS_DISPATCH(md.dt, hipLaunchKernelGGL((norm_apply_kernel<T>), grid, dim3(256), 0, st, h, ss, ss_ld, n_tiles,
+                                            md.d, md.eps, static_cast<const T *>(gain), static_cast<T *>(u)));
 }
 
 // ------------------------------------------------------------------ argmax per row (lowest index on ties)

@@ -1,4 +1,5 @@
-// Weight-streaming GEMM for M <= 128 activation rows:  part[s][m][n] = sum_{k in split s} X[m][k] W[n][k].
+// Weight-streaming GEMM for M <= 128 activation rows:  Y[m][n] = sum_k X[m][k] W[n][k], with the
+// operation that follows it in a Llama decoder layer fused into its epilogue.
 //
 // The round is bound by reading every weight once (the verify pass reads the whole target, each
 // draft pass one specialist and the shared LM head; sections 3.3 and 6.2 of the paper discuss the
@@ -9,9 +10,12 @@
 //   * the (small, L2-resident) activation slice is staged in LDS in A-operand order, double
 //     buffered, its global loads issued one chunk ahead so they are older than the weight loads
 //     they overlap and never force the weight ring to drain;
-//   * K is split across workgroups (fixed order, summed by the consumer kernel: bitwise
-//     repeatable, no atomics).
-#include "common.h"
+//   * K is split across workgroups into partial planes; a tile-parallel epilogue kernel (one
+//     workgroup per 128 output columns) sums them in split order and applies the fused operation:
+//     rotary embedding + KV-cache write, residual add + RMSNorm partials, SiLU * up.  Bitwise
+//     repeatable.  (Doing this inside the GEMM by the last workgroup to arrive at a tile was
+//     measured 3.5x slower: agent-scope fences write back and invalidate the per-XCD L2s.)
+#include "device_utils.h"
 
 namespace poss {
 
@@ -35,6 +39,109 @@ template <> struct Mfma<f16_t> {
 
 constexpr int KCS = GEMM_KCHUNK / GEMM_KSTEP;   // k-steps per LDS chunk (8)
 constexpr int PF  = 4;                          // weight k-steps in flight per wave
+
+// ------------------------------------------------------------------------------------------
+// Epilogue of one output tile (columns [tile*128, tile*128+128)) for rows [r_begin, r_end), run by
+// 256 threads.  Split-K planes are added in split order; loads are issued four at a time.
+constexpr int EPI_ROWS = 16;       // rows per epilogue workgroup
+
+__device__ __forceinline__ float sum_planes(const float *part, size_t plane, int S, size_t idx) {
+    float a = 0.f;
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {
+        const float v0 = part[(size_t)s * plane + idx], v1 = part[(size_t)(s + 1) * plane + idx];
+        const float v2 = part[(size_t)(s + 2) * plane + idx], v3 = part[(size_t)(s + 3) * plane + idx];
+        a = (((a + v0) + v1) + v2) + v3;
+    }
+    for (; s < S; ++s) a += part[(size_t)s * plane + idx];
+    return a;
+}
+
+__device__ __forceinline__ f32x4 sum_planes4(const float *part, size_t plane, int S, size_t idx) {
+    f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {
+        const f32x4 v0 = *reinterpret_cast<const f32x4 *>(part + (size_t)s * plane + idx);
+        const f32x4 v1 = *reinterpret_cast<const f32x4 *>(part + (size_t)(s + 1) * plane + idx);
+        const f32x4 v2 = *reinterpret_cast<const f32x4 *>(part + (size_t)(s + 2) * plane + idx);
+        const f32x4 v3 = *reinterpret_cast<const f32x4 *>(part + (size_t)(s + 3) * plane + idx);
+        a = (((a + v0) + v1) + v2) + v3;
+    }
+    for (; s < S; ++s) a += *reinterpret_cast<const f32x4 *>(part + (size_t)s * plane + idx);
+    return a;
+}
+
+template <typename T, int EPI>
+__device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, size_t plane, int S, int Npad,
+                                              int N, int r_begin, int r_end, int tile, const EpiArgs &e) {
+    const int t = threadIdx.x, n0 = tile * GEMM_BLOCK_N;
+    if constexpr (EPI == EPI_ROPE_KV) {
+        // thread -> rotary pair i of one head inside the tile; pairs are (i, i + dh/2)
+        const int half = e.dh >> 1, c = t & 63;
+        const int hb = n0 + (c / half) * e.dh, i = c % half, gh = hb / e.dh;
+        if (gh >= e.hq + 2 * e.hkv) return;
+        T *kc = static_cast<T *>(e.kv.k), *vc = static_cast<T *>(e.kv.vt), *q = static_cast<T *>(e.q);
+        for (int r = r_begin + (t >> 6); r < r_end; r += 4) {
+            if (gh < e.hq && r >= e.rows_q) continue;
+            const float x1 = sum_planes(part, plane, S, (size_t)r * Npad + hb + i);
+            const float x2 = sum_planes(part, plane, S, (size_t)r * Npad + hb + i + half);
+            const float2 cs = e.cs[r * half + i];
+            if (gh < e.hq) {
+                T *dst = q + ((size_t)r * e.hq + gh) * e.dh;
+                dst[i] = from_f<T>(x1 * cs.x - x2 * cs.y);
+                dst[i + half] = from_f<T>(x2 * cs.x + x1 * cs.y);
+            } else if (gh < e.hq + e.hkv) {
+                T *dst = kc + k_offset(e.kv, e.slot[r], gh - e.hq, e.hkv, e.dh);
+                dst[i] = from_f<T>(x1 * cs.x - x2 * cs.y);
+                dst[i + half] = from_f<T>(x2 * cs.x + x1 * cs.y);
+            } else {
+                const int vh = gh - e.hq - e.hkv, sl = e.slot[r];
+                vc[vt_offset(e.kv, sl, vh, e.hkv, e.dh, i)] = from_f<T>(x1);
+                vc[vt_offset(e.kv, sl, vh, e.hkv, e.dh, i + half)] = from_f<T>(x2);
+            }
+        }
+    } else if constexpr (EPI == EPI_SILU) {
+        const int c = t & 63, f = tile * 64 + c;
+        if (f >= e.F) return;
+        T *act = static_cast<T *>(e.act);
+        for (int r = r_begin + (t >> 6); r < r_end; r += 4) {
+            const float g = sum_planes(part, plane, S, (size_t)r * Npad + n0 + c);
+            const float up = sum_planes(part, plane, S, (size_t)r * Npad + n0 + 64 + c);
+            act[(size_t)r * e.F + f] = from_f<T>(g / (1.0f + expf(-g)) * up);
+        }
+    } else {    // EPI_RESIDUAL, EPI_PLAIN: 32 threads x 4 columns per row, 8 rows per sweep
+        const int c4 = (t & 31) * 4, n = n0 + c4;
+        const T *bias = static_cast<const T *>(e.bias);
+        for (int rb = r_begin; rb < r_end; rb += 8) {
+            const int r = rb + (t >> 5);
+            float ss = 0.f;
+            if (r < r_end && n < N) {
+                const f32x4 v = sum_planes4(part, plane, S, (size_t)r * Npad + n);
+                if constexpr (EPI == EPI_PLAIN) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (n + j < N) e.out[(size_t)r * e.ld_out + n + j] = v[j];
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (n + j >= N) continue;
+                        float x = v[j];
+                        if (bias) x += to_f(bias[n + j]);
+                        if (e.residual) x += e.h[(size_t)r * N + n + j];
+                        e.h[(size_t)r * N + n + j] = x;
+                        if (e.h_copy) e.h_copy[(size_t)r * N + n + j] = x;
+                        ss += x * x;
+                    }
+                }
+            }
+            if constexpr (EPI == EPI_RESIDUAL) {
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+                if ((t & 31) == 0 && r < r_end) e.ss[(size_t)r * e.ss_ld + tile] = ss;
+            }
+        }
+    }
+}
 
 // ------------------------------------------------------------------------------------------
 template <typename T, int MT>
@@ -144,7 +251,7 @@ __global__ __launch_bounds__(GEMM_WPB * 64) void gemm_stream_kernel(
 
 // ------------------------------------------------------------------------------------------
 // float32 storage (reference-precision mode of the small test shape): plain FMA loop, weights
-// kept row-major.  One thread per output element, k ascending.
+// kept row-major, one thread per output element, k ascending.
 __global__ void gemm_f32_kernel(const float *__restrict__ W, const float *__restrict__ X, int ldx,
                                 float *__restrict__ part, int M, int N, int Npad, int K) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
@@ -156,6 +263,15 @@ __global__ void gemm_f32_kernel(const float *__restrict__ W, const float *__rest
         for (int k = 0; k < K; ++k) acc = fmaf(x[k], w[k], acc);
     }
     part[(size_t)m * Npad + n] = acc;
+}
+
+// The epilogue of every (128-column tile, 16-row block), one workgroup each: sums the split-K planes in split
+// order (bitwise repeatable) and applies the fused operation.
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void epilogue_kernel(const float *__restrict__ part, size_t plane, int S, int Npad,
+                                                       int N, int M, EpiArgs epi) {
+    const int r0 = blockIdx.y * EPI_ROWS;
+    tile_epilogue<T, EPI>(part, plane, S, Npad, N, r0, min(M, r0 + EPI_ROWS), blockIdx.x, epi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -186,8 +302,29 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
 }
 
 template <typename T>
+static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiArgs &epi, hipStream_t st) {
+    const size_t plane = (size_t)g.Mpad * g.Npad;
+    dim3 eg(g.Npad / GEMM_BLOCK_N, (g.M + EPI_ROWS - 1) / EPI_ROWS), eb(256);
+    switch (epi.mode) {
+        case EPI_ROPE_KV:
+            hipLaunchKernelGGL((epilogue_kernel<T, EPI_ROPE_KV>), eg, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+            break;
+        case EPI_RESIDUAL:
+            hipLaunchKernelGGL((epilogue_kernel<T, EPI_RESIDUAL>), eg, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+            break;
+        case EPI_SILU:
+            hipLaunchKernelGGL((epilogue_kernel<T, EPI_SILU>), eg, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+            break;
+        default:
+            if (g.S > 1 || epi.out)     // S == 1 without an output buffer: plane 0 is the result
+                hipLaunchKernelGGL((epilogue_kernel<T, EPI_PLAIN>), eg, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+            break;
+    }
+}
+
+template <typename T>
 static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                          hipStream_t st) {
+                          const EpiArgs &epi, hipStream_t st) {
     dim3 grid(g.Npad / GEMM_BLOCK_N, g.S), block(GEMM_WPB * 64);
     const int ksteps = g.Kpad / GEMM_KSTEP;
     const u32x4 *w = static_cast<const u32x4 *>(Wp);
@@ -203,23 +340,39 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
         default: POSS_GEMM_CASE(8); break;
     }
 #undef POSS_GEMM_CASE
+    launch_epilogue_t<T>(g, part, epi, st);
 }
 
 void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 hipStream_t st) {
+                 const EpiArgs &epi, hipStream_t st) {
     if (dt == DT_F32) {
         dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
         hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
                            static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
+        launch_epilogue_t<float>(g, part, epi, st);
     } else if (dt == DT_BF16) {
-        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, st);
+        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, st);
     } else {
-        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, st);
+        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, st);
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// Repack up to three row-major [rows_i, K] matrices, stacked along N, into B-operand order.
+// Repack row-major [rows_i, K] matrices, stacked along N (or gate/up interleaved in groups of 64
+// rows), into B-operand order.
+__device__ __forceinline__ bool pack_source_row(const PackSrc &src, int n, int &which, int &row) {
+    if (src.interleave64) {          // tile of 128 rows = 64 rows of matrix 0, then 64 rows of matrix 1
+        const int w = n & 127;
+        which = w >> 6; row = (n >> 7) * 64 + (w & 63);
+        return row < src.rows[which];
+    }
+    for (which = 0; which < 3; ++which) {
+        if (n < src.rows[which]) { row = n; return true; }
+        n -= src.rows[which];
+    }
+    return false;
+}
+
 __global__ void pack16_kernel(PackSrc src, int K, int Kpad, int Npad, u32x4 *__restrict__ dst) {
     const size_t unit = (size_t)blockIdx.x * blockDim.x + threadIdx.x;     // one 16-byte unit of dst
     const size_t total = (size_t)Npad * Kpad / 8;
@@ -230,43 +383,25 @@ __global__ void pack16_kernel(PackSrc src, int K, int Kpad, int Npad, u32x4 *__r
     const int nt = r % GEMM_NT; r /= GEMM_NT;
     const int ks = r % ksteps;
     const int ngroup = r / ksteps;
-    int n = (ngroup * GEMM_NT + nt) * 16 + (lane & 15);
+    const int n = (ngroup * GEMM_NT + nt) * 16 + (lane & 15);
     const int k = ks * GEMM_KSTEP + (lane >> 4) * 8;
     u32x4 v = u32x4{0u, 0u, 0u, 0u};
-    if (k < K) {
-#pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            if (n >= 0 && n < src.rows[i]) {
-                v = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(src.ptr[i]) + (size_t)n * K + k);
-                n = -1;
-            } else if (n >= 0) {
-                n -= src.rows[i];
-            }
-        }
-    }
+    int which, row;
+    if (k < K && pack_source_row(src, n, which, row))
+        v = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(src.ptr[which]) + (size_t)row * K + k);
     dst[unit] = v;
 }
 
 __global__ void pack32_kernel(PackSrc src, int K, int Npad, float *__restrict__ dst) {
     const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= (size_t)Npad * K) return;
-    int n = e / K;
-    const int k = e % K;
-    float v = 0.f;
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        if (n >= 0 && n < src.rows[i]) {
-            v = static_cast<const float *>(src.ptr[i])[(size_t)n * K + k];
-            n = -1;
-        } else if (n >= 0) {
-            n -= src.rows[i];
-        }
-    }
-    dst[e] = v;
+    const int n = e / K, k = e % K;
+    int which, row;
+    dst[e] = pack_source_row(src, n, which, row) ? static_cast<const float *>(src.ptr[which])[(size_t)row * K + k] : 0.f;
 }
 
 void launch_pack(int dt, const PackSrc &src, int K, void *dst, hipStream_t st) {
-    const int N = src.rows[0] + src.rows[1] + src.rows[2];
+    const int N = src.interleave64 ? gate_up_rows(src.rows[0]) : src.rows[0] + src.rows[1] + src.rows[2];
     const int Npad = gemm_npad(N), Kpad = gemm_kpad(dt, K);
     if (dt == DT_F32) {
         const size_t total = (size_t)Npad * K;
