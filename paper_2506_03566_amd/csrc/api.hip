@@ -193,7 +193,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     void *q = a.take((size_t)R * qd * es), *ao = a.take((size_t)R * qd * es), *act = a.take((size_t)R * F * es);
     const int G = c.n_q_heads / c.n_kv_heads;
     const int rho_pad = round_up(R * G, 16);
-    const int max_splits = attention_splits(slots, 128);
+    const int max_splits = attention_splits(slots, 64);
     float *ao_part = a.take_n<float>((size_t)max_splits * c.n_kv_heads * rho_pad * c.head_dim);
     float *ml_part = a.take_n<float>((size_t)max_splits * c.n_kv_heads * rho_pad * 2);
     int32_t *row_pos = a.take_n<int32_t>(R), *row_slot = a.take_n<int32_t>(R), *tree_slot = a.take_n<int32_t>(R);
@@ -433,7 +433,7 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     c->st = static_cast<hipStream_t>(hip_stream);
     c->err[0] = 0;
     c->taps_user = nullptr;
-    c->gemm_target_wgs = 0; c->attn_keys_per_split = 256;
+    c->gemm_target_wgs = 0; c->attn_keys_per_split = 64;
     c->prof_on = 0; c->prof_n = 0; c->prof_bytes = 0; c->prof_launches = 0; c->prof_ms = 0;
     c->spec_len.assign(cfg->n_specialists, 0);
     c->spec_tmp_depth.assign(cfg->n_specialists, 0);
@@ -771,7 +771,7 @@ int poss_gemm_profile(poss_ctx *c, int64_t *launches, double *ms, double *weight
 int poss_set_tuning(poss_ctx *c, int32_t gemm_target_workgroups, int32_t attn_keys_per_split) {
     if (!c) return POSS_E_INVALID_ARG;
     if (gemm_target_workgroups < 0 || gemm_target_workgroups > 4096) return fail(c, POSS_E_INVALID_ARG, "poss_set_tuning: workgroup target out of range");
-    if (attn_keys_per_split && (attn_keys_per_split < 128 || attn_keys_per_split % 32)) return fail(c, POSS_E_INVALID_ARG, "poss_set_tuning: keys per split must be a multiple of 32, >= 128");
+    if (attn_keys_per_split && (attn_keys_per_split < 64 || attn_keys_per_split % 32)) return fail(c, POSS_E_INVALID_ARG, "poss_set_tuning: keys per split must be a multiple of 32, >= 64");
     c->gemm_target_wgs = gemm_target_workgroups;
     if (attn_keys_per_split) c->attn_keys_per_split = attn_keys_per_split;
     return POSS_OK;

@@ -75,21 +75,37 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(
     for (int dt = 0; dt < DT; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
 
-    for (int b = b0; b < b1; ++b) {
+    // Key and value fragments of one 32-slot block: K rows slot0 + tt*16 + lr (A operand of S^T),
+    // V^T rows dt*16 + lr at keys {slot0 + 4lg..+3} and {slot0 + 16 + 4lg..+3} (A operand of O^T).
+    // Both are requested together, one block ahead of the arithmetic.
+    u32x4 kf[2][2][KS];
+    u32x2 vf[2][DT][2];
+    auto load_block = [&](int b, int buf) {
         const int slot0 = b << 5;
         const int pg = kv.page_table[slot0 >> kv.page_shift], off = slot0 & (P - 1);
         const size_t head_base = (size_t)(pg * hkv + kvh);
-        // S^T tiles: rows = keys slot0 + tt*16 + (0..15), columns = query rows
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            const T *krow = kc + (head_base * P + off + tt * 16 + lr) * DH + lg * 8;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kf[buf][tt][ks] = *reinterpret_cast<const u32x4 *>(krow + ks * 32);
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const T *vrow = vc + (head_base * DH + dt * 16 + lr) * P + off + 4 * lg;
+            vf[buf][dt][0] = *reinterpret_cast<const u32x2 *>(vrow);
+            vf[buf][dt][1] = *reinterpret_cast<const u32x2 *>(vrow + 16);
+        }
+    };
+    auto compute_block = [&](int b, int buf) {
+        const int slot0 = b << 5;
         f32x4 s[2];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
             s[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const T *krow = kc + (head_base * P + off + tt * 16 + lr) * DH + lg * 8;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const V8 kf = __builtin_bit_cast(V8, *reinterpret_cast<const u32x4 *>(krow + ks * 32));
-                s[tt] = Vec8<T>::mfma(kf, qf[ks], s[tt]);
-            }
+            for (int ks = 0; ks < KS; ++ks)
+                s[tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf[buf][tt][ks]), qf[ks], s[tt]);
         }
         // lane holds keys slot0 + tt*16 + 4*lg + r of query row lr
         float sv[8], bm = -INFINITY;
@@ -125,12 +141,17 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             acc[dt] *= alpha;
-            // V^T rows dt*16 + lr, keys {slot0 + 4lg .. +3} and {slot0 + 16 + 4lg .. +3}
-            const T *vrow = vc + (head_base * DH + dt * 16 + lr) * P + off + 4 * lg;
-            const u32x2 lo = *reinterpret_cast<const u32x2 *>(vrow);
-            const u32x2 hi = *reinterpret_cast<const u32x2 *>(vrow + 16);
-            const V8 vf = __builtin_bit_cast(V8, (u32x4{lo.x, lo.y, hi.x, hi.y}));
-            acc[dt] = Vec8<T>::mfma(vf, pf, acc[dt]);
+            const u32x2 lo = vf[buf][dt][0], hi = vf[buf][dt][1];
+            acc[dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, (u32x4{lo.x, lo.y, hi.x, hi.y})), pf, acc[dt]);
+        }
+    };
+    if (b0 < b1) load_block(b0, 0);
+    for (int b = b0; b < b1; b += 2) {               // two blocks per trip so the buffer index is static
+        if (b + 1 < b1) load_block(b + 1, 1);
+        compute_block(b, 0);
+        if (b + 1 < b1) {
+            if (b + 2 < b1) load_block(b + 2, 0);
+            compute_block(b + 1, 1);
         }
     }
     l_run += __shfl_xor(l_run, 16, 64);

@@ -21,8 +21,14 @@ static inline size_t dtype_size(int dt) { return dt == DT_F32 ? 4 : 2; }
 //   Wp[n_group][k_step][nt][lane][8],  n = (n_group*GEMM_NT + nt)*16 + lane%16,
 //                                       k = k_step*32 + (lane/16)*8 + j
 // so that one wave reads GEMM_NT KiB per k-step, contiguous and in k order.
-constexpr int GEMM_NT      = 2;                       // 16-column tiles per wave
-constexpr int GEMM_WPB     = 4;                       // waves per workgroup
+#ifndef POSS_GEMM_NT
+#define POSS_GEMM_NT 2
+#endif
+#ifndef POSS_GEMM_WPB
+#define POSS_GEMM_WPB 4
+#endif
+constexpr int GEMM_NT      = POSS_GEMM_NT;            // 16-column tiles per wave
+constexpr int GEMM_WPB     = POSS_GEMM_WPB;           // waves per workgroup
 constexpr int GEMM_BLOCK_N = GEMM_NT * 16 * GEMM_WPB; // 128 columns per workgroup
 constexpr int GEMM_KSTEP   = 32;
 constexpr int GEMM_KCHUNK  = 256;                     // K is padded to this at pack time

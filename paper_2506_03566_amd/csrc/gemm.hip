@@ -17,6 +17,8 @@
 //     measured 3.5x slower: agent-scope fences write back and invalidate the per-XCD L2s.)
 #include "device_utils.h"
 
+#include <type_traits>
+
 namespace poss {
 
 typedef float  f32x4 __attribute__((ext_vector_type(4)));
@@ -38,20 +40,29 @@ template <> struct Mfma<f16_t> {
 };
 
 constexpr int KCS = GEMM_KCHUNK / GEMM_KSTEP;   // k-steps per LDS chunk (8)
-constexpr int PF  = 4;                          // weight k-steps in flight per wave
+#ifndef POSS_GEMM_PF
+#define POSS_GEMM_PF 4
+#endif
+constexpr int PF  = POSS_GEMM_PF;               // weight k-steps in flight per wave
 
 // ------------------------------------------------------------------------------------------
 // Epilogue of one output tile (columns [tile*128, tile*128+128)) for rows [r_begin, r_end), run by
-// 256 threads.  Split-K planes are added in split order; loads are issued four at a time.
+// 256 threads.  Split-K planes are added in split order; loads are issued eight at a time.
 constexpr int EPI_ROWS = 16;       // rows per epilogue workgroup
 
 __device__ __forceinline__ float sum_planes(const float *part, size_t plane, int S, size_t idx) {
     float a = 0.f;
     int s = 0;
-    for (; s + 4 <= S; s += 4) {
+    for (; s + 8 <= S; s += 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = part[(size_t)(s + j) * plane + idx];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a += v[j];
+    }
+    for (; s + 2 <= S; s += 2) {
         const float v0 = part[(size_t)s * plane + idx], v1 = part[(size_t)(s + 1) * plane + idx];
-        const float v2 = part[(size_t)(s + 2) * plane + idx], v3 = part[(size_t)(s + 3) * plane + idx];
-        a = (((a + v0) + v1) + v2) + v3;
+        a = (a + v0) + v1;
     }
     for (; s < S; ++s) a += part[(size_t)s * plane + idx];
     return a;
@@ -60,12 +71,17 @@ __device__ __forceinline__ float sum_planes(const float *part, size_t plane, int
 __device__ __forceinline__ f32x4 sum_planes4(const float *part, size_t plane, int S, size_t idx) {
     f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
     int s = 0;
-    for (; s + 4 <= S; s += 4) {
+    for (; s + 8 <= S; s += 8) {
+        f32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const f32x4 *>(part + (size_t)(s + j) * plane + idx);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a += v[j];
+    }
+    for (; s + 2 <= S; s += 2) {
         const f32x4 v0 = *reinterpret_cast<const f32x4 *>(part + (size_t)s * plane + idx);
         const f32x4 v1 = *reinterpret_cast<const f32x4 *>(part + (size_t)(s + 1) * plane + idx);
-        const f32x4 v2 = *reinterpret_cast<const f32x4 *>(part + (size_t)(s + 2) * plane + idx);
-        const f32x4 v3 = *reinterpret_cast<const f32x4 *>(part + (size_t)(s + 3) * plane + idx);
-        a = (((a + v0) + v1) + v2) + v3;
+        a = (a + v0) + v1;
     }
     for (; s < S; ++s) a += *reinterpret_cast<const f32x4 *>(part + (size_t)s * plane + idx);
     return a;
@@ -157,27 +173,38 @@ __global__ __launch_bounds__(GEMM_WPB * 64) void gemm_stream_kernel(
     const int chunk0 = blockIdx.y * chunks_per_split;
     const int n_chunks_total = ksteps_total / KCS;
     const int chunk1 = min(n_chunks_total, chunk0 + chunks_per_split);
-    const int ks_end = chunk1 * KCS;
     const int ngroup = blockIdx.x * GEMM_WPB + wave;
     const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCS) * (GEMM_NT * 64) + lane;
 
     // Global->LDS staging map: unit u of a chunk covers row m = u / 32, 8 consecutive k starting at
     // (u % 32) * 8 (coalesced along k); it lands at A-operand position [k_step][m_tile][lane].
-    int x_m[XPT], x_k8[XPT], x_dst[XPT];
+    // Loads are never predicated (a predicated load becomes a branch, and the compiler then waits
+    // for every outstanding load at it): out-of-range units read a clamped, valid address and are
+    // zeroed by a select.
+    const T *x_src[XPT];
+    int x_k[XPT], x_dst[XPT];
+    bool x_row_ok[XPT];
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
         const int u = tid + i * (GEMM_WPB * 64);
         const int m = u >> 5, k8 = u & 31;
-        x_m[i] = m; x_k8[i] = k8;
+        x_row_ok[i] = m < M;
+        x_src[i] = X + (size_t)(m < M ? m : M - 1) * ldx;
+        x_k[i] = k8 * 8;
         x_dst[i] = ((k8 >> 2) * MT + (m >> 4)) * 64 + ((k8 & 3) << 4) + (m & 15);
     }
     auto load_x = [&](int chunk, u32x4 (&xr)[XPT]) {
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const int k = chunk * GEMM_KCHUNK + x_k8[i] * 8;
-            xr[i] = (x_m[i] < M && k < K)
-                        ? *reinterpret_cast<const u32x4 *>(X + (size_t)x_m[i] * ldx + k)
-                        : u32x4{0u, 0u, 0u, 0u};
+            const int k = chunk * GEMM_KCHUNK + x_k[i];
+            xr[i] = *reinterpret_cast<const u32x4 *>(x_src[i] + (k < K ? k : K - 8));
+        }
+    };
+    auto store_x = [&](int chunk, int b, const u32x4 (&xr)[XPT]) {   // the select happens here, not at the load
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            const bool ok = x_row_ok[i] && chunk * GEMM_KCHUNK + x_k[i] < K;
+            xs[b][x_dst[i]] = ok ? xr[i] : u32x4{0u, 0u, 0u, 0u};
         }
     };
 
@@ -190,24 +217,23 @@ __global__ __launch_bounds__(GEMM_WPB * 64) void gemm_stream_kernel(
     u32x4 xr[XPT];
     load_x(chunk0, xr);
     u32x4 wr[PF][GEMM_NT];
-    int ks_issue = chunk0 * KCS;                     // next k-step whose weights get requested
 #pragma unroll
-    for (int p = 0; p < PF; ++p) {
-        if (ks_issue < ks_end) {
+    for (int p = 0; p < PF; ++p) {                   // a workgroup owns at least one chunk (KCS >= PF steps)
 #pragma unroll
-            for (int nt = 0; nt < GEMM_NT; ++nt) wr[p][nt] = __builtin_nontemporal_load(wp + nt * 64);
-            wp += GEMM_NT * 64;
-        }
-        ++ks_issue;
+        for (int nt = 0; nt < GEMM_NT; ++nt) wr[p][nt] = __builtin_nontemporal_load(wp + nt * 64);
+        wp += GEMM_NT * 64;
     }
-#pragma unroll
-    for (int i = 0; i < XPT; ++i) xs[0][x_dst[i]] = xr[i];
+    store_x(chunk0, 0, xr);
     __syncthreads();
 
+    // One chunk of KCS k-steps.  MORE (another chunk follows) is a compile-time flag so that the
+    // body is straight-line code: the weight ring is refilled PF steps ahead, across the chunk
+    // boundary when MORE, and the next chunk's activations are requested before any of it.
     int buf = 0;
-    for (int chunk = chunk0; chunk < chunk1; ++chunk) {
-        const bool more = chunk + 1 < chunk1;
-        if (more) load_x(chunk + 1, xr);             // older than every weight load issued below
+    auto chunk_body = [&](auto more_tag, int chunk) {
+        constexpr bool MORE = decltype(more_tag)::value;
+        if constexpr (MORE) load_x(chunk + 1, xr);
+        __builtin_amdgcn_sched_barrier(0);           // keep these loads older than the weight loads below
 #pragma unroll
         for (int i = 0; i < KCS; ++i) {
             u32x4 a[MT];
@@ -216,24 +242,25 @@ __global__ __launch_bounds__(GEMM_WPB * 64) void gemm_stream_kernel(
             u32x4 w[GEMM_NT];
 #pragma unroll
             for (int nt = 0; nt < GEMM_NT; ++nt) w[nt] = wr[i % PF][nt];
-            if (ks_issue < ks_end) {
+            if (MORE || i + PF < KCS) {
 #pragma unroll
                 for (int nt = 0; nt < GEMM_NT; ++nt) wr[i % PF][nt] = __builtin_nontemporal_load(wp + nt * 64);
                 wp += GEMM_NT * 64;
             }
-            ++ks_issue;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[mt], w[nt], acc[mt][nt]);
+            __builtin_amdgcn_sched_barrier(0);       // one k-step at a time: loads stay in ring order
         }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < XPT; ++i) xs[buf ^ 1][x_dst[i]] = xr[i];
+        if constexpr (MORE) {
+            store_x(chunk + 1, buf ^ 1, xr);
+            __syncthreads();
+            buf ^= 1;
         }
-        __syncthreads();
-        buf ^= 1;
-    }
+    };
+    for (int chunk = chunk0; chunk + 1 < chunk1; ++chunk) chunk_body(std::true_type{}, chunk);
+    chunk_body(std::false_type{}, chunk1 - 1);
 
     // D tile: lane -> column n = lane % 16, register r -> row m = 4 * (lane / 16) + r
     float *out = part + (size_t)blockIdx.y * (MT * 16) * Npad;
@@ -291,7 +318,7 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
     g.Mpad = gemm_rows_written(g.Mpad);       // the kernel is instantiated for 1, 2, 4, 6 or 8 row tiles
     const int n_blocks = g.Npad / GEMM_BLOCK_N;
     const int n_chunks = g.Kpad / GEMM_KCHUNK;
-    if (target_wgs <= 0) target_wgs = 512;
+    if (target_wgs <= 0) target_wgs = 256;     // one workgroup per CU: more splits only add partial-plane traffic
     int S = (target_wgs + n_blocks - 1) / n_blocks;
     int max_s = n_chunks / 2; if (max_s < 1) max_s = 1;          // at least 512 of K per split
     if (S > max_s) S = max_s;
