@@ -123,3 +123,17 @@ def specialist_pass(W, cfg, s, tokens, feats, pos, allowed, q_rows, act=None):
     z = np.zeros((0, cfg.n_kv_heads, cfg.head_dim))
     out, _, _ = decoder_layer(W, p, cfg, h0, np.asarray(pos), z, z, allowed, act, q_rows=q_rows)
     return out
+
+
+def specialist_kv(W, cfg, s, tokens, feats, pos, act=None):
+    """Keys (rotated) and values specialist s holds for a sequence of [x ; f] pairs: what its own,
+    unshared cache must contain (section 3.3).  Returns (k, v) of shape [n, Hkv, dh]."""
+    Q = lambda x: round_storage(x, act)
+    p = f"spec{s}."
+    n = len(tokens)
+    x = np.concatenate([W("embed")[np.asarray(tokens, dtype=np.int64)], Q(np.asarray(feats))], axis=1)
+    h0 = x @ W(p + "fc_w").T + W(p + "fc_b")
+    u = Q(rmsnorm(h0, W(p + "attn_norm"), cfg.rms_eps))
+    k = Q(rope((u @ W(p + "wk").T).reshape(n, cfg.n_kv_heads, cfg.head_dim), np.asarray(pos), cfg.rope_theta))
+    v = Q((u @ W(p + "wv").T).reshape(n, cfg.n_kv_heads, cfg.head_dim))
+    return k, v

@@ -117,6 +117,52 @@ class PossOracle:
         self.last["builder"], self.last["topk"] = tb, dbg_logp
         return tree
 
+    def score_tree(self, tree):
+        """Cumulative drafter log-probability (float64) of every node of a tree built elsewhere:
+        node v at depth d scores score(parent) + log P_d(token_v | path), P_d from the specialist
+        serving draft position d-1.  Used to judge a tree that differs from draft_tree()'s only
+        through near-ties.  Also returns, per expanded node, its full log-probability row."""
+        cfg, W, t = self.cfg, self.W, self.t
+        n, S = cfg.positions_per_specialist, cfg.n_specialists
+        seq_tok = list(self.tokens[1:t + 1])
+        seq_feat = [self.feats[j - 1] for j in range(1, t + 1)]
+        seq_pos = list(range(t))
+        children = {}
+        for i in range(1, tree.n):
+            children.setdefault(tree.parent[i], []).append(i)
+        depth = tree.depth
+        score = [0.0] * tree.n
+        row_of, fhat, logp_rows = {}, {}, {}
+        for d in range(1, max(depth) + 1):
+            s = specialist_index(d - 1, n, S)
+            expand = [v for v in range(tree.n) if depth[v] == d - 1 and v in children]
+            if d == 1:
+                q_rows, allowed = [t - 1], np.ones((1, t), dtype=bool)
+            else:
+                for v in expand:
+                    row_of[v] = len(seq_tok)
+                    seq_tok.append(tree.token[v])
+                    seq_feat.append(fhat[tree.parent[v]])
+                    seq_pos.append(t - 1 + depth[v])
+                q_rows = [row_of[v] for v in expand]
+                allowed = np.zeros((len(expand), len(seq_tok)), dtype=bool)
+                allowed[:, :t] = True
+                for r, v in enumerate(expand):
+                    u = v
+                    while u != 0:
+                        allowed[r, row_of[u]] = True
+                        u = tree.parent[u]
+            if not expand:
+                continue
+            out = specialist_pass(W, cfg, s, seq_tok, np.stack(seq_feat), seq_pos, allowed, q_rows, self.act)
+            lp = log_softmax(head(W, cfg, out, self.act))
+            for r, v in enumerate(expand):
+                fhat[v] = out[r]
+                logp_rows[v] = lp[r]
+                for c in children[v]:
+                    score[c] = score[v] + lp[r, tree.token[c]]
+        return np.array(score), logp_rows
+
     # ------------------------------------------------------------------ verify
     def verify_tree(self, tree):
         """One target pass over all tree rows (section 2.1, second phase).

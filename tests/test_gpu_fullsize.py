@@ -1,0 +1,100 @@
+"""Llama-3-8B shape (the benchmark workload, launch configuration of bench.py): the oracle cannot
+run the whole model in test time, so single outputs are sampled: one target layer and the Head
+recomputed by the oracle from the library's own inputs, plus properties that hold at any size
+(speculative stream == the library's vanilla greedy stream up to near-ties, tree validity)."""
+import numpy as np
+import pytest
+
+from gpu_util import have_gpu
+
+pytestmark = pytest.mark.gpu
+
+if have_gpu():
+    import torch
+    import paper_2506_03566_amd as P
+    from synth import get_config, make_prompt
+    from synth.gpu import make_weights_on_device
+    from oracle.model import Weights, decoder_layer, head
+    from oracle.tree import ancestor_masks, validate_tree, Tree, accept_bruteforce
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def test_llama3_8b_shape_sampled_parity_and_losslessness():
+    cfg = get_config("c1_llama3_8b_3x2", n_prompt=200)
+    layer = 17
+    keep = [f"layer{layer}.", "lm_head", "final_norm"]
+    _say("generating 8B-shape weights")
+    dev, host = make_weights_on_device(cfg, keep_host=keep)
+    ctx = P.Poss(cfg, dev)
+    del dev
+    torch.cuda.empty_cache()
+    W = Weights(cfg, host, cache=False)
+    prompt = make_prompt(cfg)
+    t = len(prompt)
+    first = ctx.prefill(prompt)
+    # ---- vanilla greedy stream from root-only rounds, with the top-2 gap of every step
+    logits1 = torch.zeros(1, cfg.vocab, device="cuda")
+    ar, gaps = [first], []
+    for _ in range(10):
+        ctx.verify_tree(P.TreeArrays.from_lists([0], [-1]), logits_out=logits1)
+        top2 = torch.topk(logits1[0], 2).values
+        gaps.append(float(top2[0] - top2[1]))
+        _, _, toks = ctx.accept_and_commit()
+        ar.append(toks[0])
+    # ---- speculative rounds from the same prompt
+    ctx.reset()
+    assert ctx.prefill(prompt) == first
+    taps = torch.zeros(cfg.n_layers + 1, cfg.total_tokens + 1, cfg.d_model, device="cuda")
+    logits = torch.zeros(cfg.total_tokens + 1, cfg.vocab, device="cuda")
+    feats = torch.zeros(cfg.total_tokens + 1, cfg.d_model, device="cuda")
+    ctx.debug_set_taps(taps)
+    tr = ctx.draft_tree()
+    d = tr.as_dict()
+    assert d["n"] == cfg.total_tokens + 1 and validate_tree(d["token"], d["parent"])
+    assert d["mask"] == ancestor_masks(d["parent"]) and d["pos"] == [t + x for x in d["depth"]]
+    assert all(d["score"][i] <= d["score"][d["parent"][i]] for i in range(1, d["n"]))
+    g = ctx.verify_tree(None, logits_out=logits, feat_out=feats)[:d["n"]]
+    ctx.debug_set_taps(None)
+    # ---- sampled layer: oracle layer `layer` on the library's input rows and cached keys/values
+    _say("oracle: one decoder layer on 61 rows")
+    h_in = taps[layer].cpu().numpy().astype(np.float64)
+    h_out = taps[layer + 1].cpu().numpy().astype(np.float64)
+    kc, vc = ctx.debug_read_kv(-1, layer, 0, t)
+    tree = Tree(d["token"], d["parent"]).finish(t)
+    o_out, k_new, v_new = decoder_layer(W, f"layer{layer}.", cfg, h_in, np.array(tree.pos), kc.astype(np.float64),
+                                        vc.astype(np.float64), tree.allowed(t), act=cfg.dtype)
+    rms = np.sqrt((h_out ** 2).mean())
+    err = np.abs(o_out - h_out).max()
+    _say(f"  layer {layer}: max|dh| = {err:.3e}, rms(h) = {rms:.2f}")
+    assert err <= 2e-2 * max(1.0, rms)
+    gk, gv = ctx.debug_read_kv(-1, layer, t, d["n"])
+    assert np.abs(gk - k_new).max() <= 2e-2 and np.abs(gv - v_new).max() <= 2e-2
+    # ---- sampled Head rows: the library's features through the oracle's Head
+    rows = [0, 1, 17, d["n"] - 1]
+    ol = head(W, cfg, feats[rows].cpu().numpy().astype(np.float64), act=cfg.dtype)
+    herr = np.abs(ol - logits[rows].cpu().numpy()).max()
+    _say(f"  Head on rows {rows}: max|dlogit| = {herr:.3e}")
+    assert herr <= 2e-2
+    for j, r in enumerate(rows):
+        top2 = np.partition(ol[j], -2)[-2:]
+        if top2[1] - top2[0] > 4e-2:
+            assert g[r] == int(np.argmax(ol[j]))
+    # ---- acceptance and losslessness: the committed stream equals the vanilla stream
+    path, m, toks = ctx.accept_and_commit()
+    assert accept_bruteforce(d["token"], d["parent"], g.tolist())[0] == path
+    spec = [first] + toks
+    while len(spec) < len(ar):
+        ctx.draft_tree(want_tree=False)
+        ctx.verify_tree(want_argmax=False)
+        _, _, toks = ctx.accept_and_commit()
+        spec += toks
+    for j in range(len(ar)):
+        if spec[j] != ar[j]:
+            assert j >= 1 and gaps[j - 1] <= 4e-2, f"streams differ at {j} with a clear margin {gaps[j - 1]}"
+            break
+    st = ctx.stats()
+    assert st.rounds >= 1 and st.committed_tokens == len(spec) - 1
+    ctx.close()

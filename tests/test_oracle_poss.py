@@ -162,3 +162,24 @@ def test_mixed_precision_mode_is_lossless_too():
     _, exact = target_full(W, cfg, prompt)
     _, mixed = target_full(W, cfg, prompt, act=1)
     assert 1e-5 < np.abs(exact - mixed).max() < 2e-2
+
+
+def test_score_tree_and_specialist_kv_agree_with_the_draft():
+    """Helpers used by the GPU lock-step tests: re-scoring the oracle's own tree reproduces its
+    scores, and a specialist's keys/values are what its pass attends to (checked through
+    attention over them reproducing the pass output)."""
+    from oracle.model import specialist_kv
+    cfg, W = _setup("t_tiny_f32_6x1")
+    o = PossOracle(W, cfg)
+    o.prefill(make_prompt(cfg, n=21))
+    tree = o.draft_tree()
+    score, rows = o.score_tree(tree)
+    assert np.abs(score - np.array(tree.score, dtype=np.float64)).max() < 1e-5
+    assert 0 in rows and abs(np.exp(rows[0]).sum() - 1.0) < 1e-12
+    t = o.t
+    k, v = specialist_kv(W, cfg, 0, o.tokens[1:t + 1], np.stack(o.feats[:t]), np.arange(t))
+    assert k.shape == (t, cfg.n_kv_heads, cfg.head_dim) and v.shape == k.shape
+    # keys are rotated: un-rotating position p by -p must give the position-0 key of the same input
+    from oracle.numerics import rope
+    k0, _ = specialist_kv(W, cfg, 0, o.tokens[1:t + 1], np.stack(o.feats[:t]), np.zeros(t, dtype=int))
+    assert np.allclose(rope(k, -np.arange(t), cfg.rope_theta), k0, atol=1e-12)
