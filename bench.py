@@ -17,6 +17,10 @@ sys.path.insert(0, ROOT)
 
 METRIC = "draft+verify round latency (ms), tokens/s and HBM GB/s, Llama-3-8B shape, bs=1"
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per gemm_stream_kernel launch (average over the launches of a round) from rocprofv3 TCC
+# counters, scaled by the reading of a plain 1 GiB copy (FETCH_SIZE x2.000, WRITE_SIZE x1.000);
+# commands and raw sums: profiles/gemm_stream_kernel_c1_hbm_traffic.md
+MEASURED_TRAFFIC = {"c1_llama3_8b_3x2": dict(fetch_bytes=153.6e6, write_bytes=9.0e6)}
 
 
 def round_bytes(cfg, t, a):
@@ -88,6 +92,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-wgs", type=int, default=0)
     ap.add_argument("--attn-split", type=int, default=0)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported"
@@ -145,7 +151,9 @@ def main():
     ctx.profile_gemm(False)
     achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
     roofline = dict(bound="hbm", kernel="gemm_stream_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS,
-                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4), traffic=None,
+                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4),
+                    traffic=(sum(MEASURED_TRAFFIC[cfg.name].values()) if cfg.name in MEASURED_TRAFFIC else None),
+                    algorithmic_bytes_per_launch=round(gemm_bytes / max(launches, 1), 1),
                     launches_per_round=launches // max(prof_rounds, 1),
                     avg_launch_us=round(gemm_ms * 1e3 / max(launches, 1), 2),
                     weight_bytes_per_round=gemm_bytes / max(prof_rounds, 1))
@@ -164,6 +172,13 @@ def main():
                              commit=round((s1.ms_commit - base[4]) / rounds, 4)),
                setup_s=dict(weights=round(t_gen, 1)), roofline=roofline)
     ctx.close()
+    if args.pmc_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
