@@ -433,7 +433,7 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     c->st = static_cast<hipStream_t>(hip_stream);
     c->err[0] = 0;
     c->taps_user = nullptr;
-    c->gemm_target_wgs = 0; c->attn_keys_per_split = 64;
+    c->gemm_target_wgs = 0; c->attn_keys_per_split = 0;
     c->prof_on = 0; c->prof_n = 0; c->prof_bytes = 0; c->prof_launches = 0; c->prof_ms = 0;
     c->spec_len.assign(cfg->n_specialists, 0);
     c->spec_tmp_depth.assign(cfg->n_specialists, 0);

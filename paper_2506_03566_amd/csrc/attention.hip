@@ -4,7 +4,8 @@
 // that follow them (the rows of this round: tree nodes in verification, drafted ancestors in a
 // specialist pass, the chunk itself in prefill), those whose bit is set in the row's mask.
 //
-// 16-bit types: one wave per (16 query rows, KV head, key split), on v_mfma_f32_16x16x32.
+// 16-bit types: one wave per 16 query rows, four waves (one KV head) per workgroup sharing the
+// key/value blocks through LDS, on v_mfma_f32_16x16x32.
 // Query rows of the G = Hq/Hkv heads that share a KV head are stacked (rho = m*G + g) so a wave's
 // 16 rows reuse every key it loads.  Scores are formed transposed, S^T = K Q^T (keys as MFMA rows):
 // a lane then holds 8 scores of ONE query row per 32-key block, which is already the B-operand
@@ -41,25 +42,38 @@ __device__ __forceinline__ bool slot_visible(int slot, int n_prefix, int region_
     return ((j < 64 ? m0 >> j : m1 >> (j - 64)) & 1ull) != 0;
 }
 
+// One workgroup = 4 waves = 4 tiles of 16 query rows of ONE KV head, over the key blocks of one
+// split.  Key / value blocks (32 slots) go global -> registers -> LDS one block ahead of the
+// arithmetic and are shared by the four waves.  LDS layouts: K rows padded to DH+8 elements (row
+// stride 272 B: conflict-free 16-byte operand reads); V^T rows hold their 32 keys permuted so that
+// the 8 keys a lane contracts (4 of each 16-key half) are one 16-byte chunk.
+// With a single split the result is normalised and written in the storage type directly;
+// otherwise (max, sum, O) partials go to the merge kernel.
 template <typename T, int DH>
-__global__ __launch_bounds__(64) void attn_mfma_kernel(
+__global__ __launch_bounds__(256) void attn_mfma_kernel(
     const T *__restrict__ q, int rows, int hq, int hkv, const uint64_t *__restrict__ mask, int n_prefix,
     int region_len, KVCache kv, int blocks_per_split, float scale, float *__restrict__ o_part,
-    float *__restrict__ ml_part, int rho_pad) {
+    float *__restrict__ ml_part, int rho_pad, T *__restrict__ out_direct) {
     typedef typename Vec8<T>::type V8;
     constexpr int KS = DH / 32, DT = DH / 16;
-    const int lane = threadIdx.x, lr = lane & 15, lg = lane >> 4;
+    constexpr int KROW = DH + 8;                          // padded K row, elements
+    constexpr int K_UNITS = 32 * DH / 8;                  // 16-byte units of one K block
+    constexpr int KPT = K_UNITS / 256, VPT = K_UNITS / 256;
+    __shared__ __attribute__((aligned(16))) T ks_lds[2][32 * KROW];
+    __shared__ __attribute__((aligned(16))) T vs_lds[2][DH * 32];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
     const int G = hq / hkv, kvh = blockIdx.y, split = blockIdx.z;
-    const int rho = blockIdx.x * 16 + lr;
+    const int tile = blockIdx.x * 4 + wave;
+    const int rho = tile * 16 + lr;
     const bool valid = rho < rows * G;
     const int m = valid ? rho / G : 0, qh = kvh * G + (valid ? rho % G : 0);
 
     V8 qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        u32x4 v = u32x4{0u, 0u, 0u, 0u};
-        if (valid) v = *reinterpret_cast<const u32x4 *>(q + ((size_t)m * hq + qh) * DH + ks * 32 + lg * 8);
-        qf[ks] = __builtin_bit_cast(V8, v);
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(q + ((size_t)m * hq + qh) * DH + ks * 32 + lg * 8);
+        qf[ks] = __builtin_bit_cast(V8, valid ? v : u32x4{0u, 0u, 0u, 0u});
     }
     const uint64_t m0 = valid ? mask[(size_t)m * MASK_WORDS] : 0ull;
     const uint64_t m1 = valid ? mask[(size_t)m * MASK_WORDS + 1] : 0ull;
@@ -70,54 +84,78 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(
     const int P = 1 << kv.page_shift;
     const T *kc = static_cast<const T *>(kv.k), *vc = static_cast<const T *>(kv.vt);
 
+    // staging: K block = 32 consecutive token rows = 32*DH contiguous elements; V^T block = DH rows
+    // of 32 keys (64 bytes each, row stride P elements)
+    u32x4 kr[KPT], vr[VPT];
+    auto load_block = [&](int b) {
+        const int slot0 = b << 5;
+        const int pg = kv.page_table[slot0 >> kv.page_shift], off = slot0 & (P - 1);
+        const size_t head_base = (size_t)(pg * hkv + kvh);
+        const T *kb = kc + (head_base * P + off) * DH;
+        const T *vb = vc + head_base * DH * P + off;
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) kr[i] = *reinterpret_cast<const u32x4 *>(kb + (size_t)(tid + i * 256) * 8);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int u = tid + i * 256;                  // unit: dh row u / 4, keys (u % 4) * 8 .. +8
+            vr[i] = *reinterpret_cast<const u32x4 *>(vb + (size_t)(u >> 2) * P + (u & 3) * 8);
+        }
+    };
+    auto store_block = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const int u = tid + i * 256, row = u / (DH / 8), c8 = u % (DH / 8);
+            *reinterpret_cast<u32x4 *>(&ks_lds[buf][row * KROW + c8 * 8]) = kr[i];
+        }
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            // keys k0 = (u%4)*8 .. k0+7: key k sits at element (k%16)/4*8 + (k/16)*4 + k%4 of its row
+            const int u = tid + i * 256, row = u >> 2, k0 = (u & 3) * 8;
+            const int half = k0 >> 4, g0 = (k0 & 15) >> 2;                 // k0..k0+3 -> group g0, k0+4..k0+7 -> g0+1
+            T *dst = &vs_lds[buf][row * 32];
+            *reinterpret_cast<u32x2 *>(dst + g0 * 8 + half * 4) = u32x2{vr[i].x, vr[i].y};
+            *reinterpret_cast<u32x2 *>(dst + (g0 + 1) * 8 + half * 4) = u32x2{vr[i].z, vr[i].w};
+        }
+    };
+
     f32x4 acc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
 
-    // Key and value fragments of one 32-slot block: K rows slot0 + tt*16 + lr (A operand of S^T),
-    // V^T rows dt*16 + lr at keys {slot0 + 4lg..+3} and {slot0 + 16 + 4lg..+3} (A operand of O^T).
-    // Both are requested together, one block ahead of the arithmetic.
-    u32x4 kf[2][2][KS];
-    u32x2 vf[2][DT][2];
-    auto load_block = [&](int b, int buf) {
+    load_block(b0);
+    store_block(0);
+    __syncthreads();
+    int buf = 0;
+    for (int b = b0; b < b1; ++b) {
+        load_block(b + 1 < b1 ? b + 1 : b);               // never predicated; the last trip reloads its own block
         const int slot0 = b << 5;
-        const int pg = kv.page_table[slot0 >> kv.page_shift], off = slot0 & (P - 1);
-        const size_t head_base = (size_t)(pg * hkv + kvh);
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            const T *krow = kc + (head_base * P + off + tt * 16 + lr) * DH + lg * 8;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kf[buf][tt][ks] = *reinterpret_cast<const u32x4 *>(krow + ks * 32);
-        }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            const T *vrow = vc + (head_base * DH + dt * 16 + lr) * P + off + 4 * lg;
-            vf[buf][dt][0] = *reinterpret_cast<const u32x2 *>(vrow);
-            vf[buf][dt][1] = *reinterpret_cast<const u32x2 *>(vrow + 16);
-        }
-    };
-    auto compute_block = [&](int b, int buf) {
-        const int slot0 = b << 5;
+        // S^T tiles: rows = keys slot0 + tt*16 + (0..15), columns = query rows of this wave
         f32x4 s[2];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
             s[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                s[tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf[buf][tt][ks]), qf[ks], s[tt]);
-        }
-        // lane holds keys slot0 + tt*16 + 4*lg + r of query row lr
-        float sv[8], bm = -INFINITY;
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int slot = slot0 + tt * 16 + 4 * lg + r;
-                const float x = slot_visible(slot, n_prefix, region_len, m0, m1) ? s[tt][r] * scale : -INFINITY;
-                sv[tt * 4 + r] = x;
-                bm = fmaxf(bm, x);
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 kf = *reinterpret_cast<const u32x4 *>(&ks_lds[buf][(tt * 16 + lr) * KROW + ks * 32 + lg * 8]);
+                s[tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf), qf[ks], s[tt]);
             }
+        }
+        // lane holds keys slot0 + tt*16 + 4*lg + r of query row lr.  Scores are kept in the log2
+        // domain (scale * log2 e folded into one factor) so that the exponentials are single
+        // v_exp_f32 instructions; the softmax is VALU-bound, not MFMA-bound, at these sizes.
+        float sv[8], bm = -INFINITY;
+        if (slot0 + 32 <= n_prefix) {                    // whole block inside the committed prefix
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { sv[j] = s[j >> 2][j & 3] * scale; bm = fmaxf(bm, sv[j]); }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int slot = slot0 + (j >> 2) * 16 + 4 * lg + (j & 3);
+                sv[j] = slot_visible(slot, n_prefix, region_len, m0, m1) ? s[j >> 2][j & 3] * scale : -INFINITY;
+                bm = fmaxf(bm, sv[j]);
+            }
+        }
         bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
         bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
         const float m_new = fmaxf(m_run, bm);
@@ -127,44 +165,51 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(
 #pragma unroll
             for (int j = 0; j < 8; ++j) pf[j] = (T)0.f;
         } else {
-            alpha = expf(m_run - m_new);             // exp(-inf) = 0 on the first visible block
+            alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 2^(-inf) = 0 on the first visible block
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const float p = expf(sv[j] - m_new);
-                const T pt = from_f<T>(p);
+                const T pt = from_f<T>(__builtin_amdgcn_exp2f(sv[j] - m_new));
                 pf[j] = pt;
-                psum += to_f(pt);                    // normalise by what is actually multiplied into V
+                psum += to_f(pt);                        // normalise by what is actually multiplied into V
             }
         }
         l_run = l_run * alpha + psum;
         m_run = m_new;
+        const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.f) != 0;   // rare once the maximum has settled
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            acc[dt] *= alpha;
-            const u32x2 lo = vf[buf][dt][0], hi = vf[buf][dt][1];
-            acc[dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, (u32x4{lo.x, lo.y, hi.x, hi.y})), pf, acc[dt]);
+            if (rescale) acc[dt] *= alpha;
+            const u32x4 vf = *reinterpret_cast<const u32x4 *>(&vs_lds[buf][(dt * 16 + lr) * 32 + lg * 8]);
+            acc[dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf), pf, acc[dt]);
         }
-    };
-    if (b0 < b1) load_block(b0, 0);
-    for (int b = b0; b < b1; b += 2) {               // two blocks per trip so the buffer index is static
-        if (b + 1 < b1) load_block(b + 1, 1);
-        compute_block(b, 0);
-        if (b + 1 < b1) {
-            if (b + 2 < b1) load_block(b + 2, 0);
-            compute_block(b + 1, 1);
-        }
+        store_block(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
     }
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
 
     // O^T tile dt: lane -> query row lr, register r -> dh index dt*16 + 4*lg + r
-    const size_t prow = ((size_t)split * hkv + kvh) * rho_pad + blockIdx.x * 16 + lr;
+    if (out_direct) {
+        if (valid) {
+            const float inv = 1.0f / l_run;
+            T *dst = out_direct + ((size_t)m * hq + qh) * DH + 4 * lg;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-        *reinterpret_cast<f32x4 *>(o_part + prow * DH + dt * 16 + 4 * lg) = acc[dt];
-    if (lg == 0) {
-        ml_part[prow * 2] = m_run;
-        ml_part[prow * 2 + 1] = l_run;
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dst[dt * 16 + r] = from_f<T>(acc[dt][r] * inv);
+        }
+        return;
+    }
+    const size_t prow = ((size_t)split * hkv + kvh) * rho_pad + tile * 16 + lr;
+    if (tile * 16 < rho_pad) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            *reinterpret_cast<f32x4 *>(o_part + prow * DH + dt * 16 + 4 * lg) = acc[dt];
+        if (lg == 0) {
+            ml_part[prow * 2] = m_run;
+            ml_part[prow * 2 + 1] = l_run;
+        }
     }
 }
 
@@ -182,7 +227,7 @@ __global__ void attn_merge_kernel(const float *__restrict__ o_part, const float 
             const size_t prow = ((size_t)s * hkv + kvh) * rho_pad + rho;
             const float ms = ml_part[prow * 2];
             if (ms == -INFINITY) continue;
-            const float w = expf(ms - M);
+            const float w = __builtin_amdgcn_exp2f(ms - M);      // the partial maxima are in the log2 domain
             num += w * o_part[prow * dh + i];
             den += w * ml_part[prow * 2 + 1];
         }
@@ -228,6 +273,17 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float *__restrict__ 
     }
 }
 
+// Number of key splits: one while the whole key range is short (no merge kernel needed), else
+// enough that a workgroup walks about 32 blocks.  keys_per_split > 0 overrides.
+static int choose_splits(int n_blocks, int keys_per_split) {
+    if (keys_per_split > 0) {
+        int bps = keys_per_split / 32; if (bps < 1) bps = 1;
+        return (n_blocks + bps - 1) / bps;
+    }
+    if (n_blocks <= 24) return 1;
+    return (n_blocks + 31) / 32;
+}
+
 template <typename T>
 static void launch_attention_t(const ModelDims &md, const void *q, int rows, const RowMeta &rm, int n_prefix,
                                int region_len, const KVCache &kv, int keys_per_split, const AttnScratch &sc,
@@ -235,18 +291,20 @@ static void launch_attention_t(const ModelDims &md, const void *q, int rows, con
     const int G = md.hq / md.hkv;
     const int tiles = (rows * G + 15) / 16, rho_pad = tiles * 16;
     const int n_blocks = (n_prefix + region_len + 31) / 32;
-    int bps = keys_per_split / 32; if (bps < 1) bps = 1;
-    const int n_splits = (n_blocks + bps - 1) / bps;
-    const float scale = 1.0f / sqrtf((float)md.dh);
-    dim3 grid(tiles, md.hkv, n_splits);
+    const int n_splits = choose_splits(n_blocks, keys_per_split);
+    const int bps = (n_blocks + n_splits - 1) / n_splits;
+    const float scale = 1.4426950408889634f / sqrtf((float)md.dh);     // log2(e) / sqrt(dh): scores in the log2 domain
+    dim3 grid((tiles + 3) / 4, md.hkv, n_splits);
+    T *direct = n_splits == 1 ? static_cast<T *>(out) : nullptr;
     if (md.dh == 128)
-        hipLaunchKernelGGL((attn_mfma_kernel<T, 128>), grid, dim3(64), 0, st, static_cast<const T *>(q), rows, md.hq,
-                           md.hkv, rm.mask, n_prefix, region_len, kv, bps, scale, sc.o, sc.ml, rho_pad);
+        hipLaunchKernelGGL((attn_mfma_kernel<T, 128>), grid, dim3(256), 0, st, static_cast<const T *>(q), rows, md.hq,
+                           md.hkv, rm.mask, n_prefix, region_len, kv, bps, scale, sc.o, sc.ml, rho_pad, direct);
     else
-        hipLaunchKernelGGL((attn_mfma_kernel<T, 64>), grid, dim3(64), 0, st, static_cast<const T *>(q), rows, md.hq,
-                           md.hkv, rm.mask, n_prefix, region_len, kv, bps, scale, sc.o, sc.ml, rho_pad);
-    hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(rows, md.hq), dim3(md.dh < 64 ? 64 : md.dh), 0, st, sc.o, sc.ml,
-                       n_splits, md.hq, md.hkv, md.dh, rho_pad, static_cast<T *>(out));
+        hipLaunchKernelGGL((attn_mfma_kernel<T, 64>), grid, dim3(256), 0, st, static_cast<const T *>(q), rows, md.hq,
+                           md.hkv, rm.mask, n_prefix, region_len, kv, bps, scale, sc.o, sc.ml, rho_pad, direct);
+    if (n_splits > 1)
+        hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(rows, md.hq), dim3(md.dh < 64 ? 64 : md.dh), 0, st, sc.o, sc.ml,
+                           n_splits, md.hq, md.hkv, md.dh, rho_pad, static_cast<T *>(out));
 }
 
 int attention_splits(int total_keys, int keys_per_split) {
