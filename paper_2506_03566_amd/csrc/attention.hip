@@ -15,6 +15,8 @@
 // are merged by a second kernel in fixed order.
 #include "device_utils.h"
 
+#include <type_traits>
+
 namespace poss {
 
 typedef float  f32x4 __attribute__((ext_vector_type(4)));
@@ -49,8 +51,8 @@ __device__ __forceinline__ bool slot_visible(int slot, int n_prefix, int region_
 // the 8 keys a lane contracts (4 of each 16-key half) are one 16-byte chunk.
 // With a single split the result is normalised and written in the storage type directly;
 // otherwise (max, sum, O) partials go to the merge kernel.
-template <typename T, int DH>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(
+template <typename T, int DH, int KW>
+__global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     const T *__restrict__ q, int rows, int hq, int hkv, const uint64_t *__restrict__ mask, int n_prefix,
     int region_len, KVCache kv, int blocks_per_split, float scale, float *__restrict__ o_part,
     float *__restrict__ ml_part, int rho_pad, T *__restrict__ out_direct) {
@@ -59,12 +61,16 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
     constexpr int KROW = DH + 8;                          // padded K row, elements
     constexpr int K_UNITS = 32 * DH / 8;                  // 16-byte units of one K block
     constexpr int KPT = K_UNITS / 256, VPT = K_UNITS / 256;
-    __shared__ __attribute__((aligned(16))) T ks_lds[2][32 * KROW];
-    __shared__ __attribute__((aligned(16))) T vs_lds[2][DH * 32];
+    constexpr int KBLK = 32 * KROW, VBLK = DH * 32;       // elements of one staged K / V^T block
+    // [2 buffers][KW blocks]; after the last block the same memory carries the KW-way merge
+    __shared__ __attribute__((aligned(16))) T lds_all[2 * KW * (KBLK + VBLK)];
+    T *ks_lds = lds_all, *vs_lds = lds_all + 2 * KW * KBLK;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
+    const int kway = wave >> 2;                           // which of the KW blocks of an iteration this wave takes
+    const int stage_blk = tid >> 8, stid = tid & 255;     // staging: 256 threads per block
     const int G = hq / hkv, kvh = blockIdx.y, split = blockIdx.z;
-    const int tile = blockIdx.x * 4 + wave;
+    const int tile = blockIdx.x * 4 + (wave & 3);
     const int rho = tile * 16 + lr;
     const bool valid = rho < rows * G;
     const int m = valid ? rho / G : 0, qh = kvh * G + (valid ? rho % G : 0);
@@ -86,35 +92,42 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
 
     // staging: K block = 32 consecutive token rows = 32*DH contiguous elements; V^T block = DH rows
     // of 32 keys (64 bytes each, row stride P elements)
-    u32x4 kr[KPT], vr[VPT];
-    auto load_block = [&](int b) {
+    // ring of PFD iterations of key/value loads in flight: an iteration's arithmetic is much shorter
+    // than the latency of its loads, so one block of look-ahead would leave the loop latency-bound
+    constexpr int PFD = KW >= 4 ? 1 : 2;                  // 1024-thread workgroups have 128 VGPRs per lane
+    u32x4 kr[PFD][KPT], vr[PFD][VPT];
+    auto load_block = [&](auto slot_tag, int bfirst) {    // this thread's share of block bfirst + stage_blk
+        constexpr int SLOT = decltype(slot_tag)::value;
+        int b = bfirst + stage_blk;
+        if (b >= b1) b = b1 - 1;                          // never predicated: reload a valid block, it is ignored
         const int slot0 = b << 5;
         const int pg = kv.page_table[slot0 >> kv.page_shift], off = slot0 & (P - 1);
         const size_t head_base = (size_t)(pg * hkv + kvh);
         const T *kb = kc + (head_base * P + off) * DH;
         const T *vb = vc + head_base * DH * P + off;
 #pragma unroll
-        for (int i = 0; i < KPT; ++i) kr[i] = *reinterpret_cast<const u32x4 *>(kb + (size_t)(tid + i * 256) * 8);
+        for (int i = 0; i < KPT; ++i) kr[SLOT][i] = *reinterpret_cast<const u32x4 *>(kb + (size_t)(stid + i * 256) * 8);
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
-            const int u = tid + i * 256;                  // unit: dh row u / 4, keys (u % 4) * 8 .. +8
-            vr[i] = *reinterpret_cast<const u32x4 *>(vb + (size_t)(u >> 2) * P + (u & 3) * 8);
+            const int u = stid + i * 256;                 // unit: dh row u / 4, keys (u % 4) * 8 .. +8
+            vr[SLOT][i] = *reinterpret_cast<const u32x4 *>(vb + (size_t)(u >> 2) * P + (u & 3) * 8);
         }
     };
-    auto store_block = [&](int buf) {
+    auto store_block = [&](auto slot_tag, int buf) {
+        constexpr int SLOT = decltype(slot_tag)::value;
 #pragma unroll
         for (int i = 0; i < KPT; ++i) {
-            const int u = tid + i * 256, row = u / (DH / 8), c8 = u % (DH / 8);
-            *reinterpret_cast<u32x4 *>(&ks_lds[buf][row * KROW + c8 * 8]) = kr[i];
+            const int u = stid + i * 256, row = u / (DH / 8), c8 = u % (DH / 8);
+            *reinterpret_cast<u32x4 *>(&ks_lds[(buf * KW + stage_blk) * KBLK + row * KROW + c8 * 8]) = kr[SLOT][i];
         }
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             // keys k0 = (u%4)*8 .. k0+7: key k sits at element (k%16)/4*8 + (k/16)*4 + k%4 of its row
-            const int u = tid + i * 256, row = u >> 2, k0 = (u & 3) * 8;
+            const int u = stid + i * 256, row = u >> 2, k0 = (u & 3) * 8;
             const int half = k0 >> 4, g0 = (k0 & 15) >> 2;                 // k0..k0+3 -> group g0, k0+4..k0+7 -> g0+1
-            T *dst = &vs_lds[buf][row * 32];
-            *reinterpret_cast<u32x2 *>(dst + g0 * 8 + half * 4) = u32x2{vr[i].x, vr[i].y};
-            *reinterpret_cast<u32x2 *>(dst + (g0 + 1) * 8 + half * 4) = u32x2{vr[i].z, vr[i].w};
+            T *dst = &vs_lds[(buf * KW + stage_blk) * VBLK + row * 32];
+            *reinterpret_cast<u32x2 *>(dst + g0 * 8 + half * 4) = u32x2{vr[SLOT][i].x, vr[SLOT][i].y};
+            *reinterpret_cast<u32x2 *>(dst + (g0 + 1) * 8 + half * 4) = u32x2{vr[SLOT][i].z, vr[SLOT][i].w};
         }
     };
 
@@ -123,13 +136,25 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
     for (int dt = 0; dt < DT; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
 
-    load_block(b0);
-    store_block(0);
+    auto static_for = [&](auto f) {                       // f(integral_constant<int, p>) for p < PFD
+        f(std::integral_constant<int, 0>{});
+        if constexpr (PFD > 1) f(std::integral_constant<int, 1>{});
+        if constexpr (PFD > 2) f(std::integral_constant<int, 2>{});
+        if constexpr (PFD > 3) f(std::integral_constant<int, 3>{});
+    };
+    static_for([&](auto p) { load_block(p, b0 + decltype(p)::value * KW); });
+    store_block(std::integral_constant<int, 0>{}, 0);
     __syncthreads();
     int buf = 0;
-    for (int b = b0; b < b1; ++b) {
-        load_block(b + 1 < b1 ? b + 1 : b);               // never predicated; the last trip reloads its own block
+    // iteration `it` (blocks bi .. bi+KW-1): refill ring slot it%PFD with iteration it+PFD, compute
+    // from LDS buffer `buf`, move iteration it+1 (slot (it+1)%PFD) into the other buffer.
+    auto iteration = [&](auto slot_tag, int bi) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        load_block(slot_tag, bi + PFD * KW);
+        const int b = bi + kway;
+        if (b < b1) {                                     // wave-uniform
         const int slot0 = b << 5;
+        const T *kbuf = &ks_lds[(buf * KW + kway) * KBLK], *vbuf = &vs_lds[(buf * KW + kway) * VBLK];
         // S^T tiles: rows = keys slot0 + tt*16 + (0..15), columns = query rows of this wave
         f32x4 s[2];
 #pragma unroll
@@ -137,7 +162,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
             s[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const u32x4 kf = *reinterpret_cast<const u32x4 *>(&ks_lds[buf][(tt * 16 + lr) * KROW + ks * 32 + lg * 8]);
+                const u32x4 kf = *reinterpret_cast<const u32x4 *>(&kbuf[(tt * 16 + lr) * KROW + ks * 32 + lg * 8]);
                 s[tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf), qf[ks], s[tt]);
             }
         }
@@ -179,15 +204,53 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             if (rescale) acc[dt] *= alpha;
-            const u32x4 vf = *reinterpret_cast<const u32x4 *>(&vs_lds[buf][(dt * 16 + lr) * 32 + lg * 8]);
+            const u32x4 vf = *reinterpret_cast<const u32x4 *>(&vbuf[(dt * 16 + lr) * 32 + lg * 8]);
             acc[dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf), pf, acc[dt]);
         }
-        store_block(buf ^ 1);
+        }
+        store_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, buf ^ 1);
         __syncthreads();
         buf ^= 1;
-    }
+    };
+    for (int bi = b0; bi < b1; bi += PFD * KW)            // unrolled by PFD so that ring slots are static
+        static_for([&](auto p) {
+            constexpr int I = decltype(p)::value;
+            if (bi + I * KW < b1) iteration(p, bi + I * KW);
+        });
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
+
+    if constexpr (KW > 1) {
+        // Merge the KW partial (max, sum, O) of each row tile in key-way order: ways 1.. park theirs
+        // in LDS (the staging buffers are free after the loop's final barrier), way 0 folds them in.
+        float *xch = reinterpret_cast<float *>(lds_all);  // per (way-1, tile): 64 lanes x (DT*4 + 2) floats
+        constexpr int REC = DT * 4 + 2;
+        static_assert((size_t)(KW - 1) * 4 * 64 * REC * sizeof(float) <= sizeof(lds_all), "merge records must fit");
+        float *mine = xch + ((size_t)((kway - 1) * 4 + (wave & 3)) * 64 + lane) * REC;
+        if (kway > 0) {
+            mine[0] = m_run; mine[1] = l_run;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) mine[2 + dt * 4 + r] = acc[dt][r];
+        }
+        __syncthreads();
+        if (kway > 0) return;
+#pragma unroll
+        for (int w = 1; w < KW; ++w) {
+            const float *o = xch + ((size_t)((w - 1) * 4 + (wave & 3)) * 64 + lane) * REC;
+            const float mo = o[0], lo = o[1];
+            const float mn = fmaxf(m_run, mo);
+            if (mn == -INFINITY) continue;
+            const float a0 = __builtin_amdgcn_exp2f(m_run - mn), a1 = __builtin_amdgcn_exp2f(mo - mn);
+            l_run = l_run * a0 + lo * a1;
+            m_run = mn;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[dt][r] = acc[dt][r] * a0 + o[2 + dt * 4 + r] * a1;
+        }
+    }
 
     // O^T tile dt: lane -> query row lr, register r -> dh index dt*16 + 4*lg + r
     if (out_direct) {
@@ -296,12 +359,13 @@ static void launch_attention_t(const ModelDims &md, const void *q, int rows, con
     const float scale = 1.4426950408889634f / sqrtf((float)md.dh);     // log2(e) / sqrt(dh): scores in the log2 domain
     dim3 grid((tiles + 3) / 4, md.hkv, n_splits);
     T *direct = n_splits == 1 ? static_cast<T *>(out) : nullptr;
-    if (md.dh == 128)
-        hipLaunchKernelGGL((attn_mfma_kernel<T, 128>), grid, dim3(256), 0, st, static_cast<const T *>(q), rows, md.hq,
-                           md.hkv, rm.mask, n_prefix, region_len, kv, bps, scale, sc.o, sc.ml, rho_pad, direct);
-    else
-        hipLaunchKernelGGL((attn_mfma_kernel<T, 64>), grid, dim3(256), 0, st, static_cast<const T *>(q), rows, md.hq,
-                           md.hkv, rm.mask, n_prefix, region_len, kv, bps, scale, sc.o, sc.ml, rho_pad, direct);
+    const int kw = bps >= 8 ? 4 : bps >= 4 ? 2 : 1;       // key-ways inside the workgroup
+#define POSS_ATTN(DH, KW)                                                                                        \
+    hipLaunchKernelGGL((attn_mfma_kernel<T, DH, KW>), grid, dim3(256 * KW), 0, st, static_cast<const T *>(q), rows, \
+                       md.hq, md.hkv, rm.mask, n_prefix, region_len, kv, bps, scale, sc.o, sc.ml, rho_pad, direct)
+    if (md.dh == 128) { if (kw == 4) POSS_ATTN(128, 4); else if (kw == 2) POSS_ATTN(128, 2); else POSS_ATTN(128, 1); }
+    else              { if (kw == 4) POSS_ATTN(64, 4);  else if (kw == 2) POSS_ATTN(64, 2);  else POSS_ATTN(64, 1); }
+#undef POSS_ATTN
     if (n_splits > 1)
         hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(rows, md.hq), dim3(md.dh < 64 ? 64 : md.dh), 0, st, sc.o, sc.ml,
                            n_splits, md.hq, md.hkv, md.dh, rho_pad, static_cast<T *>(out));
