@@ -160,20 +160,22 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
 }
 
 // ------------------------------------------------------------------------------------------
-template <typename T, int MT>
-__global__ __launch_bounds__(GEMM_WPB * 64) void gemm_stream_kernel(
+// WPB waves per workgroup: 4 (one 128-column tile) or 8 (two tiles sharing one staged activation
+// slice: halves the L2 traffic per weight byte; used where N alone fills the GPU).
+template <typename T, int MT, int WPB>
+__global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
     int M, int K, int Npad, int ksteps_total, int chunks_per_split) {
     static_assert(KCS % PF == 0, "ring index must be static");
     constexpr int XUNITS = KCS * MT * 64;                 // 16-byte units of one staged chunk
-    constexpr int XPT    = XUNITS / (GEMM_WPB * 64);      // units per thread (2*MT)
+    constexpr int XPT    = XUNITS / (WPB * 64);           // units per thread
     __shared__ u32x4 xs[2][XUNITS];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int chunk0 = blockIdx.y * chunks_per_split;
     const int n_chunks_total = ksteps_total / KCS;
     const int chunk1 = min(n_chunks_total, chunk0 + chunks_per_split);
-    const int ngroup = blockIdx.x * GEMM_WPB + wave;
+    const int ngroup = blockIdx.x * WPB + wave;
     const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCS) * (GEMM_NT * 64) + lane;
 
     // Global->LDS staging map: unit u of a chunk covers row m = u / 32, 8 consecutive k starting at
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(GEMM_WPB * 64) void gemm_stream_kernel(
     bool x_row_ok[XPT];
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
-        const int u = tid + i * (GEMM_WPB * 64);
+        const int u = tid + i * (WPB * 64);
         const int m = u >> 5, k8 = u & 31;
         x_row_ok[i] = m < M;
         x_src[i] = X + (size_t)(m < M ? m : M - 1) * ldx;
@@ -352,13 +354,22 @@ static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiAr
 template <typename T>
 static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
                           const EpiArgs &epi, hipStream_t st) {
-    dim3 grid(g.Npad / GEMM_BLOCK_N, g.S), block(GEMM_WPB * 64);
+    // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
+    const bool wide = g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
+    const int wpb = wide ? 8 : 4;
+    dim3 grid(g.Npad / (GEMM_NT * 16 * wpb), g.S), block(wpb * 64);
     const int ksteps = g.Kpad / GEMM_KSTEP;
     const u32x4 *w = static_cast<const u32x4 *>(Wp);
     const T *x = static_cast<const T *>(X);
-#define POSS_GEMM_CASE(MT)                                                                        \
-    hipLaunchKernelGGL((gemm_stream_kernel<T, MT>), grid, block, 0, st, w, x, ldx, part, g.M, g.K, \
-                       g.Npad, ksteps, g.chunks_per_split)
+#define POSS_GEMM_CASE(MT)                                                                                    \
+    do {                                                                                                      \
+        if (wide)                                                                                             \
+            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 8>), grid, block, 0, st, w, x, ldx, part, g.M, g.K,    \
+                               g.Npad, ksteps, g.chunks_per_split);                                           \
+        else                                                                                                  \
+            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 4>), grid, block, 0, st, w, x, ldx, part, g.M, g.K,    \
+                               g.Npad, ksteps, g.chunks_per_split);                                           \
+    } while (0)
     switch (g.Mpad / 16) {
         case 1: POSS_GEMM_CASE(1); break;
         case 2: POSS_GEMM_CASE(2); break;
