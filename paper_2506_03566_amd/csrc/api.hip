@@ -116,6 +116,7 @@ const char *check_config(const poss_config &c) {
     if (c.total_tokens < 1 || c.total_tokens + 1 > POSS_MAX_ROWS) return "total_tokens must be in 1..127";
     if (c.total_tokens > pool) return "total_tokens exceeds the candidate pool k + (depth-1) k^2";
     if (pool > 2048) return "candidate pool too large";
+    if ((long long)((c.vocab + 2047) / 2048) * c.top_k > 2048) return "vocab * top_k too large for the top-k merge";
     if ((c.depth - 1) * c.top_k > 64 * POSS_MASK_WORDS) return "(depth-1)*top_k must fit the 128-bit ancestor mask";
     if (c.top_k + (c.depth + 1) + (c.depth - 1) * c.top_k > POSS_MAX_ROWS) return "a specialist pass would exceed 128 rows";
     if (c.kv_page_tokens != 32 && c.kv_page_tokens != 64 && c.kv_page_tokens != 128) return "kv_page_tokens must be 32, 64 or 128";

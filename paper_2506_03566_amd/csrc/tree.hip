@@ -11,91 +11,121 @@
 
 namespace poss {
 
-// ------------------------------------------------------------------ top-k + log-sum-exp, stage 1
-// One workgroup per (segment of <= TOPK_SEG logits, row): segment maximum, sum of exp(l - max) and
-// the segment's k best (value, index).
+// ------------------------------------------------------------------ top-k + log-sum-exp
+// Selection of the k best (value, index) pairs held NV per thread by a 256-thread workgroup: every
+// wave extracts its own k best with shuffles only (no workgroup barrier inside the k rounds), then
+// wave 0 picks the k best of the 4k survivors.  Thread r < k of wave 0 ends up with the r-th best.
 constexpr int TOPK_SEG = 2048;
 constexpr int TOPK_MAXK = 16;
 
-__global__ __launch_bounds__(256) void topk_seg_kernel(const float *__restrict__ logits, int ld, int vocab, int k,
-                                                       int n_seg, float *__restrict__ seg_out) {
-    __shared__ float vals[TOPK_SEG];
-    __shared__ float red_v[17];
-    __shared__ int red_i[17];
-    const int seg = blockIdx.x, row = blockIdx.y;
-    const int base = seg * TOPK_SEG, n = min(TOPK_SEG, vocab - base);
-    const float *src = logits + (size_t)row * ld + base;
-    float mx = -INFINITY;
-    for (int i = threadIdx.x; i < TOPK_SEG; i += blockDim.x) {
-        const float v = i < n ? src[i] : -INFINITY;
-        vals[i] = v;
-        mx = fmaxf(mx, v);
-    }
-    int dummy = 0;
-    {   // segment max via the argmax reduction (index irrelevant)
-        float v = mx; int i = threadIdx.x;
-        block_argmax(v, i, red_v, red_i);
-        mx = v; dummy = i;
-    }
-    (void)dummy;
-    float se = 0.f;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) se += expf(vals[i] - mx);
-    se = block_sum(se, red_v);
-    // record layout per (row, seg): [max, sumexp, k values, k indices(as float bits)]
-    float *rec = seg_out + ((size_t)row * n_seg + seg) * (2 + 2 * TOPK_MAXK);
-    if (threadIdx.x == 0) { rec[0] = mx; rec[1] = se; }
-    for (int j = 0; j < k; ++j) {
+template <int NV>
+__device__ __forceinline__ void block_topk(float (&v)[NV], int (&id)[NV], int k, float *s_val, int *s_id,
+                                           float &out_v, int &out_i) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int r = 0; r < k; ++r) {
         float bv = -INFINITY; int bi = 0x7fffffff;
-        for (int i = threadIdx.x; i < TOPK_SEG; i += blockDim.x) {
-            const float v = vals[i];
-            if (better(v, i, bv, bi)) { bv = v; bi = i; }
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+            if (better(v[j], id[j], bv, bi)) { bv = v[j]; bi = id[j]; }
+        wave_argmax(bv, bi);
+        if (lane == 0) { s_val[wave * TOPK_MAXK + r] = bv; s_id[wave * TOPK_MAXK + r] = bi; }
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+            if (id[j] == bi) v[j] = -INFINITY;           // indices are unique: removes exactly the winner
+    }
+    __syncthreads();
+    out_v = -INFINITY; out_i = 0x7fffffff;
+    if (wave == 0) {
+        const int w = lane / TOPK_MAXK, r = lane % TOPK_MAXK;
+        float cv = -INFINITY; int ci = 0x7fffffff;
+        if (w < (int)(blockDim.x >> 6) && r < k) { cv = s_val[w * TOPK_MAXK + r]; ci = s_id[w * TOPK_MAXK + r]; }
+        for (int r2 = 0; r2 < k; ++r2) {
+            float bv = cv; int bi = ci;
+            wave_argmax(bv, bi);
+            if (lane == r2) { out_v = bv; out_i = bi; }
+            if (ci == bi) cv = -INFINITY;
         }
-        block_argmax(bv, bi, red_v, red_i);
-        if (threadIdx.x == 0) {
-            rec[2 + j] = bv;
-            reinterpret_cast<int *>(rec)[2 + TOPK_MAXK + j] = (bi < TOPK_SEG && bv > -INFINITY) ? base + bi : 0x7fffffff;
-            if (bi < TOPK_SEG) vals[bi] = -INFINITY;
-        }
-        __syncthreads();
     }
 }
 
-// stage 2: one workgroup per row merges the segments.
+// stage 1: one workgroup per (segment of <= TOPK_SEG logits, row): segment maximum, sum of
+// exp(l - max) and the segment's k best.  record: [max, sumexp, k values, k indices (as bits)]
+__global__ __launch_bounds__(256) void topk_seg_kernel(const float *__restrict__ logits, int ld, int vocab, int k,
+                                                       int n_seg, float *__restrict__ seg_out) {
+    constexpr int NV = TOPK_SEG / 256;
+    __shared__ float s_val[4 * TOPK_MAXK];
+    __shared__ int s_id[4 * TOPK_MAXK];
+    __shared__ float red[17];
+    const int seg = blockIdx.x, row = blockIdx.y;
+    const int base = seg * TOPK_SEG;
+    const float *src = logits + (size_t)row * ld;
+    float v[NV]; int id[NV];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = base + threadIdx.x + j * 256;
+        const bool ok = i < vocab;
+        v[j] = ok ? src[i] : -INFINITY;
+        id[j] = ok ? i : 0x7fffffff - j;                  // distinct dummies keep "indices are unique" true
+        mx = fmaxf(mx, v[j]);
+    }
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float se = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) se += v[j] > -INFINITY ? expf(v[j] - mx) : 0.f;
+    se = block_sum(se, red);
+    float *rec = seg_out + ((size_t)row * n_seg + seg) * (2 + 2 * TOPK_MAXK);
+    if (threadIdx.x == 0) { rec[0] = mx; rec[1] = se; }
+    float ov; int oi;
+    block_topk<NV>(v, id, k, s_val, s_id, ov, oi);
+    if ((int)threadIdx.x < k) {
+        rec[2 + threadIdx.x] = ov;
+        reinterpret_cast<int *>(rec)[2 + TOPK_MAXK + threadIdx.x] = ov > -INFINITY ? oi : 0x7fffffff;
+    }
+}
+
+// stage 2: one workgroup per row merges the segments: lse over the segment records, then the k
+// best of the n_seg * k candidates; writes token ids and log-probabilities (value - lse).
+constexpr int TOPK_MERGE_NV = 8;                          // up to 2048 candidates (128 segments x 16)
 __global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict__ seg_out, int n_seg, int k,
                                                          int32_t *__restrict__ out_id, float *__restrict__ out_logp) {
-    extern __shared__ float cand[];                 // n_seg * k values, then n_seg * k ids
-    __shared__ float red_v[17];
-    __shared__ int red_i[17];
+    __shared__ float s_val[4 * TOPK_MAXK];
+    __shared__ int s_id[4 * TOPK_MAXK];
+    __shared__ float red[17];
     const int row = blockIdx.x, nc = n_seg * k;
-    int *cid = reinterpret_cast<int *>(cand + nc);
     const float *recs = seg_out + (size_t)row * n_seg * (2 + 2 * TOPK_MAXK);
     float mx = -INFINITY;
     for (int s = threadIdx.x; s < n_seg; s += blockDim.x) mx = fmaxf(mx, recs[(size_t)s * (2 + 2 * TOPK_MAXK)]);
-    { float v = mx; int i = threadIdx.x; block_argmax(v, i, red_v, red_i); mx = v; }
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     float se = 0.f;
     for (int s = threadIdx.x; s < n_seg; s += blockDim.x) {
         const float *r = recs + (size_t)s * (2 + 2 * TOPK_MAXK);
         se += r[1] * expf(r[0] - mx);
     }
-    se = block_sum(se, red_v);
+    se = block_sum(se, red);
     const float lse = mx + logf(se);
-    for (int c = threadIdx.x; c < nc; c += blockDim.x) {
-        const float *r = recs + (size_t)(c / k) * (2 + 2 * TOPK_MAXK);
-        cand[c] = r[2 + c % k];
-        cid[c] = reinterpret_cast<const int *>(r)[2 + TOPK_MAXK + c % k];
-    }
-    __syncthreads();
-    for (int j = 0; j < k; ++j) {
-        float bv = -INFINITY; int bi = 0x7fffffff, bc = -1;
-        for (int c = threadIdx.x; c < nc; c += blockDim.x)
-            if (better(cand[c], cid[c], bv, bi)) { bv = cand[c]; bi = cid[c]; bc = c; }
-        block_argmax(bv, bi, red_v, red_i);          // ids are unique, so (value, id) names one candidate
-        if (bc >= 0 && cid[bc] == bi && cand[bc] == bv) cand[bc] = -INFINITY;
-        if (threadIdx.x == 0) {
-            out_id[row * k + j] = bi;
-            out_logp[row * k + j] = bv - lse;
+    float v[TOPK_MERGE_NV]; int id[TOPK_MERGE_NV];
+#pragma unroll
+    for (int j = 0; j < TOPK_MERGE_NV; ++j) {
+        const int c = threadIdx.x + j * 256;
+        v[j] = -INFINITY; id[j] = 0x7fffffff - j;
+        if (c < nc) {
+            const float *r = recs + (size_t)(c / k) * (2 + 2 * TOPK_MAXK);
+            const int ci = reinterpret_cast<const int *>(r)[2 + TOPK_MAXK + c % k];
+            if (ci != 0x7fffffff) { v[j] = r[2 + c % k]; id[j] = ci; }
         }
-        __syncthreads();
+    }
+    float ov; int oi;
+    block_topk<TOPK_MERGE_NV>(v, id, k, s_val, s_id, ov, oi);
+    if ((int)threadIdx.x < k) {
+        out_id[row * k + threadIdx.x] = oi;
+        out_logp[row * k + threadIdx.x] = ov - lse;
     }
 }
 
@@ -103,8 +133,7 @@ void launch_topk_logsoftmax(const float *logits, int ld, int rows, int vocab, in
                             int32_t *out_id, float *out_logp, hipStream_t st) {
     const int n_seg = (vocab + TOPK_SEG - 1) / TOPK_SEG;
     hipLaunchKernelGGL(topk_seg_kernel, dim3(n_seg, rows), dim3(256), 0, st, logits, ld, vocab, k, n_seg, seg_scratch);
-    hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(256), (size_t)n_seg * k * 8, st, seg_scratch, n_seg, k,
-                       out_id, out_logp);
+    hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(256), 0, st, seg_scratch, n_seg, k, out_id, out_logp);
 }
 
 size_t topk_scratch_floats(int rows, int vocab) {
