@@ -104,6 +104,7 @@ const char *check_config(const poss_config &c) {
     if (c.n_layers < 1 || c.d_model < 8 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.d_ffn < 8 || c.vocab < 2)
         return "non-positive model dimension";
     if (c.dtype < 0 || c.dtype > 2) return "dtype must be 0 (f32), 1 (bf16) or 2 (f16)";
+    if (c.d_model > 16384) return "d_model above 16384 is not supported by the residual epilogue";
     if (c.n_q_heads % c.n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
     if (c.dtype != POSS_DTYPE_F32 && c.head_dim != 64 && c.head_dim != 128)
         return "16-bit kernels support head_dim 64 or 128";
@@ -241,7 +242,7 @@ GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int
     GemmShape g = gemm_plan(c->md.dt, M, N, K, single_split ? 1 : c->gemm_target_wgs);
     const bool prof = c->prof_on && c->prof_n < PROFILE_EVENTS;
     if (prof) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->st);
-    launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->st);
+    launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st);
     if (prof) {
         (void)hipEventRecord(c->prof_ev[2 * c->prof_n + 1], c->st);
         ++c->prof_n;
@@ -250,15 +251,12 @@ GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int
     return g;
 }
 
-EpiArgs epi_residual(poss_ctx *c, bool residual, const void *bias, float *h_copy) {
+// h (+)= GEMM (+ bias), then u = T(rmsnorm(h) * gain) for the next GEMM
+EpiArgs epi_residual(poss_ctx *c, bool residual, const void *bias, float *h_copy, const void *gain) {
     EpiArgs e{};
     e.mode = EPI_RESIDUAL; e.h = c->h; e.bias = bias; e.residual = residual ? 1 : 0; e.h_copy = h_copy;
-    e.ss = c->ss; e.ss_ld = c->ss_ld;
+    e.gain = gain; e.u = c->u;
     return e;
-}
-
-void norm_rows(poss_ctx *c, int rows, const void *gain) {
-    launch_norm_apply(c->md, c->h, c->ss, c->ss_ld, gemm_npad(c->md.d) / GEMM_BLOCK_N, rows, gain, c->u, c->st);
 }
 
 // One decoder layer on rows_all rows (all produce K/V) of which the first rows_q go through
@@ -275,13 +273,11 @@ void run_layer(poss_ctx *c, const LayerW &w, const KVCache &kv, int rows_all, in
     if (rows_q == 0) return;
     launch_attention(md, c->q, rows_q, rm, n_prefix, region_len, kv, c->attn_keys_per_split, c->attn_sc,
                      c->attn_out, c->st);
-    run_gemm(c, w.wo, md.d, qd, c->attn_out, qd, rows_q, c->part, false, epi_residual(c, true, nullptr, nullptr));
-    norm_rows(c, rows_q, w.mlp_norm);
+    run_gemm(c, w.wo, md.d, qd, c->attn_out, qd, rows_q, c->part, false, epi_residual(c, true, nullptr, nullptr, w.mlp_norm));
     EpiArgs es{};
     es.mode = EPI_SILU; es.act = c->act; es.F = md.ffn;
     run_gemm(c, w.wgu, gate_up_rows(md.ffn), md.d, c->u, md.d, rows_q, c->part, false, es);
-    run_gemm(c, w.wdown, md.d, md.ffn, c->act, md.ffn, rows_q, c->part, false, epi_residual(c, true, nullptr, h_copy));
-    norm_rows(c, rows_q, next_gain);
+    run_gemm(c, w.wdown, md.d, md.ffn, c->act, md.ffn, rows_q, c->part, false, epi_residual(c, true, nullptr, h_copy, next_gain));
 }
 
 // Target pass over `rows` rows whose tokens / metadata are on the device.  Leaves features in
@@ -345,8 +341,7 @@ void spec_pass(poss_ctx *c, int s, const DraftRowPlan &plan, int depth_index, in
                           fhat_prev, c->xin_tmp, c->xin, c->row_pos, c->row_slot, c->row_mask, c->st);
     launch_rope_table(c->row_pos, c->inv_freq, md.dh / 2, plan.n_rows, c->cs, c->st);
     run_gemm(c, w.fc_w, md.d, 2 * md.d, c->xin, 2 * md.d, plan.n_rows, c->part, false,
-             epi_residual(c, false, c->cfg.fc_bias ? w.fc_b : nullptr, nullptr));
-    norm_rows(c, plan.n_rows, w.layer.attn_norm);
+             epi_residual(c, false, c->cfg.fc_bias ? w.fc_b : nullptr, nullptr, w.layer.attn_norm));
     RowMeta rm{c->row_pos, c->row_slot, c->row_mask};
     run_layer(c, w.layer, c->spec_kv[s], plan.n_rows, rows_q, rm, n_prefix, region_len, c->final_norm, fhat_out);
 }
@@ -838,9 +833,9 @@ int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_
     launch_pack(dtype, PackSrc{{w, nullptr, nullptr}, {N, 0, 0}}, K, wp, st);
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return fail(nullptr, POSS_E_HIP, "poss_debug_gemm: event creation failed");
-    launch_gemm(dtype, g, wp, x, K, part, epi, st);
+    launch_gemm(dtype, g, wp, x, K, part, epi, 0.f, st);
     (void)hipEventRecord(e0, st);
-    for (int i = 0; i < repeats; ++i) launch_gemm(dtype, g, wp, x, K, part, epi, st);
+    for (int i = 0; i < repeats; ++i) launch_gemm(dtype, g, wp, x, K, part, epi, 0.f, st);
     (void)hipEventRecord(e1, st);
     hipError_t e = hipStreamSynchronize(st);
     float ms = 0.f;

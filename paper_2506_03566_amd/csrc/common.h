@@ -90,22 +90,19 @@ struct EpiArgs {
     // EPI_ROPE_KV: columns are [q heads | k heads | v heads]; rows < rows_q get a rotated query,
     // every row its rotated key and its value written to cache slot slot[m]
     int rows_q; const float2 *cs; const int32_t *slot; void *q; KVCache kv; int hq, hkv, dh;
-    // EPI_RESIDUAL: h[m][n] = sum + bias[n] + (residual ? h[m][n] : 0); h_copy likewise;
-    // ss[m][tile] = sum over the tile's columns of h^2 (RMSNorm partials)
-    float *h; const void *bias; int residual; float *h_copy; float *ss; int ss_ld;
+    // EPI_RESIDUAL: h[m][n] = sum + bias[n] + (residual ? h[m][n] : 0); h_copy likewise; then, if
+    // gain != nullptr, u[m][n] = T(rmsnorm(h[m]) * gain[n]) - the operand of the next GEMM
+    float *h; const void *bias; int residual; float *h_copy; const void *gain; void *u;
     // EPI_SILU: tile j holds gate[64j..64j+63] | up[64j..64j+63]; act[m][f] = T(silu(gate) * up)
     void *act; int F;
 };
 // part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.
 void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 const EpiArgs &epi, hipStream_t st);
+                 const EpiArgs &epi, float rms_eps, hipStream_t st);
 
 // ---------------------------------------------------------------- launchers: elementwise
 void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *tokens, int rows,
                        const void *gain, float *h, void *u, hipStream_t st);
-// u = T(h / sqrt(sum_tiles ss / d + eps) * gain)
-void launch_norm_apply(const ModelDims &md, const float *h, const float *ss, int ss_ld, int n_tiles, int rows,
-                       const void *gain, void *u, hipStream_t st);
 // cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)), angle formed in float64
 void launch_rope_table(const int32_t *pos, const double *inv_freq, int half, int rows, float2 *cs, hipStream_t st);
 void launch_argmax(const float *logits, int ld, int rows, int vocab, int32_t *out, hipStream_t st);

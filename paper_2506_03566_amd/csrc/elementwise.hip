@@ -1,5 +1,4 @@
-// Small kernels around the GEMMs: embedding gather + first RMSNorm, RMSNorm application from the
-// GEMM epilogue's partial sums of squares, rotary table, argmax, row copies.  All arithmetic in
+// Small kernels around the GEMMs: embedding gather + first RMSNorm, rotary table, argmax, row copies.  All arithmetic in
 // float32; values become the storage type only where they are the next GEMM's operand.
 #include "device_utils.h"
 
@@ -53,30 +52,6 @@ __global__ void rope_table_kernel(const int32_t *__restrict__ pos, const double 
 
 void launch_rope_table(const int32_t *pos, const double *inv_freq, int half, int rows, float2 *cs, hipStream_t st) {
     hipLaunchKernelGGL(rope_table_kernel, dim3(rows), dim3(half < 64 ? 64 : half), 0, st, pos, inv_freq, half, cs);
-}
-
-// ------------------------------------------------------------------ u = T(rmsnorm(h) g) from tile partials
-// ss[m][tile] holds the sum of squares of 128 columns of h (written by the GEMM epilogue); every
-// workgroup re-adds the row's partials in tile order.
-template <typename T>
-__global__ __launch_bounds__(256) void norm_apply_kernel(const float *__restrict__ h, const float *__restrict__ ss,
-                                                         int ss_ld, int n_tiles, int d, float eps,
-                                                         const T *__restrict__ gain, T *__restrict__ u) {
-    const int m = blockIdx.y;
-    float tot = 0.f;
-    for (int i = 0; i < n_tiles; ++i) tot += ss[(size_t)m * ss_ld + i];
-    const float rs = 1.0f / sqrtf(tot / (float)d + eps);
-    const int c = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        if (c + j < d) u[(size_t)m * d + c + j] = from_f<T>(h[(size_t)m * d + c + j] * rs * to_f(gain[c + j]));
-}
-
-void launch_norm_apply(const ModelDims &md, const float *h, const float *ss, int ss_ld, int n_tiles, int rows,
-                       const void *gain, void *u, hipStream_t st) {
-    dim3 grid((md.d + 1023) / 1024, rows);
-    POSS_DISPATCH(md.dt, hipLaunchKernelGGL((norm_apply_kernel<T>), grid, dim3(256), 0, st, h, ss, ss_ld, n_tiles,
-                                            md.d, md.eps, static_cast<const T *>(gain), static_cast<T *>(u)));
 }
 
 // ------------------------------------------------------------------ argmax per row (lowest index on ties)

@@ -48,7 +48,8 @@ constexpr int PF  = POSS_GEMM_PF;               // weight k-steps in flight per 
 // ------------------------------------------------------------------------------------------
 // Epilogue of one output tile (columns [tile*128, tile*128+128)) for rows [r_begin, r_end), run by
 // 256 threads.  Split-K planes are added in split order; loads are issued eight at a time.
-constexpr int EPI_ROWS = 16;       // rows per epilogue workgroup
+constexpr int EPI_ROWS_PLAIN = 16;  // rows per epilogue workgroup: plain sums sweep 8 rows at a time,
+constexpr int EPI_ROWS_PAIR = 4;    // rotary / SiLU epilogues give every 64-thread group one row
 
 __device__ __forceinline__ float sum_planes(const float *part, size_t plane, int S, size_t idx) {
     float a = 0.f;
@@ -125,35 +126,17 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
             const float up = sum_planes(part, plane, S, (size_t)r * Npad + n0 + 64 + c);
             act[(size_t)r * e.F + f] = from_f<T>(g / (1.0f + expf(-g)) * up);
         }
-    } else {    // EPI_RESIDUAL, EPI_PLAIN: 32 threads x 4 columns per row, 8 rows per sweep
+    } else {    // EPI_PLAIN: 32 threads x 4 columns per row, 8 rows per sweep
         const int c4 = (t & 31) * 4, n = n0 + c4;
-        const T *bias = static_cast<const T *>(e.bias);
         for (int rb = r_begin; rb < r_end; rb += 8) {
             const int r = rb + (t >> 5);
-            float ss = 0.f;
             if (r < r_end && n < N) {
                 const f32x4 v = sum_planes4(part, plane, S, (size_t)r * Npad + n);
                 if constexpr (EPI == EPI_PLAIN) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         if (n + j < N) e.out[(size_t)r * e.ld_out + n + j] = v[j];
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        if (n + j >= N) continue;
-                        float x = v[j];
-                        if (bias) x += to_f(bias[n + j]);
-                        if (e.residual) x += e.h[(size_t)r * N + n + j];
-                        e.h[(size_t)r * N + n + j] = x;
-                        if (e.h_copy) e.h_copy[(size_t)r * N + n + j] = x;
-                        ss += x * x;
-                    }
                 }
-            }
-            if constexpr (EPI == EPI_RESIDUAL) {
-#pragma unroll
-                for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-                if ((t & 31) == 0 && r < r_end) e.ss[(size_t)r * e.ss_ld + tile] = ss;
             }
         }
     }
@@ -279,6 +262,50 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// Residual epilogue, one workgroup per row: h = sum of planes (+ bias) (+ h); then, because the
+// whole row is in this workgroup, the RMSNorm that feeds the next GEMM right away:
+// u = T(h / sqrt(mean(h^2) + eps) * gain).  Saves a kernel per norm.
+template <typename T>
+__global__ __launch_bounds__(1024) void epilogue_residual_norm_kernel(const float *__restrict__ part, size_t plane, int S,
+                                                                      int Npad, int N, float eps, EpiArgs e) {
+    __shared__ float red[17];
+    constexpr int MAXIT = 4;                               // N <= 4 * 4 * 1024
+    const int m = blockIdx.x;
+    const T *bias = static_cast<const T *>(e.bias), *gain = static_cast<const T *>(e.gain);
+    T *u = static_cast<T *>(e.u);
+    f32x4 x[MAXIT];
+    float ss = 0.f;
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it) {
+        const int n = (it * (int)blockDim.x + (int)threadIdx.x) * 4;
+        x[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (n < N) {
+            f32x4 v = sum_planes4(part, plane, S, (size_t)m * Npad + n);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (n + j >= N) { v[j] = 0.f; continue; }
+                if (bias) v[j] += to_f(bias[n + j]);
+                if (e.residual) v[j] += e.h[(size_t)m * N + n + j];
+                e.h[(size_t)m * N + n + j] = v[j];
+                if (e.h_copy) e.h_copy[(size_t)m * N + n + j] = v[j];
+                ss += v[j] * v[j];
+            }
+            x[it] = v;
+        }
+    }
+    if (!gain) return;
+    ss = block_sum(ss, red);
+    const float rs = 1.0f / sqrtf(ss / (float)N + eps);
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it) {
+        const int n = (it * (int)blockDim.x + (int)threadIdx.x) * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (n + j < N) u[(size_t)m * N + n + j] = from_f<T>(x[it][j] * rs * to_f(gain[n + j]));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // float32 storage (reference-precision mode of the small test shape): plain FMA loop, weights
 // kept row-major, one thread per output element, k ascending.
 __global__ void gemm_f32_kernel(const float *__restrict__ W, const float *__restrict__ X, int ldx,
@@ -299,8 +326,9 @@ __global__ void gemm_f32_kernel(const float *__restrict__ W, const float *__rest
 template <typename T, int EPI>
 __global__ __launch_bounds__(256) void epilogue_kernel(const float *__restrict__ part, size_t plane, int S, int Npad,
                                                        int N, int M, EpiArgs epi) {
-    const int r0 = blockIdx.y * EPI_ROWS;
-    tile_epilogue<T, EPI>(part, plane, S, Npad, N, r0, min(M, r0 + EPI_ROWS), blockIdx.x, epi);
+    constexpr int ROWS = EPI == EPI_PLAIN ? EPI_ROWS_PLAIN : EPI_ROWS_PAIR;
+    const int r0 = blockIdx.y * ROWS;
+    tile_epilogue<T, EPI>(part, plane, S, Npad, N, r0, min(M, r0 + ROWS), blockIdx.x, epi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -331,29 +359,35 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
 }
 
 template <typename T>
-static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiArgs &epi, hipStream_t st) {
+static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiArgs &epi, float eps, hipStream_t st) {
     const size_t plane = (size_t)g.Mpad * g.Npad;
-    dim3 eg(g.Npad / GEMM_BLOCK_N, (g.M + EPI_ROWS - 1) / EPI_ROWS), eb(256);
+    const int tiles = g.Npad / GEMM_BLOCK_N;
+    dim3 pair_grid(tiles, (g.M + EPI_ROWS_PAIR - 1) / EPI_ROWS_PAIR), plain_grid(tiles, (g.M + EPI_ROWS_PLAIN - 1) / EPI_ROWS_PLAIN);
+    dim3 eb(256);
     switch (epi.mode) {
         case EPI_ROPE_KV:
-            hipLaunchKernelGGL((epilogue_kernel<T, EPI_ROPE_KV>), eg, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+            hipLaunchKernelGGL((epilogue_kernel<T, EPI_ROPE_KV>), pair_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
             break;
-        case EPI_RESIDUAL:
-            hipLaunchKernelGGL((epilogue_kernel<T, EPI_RESIDUAL>), eg, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+        case EPI_RESIDUAL: {
+            int threads = round_up((g.N + 3) / 4, 64);
+            if (threads > 1024) threads = 1024;
+            hipLaunchKernelGGL((epilogue_residual_norm_kernel<T>), dim3(g.M), dim3(threads), 0, st, part, plane, g.S, g.Npad,
+                               g.N, eps, epi);
             break;
+        }
         case EPI_SILU:
-            hipLaunchKernelGGL((epilogue_kernel<T, EPI_SILU>), eg, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+            hipLaunchKernelGGL((epilogue_kernel<T, EPI_SILU>), pair_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
             break;
         default:
             if (g.S > 1 || epi.out)     // S == 1 without an output buffer: plane 0 is the result
-                hipLaunchKernelGGL((epilogue_kernel<T, EPI_PLAIN>), eg, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+                hipLaunchKernelGGL((epilogue_kernel<T, EPI_PLAIN>), plain_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
             break;
     }
 }
 
 template <typename T>
 static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                          const EpiArgs &epi, hipStream_t st) {
+                          const EpiArgs &epi, float eps, hipStream_t st) {
     // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
     const bool wide = g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
     const int wpb = wide ? 8 : 4;
@@ -378,20 +412,20 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
         default: POSS_GEMM_CASE(8); break;
     }
 #undef POSS_GEMM_CASE
-    launch_epilogue_t<T>(g, part, epi, st);
+    launch_epilogue_t<T>(g, part, epi, eps, st);
 }
 
 void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 const EpiArgs &epi, hipStream_t st) {
+                 const EpiArgs &epi, float eps, hipStream_t st) {
     if (dt == DT_F32) {
         dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
         hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
                            static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
-        launch_epilogue_t<float>(g, part, epi, st);
+        launch_epilogue_t<float>(g, part, epi, eps, st);
     } else if (dt == DT_BF16) {
-        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, st);
+        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st);
     } else {
-        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, st);
+        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st);
     }
 }
 
