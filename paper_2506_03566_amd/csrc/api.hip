@@ -190,7 +190,9 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     float *logits = a.take_n<float>((size_t)R * gemm_npad(V));
     float *feats = a.take_n<float>((size_t)R * d);
     float *fhat0 = a.take_n<float>((size_t)16 * d), *fhat1 = a.take_n<float>((size_t)16 * d);
-    float *topk_scr = a.take_n<float>(topk_scratch_floats(16, V));
+    size_t scr_floats = topk_scratch_floats(16, V);
+    if (argmax_scratch_floats(R, V) > scr_floats) scr_floats = argmax_scratch_floats(R, V);
+    float *topk_scr = a.take_n<float>(scr_floats);      // shared by top-k (draft) and argmax (verify)
     void *u = a.take((size_t)R * d * es), *xin = a.take((size_t)R * 2 * d * es);
     void *q = a.take((size_t)R * qd * es), *ao = a.take((size_t)R * qd * es), *act = a.take((size_t)R * F * es);
     const int G = c.n_q_heads / c.n_kv_heads;
@@ -535,7 +537,7 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
             EpiArgs pe{};
             pe.mode = EPI_PLAIN;
             GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true, pe);
-            launch_argmax(c->logits, g.Npad, 1, md.vocab, c->argmax_dev, c->st);
+            launch_argmax(c->logits, g.Npad, 1, md.vocab, c->topk_scratch, c->argmax_dev, c->st);
             HIP_TRY(c, hipMemcpyAsync(c->tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
         }
         HIP_TRY(c, hipStreamSynchronize(c->st));          // the staging buffer is reused by the next chunk
@@ -678,7 +680,7 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     RowMeta rm{c->td.pos, c->tree_slot, c->td.mask};
     target_forward(c, n, c->td.token, rm, t, n);
     GemmShape g = run_head(c, n);
-    launch_argmax(c->logits, g.Npad, n, cf.vocab, c->argmax_dev, c->st);
+    launch_argmax(c->logits, g.Npad, n, cf.vocab, c->topk_scratch, c->argmax_dev, c->st);
     (void)hipEventRecord(c->ev1, c->st);
     if (logits_out) launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
     if (feat_out) launch_copy_rows_f32(c->feats, cf.d_model, static_cast<float *>(feat_out), cf.d_model, n, cf.d_model, c->st);

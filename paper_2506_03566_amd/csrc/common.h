@@ -105,7 +105,8 @@ void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *to
                        const void *gain, float *h, void *u, hipStream_t st);
 // cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)), angle formed in float64
 void launch_rope_table(const int32_t *pos, const double *inv_freq, int half, int rows, float2 *cs, hipStream_t st);
-void launch_argmax(const float *logits, int ld, int rows, int vocab, int32_t *out, hipStream_t st);
+size_t argmax_scratch_floats(int rows, int vocab);
+void launch_argmax(const float *logits, int ld, int rows, int vocab, float *scratch, int32_t *out, hipStream_t st);
 void launch_copy_rows_f32(const float *src, int ld_src, float *dst, int ld_dst, int rows, int cols,
                           hipStream_t st);
 

@@ -55,22 +55,45 @@ void launch_rope_table(const int32_t *pos, const double *inv_freq, int half, int
 }
 
 // ------------------------------------------------------------------ argmax per row (lowest index on ties)
-__global__ __launch_bounds__(1024) void argmax_kernel(const float *__restrict__ logits, int ld, int vocab,
-                                                      int32_t *__restrict__ out) {
+// Two stages so that a 128K-entry row is not one workgroup's serial scan: (segment, row) partial
+// winners, then one small workgroup per row over the partials.
+constexpr int ARGMAX_SEG = 4096;
+__global__ __launch_bounds__(256) void argmax_seg_kernel(const float *__restrict__ logits, int ld, int vocab, int n_seg,
+                                                         float *__restrict__ pv, int *__restrict__ pi) {
     __shared__ float red_v[17];
     __shared__ int red_i[17];
-    const float *row = logits + (size_t)blockIdx.x * ld;
+    const int seg = blockIdx.x, rowi = blockIdx.y;
+    const float *row = logits + (size_t)rowi * ld;
     float bv = -INFINITY; int bi = 0x7fffffff;
-    for (int i = threadIdx.x; i < vocab; i += blockDim.x) {
+    const int end = min(vocab, (seg + 1) * ARGMAX_SEG);
+    for (int i = seg * ARGMAX_SEG + threadIdx.x; i < end; i += blockDim.x) {
         const float v = row[i];
         if (better(v, i, bv, bi)) { bv = v; bi = i; }
     }
     block_argmax(bv, bi, red_v, red_i);
-    if (threadIdx.x == 0) out[blockIdx.x] = bi;
+    if (threadIdx.x == 0) { pv[rowi * n_seg + seg] = bv; pi[rowi * n_seg + seg] = bi; }
 }
 
-void launch_argmax(const float *logits, int ld, int rows, int vocab, int32_t *out, hipStream_t st) {
-    hipLaunchKernelGGL(argmax_kernel, dim3(rows), dim3(1024), 0, st, logits, ld, vocab, out);
+__global__ __launch_bounds__(64) void argmax_merge_kernel(const float *__restrict__ pv, const int *__restrict__ pi, int n_seg,
+                                                          int32_t *__restrict__ out) {
+    const int rowi = blockIdx.x;
+    float bv = -INFINITY; int bi = 0x7fffffff;
+    for (int s = threadIdx.x; s < n_seg; s += 64) {
+        const float v = pv[rowi * n_seg + s]; const int i = pi[rowi * n_seg + s];
+        if (better(v, i, bv, bi)) { bv = v; bi = i; }
+    }
+    wave_argmax(bv, bi);
+    if (threadIdx.x == 0) out[rowi] = bi;
+}
+
+size_t argmax_scratch_floats(int rows, int vocab) { return (size_t)2 * rows * ((vocab + ARGMAX_SEG - 1) / ARGMAX_SEG); }
+
+void launch_argmax(const float *logits, int ld, int rows, int vocab, float *scratch, int32_t *out, hipStream_t st) {
+    const int n_seg = (vocab + ARGMAX_SEG - 1) / ARGMAX_SEG;
+    float *pv = scratch;
+    int *pi = reinterpret_cast<int *>(scratch + (size_t)rows * n_seg);
+    hipLaunchKernelGGL(argmax_seg_kernel, dim3(n_seg, rows), dim3(256), 0, st, logits, ld, vocab, n_seg, pv, pi);
+    hipLaunchKernelGGL(argmax_merge_kernel, dim3(rows), dim3(64), 0, st, pv, pi, n_seg, out);
 }
 
 __global__ void copy_rows_f32_kernel(const float *__restrict__ src, int ld_src, float *__restrict__ dst, int ld_dst,

@@ -153,7 +153,6 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     constexpr int XUNITS = KCS * MT * 64;                 // 16-byte units of one staged chunk
     constexpr int XPT    = XUNITS / (WPB * 64);           // units per thread
     __shared__ u32x4 xs[2][XUNITS];
-
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int chunk0 = blockIdx.y * chunks_per_split;
     const int n_chunks_total = ksteps_total / KCS;
