@@ -278,7 +278,8 @@ void run_layer(poss_ctx *c, const LayerW &w, const KVCache &kv, int rows_all, in
     run_gemm(c, w.wo, md.d, qd, c->attn_out, qd, rows_q, c->part, false, epi_residual(c, true, nullptr, nullptr, w.mlp_norm));
     EpiArgs es{};
     es.mode = EPI_SILU; es.act = c->act; es.F = md.ffn;
-    run_gemm(c, w.wgu, gate_up_rows(md.ffn), md.d, c->u, md.d, rows_q, c->part, false, es);
+    // K unsplit: the stream kernel then applies SiLU * up itself (one tile per workgroup already fills most CUs)
+    run_gemm(c, w.wgu, gate_up_rows(md.ffn), md.d, c->u, md.d, rows_q, c->part, true, es);
     run_gemm(c, w.wdown, md.d, md.ffn, c->act, md.ffn, rows_q, c->part, false, epi_residual(c, true, nullptr, h_copy, next_gain));
 }
 

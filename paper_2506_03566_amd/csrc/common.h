@@ -52,10 +52,10 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs);
 
 struct PackSrc {
     const void *ptr[3]; int rows[3];   // up to three matrices stacked along N
-    int interleave64;                  // 1: ptr[0]/ptr[1] alternate in groups of 64 rows (gate | up per 128-column tile)
+    int interleave16;                  // 1: ptr[0]/ptr[1] alternate in groups of 16 rows (gate | up per 32-column wave tile)
 };
 void launch_pack(int dt, const PackSrc &src, int K, void *dst, hipStream_t st);
-static inline int gate_up_rows(int F) { return 2 * round_up(F, 64); }
+static inline int gate_up_rows(int F) { return 2 * round_up(F, 16); }
 
 // ---------------------------------------------------------------- KV caches
 // K  : [phys_page][Hkv][P][dh]      (row per token)
@@ -93,7 +93,8 @@ struct EpiArgs {
     // EPI_RESIDUAL: h[m][n] = sum + bias[n] + (residual ? h[m][n] : 0); h_copy likewise; then, if
     // gain != nullptr, u[m][n] = T(rmsnorm(h[m]) * gain[n]) - the operand of the next GEMM
     float *h; const void *bias; int residual; float *h_copy; const void *gain; void *u;
-    // EPI_SILU: tile j holds gate[64j..64j+63] | up[64j..64j+63]; act[m][f] = T(silu(gate) * up)
+    // EPI_SILU: columns [32j, 32j+16) hold gate[16j..16j+15], the next 16 up[16j..16j+15], so one MFMA lane
+    // owns both factors of act[m][f] = T(silu(gate) * up); with S == 1 the stream kernel writes act itself
     void *act; int F;
 };
 // part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.

@@ -118,12 +118,12 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
             }
         }
     } else if constexpr (EPI == EPI_SILU) {
-        const int c = t & 63, f = tile * 64 + c;
+        const int c = t & 63, f = tile * 64 + c, cg = n0 + (c >> 4) * 32 + (c & 15);   // gate column; up is 16 further
         if (f >= e.F) return;
         T *act = static_cast<T *>(e.act);
         for (int r = r_begin + (t >> 6); r < r_end; r += 4) {
-            const float g = sum_planes(part, plane, S, (size_t)r * Npad + n0 + c);
-            const float up = sum_planes(part, plane, S, (size_t)r * Npad + n0 + 64 + c);
+            const float g = sum_planes(part, plane, S, (size_t)r * Npad + cg);
+            const float up = sum_planes(part, plane, S, (size_t)r * Npad + cg + 16);
             act[(size_t)r * e.F + f] = from_f<T>(g / (1.0f + expf(-g)) * up);
         }
     } else {    // EPI_PLAIN: 32 threads x 4 columns per row, 8 rows per sweep
@@ -145,10 +145,12 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
 // ------------------------------------------------------------------------------------------
 // WPB waves per workgroup: 4 (one 128-column tile) or 8 (two tiles sharing one staged activation
 // slice: halves the L2 traffic per weight byte; used where N alone fills the GPU).
-template <typename T, int MT, int WPB>
+// FUSE_SILU (K not split, gate/up interleaved per wave tile): the kernel applies SiLU(gate) * up to its
+// accumulators and writes the activation act[M][F] itself; no partial plane, no epilogue kernel.
+template <typename T, int MT, int WPB, bool FUSE_SILU>
 __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
-    int M, int K, int Npad, int ksteps_total, int chunks_per_split) {
+    int M, int K, int Npad, int ksteps_total, int chunks_per_split, T *__restrict__ act, int F) {
     static_assert(KCS % PF == 0, "ring index must be static");
     constexpr int XUNITS = KCS * MT * 64;                 // 16-byte units of one staged chunk
     constexpr int XPT    = XUNITS / (WPB * 64);           // units per thread
@@ -247,6 +249,21 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     chunk_body(std::false_type{}, chunk1 - 1);
 
     // D tile: lane -> column n = lane % 16, register r -> row m = 4 * (lane / 16) + r
+    if constexpr (FUSE_SILU) {
+        static_assert(GEMM_NT == 2, "gate and up are the two column tiles of a wave");
+        const int f = ngroup * 16 + (lane & 15);
+        if (f < F) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = mt * 16 + 4 * (lane >> 4) + r;
+                    const float g = acc[mt][0][r], up = acc[mt][1][r];
+                    if (m < M) act[(size_t)m * F + f] = from_f<T>(g / (1.0f + expf(-g)) * up);
+                }
+        }
+        return;
+    }
     float *out = part + (size_t)blockIdx.y * (MT * 16) * Npad;
     const int n0 = ngroup * (GEMM_NT * 16) + (lane & 15);
 #pragma unroll
@@ -358,7 +375,8 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
 }
 
 template <typename T>
-static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiArgs &epi, float eps, hipStream_t st) {
+static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiArgs &epi, float eps, bool silu_done,
+                              hipStream_t st) {
     const size_t plane = (size_t)g.Mpad * g.Npad;
     const int tiles = g.Npad / GEMM_BLOCK_N;
     dim3 pair_grid(tiles, (g.M + EPI_ROWS_PAIR - 1) / EPI_ROWS_PAIR), plain_grid(tiles, (g.M + EPI_ROWS_PLAIN - 1) / EPI_ROWS_PLAIN);
@@ -375,6 +393,7 @@ static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiAr
             break;
         }
         case EPI_SILU:
+            if (silu_done) break;       // applied inside the stream kernel
             hipLaunchKernelGGL((epilogue_kernel<T, EPI_SILU>), pair_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
             break;
         default:
@@ -388,20 +407,25 @@ template <typename T>
 static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
                           const EpiArgs &epi, float eps, hipStream_t st) {
     // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
-    const bool wide = g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
+    const bool fuse_silu = epi.mode == EPI_SILU && g.S == 1;
+    const bool wide = !fuse_silu && g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
     const int wpb = wide ? 8 : 4;
     dim3 grid(g.Npad / (GEMM_NT * 16 * wpb), g.S), block(wpb * 64);
     const int ksteps = g.Kpad / GEMM_KSTEP;
     const u32x4 *w = static_cast<const u32x4 *>(Wp);
     const T *x = static_cast<const T *>(X);
+    T *act = static_cast<T *>(epi.act);
 #define POSS_GEMM_CASE(MT)                                                                                    \
     do {                                                                                                      \
-        if (wide)                                                                                             \
-            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 8>), grid, block, 0, st, w, x, ldx, part, g.M, g.K,    \
-                               g.Npad, ksteps, g.chunks_per_split);                                           \
+        if (fuse_silu)                                                                                        \
+            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 4, true>), grid, block, 0, st, w, x, ldx, part, g.M,   \
+                               g.K, g.Npad, ksteps, g.chunks_per_split, act, epi.F);                          \
+        else if (wide)                                                                                        \
+            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 8, false>), grid, block, 0, st, w, x, ldx, part, g.M,  \
+                               g.K, g.Npad, ksteps, g.chunks_per_split, act, 0);                              \
         else                                                                                                  \
-            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 4>), grid, block, 0, st, w, x, ldx, part, g.M, g.K,    \
-                               g.Npad, ksteps, g.chunks_per_split);                                           \
+            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 4, false>), grid, block, 0, st, w, x, ldx, part, g.M,  \
+                               g.K, g.Npad, ksteps, g.chunks_per_split, act, 0);                              \
     } while (0)
     switch (g.Mpad / 16) {
         case 1: POSS_GEMM_CASE(1); break;
@@ -411,7 +435,7 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
         default: POSS_GEMM_CASE(8); break;
     }
 #undef POSS_GEMM_CASE
-    launch_epilogue_t<T>(g, part, epi, eps, st);
+    launch_epilogue_t<T>(g, part, epi, eps, fuse_silu, st);
 }
 
 void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
@@ -420,7 +444,7 @@ void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int 
         dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
         hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
                            static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
-        launch_epilogue_t<float>(g, part, epi, eps, st);
+        launch_epilogue_t<float>(g, part, epi, eps, false, st);
     } else if (dt == DT_BF16) {
         launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st);
     } else {
@@ -432,9 +456,9 @@ void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int 
 // Repack row-major [rows_i, K] matrices, stacked along N (or gate/up interleaved in groups of 64
 // rows), into B-operand order.
 __device__ __forceinline__ bool pack_source_row(const PackSrc &src, int n, int &which, int &row) {
-    if (src.interleave64) {          // tile of 128 rows = 64 rows of matrix 0, then 64 rows of matrix 1
-        const int w = n & 127;
-        which = w >> 6; row = (n >> 7) * 64 + (w & 63);
+    if (src.interleave16) {          // 32 rows = 16 rows of matrix 0, then the same 16 rows of matrix 1
+        const int w = n & 31;
+        which = w >> 4; row = (n >> 5) * 16 + (w & 15);
         return row < src.rows[which];
     }
     for (which = 0; which < 3; ++which) {
@@ -472,7 +496,7 @@ __global__ void pack32_kernel(PackSrc src, int K, int Npad, float *__restrict__ 
 }
 
 void launch_pack(int dt, const PackSrc &src, int K, void *dst, hipStream_t st) {
-    const int N = src.interleave64 ? gate_up_rows(src.rows[0]) : src.rows[0] + src.rows[1] + src.rows[2];
+    const int N = src.interleave16 ? gate_up_rows(src.rows[0]) : src.rows[0] + src.rows[1] + src.rows[2];
     const int Npad = gemm_npad(N), Kpad = gemm_kpad(dt, K);
     if (dt == DT_F32) {
         const size_t total = (size_t)Npad * K;
