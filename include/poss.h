@@ -125,14 +125,18 @@ int poss_prefill(poss_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t
 
 /* Draft phase (section 6.2): `depth` specialist passes expand the tree level by level; the
  * total_tokens best candidates by cumulative log-probability form the tree.  out (HOST, may be
- * NULL) receives it; it also stays on the device for poss_verify_tree(ctx, NULL, ..). */
+ * NULL) receives it; it also stays on the device for poss_verify_tree(ctx, NULL, ..).  With
+ * out == NULL the call returns once the work is queued on the stream (no host wait); a device
+ * error then surfaces at the next call that waits. */
 int poss_draft_tree(poss_ctx *ctx, poss_tree *out);
 
 /* Verification phase (section 2.1): one target pass over all tree rows with tree position ids
  * and the ancestor mask.  tree: HOST, or NULL for the tree drafted last.  argmax_out (HOST,
  * int32[n_nodes], may be NULL): the target's greedy token after each node, lowest id on ties.
  * logits_out (DEVICE float32 [n_nodes, vocab], may be NULL) and feat_out (DEVICE float32
- * [n_nodes, d_model], may be NULL) receive Head(f) and f of every row (Eq. 6). */
+ * [n_nodes, d_model], may be NULL) receive Head(f) and f of every row (Eq. 6).  With tree and all
+ * three outputs NULL the call returns once the work is queued (no host wait), so that a round
+ * draft -> verify -> accept waits for the device once, in poss_accept_and_commit. */
 int poss_verify_tree(poss_ctx *ctx, const poss_tree *tree, int32_t *argmax_out,
                      void *logits_out, void *feat_out);
 
@@ -145,6 +149,7 @@ int poss_verify_tree(poss_ctx *ctx, const poss_tree *tree, int32_t *argmax_out,
 int poss_accept_and_commit(poss_ctx *ctx, int32_t *path_idx_out, int32_t *n_accepted_out,
                            int32_t *committed_out, int32_t *n_committed_out);
 
+/* Waits for queued work, then copies the statistics. */
 int poss_get_stats(poss_ctx *ctx, poss_stats *out);
 /* Number of committed tokens (prompt included); tokens_out (HOST, may be NULL) of capacity cap. */
 int poss_get_tokens(poss_ctx *ctx, int32_t *tokens_out, int32_t cap, int32_t *n_out);

@@ -73,7 +73,8 @@ struct poss_ctx {
     std::vector<int> spec_len, spec_tmp_depth;
     poss_stats stats;
     void *pinned; size_t pinned_bytes;
-    hipEvent_t ev0, ev1;
+    hipEvent_t ev[6];                  // begin/end of the draft, verify and commit phases
+    bool ev_pending[3];                // phase recorded, elapsed time not yet added to the statistics
     int gemm_target_wgs, attn_keys_per_split;
     // gemm profiling
     int prof_on, prof_n;
@@ -244,9 +245,8 @@ GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int
     GemmShape g = gemm_plan(c->md.dt, M, N, K, single_split ? 1 : c->gemm_target_wgs);
     const bool prof = c->prof_on && c->prof_n < PROFILE_EVENTS;
     if (prof) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->st);
-    launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st);
+    launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st, prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr);
     if (prof) {
-        (void)hipEventRecord(c->prof_ev[2 * c->prof_n + 1], c->st);
         ++c->prof_n;
         c->prof_bytes += (double)N * K * dtype_size(c->md.dt);
     }
@@ -486,8 +486,8 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
         for (int l = 0; l < cfg->n_layers; ++l) kvh[l] = c->target_kv[l];
         LOAD_TRY(hipMemcpyAsync(c->target_kv_dev, kvh, cfg->n_layers * sizeof(KVCache), hipMemcpyHostToDevice, c->st));
     }
-    LOAD_TRY(hipEventCreate(&c->ev0));
-    LOAD_TRY(hipEventCreate(&c->ev1));
+    for (int i = 0; i < 6; ++i) LOAD_TRY(hipEventCreate(&c->ev[i]));
+    c->ev_pending[0] = c->ev_pending[1] = c->ev_pending[2] = false;
     for (int i = 0; i < 2 * PROFILE_EVENTS; ++i) LOAD_TRY(hipEventCreate(&c->prof_ev[i]));
     LOAD_TRY(hipStreamSynchronize(c->st));
     LOAD_TRY(hipGetLastError());
@@ -499,6 +499,8 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
 
 int poss_reset(poss_ctx *c) {
     if (!c) return POSS_E_INVALID_ARG;
+    (void)hipStreamSynchronize(c->st);
+    c->ev_pending[0] = c->ev_pending[1] = c->ev_pending[2] = false;
     reset_sequence(c);
     return POSS_OK;
 }
@@ -506,8 +508,7 @@ int poss_reset(poss_ctx *c) {
 void poss_free(poss_ctx *c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->st);
-    (void)hipEventDestroy(c->ev0);
-    (void)hipEventDestroy(c->ev1);
+    for (int i = 0; i < 6; ++i) (void)hipEventDestroy(c->ev[i]);
     for (int i = 0; i < 2 * PROFILE_EVENTS; ++i) (void)hipEventDestroy(c->prof_ev[i]);
     (void)hipHostFree(c->pinned);
     delete c;
@@ -556,6 +557,21 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
     return POSS_OK;
 }
 
+// Wait for the stream; then add the elapsed time of every phase recorded since the last wait to the
+// statistics (draft, verify, commit: event pairs 0/1, 2/3, 4/5).
+static int sync_and_harvest(poss_ctx *c) {
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    HIP_TRY(c, hipGetLastError());
+    double *acc[3] = {&c->stats.ms_draft, &c->stats.ms_verify, &c->stats.ms_commit};
+    for (int i = 0; i < 3; ++i) {
+        if (!c->ev_pending[i]) continue;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->ev[2 * i], c->ev[2 * i + 1]) == hipSuccess) *acc[i] += ms;
+        c->ev_pending[i] = false;
+    }
+    return POSS_OK;
+}
+
 int poss_draft_tree(poss_ctx *c, poss_tree *out) {
     if (!c) return POSS_E_INVALID_ARG;
     if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_draft_tree: needs a prefilled context with no pending verification");
@@ -563,7 +579,8 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
     const int t = c->t, k = cf.top_k, L = cf.depth;
     if (t + cf.total_tokens + 1 > c->cache_slots || t + L + 1 > cf.max_seq)
         return fail(c, POSS_E_CAPACITY, "poss_draft_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
-    (void)hipEventRecord(c->ev0, c->st);
+    if (c->ev_pending[0]) { int rc = sync_and_harvest(c); if (rc) return rc; }   // a re-draft: keep the first one's time
+    (void)hipEventRecord(c->ev[0], c->st);
     for (int s = 0; s < cf.n_specialists; ++s) {
         c->spec_tmp_depth[s] = 0;
         if (t - 1 - c->spec_len[s] > L) spec_catchup(c, s, t - 1);      // only after caller-supplied trees
@@ -597,16 +614,16 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
         c->spec_tmp_depth[s] = d - 1;
     }
     launch_tree_finalize(c->td, k, L, cf.total_tokens, t, c->tokens_dev, c->st);
-    (void)hipEventRecord(c->ev1, c->st);
+    (void)hipEventRecord(c->ev[1], c->st);
+    c->ev_pending[0] = true;
     const int pool = k + (L - 1) * k * k;
     c->tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
     c->tree_ready = 1;
-    if (out) { int rc = copy_tree_out(c, out); if (rc) return rc; }
-    HIP_TRY(c, hipStreamSynchronize(c->st));
     HIP_TRY(c, hipGetLastError());
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) c->stats.ms_draft += ms;
-    return POSS_OK;
+    if (!out) return POSS_OK;                    // nothing for the host: the work stays queued
+    int rc = copy_tree_out(c, out);
+    if (rc) return rc;
+    return sync_and_harvest(c);
 }
 
 int poss_debug_build_tree(poss_ctx *c, const int32_t *ids, const float *logp, poss_tree *out) {
@@ -663,7 +680,7 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     }
     if (t + n > c->cache_slots || t + cf.depth + 1 > cf.max_seq)
         return fail(c, POSS_E_CAPACITY, "poss_verify_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
-    (void)hipEventRecord(c->ev0, c->st);
+    (void)hipEventRecord(c->ev[2], c->st);
     if (tree) {
         int32_t *stage = static_cast<int32_t *>(c->pinned);
         memcpy(stage, tree->token, n * sizeof(int32_t));
@@ -682,16 +699,15 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     target_forward(c, n, c->td.token, rm, t, n);
     GemmShape g = run_head(c, n);
     launch_argmax(c->logits, g.Npad, n, cf.vocab, c->topk_scratch, c->argmax_dev, c->st);
-    (void)hipEventRecord(c->ev1, c->st);
+    (void)hipEventRecord(c->ev[3], c->st);
+    c->ev_pending[1] = true;
     if (logits_out) launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
     if (feat_out) launch_copy_rows_f32(c->feats, cf.d_model, static_cast<float *>(feat_out), cf.d_model, n, cf.d_model, c->st);
-    if (argmax_out) HIP_TRY(c, hipMemcpyAsync(argmax_out, c->argmax_dev, n * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
-    HIP_TRY(c, hipStreamSynchronize(c->st));
     HIP_TRY(c, hipGetLastError());
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) c->stats.ms_verify += ms;
     c->state = ST_VERIFIED;
-    return POSS_OK;
+    if (!argmax_out && !logits_out && !feat_out && !tree) return POSS_OK;     // nothing to hand over: stay queued
+    if (argmax_out) HIP_TRY(c, hipMemcpyAsync(argmax_out, c->argmax_dev, n * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
+    return sync_and_harvest(c);
 }
 
 int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accepted_out, int32_t *committed_out,
@@ -700,17 +716,17 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
     if (c->state != ST_VERIFIED) return fail(c, POSS_E_BAD_STATE, "poss_accept_and_commit: no verified tree");
     const poss_config &cf = c->cfg;
     const int t = c->t, L = cf.depth;
-    (void)hipEventRecord(c->ev0, c->st);
+    (void)hipEventRecord(c->ev[4], c->st);
     launch_accept_walk(c->td.token, c->td.parent, c->argmax_dev, c->td.n_nodes, L, c->walk_dev, c->st);
     launch_commit(c->md, cf.n_layers, c->target_kv_dev, c->walk_dev, L, t, c->feats, c->feat_stash, c->tokens_dev,
                   c->td.token, c->st);
-    (void)hipEventRecord(c->ev1, c->st);
+    (void)hipEventRecord(c->ev[5], c->st);
+    c->ev_pending[2] = true;
     int32_t *walk = static_cast<int32_t *>(c->pinned);
     int32_t *toks = walk + 32;
     HIP_TRY(c, hipMemcpyAsync(walk, c->walk_dev, (L + 3) * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
     HIP_TRY(c, hipMemcpyAsync(toks, c->tokens_dev + t + 1, (L + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
-    HIP_TRY(c, hipStreamSynchronize(c->st));
-    HIP_TRY(c, hipGetLastError());
+    { int rc = sync_and_harvest(c); if (rc) return rc; }
     const int m = walk[0];
     if (m < 0 || m > L) return fail(c, POSS_E_HIP, "poss_accept_and_commit: walk returned %d accepted tokens", m);
     for (int j = 0; j <= m; ++j) c->tokens.push_back(toks[j]);
@@ -718,8 +734,6 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
     c->stats.rounds += 1;
     c->stats.committed_tokens += m + 1;
     for (int i = 1; i <= m; ++i) c->stats.c[i] += 1;
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, c->ev0, c->ev1) == hipSuccess) c->stats.ms_commit += ms;
     if (path_idx_out) for (int j = 0; j <= m; ++j) path_idx_out[j] = walk[2 + j];
     if (n_accepted_out) *n_accepted_out = m;
     if (committed_out) for (int j = 0; j <= m; ++j) committed_out[j] = toks[j];
@@ -730,6 +744,7 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
 
 int poss_get_stats(poss_ctx *c, poss_stats *out) {
     if (!c || !out) return POSS_E_INVALID_ARG;
+    { int rc = sync_and_harvest(c); if (rc) return rc; }
     *out = c->stats;
     return POSS_OK;
 }

@@ -336,20 +336,20 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float *__restrict__ 
     }
 }
 
-// Number of key splits.  One workgroup pulls keys and values at a few tens of GB/s at most, so a short
-// context is still cut into pieces of >= 4 blocks until about 128 workgroups are in flight (the merge
-// kernel costs less than the serial walk it replaces); long contexts walk 32 blocks per workgroup.
-// keys_per_split > 0 overrides.
-static int choose_splits(int n_blocks, int base_wgs, int keys_per_split) {
-    if (keys_per_split > 0) {
-        int bps = keys_per_split / 32; if (bps < 1) bps = 1;
-        return (n_blocks + bps - 1) / bps;
-    }
-    const int fill = (128 + base_wgs - 1) / base_wgs;
-    int bps = (n_blocks + fill - 1) / fill;
+// Blocks of 32 keys per split.  One workgroup pulls keys and values at a few tens of GB/s at most, so a
+// short context is still cut into about four pieces of >= 4 blocks (the merge kernel costs less than the
+// serial walk it replaces); long contexts walk 32 blocks per workgroup.  The rule looks at the committed
+// prefix only, never at the number of rows or the size of the tree region: a row's arithmetic (which keys
+// meet in which split, in which order) is then the same whether it is verified alone or among 60 others,
+// which is what makes the speculative stream reproduce the one-token-at-a-time stream bit for bit as long
+// as only bonus tokens are committed.  keys_per_split > 0 overrides.
+static int blocks_per_split(int n_prefix, int keys_per_split) {
+    if (keys_per_split > 0) return keys_per_split >= 32 ? keys_per_split / 32 : 1;
+    const int prefix_blocks = (n_prefix + 31) / 32;
+    int bps = (prefix_blocks + 3) / 4;
     if (bps < 4) bps = 4;
     if (bps > 32) bps = 32;
-    return (n_blocks + bps - 1) / bps;
+    return bps;
 }
 
 template <typename T>
@@ -359,8 +359,8 @@ static void launch_attention_t(const ModelDims &md, const void *q, int rows, con
     const int G = md.hq / md.hkv;
     const int tiles = (rows * G + 15) / 16, rho_pad = tiles * 16;
     const int n_blocks = (n_prefix + region_len + 31) / 32;
-    const int n_splits = choose_splits(n_blocks, ((tiles + 3) / 4) * md.hkv, keys_per_split);
-    const int bps = (n_blocks + n_splits - 1) / n_splits;
+    const int bps = blocks_per_split(n_prefix, keys_per_split);
+    const int n_splits = (n_blocks + bps - 1) / bps;
     const float scale = 1.4426950408889634f / sqrtf((float)md.dh);     // log2(e) / sqrt(dh): scores in the log2 domain
     dim3 grid((tiles + 3) / 4, md.hkv, n_splits);
     T *direct = n_splits == 1 ? static_cast<T *>(out) : nullptr;

@@ -97,9 +97,10 @@ struct EpiArgs {
     // owns both factors of act[m][f] = T(silu(gate) * up); with S == 1 the stream kernel writes act itself
     void *act; int F;
 };
-// part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.
+// part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.  after_stream, if given, is
+// recorded between the weight-streaming kernel and its epilogue kernel (per-launch timing).
 void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 const EpiArgs &epi, float rms_eps, hipStream_t st);
+                 const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t after_stream = nullptr);
 
 // ---------------------------------------------------------------- launchers: elementwise
 void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *tokens, int rows,

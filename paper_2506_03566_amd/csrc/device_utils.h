@@ -22,16 +22,12 @@ __device__ __forceinline__ float wave_max(float v) {
 __device__ __forceinline__ float block_sum(float v, float *red /* >= 17 floats of LDS */) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
     v = wave_sum(v);
-    __syncthreads();
+    __syncthreads();                      // red may still be read from an earlier call
     if (lane == 0) red[wave] = v;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        float s = 0.f;
-        for (int i = 0; i < nw; ++i) s += red[i];
-        red[16] = s;
-    }
-    __syncthreads();
-    return red[16];
+    float s = 0.f;
+    for (int i = 0; i < nw; ++i) s += red[i];
+    return s;
 }
 
 // (value, index) ordering used by every argmax / top-k here: larger value first, then lower index.

@@ -100,19 +100,20 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
         T *kc = static_cast<T *>(e.kv.k), *vc = static_cast<T *>(e.kv.vt), *q = static_cast<T *>(e.q);
         for (int r = r_begin + (t >> 6); r < r_end; r += 4) {
             if (gh < e.hq && r >= e.rows_q) continue;
+            const float2 cs = e.cs[r * half + i];          // requested together with the planes
+            const int sl = e.slot[r];
             const float x1 = sum_planes(part, plane, S, (size_t)r * Npad + hb + i);
             const float x2 = sum_planes(part, plane, S, (size_t)r * Npad + hb + i + half);
-            const float2 cs = e.cs[r * half + i];
             if (gh < e.hq) {
                 T *dst = q + ((size_t)r * e.hq + gh) * e.dh;
                 dst[i] = from_f<T>(x1 * cs.x - x2 * cs.y);
                 dst[i + half] = from_f<T>(x2 * cs.x + x1 * cs.y);
             } else if (gh < e.hq + e.hkv) {
-                T *dst = kc + k_offset(e.kv, e.slot[r], gh - e.hq, e.hkv, e.dh);
+                T *dst = kc + k_offset(e.kv, sl, gh - e.hq, e.hkv, e.dh);
                 dst[i] = from_f<T>(x1 * cs.x - x2 * cs.y);
                 dst[i + half] = from_f<T>(x2 * cs.x + x1 * cs.y);
             } else {
-                const int vh = gh - e.hq - e.hkv, sl = e.slot[r];
+                const int vh = gh - e.hq - e.hkv;
                 vc[vt_offset(e.kv, sl, vh, e.hkv, e.dh, i)] = from_f<T>(x1);
                 vc[vt_offset(e.kv, sl, vh, e.hkv, e.dh, i + half)] = from_f<T>(x2);
             }
@@ -289,21 +290,31 @@ __global__ __launch_bounds__(1024) void epilogue_residual_norm_kernel(const floa
     const int m = blockIdx.x;
     const T *bias = static_cast<const T *>(e.bias), *gain = static_cast<const T *>(e.gain);
     T *u = static_cast<T *>(e.u);
-    f32x4 x[MAXIT];
+    float *h = e.h + (size_t)m * N, *h_copy = e.h_copy ? e.h_copy + (size_t)m * N : nullptr;
+    f32x4 x[MAXIT], gn[MAXIT];
     float ss = 0.f;
 #pragma unroll
     for (int it = 0; it < MAXIT; ++it) {
         const int n = (it * (int)blockDim.x + (int)threadIdx.x) * 4;
         x[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+        gn[it] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (n < N) {
+            // every operand is requested before the first use: one memory round trip, not four
+            f32x4 add = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (n + j >= N) continue;
+                if (e.residual) add[j] = h[n + j];
+                if (bias) add[j] += to_f(bias[n + j]);
+                if (gain) gn[it][j] = to_f(gain[n + j]);
+            }
             f32x4 v = sum_planes4(part, plane, S, (size_t)m * Npad + n);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (n + j >= N) { v[j] = 0.f; continue; }
-                if (bias) v[j] += to_f(bias[n + j]);
-                if (e.residual) v[j] += e.h[(size_t)m * N + n + j];
-                e.h[(size_t)m * N + n + j] = v[j];
-                if (e.h_copy) e.h_copy[(size_t)m * N + n + j] = v[j];
+                v[j] += add[j];
+                h[n + j] = v[j];
+                if (h_copy) h_copy[n + j] = v[j];
                 ss += v[j] * v[j];
             }
             x[it] = v;
@@ -317,7 +328,7 @@ __global__ __launch_bounds__(1024) void epilogue_residual_norm_kernel(const floa
         const int n = (it * (int)blockDim.x + (int)threadIdx.x) * 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (n + j < N) u[(size_t)m * N + n + j] = from_f<T>(x[it][j] * rs * to_f(gain[n + j]));
+            if (n + j < N) u[(size_t)m * N + n + j] = from_f<T>(x[it][j] * rs * gn[it][j]);
     }
 }
 
@@ -405,7 +416,7 @@ static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiAr
 
 template <typename T>
 static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                          const EpiArgs &epi, float eps, hipStream_t st) {
+                          const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream) {
     // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
     const bool fuse_silu = epi.mode == EPI_SILU && g.S == 1;
     const bool wide = !fuse_silu && g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
@@ -435,20 +446,22 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
         default: POSS_GEMM_CASE(8); break;
     }
 #undef POSS_GEMM_CASE
+    if (after_stream) (void)hipEventRecord(after_stream, st);
     launch_epilogue_t<T>(g, part, epi, eps, fuse_silu, st);
 }
 
 void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 const EpiArgs &epi, float eps, hipStream_t st) {
+                 const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream) {
     if (dt == DT_F32) {
         dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
         hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
                            static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
+        if (after_stream) (void)hipEventRecord(after_stream, st);
         launch_epilogue_t<float>(g, part, epi, eps, false, st);
     } else if (dt == DT_BF16) {
-        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st);
+        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st, after_stream);
     } else {
-        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st);
+        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st, after_stream);
     }
 }
 
