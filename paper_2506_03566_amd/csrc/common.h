@@ -44,8 +44,7 @@ struct GemmShape {
     int M;          // real rows
     int N, K;       // logical sizes
     int Npad, Kpad; // padded sizes of the packed weight
-    int S;          // K splits; partial sums land in part[S][Mpad][Npad]
-    int chunks_per_split;
+    int S;          // K splits (chunks dealt out evenly); partial sums land in part[S][Mpad][Npad]
     int Mpad;       // rows of one partial plane (row stride Npad)
 };
 GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs);

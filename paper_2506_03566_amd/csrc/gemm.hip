@@ -151,15 +151,16 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
 template <typename T, int MT, int WPB, bool FUSE_SILU>
 __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
-    int M, int K, int Npad, int ksteps_total, int chunks_per_split, T *__restrict__ act, int F) {
+    int M, int K, int Npad, int ksteps_total, T *__restrict__ act, int F) {
     static_assert(KCS % PF == 0, "ring index must be static");
     constexpr int XUNITS = KCS * MT * 64;                 // 16-byte units of one staged chunk
     constexpr int XPT    = XUNITS / (WPB * 64);           // units per thread
     __shared__ u32x4 xs[2][XUNITS];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int chunk0 = blockIdx.y * chunks_per_split;
+    // split y of gridDim.y owns chunks [y * n / S, (y + 1) * n / S): sizes differ by at most one chunk
     const int n_chunks_total = ksteps_total / KCS;
-    const int chunk1 = min(n_chunks_total, chunk0 + chunks_per_split);
+    const int chunk0 = (int)blockIdx.y * n_chunks_total / (int)gridDim.y;
+    const int chunk1 = ((int)blockIdx.y + 1) * n_chunks_total / (int)gridDim.y;
     const int ngroup = blockIdx.x * WPB + wave;
     const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCS) * (GEMM_NT * 64) + lane;
 
@@ -371,17 +372,19 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
     g.Npad = gemm_npad(N);
     g.Kpad = gemm_kpad(dt, K);
     g.Mpad = round_up(M < 1 ? 1 : M, 16);
-    if (dt == DT_F32) { g.S = 1; g.chunks_per_split = 0; return g; }
+    if (dt == DT_F32) { g.S = 1; return g; }
     g.Mpad = gemm_rows_written(g.Mpad);       // the kernel is instantiated for 1, 2, 4, 6 or 8 row tiles
     const int n_blocks = g.Npad / GEMM_BLOCK_N;
     const int n_chunks = g.Kpad / GEMM_KCHUNK;
-    if (target_wgs <= 0) target_wgs = 256;     // one workgroup per CU: more splits only add partial-plane traffic
-    int S = (target_wgs + n_blocks - 1) / n_blocks;
+    // A CU streams at a fixed rate however many workgroups it holds, so a launch takes as long as its
+    // busiest CU: at most one workgroup per CU (256), as many as fit, chunks dealt out evenly.  More
+    // splits only add partial-plane traffic.
+    if (target_wgs <= 0) target_wgs = 256;
+    int S = target_wgs / n_blocks;
     int max_s = n_chunks / 2; if (max_s < 1) max_s = 1;          // at least 512 of K per split
     if (S > max_s) S = max_s;
     if (S < 1) S = 1;
-    g.chunks_per_split = (n_chunks + S - 1) / S;
-    g.S = (n_chunks + g.chunks_per_split - 1) / g.chunks_per_split;
+    g.S = S;
     return g;
 }
 
@@ -430,13 +433,13 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     do {                                                                                                      \
         if (fuse_silu)                                                                                        \
             hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 4, true>), grid, block, 0, st, w, x, ldx, part, g.M,   \
-                               g.K, g.Npad, ksteps, g.chunks_per_split, act, epi.F);                          \
+                               g.K, g.Npad, ksteps, act, epi.F);                                        \
         else if (wide)                                                                                        \
             hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 8, false>), grid, block, 0, st, w, x, ldx, part, g.M,  \
-                               g.K, g.Npad, ksteps, g.chunks_per_split, act, 0);                              \
+                               g.K, g.Npad, ksteps, act, 0);                                            \
         else                                                                                                  \
             hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 4, false>), grid, block, 0, st, w, x, ldx, part, g.M,  \
-                               g.K, g.Npad, ksteps, g.chunks_per_split, act, 0);                              \
+                               g.K, g.Npad, ksteps, act, 0);                                            \
     } while (0)
     switch (g.Mpad / 16) {
         case 1: POSS_GEMM_CASE(1); break;
