@@ -44,18 +44,19 @@ __device__ __forceinline__ bool slot_visible(int slot, int n_prefix, int region_
     return ((j < 64 ? m0 >> j : m1 >> (j - 64)) & 1ull) != 0;
 }
 
-// One workgroup = 4 waves = 4 tiles of 16 query rows of ONE KV head, over the key blocks of one
-// split.  Key / value blocks (32 slots) go global -> registers -> LDS one block ahead of the
+// One workgroup = 4 waves x RT tiles of 16 query rows of ONE KV head (times KW key-ways), over the key
+// blocks of one split.  RT = 2 halves the LDS operand reads per MFMA (every key / value fragment
+// feeds two row tiles): long contexts are bound by exactly those reads.  Key / value blocks (32 slots) go global -> registers -> LDS one block ahead of the
 // arithmetic and are shared by the four waves.  LDS layouts: K rows padded to DH+8 elements (row
 // stride 272 B: conflict-free 16-byte operand reads); V^T rows hold their 32 keys permuted so that
 // the 8 keys a lane contracts (4 of each 16-key half) are one 16-byte chunk.
 // With a single split the result is normalised and written in the storage type directly;
 // otherwise (max, sum, O) partials go to the merge kernel.
-template <typename T, int DH, int KW>
+template <typename T, int DH, int KW, int RT>
 __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     const T *__restrict__ q, int rows, int hq, int hkv, const uint64_t *__restrict__ mask, int n_prefix,
-    int region_len, KVCache kv, int blocks_per_split, float scale, float *__restrict__ o_part,
-    float *__restrict__ ml_part, int rho_pad, T *__restrict__ out_direct) {
+    int region_len, KVCache kv, int blocks_per_split, int n_splits, int n_row_groups, float scale,
+    float *__restrict__ o_part, float *__restrict__ ml_part, int rho_pad, T *__restrict__ out_direct) {
     typedef typename Vec8<T>::type V8;
     constexpr int KS = DH / 32, DT = DH / 16;
     constexpr int KROW = DH + 8;                          // padded K row, elements
@@ -69,20 +70,33 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
     const int kway = wave >> 2;                           // which of the KW blocks of an iteration this wave takes
     const int stage_blk = tid >> 8, stid = tid & 255;     // staging: 256 threads per block
-    const int G = hq / hkv, kvh = blockIdx.y, split = blockIdx.z;
-    const int tile = blockIdx.x * 4 + (wave & 3);
-    const int rho = tile * 16 + lr;
-    const bool valid = rho < rows * G;
-    const int m = valid ? rho / G : 0, qh = kvh * G + (valid ? rho % G : 0);
-
-    V8 qf[KS];
+    // Workgroup id -> (row group, KV head, split).  Consecutive ids go to the 8 XCDs in turn, each with an
+    // L2 of its own, so the row groups that read the same keys and values (same head and split) are given
+    // ids that are equal modulo 8: the block is fetched from memory once and then found in that L2.
+    const int n_pairs = hkv * n_splits;
+    const int xcd = blockIdx.x & 7, qid = blockIdx.x >> 3;
+    const int row_group = qid % n_row_groups, pair = (qid / n_row_groups) * 8 + xcd;
+    if (pair >= n_pairs) return;                          // padding of the last round of eight
+    const int G = hq / hkv, kvh = pair % hkv, split = pair / hkv;
+    const int tile0 = (row_group * 4 + (wave & 3)) * RT;  // this wave's tiles: tile0 .. tile0 + RT - 1
+    bool valid[RT];
+    int m[RT], qh[RT];
+    V8 qf[RT][KS];
+    uint64_t m0[RT], m1[RT];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(q + ((size_t)m * hq + qh) * DH + ks * 32 + lg * 8);
-        qf[ks] = __builtin_bit_cast(V8, valid ? v : u32x4{0u, 0u, 0u, 0u});
+    for (int rt = 0; rt < RT; ++rt) {
+        const int rho = (tile0 + rt) * 16 + lr;
+        valid[rt] = rho < rows * G;
+        m[rt] = valid[rt] ? rho / G : 0;
+        qh[rt] = kvh * G + (valid[rt] ? rho % G : 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(q + ((size_t)m[rt] * hq + qh[rt]) * DH + ks * 32 + lg * 8);
+            qf[rt][ks] = __builtin_bit_cast(V8, valid[rt] ? v : u32x4{0u, 0u, 0u, 0u});
+        }
+        m0[rt] = valid[rt] ? mask[(size_t)m[rt] * MASK_WORDS] : 0ull;
+        m1[rt] = valid[rt] ? mask[(size_t)m[rt] * MASK_WORDS + 1] : 0ull;
     }
-    const uint64_t m0 = valid ? mask[(size_t)m * MASK_WORDS] : 0ull;
-    const uint64_t m1 = valid ? mask[(size_t)m * MASK_WORDS + 1] : 0ull;
 
     const int total = n_prefix + region_len;
     const int n_blocks = (total + 31) >> 5;
@@ -94,7 +108,7 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     // of 32 keys (64 bytes each, row stride P elements)
     // ring of PFD iterations of key/value loads in flight: an iteration's arithmetic is much shorter
     // than the latency of its loads, so one block of look-ahead would leave the loop latency-bound
-    constexpr int PFD = KW >= 4 ? 1 : 2;                  // 1024-thread workgroups have 128 VGPRs per lane
+    constexpr int PFD = 2;
     u32x4 kr[PFD][KPT], vr[PFD][VPT];
     auto load_block = [&](auto slot_tag, int bfirst) {    // this thread's share of block bfirst + stage_blk
         constexpr int SLOT = decltype(slot_tag)::value;
@@ -131,10 +145,14 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
         }
     };
 
-    f32x4 acc[DT];
+    f32x4 acc[RT][DT];
+    float m_run[RT], l_run[RT];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
+    for (int rt = 0; rt < RT; ++rt) {
+        m_run[rt] = -INFINITY; l_run[rt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) acc[rt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
     auto static_for = [&](auto f) {                       // f(integral_constant<int, p>) for p < PFD
         f(std::integral_constant<int, 0>{});
@@ -155,57 +173,69 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
         if (b < b1) {                                     // wave-uniform
         const int slot0 = b << 5;
         const T *kbuf = &ks_lds[(buf * KW + kway) * KBLK], *vbuf = &vs_lds[(buf * KW + kway) * VBLK];
-        // S^T tiles: rows = keys slot0 + tt*16 + (0..15), columns = query rows of this wave
-        f32x4 s[2];
+        // S^T tiles: rows = keys slot0 + tt*16 + (0..15), columns = query rows of a tile of this wave
+        f32x4 s[RT][2];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
-            s[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) s[rt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const u32x4 kf = *reinterpret_cast<const u32x4 *>(&kbuf[(tt * 16 + lr) * KROW + ks * 32 + lg * 8]);
-                s[tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf), qf[ks], s[tt]);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    s[rt][tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf), qf[rt][ks], s[rt][tt]);
             }
         }
         // lane holds keys slot0 + tt*16 + 4*lg + r of query row lr.  Scores are kept in the log2
         // domain (scale * log2 e folded into one factor) so that the exponentials are single
         // v_exp_f32 instructions; the softmax is VALU-bound, not MFMA-bound, at these sizes.
-        float sv[8], bm = -INFINITY;
-        if (slot0 + 32 <= n_prefix) {                    // whole block inside the committed prefix
+        V8 pf[RT];
+        float alpha[RT];
+        bool rescale = false;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) { sv[j] = s[j >> 2][j & 3] * scale; bm = fmaxf(bm, sv[j]); }
-        } else {
+        for (int rt = 0; rt < RT; ++rt) {
+            float sv[8], bm = -INFINITY;
+            if (slot0 + 32 <= n_prefix) {                // whole block inside the committed prefix
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int slot = slot0 + (j >> 2) * 16 + 4 * lg + (j & 3);
-                sv[j] = slot_visible(slot, n_prefix, region_len, m0, m1) ? s[j >> 2][j & 3] * scale : -INFINITY;
-                bm = fmaxf(bm, sv[j]);
+                for (int j = 0; j < 8; ++j) { sv[j] = s[rt][j >> 2][j & 3] * scale; bm = fmaxf(bm, sv[j]); }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int slot = slot0 + (j >> 2) * 16 + 4 * lg + (j & 3);
+                    sv[j] = slot_visible(slot, n_prefix, region_len, m0[rt], m1[rt]) ? s[rt][j >> 2][j & 3] * scale : -INFINITY;
+                    bm = fmaxf(bm, sv[j]);
+                }
             }
-        }
-        bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
-        bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-        const float m_new = fmaxf(m_run, bm);
-        float alpha = 1.f, psum = 0.f;
-        V8 pf;
-        if (m_new == -INFINITY) {
+            bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+            const float m_new = fmaxf(m_run[rt], bm);
+            float psum = 0.f;
+            alpha[rt] = 1.f;
+            if (m_new == -INFINITY) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) pf[j] = (T)0.f;
-        } else {
-            alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 2^(-inf) = 0 on the first visible block
+                for (int j = 0; j < 8; ++j) pf[rt][j] = (T)0.f;
+            } else {
+                alpha[rt] = __builtin_amdgcn_exp2f(m_run[rt] - m_new);   // 2^(-inf) = 0 on the first visible block
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const T pt = from_f<T>(__builtin_amdgcn_exp2f(sv[j] - m_new));
-                pf[j] = pt;
-                psum += to_f(pt);                        // normalise by what is actually multiplied into V
+                for (int j = 0; j < 8; ++j) {
+                    const T pt = from_f<T>(__builtin_amdgcn_exp2f(sv[j] - m_new));
+                    pf[rt][j] = pt;
+                    psum += to_f(pt);                    // normalise by what is actually multiplied into V
+                }
             }
+            l_run[rt] = l_run[rt] * alpha[rt] + psum;
+            m_run[rt] = m_new;
+            rescale = rescale || __builtin_amdgcn_ballot_w64(alpha[rt] != 1.f) != 0;   // rare once the maximum has settled
         }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-        const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.f) != 0;   // rare once the maximum has settled
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            if (rescale) acc[dt] *= alpha;
             const u32x4 vf = *reinterpret_cast<const u32x4 *>(&vbuf[(dt * 16 + lr) * 32 + lg * 8]);
-            acc[dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf), pf, acc[dt]);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                if (rescale) acc[rt][dt] *= alpha[rt];
+                acc[rt][dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf), pf[rt], acc[rt][dt]);
+            }
         }
         }
         store_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, buf ^ 1);
@@ -217,61 +247,75 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
             constexpr int I = decltype(p)::value;
             if (bi + I * KW < b1) iteration(p, bi + I * KW);
         });
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        l_run[rt] += __shfl_xor(l_run[rt], 16, 64);
+        l_run[rt] += __shfl_xor(l_run[rt], 32, 64);
+    }
 
     if constexpr (KW > 1) {
         // Merge the KW partial (max, sum, O) of each row tile in key-way order: ways 1.. park theirs
-        // in LDS (the staging buffers are free after the loop's final barrier), way 0 folds them in.
-        float *xch = reinterpret_cast<float *>(lds_all);  // per (way-1, tile): 64 lanes x (DT*4 + 2) floats
+        // in LDS (the staging buffers are free after the loop's final barrier), way 0 folds them in;
+        // one tile of each wave at a time, so that the records fit the staging memory.
+        float *xch = reinterpret_cast<float *>(lds_all);  // per (way-1, wave): 64 lanes x (DT*4 + 2) floats
         constexpr int REC = DT * 4 + 2;
         static_assert((size_t)(KW - 1) * 4 * 64 * REC * sizeof(float) <= sizeof(lds_all), "merge records must fit");
         float *mine = xch + ((size_t)((kway - 1) * 4 + (wave & 3)) * 64 + lane) * REC;
-        if (kway > 0) {
-            mine[0] = m_run; mine[1] = l_run;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+        for (int rt = 0; rt < RT; ++rt) {
+            if (rt > 0) __syncthreads();                  // way 0 has read the previous tile's records
+            if (kway > 0) {
+                mine[0] = m_run[rt]; mine[1] = l_run[rt];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) mine[2 + dt * 4 + r] = acc[dt][r];
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) mine[2 + dt * 4 + r] = acc[rt][dt][r];
+            }
+            __syncthreads();
+            if (kway == 0) {
+#pragma unroll
+                for (int w = 1; w < KW; ++w) {
+                    const float *o = xch + ((size_t)((w - 1) * 4 + (wave & 3)) * 64 + lane) * REC;
+                    const float mo = o[0], lo = o[1];
+                    const float mn = fmaxf(m_run[rt], mo);
+                    if (mn == -INFINITY) continue;
+                    const float a0 = __builtin_amdgcn_exp2f(m_run[rt] - mn), a1 = __builtin_amdgcn_exp2f(mo - mn);
+                    l_run[rt] = l_run[rt] * a0 + lo * a1;
+                    m_run[rt] = mn;
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[rt][dt][r] = acc[rt][dt][r] * a0 + o[2 + dt * 4 + r] * a1;
+                }
+            }
         }
-        __syncthreads();
         if (kway > 0) return;
-#pragma unroll
-        for (int w = 1; w < KW; ++w) {
-            const float *o = xch + ((size_t)((w - 1) * 4 + (wave & 3)) * 64 + lane) * REC;
-            const float mo = o[0], lo = o[1];
-            const float mn = fmaxf(m_run, mo);
-            if (mn == -INFINITY) continue;
-            const float a0 = __builtin_amdgcn_exp2f(m_run - mn), a1 = __builtin_amdgcn_exp2f(mo - mn);
-            l_run = l_run * a0 + lo * a1;
-            m_run = mn;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[dt][r] = acc[dt][r] * a0 + o[2 + dt * 4 + r] * a1;
-        }
     }
 
     // O^T tile dt: lane -> query row lr, register r -> dh index dt*16 + 4*lg + r
-    if (out_direct) {
-        if (valid) {
-            const float inv = 1.0f / l_run;
-            T *dst = out_direct + ((size_t)m * hq + qh) * DH + 4 * lg;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        if (out_direct) {
+            if (valid[rt]) {
+                const float inv = 1.0f / l_run[rt];
+                T *dst = out_direct + ((size_t)m[rt] * hq + qh[rt]) * DH + 4 * lg;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) dst[dt * 16 + r] = from_f<T>(acc[rt][dt][r] * inv);
+            }
+            continue;
+        }
+        const int tile = tile0 + rt;
+        const size_t prow = ((size_t)split * hkv + kvh) * rho_pad + tile * 16 + lr;
+        if (tile * 16 < rho_pad) {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) dst[dt * 16 + r] = from_f<T>(acc[dt][r] * inv);
-        }
-        return;
-    }
-    const size_t prow = ((size_t)split * hkv + kvh) * rho_pad + tile * 16 + lr;
-    if (tile * 16 < rho_pad) {
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-            *reinterpret_cast<f32x4 *>(o_part + prow * DH + dt * 16 + 4 * lg) = acc[dt];
-        if (lg == 0) {
-            ml_part[prow * 2] = m_run;
-            ml_part[prow * 2 + 1] = l_run;
+                *reinterpret_cast<f32x4 *>(o_part + prow * DH + dt * 16 + 4 * lg) = acc[rt][dt];
+            if (lg == 0) {
+                ml_part[prow * 2] = m_run[rt];
+                ml_part[prow * 2 + 1] = l_run[rt];
+            }
         }
     }
 }
@@ -362,14 +406,24 @@ static void launch_attention_t(const ModelDims &md, const void *q, int rows, con
     const int bps = blocks_per_split(n_prefix, keys_per_split);
     const int n_splits = (n_blocks + bps - 1) / bps;
     const float scale = 1.4426950408889634f / sqrtf((float)md.dh);     // log2(e) / sqrt(dh): scores in the log2 domain
-    dim3 grid((tiles + 3) / 4, md.hkv, n_splits);
     T *direct = n_splits == 1 ? static_cast<T *>(out) : nullptr;
-    const int kw = bps >= 8 ? 4 : bps >= 4 ? 2 : 1;       // key-ways inside the workgroup
-#define POSS_ATTN(DH, KW)                                                                                        \
-    hipLaunchKernelGGL((attn_mfma_kernel<T, DH, KW>), grid, dim3(256 * KW), 0, st, static_cast<const T *>(q), rows, \
-                       md.hq, md.hkv, rm.mask, n_prefix, region_len, kv, bps, scale, sc.o, sc.ml, rho_pad, direct)
-    if (md.dh == 128) { if (kw == 4) POSS_ATTN(128, 4); else if (kw == 2) POSS_ATTN(128, 2); else POSS_ATTN(128, 1); }
-    else              { if (kw == 4) POSS_ATTN(64, 4);  else if (kw == 2) POSS_ATTN(64, 2);  else POSS_ATTN(64, 1); }
+    // Key-ways follow the split size (so, like it, the committed prefix only); the number of row tiles per
+    // wave may follow the row count: it does not change any row's arithmetic.
+    const int kw = bps >= 4 ? 2 : 1;
+    const int rt = tiles > 4 && bps >= 8 ? 2 : 1;         // pays only where the walk is long
+    const int n_row_groups = (tiles + 4 * rt - 1) / (4 * rt), n_pairs = md.hkv * n_splits;
+    dim3 grid(8 * n_row_groups * ((n_pairs + 7) / 8));
+#define POSS_ATTN(DH, KW, RT)                                                                                    \
+    hipLaunchKernelGGL((attn_mfma_kernel<T, DH, KW, RT>), grid, dim3(256 * KW), 0, st, static_cast<const T *>(q),   \
+                       rows, md.hq, md.hkv, rm.mask, n_prefix, region_len, kv, bps, n_splits, n_row_groups, scale,  \
+                       sc.o, sc.ml, rho_pad, direct)
+#define POSS_ATTN_DH(DH)                                                                                         \
+    do {                                                                                                         \
+        if (kw == 2) { if (rt == 2) POSS_ATTN(DH, 2, 2); else POSS_ATTN(DH, 2, 1); }                             \
+        else         { if (rt == 2) POSS_ATTN(DH, 1, 2); else POSS_ATTN(DH, 1, 1); }                             \
+    } while (0)
+    if (md.dh == 128) POSS_ATTN_DH(128); else POSS_ATTN_DH(64);
+#undef POSS_ATTN_DH
 #undef POSS_ATTN
     if (n_splits > 1)
         hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(rows, md.hq), dim3(md.dh < 64 ? 64 : md.dh), 0, st, sc.o, sc.ml,
