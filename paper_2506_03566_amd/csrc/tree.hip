@@ -12,15 +12,28 @@
 namespace poss {
 
 // ------------------------------------------------------------------ top-k + log-sum-exp
-// Selection of the k best (value, index) pairs held NV per thread by a 256-thread workgroup: every
-// wave extracts its own k best with shuffles only (no workgroup barrier inside the k rounds), then
-// wave 0 picks the k best of the 4k survivors.  Thread r < k of wave 0 ends up with the r-th best.
+// Selection of the k best (value, index) pairs held NV per thread by a 256-thread workgroup.
+// block_topk_rounds: every wave extracts its own k best with shuffles only (no workgroup barrier
+// inside the k rounds), then wave 0 picks the k best of the 4k survivors.
+// block_topk: threshold first.  The k-th largest of the 256 per-thread maxima is a lower bound of
+// the k-th largest element, so every winner is among the elements >= that bound: a handful, ranked
+// by counting.  No chain of dependent shuffles; the rounds remain as the fallback for inputs with
+// more than TOPK_CAND elements above the bound (long runs of equal values).
+// Either way thread r < k ends up with the r-th best, (-inf, 0x7fffffff...) where fewer than k exist.
 constexpr int TOPK_SEG = 2048;
 constexpr int TOPK_MAXK = 16;
+constexpr int TOPK_CAND = 256;
+struct __attribute__((aligned(16))) TopkLds {
+    float tmax[256];
+    float cand_v[TOPK_CAND]; int cand_i[TOPK_CAND];
+    float out_v[TOPK_MAXK]; int out_i[TOPK_MAXK];
+    float rounds_v[4 * TOPK_MAXK]; int rounds_i[4 * TOPK_MAXK];
+    float thr; int cnt;
+};
 
 template <int NV>
-__device__ __forceinline__ void block_topk(float (&v)[NV], int (&id)[NV], int k, float *s_val, int *s_id,
-                                           float &out_v, int &out_i) {
+__device__ __forceinline__ void block_topk_rounds(float (&v)[NV], int (&id)[NV], int k, float *s_val, int *s_id,
+                                                  float &out_v, int &out_i) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int r = 0; r < k; ++r) {
         float bv = -INFINITY; int bi = 0x7fffffff;
@@ -48,13 +61,56 @@ __device__ __forceinline__ void block_topk(float (&v)[NV], int (&id)[NV], int k,
     }
 }
 
+template <int NV>
+__device__ __forceinline__ void block_topk(float (&v)[NV], int (&id)[NV], int k, TopkLds &L, float &out_v, int &out_i) {
+    const int tid = threadIdx.x;                          // blockDim.x == 256
+    float tm = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) tm = fmaxf(tm, v[j]);
+    L.tmax[tid] = tm;
+    if (tid == 0) { L.cnt = 0; L.thr = -INFINITY; }
+    if (tid < TOPK_MAXK) { L.out_v[tid] = -INFINITY; L.out_i[tid] = 0x7fffffff; }
+    __syncthreads();
+    int rank = 0;                                         // of this thread's maximum, ties to the lower thread
+    for (int j = 0; j < 256; j += 4) {
+        const float4 o = *reinterpret_cast<const float4 *>(&L.tmax[j]);
+        rank += (o.x > tm) || (o.x == tm && j < tid);
+        rank += (o.y > tm) || (o.y == tm && j + 1 < tid);
+        rank += (o.z > tm) || (o.z == tm && j + 2 < tid);
+        rank += (o.w > tm) || (o.w == tm && j + 3 < tid);
+    }
+    if (rank == k - 1) L.thr = tm;                        // exactly one thread
+    __syncthreads();
+    const float thr = L.thr;
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+        if (v[j] > -INFINITY && v[j] >= thr) {
+            const int p = atomicAdd(&L.cnt, 1);           // arrival order does not matter: ranks are by (value, index)
+            if (p < TOPK_CAND) { L.cand_v[p] = v[j]; L.cand_i[p] = id[j]; }
+        }
+    __syncthreads();
+    const int cnt = L.cnt;
+    if (cnt > TOPK_CAND) {                                // workgroup-uniform
+        block_topk_rounds<NV>(v, id, k, L.rounds_v, L.rounds_i, out_v, out_i);
+        return;
+    }
+    if (tid < cnt) {
+        const float cv = L.cand_v[tid]; const int ci = L.cand_i[tid];
+        int r = 0;
+        for (int j = 0; j < cnt; ++j) r += better(L.cand_v[j], L.cand_i[j], cv, ci);
+        if (r < k) { L.out_v[r] = cv; L.out_i[r] = ci; }
+    }
+    __syncthreads();
+    out_v = -INFINITY; out_i = 0x7fffffff;
+    if (tid < k) { out_v = L.out_v[tid]; out_i = L.out_i[tid]; }
+}
+
 // stage 1: one workgroup per (segment of <= TOPK_SEG logits, row): segment maximum, sum of
 // exp(l - max) and the segment's k best.  record: [max, sumexp, k values, k indices (as bits)]
 __global__ __launch_bounds__(256) void topk_seg_kernel(const float *__restrict__ logits, int ld, int vocab, int k,
                                                        int n_seg, float *__restrict__ seg_out) {
     constexpr int NV = TOPK_SEG / 256;
-    __shared__ float s_val[4 * TOPK_MAXK];
-    __shared__ int s_id[4 * TOPK_MAXK];
+    __shared__ TopkLds lds;
     __shared__ float red[17];
     const int seg = blockIdx.x, row = blockIdx.y;
     const int base = seg * TOPK_SEG;
@@ -80,7 +136,7 @@ __global__ __launch_bounds__(256) void topk_seg_kernel(const float *__restrict__
     float *rec = seg_out + ((size_t)row * n_seg + seg) * (2 + 2 * TOPK_MAXK);
     if (threadIdx.x == 0) { rec[0] = mx; rec[1] = se; }
     float ov; int oi;
-    block_topk<NV>(v, id, k, s_val, s_id, ov, oi);
+    block_topk<NV>(v, id, k, lds, ov, oi);
     if ((int)threadIdx.x < k) {
         rec[2 + threadIdx.x] = ov;
         reinterpret_cast<int *>(rec)[2 + TOPK_MAXK + threadIdx.x] = ov > -INFINITY ? oi : 0x7fffffff;
@@ -92,8 +148,7 @@ __global__ __launch_bounds__(256) void topk_seg_kernel(const float *__restrict__
 constexpr int TOPK_MERGE_NV = 8;                          // up to 2048 candidates (128 segments x 16)
 __global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict__ seg_out, int n_seg, int k,
                                                          int32_t *__restrict__ out_id, float *__restrict__ out_logp) {
-    __shared__ float s_val[4 * TOPK_MAXK];
-    __shared__ int s_id[4 * TOPK_MAXK];
+    __shared__ TopkLds lds;
     __shared__ float red[17];
     const int row = blockIdx.x, nc = n_seg * k;
     const float *recs = seg_out + (size_t)row * n_seg * (2 + 2 * TOPK_MAXK);
@@ -122,7 +177,7 @@ __global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict
         }
     }
     float ov; int oi;
-    block_topk<TOPK_MERGE_NV>(v, id, k, s_val, s_id, ov, oi);
+    block_topk<TOPK_MERGE_NV>(v, id, k, lds, ov, oi);
     if ((int)threadIdx.x < k) {
         out_id[row * k + threadIdx.x] = oi;
         out_logp[row * k + threadIdx.x] = ov - lse;

@@ -185,3 +185,60 @@ def test_verify_after_caller_trees_then_draft_catches_up():
         assert d["token"] == ot.token and d["parent"] == ot.parent
     assert np.abs(d["score"] - np.array(ot.score, dtype=np.float32)).max() < 1e-4 or min(o.margins) <= 2e-5
     pair.close()
+
+
+def test_all_equal_logits_pick_lowest_ids():
+    """A zero LM head makes every logit equal: top-k must return tokens 0..k-1 with log-probability
+    -log(V) at every expanded node (ties to the lower id, then to the earlier candidate), exactly
+    the oracle's tree.  On the GPU this is the case where the threshold selection finds more
+    candidates than it keeps and falls back to selection in rounds."""
+    cfg = get_config("c0_tiny_f32")
+    st = make_weights(cfg)
+    st["lm_head"] = to_storage(np.zeros(st["lm_head"].shape), cfg.dtype)
+    pair = Pair("c0_tiny_f32", storage=st)
+    ctx, o = pair.ctx, pair.oracle()
+    prompt = make_prompt(cfg, n=12)
+    assert ctx.prefill(prompt) == o.prefill(prompt) == 0          # argmax of equal logits: id 0
+    d = ctx.draft_tree().as_dict()
+    ot = o.draft_tree()
+    assert d["token"] == ot.token and d["parent"] == ot.parent
+    k = cfg.top_k
+    for i in range(1, d["n"]):
+        assert d["token"][i] < k
+        assert abs(d["score"][i] + d["depth"][i] * np.log(cfg.vocab)) < 1e-4
+    g = ctx.verify_tree()[:d["n"]]
+    assert list(g) == [0] * d["n"]
+    path, m, toks = ctx.accept_and_commit()
+    og, _, _ = o.verify_tree(ot)
+    assert (path, m, toks[-1]) == o.accept_and_commit()
+    pair.close()
+
+
+def test_duplicated_head_rows_order_equal_logits_by_id():
+    """LM-head rows 2i and 2i+1 made identical: their logits are bitwise equal, so wherever the
+    odd token appears among a node's children the even one must be there too, ranked just before
+    it (same parent, the even one earlier among the siblings)."""
+    cfg = get_config("c0_tiny_f32")
+    st = make_weights(cfg)
+    head = st["lm_head"].copy()
+    head[1::2] = head[0::2]
+    st["lm_head"] = head
+    pair = Pair("c0_tiny_f32", storage=st)
+    ctx = pair.ctx
+    ctx.prefill(make_prompt(cfg, n=20))
+    pairs_seen = 0
+    for _ in range(3):
+        d = ctx.draft_tree().as_dict()
+        kids = {}
+        for i in range(1, d["n"]):
+            kids.setdefault(d["parent"][i], []).append((i, d["token"][i], d["score"][i]))
+        for p, ch in kids.items():
+            toks = {t: (i, s) for i, t, s in ch}
+            for t, (i, s) in toks.items():
+                if t % 2 == 1 and t - 1 in toks:
+                    pairs_seen += 1
+                    assert toks[t - 1][0] < i and toks[t - 1][1] == s     # earlier node, bit-equal score
+        ctx.verify_tree()
+        ctx.accept_and_commit()
+    assert pairs_seen > 0
+    pair.close()
