@@ -1,7 +1,8 @@
-"""Llama-3-8B shape (the benchmark workload, launch configuration of bench.py): the oracle cannot
-run the whole model in test time, so single outputs are sampled: one target layer and the Head
-recomputed by the oracle from the library's own inputs, plus properties that hold at any size
-(speculative stream == the library's vanilla greedy stream up to near-ties, tree validity)."""
+"""Full-size shapes (the benchmark workload in the launch configuration bench.py times, the
+Llama-2-13B shape in fp16, the 8192-token context with depth 7 / 80 draft tokens): the oracle
+cannot run a whole model in test time, so single outputs are sampled: one target layer and the
+Head recomputed by the oracle from the library's own inputs, plus properties that hold at any
+size (speculative stream == the library's own vanilla greedy stream, tree validity)."""
 import numpy as np
 import pytest
 
@@ -22,11 +23,12 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def test_llama3_8b_shape_sampled_parity_and_losslessness():
-    cfg = get_config("c1_llama3_8b_3x2", n_prompt=200)
-    layer = 17
+@pytest.mark.parametrize("name,layer,n_ar", [("c1_llama3_8b_3x2", 17, 10), ("c3_llama2_13b_3x2", 23, 6),
+                                             ("c4_llama3_8b_long", 5, 5)])
+def test_full_size_sampled_parity_and_losslessness(name, layer, n_ar):
+    cfg = get_config(name)
     keep = [f"layer{layer}.", "lm_head", "final_norm"]
-    _say("generating 8B-shape weights")
+    _say(f"generating weights of {name}")
     dev, host = make_weights_on_device(cfg, keep_host=keep)
     ctx = P.Poss(cfg, dev)
     del dev
@@ -38,7 +40,7 @@ def test_llama3_8b_shape_sampled_parity_and_losslessness():
     # ---- vanilla greedy stream from root-only rounds, with the top-2 gap of every step
     logits1 = torch.zeros(1, cfg.vocab, device="cuda")
     ar, gaps = [first], []
-    for _ in range(10):
+    for _ in range(n_ar):
         ctx.verify_tree(P.TreeArrays.from_lists([0], [-1]), logits_out=logits1)
         top2 = torch.topk(logits1[0], 2).values
         gaps.append(float(top2[0] - top2[1]))
@@ -59,7 +61,7 @@ def test_llama3_8b_shape_sampled_parity_and_losslessness():
     g = ctx.verify_tree(None, logits_out=logits, feat_out=feats)[:d["n"]]
     ctx.debug_set_taps(None)
     # ---- sampled layer: oracle layer `layer` on the library's input rows and cached keys/values
-    _say("oracle: one decoder layer on 61 rows")
+    _say(f"oracle: one decoder layer on {d['n']} rows over {t} cached tokens")
     h_in = taps[layer].cpu().numpy().astype(np.float64)
     h_out = taps[layer + 1].cpu().numpy().astype(np.float64)
     kc, vc = ctx.debug_read_kv(-1, layer, 0, t)
