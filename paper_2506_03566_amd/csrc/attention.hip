@@ -320,24 +320,48 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     }
 }
 
-// out[m][qh][:] = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s
+// out[m][qh][:] = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, splits in order.  The (max, sum) pairs of
+// all splits are fetched in one go and turned into weights once; the partial outputs are then read
+// four splits at a time so that their latencies overlap.
+constexpr int ATTN_MAX_SPLITS = 256;
 template <typename T>
 __global__ void attn_merge_kernel(const float *__restrict__ o_part, const float *__restrict__ ml_part, int n_splits,
                                   int hq, int hkv, int dh, int rho_pad, T *__restrict__ out) {
+    __shared__ float w_lds[ATTN_MAX_SPLITS];
+    __shared__ float den_lds;
     const int m = blockIdx.x, qh = blockIdx.y, G = hq / hkv;
     const int kvh = qh / G, rho = m * G + qh % G;
+    const size_t stride = (size_t)hkv * rho_pad;          // rows between consecutive splits
+    const size_t row0 = (size_t)kvh * rho_pad + rho;
+    for (int s0 = threadIdx.x; s0 < n_splits; s0 += blockDim.x) w_lds[s0] = ml_part[(row0 + s0 * stride) * 2];
+    __syncthreads();
     float M = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml_part[(((size_t)s * hkv + kvh) * rho_pad + rho) * 2]);
-    for (int i = threadIdx.x; i < dh; i += blockDim.x) {
-        float num = 0.f, den = 0.f;
-        for (int s = 0; s < n_splits; ++s) {
-            const size_t prow = ((size_t)s * hkv + kvh) * rho_pad + rho;
-            const float ms = ml_part[prow * 2];
-            if (ms == -INFINITY) continue;
-            const float w = __builtin_amdgcn_exp2f(ms - M);      // the partial maxima are in the log2 domain
-            num += w * o_part[prow * dh + i];
-            den += w * ml_part[prow * 2 + 1];
+    for (int s0 = 0; s0 < n_splits; ++s0) M = fmaxf(M, w_lds[s0]);
+    __syncthreads();
+    if (threadIdx.x == 0) {                               // one thread: the order of the sum is fixed
+        float den = 0.f;
+        for (int s0 = 0; s0 < n_splits; ++s0) {
+            const float ms = w_lds[s0];
+            const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - M);   // maxima are in the log2 domain
+            w_lds[s0] = w;
+            den += w * ml_part[(row0 + s0 * stride) * 2 + 1];
         }
+        den_lds = den;
+    }
+    __syncthreads();
+    const float den = den_lds;
+    for (int i = threadIdx.x; i < dh; i += blockDim.x) {
+        const float *src = o_part + row0 * dh + i;
+        float num = 0.f;
+        int s0 = 0;
+        for (; s0 + 4 <= n_splits; s0 += 4) {
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = src[(size_t)(s0 + j) * stride * dh];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) num += w_lds[s0 + j] * v[j];    // a split without visible keys has weight 0 and O = 0
+        }
+        for (; s0 < n_splits; ++s0) num += w_lds[s0] * src[(size_t)s0 * stride * dh];
         out[((size_t)m * hq + qh) * dh + i] = from_f<T>(num / den);
     }
 }
@@ -403,7 +427,8 @@ static void launch_attention_t(const ModelDims &md, const void *q, int rows, con
     const int G = md.hq / md.hkv;
     const int tiles = (rows * G + 15) / 16, rho_pad = tiles * 16;
     const int n_blocks = (n_prefix + region_len + 31) / 32;
-    const int bps = blocks_per_split(n_prefix, keys_per_split);
+    int bps = blocks_per_split(n_prefix, keys_per_split);
+    while ((n_blocks + bps - 1) / bps > ATTN_MAX_SPLITS) bps *= 2;     // only with a tiny split override on a very long context
     const int n_splits = (n_blocks + bps - 1) / bps;
     const float scale = 1.4426950408889634f / sqrtf((float)md.dh);     // log2(e) / sqrt(dh): scores in the log2 domain
     T *direct = n_splits == 1 ? static_cast<T *>(out) : nullptr;
