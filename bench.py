@@ -39,10 +39,10 @@ def round_bytes(cfg, t, a):
     return es * (target + draft + kv_target + kv_draft)
 
 
-def cpu_baseline(cfg, seconds_hint=20.0):
+def cpu_baseline(cfg, n_layers_sample=16):
     """The CPU oracle timed on a bounded sample of the same round and scaled to a whole round:
-    one of the target's layers and its Head over the 61 tree rows at t = n_prompt, and one
-    specialist pass with its Head over top_k rows."""
+    n_layers_sample of the target's layers and its Head over the tree rows at t = n_prompt, and one
+    pass of every specialist with its Head over top_k rows."""
     import numpy as np
     from synth import make_weights
     from oracle.model import Weights, decoder_layer, head, specialist_pass
@@ -52,7 +52,9 @@ def cpu_baseline(cfg, seconds_hint=20.0):
     except Exception:
         cores = os.cpu_count() or 1
     act = None if cfg.dtype == 0 else cfg.dtype
-    names = ["layer0.", "lm_head", "final_norm", "embed", "spec0."]
+    n_layers_sample = min(n_layers_sample, cfg.n_layers)
+    names = ["layer%d." % l for l in range(n_layers_sample)] + ["lm_head", "final_norm", "embed"] + \
+            ["spec%d." % s for s in range(cfg.n_specialists)]
     W = Weights(cfg, make_weights(cfg, names=names), cache=False)
     rng = np.random.default_rng(0)
     t, M, k = cfg.n_prompt, cfg.total_tokens + 1, cfg.top_k
@@ -62,8 +64,10 @@ def cpu_baseline(cfg, seconds_hint=20.0):
     allowed = np.ones((M, t + M), dtype=bool)
     allowed[:, t:] = np.tril(np.ones((M, M), dtype=bool))
     t0 = time.perf_counter()
-    f, _, _ = decoder_layer(W, "layer0.", cfg, h, np.arange(t, t + M), kc, vc, allowed, act)
-    t_layer = time.perf_counter() - t0
+    f = h
+    for l in range(n_layers_sample):
+        f, _, _ = decoder_layer(W, "layer%d." % l, cfg, f, np.arange(t, t + M), kc, vc, allowed, act)
+    t_layers = time.perf_counter() - t0
     t0 = time.perf_counter()
     head(W, cfg, f, act)
     t_head_v = time.perf_counter() - t0
@@ -72,17 +76,18 @@ def cpu_baseline(cfg, seconds_hint=20.0):
     feats = rng.normal(size=(n_seq, cfg.d_model))
     al = np.ones((k, n_seq), dtype=bool)
     t0 = time.perf_counter()
-    out = specialist_pass(W, cfg, 0, toks, feats, np.arange(n_seq), al, list(range(t, n_seq)), act)
-    t_spec = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    head(W, cfg, out, act)
-    t_head_d = time.perf_counter() - t0
-    round_s = cfg.n_layers * t_layer + t_head_v + cfg.depth * (t_spec + t_head_d)
+    for s in range(cfg.n_specialists):
+        out = specialist_pass(W, cfg, s, toks, feats, np.arange(n_seq), al, list(range(t, n_seq)), act)
+        head(W, cfg, out, act)
+    t_spec = (time.perf_counter() - t0) / cfg.n_specialists
+    round_s = cfg.n_layers * t_layers / n_layers_sample + t_head_v + cfg.depth * t_spec
+    measured = t_layers + t_head_v + t_spec * cfg.n_specialists
     return dict(value=1.0 / round_s, unit="tokens/s", cores=int(cores), kind="oracle",
-                sample=("oracle timed on 1 of %d target layers + Head over %d tree rows at t=%d, and 1 of %d "
-                        "specialist passes + Head over %d rows; scaled to a full round at 1 committed "
-                        "token per round; %.2f s measured, %.1f s per round extrapolated"
-                        % (cfg.n_layers, M, t, cfg.depth, k, t_layer + t_head_v + t_spec + t_head_d, round_s)),
+                sample=("oracle timed on %d of %d target layers + Head over %d tree rows at t=%d, and one pass + "
+                        "Head of each of the %d specialists over %d rows; scaled to a full round (%d layers, %d "
+                        "draft passes) at 1 committed token per round; %.1f s measured, %.1f s per round extrapolated"
+                        % (n_layers_sample, cfg.n_layers, M, t, cfg.n_specialists, k, cfg.n_layers, cfg.depth,
+                           measured, round_s)),
                 ms_per_round=round_s * 1e3)
 
 

@@ -55,10 +55,8 @@ struct poss_ctx {
     KVCache *target_kv_dev;
     size_t cache_bytes_each;
     // activations
-    float *h, *part, *logits, *feats, *fhat[2], *topk_scratch, *taps_user, *ss;
-    unsigned *counters;
+    float *h, *part, *logits, *feats, *fhat[2], *topk_scratch, *taps_user;
     float2 *cs;
-    int ss_ld, n_counters;
     void *u, *xin, *q, *attn_out, *act;
     AttnScratch attn_sc;
     int32_t *row_pos, *row_slot, *tree_slot;
@@ -174,18 +172,13 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     const int R = MAX_ROWS;
     size_t part_floats = 0;
     const int shapes[6][2] = {{qd + 2 * kd, d}, {d, qd}, {gate_up_rows(F), d}, {d, F}, {d, 2 * d}, {V, d}};
-    int max_tiles = 1;
     for (int i = 0; i < 5; ++i) {
         // split count does not depend on M; planes are at most R rows
         GemmShape g = gemm_plan(dt, R, shapes[i][0], shapes[i][1], 4096);   // upper bound on splits
         const size_t f = (size_t)g.S * R * g.Npad;
         if (f > part_floats) part_floats = f;
-        if (g.Npad / GEMM_BLOCK_N > max_tiles) max_tiles = g.Npad / GEMM_BLOCK_N;
     }
     float *h = a.take_n<float>((size_t)R * d);
-    const int ss_ld = gemm_npad(d) / GEMM_BLOCK_N;
-    float *ss = a.take_n<float>((size_t)R * ss_ld);
-    unsigned *counters = a.take_n<unsigned>(max_tiles);
     float2 *cs = a.take_n<float2>((size_t)R * (c.head_dim / 2));
     float *part = a.take_n<float>(part_floats);
     float *logits = a.take_n<float>((size_t)R * gemm_npad(V));
@@ -228,7 +221,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         for (int s = 0; s < c.n_specialists; ++s)
             ctx->spec_kv.push_back(KVCache{kvp[2 * (c.n_layers + s)], kvp[2 * (c.n_layers + s) + 1], pt, shift});
         ctx->target_kv_dev = kv_dev;
-        ctx->ss = ss; ctx->ss_ld = ss_ld; ctx->counters = counters; ctx->cs = cs; ctx->n_counters = max_tiles;
+        ctx->cs = cs;
         ctx->h = h; ctx->part = part; ctx->logits = logits; ctx->feats = feats; ctx->fhat[0] = fhat0; ctx->fhat[1] = fhat1;
         ctx->topk_scratch = topk_scr; ctx->u = u; ctx->xin = xin; ctx->q = q; ctx->attn_out = ao; ctx->act = act;
         ctx->attn_sc = AttnScratch{ao_part, ml_part};

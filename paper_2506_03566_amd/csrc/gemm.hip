@@ -10,11 +10,15 @@
 //   * the (small, L2-resident) activation slice is staged in LDS in A-operand order, double
 //     buffered, its global loads issued one chunk ahead so they are older than the weight loads
 //     they overlap and never force the weight ring to drain;
-//   * K is split across workgroups into partial planes; a tile-parallel epilogue kernel (one
-//     workgroup per 128 output columns) sums them in split order and applies the fused operation:
-//     rotary embedding + KV-cache write, residual add + RMSNorm partials, SiLU * up.  Bitwise
-//     repeatable.  (Doing this inside the GEMM by the last workgroup to arrive at a tile was
-//     measured 3.5x slower: agent-scope fences write back and invalidate the per-XCD L2s.)
+//   * K is split across workgroups (as many splits as keep the launch at one workgroup per CU) into
+//     partial planes; an epilogue kernel sums them in split order and applies the fused operation:
+//     rotary embedding + KV-cache write (tile-parallel), or residual add followed by the RMSNorm
+//     that feeds the next GEMM (one workgroup per row).  Bitwise repeatable, and a row's result
+//     does not depend on how many rows the launch carries.  (Reducing inside the GEMM by the last
+//     workgroup to arrive at a tile was measured 3.5x slower: agent-scope fences write back and
+//     invalidate the per-XCD L2s.)
+//   * the gate/up projection is not split: gate and up rows are interleaved so that one lane holds
+//     both factors, and the kernel writes SiLU(gate) * up in the storage type itself.
 #include "device_utils.h"
 
 #include <type_traits>
@@ -133,11 +137,9 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
             const int r = rb + (t >> 5);
             if (r < r_end && n < N) {
                 const f32x4 v = sum_planes4(part, plane, S, (size_t)r * Npad + n);
-                if constexpr (EPI == EPI_PLAIN) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (n + j < N) e.out[(size_t)r * e.ld_out + n + j] = v[j];
-                }
+                for (int j = 0; j < 4; ++j)
+                    if (n + j < N) e.out[(size_t)r * e.ld_out + n + j] = v[j];
             }
         }
     }
