@@ -72,7 +72,8 @@ struct poss_ctx {
     poss_stats stats;
     void *pinned; size_t pinned_bytes;
     hipEvent_t ev[6];                  // begin/end of the draft, verify and commit phases
-    bool ev_pending[3];                // phase recorded, elapsed time not yet added to the statistics
+    bool ev_pending[3];
+    bool launch_refused;               // a GEMM launch was refused on the host (null operand): internal error                // phase recorded, elapsed time not yet added to the statistics
     int gemm_target_wgs, attn_keys_per_split;
     // gemm profiling
     int prof_on, prof_n;
@@ -238,7 +239,8 @@ GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int
     GemmShape g = gemm_plan(c->md.dt, M, N, K, single_split ? 1 : c->gemm_target_wgs);
     const bool prof = c->prof_on && c->prof_n < PROFILE_EVENTS;
     if (prof) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->st);
-    launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st, prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr);
+    if (!launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st, prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr))
+        c->launch_refused = true;                   // reported by the next call that waits for the stream
     if (prof) {
         ++c->prof_n;
         c->prof_bytes += (double)N * K * dtype_size(c->md.dt);
@@ -481,6 +483,7 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     }
     for (int i = 0; i < 6; ++i) LOAD_TRY(hipEventCreate(&c->ev[i]));
     c->ev_pending[0] = c->ev_pending[1] = c->ev_pending[2] = false;
+    c->launch_refused = false;
     for (int i = 0; i < 2 * PROFILE_EVENTS; ++i) LOAD_TRY(hipEventCreate(&c->prof_ev[i]));
     LOAD_TRY(hipStreamSynchronize(c->st));
     LOAD_TRY(hipGetLastError());
@@ -494,6 +497,7 @@ int poss_reset(poss_ctx *c) {
     if (!c) return POSS_E_INVALID_ARG;
     (void)hipStreamSynchronize(c->st);
     c->ev_pending[0] = c->ev_pending[1] = c->ev_pending[2] = false;
+    c->launch_refused = false;
     reset_sequence(c);
     return POSS_OK;
 }
@@ -555,6 +559,7 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
 static int sync_and_harvest(poss_ctx *c) {
     HIP_TRY(c, hipStreamSynchronize(c->st));
     HIP_TRY(c, hipGetLastError());
+    if (c->launch_refused) return fail(c, POSS_E_HIP, "internal error: a GEMM launch was refused (null operand)");
     double *acc[3] = {&c->stats.ms_draft, &c->stats.ms_verify, &c->stats.ms_commit};
     for (int i = 0; i < 3; ++i) {
         if (!c->ev_pending[i]) continue;
@@ -844,7 +849,7 @@ int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_
     launch_pack(dtype, PackSrc{{w, nullptr, nullptr}, {N, 0, 0}}, K, wp, st);
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return fail(nullptr, POSS_E_HIP, "poss_debug_gemm: event creation failed");
-    launch_gemm(dtype, g, wp, x, K, part, epi, 0.f, st);
+    if (!launch_gemm(dtype, g, wp, x, K, part, epi, 0.f, st)) return fail(nullptr, POSS_E_INVALID_ARG, "poss_debug_gemm: launch refused");
     (void)hipEventRecord(e0, st);
     for (int i = 0; i < repeats; ++i) launch_gemm(dtype, g, wp, x, K, part, epi, 0.f, st);
     (void)hipEventRecord(e1, st);

@@ -98,7 +98,8 @@ struct EpiArgs {
 };
 // part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.  after_stream, if given, is
 // recorded between the weight-streaming kernel and its epilogue kernel (per-launch timing).
-void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
+// Returns false, launching nothing, if a pointer the chosen epilogue writes through is null.
+bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
                  const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t after_stream = nullptr);
 
 // ---------------------------------------------------------------- launchers: elementwise

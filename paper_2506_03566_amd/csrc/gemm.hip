@@ -44,10 +44,8 @@ template <> struct Mfma<f16_t> {
 };
 
 constexpr int KCS = GEMM_KCHUNK / GEMM_KSTEP;   // k-steps per LDS chunk (8)
-#ifndef POSS_GEMM_PF
-#define POSS_GEMM_PF 4
-#endif
-constexpr int PF  = POSS_GEMM_PF;               // weight k-steps in flight per wave
+// PF = weight k-steps in flight per wave (template parameter of the stream kernel): 4, or 8 for launches
+// with fewer workgroups than CUs, where each CU has to keep more bytes in flight to fill the memory system.
 
 // ------------------------------------------------------------------------------------------
 // Epilogue of one output tile (columns [tile*128, tile*128+128)) for rows [r_begin, r_end), run by
@@ -150,7 +148,7 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
 // slice: halves the L2 traffic per weight byte; used where N alone fills the GPU).
 // FUSE_SILU (K not split, gate/up interleaved per wave tile): the kernel applies SiLU(gate) * up to its
 // accumulators and writes the activation act[M][F] itself; no partial plane, no epilogue kernel.
-template <typename T, int MT, int WPB, bool FUSE_SILU>
+template <typename T, int MT, int WPB, bool FUSE_SILU, int PF>
 __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
     int M, int K, int Npad, int ksteps_total, T *__restrict__ act, int F) {
@@ -224,11 +222,16 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
         constexpr bool MORE = decltype(more_tag)::value;
         if constexpr (MORE) load_x(chunk + 1, xr);
         __builtin_amdgcn_sched_barrier(0);           // keep these loads older than the weight loads below
+        // A fragments of k-step i + 1 are requested from LDS before the MFMAs of k-step i are issued
+        u32x4 a[2][MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) a[0][mt] = xs[buf][mt * 64 + lane];
 #pragma unroll
         for (int i = 0; i < KCS; ++i) {
-            u32x4 a[MT];
+            if (i + 1 < KCS) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) a[mt] = xs[buf][(i * MT + mt) * 64 + lane];
+                for (int mt = 0; mt < MT; ++mt) a[(i + 1) & 1][mt] = xs[buf][((i + 1) * MT + mt) * 64 + lane];
+            }
             u32x4 w[GEMM_NT];
 #pragma unroll
             for (int nt = 0; nt < GEMM_NT; ++nt) w[nt] = wr[i % PF][nt];
@@ -240,7 +243,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[mt], w[nt], acc[mt][nt]);
+                for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[i & 1][mt], w[nt], acc[mt][nt]);
             __builtin_amdgcn_sched_barrier(0);       // one k-step at a time: loads stay in ring order
         }
         if constexpr (MORE) {
@@ -431,17 +434,16 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     const u32x4 *w = static_cast<const u32x4 *>(Wp);
     const T *x = static_cast<const T *>(X);
     T *act = static_cast<T *>(epi.act);
+    const bool deep = !wide && (int)(grid.x * grid.y) < 256;     // fewer workgroups than CUs: deeper weight ring
+#define POSS_GEMM_LAUNCH(MT, W, FUSE, PFV, FARG)                                                              \
+    hipLaunchKernelGGL((gemm_stream_kernel<T, MT, W, FUSE, PFV>), grid, block, 0, st, w, x, ldx, part, g.M,   \
+                       g.K, g.Npad, ksteps, act, FARG)
 #define POSS_GEMM_CASE(MT)                                                                                    \
     do {                                                                                                      \
-        if (fuse_silu)                                                                                        \
-            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 4, true>), grid, block, 0, st, w, x, ldx, part, g.M,   \
-                               g.K, g.Npad, ksteps, act, epi.F);                                        \
-        else if (wide)                                                                                        \
-            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 8, false>), grid, block, 0, st, w, x, ldx, part, g.M,  \
-                               g.K, g.Npad, ksteps, act, 0);                                            \
-        else                                                                                                  \
-            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, 4, false>), grid, block, 0, st, w, x, ldx, part, g.M,  \
-                               g.K, g.Npad, ksteps, act, 0);                                            \
+        if (fuse_silu) { if (deep) POSS_GEMM_LAUNCH(MT, 4, true, 8, epi.F); else POSS_GEMM_LAUNCH(MT, 4, true, 4, epi.F); } \
+        else if (wide) POSS_GEMM_LAUNCH(MT, 8, false, 4, 0);                                                  \
+        else if (deep) POSS_GEMM_LAUNCH(MT, 4, false, 8, 0);                                                  \
+        else POSS_GEMM_LAUNCH(MT, 4, false, 4, 0);                                                            \
     } while (0)
     switch (g.Mpad / 16) {
         case 1: POSS_GEMM_CASE(1); break;
@@ -451,12 +453,26 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
         default: POSS_GEMM_CASE(8); break;
     }
 #undef POSS_GEMM_CASE
+#undef POSS_GEMM_LAUNCH
     if (after_stream) (void)hipEventRecord(after_stream, st);
     launch_epilogue_t<T>(g, part, epi, eps, fuse_silu, st);
 }
 
-void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
+// Refuse, on the host, argument sets that would make a kernel write through a null pointer.
+static bool gemm_args_ok(const GemmShape &g, const void *Wp, const void *X, const float *part, const EpiArgs &e) {
+    if (!Wp || !X || !part || g.M < 1 || g.M > MAX_ROWS || g.S < 1) return false;
+    switch (e.mode) {
+        case EPI_PLAIN: return e.out || g.S == 1;          // unsplit: plane 0 is the result
+        case EPI_ROPE_KV: return e.q && e.cs && e.slot && e.kv.k && e.kv.vt && e.kv.page_table;
+        case EPI_RESIDUAL: return e.h && (!e.gain || e.u);
+        case EPI_SILU: return e.act != nullptr;
+        default: return false;
+    }
+}
+
+bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
                  const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream) {
+    if (!gemm_args_ok(g, Wp, X, part, epi)) return false;
     if (dt == DT_F32) {
         dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
         hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
@@ -468,10 +484,11 @@ void launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int 
     } else {
         launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st, after_stream);
     }
+    return true;
 }
 
 // ------------------------------------------------------------------------------------------
-// Repack row-major [rows_i, K] matrices, stacked along N (or gate/up interleaved in groups of 64
+// Repack row-major [rows_i, K] matrices, stacked along N (or gate/up interleaved in groups of 16
 // rows), into B-operand order.
 __device__ __forceinline__ bool pack_source_row(const PackSrc &src, int n, int &which, int &row) {
     if (src.interleave16) {          // 32 rows = 16 rows of matrix 0, then the same 16 rows of matrix 1
