@@ -404,9 +404,9 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float *__restrict__ 
     }
 }
 
-// Blocks of 32 keys per split.  One workgroup pulls keys and values at a few tens of GB/s at most, so a
-// short context is still cut into about four pieces of >= 4 blocks (the merge kernel costs less than the
-// serial walk it replaces); long contexts walk 32 blocks per workgroup.  The rule looks at the committed
+// Blocks of 32 keys per split.  A workgroup walks its blocks one after the other, each a dependent trip
+// to memory, so a short context is still cut into about four pieces of >= 4 blocks (the merge kernel
+// costs less than the serial walk it replaces); long contexts walk 32 blocks per workgroup.  The rule looks at the committed
 // prefix only, never at the number of rows or the size of the tree region: a row's arithmetic (which keys
 // meet in which split, in which order) is then the same whether it is verified alone or among 60 others,
 // which is what makes the speculative stream reproduce the one-token-at-a-time stream bit for bit as long

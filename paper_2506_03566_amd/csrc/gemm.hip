@@ -381,9 +381,9 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
     g.Mpad = gemm_rows_written(g.Mpad);       // the kernel is instantiated for 1, 2, 4, 6 or 8 row tiles
     const int n_blocks = g.Npad / GEMM_BLOCK_N;
     const int n_chunks = g.Kpad / GEMM_KCHUNK;
-    // A CU streams at a fixed rate however many workgroups it holds, so a launch takes as long as its
-    // busiest CU: at most one workgroup per CU (256), as many as fit, chunks dealt out evenly.  More
-    // splits only add partial-plane traffic.
+    // One workgroup per CU (256) at most, as many as fit, chunks dealt out evenly: in every sweep more
+    // splits were slower (partial-plane traffic grows, two workgroups on a CU share its LDS and barriers)
+    // and fewer leave CUs without a stream.
     if (target_wgs <= 0) target_wgs = 256;
     int S = target_wgs / n_blocks;
     int max_s = n_chunks / 2; if (max_s < 1) max_s = 1;          // at least 512 of K per split
