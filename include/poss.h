@@ -134,9 +134,10 @@ int poss_draft_tree(poss_ctx *ctx, poss_tree *out);
  * and the ancestor mask.  tree: HOST, or NULL for the tree drafted last.  argmax_out (HOST,
  * int32[n_nodes], may be NULL): the target's greedy token after each node, lowest id on ties.
  * logits_out (DEVICE float32 [n_nodes, vocab], may be NULL) and feat_out (DEVICE float32
- * [n_nodes, d_model], may be NULL) receive Head(f) and f of every row (Eq. 6).  With tree and all
- * three outputs NULL the call returns once the work is queued (no host wait), so that a round
- * draft -> verify -> accept waits for the device once, in poss_accept_and_commit. */
+ * [n_nodes, d_model], may be NULL) receive Head(f) and f of every row (Eq. 6).  With all three
+ * outputs NULL the call returns once the work is queued (no host wait), so that a round
+ * draft -> verify -> accept waits for the device once, in poss_accept_and_commit; the tree
+ * arrays are copied before the call returns. */
 int poss_verify_tree(poss_ctx *ctx, const poss_tree *tree, int32_t *argmax_out,
                      void *logits_out, void *feat_out);
 

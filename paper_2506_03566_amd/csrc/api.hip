@@ -703,7 +703,9 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     if (feat_out) launch_copy_rows_f32(c->feats, cf.d_model, static_cast<float *>(feat_out), cf.d_model, n, cf.d_model, c->st);
     HIP_TRY(c, hipGetLastError());
     c->state = ST_VERIFIED;
-    if (!argmax_out && !logits_out && !feat_out && !tree) return POSS_OK;     // nothing to hand over: stay queued
+    // Nothing to hand over: stay queued.  (A caller's tree was staged in pinned memory; the only call
+    // allowed next, poss_accept_and_commit, waits for the stream before that memory is touched again.)
+    if (!argmax_out && !logits_out && !feat_out) return POSS_OK;
     if (argmax_out) HIP_TRY(c, hipMemcpyAsync(argmax_out, c->argmax_dev, n * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
     return sync_and_harvest(c);
 }

@@ -62,7 +62,8 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     constexpr int KROW = DH + 8;                          // padded K row, elements
     constexpr int K_UNITS = 32 * DH / 8;                  // 16-byte units of one K block
     constexpr int KPT = K_UNITS / 256, VPT = K_UNITS / 256;
-    constexpr int KBLK = 32 * KROW, VBLK = DH * 32;       // elements of one staged K / V^T block
+    constexpr int VROW = 32 + 8;                          // padded V^T row (80 B stride: conflict-free operand reads)
+    constexpr int KBLK = 32 * KROW, VBLK = DH * VROW;     // elements of one staged K / V^T block
     // [2 buffers][KW blocks]; after the last block the same memory carries the KW-way merge
     __shared__ __attribute__((aligned(16))) T lds_all[2 * KW * (KBLK + VBLK)];
     T *ks_lds = lds_all, *vs_lds = lds_all + 2 * KW * KBLK;
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
             // keys k0 = (u%4)*8 .. k0+7: key k sits at element (k%16)/4*8 + (k/16)*4 + k%4 of its row
             const int u = stid + i * 256, row = u >> 2, k0 = (u & 3) * 8;
             const int half = k0 >> 4, g0 = (k0 & 15) >> 2;                 // k0..k0+3 -> group g0, k0+4..k0+7 -> g0+1
-            T *dst = &vs_lds[(buf * KW + stage_blk) * VBLK + row * 32];
+            T *dst = &vs_lds[(buf * KW + stage_blk) * VBLK + row * VROW];
             *reinterpret_cast<u32x2 *>(dst + g0 * 8 + half * 4) = u32x2{vr[SLOT][i].x, vr[SLOT][i].y};
             *reinterpret_cast<u32x2 *>(dst + (g0 + 1) * 8 + half * 4) = u32x2{vr[SLOT][i].z, vr[SLOT][i].w};
         }
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
         }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            const u32x4 vf = *reinterpret_cast<const u32x4 *>(&vbuf[(dt * 16 + lr) * 32 + lg * 8]);
+            const u32x4 vf = *reinterpret_cast<const u32x4 *>(&vbuf[(dt * 16 + lr) * VROW + lg * 8]);
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 if (rescale) acc[rt][dt] *= alpha[rt];
