@@ -19,6 +19,7 @@ from .model import (target_rows, head, causal_allowed, empty_kv, specialist_pass
                     specialist_index)
 from .numerics import log_softmax
 from .tree import TreeBuilder, Tree, accept_walk, AcceptStats
+from .sampling import sample_token
 
 
 def topk_lowest_id(row, k):
@@ -41,14 +42,16 @@ class PossOracle:
     def t(self):
         return len(self.tokens) - 1
 
-    def prefill(self, prompt):
-        """Causal target pass over the prompt; x_P = greedy token after the prompt."""
+    def prefill(self, prompt, temperature=0.0, U=None):
+        """Causal target pass over the prompt; x_P = greedy token after the prompt (temperature
+        > 0: drawn with U[P], see oracle/sampling.py)."""
         cfg, P = self.cfg, len(prompt)
         f, kv = target_rows(self.W, cfg, prompt, np.arange(P), empty_kv(cfg),
                             causal_allowed(0, P), self.act)
         logits = head(self.W, cfg, f[-1:], self.act)[0]
         self._note_margin(logits)
-        self.tokens = [int(x) for x in prompt] + [int(np.argmax(logits))]
+        first = sample_token(logits, temperature, U[P]) if temperature > 0 else int(np.argmax(logits))
+        self.tokens = [int(x) for x in prompt] + [first]
         self.feats = [f[i] for i in range(P)]
         self.kv = kv
         return self.tokens[-1]
@@ -164,15 +167,19 @@ class PossOracle:
         return np.array(score), logp_rows
 
     # ------------------------------------------------------------------ verify
-    def verify_tree(self, tree):
+    def verify_tree(self, tree, temperature=0.0, U=None):
         """One target pass over all tree rows (section 2.1, second phase).
-        Returns (greedy token after each node, logits, features)."""
+        Returns (the target's token after each node, logits, features): the argmax, or at
+        temperature > 0 a draw with U[position of that token] = U[t + depth + 1]."""
         cfg, t = self.cfg, self.t
         if tree.pos is None:
             tree.finish(t)
         F, new_kv = target_rows(self.W, cfg, tree.token, tree.pos, self.kv, tree.allowed(t), self.act)
         logits = head(self.W, cfg, F, self.act)
-        g = [int(np.argmax(logits[i])) for i in range(tree.n)]
+        if temperature > 0:
+            g = [sample_token(logits[i], temperature, U[t + tree.depth[i] + 1]) for i in range(tree.n)]
+        else:
+            g = [int(np.argmax(logits[i])) for i in range(tree.n)]
         self.last.update(tree=tree, F=F, new_kv=new_kv, logits=logits, g=g)
         return g, logits, F
 
@@ -195,14 +202,14 @@ class PossOracle:
         return list(path), m, int(bonus)
 
     # ------------------------------------------------------------------ whole run
-    def generate(self, prompt, n_new, record=None):
+    def generate(self, prompt, n_new, record=None, temperature=0.0, U=None):
         """prefill + rounds until n_new new tokens exist; the stream is cut to exactly n_new
         (a last round that overshoots still counts fully in the statistics)."""
         P = len(prompt)
-        self.prefill(prompt)
+        self.prefill(prompt, temperature, U)
         while len(self.tokens) - P < n_new:
             tree = self.draft_tree()
-            g, _, _ = self.verify_tree(tree)
+            g, _, _ = self.verify_tree(tree, temperature, U)
             path, m, bonus = self.accept_and_commit()
             if record is not None:
                 record.append(dict(tree=tree, g=g, path=path, m=m, bonus=bonus))
