@@ -107,6 +107,9 @@ def main():
     ap.add_argument("--total-tokens", type=int, default=0, help="override the number of draft tokens N (sweeps)")
     ap.add_argument("--specialists", type=int, default=0, help="override the number of specialists S (sweeps)")
     ap.add_argument("--positions", type=int, default=0, help="override positions per specialist n (sweeps)")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="> 0: verification draws the target's tokens at this temperature (sampler kernels "
+                         "instead of argmax); the headline metric is quoted at 0")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
@@ -138,7 +141,12 @@ def main():
     prompt = make_prompt(cfg)
     ctx.prefill(prompt)
 
+    import numpy as np
+    u_rng = np.random.default_rng(0)
+
     def one_round():
+        if args.temperature > 0:
+            ctx.set_sampling(args.temperature, u_rng.random(cfg.depth + 1).astype(np.float32))
         ctx.draft_tree(want_tree=False)
         ctx.verify_tree(None, want_argmax=False)
         return ctx.accept_and_commit()
@@ -196,6 +204,8 @@ def main():
     # speed-up ratio (Table 2); measured, while the ratio at the paper's tau stays a projection.
     if args.vanilla_steps > 0:
         ctx.reset()
+        if args.temperature > 0:
+            ctx.set_sampling(0.0)
         ctx.prefill(prompt)
         root = P.TreeArrays.from_lists([0], [-1])
         for _ in range(3):
@@ -215,6 +225,8 @@ def main():
                                       "round_over_vanilla")
     if over:
         out["config"]["overrides"] = over
+    if args.temperature > 0:
+        out["config"]["temperature"] = args.temperature
     if cfg.name in PAPER_TAU and not over:
         # NOT a measurement: random-init drafters accept nothing (tau_gen = 1), so this only restates the
         # measured round latency at the acceptance length the paper reports for trained drafters.

@@ -150,6 +150,18 @@ int poss_verify_tree(poss_ctx *ctx, const poss_tree *tree, int32_t *argmax_out,
 int poss_accept_and_commit(poss_ctx *ctx, int32_t *path_idx_out, int32_t *n_accepted_out,
                            int32_t *committed_out, int32_t *n_committed_out);
 
+/* Verification at temperature > 0 (the paper evaluates temperature 0 and 1, section 4.1; section 2.1
+ * only requires that verification keeps the target's output distribution).  The draft tree is built
+ * as at temperature 0; the token the target chooses after a node is DRAWN from
+ * softmax(logits / temperature) by inverse CDF in vocabulary order (the first id whose cumulative
+ * probability exceeds u), with u[d] for a node of depth d, i.e. one uniform number in [0, 1) per
+ * sequence position; poss_prefill draws x_P with u[0].  The walk then descends where a child
+ * carries the drawn token, so every committed token is an exact sample of the target given its
+ * prefix.  u: HOST, n_u values (1..depth+1; deeper levels reuse the last); copied before the call
+ * returns; it stays in force until the next call.  temperature == 0 restores greedy verification
+ * (u ignored).  Statistics count accepted draft tokens as before. */
+int poss_set_sampling(poss_ctx *ctx, float temperature, const float *u, int32_t n_u);
+
 /* Waits for queued work, then copies the statistics. */
 int poss_get_stats(poss_ctx *ctx, poss_stats *out);
 /* Number of committed tokens (prompt included); tokens_out (HOST, may be NULL) of capacity cap. */

@@ -73,7 +73,9 @@ struct poss_ctx {
     void *pinned; size_t pinned_bytes;
     hipEvent_t ev[6];                  // begin/end of the draft, verify and commit phases
     bool ev_pending[3];
-    bool launch_refused;               // a GEMM launch was refused on the host (null operand): internal error                // phase recorded, elapsed time not yet added to the statistics
+    bool launch_refused;               // a GEMM launch was refused on the host (null operand): internal error
+    float temperature;                 // 0: greedy verification; > 0: the target's tokens are drawn (poss_set_sampling)
+    float *u_pinned, *u_dev;           // one uniform number per tree depth, host staging and device copy                // phase recorded, elapsed time not yet added to the statistics
     int gemm_target_wgs, attn_keys_per_split;
     // gemm profiling
     int prof_on, prof_n;
@@ -187,6 +189,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     float *fhat0 = a.take_n<float>((size_t)16 * d), *fhat1 = a.take_n<float>((size_t)16 * d);
     size_t scr_floats = topk_scratch_floats(16, V);
     if (argmax_scratch_floats(R, V) > scr_floats) scr_floats = argmax_scratch_floats(R, V);
+    if (sample_scratch_floats(R, V) > scr_floats) scr_floats = sample_scratch_floats(R, V);
     float *topk_scr = a.take_n<float>(scr_floats);      // shared by top-k (draft) and argmax (verify)
     void *u = a.take((size_t)R * d * es), *xin = a.take((size_t)R * 2 * d * es);
     void *q = a.take((size_t)R * qd * es), *ao = a.take((size_t)R * qd * es), *act = a.take((size_t)R * F * es);
@@ -214,6 +217,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     void *stash = a.take((size_t)slots * d * es);
     void *xin_tmp = a.take((size_t)MAX_ROWS * 2 * d * es);
     double *inv_freq = a.take_n<double>(c.head_dim / 2);
+    float *u_dev = a.take_n<float>(POSS_MAX_DEPTH + 1);
     (void)tw;
     if (ctx) {
         ctx->cache_slots = slots; ctx->n_pages = pages; ctx->page_table = pt; ctx->cache_bytes_each = cache_each;
@@ -228,7 +232,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         ctx->attn_sc = AttnScratch{ao_part, ml_part};
         ctx->row_pos = row_pos; ctx->row_slot = row_slot; ctx->tree_slot = tree_slot; ctx->row_mask = row_mask;
         ctx->td = td; ctx->tokens_dev = tokens_dev; ctx->argmax_dev = argmax_dev; ctx->walk_dev = walk_dev;
-        ctx->feat_stash = stash; ctx->xin_tmp = xin_tmp; ctx->inv_freq = inv_freq;
+        ctx->feat_stash = stash; ctx->xin_tmp = xin_tmp; ctx->inv_freq = inv_freq; ctx->u_dev = u_dev;
     }
     return a.off + 256;
 }
@@ -466,6 +470,9 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     // small host->device tables
     c->pinned_bytes = 1 << 20;
     LOAD_TRY(hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault));
+    LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->u_pinned), (POSS_MAX_DEPTH + 1) * sizeof(float), hipHostMallocDefault));
+    for (int i = 0; i <= POSS_MAX_DEPTH; ++i) c->u_pinned[i] = 0.f;
+    c->temperature = 0.f;
     {
         char *p = static_cast<char *>(c->pinned);
         int32_t *pt = reinterpret_cast<int32_t *>(p);
@@ -508,10 +515,13 @@ void poss_free(poss_ctx *c) {
     for (int i = 0; i < 6; ++i) (void)hipEventDestroy(c->ev[i]);
     for (int i = 0; i < 2 * PROFILE_EVENTS; ++i) (void)hipEventDestroy(c->prof_ev[i]);
     (void)hipHostFree(c->pinned);
+    (void)hipHostFree(c->u_pinned);
     delete c;
 }
 
 const char *poss_last_error(poss_ctx *c) { return c ? c->err : g_load_error; }
+
+static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth);
 
 int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
     if (!c) return POSS_E_INVALID_ARG;
@@ -536,7 +546,7 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
             EpiArgs pe{};
             pe.mode = EPI_PLAIN;
             GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true, pe);
-            launch_argmax(c->logits, g.Npad, 1, md.vocab, c->topk_scratch, c->argmax_dev, c->st);
+            { int rc = choose_tokens(c, g.Npad, 1, nullptr); if (rc) return rc; }
             HIP_TRY(c, hipMemcpyAsync(c->tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
         }
         HIP_TRY(c, hipStreamSynchronize(c->st));          // the staging buffer is reused by the next chunk
@@ -551,6 +561,19 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
     HIP_TRY(c, hipGetLastError());
     c->state = ST_READY; c->tree_ready = 0;
     if (first_token_out) *first_token_out = first;
+    return POSS_OK;
+}
+
+// The token the target chooses after each of `rows` rows of c->logits: the argmax, or at temperature > 0 a
+// draw by inverse CDF with the uniform number of the row's depth (depth == nullptr: all rows use u[0]).
+static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth) {
+    if (c->temperature > 0.f) {
+        HIP_TRY(c, hipMemcpyAsync(c->u_dev, c->u_pinned, (POSS_MAX_DEPTH + 1) * sizeof(float), hipMemcpyHostToDevice, c->st));
+        if (!launch_sample(c->logits, ld, rows, c->cfg.vocab, c->temperature, c->u_dev, depth, c->topk_scratch, c->argmax_dev, c->st))
+            return fail(c, POSS_E_INVALID_ARG, "sampling: vocabulary too large for the sampler");
+    } else {
+        launch_argmax(c->logits, ld, rows, c->cfg.vocab, c->topk_scratch, c->argmax_dev, c->st);
+    }
     return POSS_OK;
 }
 
@@ -696,7 +719,7 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     RowMeta rm{c->td.pos, c->tree_slot, c->td.mask};
     target_forward(c, n, c->td.token, rm, t, n);
     GemmShape g = run_head(c, n);
-    launch_argmax(c->logits, g.Npad, n, cf.vocab, c->topk_scratch, c->argmax_dev, c->st);
+    { int rc = choose_tokens(c, g.Npad, n, c->td.depth); if (rc) return rc; }
     (void)hipEventRecord(c->ev[3], c->st);
     c->ev_pending[1] = true;
     if (logits_out) launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
@@ -739,6 +762,20 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
     if (committed_out) for (int j = 0; j <= m; ++j) committed_out[j] = toks[j];
     if (n_committed_out) *n_committed_out = m + 1;
     c->state = ST_READY; c->tree_ready = 0;
+    return POSS_OK;
+}
+
+int poss_set_sampling(poss_ctx *c, float temperature, const float *u, int32_t n_u) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (!(temperature >= 0.f)) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: temperature must be >= 0");
+    if (temperature > 0.f) {
+        if (!u || n_u < 1 || n_u > POSS_MAX_DEPTH + 1) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: needs 1..%d uniform numbers", POSS_MAX_DEPTH + 1);
+        for (int i = 0; i < n_u; ++i)
+            if (!(u[i] >= 0.f && u[i] < 1.f)) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: u[%d] is not in [0, 1)", i);
+        HIP_TRY(c, hipStreamSynchronize(c->st));           // a queued verification may still read the staging array
+        for (int i = 0; i <= POSS_MAX_DEPTH; ++i) c->u_pinned[i] = i < n_u ? u[i] : u[n_u - 1];
+    }
+    c->temperature = temperature;
     return POSS_OK;
 }
 

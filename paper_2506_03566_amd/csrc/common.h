@@ -109,6 +109,12 @@ void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *to
 void launch_rope_table(const int32_t *pos, const double *inv_freq, int half, int rows, float2 *cs, hipStream_t st);
 size_t argmax_scratch_floats(int rows, int vocab);
 void launch_argmax(const float *logits, int ld, int rows, int vocab, float *scratch, int32_t *out, hipStream_t st);
+// Temperature sampling: out[r] = first id whose cumulative probability under softmax(logits[r] / temperature)
+// exceeds u_by_depth[depth ? depth[r] : 0] (DEVICE arrays).  Returns false (nothing launched) for temperature <= 0
+// or a vocabulary beyond 4M entries.
+size_t sample_scratch_floats(int rows, int vocab);
+bool launch_sample(const float *logits, int ld, int rows, int vocab, float temperature, const float *u_by_depth,
+                   const int32_t *depth, float *scratch, int32_t *out, hipStream_t st);
 void launch_copy_rows_f32(const float *src, int ld_src, float *dst, int ld_dst, int rows, int cols,
                           hipStream_t st);
 

@@ -96,6 +96,117 @@ void launch_argmax(const float *logits, int ld, int rows, int vocab, float *scra
     hipLaunchKernelGGL(argmax_merge_kernel, dim3(rows), dim3(64), 0, st, pv, pi, n_seg, out);
 }
 
+// ------------------------------------------------------------------ temperature sampling per row
+// The token after a row is drawn from softmax(logits / T) by inverse CDF in vocabulary order: the first
+// id whose cumulative probability exceeds u.  Stage 1: per (segment, row) the maximum and the sum of
+// exp((l - max) / T).  Stage 2: one workgroup per row picks the segment in which u * Z falls, then the
+// id inside it.  All sums run in a fixed order: the same inputs give the same token on every run.
+constexpr int SAMPLE_SEG = 4096, SAMPLE_PER_THREAD = SAMPLE_SEG / 256;
+constexpr int SAMPLE_MAX_SEGS = 1024;
+
+__global__ __launch_bounds__(256) void sample_seg_kernel(const float *__restrict__ logits, int ld, int vocab, int n_seg,
+                                                         float inv_t, float *__restrict__ pm, float *__restrict__ pe) {
+    __shared__ float red[17];
+    const int seg = blockIdx.x, rowi = blockIdx.y;
+    const float *row = logits + (size_t)rowi * ld;
+    const int i0 = seg * SAMPLE_SEG + threadIdx.x * SAMPLE_PER_THREAD;       // a contiguous run per thread
+    float v[SAMPLE_PER_THREAD], mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < SAMPLE_PER_THREAD; ++j) {
+        v[j] = i0 + j < vocab ? row[i0 + j] : -INFINITY;
+        mx = fmaxf(mx, v[j]);
+    }
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float se = 0.f;
+#pragma unroll
+    for (int j = 0; j < SAMPLE_PER_THREAD; ++j) se += v[j] > -INFINITY ? expf((v[j] - mx) * inv_t) : 0.f;
+    se = block_sum(se, red);
+    if (threadIdx.x == 0) { pm[rowi * n_seg + seg] = mx; pe[rowi * n_seg + seg] = se; }
+}
+
+__global__ __launch_bounds__(256) void sample_pick_kernel(const float *__restrict__ logits, int ld, int vocab, int n_seg,
+                                                          float inv_t, const float *__restrict__ pm,
+                                                          const float *__restrict__ pe, const float *__restrict__ u_by_depth,
+                                                          const int32_t *__restrict__ depth, int32_t *__restrict__ out) {
+    __shared__ float w[SAMPLE_MAX_SEGS];
+    __shared__ float tsum[256];
+    __shared__ float red[17];
+    __shared__ int s_seg, s_first, s_last;
+    __shared__ float s_rest;
+    const int rowi = blockIdx.x, tid = threadIdx.x;
+    const float u = u_by_depth[depth ? depth[rowi] : 0];
+    float mx = -INFINITY;
+    for (int s = tid; s < n_seg; s += 256) mx = fmaxf(mx, pm[rowi * n_seg + s]);
+    mx = wave_max(mx);
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    for (int s = tid; s < n_seg; s += 256) {
+        const float m = pm[rowi * n_seg + s];
+        w[s] = m > -INFINITY ? pe[rowi * n_seg + s] * expf((m - mx) * inv_t) : 0.f;
+    }
+    __syncthreads();
+    if (tid == 0) {                                       // at most a few dozen segments: one thread, fixed order
+        float z = 0.f;
+        for (int s = 0; s < n_seg; ++s) z += w[s];
+        const float target = u * z;
+        float cum = 0.f;
+        int pick = -1, last = 0;
+        for (int s = 0; s < n_seg; ++s) {
+            if (w[s] > 0.f) last = s;
+            if (pick < 0 && cum + w[s] > target) { pick = s; s_rest = target - cum; }
+            if (pick < 0) cum += w[s];
+        }
+        if (pick < 0) { pick = last; s_rest = INFINITY; }  // rounding pushed u * Z past the total: last id with mass
+        s_seg = pick; s_first = 0x7fffffff; s_last = -1;
+    }
+    __syncthreads();
+    const int seg = s_seg;
+    const float rest = s_rest;
+    const float *row = logits + (size_t)rowi * ld;
+    const int i0 = seg * SAMPLE_SEG + tid * SAMPLE_PER_THREAD;
+    float x[SAMPLE_PER_THREAD], ts = 0.f;
+#pragma unroll
+    for (int j = 0; j < SAMPLE_PER_THREAD; ++j) {
+        x[j] = i0 + j < vocab ? expf((row[i0 + j] - mx) * inv_t) : 0.f;
+        ts += x[j];
+    }
+    tsum[tid] = ts;
+    __syncthreads();
+    float before = 0.f;                                   // mass of the threads before this one, summed in order
+    for (int t = 0; t < tid; ++t) before += tsum[t];
+    int mine = 0x7fffffff, last_mass = -1;
+    float cum = before;
+#pragma unroll
+    for (int j = 0; j < SAMPLE_PER_THREAD; ++j) {
+        if (x[j] > 0.f) last_mass = i0 + j;
+        cum += x[j];
+        if (mine == 0x7fffffff && cum > rest) mine = i0 + j;
+    }
+    if (mine != 0x7fffffff) atomicMin(&s_first, mine);
+    if (last_mass >= 0) atomicMax(&s_last, last_mass);
+    __syncthreads();
+    // nothing crossed (rounding pushed the target past the segment's mass): the last id with mass in the segment
+    if (tid == 0) out[rowi] = s_first != 0x7fffffff ? s_first : (s_last >= 0 ? s_last : 0);
+}
+
+size_t sample_scratch_floats(int rows, int vocab) { return (size_t)2 * rows * ((vocab + SAMPLE_SEG - 1) / SAMPLE_SEG); }
+
+bool launch_sample(const float *logits, int ld, int rows, int vocab, float temperature, const float *u_by_depth,
+                   const int32_t *depth, float *scratch, int32_t *out, hipStream_t st) {
+    const int n_seg = (vocab + SAMPLE_SEG - 1) / SAMPLE_SEG;
+    if (n_seg > SAMPLE_MAX_SEGS || !(temperature > 0.f)) return false;
+    float *pm = scratch, *pe = scratch + (size_t)rows * n_seg;
+    const float inv_t = 1.0f / temperature;
+    hipLaunchKernelGGL(sample_seg_kernel, dim3(n_seg, rows), dim3(256), 0, st, logits, ld, vocab, n_seg, inv_t, pm, pe);
+    hipLaunchKernelGGL(sample_pick_kernel, dim3(rows), dim3(256), 0, st, logits, ld, vocab, n_seg, inv_t, pm, pe, u_by_depth,
+                       depth, out);
+    return true;
+}
+
 __global__ void copy_rows_f32_kernel(const float *__restrict__ src, int ld_src, float *__restrict__ dst, int ld_dst,
                                      int cols) {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;

@@ -113,3 +113,33 @@ def test_full_size_sampled_parity_and_losslessness(name, layer, n_ar):
     st = ctx.stats()
     assert st.rounds >= 1 and st.committed_tokens == len(spec) - 1
     ctx.close()
+
+
+def test_sampler_at_full_vocabulary():
+    """Temperature sampling over the 128256-entry vocabulary of the benchmark shape: drawn tokens
+    of sampled tree rows against the float64 inverse CDF of the library's own logits."""
+    from oracle.sampling import cdf_interval, sample_token
+    cfg = get_config("c1_llama3_8b_3x2", n_prompt=64)
+    dev = make_weights_on_device(cfg)
+    ctx = P.Poss(cfg, dev)
+    del dev
+    torch.cuda.empty_cache()
+    ctx.prefill(make_prompt(cfg))
+    d = ctx.draft_tree().as_dict()
+    u = np.random.default_rng(7).random(cfg.depth + 1).astype(np.float32)
+    logits = torch.zeros(d["n"], cfg.vocab, device="cuda")
+    same = 0
+    rows = [0, 1, 2, 11, 30, d["n"] - 1]
+    for T in (1.0, 0.8):
+        ctx.set_sampling(T, u)
+        g = ctx.verify_tree(None, logits_out=logits)[:d["n"]]
+        lg = logits[rows].cpu().numpy().astype(np.float64)
+        for j, r in enumerate(rows):
+            ur = float(u[d["depth"][r]])
+            lo, hi = cdf_interval(lg[j], T, int(g[r]))
+            assert lo - 3e-5 <= ur < hi + 3e-5, (T, r, int(g[r]), ur, lo, hi)
+            same += int(g[r]) == sample_token(lg[j], T, ur)
+        ctx.accept_and_commit()
+        ctx.draft_tree(want_tree=True)
+    _say(f"  {same}/{2 * len(rows)} draws identical to the float64 inverse CDF")
+    ctx.close()
