@@ -45,6 +45,7 @@ struct GemmShape {
     int N, K;       // logical sizes
     int Npad, Kpad; // padded sizes of the packed weight
     int S;          // K splits (chunks dealt out evenly); partial sums land in part[S][Mpad][Npad]
+    int wpb;        // waves per workgroup the plan assumes: 4 (128 columns) or 6 (192 columns)
     int Mpad;       // rows of one partial plane (row stride Npad)
 };
 GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs);
