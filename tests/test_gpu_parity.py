@@ -133,6 +133,21 @@ def test_verify_logits_features_and_cache(name):
     pair.close()
 
 
+@pytest.mark.parametrize("gemm_wgs,attn_keys", [(32, 64), (1024, 64), (64, 1024), (2048, 96)])
+def test_verify_parity_with_other_launch_shapes(gemm_wgs, attn_keys):
+    """Other K-split counts (down to unsplit, up to the cap of two chunks per split) and other
+    attention splits (many small ones with a merge, a single unsplit walk): same tolerance."""
+    pair = Pair("t_mid_bf16")
+    cfg = pair.cfg
+    pair.ctx.set_tuning(gemm_wgs, attn_keys)
+    o, first, tr, g, logits, feats, og, ologits, ofeats = _verify_both(pair, make_prompt(cfg))
+    tol = tol_for(cfg)
+    err = np.abs(logits - ologits).max()
+    _say(f"  target workgroups {gemm_wgs}, keys per split {attn_keys}: max|dlogit| = {err:.3e}")
+    assert err <= tol
+    pair.close()
+
+
 def test_verify_is_bitwise_repeatable_and_layout_independent():
     name = "t_mid_bf16"
     cfg = get_config(name)
