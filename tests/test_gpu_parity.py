@@ -153,8 +153,8 @@ def test_verify_is_bitwise_repeatable_and_layout_independent():
     cfg = get_config(name)
     prompt = make_prompt(cfg)
     outs = []
-    for order in (0, 0, 1):
-        pair = Pair(name, kv_page_order=order)
+    for order, page in ((0, 64), (0, 64), (1, 64), (0, 32), (1, 128)):
+        pair = Pair(name, kv_page_order=order, kv_page_tokens=page)
         pair.ctx.prefill(prompt)
         tr = pair.ctx.draft_tree()
         logits = torch.zeros(tr.n, cfg.vocab, device="cuda")
@@ -164,7 +164,7 @@ def test_verify_is_bitwise_repeatable_and_layout_independent():
     for a in outs[1:]:
         assert a[0]["token"] == outs[0][0]["token"] and a[0]["parent"] == outs[0][0]["parent"]
         assert np.array_equal(a[1], outs[0][1])
-        assert np.array_equal(a[2], outs[0][2])          # same bits, also with reversed physical pages
+        assert np.array_equal(a[2], outs[0][2])          # same bits, also with reversed physical pages and other page sizes
 
 
 # --------------------------------------------------------------------------- acceptance with injected trees
