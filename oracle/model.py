@@ -119,7 +119,9 @@ def specialist_pass(W, cfg, s, tokens, feats, pos, allowed, q_rows, act=None):
     Q = lambda x: round_storage(x, act)
     p = f"spec{s}."
     x = np.concatenate([W("embed")[np.asarray(tokens, dtype=np.int64)], Q(np.asarray(feats))], axis=1)
-    h0 = x @ W(p + "fc_w").T + W(p + "fc_b")
+    h0 = x @ W(p + "fc_w").T
+    if cfg.fc_bias:                      # the draft model's fc layer has a bias in the paper's configuration (appendix B)
+        h0 = h0 + W(p + "fc_b")
     z = np.zeros((0, cfg.n_kv_heads, cfg.head_dim))
     out, _, _ = decoder_layer(W, p, cfg, h0, np.asarray(pos), z, z, allowed, act, q_rows=q_rows)
     return out
@@ -132,7 +134,9 @@ def specialist_kv(W, cfg, s, tokens, feats, pos, act=None):
     p = f"spec{s}."
     n = len(tokens)
     x = np.concatenate([W("embed")[np.asarray(tokens, dtype=np.int64)], Q(np.asarray(feats))], axis=1)
-    h0 = x @ W(p + "fc_w").T + W(p + "fc_b")
+    h0 = x @ W(p + "fc_w").T
+    if cfg.fc_bias:                      # the draft model's fc layer has a bias in the paper's configuration (appendix B)
+        h0 = h0 + W(p + "fc_b")
     u = Q(rmsnorm(h0, W(p + "attn_norm"), cfg.rms_eps))
     k = Q(rope((u @ W(p + "wk").T).reshape(n, cfg.n_kv_heads, cfg.head_dim), np.asarray(pos), cfg.rope_theta))
     v = Q((u @ W(p + "wv").T).reshape(n, cfg.n_kv_heads, cfg.head_dim))

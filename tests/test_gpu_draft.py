@@ -242,3 +242,22 @@ def test_duplicated_head_rows_order_equal_logits_by_id():
         ctx.accept_and_commit()
     assert pairs_seen > 0
     pair.close()
+
+
+def test_fc_bias_flag_off_ignores_the_bias_tensor():
+    """fc_bias = 0: both sides must leave the bias tensor out even when it holds values."""
+    cfg = get_config("c0_tiny_f32", fc_bias=0)
+    st = make_weights(get_config("c0_tiny_f32"))             # generated WITH non-zero biases
+    assert np.abs(to_float64(st["spec0.fc_b"], cfg.dtype)).max() > 0
+    pair = Pair("c0_tiny_f32", storage=st, fc_bias=0)
+    with_bias = Pair("c0_tiny_f32", storage=st)
+    prompt = make_prompt(cfg, n=18)
+    o = pair.oracle()
+    assert pair.ctx.prefill(prompt) == o.prefill(prompt) == with_bias.ctx.prefill(prompt)
+    d, ot = pair.ctx.draft_tree().as_dict(), o.draft_tree()
+    db = with_bias.ctx.draft_tree().as_dict()
+    assert np.abs(d["score"] - np.array(ot.score, dtype=np.float32)).max() < 1e-4
+    if min(o.margins) > 2e-5:
+        assert d["token"] == ot.token and d["parent"] == ot.parent
+    assert not np.array_equal(d["score"], db["score"])        # the bias does change the draft
+    pair.close(); with_bias.close()
