@@ -261,3 +261,51 @@ def test_fc_bias_flag_off_ignores_the_bias_tensor():
         assert d["token"] == ot.token and d["parent"] == ot.parent
     assert not np.array_equal(d["score"], db["score"])        # the bias does change the draft
     pair.close(); with_bias.close()
+
+
+@pytest.mark.parametrize("over,n_prompt", [
+    (dict(top_k=1, depth=1, total_tokens=1), 1),               # smallest everything: one-token prompt, one draft token
+    (dict(top_k=1, depth=6, total_tokens=6), 2),               # a chain
+    (dict(top_k=2, depth=2, total_tokens=6), 5),               # the tree keeps the whole candidate pool
+    (dict(top_k=16, depth=5, total_tokens=127), 40),           # 128 rows in verification, widest top-k, pool of 1040
+    (dict(top_k=6, depth=16, total_tokens=100, n_specialists=3, positions_per_specialist=2), 33),   # deepest tree; depth > S*n
+])
+def test_degenerate_and_maximal_tree_shapes(over, n_prompt):
+    """Smallest and largest tree parameters the library accepts, in float32, lock-step with the
+    oracle (large candidate pools always hold a pair of scores closer than float32 resolves):
+    structure exact as a function of the library's parents, scores within 1e-4 of the oracle's
+    re-scoring, identical tree whenever every decision margin is clear, kept set as good as the
+    oracle's otherwise; greedy tokens equal where the margin is clear; walk and stream equal."""
+    pair = Pair("c0_tiny_f32", **over)
+    cfg, ctx, o = pair.cfg, pair.ctx, pair.oracle()
+    prompt = make_prompt(cfg, n=n_prompt)
+    assert ctx.prefill(prompt) == o.prefill(prompt)
+    identical = 0
+    for rnd in range(3):
+        otree, d = tree_from_gpu(ctx.draft_tree())
+        t = o.t
+        assert d["n"] == cfg.total_tokens + 1 and validate_tree(d["token"], d["parent"])
+        otree.finish(t)
+        assert d["depth"] == otree.depth and d["pos"] == otree.pos and d["mask"] == otree.mask
+        score, _ = o.score_tree(otree)
+        assert np.abs(score - d["score"].astype(np.float64)).max() < 1e-4
+        n_marg = len(o.margins)
+        own = o.draft_tree()
+        if min(o.margins[n_marg:]) > 2e-5:
+            assert d["token"] == own.token and d["parent"] == own.parent, f"round {rnd}"
+            identical += 1
+        else:
+            assert score[1:].min() >= min(float(x) for x in own.score[1:]) - 1e-4
+        g = ctx.verify_tree()[:d["n"]]
+        og, ologits, _ = o.verify_tree(otree)
+        for i in range(otree.n):
+            top2 = np.partition(ologits[i], -2)[-2:]
+            if top2[1] - top2[0] > 2e-5:
+                assert g[i] == og[i]
+        path, m, toks = ctx.accept_and_commit()
+        wpath, wbonus = accept_walk(d["token"], d["parent"], g.tolist())
+        assert path == wpath and toks[-1] == wbonus
+        o.accept_and_commit(path=path, bonus=toks[-1])
+        assert ctx.tokens() == o.tokens
+    _say(f"  {over}: {identical}/3 rounds with an identical tree")
+    pair.close()
