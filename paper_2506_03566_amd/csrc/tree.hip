@@ -246,38 +246,59 @@ constexpr int POOL_MAX = 2048;
 __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int pool_n, int n_keep, int t,
                                                              const int32_t *__restrict__ tokens_dev) {
     __shared__ float sc[POOL_MAX];
-    __shared__ int16_t new_idx[POOL_MAX];
-    const int tid = threadIdx.x;
-    for (int i = tid; i < pool_n; i += blockDim.x) sc[i] = td.pool_score[i];
+    __shared__ int16_t par[POOL_MAX];                 // candidate -> parent candidate (-1: the root)
+    __shared__ int16_t new_idx[POOL_MAX];             // candidate -> node index in the tree, -1 if dropped
+    __shared__ int wave_cnt[2 * 16];                  // kept candidates per (pass, wave)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < pool_n; i += 1024) { sc[i] = td.pool_score[i]; par[i] = (int16_t)td.pool_parent[i]; }
     __syncthreads();
-    for (int i = tid; i < pool_n; i += blockDim.x) {
-        const float s = sc[i];
-        int rank = 0;
-        for (int j = 0; j < pool_n; ++j) rank += (sc[j] > s) || (sc[j] == s && j < i);
-        new_idx[i] = rank < n_keep ? 1 : 0;
+    // rank by counting; node index = 1 + number of kept candidates before this one (candidate order is
+    // kept, so parents come first), from wave ballots instead of a serial scan
+    bool keep[2];
+    int before[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int i = tid + p * 1024;
+        keep[p] = false;
+        if (i < pool_n) {
+            const float s = sc[i];
+            int rank = 0;
+            for (int j = 0; j < pool_n; ++j) rank += (sc[j] > s) || (sc[j] == s && j < i);
+            keep[p] = rank < n_keep;
+        }
+        const unsigned long long b = __ballot(keep[p]);
+        before[p] = __popcll(b & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_cnt[p * 16 + wave] = __popcll(b);
     }
     __syncthreads();
-    if (tid == 0) {                                  // running count -> node index (pool_n <= 2048)
-        int c = 0;
-        for (int i = 0; i < pool_n; ++i) new_idx[i] = new_idx[i] ? (int16_t)(++c) : (int16_t)-1;
-        td.n_nodes[0] = c + 1;
+    int total = 0;
+    for (int w = 0; w < 32; ++w) total += wave_cnt[w];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int i = tid + p * 1024;
+        int off = 0;
+        for (int w = 0; w < p * 16 + wave; ++w) off += wave_cnt[w];
+        if (i < pool_n) new_idx[i] = keep[p] ? (int16_t)(off + before[p] + 1) : (int16_t)-1;
+    }
+    if (tid == 0) {
+        td.n_nodes[0] = total + 1;
         td.token[0] = tokens_dev[t]; td.parent[0] = -1; td.depth[0] = 0; td.pos[0] = t; td.score[0] = 0.f;
         td.mask[0] = 1ull; td.mask[1] = 0ull;
     }
     __syncthreads();
-    for (int i = tid; i < pool_n; i += blockDim.x) {
+    for (int i = tid; i < pool_n; i += 1024) {
         const int ni = new_idx[i];
         if (ni < 0) continue;
-        const int pp = td.pool_parent[i];
+        const int pp = par[i], dep = td.pool_depth[i];
         td.token[ni] = td.pool_token[i];
         td.parent[ni] = pp < 0 ? 0 : new_idx[pp];
-        td.depth[ni] = td.pool_depth[i];
-        td.pos[ni] = t + td.pool_depth[i];
+        td.depth[ni] = dep;
+        td.pos[ni] = t + dep;
         td.score[ni] = sc[i];
         uint64_t w0 = 1ull, w1 = 0ull;               // the root
-        for (int u = i; u >= 0; u = td.pool_parent[u]) {
-            const int b = new_idx[u];
-            if (b < 64) w0 |= 1ull << b; else w1 |= 1ull << (b - 64);
+        for (int u = i; u >= 0; u = par[u]) {
+            const int bit = new_idx[u];
+            if (bit < 64) w0 |= 1ull << bit; else w1 |= 1ull << (bit - 64);
         }
         td.mask[ni * MASK_WORDS] = w0;
         td.mask[ni * MASK_WORDS + 1] = w1;
