@@ -247,3 +247,37 @@ def test_tree_builder_bit_exact(name, ties):
         assert np.array_equal(d_["score"], np.array(ot.score, dtype=np.float32))
         assert d_["mask"] == ancestor_masks(d_["parent"])
     pair.close()
+
+
+def test_two_contexts_on_their_own_streams_give_the_default_stream_result():
+    """The library queues everything on the stream given at load.  Two contexts on two streams,
+    driven in turn, must each reproduce bit for bit what a context on the default stream gives."""
+    name = "t_mid_bf16"
+    cfg = get_config(name)
+    prompt = make_prompt(cfg)
+
+    def run(pairs):
+        outs = []
+        for p in pairs:
+            p.ctx.prefill(prompt)
+        trees = [p.ctx.draft_tree() for p in pairs]
+        bufs = [torch.zeros(tr.n, cfg.vocab, device="cuda") for tr in trees]
+        torch.cuda.synchronize()                              # torch filled the buffers on its own stream
+        gs = [p.ctx.verify_tree(None, logits_out=b) for p, b in zip(pairs, bufs)]
+        res = [p.ctx.accept_and_commit() for p in pairs]
+        torch.cuda.synchronize()
+        for tr, g, b, r in zip(trees, gs, bufs, res):
+            outs.append((tr.as_dict()["token"], g[:tr.n].tolist(), b.cpu().numpy(), r))
+        return outs
+
+    ref_pair = Pair(name)
+    ref = run([ref_pair])[0]
+    ref_pair.close()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    a, b = Pair(name, lib_over=dict(stream=s1)), Pair(name, lib_over=dict(stream=s2))
+    torch.cuda.synchronize()
+    for got in run([a, b]):
+        assert got[0] == ref[0] and got[1] == ref[1] and got[3] == ref[3]
+        assert np.array_equal(got[2], ref[2])
+    a.close(); b.close()
