@@ -1,7 +1,7 @@
 /* poss.h - C ABI of the MI355X (gfx950) PosS draft-and-verify library.
  *
  * One round of position-specialist speculative decoding (arXiv 2506.03566) at
- * batch 1 under greedy verification:
+ * batch 1, under greedy verification or, after poss_set_sampling, at a temperature:
  *
  *   poss_load -> poss_prefill -> ( poss_draft_tree -> poss_verify_tree
  *                                  -> poss_accept_and_commit )*
@@ -10,7 +10,8 @@
  * are plain addresses; each argument says whether it is HOST or DEVICE memory.
  * The library never allocates device memory: weights, the workspace and the
  * stream belong to the caller.  Calls enqueue work on the stream given to
- * poss_load and block only to hand back their (small) host outputs.
+ * poss_load and wait for it only to hand back host outputs: a round whose draft and
+ * verify calls ask for none waits once, in poss_accept_and_commit.
  *
  * Every function returning int returns POSS_OK (0) or a negative POSS_E_*
  * code; a failing call leaves the context as it was and poss_last_error()
