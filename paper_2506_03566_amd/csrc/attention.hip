@@ -229,14 +229,19 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
             m_run[rt] = m_new;
             rescale = rescale || __builtin_amdgcn_ballot_w64(alpha[rt] != 1.f) != 0;   // rare once the maximum has settled
         }
+        if (rescale) {                                   // wave-uniform: a real branch, taken rarely
+            asm volatile("" ::: "memory");               // (keeps the compiler from turning it into 64 selects)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) acc[rt][dt] *= alpha[rt];
+        }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             const u32x4 vf = *reinterpret_cast<const u32x4 *>(&vbuf[(dt * 16 + lr) * VROW + lg * 8]);
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
-                if (rescale) acc[rt][dt] *= alpha[rt];
+            for (int rt = 0; rt < RT; ++rt)
                 acc[rt][dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf), pf[rt], acc[rt][dt]);
-            }
         }
         }
         store_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, buf ^ 1);
