@@ -139,7 +139,11 @@ def main():
     if args.gemm_wgs or args.attn_split:
         ctx.set_tuning(args.gemm_wgs, args.attn_split)
     prompt = make_prompt(cfg)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     ctx.prefill(prompt)
+    torch.cuda.synchronize()
+    t_prefill = time.perf_counter() - t0
 
     import numpy as np
     u_rng = np.random.default_rng(0)
@@ -198,7 +202,7 @@ def main():
                phase_ms=dict(draft=round((s1.ms_draft - base[2]) / rounds, 4),
                              verify=round((s1.ms_verify - base[3]) / rounds, 4),
                              commit=round((s1.ms_commit - base[4]) / rounds, 4)),
-               setup_s=dict(weights=round(t_gen, 1)), roofline=roofline)
+               setup_s=dict(weights=round(t_gen, 1), prefill=round(t_prefill, 3)), roofline=roofline)
     # Plain autoregressive decoding of the same target through the same library: rounds whose tree is the
     # root alone (one target pass over one row, one committed token).  The denominator of the paper's
     # speed-up ratio (Table 2); measured, while the ratio at the paper's tau stays a projection.
