@@ -287,8 +287,7 @@ void run_layer(poss_ctx *c, const LayerW &w, const KVCache &kv, int rows_all, in
 void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowMeta &rm, int n_prefix,
                     int region_len) {
     const ModelDims &md = c->md;
-    launch_rope_table(rm.pos, c->inv_freq, md.dh / 2, rows, c->cs, c->st);
-    launch_embed_norm(md, c->embed, tokens_dev, rows, c->layers[0].attn_norm, c->h, c->u, c->st);
+    launch_embed_norm(md, c->embed, tokens_dev, rows, c->layers[0].attn_norm, c->h, c->u, rm.pos, c->inv_freq, c->cs, c->st);
     const int nl = c->cfg.n_layers;
     for (int l = 0; l < nl; ++l) {
         if (c->taps_user)
@@ -340,8 +339,7 @@ void spec_pass(poss_ctx *c, int s, const DraftRowPlan &plan, int depth_index, in
     const ModelDims &md = c->md;
     const SpecW &w = c->specs[s];
     launch_draft_assemble(md, plan, depth_index, c->cfg.top_k, c->embed, c->tokens_dev, c->feat_stash, c->td,
-                          fhat_prev, c->xin_tmp, c->xin, c->row_pos, c->row_slot, c->row_mask, c->st);
-    launch_rope_table(c->row_pos, c->inv_freq, md.dh / 2, plan.n_rows, c->cs, c->st);
+                          fhat_prev, c->xin_tmp, c->xin, c->row_pos, c->row_slot, c->row_mask, c->inv_freq, c->cs, c->st);
     run_gemm(c, w.fc_w, md.d, 2 * md.d, c->xin, 2 * md.d, plan.n_rows, c->part, false,
              epi_residual(c, false, c->cfg.fc_bias ? w.fc_b : nullptr, nullptr, w.layer.attn_norm));
     RowMeta rm{c->row_pos, c->row_slot, c->row_mask};

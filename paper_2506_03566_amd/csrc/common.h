@@ -104,10 +104,10 @@ bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int 
                  const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t after_stream = nullptr);
 
 // ---------------------------------------------------------------- launchers: elementwise
+// also writes the rotary table of the rows: cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)), angle formed in float64
 void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *tokens, int rows,
-                       const void *gain, float *h, void *u, hipStream_t st);
-// cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)), angle formed in float64
-void launch_rope_table(const int32_t *pos, const double *inv_freq, int half, int rows, float2 *cs, hipStream_t st);
+                       const void *gain, float *h, void *u, const int32_t *pos, const double *inv_freq,
+                       float2 *cs, hipStream_t st);
 size_t argmax_scratch_floats(int rows, int vocab);
 void launch_argmax(const float *logits, int ld, int rows, int vocab, float *scratch, int32_t *out, hipStream_t st);
 // Temperature sampling: out[r] = first id whose cumulative probability under softmax(logits[r] / temperature)
@@ -155,7 +155,8 @@ struct DraftRowPlan {
 void launch_draft_assemble(const ModelDims &md, const DraftRowPlan &plan, int depth_index, int k,
                            const void *embed, const int32_t *tokens_dev, const void *feat_stash,
                            const TreeDev &td, const float *fhat_prev, void *xin_tmp, void *x_out,
-                           int32_t *pos_out, int32_t *slot_out, uint64_t *mask_out, hipStream_t st);
+                           int32_t *pos_out, int32_t *slot_out, uint64_t *mask_out, const double *inv_freq,
+                           float2 *cs, hipStream_t st);     // also writes the rows' rotary table cs
 
 // ---------------------------------------------------------------- accept + commit
 void launch_tree_upload_finish(int n, int t, const int32_t *token, const int32_t *parent, int32_t *depth,

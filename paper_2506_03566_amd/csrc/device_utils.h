@@ -61,6 +61,18 @@ __device__ __forceinline__ void block_argmax(float &v, int &i, float *red_v, int
     v = red_v[16]; i = red_i[16];
 }
 
+// Rotary table of one row, by the first `half` threads of the row's workgroup:
+// cs[i] = (cos, sin)(pos * theta^(-2i/dh)).  The angle is formed in float64 so that positions in the
+// thousands keep float32-accurate sines; one table serves every layer of the pass.
+__device__ __forceinline__ void rope_table_row(int pos, const double *__restrict__ inv_freq, int half,
+                                               float2 *__restrict__ cs_row) {
+    const int i = threadIdx.x;
+    if (i >= half) return;
+    double s, c;
+    sincos((double)pos * inv_freq[i], &s, &c);
+    cs_row[i] = make_float2((float)c, (float)s);
+}
+
 // Element offsets into the paged caches.
 __device__ __forceinline__ size_t k_offset(const KVCache &kv, int slot, int head, int hkv, int dh) {
     const int P = 1 << kv.page_shift;

@@ -12,12 +12,17 @@ namespace poss {
     }
 
 // ------------------------------------------------------------------ h = emb[token]; u = T(rmsnorm(h) g)
+// (and the row's rotary table, which every layer of the pass uses)
 template <typename T>
 __global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ embed, const int32_t *__restrict__ tokens,
                                                          int d, float eps, const T *__restrict__ gain,
-                                                         float *__restrict__ h, T *__restrict__ u) {
+                                                         float *__restrict__ h, T *__restrict__ u,
+                                                         const int32_t *__restrict__ pos,
+                                                         const double *__restrict__ inv_freq, int half,
+                                                         float2 *__restrict__ cs) {
     __shared__ float red[17];
     const int row = blockIdx.x;
+    rope_table_row(pos[row], inv_freq, half, cs + (size_t)row * half);
     const T *e = embed + (size_t)tokens[row] * d;
     float ss = 0.f;
     for (int i = threadIdx.x; i < d; i += blockDim.x) {
@@ -32,26 +37,12 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ e
 }
 
 void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *tokens, int rows,
-                       const void *gain, float *h, void *u, hipStream_t st) {
+                       const void *gain, float *h, void *u, const int32_t *pos, const double *inv_freq,
+                       float2 *cs, hipStream_t st) {
     POSS_DISPATCH(md.dt, hipLaunchKernelGGL((embed_norm_kernel<T>), dim3(rows), dim3(256), 0, st,
                                             static_cast<const T *>(embed), tokens, md.d, md.eps,
-                                            static_cast<const T *>(gain), h, static_cast<T *>(u)));
-}
-
-// ------------------------------------------------------------------ rotary table of one pass
-// cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)).  The angle is formed in float64 so positions in
-// the thousands keep float32-accurate sines; one table serves every layer of the pass.
-__global__ void rope_table_kernel(const int32_t *__restrict__ pos, const double *__restrict__ inv_freq, int half,
-                                  float2 *__restrict__ cs) {
-    const int m = blockIdx.x, i = threadIdx.x;
-    if (i >= half) return;
-    double s, c;
-    sincos((double)pos[m] * inv_freq[i], &s, &c);
-    cs[m * half + i] = make_float2((float)c, (float)s);
-}
-
-void launch_rope_table(const int32_t *pos, const double *inv_freq, int half, int rows, float2 *cs, hipStream_t st) {
-    hipLaunchKernelGGL(rope_table_kernel, dim3(rows), dim3(half < 64 ? 64 : half), 0, st, pos, inv_freq, half, cs);
+                                            static_cast<const T *>(gain), h, static_cast<T *>(u), pos, inv_freq,
+                                            md.dh / 2, cs));
 }
 
 // ------------------------------------------------------------------ argmax per row (lowest index on ties)

@@ -318,8 +318,10 @@ __global__ __launch_bounds__(256) void draft_assemble_kernel(
     DraftRowPlan plan, int depth_index, int k, int d_model, const T *__restrict__ embed,
     const int32_t *__restrict__ tokens_dev, const T *__restrict__ feat_stash, TreeDev td,
     const float *__restrict__ fhat_prev, T *__restrict__ xin_tmp, T *__restrict__ x_out,
-    int32_t *__restrict__ pos_out, int32_t *__restrict__ slot_out, uint64_t *__restrict__ mask_out) {
+    int32_t *__restrict__ pos_out, int32_t *__restrict__ slot_out, uint64_t *__restrict__ mask_out,
+    const double *__restrict__ inv_freq, int half, float2 *__restrict__ cs) {
     const int row = blockIdx.x, kind = plan.kind[row], idx = plan.idx[row];
+    rope_table_row(plan.pos[row], inv_freq, half, cs + (size_t)row * half);    // the pass's rotary table, row by row
     T *dst = x_out + (size_t)row * 2 * d_model;
     uint64_t w0 = plan.mask0[0], w1 = plan.mask0[1];
     if (kind == 0) {                    // committed pair [x_{i+1} ; f_i]
@@ -351,11 +353,13 @@ __global__ __launch_bounds__(256) void draft_assemble_kernel(
 void launch_draft_assemble(const ModelDims &md, const DraftRowPlan &plan, int depth_index, int k,
                            const void *embed, const int32_t *tokens_dev, const void *feat_stash,
                            const TreeDev &td, const float *fhat_prev, void *xin_tmp, void *x_out,
-                           int32_t *pos_out, int32_t *slot_out, uint64_t *mask_out, hipStream_t st) {
+                           int32_t *pos_out, int32_t *slot_out, uint64_t *mask_out, const double *inv_freq,
+                           float2 *cs, hipStream_t st) {
 #define POSS_ASM(T)                                                                                          \
     hipLaunchKernelGGL((draft_assemble_kernel<T>), dim3(plan.n_rows), dim3(256), 0, st, plan, depth_index, k,   \
                        md.d, static_cast<const T *>(embed), tokens_dev, static_cast<const T *>(feat_stash), td, \
-                       fhat_prev, static_cast<T *>(xin_tmp), static_cast<T *>(x_out), pos_out, slot_out, mask_out)
+                       fhat_prev, static_cast<T *>(xin_tmp), static_cast<T *>(x_out), pos_out, slot_out, mask_out, \
+                       inv_freq, md.dh / 2, cs)
     if (md.dt == DT_F32) POSS_ASM(float); else if (md.dt == DT_BF16) POSS_ASM(bf16_t); else POSS_ASM(f16_t);
 #undef POSS_ASM
 }
