@@ -15,10 +15,11 @@ namespace poss {
 // Selection of the k best (value, index) pairs held NV per thread by a 256-thread workgroup.
 // block_topk_rounds: every wave extracts its own k best with shuffles only (no workgroup barrier
 // inside the k rounds), then wave 0 picks the k best of the 4k survivors.
-// block_topk: threshold first.  The k-th largest of the 256 per-thread maxima is a lower bound of
-// the k-th largest element, so every winner is among the elements >= that bound: a handful, ranked
-// by counting.  No chain of dependent shuffles; the rounds remain as the fallback for inputs with
-// more than TOPK_CAND elements above the bound (long runs of equal values).
+// block_topk: threshold first.  The k-th largest of any 64 of the per-thread maxima (one wave's) is a
+// lower bound of the k-th largest element; the largest of the four waves' bounds is used, so every
+// winner is among the elements >= it: a few dozen, ranked by counting.  No chain of dependent
+// shuffles; the rounds remain as the fallback for inputs with more than TOPK_CAND elements above
+// the bound (long runs of equal values).
 // Either way thread r < k ends up with the r-th best, (-inf, 0x7fffffff...) where fewer than k exist.
 constexpr int TOPK_SEG = 2048;
 constexpr int TOPK_MAXK = 16;
@@ -28,7 +29,7 @@ struct __attribute__((aligned(16))) TopkLds {
     float cand_v[TOPK_CAND]; int cand_i[TOPK_CAND];
     float out_v[TOPK_MAXK]; int out_i[TOPK_MAXK];
     float rounds_v[4 * TOPK_MAXK]; int rounds_i[4 * TOPK_MAXK];
-    float thr; int cnt;
+    float thr_w[4]; int cnt;
 };
 
 template <int NV>
@@ -67,21 +68,23 @@ __device__ __forceinline__ void block_topk(float (&v)[NV], int (&id)[NV], int k,
     float tm = -INFINITY;
 #pragma unroll
     for (int j = 0; j < NV; ++j) tm = fmaxf(tm, v[j]);
+    const int lane = tid & 63, wave = tid >> 6;
     L.tmax[tid] = tm;
-    if (tid == 0) { L.cnt = 0; L.thr = -INFINITY; }
+    if (tid == 0) L.cnt = 0;
+    if (tid < 4) L.thr_w[tid] = -INFINITY;
     if (tid < TOPK_MAXK) { L.out_v[tid] = -INFINITY; L.out_i[tid] = 0x7fffffff; }
     __syncthreads();
-    int rank = 0;                                         // of this thread's maximum, ties to the lower thread
-    for (int j = 0; j < 256; j += 4) {
-        const float4 o = *reinterpret_cast<const float4 *>(&L.tmax[j]);
-        rank += (o.x > tm) || (o.x == tm && j < tid);
-        rank += (o.y > tm) || (o.y == tm && j + 1 < tid);
-        rank += (o.z > tm) || (o.z == tm && j + 2 < tid);
-        rank += (o.w > tm) || (o.w == tm && j + 3 < tid);
+    int rank = 0;                                         // of this thread's maximum within its wave, ties to the lower lane
+    for (int j = 0; j < 64; j += 4) {
+        const float4 o = *reinterpret_cast<const float4 *>(&L.tmax[wave * 64 + j]);
+        rank += (o.x > tm) || (o.x == tm && j < lane);
+        rank += (o.y > tm) || (o.y == tm && j + 1 < lane);
+        rank += (o.z > tm) || (o.z == tm && j + 2 < lane);
+        rank += (o.w > tm) || (o.w == tm && j + 3 < lane);
     }
-    if (rank == k - 1) L.thr = tm;                        // exactly one thread
+    if (rank == k - 1) L.thr_w[wave] = tm;                // exactly one lane per wave (k <= 16 < 64)
     __syncthreads();
-    const float thr = L.thr;
+    const float thr = fmaxf(fmaxf(L.thr_w[0], L.thr_w[1]), fmaxf(L.thr_w[2], L.thr_w[3]));
 #pragma unroll
     for (int j = 0; j < NV; ++j)
         if (v[j] > -INFINITY && v[j] >= thr) {
