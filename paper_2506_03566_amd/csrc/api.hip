@@ -75,6 +75,7 @@ struct poss_ctx {
     bool ev_pending[3];
     bool launch_refused;               // a GEMM launch was refused on the host (null operand): internal error
     float temperature;                 // 0: greedy verification; > 0: the target's tokens are drawn (poss_set_sampling)
+    int32_t *result_pinned, *result_dev;   // the commit kernel's result: host memory and its device address
     float *u_pinned, *u_dev;           // one uniform number per tree depth, host staging and device copy                // phase recorded, elapsed time not yet added to the statistics
     int gemm_target_wgs, attn_keys_per_split;
     // gemm profiling
@@ -470,6 +471,8 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     LOAD_TRY(hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault));
     LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->u_pinned), (POSS_MAX_DEPTH + 1) * sizeof(float), hipHostMallocDefault));
     for (int i = 0; i <= POSS_MAX_DEPTH; ++i) c->u_pinned[i] = 0.f;
+    LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->result_pinned), 64 * sizeof(int32_t), hipHostMallocDefault));
+    LOAD_TRY(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->result_dev), c->result_pinned, 0));
     c->temperature = 0.f;
     {
         char *p = static_cast<char *>(c->pinned);
@@ -514,6 +517,7 @@ void poss_free(poss_ctx *c) {
     for (int i = 0; i < 2 * PROFILE_EVENTS; ++i) (void)hipEventDestroy(c->prof_ev[i]);
     (void)hipHostFree(c->pinned);
     (void)hipHostFree(c->u_pinned);
+    (void)hipHostFree(c->result_pinned);
     delete c;
 }
 
@@ -738,15 +742,11 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
     const poss_config &cf = c->cfg;
     const int t = c->t, L = cf.depth;
     (void)hipEventRecord(c->ev[4], c->st);
-    launch_accept_walk(c->td.token, c->td.parent, c->argmax_dev, c->td.n_nodes, L, c->walk_dev, c->st);
-    launch_commit(c->md, cf.n_layers, c->target_kv_dev, c->walk_dev, L, t, c->feats, c->feat_stash, c->tokens_dev,
-                  c->td.token, c->st);
+    launch_commit(c->md, cf.n_layers, c->target_kv_dev, c->td.token, c->td.parent, c->argmax_dev, c->td.n_nodes, L, t,
+                  c->feats, c->feat_stash, c->tokens_dev, c->walk_dev, c->result_dev, c->st);
     (void)hipEventRecord(c->ev[5], c->st);
     c->ev_pending[2] = true;
-    int32_t *walk = static_cast<int32_t *>(c->pinned);
-    int32_t *toks = walk + 32;
-    HIP_TRY(c, hipMemcpyAsync(walk, c->walk_dev, (L + 3) * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
-    HIP_TRY(c, hipMemcpyAsync(toks, c->tokens_dev + t + 1, (L + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
+    const int32_t *walk = c->result_pinned, *toks = walk + 32;     // written by the kernel itself
     { int rc = sync_and_harvest(c); if (rc) return rc; }
     const int m = walk[0];
     if (m < 0 || m > L) return fail(c, POSS_E_HIP, "poss_accept_and_commit: walk returned %d accepted tokens", m);

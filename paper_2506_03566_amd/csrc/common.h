@@ -45,7 +45,6 @@ struct GemmShape {
     int N, K;       // logical sizes
     int Npad, Kpad; // padded sizes of the packed weight
     int S;          // K splits (chunks dealt out evenly); partial sums land in part[S][Mpad][Npad]
-    int wpb;        // waves per workgroup the plan assumes: 4 (128 columns) or 6 (192 columns)
     int Mpad;       // rows of one partial plane (row stride Npad)
 };
 GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs);
@@ -162,11 +161,12 @@ void launch_draft_assemble(const ModelDims &md, const DraftRowPlan &plan, int de
 void launch_tree_upload_finish(int n, int t, const int32_t *token, const int32_t *parent, int32_t *depth,
                                int32_t *pos, int32_t *slot, uint64_t *mask, hipStream_t st);
 void launch_iota_slots(int n, int t, int32_t *slot, hipStream_t st);
-// walk: [0] = m, [1] = bonus token, [2..2+m] = node indices of the accepted path
-void launch_accept_walk(const int32_t *token, const int32_t *parent, const int32_t *g, const int32_t *n_nodes,
-                        int max_path, int32_t *walk, hipStream_t st);
-void launch_commit(const ModelDims &md, int n_layers, const KVCache *caches_dev, const int32_t *walk, int max_path,
-                   int t, const float *feats, void *feat_stash, int32_t *tokens_dev, const int32_t *tree_token,
+// One launch: the greedy walk over the verified tree, then KV compaction, feature stash and token
+// stream.  walk_dev / result: [0] = m, [1] = bonus token, [2..2+m] = node indices of the accepted
+// path; result[32 + j] = committed token j.  result must be host memory mapped into the device.
+void launch_commit(const ModelDims &md, int n_layers, const KVCache *caches_dev, const int32_t *tree_token,
+                   const int32_t *tree_parent, const int32_t *g, const int32_t *n_nodes, int max_path, int t,
+                   const float *feats, void *feat_stash, int32_t *tokens_dev, int32_t *walk_dev, int32_t *result,
                    hipStream_t st);
 
 void launch_read_kv(const ModelDims &md, const KVCache &kv, int slot0, int n, float *k_out, float *v_out,

@@ -61,13 +61,13 @@ __device__ __forceinline__ void block_argmax(float &v, int &i, float *red_v, int
     v = red_v[16]; i = red_i[16];
 }
 
-// Rotary table of one row, by the first `half` threads of the row's workgroup:
+// Rotary table of one row, by `half` threads of the row's workgroup starting at first_thread:
 // cs[i] = (cos, sin)(pos * theta^(-2i/dh)).  The angle is formed in float64 so that positions in the
 // thousands keep float32-accurate sines; one table serves every layer of the pass.
 __device__ __forceinline__ void rope_table_row(int pos, const double *__restrict__ inv_freq, int half,
-                                               float2 *__restrict__ cs_row) {
-    const int i = threadIdx.x;
-    if (i >= half) return;
+                                               float2 *__restrict__ cs_row, int first_thread = 0) {
+    const int i = (int)threadIdx.x - first_thread;
+    if (i < 0 || i >= half) return;
     double s, c;
     sincos((double)pos * inv_freq[i], &s, &c);
     cs_row[i] = make_float2((float)c, (float)s);

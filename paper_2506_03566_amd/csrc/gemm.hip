@@ -378,7 +378,6 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
     g.Npad = gemm_npad(N);
     g.Kpad = gemm_kpad(dt, K);
     g.Mpad = round_up(M < 1 ? 1 : M, 16);
-    g.wpb = 4;
     if (dt == DT_F32) { g.S = 1; return g; }
     g.Mpad = gemm_rows_written(g.Mpad);       // the kernel is instantiated for 1, 2, 4, 6 or 8 row tiles
     const int n_blocks = g.Npad / GEMM_BLOCK_N;
@@ -391,20 +390,11 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
     int max_s = n_chunks / 2; if (max_s < 1) max_s = 1;          // at least 512 of K per split
     if (S > max_s) S = max_s;
     if (S < 1) S = 1;
+    // The longest stream sets the time: take the fewest splits that keep it (16 chunks over 5 splits
+    // is 4 chunks on the busiest; 4 splits do the same with one partial plane less).
+    const int longest = (n_chunks + S - 1) / S;
+    S = (n_chunks + longest - 1) / longest;
     g.S = S;
-    g.wpb = 4;
-    // Six waves (192 columns) per workgroup where that deals the (tile, chunk) work out more evenly over the
-    // CUs: compare the wave-chunks the busiest workgroup gets (QKV of the 8B shape: 32 x 8 workgroups of
-    // 6 x 2 against 48 x 5 of 4 x 4).
-    if (g.Npad % (6 * GEMM_NT * 16) == 0) {
-        const int tiles6 = g.Npad / (6 * GEMM_NT * 16);
-        int S6 = target_wgs / tiles6;
-        if (S6 > max_s) S6 = max_s;
-        if (S6 >= 1) {
-            const int crit4 = ((n_chunks + S - 1) / S) * 4, crit6 = ((n_chunks + S6 - 1) / S6) * 6;
-            if (n_blocks * S <= 256 && tiles6 * S6 <= 256 && crit6 < crit4) { g.S = S6; g.wpb = 6; }
-        }
-    }
     return g;
 }
 
@@ -442,15 +432,14 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
                           const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream) {
     // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
     const bool fuse_silu = epi.mode == EPI_SILU && g.S == 1;
-    const bool six = !fuse_silu && g.wpb == 6;
-    const bool wide = !fuse_silu && !six && g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
-    const int wpb = wide ? 8 : six ? 6 : 4;
+    const bool wide = !fuse_silu && g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
+    const int wpb = wide ? 8 : 4;
     dim3 grid(g.Npad / (GEMM_NT * 16 * wpb), g.S), block(wpb * 64);
     const int ksteps = g.Kpad / GEMM_KSTEP;
     const u32x4 *w = static_cast<const u32x4 *>(Wp);
     const T *x = static_cast<const T *>(X);
     T *act = static_cast<T *>(epi.act);
-    const bool deep = !wide && !six && (int)(grid.x * grid.y) < 256;     // fewer workgroups than CUs: deeper weight ring
+    const bool deep = !wide && (int)(grid.x * grid.y) < 256;     // fewer workgroups than CUs: deeper weight ring
 #define POSS_GEMM_LAUNCH(MT, W, FUSE, PFV, FARG)                                                              \
     hipLaunchKernelGGL((gemm_stream_kernel<T, MT, W, FUSE, PFV>), grid, block, 0, st, w, x, ldx, part, g.M,   \
                        g.K, g.Npad, ksteps, act, FARG)
@@ -458,7 +447,6 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     do {                                                                                                      \
         if (fuse_silu) { if (deep) POSS_GEMM_LAUNCH(MT, 4, true, 8, epi.F); else POSS_GEMM_LAUNCH(MT, 4, true, 4, epi.F); } \
         else if (wide) POSS_GEMM_LAUNCH(MT, 8, false, 4, 0);                                                  \
-        else if (six) POSS_GEMM_LAUNCH(MT, 6, false, 4, 0);                                                   \
         else if (deep) POSS_GEMM_LAUNCH(MT, 4, false, 8, 0);                                                  \
         else POSS_GEMM_LAUNCH(MT, 4, false, 4, 0);                                                            \
     } while (0)

@@ -324,24 +324,56 @@ __global__ __launch_bounds__(256) void draft_assemble_kernel(
     int32_t *__restrict__ pos_out, int32_t *__restrict__ slot_out, uint64_t *__restrict__ mask_out,
     const double *__restrict__ inv_freq, int half, float2 *__restrict__ cs) {
     const int row = blockIdx.x, kind = plan.kind[row], idx = plan.idx[row];
-    rope_table_row(plan.pos[row], inv_freq, half, cs + (size_t)row * half);    // the pass's rotary table, row by row
+    // the pass's rotary table, row by row; by the last wave, which has the least copying to do
+    rope_table_row(plan.pos[row], inv_freq, half, cs + (size_t)row * half, half <= 64 ? (int)blockDim.x - 64 : 0);
     T *dst = x_out + (size_t)row * 2 * d_model;
     uint64_t w0 = plan.mask0[0], w1 = plan.mask0[1];
+    constexpr int VE = 16 / (int)sizeof(T);              // elements per 16-byte access
+    const bool vec = d_model % VE == 0;
+    const int nv = d_model / VE;
     if (kind == 0) {                    // committed pair [x_{i+1} ; f_i]
         const T *e = embed + (size_t)tokens_dev[idx + 1] * d_model, *f = feat_stash + (size_t)idx * d_model;
-        for (int i = threadIdx.x; i < d_model; i += blockDim.x) { dst[i] = e[i]; dst[d_model + i] = f[i]; }
+        if (vec) {
+            const uint4 *e4 = reinterpret_cast<const uint4 *>(e), *f4 = reinterpret_cast<const uint4 *>(f);
+            uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+            for (int i = threadIdx.x; i < nv; i += blockDim.x) { d4[i] = e4[i]; d4[nv + i] = f4[i]; }
+        } else {
+            for (int i = threadIdx.x; i < d_model; i += blockDim.x) { dst[i] = e[i]; dst[d_model + i] = f[i]; }
+        }
     } else if (kind == 1) {             // a frontier row of an earlier depth, as assembled then
         const T *src = xin_tmp + (size_t)idx * 2 * d_model;
-        for (int i = threadIdx.x; i < 2 * d_model; i += blockDim.x) dst[i] = src[i];
+        if (vec) {
+            const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
+            uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+            for (int i = threadIdx.x; i < 2 * nv; i += blockDim.x) d4[i] = s4[i];
+        } else {
+            for (int i = threadIdx.x; i < 2 * d_model; i += blockDim.x) dst[i] = src[i];
+        }
     } else {                            // new frontier row: [emb(token_v) ; drafted feature of parent(v)]
         const int o = depth_index * k + idx;
         const T *e = embed + (size_t)td.fr_token[o] * d_model;
         const float *f = fhat_prev + (size_t)td.fr_parent_rank[o] * d_model;
         T *keep = xin_tmp + (size_t)((depth_index - 1) * k + idx) * 2 * d_model;
-        for (int i = threadIdx.x; i < d_model; i += blockDim.x) {
-            const T ev = e[i], fv = from_f<T>(f[i]);
-            dst[i] = ev; dst[d_model + i] = fv;
-            keep[i] = ev; keep[d_model + i] = fv;
+        if (vec) {
+            const uint4 *e4 = reinterpret_cast<const uint4 *>(e);
+            uint4 *d4 = reinterpret_cast<uint4 *>(dst), *k4 = reinterpret_cast<uint4 *>(keep);
+            for (int i = threadIdx.x; i < nv; i += blockDim.x) {
+                const uint4 ev = e4[i];
+                union { uint4 q; T t[VE]; } fv;
+#pragma unroll
+                for (int j = 0; j < VE; j += 4) {
+                    const float4 x = *reinterpret_cast<const float4 *>(f + (size_t)i * VE + j);
+                    fv.t[j] = from_f<T>(x.x); fv.t[j + 1] = from_f<T>(x.y); fv.t[j + 2] = from_f<T>(x.z); fv.t[j + 3] = from_f<T>(x.w);
+                }
+                d4[i] = ev; d4[nv + i] = fv.q;
+                k4[i] = ev; k4[nv + i] = fv.q;
+            }
+        } else {
+            for (int i = threadIdx.x; i < d_model; i += blockDim.x) {
+                const T ev = e[i], fv = from_f<T>(f[i]);
+                dst[i] = ev; dst[d_model + i] = fv;
+                keep[i] = ev; keep[d_model + i] = fv;
+            }
         }
         w0 = td.fr_mask[o * MASK_WORDS]; w1 = td.fr_mask[o * MASK_WORDS + 1];
     }
@@ -397,12 +429,15 @@ void launch_iota_slots(int n, int t, int32_t *slot, hipStream_t st) {
     hipLaunchKernelGGL(iota_slots_kernel, dim3(1), dim3(128), 0, st, n, t, slot);
 }
 
-// ------------------------------------------------------------------ greedy acceptance walk
+// ------------------------------------------------------------------ greedy acceptance walk + commit
+// The walk (Eq. 4 with the tree's nodes as candidates): from the root, follow the child whose token
+// is the target's choice g at the current node, lowest node index first, until none matches.
 // walk[0] = m (accepted draft tokens), walk[1] = bonus token, walk[2..2+m] = node indices of the path.
-__global__ __launch_bounds__(64) void accept_walk_kernel(const int32_t *__restrict__ token, const int32_t *__restrict__ parent,
-                                                         const int32_t *__restrict__ g, const int32_t *__restrict__ n_nodes,
-                                                         int max_path, int32_t *__restrict__ walk) {
-    const int lane = threadIdx.x, n = n_nodes[0];
+// Run by the first wave of a workgroup into its own LDS copy: 60 nodes and at most max_path steps
+// cost less than a dependent launch, so every workgroup of the commit repeats it.
+__device__ __forceinline__ void accept_walk_wave(const int32_t *__restrict__ token, const int32_t *__restrict__ parent,
+                                                 const int32_t *__restrict__ g, int n, int max_path, int32_t *walk) {
+    const int lane = threadIdx.x;
     int cur = 0, m = 0;
     if (lane == 0) walk[2] = 0;
     while (m < max_path) {
@@ -419,60 +454,72 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const int32_t *__restri
     if (lane == 0) { walk[0] = m; walk[1] = g[cur]; }
 }
 
-void launch_accept_walk(const int32_t *token, const int32_t *parent, const int32_t *g, const int32_t *n_nodes,
-                        int max_path, int32_t *walk, hipStream_t st) {
-    hipLaunchKernelGGL(accept_walk_kernel, dim3(1), dim3(64), 0, st, token, parent, g, n_nodes, max_path, walk);
-}
-
-// ------------------------------------------------------------------ commit
-// Keys/values of the accepted rows move from slot t + path[j] to slot t + j.  A destination may be
-// another move's source, so each (layer, KV head) workgroup gathers everything, synchronises, scatters.
+// One launch commits a round.  Workgroups [0, n_layers * hkv): keys/values of the accepted rows of
+// one (layer, KV head) move from slot t + path[j] to slot t + j; a destination may be another
+// move's source, so the workgroup gathers everything, synchronises, scatters.  Workgroups after
+// those, one per path position j <= m: the feature of the accepted row becomes f_{t+j}, the accepted
+// token (the bonus token for j = m) joins the stream; they also write the result the host reads:
+// result[0..2+m] = the walk, result[32 + j] = committed token j.  `result` is host memory the device
+// can write, so no copy follows the kernel.
 template <typename T>
-__global__ __launch_bounds__(256) void commit_kv_kernel(const KVCache *__restrict__ caches, const int32_t *__restrict__ walk,
-                                                        int t, int hkv, int dh) {
+__global__ __launch_bounds__(256) void commit_kernel(const KVCache *__restrict__ caches, int n_kv_wgs, int hkv, int dh,
+                                                     const int32_t *__restrict__ tree_token,
+                                                     const int32_t *__restrict__ tree_parent,
+                                                     const int32_t *__restrict__ g, const int32_t *__restrict__ n_nodes,
+                                                     int max_path, int t, int d_model, const float *__restrict__ feats,
+                                                     T *__restrict__ feat_stash, int32_t *__restrict__ tokens_dev,
+                                                     int32_t *__restrict__ walk_dev, int32_t *__restrict__ result) {
     extern __shared__ unsigned char smem[];
-    T *kbuf = reinterpret_cast<T *>(smem);
-    const int m = walk[0], n = (m + 1) * dh;
-    T *vbuf = kbuf + n;
-    const KVCache kv = caches[blockIdx.x];
-    const int head = blockIdx.y;
-    T *kc = static_cast<T *>(kv.k), *vc = static_cast<T *>(kv.vt);
-    for (int e = threadIdx.x; e < n; e += blockDim.x) {
-        const int j = e / dh, i = e % dh, src = t + walk[2 + j];
-        kbuf[e] = kc[k_offset(kv, src, head, hkv, dh) + i];
-        vbuf[e] = vc[vt_offset(kv, src, head, hkv, dh, i)];
-    }
+    __shared__ int32_t walk[32];                      // 3 + the longest path (depth <= 16)
+    if (threadIdx.x < 64) accept_walk_wave(tree_token, tree_parent, g, n_nodes[0], max_path, walk);
     __syncthreads();
-    for (int e = threadIdx.x; e < n; e += blockDim.x) {
-        const int j = e / dh, i = e % dh, dst = t + j;
-        kc[k_offset(kv, dst, head, hkv, dh) + i] = kbuf[e];
-        vc[vt_offset(kv, dst, head, hkv, dh, i)] = vbuf[e];
+    const int m = walk[0];
+    if ((int)blockIdx.x < n_kv_wgs) {
+        T *kbuf = reinterpret_cast<T *>(smem);
+        const int n = (m + 1) * dh;
+        T *vbuf = kbuf + n;
+        const KVCache kv = caches[blockIdx.x / hkv];
+        const int head = blockIdx.x % hkv;
+        T *kc = static_cast<T *>(kv.k), *vc = static_cast<T *>(kv.vt);
+        for (int e = threadIdx.x; e < n; e += blockDim.x) {
+            const int j = e / dh, i = e % dh, src = t + walk[2 + j];
+            kbuf[e] = kc[k_offset(kv, src, head, hkv, dh) + i];
+            vbuf[e] = vc[vt_offset(kv, src, head, hkv, dh, i)];
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < n; e += blockDim.x) {
+            const int j = e / dh, i = e % dh, dst = t + j;
+            kc[k_offset(kv, dst, head, hkv, dh) + i] = kbuf[e];
+            vc[vt_offset(kv, dst, head, hkv, dh, i)] = vbuf[e];
+        }
+        return;
     }
-}
-
-// Features of the accepted rows become f_{t+j}; accepted tokens and the bonus token join the stream.
-template <typename T>
-__global__ __launch_bounds__(256) void commit_misc_kernel(const int32_t *__restrict__ walk, int t, int d_model,
-                                                          const float *__restrict__ feats, T *__restrict__ feat_stash,
-                                                          int32_t *__restrict__ tokens_dev,
-                                                          const int32_t *__restrict__ tree_token) {
-    const int j = blockIdx.x, m = walk[0];
+    const int j = blockIdx.x - n_kv_wgs;
     if (j > m) return;
     const float *src = feats + (size_t)walk[2 + j] * d_model;
     T *dst = feat_stash + (size_t)(t + j) * d_model;
     for (int i = threadIdx.x; i < d_model; i += blockDim.x) dst[i] = from_f<T>(src[i]);
-    if (threadIdx.x == 0) tokens_dev[t + 1 + j] = j < m ? tree_token[walk[2 + j + 1]] : walk[1];
+    if (threadIdx.x == 0) {
+        const int32_t tok = j < m ? tree_token[walk[2 + j + 1]] : walk[1];
+        tokens_dev[t + 1 + j] = tok;
+        result[32 + j] = tok;
+    }
+    if (j == 0 && (int)threadIdx.x < m + 3) {
+        walk_dev[threadIdx.x] = walk[threadIdx.x];
+        result[threadIdx.x] = walk[threadIdx.x];
+    }
 }
 
-void launch_commit(const ModelDims &md, int n_layers, const KVCache *caches_dev, const int32_t *walk, int max_path,
-                   int t, const float *feats, void *feat_stash, int32_t *tokens_dev, const int32_t *tree_token,
+void launch_commit(const ModelDims &md, int n_layers, const KVCache *caches_dev, const int32_t *tree_token,
+                   const int32_t *tree_parent, const int32_t *g, const int32_t *n_nodes, int max_path, int t,
+                   const float *feats, void *feat_stash, int32_t *tokens_dev, int32_t *walk_dev, int32_t *result,
                    hipStream_t st) {
     const size_t lds = (size_t)2 * (max_path + 1) * md.dh * dtype_size(md.dt);
+    const int n_kv_wgs = n_layers * md.hkv;
 #define POSS_COMMIT(T)                                                                                             \
-    hipLaunchKernelGGL((commit_kv_kernel<T>), dim3(n_layers, md.hkv), dim3(256), lds, st, caches_dev, walk, t, md.hkv, \
-                       md.dh);                                                                                     \
-    hipLaunchKernelGGL((commit_misc_kernel<T>), dim3(max_path + 1), dim3(256), 0, st, walk, t, md.d, feats,           \
-                       static_cast<T *>(feat_stash), tokens_dev, tree_token)
+    hipLaunchKernelGGL((commit_kernel<T>), dim3(n_kv_wgs + max_path + 1), dim3(256), lds, st, caches_dev, n_kv_wgs,   \
+                       md.hkv, md.dh, tree_token, tree_parent, g, n_nodes, max_path, t, md.d, feats,               \
+                       static_cast<T *>(feat_stash), tokens_dev, walk_dev, result)
     if (md.dt == DT_F32) { POSS_COMMIT(float); } else if (md.dt == DT_BF16) { POSS_COMMIT(bf16_t); } else { POSS_COMMIT(f16_t); }
 #undef POSS_COMMIT
 }
