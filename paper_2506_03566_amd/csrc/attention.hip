@@ -70,7 +70,9 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
     const int kway = wave >> 2;                           // which of the KW blocks of an iteration this wave takes
-    const int stage_blk = tid >> 8, stid = tid & 255;     // staging: 256 threads per block
+    // staging: 256 threads per block; the block index is wave-uniform, and said to be, so that the
+    // page-table reads become scalar loads that do not queue behind the key/value loads in flight
+    const int stage_blk = __builtin_amdgcn_readfirstlane(tid >> 8), stid = tid & 255;
     // Workgroup id -> (row group, KV head, split).  Consecutive ids go to the 8 XCDs in turn, each with an
     // L2 of its own, so the row groups that read the same keys and values (same head and split) are given
     // ids that are equal modulo 8: the block is fetched from memory once and then found in that L2.
@@ -111,12 +113,25 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     // than the latency of its loads, so one block of look-ahead would leave the loop latency-bound
     constexpr int PFD = 2;
     u32x4 kr[PFD][KPT], vr[PFD][VPT];
+    // The page-table entry of a block is fetched one call ahead of the block itself: read where it is
+    // used, it would put a dependent trip to memory (and a wait for every load in flight) into each
+    // iteration.  Calls go up in steps of KW blocks.
+    // (The table is read through the constant address space: nothing writes it while a kernel runs,
+    // and a wave-uniform read from there is a scalar load, outside the vector-memory queue.)
+    typedef const __attribute__((address_space(4))) int32_t *ConstTable;
+    const ConstTable page_table_c = (ConstTable)(uintptr_t)kv.page_table;
+    auto page_of = [&](int bfirst) {
+        const int b = min(bfirst + stage_blk, b1 - 1);
+        return page_table_c[(b << 5) >> kv.page_shift];
+    };
+    int pg_next = page_of(b0);
     auto load_block = [&](auto slot_tag, int bfirst) {    // this thread's share of block bfirst + stage_blk
         constexpr int SLOT = decltype(slot_tag)::value;
         int b = bfirst + stage_blk;
         if (b >= b1) b = b1 - 1;                          // never predicated: reload a valid block, it is ignored
         const int slot0 = b << 5;
-        const int pg = kv.page_table[slot0 >> kv.page_shift], off = slot0 & (P - 1);
+        const int pg = pg_next, off = slot0 & (P - 1);
+        pg_next = page_of(bfirst + KW);
         const size_t head_base = (size_t)(pg * hkv + kvh);
         const T *kb = kc + (head_base * P + off) * DH;
         const T *vb = vc + head_base * DH * P + off;
