@@ -636,7 +636,7 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
         c->spec_len[s] = t;
         c->spec_tmp_depth[s] = d - 1;
     }
-    launch_tree_finalize(c->td, k, L, cf.total_tokens, t, c->tokens_dev, c->st);
+    launch_tree_finalize(c->td, k, L, cf.total_tokens, t, c->tokens_dev, c->tree_slot, c->st);
     (void)hipEventRecord(c->ev[1], c->st);
     c->ev_pending[0] = true;
     const int pool = k + (L - 1) * k * k;
@@ -665,7 +665,7 @@ int poss_debug_build_tree(poss_ctx *c, const int32_t *ids, const float *logp, po
         HIP_TRY(c, hipMemcpyAsync(c->td.topk_logp, slp + (size_t)(d - 1) * k * k, rows * k * sizeof(float), hipMemcpyHostToDevice, c->st));
         launch_tree_expand(c->td, d, k, L, rows, c->st);
     }
-    launch_tree_finalize(c->td, k, L, cf.total_tokens, c->t, c->tokens_dev, c->st);
+    launch_tree_finalize(c->td, k, L, cf.total_tokens, c->t, c->tokens_dev, c->tree_slot, c->st);
     const int pool = k + (L - 1) * k * k;
     c->tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
     c->tree_ready = 1;
@@ -715,9 +715,7 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
         HIP_TRY(c, hipMemcpyAsync(c->td.n_nodes, stage + 2 * MAX_ROWS, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
         launch_tree_upload_finish(n, t, c->td.token, c->td.parent, c->td.depth, c->td.pos, c->tree_slot, c->td.mask, c->st);
         c->tree_n = n; c->tree_ready = 1;
-    } else {
-        launch_iota_slots(n, t, c->tree_slot, c->st);
-    }
+    }                                     // (a drafted tree's slots were written when it was finalized)
     RowMeta rm{c->td.pos, c->tree_slot, c->td.mask};
     target_forward(c, n, c->td.token, rm, t, n);
     GemmShape g = run_head(c, n);

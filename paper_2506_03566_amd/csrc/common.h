@@ -139,8 +139,9 @@ size_t topk_scratch_floats(int rows, int vocab);
 void launch_topk_logsoftmax(const float *logits, int ld, int rows, int vocab, int k, float *seg_scratch,
                             int32_t *out_id, float *out_logp, hipStream_t st);
 void launch_tree_expand(const TreeDev &td, int d, int k, int L, int rows, hipStream_t st);
+// also writes the KV slot of every node (slot_out[i] = t + i), which the verification pass reads
 void launch_tree_finalize(const TreeDev &td, int k, int L, int n_keep, int t, const int32_t *tokens_dev,
-                          hipStream_t st);
+                          int32_t *slot_out, hipStream_t st);
 // rows of [embedding ; feature] pairs for one specialist pass
 struct DraftRowPlan {
     int n_rows;
@@ -160,7 +161,6 @@ void launch_draft_assemble(const ModelDims &md, const DraftRowPlan &plan, int de
 // ---------------------------------------------------------------- accept + commit
 void launch_tree_upload_finish(int n, int t, const int32_t *token, const int32_t *parent, int32_t *depth,
                                int32_t *pos, int32_t *slot, uint64_t *mask, hipStream_t st);
-void launch_iota_slots(int n, int t, int32_t *slot, hipStream_t st);
 // One launch: the greedy walk over the verified tree, then KV compaction, feature stash and token
 // stream.  walk_dev / result: [0] = m, [1] = bonus token, [2..2+m] = node indices of the accepted
 // path; result[32 + j] = committed token j.  result must be host memory mapped into the device.

@@ -154,31 +154,36 @@ __global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict
     __shared__ TopkLds lds;
     __shared__ float red[17];
     const int row = blockIdx.x, nc = n_seg * k;
-    const float *recs = seg_out + (size_t)row * n_seg * (2 + 2 * TOPK_MAXK);
-    float mx = -INFINITY;
-    for (int s = threadIdx.x; s < n_seg; s += blockDim.x) mx = fmaxf(mx, recs[(size_t)s * (2 + 2 * TOPK_MAXK)]);
-    mx = wave_max(mx);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    float se = 0.f;
-    for (int s = threadIdx.x; s < n_seg; s += blockDim.x) {
-        const float *r = recs + (size_t)s * (2 + 2 * TOPK_MAXK);
-        se += r[1] * expf(r[0] - mx);
-    }
-    se = block_sum(se, red);
-    const float lse = mx + logf(se);
+    constexpr int REC = 2 + 2 * TOPK_MAXK;
+    const float *recs = seg_out + (size_t)row * n_seg * REC;
+    // Every load is issued before the first reduction, unconditionally (an entry that does not exist
+    // reads slot 0 of segment 0 and is discarded afterwards): one trip to memory, not one per step.
     float v[TOPK_MERGE_NV]; int id[TOPK_MERGE_NV];
 #pragma unroll
     for (int j = 0; j < TOPK_MERGE_NV; ++j) {
         const int c = threadIdx.x + j * 256;
-        v[j] = -INFINITY; id[j] = 0x7fffffff - j;
-        if (c < nc) {
-            const float *r = recs + (size_t)(c / k) * (2 + 2 * TOPK_MAXK);
-            const int ci = reinterpret_cast<const int *>(r)[2 + TOPK_MAXK + c % k];
-            if (ci != 0x7fffffff) { v[j] = r[2 + c % k]; id[j] = ci; }
-        }
+        const bool exists = c < nc;
+        const float *r = recs + (exists ? (size_t)(c / k) * REC + c % k : 0);
+        const float cv = r[2];
+        const int ci = reinterpret_cast<const int *>(r)[2 + TOPK_MAXK];
+        const bool ok = exists && ci != 0x7fffffff;
+        v[j] = ok ? cv : -INFINITY; id[j] = ok ? ci : 0x7fffffff - j;
     }
+    const bool own = (int)threadIdx.x < n_seg;            // this thread's segment record (more than 256 segments: the loops)
+    const float m0 = recs[own ? (size_t)threadIdx.x * REC : 0], z0 = recs[(own ? (size_t)threadIdx.x * REC : 0) + 1];
+    float mx = own ? m0 : -INFINITY;
+    for (int s = threadIdx.x + 256; s < n_seg; s += 256) mx = fmaxf(mx, recs[(size_t)s * REC]);
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float se = own ? z0 * expf(m0 - mx) : 0.f;
+    for (int s = threadIdx.x + 256; s < n_seg; s += 256) {
+        const float *r = recs + (size_t)s * REC;
+        se += r[1] * expf(r[0] - mx);
+    }
+    se = block_sum(se, red);
+    const float lse = mx + logf(se);
     float ov; int oi;
     block_topk<TOPK_MERGE_NV>(v, id, k, lds, ov, oi);
     if ((int)threadIdx.x < k) {
@@ -207,9 +212,11 @@ __global__ __launch_bounds__(256) void tree_expand_kernel(TreeDev td, int d, int
     const int n_child = rows * k;
     const int base = d == 1 ? 0 : k + (d - 2) * k * k;
     const int tid = threadIdx.x;
+    uint64_t pw0 = 0ull, pw1 = 0ull;                      // the parent's ancestor mask, asked for with the rest
     if (tid < n_child) {
         const int r = tid / k;
         const float ps = d == 1 ? 0.f : td.fr_score[(d - 1) * k + r];
+        if (d > 1 && d < L) { pw0 = td.fr_mask[((d - 1) * k + r) * MASK_WORDS]; pw1 = td.fr_mask[((d - 1) * k + r) * MASK_WORDS + 1]; }
         const float s = ps + td.topk_logp[tid];
         sc[tid] = s;
         td.pool_token[base + tid] = td.topk_id[tid];
@@ -229,8 +236,7 @@ __global__ __launch_bounds__(256) void tree_expand_kernel(TreeDev td, int d, int
             td.fr_parent_rank[o] = r;
             td.fr_score[o] = s;
             const int bit = (d - 1) * k + rank;
-            uint64_t w0 = d == 1 ? 0ull : td.fr_mask[((d - 1) * k + r) * MASK_WORDS];
-            uint64_t w1 = d == 1 ? 0ull : td.fr_mask[((d - 1) * k + r) * MASK_WORDS + 1];
+            uint64_t w0 = pw0, w1 = pw1;
             if (bit < 64) w0 |= 1ull << bit; else w1 |= 1ull << (bit - 64);
             td.fr_mask[o * MASK_WORDS] = w0;
             td.fr_mask[o * MASK_WORDS + 1] = w1;
@@ -247,7 +253,8 @@ void launch_tree_expand(const TreeDev &td, int d, int k, int L, int rows, hipStr
 // the root x_t.  pos = t + depth; mask = node and its ancestors; slot = t + node index.
 constexpr int POOL_MAX = 2048;
 __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int pool_n, int n_keep, int t,
-                                                             const int32_t *__restrict__ tokens_dev) {
+                                                             const int32_t *__restrict__ tokens_dev,
+                                                             int32_t *__restrict__ slot_out) {
     __shared__ float sc[POOL_MAX];
     __shared__ int16_t par[POOL_MAX];                 // candidate -> parent candidate (-1: the root)
     __shared__ int16_t new_idx[POOL_MAX];             // candidate -> node index in the tree, -1 if dropped
@@ -287,6 +294,7 @@ __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int poo
         td.n_nodes[0] = total + 1;
         td.token[0] = tokens_dev[t]; td.parent[0] = -1; td.depth[0] = 0; td.pos[0] = t; td.score[0] = 0.f;
         td.mask[0] = 1ull; td.mask[1] = 0ull;
+        slot_out[0] = t;
     }
     __syncthreads();
     for (int i = tid; i < pool_n; i += 1024) {
@@ -297,6 +305,7 @@ __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int poo
         td.parent[ni] = pp < 0 ? 0 : new_idx[pp];
         td.depth[ni] = dep;
         td.pos[ni] = t + dep;
+        slot_out[ni] = t + ni;
         td.score[ni] = sc[i];
         uint64_t w0 = 1ull, w1 = 0ull;               // the root
         for (int u = i; u >= 0; u = par[u]) {
@@ -309,10 +318,10 @@ __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int poo
 }
 
 void launch_tree_finalize(const TreeDev &td, int k, int L, int n_keep, int t, const int32_t *tokens_dev,
-                          hipStream_t st) {
+                          int32_t *slot_out, hipStream_t st) {
     const int pool_n = k + (L - 1) * k * k;
     hipLaunchKernelGGL(tree_finalize_kernel, dim3(1), dim3(1024), 0, st, td, pool_n, n_keep < pool_n ? n_keep : pool_n,
-                       t, tokens_dev);
+                       t, tokens_dev, slot_out);
 }
 
 // ------------------------------------------------------------------ rows of one specialist pass
@@ -419,14 +428,6 @@ void launch_tree_upload_finish(int n, int t, const int32_t *token, const int32_t
                                int32_t *pos, int32_t *slot, uint64_t *mask, hipStream_t st) {
     (void)token;
     hipLaunchKernelGGL(tree_upload_finish_kernel, dim3(1), dim3(128), 0, st, n, t, parent, depth, pos, slot, mask);
-}
-
-__global__ void iota_slots_kernel(int n, int t, int32_t *slot) {
-    const int i = threadIdx.x;
-    if (i < n) slot[i] = t + i;
-}
-void launch_iota_slots(int n, int t, int32_t *slot, hipStream_t st) {
-    hipLaunchKernelGGL(iota_slots_kernel, dim3(1), dim3(128), 0, st, n, t, slot);
 }
 
 // ------------------------------------------------------------------ greedy acceptance walk + commit
