@@ -23,7 +23,7 @@ PAPER_TAU = {"c1_llama3_8b_3x2": 4.55, "c2_llama3_8b_6x1": 4.54, "c3_llama2_13b_
 # HBM bytes per gemm_stream_kernel launch (average over the launches of a round) from rocprofv3 TCC
 # counters, scaled by the reading of a plain 1 GiB copy (FETCH_SIZE x2.000, WRITE_SIZE x1.000);
 # commands and raw sums: profiles/gemm_stream_kernel_c1_hbm_traffic.md
-MEASURED_TRAFFIC = {"c1_llama3_8b_3x2": dict(fetch_bytes=153.6e6, write_bytes=7.01e6)}
+MEASURED_TRAFFIC = {"c1_llama3_8b_3x2": dict(fetch_bytes=153.6e6, write_bytes=5.70e6)}
 
 
 def round_bytes(cfg, t, a):
