@@ -6,6 +6,12 @@
  *   poss_load -> poss_prefill -> ( poss_draft_tree -> poss_verify_tree
  *                                  -> poss_accept_and_commit )*
  *
+ * With poss_config.batch = B > 1 a context carries B independent sequences (greedy verification):
+ * each has its own caches, tree and token stream, every pass stacks their rows into one set of
+ * weight-streaming launches, and the three round calls advance all of them; poss_prefill_seq,
+ * poss_get_tree_seq, poss_get_commit_seq and poss_get_tokens_seq address one sequence (the calls
+ * without _seq address sequence 0).  A sequence's tokens are the ones it gets at batch 1.
+ *
  * Every step runs in hand-written HIP kernels of this library.  All pointers
  * are plain addresses; each argument says whether it is HOST or DEVICE memory.
  * The library never allocates device memory: weights, the workspace and the
@@ -67,6 +73,8 @@ typedef struct poss_config {
     int32_t max_seq;                         /* capacity in committed tokens (multiple of kv_page_tokens) */
     int32_t kv_page_tokens;                  /* tokens per KV page: 32, 64 or 128           */
     int32_t kv_page_order;                   /* 0: pages in order; 1: physical pages reversed (layout tests) */
+    int32_t batch;                           /* sequences per round: 0 or 1 = one; up to 8 while batch *
+                                              * (total_tokens + 1) and the widest specialist pass fit 128 rows */
 } poss_config;
 
 /* Weights: DEVICE pointers to row-major [out, in] tensors of `dtype`.
@@ -123,6 +131,8 @@ int poss_reset(poss_ctx *ctx);
  * (section 3.3: specialists do not share a cache).  *first_token_out = x_P, the target's greedy
  * token after the prompt; it becomes the root of the first tree. */
 int poss_prefill(poss_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out);
+/* The same for sequence seq (0 <= seq < batch).  Rounds can start once every sequence has its prompt. */
+int poss_prefill_seq(poss_ctx *ctx, int32_t seq, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out);
 
 /* Draft phase (section 6.2): `depth` specialist passes expand the tree level by level; the
  * total_tokens best candidates by cumulative log-probability form the tree.  out (HOST, may be
@@ -130,6 +140,8 @@ int poss_prefill(poss_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t
  * out == NULL the call returns once the work is queued on the stream (no host wait); a device
  * error then surfaces at the next call that waits. */
 int poss_draft_tree(poss_ctx *ctx, poss_tree *out);
+/* The tree drafted last for sequence seq (HOST arrays as for poss_draft_tree); waits for the stream. */
+int poss_get_tree_seq(poss_ctx *ctx, int32_t seq, poss_tree *out);
 
 /* Verification phase (section 2.1): one target pass over all tree rows with tree position ids
  * and the ancestor mask.  tree: HOST, or NULL for the tree drafted last.  argmax_out (HOST,
@@ -150,6 +162,9 @@ int poss_verify_tree(poss_ctx *ctx, const poss_tree *tree, int32_t *argmax_out,
  * with 0; *n_accepted_out = m; committed_out[depth+1] the m+1 new tokens; *n_committed_out = m+1. */
 int poss_accept_and_commit(poss_ctx *ctx, int32_t *path_idx_out, int32_t *n_accepted_out,
                            int32_t *committed_out, int32_t *n_committed_out);
+/* What the last poss_accept_and_commit did for sequence seq (same outputs; no device work). */
+int poss_get_commit_seq(poss_ctx *ctx, int32_t seq, int32_t *path_idx_out, int32_t *n_accepted_out,
+                        int32_t *committed_out, int32_t *n_committed_out);
 
 /* Verification at temperature > 0 (the paper evaluates temperature 0 and 1, section 4.1; section 2.1
  * only requires that verification keeps the target's output distribution).  The draft tree is built
@@ -167,6 +182,7 @@ int poss_set_sampling(poss_ctx *ctx, float temperature, const float *u, int32_t 
 int poss_get_stats(poss_ctx *ctx, poss_stats *out);
 /* Number of committed tokens (prompt included); tokens_out (HOST, may be NULL) of capacity cap. */
 int poss_get_tokens(poss_ctx *ctx, int32_t *tokens_out, int32_t cap, int32_t *n_out);
+int poss_get_tokens_seq(poss_ctx *ctx, int32_t seq, int32_t *tokens_out, int32_t cap, int32_t *n_out);
 const char *poss_last_error(poss_ctx *ctx);       /* ctx may be NULL: last poss_load error */
 void poss_free(poss_ctx *ctx);
 

@@ -16,6 +16,7 @@ MAX_ROWS, MASK_WORDS, MAX_DEPTH = 128, 2, 16
 
 EXPORTS = ["poss_workspace_bytes", "poss_load", "poss_reset", "poss_prefill", "poss_draft_tree",
            "poss_verify_tree", "poss_accept_and_commit", "poss_get_stats", "poss_get_tokens",
+           "poss_prefill_seq", "poss_get_tree_seq", "poss_get_commit_seq", "poss_get_tokens_seq",
            "poss_last_error", "poss_free", "poss_profile_gemm", "poss_gemm_profile", "poss_set_tuning", "poss_set_sampling",
            "poss_debug_build_tree", "poss_debug_set_taps", "poss_debug_read_kv",
            "poss_debug_gemm_scratch_bytes", "poss_debug_gemm"]
@@ -27,7 +28,7 @@ class PossConfig(ctypes.Structure):
     _fields_ = [(n, c_i32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
                [("rms_eps", c_f32), ("rope_theta", c_f32), ("dtype", c_i32)] + \
                [(n, c_i32) for n in ("n_specialists", "positions_per_specialist", "fc_bias", "top_k", "depth",
-                                     "total_tokens", "max_seq", "kv_page_tokens", "kv_page_order")]
+                                     "total_tokens", "max_seq", "kv_page_tokens", "kv_page_order", "batch")]
 
 
 class PossWeights(ctypes.Structure):
@@ -75,6 +76,10 @@ def load_library():
     lib.poss_accept_and_commit.argtypes = [c_vp, P(c_i32), P(c_i32), P(c_i32), P(c_i32)]
     lib.poss_get_stats.argtypes = [c_vp, P(PossStats)]
     lib.poss_get_tokens.argtypes = [c_vp, P(c_i32), c_i32, P(c_i32)]
+    lib.poss_prefill_seq.argtypes = [c_vp, c_i32, P(c_i32), c_i32, P(c_i32)]
+    lib.poss_get_tree_seq.argtypes = [c_vp, c_i32, P(PossTree)]
+    lib.poss_get_commit_seq.argtypes = [c_vp, c_i32, P(c_i32), P(c_i32), P(c_i32), P(c_i32)]
+    lib.poss_get_tokens_seq.argtypes = [c_vp, c_i32, P(c_i32), c_i32, P(c_i32)]
     lib.poss_last_error.restype = ctypes.c_char_p
     lib.poss_last_error.argtypes = [c_vp]
     lib.poss_free.restype = None
@@ -192,11 +197,24 @@ class Poss:
     def reset(self):
         self._check(self.lib.poss_reset(self.h))
 
-    def prefill(self, prompt):
+    def prefill(self, prompt, seq=0):
         p = np.ascontiguousarray(prompt, dtype=np.int32)
         first = c_i32()
-        self._check(self.lib.poss_prefill(self.h, _iptr(p), len(p), ctypes.byref(first)))
+        self._check(self.lib.poss_prefill_seq(self.h, seq, _iptr(p), len(p), ctypes.byref(first)))
         return int(first.value)
+
+    def get_tree(self, seq):
+        tr = TreeArrays()
+        self._check(self.lib.poss_get_tree_seq(self.h, seq, ctypes.byref(tr.c)))
+        return tr
+
+    def commit_result(self, seq):
+        """(path, n_accepted, committed tokens) of the last accept_and_commit for one sequence of the batch."""
+        path = np.zeros(MAX_DEPTH + 1, np.int32)
+        toks = np.zeros(MAX_DEPTH + 1, np.int32)
+        m, nc = c_i32(), c_i32()
+        self._check(self.lib.poss_get_commit_seq(self.h, seq, _iptr(path), ctypes.byref(m), _iptr(toks), ctypes.byref(nc)))
+        return path[:m.value + 1].tolist(), int(m.value), toks[:nc.value].tolist()
 
     def draft_tree(self, want_tree=True):
         tr = TreeArrays() if want_tree else None
@@ -225,11 +243,11 @@ class Poss:
         self._check(self.lib.poss_get_stats(self.h, ctypes.byref(s)))
         return s
 
-    def tokens(self):
+    def tokens(self, seq=0):
         n = c_i32()
-        self._check(self.lib.poss_get_tokens(self.h, None, 0, ctypes.byref(n)))
+        self._check(self.lib.poss_get_tokens_seq(self.h, seq, None, 0, ctypes.byref(n)))
         out = np.zeros(n.value, np.int32)
-        self._check(self.lib.poss_get_tokens(self.h, _iptr(out), n.value, ctypes.byref(n)))
+        self._check(self.lib.poss_get_tokens_seq(self.h, seq, _iptr(out), n.value, ctypes.byref(n)))
         return out.tolist()
 
     def profile_gemm(self, enable):

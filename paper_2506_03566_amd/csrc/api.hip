@@ -39,6 +39,22 @@ constexpr int PROFILE_EVENTS = 1024;
 
 }  // namespace
 
+// One sequence of the batch: its caches, its tree, its token stream.  Weights and activation
+// buffers are shared; a pass stacks the rows of every sequence into one set of GEMM launches.
+struct Seq {
+    std::vector<KVCache> target_kv, spec_kv;
+    KVCache *target_kv_dev;
+    TreeDev td;                        // final-tree arrays are slices of the batch-wide row arrays
+    int32_t *tree_slot, *tokens_dev, *walk_dev;
+    void *feat_stash, *xin_tmp;
+    int32_t *result_pinned, *result_dev;   // the commit kernel's result: host memory and its device address
+    int t, tree_ready, tree_n, prefilled;
+    std::vector<int32_t> tokens;
+    std::vector<int> spec_len, spec_tmp_depth;
+    int last_m;                        // the last commit: accepted drafts, path, committed tokens
+    int32_t last_path[POSS_MAX_DEPTH + 1], last_tokens[POSS_MAX_DEPTH + 1];
+};
+
 struct poss_ctx {
     poss_config cfg;
     ModelDims md;
@@ -51,32 +67,31 @@ struct poss_ctx {
     // caches
     int cache_slots, n_pages;
     int32_t *page_table;
-    std::vector<KVCache> target_kv, spec_kv;
-    KVCache *target_kv_dev;
     size_t cache_bytes_each;
+    int B;                             // sequences per round
+    std::vector<Seq> seq;
     // activations
     float *h, *part, *logits, *feats, *fhat[2], *topk_scratch, *taps_user;
     float2 *cs;
     void *u, *xin, *q, *attn_out, *act;
     AttnScratch attn_sc;
-    int32_t *row_pos, *row_slot, *tree_slot;
+    int32_t *row_pos, *row_slot;
     uint64_t *row_mask;
-    TreeDev td;
-    int32_t *tokens_dev, *argmax_dev, *walk_dev;
-    void *feat_stash, *xin_tmp;
+    int32_t *tree_token_all, *tree_pos_all, *tree_slot_all, *tree_depth_all;   // rows of the verification pass, all sequences
+    uint64_t *tree_mask_all;
+    int32_t *topk_id_all; float *topk_logp_all;
+    int32_t *argmax_dev;
     double *inv_freq;
     // host state
-    int state, t, tree_ready, tree_n;
-    std::vector<int32_t> tokens;
-    std::vector<int> spec_len, spec_tmp_depth;
+    int state;
     poss_stats stats;
     void *pinned; size_t pinned_bytes;
+    int32_t *result_pinned_all;
     hipEvent_t ev[6];                  // begin/end of the draft, verify and commit phases
-    bool ev_pending[3];
+    bool ev_pending[3];                // phase recorded, elapsed time not yet added to the statistics
     bool launch_refused;               // a GEMM launch was refused on the host (null operand): internal error
     float temperature;                 // 0: greedy verification; > 0: the target's tokens are drawn (poss_set_sampling)
-    int32_t *result_pinned, *result_dev;   // the commit kernel's result: host memory and its device address
-    float *u_pinned, *u_dev;           // one uniform number per tree depth, host staging and device copy                // phase recorded, elapsed time not yet added to the statistics
+    float *u_pinned, *u_dev;           // one uniform number per tree depth, host staging and device copy
     int gemm_target_wgs, attn_keys_per_split;
     // gemm profiling
     int prof_on, prof_n;
@@ -127,6 +142,21 @@ const char *check_config(const poss_config &c) {
     if (c.max_seq < 2 || c.max_seq % c.kv_page_tokens) return "max_seq must be a positive multiple of kv_page_tokens";
     if (c.kv_page_order < 0 || c.kv_page_order > 1) return "kv_page_order must be 0 or 1";
     if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return "rms_eps / rope_theta out of range";
+    if (c.batch < 0 || c.batch > 8) return "batch must be in 0..8 (0 and 1: one sequence)";
+    if (c.batch > 1) {
+        // every pass stacks the rows of all sequences: the verification pass and the widest specialist
+        // pass (k full rows, the pairs committed by the last round, the frontier rows of the depths
+        // since that specialist last ran) must fit the 128-row launches
+        if (c.batch * (c.total_tokens + 1) > POSS_MAX_ROWS) return "batch * (total_tokens + 1) must not exceed 128 rows";
+        std::vector<int> seen(c.n_specialists, 0);
+        for (int d = 1; d <= c.depth; ++d) {
+            int s = (d - 1) / c.positions_per_specialist;
+            if (s > c.n_specialists - 1) s = c.n_specialists - 1;
+            const int earlier = d >= 2 && d - 2 > seen[s] ? (d - 2 - seen[s]) * c.top_k : 0;
+            if (c.batch * (c.top_k + c.depth + 1 + earlier) > POSS_MAX_ROWS) return "a batched specialist pass would exceed 128 rows";
+            seen[s] = d - 1;
+        }
+    }
     return nullptr;
 }
 
@@ -164,14 +194,15 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         w.spec.push_back(a.take(d * es));
         layer_slots(w.spec);
     }
-    // caches
+    // caches: every sequence has its own storage and shares the page table
+    const int B = c.batch > 1 ? c.batch : 1;
     const int P = c.kv_page_tokens;
     const int slots = round_up(c.max_seq + MAX_ROWS, P), pages = slots / P;
     const size_t cache_each = (size_t)pages * c.n_kv_heads * P * c.head_dim * es;
     int32_t *pt = a.take_n<int32_t>(pages);
     std::vector<void *> kvp;
-    for (int i = 0; i < 2 * (c.n_layers + c.n_specialists); ++i) kvp.push_back(a.take(cache_each));
-    KVCache *kv_dev = a.take_n<KVCache>(c.n_layers);
+    for (int i = 0; i < B * 2 * (c.n_layers + c.n_specialists); ++i) kvp.push_back(a.take(cache_each));
+    KVCache *kv_dev = a.take_n<KVCache>((size_t)B * c.n_layers);
     // activations
     const int R = MAX_ROWS;
     size_t part_floats = 0;
@@ -182,13 +213,14 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         const size_t f = (size_t)g.S * R * g.Npad;
         if (f > part_floats) part_floats = f;
     }
+    const int QR = B * 16 < R ? B * 16 : R;                  // full rows of a draft pass: at most k <= 16 per sequence
     float *h = a.take_n<float>((size_t)R * d);
     float2 *cs = a.take_n<float2>((size_t)R * (c.head_dim / 2));
     float *part = a.take_n<float>(part_floats);
     float *logits = a.take_n<float>((size_t)R * gemm_npad(V));
     float *feats = a.take_n<float>((size_t)R * d);
-    float *fhat0 = a.take_n<float>((size_t)16 * d), *fhat1 = a.take_n<float>((size_t)16 * d);
-    size_t scr_floats = topk_scratch_floats(16, V);
+    float *fhat0 = a.take_n<float>((size_t)QR * d), *fhat1 = a.take_n<float>((size_t)QR * d);
+    size_t scr_floats = topk_scratch_floats(QR, V);
     if (argmax_scratch_floats(R, V) > scr_floats) scr_floats = argmax_scratch_floats(R, V);
     if (sample_scratch_floats(R, V) > scr_floats) scr_floats = sample_scratch_floats(R, V);
     float *topk_scr = a.take_n<float>(scr_floats);      // shared by top-k (draft) and argmax (verify)
@@ -199,52 +231,71 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     const int max_splits = attention_splits(slots, 64);
     float *ao_part = a.take_n<float>((size_t)max_splits * c.n_kv_heads * rho_pad * c.head_dim);
     float *ml_part = a.take_n<float>((size_t)max_splits * c.n_kv_heads * rho_pad * 2);
-    int32_t *row_pos = a.take_n<int32_t>(R), *row_slot = a.take_n<int32_t>(R), *tree_slot = a.take_n<int32_t>(R);
+    int32_t *row_pos = a.take_n<int32_t>(R), *row_slot = a.take_n<int32_t>(R);
     uint64_t *row_mask = a.take_n<uint64_t>((size_t)R * MASK_WORDS);
-    // tree
-    const int k = c.top_k, L = c.depth, pool = k + (L - 1) * k * k;
-    TreeDev td;
-    td.pool_token = a.take_n<int32_t>(pool); td.pool_parent = a.take_n<int32_t>(pool);
-    td.pool_depth = a.take_n<int32_t>(pool); td.pool_score = a.take_n<float>(pool);
-    td.fr_pool = a.take_n<int32_t>((L + 1) * k); td.fr_token = a.take_n<int32_t>((L + 1) * k);
-    td.fr_parent_rank = a.take_n<int32_t>((L + 1) * k); td.fr_score = a.take_n<float>((L + 1) * k);
-    td.fr_mask = a.take_n<uint64_t>((size_t)(L + 1) * k * MASK_WORDS);
-    td.topk_id = a.take_n<int32_t>(16 * 16); td.topk_logp = a.take_n<float>(16 * 16);
-    td.n_nodes = a.take_n<int32_t>(4); td.token = a.take_n<int32_t>(R); td.parent = a.take_n<int32_t>(R);
-    td.depth = a.take_n<int32_t>(R); td.pos = a.take_n<int32_t>(R);
-    td.mask = a.take_n<uint64_t>((size_t)R * MASK_WORDS); td.score = a.take_n<float>(R);
-    int32_t *tokens_dev = a.take_n<int32_t>(slots + 8);
-    int32_t *argmax_dev = a.take_n<int32_t>(R), *walk_dev = a.take_n<int32_t>(POSS_MAX_DEPTH + 4);
-    void *stash = a.take((size_t)slots * d * es);
-    void *xin_tmp = a.take((size_t)MAX_ROWS * 2 * d * es);
+    // rows of the verification pass (sequence b owns rows [b * (total_tokens + 1), ...)) and of the top-k
+    int32_t *token_all = a.take_n<int32_t>(R), *pos_all = a.take_n<int32_t>(R), *slot_all = a.take_n<int32_t>(R);
+    int32_t *depth_all = a.take_n<int32_t>(R), *parent_all = a.take_n<int32_t>(R);
+    uint64_t *mask_all = a.take_n<uint64_t>((size_t)R * MASK_WORDS);
+    float *score_all = a.take_n<float>(R);
+    int32_t *topk_id_all = a.take_n<int32_t>((size_t)QR * 16); float *topk_logp_all = a.take_n<float>((size_t)QR * 16);
+    int32_t *argmax_dev = a.take_n<int32_t>(R);
     double *inv_freq = a.take_n<double>(c.head_dim / 2);
     float *u_dev = a.take_n<float>(POSS_MAX_DEPTH + 1);
+    // per sequence: tree state, token stream, feature stash, stored frontier rows
+    const int k = c.top_k, L = c.depth, pool = k + (L - 1) * k * k, stride = c.total_tokens + 1;
+    std::vector<Seq> seqs(B);
+    for (int b = 0; b < B; ++b) {
+        Seq &sq = seqs[b];
+        TreeDev &td = sq.td;
+        td.pool_token = a.take_n<int32_t>(pool); td.pool_parent = a.take_n<int32_t>(pool);
+        td.pool_depth = a.take_n<int32_t>(pool); td.pool_score = a.take_n<float>(pool);
+        td.fr_pool = a.take_n<int32_t>((L + 1) * k); td.fr_token = a.take_n<int32_t>((L + 1) * k);
+        td.fr_parent_rank = a.take_n<int32_t>((L + 1) * k); td.fr_score = a.take_n<float>((L + 1) * k);
+        td.fr_mask = a.take_n<uint64_t>((size_t)(L + 1) * k * MASK_WORDS);
+        td.topk_id = topk_id_all; td.topk_logp = topk_logp_all;          // re-pointed at the sequence's rows per pass
+        td.n_nodes = a.take_n<int32_t>(4);
+        td.token = token_all + b * stride; td.parent = parent_all + b * stride;
+        td.depth = depth_all + b * stride; td.pos = pos_all + b * stride;
+        td.mask = mask_all + (size_t)b * stride * MASK_WORDS; td.score = score_all + b * stride;
+        sq.tree_slot = slot_all + b * stride;
+        sq.tokens_dev = a.take_n<int32_t>(slots + 8);
+        sq.walk_dev = a.take_n<int32_t>(POSS_MAX_DEPTH + 4);
+        sq.feat_stash = a.take((size_t)slots * d * es);
+        sq.xin_tmp = a.take((size_t)MAX_ROWS * 2 * d * es);
+        sq.target_kv_dev = kv_dev + (size_t)b * c.n_layers;
+        const int shift = P == 32 ? 5 : P == 64 ? 6 : 7;
+        const size_t base = (size_t)b * 2 * (c.n_layers + c.n_specialists);
+        for (int l = 0; l < c.n_layers; ++l) sq.target_kv.push_back(KVCache{kvp[base + 2 * l], kvp[base + 2 * l + 1], pt, shift});
+        for (int s2 = 0; s2 < c.n_specialists; ++s2)
+            sq.spec_kv.push_back(KVCache{kvp[base + 2 * (c.n_layers + s2)], kvp[base + 2 * (c.n_layers + s2) + 1], pt, shift});
+    }
     (void)tw;
     if (ctx) {
+        ctx->B = B;
         ctx->cache_slots = slots; ctx->n_pages = pages; ctx->page_table = pt; ctx->cache_bytes_each = cache_each;
-        const int shift = P == 32 ? 5 : P == 64 ? 6 : 7;
-        for (int l = 0; l < c.n_layers; ++l) ctx->target_kv.push_back(KVCache{kvp[2 * l], kvp[2 * l + 1], pt, shift});
-        for (int s = 0; s < c.n_specialists; ++s)
-            ctx->spec_kv.push_back(KVCache{kvp[2 * (c.n_layers + s)], kvp[2 * (c.n_layers + s) + 1], pt, shift});
-        ctx->target_kv_dev = kv_dev;
+        ctx->seq = seqs;
         ctx->cs = cs;
         ctx->h = h; ctx->part = part; ctx->logits = logits; ctx->feats = feats; ctx->fhat[0] = fhat0; ctx->fhat[1] = fhat1;
         ctx->topk_scratch = topk_scr; ctx->u = u; ctx->xin = xin; ctx->q = q; ctx->attn_out = ao; ctx->act = act;
         ctx->attn_sc = AttnScratch{ao_part, ml_part};
-        ctx->row_pos = row_pos; ctx->row_slot = row_slot; ctx->tree_slot = tree_slot; ctx->row_mask = row_mask;
-        ctx->td = td; ctx->tokens_dev = tokens_dev; ctx->argmax_dev = argmax_dev; ctx->walk_dev = walk_dev;
-        ctx->feat_stash = stash; ctx->xin_tmp = xin_tmp; ctx->inv_freq = inv_freq; ctx->u_dev = u_dev;
+        ctx->row_pos = row_pos; ctx->row_slot = row_slot; ctx->row_mask = row_mask;
+        ctx->tree_token_all = token_all; ctx->tree_pos_all = pos_all; ctx->tree_slot_all = slot_all;
+        ctx->tree_depth_all = depth_all; ctx->tree_mask_all = mask_all;
+        ctx->topk_id_all = topk_id_all; ctx->topk_logp_all = topk_logp_all;
+        ctx->argmax_dev = argmax_dev;
+        ctx->inv_freq = inv_freq; ctx->u_dev = u_dev;
     }
     return a.off + 256;
 }
 
 // ------------------------------------------------------------------------------------------ GEMM wrapper
 GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int ldx, int M, float *part,
-                   bool single_split, EpiArgs epi) {
+                   bool single_split, EpiArgs epi, bool defer_epilogue = false) {
     GemmShape g = gemm_plan(c->md.dt, M, N, K, single_split ? 1 : c->gemm_target_wgs);
     const bool prof = c->prof_on && c->prof_n < PROFILE_EVENTS;
     if (prof) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->st);
-    if (!launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st, prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr))
+    if (!launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st, prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr, defer_epilogue))
         c->launch_refused = true;                   // reported by the next call that waits for the stream
     if (prof) {
         ++c->prof_n;
@@ -261,20 +312,46 @@ EpiArgs epi_residual(poss_ctx *c, bool residual, const void *bias, float *h_copy
     return e;
 }
 
+// The rows of one sequence inside a pass: full rows [q0, q0 + nq) (query, attention, MLP) and
+// key/value-only rows [x0, x0 + nx); its cache, committed prefix and region length.
+struct Seg { int b; const KVCache *kv; int q0, nq, x0, nx, n_prefix, region_len; };
+
+char *row_ptr(void *base, size_t row, size_t row_elems, int dt) {
+    return static_cast<char *>(base) + row * row_elems * dtype_size(dt);
+}
+
 // One decoder layer on rows_all rows (all produce K/V) of which the first rows_q go through
-// attention and the MLP.  On entry c->u holds T(rmsnorm(h) * attn_norm) and c->cs the rotary table
-// of the rows; on exit c->h is updated and c->u holds T(rmsnorm(h) * next_gain).
-void run_layer(poss_ctx *c, const LayerW &w, const KVCache &kv, int rows_all, int rows_q, const RowMeta &rm,
-               int n_prefix, int region_len, const void *next_gain, float *h_copy) {
+// attention and the MLP; the full rows of every sequence come first, each sequence attends to its
+// own cache.  On entry c->u holds T(rmsnorm(h) * attn_norm) and c->cs the rotary table of the rows;
+// on exit c->h is updated and c->u holds T(rmsnorm(h) * next_gain).
+void run_layer(poss_ctx *c, const LayerW &w, const std::vector<Seg> &segs, int rows_all, int rows_q, const RowMeta &rm,
+               const void *next_gain, float *h_copy) {
     const ModelDims &md = c->md;
     const int qd = md.hq * md.dh, kd = md.hkv * md.dh;
     EpiArgs e{};
-    e.mode = EPI_ROPE_KV; e.rows_q = rows_q; e.cs = c->cs; e.slot = rm.slot; e.q = c->q; e.kv = kv;
+    e.mode = EPI_ROPE_KV; e.rows_q = rows_q; e.cs = c->cs; e.slot = rm.slot; e.q = c->q; e.kv = *segs[0].kv;
     e.hq = md.hq; e.hkv = md.hkv; e.dh = md.dh;
-    run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false, e);
+    const bool one = segs.size() == 1 && segs[0].q0 == 0 && segs[0].x0 == segs[0].nq;
+    if (one) {
+        run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false, e);
+    } else {
+        // one weight stream for every sequence, then each sequence's rows go into its own cache
+        const GemmShape g = run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false, e, true);
+        for (const Seg &sg : segs) {
+            e.kv = *sg.kv;
+            e.rows_q = sg.q0 + sg.nq;
+            if (sg.nq > 0 && !launch_rope_kv_epilogue(md.dt, g, c->part, e, sg.q0, sg.q0 + sg.nq, c->st)) c->launch_refused = true;
+            e.rows_q = 0;
+            if (sg.nx > 0 && !launch_rope_kv_epilogue(md.dt, g, c->part, e, sg.x0, sg.x0 + sg.nx, c->st)) c->launch_refused = true;
+        }
+    }
     if (rows_q == 0) return;
-    launch_attention(md, c->q, rows_q, rm, n_prefix, region_len, kv, c->attn_keys_per_split, c->attn_sc,
-                     c->attn_out, c->st);
+    for (const Seg &sg : segs) {
+        if (sg.nq == 0) continue;
+        const RowMeta srm{rm.pos + sg.q0, rm.slot + sg.q0, rm.mask + (size_t)sg.q0 * MASK_WORDS};
+        launch_attention(md, row_ptr(c->q, sg.q0, qd, md.dt), sg.nq, srm, sg.n_prefix, sg.region_len, *sg.kv,
+                         c->attn_keys_per_split, c->attn_sc, row_ptr(c->attn_out, sg.q0, qd, md.dt), c->st);
+    }
     run_gemm(c, w.wo, md.d, qd, c->attn_out, qd, rows_q, c->part, false, epi_residual(c, true, nullptr, nullptr, w.mlp_norm));
     EpiArgs es{};
     es.mode = EPI_SILU; es.act = c->act; es.F = md.ffn;
@@ -283,10 +360,10 @@ void run_layer(poss_ctx *c, const LayerW &w, const KVCache &kv, int rows_all, in
     run_gemm(c, w.wdown, md.d, md.ffn, c->act, md.ffn, rows_q, c->part, false, epi_residual(c, true, nullptr, h_copy, next_gain));
 }
 
-// Target pass over `rows` rows whose tokens / metadata are on the device.  Leaves features in
-// c->feats and T(rmsnorm_final(features)) in c->u.
-void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowMeta &rm, int n_prefix,
-                    int region_len) {
+// Target pass over `rows` rows (all of them full rows; segs says which belong to which sequence)
+// whose tokens / metadata are on the device.  Leaves features in c->feats and
+// T(rmsnorm_final(features)) in c->u.
+void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowMeta &rm, std::vector<Seg> segs) {
     const ModelDims &md = c->md;
     launch_embed_norm(md, c->embed, tokens_dev, rows, c->layers[0].attn_norm, c->h, c->u, rm.pos, c->inv_freq, c->cs, c->st);
     const int nl = c->cfg.n_layers;
@@ -294,8 +371,8 @@ void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowM
         if (c->taps_user)
             launch_copy_rows_f32(c->h, md.d, c->taps_user + (size_t)l * rows * md.d, md.d, rows, md.d, c->st);
         const void *next_gain = l + 1 < nl ? c->layers[l + 1].attn_norm : c->final_norm;
-        run_layer(c, c->layers[l], c->target_kv[l], rows, rows, rm, n_prefix, region_len, next_gain,
-                  l + 1 == nl ? c->feats : nullptr);
+        for (Seg &sg : segs) sg.kv = &c->seq[sg.b].target_kv[l];
+        run_layer(c, c->layers[l], segs, rows, rows, rm, next_gain, l + 1 == nl ? c->feats : nullptr);
     }
     if (c->taps_user)
         launch_copy_rows_f32(c->h, md.d, c->taps_user + (size_t)nl * rows * md.d, md.d, rows, md.d, c->st);
@@ -323,49 +400,74 @@ __global__ void stash_rows_kernel(const float *__restrict__ feats, int d, T *__r
     for (int i = threadIdx.x; i < d; i += blockDim.x) stash[(size_t)(row0 + r) * d + i] = (T)feats[(size_t)r * d + i];
 }
 
-void stash_rows(poss_ctx *c, int rows, int row0) {
+void stash_rows(poss_ctx *c, Seq &sq, int rows, int row0) {
     if (c->md.dt == DT_F32)
-        hipLaunchKernelGGL((stash_rows_kernel<float>), dim3(rows), dim3(256), 0, c->st, c->feats, c->md.d, (float *)c->feat_stash, row0);
+        hipLaunchKernelGGL((stash_rows_kernel<float>), dim3(rows), dim3(256), 0, c->st, c->feats, c->md.d, (float *)sq.feat_stash, row0);
     else if (c->md.dt == DT_BF16)
-        hipLaunchKernelGGL((stash_rows_kernel<bf16_t>), dim3(rows), dim3(256), 0, c->st, c->feats, c->md.d, (bf16_t *)c->feat_stash, row0);
+        hipLaunchKernelGGL((stash_rows_kernel<bf16_t>), dim3(rows), dim3(256), 0, c->st, c->feats, c->md.d, (bf16_t *)sq.feat_stash, row0);
     else
-        hipLaunchKernelGGL((stash_rows_kernel<f16_t>), dim3(rows), dim3(256), 0, c->st, c->feats, c->md.d, (f16_t *)c->feat_stash, row0);
+        hipLaunchKernelGGL((stash_rows_kernel<f16_t>), dim3(rows), dim3(256), 0, c->st, c->feats, c->md.d, (f16_t *)sq.feat_stash, row0);
 }
 
 uint64_t ones(int bits) { return bits <= 0 ? 0ull : bits >= 64 ? ~0ull : ((1ull << bits) - 1); }
 
-// One specialist pass over the rows of `plan` (the first rows_q of them full rows).
-void spec_pass(poss_ctx *c, int s, const DraftRowPlan &plan, int depth_index, int rows_q, int n_prefix,
-               int region_len, const float *fhat_prev, float *fhat_out) {
+// Rows of sequence b in one specialist pass: plan rows [0, nq) are its full rows, the rest produce
+// keys and values only.
+struct SeqPlan { int b; DraftRowPlan plan; int nq, n_prefix, region_len; };
+
+// One pass of specialist s over the rows of every plan.  Full rows of all sequences first (sequence
+// order), then the key/value-only rows: the GEMMs after attention run on the leading rows.
+// fhat_prev / fhat_out hold one row per full row of the previous / this pass.
+// Returns the first full row of each sequence through q0_out.
+void spec_pass(poss_ctx *c, int s, std::vector<SeqPlan> &plans, int depth_index, const float *fhat_prev, int prev_rows_each,
+               float *fhat_out, std::vector<int> *q0_out) {
     const ModelDims &md = c->md;
     const SpecW &w = c->specs[s];
-    launch_draft_assemble(md, plan, depth_index, c->cfg.top_k, c->embed, c->tokens_dev, c->feat_stash, c->td,
-                          fhat_prev, c->xin_tmp, c->xin, c->row_pos, c->row_slot, c->row_mask, c->inv_freq, c->cs, c->st);
-    run_gemm(c, w.fc_w, md.d, 2 * md.d, c->xin, 2 * md.d, plan.n_rows, c->part, false,
+    int rows_q = 0, rows_all = 0;
+    for (const SeqPlan &p : plans) { rows_q += p.nq; rows_all += p.plan.n_rows; }
+    std::vector<Seg> segs;
+    int q0 = 0, x0 = rows_q;
+    for (size_t i = 0; i < plans.size(); ++i) {
+        SeqPlan &p = plans[i];
+        Seq &sq = c->seq[p.b];
+        const int nx = p.plan.n_rows - p.nq;
+        for (int r = 0; r < p.nq; ++r) p.plan.dst[r] = (int16_t)(q0 + r);
+        for (int r = 0; r < nx; ++r) p.plan.dst[p.nq + r] = (int16_t)(x0 + r);
+        launch_draft_assemble(md, p.plan, depth_index, c->cfg.top_k, c->embed, sq.tokens_dev, sq.feat_stash, sq.td,
+                              fhat_prev ? fhat_prev + (size_t)i * prev_rows_each * md.d : nullptr, sq.xin_tmp, c->xin,
+                              c->row_pos, c->row_slot, c->row_mask, c->inv_freq, c->cs, c->st);
+        segs.push_back(Seg{p.b, &sq.spec_kv[s], q0, p.nq, x0, nx, p.n_prefix, p.region_len});
+        if (q0_out) q0_out->push_back(q0);
+        q0 += p.nq; x0 += nx;
+    }
+    run_gemm(c, w.fc_w, md.d, 2 * md.d, c->xin, 2 * md.d, rows_all, c->part, false,
              epi_residual(c, false, c->cfg.fc_bias ? w.fc_b : nullptr, nullptr, w.layer.attn_norm));
     RowMeta rm{c->row_pos, c->row_slot, c->row_mask};
-    run_layer(c, w.layer, c->spec_kv[s], plan.n_rows, rows_q, rm, n_prefix, region_len, c->final_norm, fhat_out);
+    run_layer(c, w.layer, segs, rows_all, rows_q, rm, c->final_norm, fhat_out);
 }
 
-// Keys/values of committed pairs [spec_len[s], upto) for specialist s, in chunks of MAX_ROWS rows.
-void spec_catchup(poss_ctx *c, int s, int upto) {
-    while (c->spec_len[s] < upto) {
-        const int i0 = c->spec_len[s], n = upto - i0 < MAX_ROWS ? upto - i0 : MAX_ROWS;
-        DraftRowPlan plan;
-        plan.n_rows = n; plan.mask0[0] = plan.mask0[1] = 0;
-        for (int r = 0; r < n; ++r) { plan.kind[r] = 0; plan.idx[r] = i0 + r; plan.slot[r] = i0 + r; plan.pos[r] = i0 + r; }
-        spec_pass(c, s, plan, 0, 0, 0, 0, nullptr, nullptr);
-        c->spec_len[s] = i0 + n;
+// Keys/values of committed pairs [spec_len[s], upto) of one sequence for specialist s, in chunks of MAX_ROWS rows.
+void spec_catchup(poss_ctx *c, int b, int s, int upto) {
+    Seq &sq = c->seq[b];
+    while (sq.spec_len[s] < upto) {
+        const int i0 = sq.spec_len[s], n = upto - i0 < MAX_ROWS ? upto - i0 : MAX_ROWS;
+        std::vector<SeqPlan> plans(1);
+        SeqPlan &p = plans[0];
+        p.b = b; p.nq = 0; p.n_prefix = 0; p.region_len = 0;
+        p.plan.n_rows = n; p.plan.mask0[0] = p.plan.mask0[1] = 0;
+        for (int r = 0; r < n; ++r) { p.plan.kind[r] = 0; p.plan.idx[r] = i0 + r; p.plan.slot[r] = i0 + r; p.plan.pos[r] = i0 + r; }
+        spec_pass(c, s, plans, 0, nullptr, 0, nullptr, nullptr);
+        sq.spec_len[s] = i0 + n;
     }
 }
 
-int copy_tree_out(poss_ctx *c, poss_tree *out) {
-    const int n = c->tree_n;
+int copy_tree_out(poss_ctx *c, Seq &sq, poss_tree *out) {
+    const int n = sq.tree_n;
     out->n_nodes = n;
     struct { void *dst; const void *src; size_t b; } cp[] = {
-        {out->token, c->td.token, n * sizeof(int32_t)}, {out->parent, c->td.parent, n * sizeof(int32_t)},
-        {out->depth, c->td.depth, n * sizeof(int32_t)}, {out->pos, c->td.pos, n * sizeof(int32_t)},
-        {out->mask, c->td.mask, (size_t)n * MASK_WORDS * sizeof(uint64_t)}, {out->score, c->td.score, n * sizeof(float)}};
+        {out->token, sq.td.token, n * sizeof(int32_t)}, {out->parent, sq.td.parent, n * sizeof(int32_t)},
+        {out->depth, sq.td.depth, n * sizeof(int32_t)}, {out->pos, sq.td.pos, n * sizeof(int32_t)},
+        {out->mask, sq.td.mask, (size_t)n * MASK_WORDS * sizeof(uint64_t)}, {out->score, sq.td.score, n * sizeof(float)}};
     for (auto &x : cp)
         if (x.dst) HIP_TRY(c, hipMemcpyAsync(x.dst, x.src, x.b, hipMemcpyDeviceToHost, c->st));
     HIP_TRY(c, hipStreamSynchronize(c->st));
@@ -389,10 +491,13 @@ LayerW layer_view(const std::vector<void *> &v, size_t base) {
 }
 
 void reset_sequence(poss_ctx *c) {
-    c->state = ST_LOADED; c->t = 0; c->tree_ready = 0; c->tree_n = 0;
-    c->tokens.clear();
-    for (auto &x : c->spec_len) x = 0;
-    for (auto &x : c->spec_tmp_depth) x = 0;
+    c->state = ST_LOADED;
+    for (Seq &sq : c->seq) {
+        sq.t = 0; sq.tree_ready = 0; sq.tree_n = 0; sq.prefilled = 0; sq.last_m = 0;
+        sq.tokens.clear();
+        sq.spec_len.assign(c->cfg.n_specialists, 0);
+        sq.spec_tmp_depth.assign(c->cfg.n_specialists, 0);
+    }
     memset(&c->stats, 0, sizeof(c->stats));
 }
 
@@ -432,8 +537,6 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     c->taps_user = nullptr;
     c->gemm_target_wgs = 0; c->attn_keys_per_split = 0;
     c->prof_on = 0; c->prof_n = 0; c->prof_bytes = 0; c->prof_launches = 0; c->prof_ms = 0;
-    c->spec_len.assign(cfg->n_specialists, 0);
-    c->spec_tmp_depth.assign(cfg->n_specialists, 0);
     Arena a(workspace);
     WeightSlots ws;
     carve(*cfg, a, c, &ws);
@@ -464,15 +567,21 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
         c->specs.push_back(SpecW{ws.spec[(size_t)s * 8], ws.spec[(size_t)s * 8 + 1], layer_view(ws.spec, (size_t)s * 8 + 2)});
     }
     // caches: zero (attention may touch, masked, slots that were never written)
-    for (auto &kv : c->target_kv) { launch_fill_u32((uint32_t *)kv.k, c->cache_bytes_each / 4, 0, c->st); launch_fill_u32((uint32_t *)kv.vt, c->cache_bytes_each / 4, 0, c->st); }
-    for (auto &kv : c->spec_kv) { launch_fill_u32((uint32_t *)kv.k, c->cache_bytes_each / 4, 0, c->st); launch_fill_u32((uint32_t *)kv.vt, c->cache_bytes_each / 4, 0, c->st); }
+    for (Seq &sq : c->seq) {
+        for (auto &kv : sq.target_kv) { launch_fill_u32((uint32_t *)kv.k, c->cache_bytes_each / 4, 0, c->st); launch_fill_u32((uint32_t *)kv.vt, c->cache_bytes_each / 4, 0, c->st); }
+        for (auto &kv : sq.spec_kv) { launch_fill_u32((uint32_t *)kv.k, c->cache_bytes_each / 4, 0, c->st); launch_fill_u32((uint32_t *)kv.vt, c->cache_bytes_each / 4, 0, c->st); }
+    }
     // small host->device tables
     c->pinned_bytes = 1 << 20;
     LOAD_TRY(hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault));
     LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->u_pinned), (POSS_MAX_DEPTH + 1) * sizeof(float), hipHostMallocDefault));
     for (int i = 0; i <= POSS_MAX_DEPTH; ++i) c->u_pinned[i] = 0.f;
-    LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->result_pinned), 64 * sizeof(int32_t), hipHostMallocDefault));
-    LOAD_TRY(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->result_dev), c->result_pinned, 0));
+    LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->result_pinned_all), (size_t)c->B * 64 * sizeof(int32_t), hipHostMallocDefault));
+    {
+        int32_t *dev = nullptr;
+        LOAD_TRY(hipHostGetDevicePointer(reinterpret_cast<void **>(&dev), c->result_pinned_all, 0));
+        for (int b = 0; b < c->B; ++b) { c->seq[b].result_pinned = c->result_pinned_all + b * 64; c->seq[b].result_dev = dev + b * 64; }
+    }
     c->temperature = 0.f;
     {
         char *p = static_cast<char *>(c->pinned);
@@ -486,8 +595,9 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
         LOAD_TRY(hipMemcpyAsync(c->inv_freq, fr, half * sizeof(double), hipMemcpyHostToDevice, c->st));
         p += round_up(half * (int)sizeof(double), 256);
         KVCache *kvh = reinterpret_cast<KVCache *>(p);
-        for (int l = 0; l < cfg->n_layers; ++l) kvh[l] = c->target_kv[l];
-        LOAD_TRY(hipMemcpyAsync(c->target_kv_dev, kvh, cfg->n_layers * sizeof(KVCache), hipMemcpyHostToDevice, c->st));
+        for (int b = 0; b < c->B; ++b)
+            for (int l = 0; l < cfg->n_layers; ++l) kvh[b * cfg->n_layers + l] = c->seq[b].target_kv[l];
+        LOAD_TRY(hipMemcpyAsync(c->seq[0].target_kv_dev, kvh, (size_t)c->B * cfg->n_layers * sizeof(KVCache), hipMemcpyHostToDevice, c->st));
     }
     for (int i = 0; i < 6; ++i) LOAD_TRY(hipEventCreate(&c->ev[i]));
     c->ev_pending[0] = c->ev_pending[1] = c->ev_pending[2] = false;
@@ -517,7 +627,7 @@ void poss_free(poss_ctx *c) {
     for (int i = 0; i < 2 * PROFILE_EVENTS; ++i) (void)hipEventDestroy(c->prof_ev[i]);
     (void)hipHostFree(c->pinned);
     (void)hipHostFree(c->u_pinned);
-    (void)hipHostFree(c->result_pinned);
+    (void)hipHostFree(c->result_pinned_all);
     delete c;
 }
 
@@ -525,10 +635,12 @@ const char *poss_last_error(poss_ctx *c) { return c ? c->err : g_load_error; }
 
 static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth);
 
-int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
+int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
     if (!c) return POSS_E_INVALID_ARG;
+    if (seq < 0 || seq >= c->B) return fail(c, POSS_E_INVALID_ARG, "poss_prefill: no sequence %d (batch %d)", seq, c->B);
     if (!prompt || n_prompt < 1) return fail(c, POSS_E_INVALID_ARG, "poss_prefill: empty prompt");
-    if (c->state != ST_LOADED) return fail(c, POSS_E_BAD_STATE, "poss_prefill: sequence already started (poss_reset first)");
+    Seq &sq = c->seq[seq];
+    if (c->state != ST_LOADED || sq.prefilled) return fail(c, POSS_E_BAD_STATE, "poss_prefill: sequence already started (poss_reset first)");
     if (n_prompt + 1 > c->cfg.max_seq) return fail(c, POSS_E_CAPACITY, "poss_prefill: prompt of %d tokens, max_seq %d", n_prompt, c->cfg.max_seq);
     for (int i = 0; i < n_prompt; ++i)
         if (prompt[i] < 0 || prompt[i] >= c->cfg.vocab) return fail(c, POSS_E_INVALID_ARG, "poss_prefill: token id %d out of range at %d", prompt[i], i);
@@ -537,11 +649,11 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
     for (int c0 = 0; c0 < n_prompt; c0 += MAX_ROWS) {
         const int rows = n_prompt - c0 < MAX_ROWS ? n_prompt - c0 : MAX_ROWS;
         memcpy(stage, prompt + c0, rows * sizeof(int32_t));
-        HIP_TRY(c, hipMemcpyAsync(c->tokens_dev + c0, stage, rows * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        HIP_TRY(c, hipMemcpyAsync(sq.tokens_dev + c0, stage, rows * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
         hipLaunchKernelGGL(causal_meta_kernel, dim3(1), dim3(MAX_ROWS), 0, c->st, rows, c0, c->row_pos, c->row_slot, c->row_mask);
         RowMeta rm{c->row_pos, c->row_slot, c->row_mask};
-        target_forward(c, rows, c->tokens_dev + c0, rm, c0, rows);
-        stash_rows(c, rows, c0);
+        target_forward(c, rows, sq.tokens_dev + c0, rm, {Seg{seq, nullptr, 0, rows, rows, 0, c0, rows}});
+        stash_rows(c, sq, rows, c0);
         if (c0 + rows == n_prompt) {
             // Head on the last row only: its normed activations sit at row rows-1 of c->u
             const char *last = static_cast<const char *>(c->u) + (size_t)(rows - 1) * md.d * dtype_size(md.dt);
@@ -549,21 +661,28 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
             pe.mode = EPI_PLAIN;
             GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true, pe);
             { int rc = choose_tokens(c, g.Npad, 1, nullptr); if (rc) return rc; }
-            HIP_TRY(c, hipMemcpyAsync(c->tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
+            HIP_TRY(c, hipMemcpyAsync(sq.tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
         }
         HIP_TRY(c, hipStreamSynchronize(c->st));          // the staging buffer is reused by the next chunk
     }
     int32_t first = 0;
     HIP_TRY(c, hipMemcpy(&first, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToHost));
-    c->tokens.assign(prompt, prompt + n_prompt);
-    c->tokens.push_back(first);
-    c->t = n_prompt;
-    for (int s = 0; s < c->cfg.n_specialists; ++s) spec_catchup(c, s, c->t - 1);
+    sq.tokens.assign(prompt, prompt + n_prompt);
+    sq.tokens.push_back(first);
+    sq.t = n_prompt;
+    for (int s = 0; s < c->cfg.n_specialists; ++s) spec_catchup(c, seq, s, sq.t - 1);
     HIP_TRY(c, hipStreamSynchronize(c->st));
     HIP_TRY(c, hipGetLastError());
-    c->state = ST_READY; c->tree_ready = 0;
+    sq.prefilled = 1; sq.tree_ready = 0;
+    bool all = true;
+    for (const Seq &o : c->seq) all = all && o.prefilled;
+    if (all) c->state = ST_READY;                          // rounds start once every sequence has its prompt
     if (first_token_out) *first_token_out = first;
     return POSS_OK;
+}
+
+int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
+    return poss_prefill_seq(c, 0, prompt, n_prompt, first_token_out);
 }
 
 // The token the target chooses after each of `rows` rows of c->logits: the argmax, or at temperature > 0 a
@@ -599,52 +718,88 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
     if (!c) return POSS_E_INVALID_ARG;
     if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_draft_tree: needs a prefilled context with no pending verification");
     const poss_config &cf = c->cfg;
-    const int t = c->t, k = cf.top_k, L = cf.depth;
-    if (t + cf.total_tokens + 1 > c->cache_slots || t + L + 1 > cf.max_seq)
-        return fail(c, POSS_E_CAPACITY, "poss_draft_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
+    const int k = cf.top_k, L = cf.depth, B = c->B;
+    for (int b = 0; b < B; ++b) {
+        const int t = c->seq[b].t;
+        if (t + cf.total_tokens + 1 > c->cache_slots || t + L + 1 > cf.max_seq)
+            return fail(c, POSS_E_CAPACITY, "poss_draft_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
+    }
     if (c->ev_pending[0]) { int rc = sync_and_harvest(c); if (rc) return rc; }   // a re-draft: keep the first one's time
     (void)hipEventRecord(c->ev[0], c->st);
-    for (int s = 0; s < cf.n_specialists; ++s) {
-        c->spec_tmp_depth[s] = 0;
-        if (t - 1 - c->spec_len[s] > L) spec_catchup(c, s, t - 1);      // only after caller-supplied trees
+    for (int b = 0; b < B; ++b) {
+        Seq &sq = c->seq[b];
+        for (int s = 0; s < cf.n_specialists; ++s) {
+            sq.spec_tmp_depth[s] = 0;
+            if (sq.t - 1 - sq.spec_len[s] > L) spec_catchup(c, b, s, sq.t - 1);      // only after caller-supplied trees
+        }
     }
     for (int d = 1; d <= L; ++d) {
         int s = (d - 1) / cf.positions_per_specialist;
         if (s > cf.n_specialists - 1) s = cf.n_specialists - 1;
-        DraftRowPlan plan;
-        int n = 0, rows_q, n_prefix, region_len;
-        if (d == 1) {
-            // root pair [x_t ; f_{t-1}] first (the only row whose output is used), then the other
-            // pairs this specialist has not seen; all of them become committed cache entries
-            n_prefix = c->spec_len[s]; region_len = t - n_prefix; rows_q = 1;
-            plan.mask0[0] = ones(region_len); plan.mask0[1] = ones(region_len - 64);
-            plan.kind[n] = 0; plan.idx[n] = t - 1; plan.slot[n] = t - 1; plan.pos[n] = t - 1; ++n;
-            for (int i = n_prefix; i < t - 1; ++i) { plan.kind[n] = 0; plan.idx[n] = i; plan.slot[n] = i; plan.pos[n] = i; ++n; }
-        } else {
-            n_prefix = t; region_len = (d - 1) * k; rows_q = k;
-            plan.mask0[0] = plan.mask0[1] = 0;
-            for (int r = 0; r < k; ++r) { plan.kind[n] = 2; plan.idx[n] = r; plan.slot[n] = t + (d - 2) * k + r; plan.pos[n] = t - 1 + (d - 1); ++n; }
-            for (int i = c->spec_len[s]; i < t; ++i) { plan.kind[n] = 0; plan.idx[n] = i; plan.slot[n] = i; plan.pos[n] = i; ++n; }
-            for (int dl = c->spec_tmp_depth[s] + 1; dl <= d - 2; ++dl)
-                for (int r = 0; r < k; ++r) { plan.kind[n] = 1; plan.idx[n] = (dl - 1) * k + r; plan.slot[n] = t + (dl - 1) * k + r; plan.pos[n] = t - 1 + dl; ++n; }
+        std::vector<SeqPlan> plans(B);
+        int rows_all = 0;
+        const int rows_q_each = d == 1 ? 1 : k;
+        for (int b = 0; b < B; ++b) {
+            Seq &sq = c->seq[b];
+            SeqPlan &sp = plans[b];
+            DraftRowPlan &plan = sp.plan;
+            const int t = sq.t;
+            int n = 0;
+            sp.b = b; sp.nq = rows_q_each;
+            if (d == 1) {
+                // root pair [x_t ; f_{t-1}] first (the only row whose output is used), then the other
+                // pairs this specialist has not seen; all of them become committed cache entries
+                sp.n_prefix = sq.spec_len[s]; sp.region_len = t - sp.n_prefix;
+                plan.mask0[0] = ones(sp.region_len); plan.mask0[1] = ones(sp.region_len - 64);
+                plan.kind[n] = 0; plan.idx[n] = t - 1; plan.slot[n] = t - 1; plan.pos[n] = t - 1; ++n;
+                for (int i = sp.n_prefix; i < t - 1; ++i) { plan.kind[n] = 0; plan.idx[n] = i; plan.slot[n] = i; plan.pos[n] = i; ++n; }
+            } else {
+                sp.n_prefix = t; sp.region_len = (d - 1) * k;
+                plan.mask0[0] = plan.mask0[1] = 0;
+                for (int r = 0; r < k; ++r) { plan.kind[n] = 2; plan.idx[n] = r; plan.slot[n] = t + (d - 2) * k + r; plan.pos[n] = t - 1 + (d - 1); ++n; }
+                for (int i = sq.spec_len[s]; i < t; ++i) { plan.kind[n] = 0; plan.idx[n] = i; plan.slot[n] = i; plan.pos[n] = i; ++n; }
+                for (int dl = sq.spec_tmp_depth[s] + 1; dl <= d - 2; ++dl)
+                    for (int r = 0; r < k; ++r) { plan.kind[n] = 1; plan.idx[n] = (dl - 1) * k + r; plan.slot[n] = t + (dl - 1) * k + r; plan.pos[n] = t - 1 + dl; ++n; }
+            }
+            plan.n_rows = n;
+            rows_all += n;
         }
-        plan.n_rows = n;
-        spec_pass(c, s, plan, d - 1, rows_q, n_prefix, region_len, c->fhat[(d - 1) & 1], c->fhat[d & 1]);
+        if (rows_all > MAX_ROWS) return fail(c, POSS_E_CAPACITY, "poss_draft_tree: a pass of %d rows (limit %d)", rows_all, MAX_ROWS);
+        std::vector<int> q0;
+        spec_pass(c, s, plans, d - 1, c->fhat[(d - 1) & 1], d - 1 == 1 ? 1 : k, c->fhat[d & 1], &q0);
+        const int rows_q = B * rows_q_each;
         GemmShape g = run_head(c, rows_q);
-        launch_topk_logsoftmax(c->logits, g.Npad, rows_q, cf.vocab, k, c->topk_scratch, c->td.topk_id, c->td.topk_logp, c->st);
-        launch_tree_expand(c->td, d, k, L, rows_q, c->st);
-        c->spec_len[s] = t;
-        c->spec_tmp_depth[s] = d - 1;
+        launch_topk_logsoftmax(c->logits, g.Npad, rows_q, cf.vocab, k, c->topk_scratch, c->topk_id_all, c->topk_logp_all, c->st);
+        for (int b = 0; b < B; ++b) {
+            Seq &sq = c->seq[b];
+            TreeDev td = sq.td;                              // this sequence's rows of the top-k
+            td.topk_id = c->topk_id_all + (size_t)q0[b] * k; td.topk_logp = c->topk_logp_all + (size_t)q0[b] * k;
+            launch_tree_expand(td, d, k, L, rows_q_each, c->st);
+            sq.spec_len[s] = sq.t;
+            sq.spec_tmp_depth[s] = d - 1;
+        }
     }
-    launch_tree_finalize(c->td, k, L, cf.total_tokens, t, c->tokens_dev, c->tree_slot, c->st);
+    const int pool = k + (L - 1) * k * k;
+    for (int b = 0; b < B; ++b) {
+        Seq &sq = c->seq[b];
+        launch_tree_finalize(sq.td, k, L, cf.total_tokens, sq.t, sq.tokens_dev, sq.tree_slot, c->st);
+        sq.tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
+        sq.tree_ready = 1;
+    }
     (void)hipEventRecord(c->ev[1], c->st);
     c->ev_pending[0] = true;
-    const int pool = k + (L - 1) * k * k;
-    c->tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
-    c->tree_ready = 1;
     HIP_TRY(c, hipGetLastError());
     if (!out) return POSS_OK;                    // nothing for the host: the work stays queued
-    int rc = copy_tree_out(c, out);
+    int rc = copy_tree_out(c, c->seq[0], out);
+    if (rc) return rc;
+    return sync_and_harvest(c);
+}
+
+int poss_get_tree_seq(poss_ctx *c, int32_t seq, poss_tree *out) {
+    if (!c || !out) return POSS_E_INVALID_ARG;
+    if (seq < 0 || seq >= c->B) return fail(c, POSS_E_INVALID_ARG, "poss_get_tree_seq: no sequence %d (batch %d)", seq, c->B);
+    if (!c->seq[seq].tree_ready) return fail(c, POSS_E_BAD_STATE, "poss_get_tree_seq: no drafted tree");
+    int rc = copy_tree_out(c, c->seq[seq], out);
     if (rc) return rc;
     return sync_and_harvest(c);
 }
@@ -655,21 +810,22 @@ int poss_debug_build_tree(poss_ctx *c, const int32_t *ids, const float *logp, po
     if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_debug_build_tree: needs a prefilled context");
     const poss_config &cf = c->cfg;
     const int k = cf.top_k, L = cf.depth;
+    Seq &sq = c->seq[0];
     int32_t *sid = static_cast<int32_t *>(c->pinned);
     float *slp = reinterpret_cast<float *>(sid + (size_t)L * k * k);
     memcpy(sid, ids, (size_t)L * k * k * sizeof(int32_t));
     memcpy(slp, logp, (size_t)L * k * k * sizeof(float));
     for (int d = 1; d <= L; ++d) {
         const int rows = d == 1 ? 1 : k;
-        HIP_TRY(c, hipMemcpyAsync(c->td.topk_id, sid + (size_t)(d - 1) * k * k, rows * k * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-        HIP_TRY(c, hipMemcpyAsync(c->td.topk_logp, slp + (size_t)(d - 1) * k * k, rows * k * sizeof(float), hipMemcpyHostToDevice, c->st));
-        launch_tree_expand(c->td, d, k, L, rows, c->st);
+        HIP_TRY(c, hipMemcpyAsync(sq.td.topk_id, sid + (size_t)(d - 1) * k * k, rows * k * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        HIP_TRY(c, hipMemcpyAsync(sq.td.topk_logp, slp + (size_t)(d - 1) * k * k, rows * k * sizeof(float), hipMemcpyHostToDevice, c->st));
+        launch_tree_expand(sq.td, d, k, L, rows, c->st);
     }
-    launch_tree_finalize(c->td, k, L, cf.total_tokens, c->t, c->tokens_dev, c->tree_slot, c->st);
+    launch_tree_finalize(sq.td, k, L, cf.total_tokens, sq.t, sq.tokens_dev, sq.tree_slot, c->st);
     const int pool = k + (L - 1) * k * k;
-    c->tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
-    c->tree_ready = 1;
-    if (out) { int rc = copy_tree_out(c, out); if (rc) return rc; }
+    sq.tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
+    sq.tree_ready = 1;
+    if (out) { int rc = copy_tree_out(c, sq, out); if (rc) return rc; }
     HIP_TRY(c, hipStreamSynchronize(c->st));
     HIP_TRY(c, hipGetLastError());
     return POSS_OK;
@@ -679,7 +835,9 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     if (!c) return POSS_E_INVALID_ARG;
     if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: needs a prefilled context with no pending verification");
     const poss_config &cf = c->cfg;
-    const int t = c->t;
+    const int B = c->B;
+    if (tree && B > 1) return fail(c, POSS_E_INVALID_ARG, "poss_verify_tree: a caller's tree needs batch 1; batched rounds verify the drafted trees");
+    Seq &s0 = c->seq[0];
     int n;
     if (tree) {
         n = tree->n_nodes;
@@ -698,28 +856,38 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
                     return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: siblings %d and %d carry the same token", j, i);
         }
     } else {
-        if (!c->tree_ready) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: no drafted tree");
-        n = c->tree_n;
+        for (int b = 0; b < B; ++b)
+            if (!c->seq[b].tree_ready) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: no drafted tree");
+        n = s0.tree_n;                                      // drafted trees all have total_tokens + 1 nodes
     }
-    if (t + n > c->cache_slots || t + cf.depth + 1 > cf.max_seq)
-        return fail(c, POSS_E_CAPACITY, "poss_verify_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
+    for (int b = 0; b < B; ++b) {
+        const int t = c->seq[b].t;
+        if (t + n > c->cache_slots || t + cf.depth + 1 > cf.max_seq)
+            return fail(c, POSS_E_CAPACITY, "poss_verify_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
+    }
     (void)hipEventRecord(c->ev[2], c->st);
     if (tree) {
+        const int t = s0.t;
         int32_t *stage = static_cast<int32_t *>(c->pinned);
         memcpy(stage, tree->token, n * sizeof(int32_t));
-        stage[0] = c->tokens[t];                                  // the root is always x_t
+        stage[0] = s0.tokens[t];                                  // the root is always x_t
         memcpy(stage + MAX_ROWS, tree->parent, n * sizeof(int32_t));
         stage[2 * MAX_ROWS] = n;
-        HIP_TRY(c, hipMemcpyAsync(c->td.token, stage, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-        HIP_TRY(c, hipMemcpyAsync(c->td.parent, stage + MAX_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-        HIP_TRY(c, hipMemcpyAsync(c->td.n_nodes, stage + 2 * MAX_ROWS, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-        launch_tree_upload_finish(n, t, c->td.token, c->td.parent, c->td.depth, c->td.pos, c->tree_slot, c->td.mask, c->st);
-        c->tree_n = n; c->tree_ready = 1;
+        HIP_TRY(c, hipMemcpyAsync(s0.td.token, stage, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        HIP_TRY(c, hipMemcpyAsync(s0.td.parent, stage + MAX_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        HIP_TRY(c, hipMemcpyAsync(s0.td.n_nodes, stage + 2 * MAX_ROWS, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+        launch_tree_upload_finish(n, t, s0.td.token, s0.td.parent, s0.td.depth, s0.td.pos, s0.tree_slot, s0.td.mask, c->st);
+        s0.tree_n = n; s0.tree_ready = 1;
     }                                     // (a drafted tree's slots were written when it was finalized)
-    RowMeta rm{c->td.pos, c->tree_slot, c->td.mask};
-    target_forward(c, n, c->td.token, rm, t, n);
-    GemmShape g = run_head(c, n);
-    { int rc = choose_tokens(c, g.Npad, n, c->td.depth); if (rc) return rc; }
+    // the trees' rows are adjacent slices of the batch-wide arrays: one pass over all of them
+    const int rows = B * n;
+    RowMeta rm{c->tree_pos_all, c->tree_slot_all, c->tree_mask_all};
+    std::vector<Seg> segs;
+    for (int b = 0; b < B; ++b) segs.push_back(Seg{b, nullptr, b * n, n, rows, 0, c->seq[b].t, n});
+    if (B == 1) segs[0].x0 = n;
+    target_forward(c, rows, c->tree_token_all, rm, segs);
+    GemmShape g = run_head(c, rows);
+    { int rc = choose_tokens(c, g.Npad, rows, c->tree_depth_all); if (rc) return rc; }
     (void)hipEventRecord(c->ev[3], c->st);
     c->ev_pending[1] = true;
     if (logits_out) launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
@@ -738,32 +906,56 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
     if (!c) return POSS_E_INVALID_ARG;
     if (c->state != ST_VERIFIED) return fail(c, POSS_E_BAD_STATE, "poss_accept_and_commit: no verified tree");
     const poss_config &cf = c->cfg;
-    const int t = c->t, L = cf.depth;
+    const int L = cf.depth, B = c->B;
     (void)hipEventRecord(c->ev[4], c->st);
-    launch_commit(c->md, cf.n_layers, c->target_kv_dev, c->td.token, c->td.parent, c->argmax_dev, c->td.n_nodes, L, t,
-                  c->feats, c->feat_stash, c->tokens_dev, c->walk_dev, c->result_dev, c->st);
+    for (int b = 0; b < B; ++b) {
+        Seq &sq = c->seq[b];
+        const int row0 = b * sq.tree_n;
+        launch_commit(c->md, cf.n_layers, sq.target_kv_dev, sq.td.token, sq.td.parent, c->argmax_dev + row0, sq.td.n_nodes, L, sq.t,
+                      c->feats + (size_t)row0 * cf.d_model, sq.feat_stash, sq.tokens_dev, sq.walk_dev, sq.result_dev, c->st);
+    }
     (void)hipEventRecord(c->ev[5], c->st);
     c->ev_pending[2] = true;
-    const int32_t *walk = c->result_pinned, *toks = walk + 32;     // written by the kernel itself
     { int rc = sync_and_harvest(c); if (rc) return rc; }
-    const int m = walk[0];
-    if (m < 0 || m > L) return fail(c, POSS_E_HIP, "poss_accept_and_commit: walk returned %d accepted tokens", m);
-    for (int j = 0; j <= m; ++j) c->tokens.push_back(toks[j]);
-    c->t = t + m + 1;
-    c->stats.rounds += 1;
-    c->stats.committed_tokens += m + 1;
-    for (int i = 1; i <= m; ++i) c->stats.c[i] += 1;
-    if (path_idx_out) for (int j = 0; j <= m; ++j) path_idx_out[j] = walk[2 + j];
-    if (n_accepted_out) *n_accepted_out = m;
-    if (committed_out) for (int j = 0; j <= m; ++j) committed_out[j] = toks[j];
-    if (n_committed_out) *n_committed_out = m + 1;
-    c->state = ST_READY; c->tree_ready = 0;
+    for (int b = 0; b < B; ++b) {
+        Seq &sq = c->seq[b];
+        const int32_t *walk = sq.result_pinned, *toks = walk + 32;     // written by the kernel itself
+        const int m = walk[0];
+        if (m < 0 || m > L) return fail(c, POSS_E_HIP, "poss_accept_and_commit: walk returned %d accepted tokens", m);
+        for (int j = 0; j <= m; ++j) { sq.tokens.push_back(toks[j]); sq.last_tokens[j] = toks[j]; sq.last_path[j] = walk[2 + j]; }
+        sq.last_m = m;
+        sq.t += m + 1;
+        sq.tree_ready = 0;
+        c->stats.rounds += 1;
+        c->stats.committed_tokens += m + 1;
+        for (int i = 1; i <= m; ++i) c->stats.c[i] += 1;
+    }
+    const Seq &s0 = c->seq[0];
+    if (path_idx_out) for (int j = 0; j <= s0.last_m; ++j) path_idx_out[j] = s0.last_path[j];
+    if (n_accepted_out) *n_accepted_out = s0.last_m;
+    if (committed_out) for (int j = 0; j <= s0.last_m; ++j) committed_out[j] = s0.last_tokens[j];
+    if (n_committed_out) *n_committed_out = s0.last_m + 1;
+    c->state = ST_READY;
+    return POSS_OK;
+}
+
+int poss_get_commit_seq(poss_ctx *c, int32_t seq, int32_t *path_idx_out, int32_t *n_accepted_out, int32_t *committed_out,
+                        int32_t *n_committed_out) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (seq < 0 || seq >= c->B) return fail(c, POSS_E_INVALID_ARG, "poss_get_commit_seq: no sequence %d (batch %d)", seq, c->B);
+    if (c->state != ST_READY || c->stats.rounds == 0) return fail(c, POSS_E_BAD_STATE, "poss_get_commit_seq: no committed round");
+    const Seq &sq = c->seq[seq];
+    if (path_idx_out) for (int j = 0; j <= sq.last_m; ++j) path_idx_out[j] = sq.last_path[j];
+    if (n_accepted_out) *n_accepted_out = sq.last_m;
+    if (committed_out) for (int j = 0; j <= sq.last_m; ++j) committed_out[j] = sq.last_tokens[j];
+    if (n_committed_out) *n_committed_out = sq.last_m + 1;
     return POSS_OK;
 }
 
 int poss_set_sampling(poss_ctx *c, float temperature, const float *u, int32_t n_u) {
     if (!c) return POSS_E_INVALID_ARG;
     if (!(temperature >= 0.f)) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: temperature must be >= 0");
+    if (temperature > 0.f && c->B > 1) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: batched rounds verify greedily (one set of uniform numbers serves one sequence)");
     if (temperature > 0.f) {
         if (!u || n_u < 1 || n_u > POSS_MAX_DEPTH + 1) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: needs 1..%d uniform numbers", POSS_MAX_DEPTH + 1);
         for (int i = 0; i < n_u; ++i)
@@ -782,15 +974,21 @@ int poss_get_stats(poss_ctx *c, poss_stats *out) {
     return POSS_OK;
 }
 
-int poss_get_tokens(poss_ctx *c, int32_t *tokens_out, int32_t cap, int32_t *n_out) {
+int poss_get_tokens_seq(poss_ctx *c, int32_t seq, int32_t *tokens_out, int32_t cap, int32_t *n_out) {
     if (!c) return POSS_E_INVALID_ARG;
-    const int n = (int)c->tokens.size();
+    if (seq < 0 || seq >= c->B) return fail(c, POSS_E_INVALID_ARG, "poss_get_tokens: no sequence %d (batch %d)", seq, c->B);
+    const std::vector<int32_t> &tokens = c->seq[seq].tokens;
+    const int n = (int)tokens.size();
     if (n_out) *n_out = n;
     if (tokens_out) {
         if (cap < n) return fail(c, POSS_E_CAPACITY, "poss_get_tokens: %d tokens, capacity %d", n, cap);
-        memcpy(tokens_out, c->tokens.data(), n * sizeof(int32_t));
+        memcpy(tokens_out, tokens.data(), n * sizeof(int32_t));
     }
     return POSS_OK;
+}
+
+int poss_get_tokens(poss_ctx *c, int32_t *tokens_out, int32_t cap, int32_t *n_out) {
+    return poss_get_tokens_seq(c, 0, tokens_out, cap, n_out);
 }
 
 int poss_profile_gemm(poss_ctx *c, int32_t enable) {
@@ -835,7 +1033,7 @@ int poss_debug_read_kv(poss_ctx *c, int32_t which, int32_t layer, int32_t slot0,
     if (n < 1 || slot0 < 0 || slot0 + n > c->cache_slots) return fail(c, POSS_E_INVALID_ARG, "poss_debug_read_kv: slots out of range");
     if (which >= c->cfg.n_specialists || (which < 0 && (layer < 0 || layer >= c->cfg.n_layers)))
         return fail(c, POSS_E_INVALID_ARG, "poss_debug_read_kv: no such cache");
-    const KVCache &kv = which < 0 ? c->target_kv[layer] : c->spec_kv[which];
+    const KVCache &kv = which < 0 ? c->seq[0].target_kv[layer] : c->seq[0].spec_kv[which];
     // stage through the partial-sum buffer (idle between calls)
     const size_t per = (size_t)c->md.hkv * c->md.dh;
     const int chunk = 64;

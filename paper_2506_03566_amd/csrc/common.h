@@ -99,8 +99,15 @@ struct EpiArgs {
 // part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.  after_stream, if given, is
 // recorded between the weight-streaming kernel and its epilogue kernel (per-launch timing).
 // Returns false, launching nothing, if a pointer the chosen epilogue writes through is null.
+// defer_epilogue (EPI_ROPE_KV only): the partial planes are left for launch_rope_kv_epilogue calls.
 bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t after_stream = nullptr);
+                 const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t after_stream = nullptr,
+                 bool defer_epilogue = false);
+// The RoPE + KV-write epilogue over rows [row_begin, row_end) of a deferred launch.  Row indices stay
+// those of the launch (epi.cs, epi.slot, epi.q are indexed by them; rows below epi.rows_q get a query):
+// several sequences batched into one GEMM each take their own rows into their own cache.
+bool launch_rope_kv_epilogue(int dt, const GemmShape &g, const float *part, const EpiArgs &epi, int row_begin, int row_end,
+                             hipStream_t st);
 
 // ---------------------------------------------------------------- launchers: elementwise
 // also writes the rotary table of the rows: cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)), angle formed in float64
@@ -151,6 +158,7 @@ struct DraftRowPlan {
     int32_t idx[MAX_ROWS];
     int32_t slot[MAX_ROWS];
     int32_t pos[MAX_ROWS];
+    int16_t dst[MAX_ROWS];        // row of the pass this plan row is written to (several sequences share a pass)
 };
 void launch_draft_assemble(const ModelDims &md, const DraftRowPlan &plan, int depth_index, int k,
                            const void *embed, const int32_t *tokens_dev, const void *feat_stash,

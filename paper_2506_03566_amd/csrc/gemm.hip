@@ -359,9 +359,9 @@ __global__ void gemm_f32_kernel(const float *__restrict__ W, const float *__rest
 // order (bitwise repeatable) and applies the fused operation.
 template <typename T, int EPI>
 __global__ __launch_bounds__(256) void epilogue_kernel(const float *__restrict__ part, size_t plane, int S, int Npad,
-                                                       int N, int M, EpiArgs epi) {
+                                                       int N, int row0, int M, EpiArgs epi) {   // rows [row0, M)
     constexpr int ROWS = EPI == EPI_PLAIN ? EPI_ROWS_PLAIN : EPI_ROWS_PAIR;
-    const int r0 = blockIdx.y * ROWS;
+    const int r0 = row0 + blockIdx.y * ROWS;
     tile_epilogue<T, EPI>(part, plane, S, Npad, N, r0, min(M, r0 + ROWS), blockIdx.x, epi);
 }
 
@@ -407,7 +407,7 @@ static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiAr
     dim3 eb(256);
     switch (epi.mode) {
         case EPI_ROPE_KV:
-            hipLaunchKernelGGL((epilogue_kernel<T, EPI_ROPE_KV>), pair_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+            hipLaunchKernelGGL((epilogue_kernel<T, EPI_ROPE_KV>), pair_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, 0, g.M, epi);
             break;
         case EPI_RESIDUAL: {
             int threads = round_up((g.N + 3) / 4, 64);
@@ -418,18 +418,18 @@ static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiAr
         }
         case EPI_SILU:
             if (silu_done) break;       // applied inside the stream kernel
-            hipLaunchKernelGGL((epilogue_kernel<T, EPI_SILU>), pair_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+            hipLaunchKernelGGL((epilogue_kernel<T, EPI_SILU>), pair_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, 0, g.M, epi);
             break;
         default:
             if (g.S > 1 || epi.out)     // S == 1 without an output buffer: plane 0 is the result
-                hipLaunchKernelGGL((epilogue_kernel<T, EPI_PLAIN>), plain_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, g.M, epi);
+                hipLaunchKernelGGL((epilogue_kernel<T, EPI_PLAIN>), plain_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, 0, g.M, epi);
             break;
     }
 }
 
 template <typename T>
 static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                          const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream) {
+                          const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream, bool defer_epilogue) {
     // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
     const bool fuse_silu = epi.mode == EPI_SILU && g.S == 1;
     const bool wide = !fuse_silu && g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
@@ -460,7 +460,7 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
 #undef POSS_GEMM_CASE
 #undef POSS_GEMM_LAUNCH
     if (after_stream) (void)hipEventRecord(after_stream, st);
-    launch_epilogue_t<T>(g, part, epi, eps, fuse_silu, st);
+    if (!defer_epilogue) launch_epilogue_t<T>(g, part, epi, eps, fuse_silu, st);
 }
 
 // Refuse, on the host, argument sets that would make a kernel write through a null pointer.
@@ -476,19 +476,35 @@ static bool gemm_args_ok(const GemmShape &g, const void *Wp, const void *X, cons
 }
 
 bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream) {
+                 const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream, bool defer_epilogue) {
     if (!gemm_args_ok(g, Wp, X, part, epi)) return false;
+    if (defer_epilogue && epi.mode != EPI_ROPE_KV) return false;       // only that epilogue can be launched by row range
     if (dt == DT_F32) {
         dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
         hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
                            static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
         if (after_stream) (void)hipEventRecord(after_stream, st);
-        launch_epilogue_t<float>(g, part, epi, eps, false, st);
+        if (!defer_epilogue) launch_epilogue_t<float>(g, part, epi, eps, false, st);
     } else if (dt == DT_BF16) {
-        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st, after_stream);
+        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st, after_stream, defer_epilogue);
     } else {
-        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st, after_stream);
+        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st, after_stream, defer_epilogue);
     }
+    return true;
+}
+
+bool launch_rope_kv_epilogue(int dt, const GemmShape &g, const float *part, const EpiArgs &epi, int row_begin, int row_end,
+                             hipStream_t st) {
+    if (!part || epi.mode != EPI_ROPE_KV || row_begin < 0 || row_end > g.M || row_begin >= row_end) return false;
+    if (!epi.q || !epi.cs || !epi.slot || !epi.kv.k || !epi.kv.vt || !epi.kv.page_table) return false;
+    const size_t plane = (size_t)g.Mpad * g.Npad;
+    dim3 grid(g.Npad / GEMM_BLOCK_N, (row_end - row_begin + EPI_ROWS_PAIR - 1) / EPI_ROWS_PAIR), eb(256);
+    if (dt == DT_F32)
+        hipLaunchKernelGGL((epilogue_kernel<float, EPI_ROPE_KV>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, row_begin, row_end, epi);
+    else if (dt == DT_BF16)
+        hipLaunchKernelGGL((epilogue_kernel<bf16_t, EPI_ROPE_KV>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, row_begin, row_end, epi);
+    else
+        hipLaunchKernelGGL((epilogue_kernel<f16_t, EPI_ROPE_KV>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, row_begin, row_end, epi);
     return true;
 }
 

@@ -332,9 +332,9 @@ __global__ __launch_bounds__(256) void draft_assemble_kernel(
     const float *__restrict__ fhat_prev, T *__restrict__ xin_tmp, T *__restrict__ x_out,
     int32_t *__restrict__ pos_out, int32_t *__restrict__ slot_out, uint64_t *__restrict__ mask_out,
     const double *__restrict__ inv_freq, int half, float2 *__restrict__ cs) {
-    const int row = blockIdx.x, kind = plan.kind[row], idx = plan.idx[row];
+    const int prow = blockIdx.x, kind = plan.kind[prow], idx = plan.idx[prow], row = plan.dst[prow];
     // the pass's rotary table, row by row; by the last wave, which has the least copying to do
-    rope_table_row(plan.pos[row], inv_freq, half, cs + (size_t)row * half, half <= 64 ? (int)blockDim.x - 64 : 0);
+    rope_table_row(plan.pos[prow], inv_freq, half, cs + (size_t)row * half, half <= 64 ? (int)blockDim.x - 64 : 0);
     T *dst = x_out + (size_t)row * 2 * d_model;
     uint64_t w0 = plan.mask0[0], w1 = plan.mask0[1];
     constexpr int VE = 16 / (int)sizeof(T);              // elements per 16-byte access
@@ -387,8 +387,8 @@ __global__ __launch_bounds__(256) void draft_assemble_kernel(
         w0 = td.fr_mask[o * MASK_WORDS]; w1 = td.fr_mask[o * MASK_WORDS + 1];
     }
     if (threadIdx.x == 0) {
-        pos_out[row] = plan.pos[row];
-        slot_out[row] = plan.slot[row];
+        pos_out[row] = plan.pos[prow];
+        slot_out[row] = plan.slot[prow];
         mask_out[row * MASK_WORDS] = w0;
         mask_out[row * MASK_WORDS + 1] = w1;
     }

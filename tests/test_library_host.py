@@ -28,8 +28,8 @@ def test_exports_match_header():
 
 
 def test_struct_layout_matches_header():
-    # 7 ints, 2 floats, 10 ints = 76 bytes; the stats struct: 2 + 17 int64 + 3 doubles
-    assert ctypes.sizeof(P.PossConfig) == 19 * 4
+    # 7 ints, 2 floats, 11 ints = 80 bytes; the stats struct: 2 + 17 int64 + 3 doubles
+    assert ctypes.sizeof(P.PossConfig) == 20 * 4
     assert ctypes.sizeof(P.PossStats) == 19 * 8 + 3 * 8
 
 
