@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--total-tokens", type=int, default=0, help="override the number of draft tokens N (sweeps)")
     ap.add_argument("--specialists", type=int, default=0, help="override the number of specialists S (sweeps)")
     ap.add_argument("--positions", type=int, default=0, help="override positions per specialist n (sweeps)")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="sequences per round (the headline metric is quoted at 1); rows of all sequences share the weight streams")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0: verification draws the target's tokens at this temperature (sampler kernels "
                          "instead of argmax); the headline metric is quoted at 0")
@@ -133,7 +135,11 @@ def main():
     t0 = time.perf_counter()
     weights = make_weights_on_device(cfg)
     t_gen = time.perf_counter() - t0
-    ctx = P.Poss(cfg, weights)
+    B = max(1, args.batch)
+    if B > 1 and args.temperature > 0:
+        print("bench.py: batched rounds verify greedily; --temperature needs --batch 1", file=sys.stderr)
+        sys.exit(2)
+    ctx = P.Poss(cfg, weights, batch=B)
     del weights
     torch.cuda.empty_cache()
     if args.gemm_wgs or args.attn_split:
@@ -144,6 +150,8 @@ def main():
     ctx.prefill(prompt)
     torch.cuda.synchronize()
     t_prefill = time.perf_counter() - t0
+    for b in range(1, B):                             # further sequences: other prompts of the same length
+        ctx.prefill(make_prompt(cfg.with_(prompt_seed=cfg.prompt_seed + 17 * b)), seq=b)
 
     import numpy as np
     u_rng = np.random.default_rng(0)
@@ -167,11 +175,11 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     s1 = ctx.stats()
-    rounds = s1.rounds - base[0]
+    rounds = (s1.rounds - base[0]) // B               # the statistics count one round per sequence and call
     committed = s1.committed_tokens - base[1]
     ms_round = wall * 1e3 / rounds
-    t_mid = t_begin + committed // 2
-    bytes_round = round_bytes(cfg, t_mid, 1)
+    t_mid = t_begin + committed // (2 * B)
+    bytes_round = round_bytes(cfg, t_mid, 1) + (B - 1) * (round_bytes(cfg, t_mid, 1) - round_bytes(cfg, 0, 1))   # weights once, KV per sequence
     gbps = bytes_round / (ms_round * 1e-3) / 1e9
 
     # dominant kernel: the weight-streaming GEMM, timed per launch with HIP events on the library's stream
@@ -184,7 +192,7 @@ def main():
     achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
     roofline = dict(bound="hbm", kernel="gemm_stream_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS,
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4),
-                    traffic=(sum(MEASURED_TRAFFIC[cfg.name].values()) if cfg.name in MEASURED_TRAFFIC and not over else None),
+                    traffic=(sum(MEASURED_TRAFFIC[cfg.name].values()) if cfg.name in MEASURED_TRAFFIC and not over and B == 1 else None),
                     algorithmic_bytes_per_launch=round(gemm_bytes / max(launches, 1), 1),
                     launches_per_round=launches // max(prof_rounds, 1),
                     avg_launch_us=round(gemm_ms * 1e3 / max(launches, 1), 2),
@@ -196,9 +204,9 @@ def main():
                config=dict(workload=cfg.name, target_layers=cfg.n_layers, d_model=cfg.d_model, vocab=cfg.vocab,
                            specialists=cfg.n_specialists, positions_per_specialist=cfg.positions_per_specialist,
                            top_k=cfg.top_k, depth=cfg.depth, total_tokens=cfg.total_tokens,
-                           n_prompt=cfg.n_prompt, batch=1, t_at_timing=t_mid),
+                           n_prompt=cfg.n_prompt, batch=B, t_at_timing=t_mid),
                round_latency_ms=round(ms_round, 4), hbm_gbps=round(gbps, 1), hbm_frac=round(gbps / HBM_PEAK_GBPS, 4),
-               bytes_per_round=bytes_round, tau_gen=round(committed / rounds, 3),
+               bytes_per_round=bytes_round, tau_gen=round(committed / (rounds * B), 3),
                phase_ms=dict(draft=round((s1.ms_draft - base[2]) / rounds, 4),
                              verify=round((s1.ms_verify - base[3]) / rounds, 4),
                              commit=round((s1.ms_commit - base[4]) / rounds, 4)),
@@ -206,7 +214,7 @@ def main():
     # Plain autoregressive decoding of the same target through the same library: rounds whose tree is the
     # root alone (one target pass over one row, one committed token).  The denominator of the paper's
     # speed-up ratio (Table 2); measured, while the ratio at the paper's tau stays a projection.
-    if args.vanilla_steps > 0:
+    if args.vanilla_steps > 0 and B == 1:
         ctx.reset()
         if args.temperature > 0:
             ctx.set_sampling(0.0)
@@ -234,7 +242,7 @@ def main():
     if cfg.name in PAPER_TAU and not over:
         # NOT a measurement: random-init drafters accept nothing (tau_gen = 1), so this only restates the
         # measured round latency at the acceptance length the paper reports for trained drafters.
-        out["projection"] = dict(tokens_per_s_at_paper_tau=round(PAPER_TAU[cfg.name] / (ms_round * 1e-3), 1),
+        out["projection"] = dict(tokens_per_s_at_paper_tau=round(B * PAPER_TAU[cfg.name] / (ms_round * 1e-3), 1),
                                  paper_tau=PAPER_TAU[cfg.name],
                                  note="projection, not measured: paper's Table 1 tau (trained drafter, six suites, "
                                       "A100; bonus-token convention not stated) x this build's round latency")

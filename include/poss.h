@@ -150,7 +150,8 @@ int poss_get_tree_seq(poss_ctx *ctx, int32_t seq, poss_tree *out);
  * [n_nodes, d_model], may be NULL) receive Head(f) and f of every row (Eq. 6).  With all three
  * outputs NULL the call returns once the work is queued (no host wait), so that a round
  * draft -> verify -> accept waits for the device once, in poss_accept_and_commit; the tree
- * arrays are copied before the call returns. */
+ * arrays are copied before the call returns.  With batch > 1: tree must be NULL (the drafted trees
+ * of all sequences are verified in one pass); the outputs then cover sequence 0's rows. */
 int poss_verify_tree(poss_ctx *ctx, const poss_tree *tree, int32_t *argmax_out,
                      void *logits_out, void *feat_out);
 
@@ -159,7 +160,9 @@ int poss_verify_tree(poss_ctx *ctx, const poss_tree *tree, int32_t *argmax_out,
  * moves the accepted rows' keys/values to positions t.., keeps their features for the next
  * draft, appends the accepted tokens and the bonus token (the target's choice after the last
  * accepted node).  All outputs HOST, any may be NULL: path_idx_out[depth+1] node indices starting
- * with 0; *n_accepted_out = m; committed_out[depth+1] the m+1 new tokens; *n_committed_out = m+1. */
+ * with 0; *n_accepted_out = m; committed_out[depth+1] the m+1 new tokens; *n_committed_out = m+1.
+ * With batch > 1 every sequence is committed (one kernel launch each, one wait); the outputs are
+ * sequence 0's, poss_get_commit_seq has the others; the statistics count one round per sequence. */
 int poss_accept_and_commit(poss_ctx *ctx, int32_t *path_idx_out, int32_t *n_accepted_out,
                            int32_t *committed_out, int32_t *n_committed_out);
 /* What the last poss_accept_and_commit did for sequence seq (same outputs; no device work). */

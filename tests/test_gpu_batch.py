@@ -1,0 +1,162 @@
+"""Several sequences per round: a batched context must give every sequence exactly what it gets
+alone (same tokens, trees, accepted paths: a row's arithmetic does not depend on which other rows
+share its launches), and through that what the oracle computes for it."""
+import numpy as np
+import pytest
+
+from gpu_util import have_gpu, Pair, tree_from_gpu
+
+pytestmark = pytest.mark.gpu
+
+if have_gpu():
+    import paper_2506_03566_amd as P
+    from synth import get_config, make_prompt
+    from test_gpu_draft import _perfect_drafter_storage
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _prompts(cfg, lengths):
+    # different prompts of different lengths: sequences sit at different positions in every round
+    return [[int(x) for x in make_prompt(cfg.with_(prompt_seed=cfg.prompt_seed + 17 * i), n=n)] for i, n in enumerate(lengths)]
+
+
+def _rounds_alone(pair, prompt, n_rounds):
+    """One sequence in a context of its own (the batch-1 path): per round (tree, path, m, tokens)."""
+    ctx = P.Poss(pair.cfg, pair.dev_weights)
+    first = ctx.prefill(prompt)
+    out = []
+    for _ in range(n_rounds):
+        tr = ctx.draft_tree().as_dict()
+        ctx.verify_tree(want_argmax=False)
+        path, m, toks = ctx.accept_and_commit()
+        out.append((tr, path, m, toks))
+    tokens = ctx.tokens()
+    ctx.close()
+    return first, out, tokens
+
+
+def _same_tree(a, b):
+    return (a["n"] == b["n"] and a["token"] == b["token"] and a["parent"] == b["parent"] and a["depth"] == b["depth"]
+            and a["pos"] == b["pos"] and a["mask"] == b["mask"] and np.array_equal(a["score"], b["score"]))
+
+
+@pytest.mark.parametrize("name,batch,lengths,perfect,n_rounds", [
+    ("c0_tiny_f32", 3, (16, 23, 40), False, 4),          # random drafter: every round commits the bonus token only
+    ("c0_tiny_f32", 3, (16, 23, 40), True, 3),           # perfect drafter: full depth accepted, long catch-up rows
+    ("t_tiny_f32_6x1", 2, (70, 33), True, 3),            # six specialists, one position each
+    ("t_mid_bf16", 2, (150, 97), False, 4),              # 16-bit storage, 2 x 61 rows in the verification pass
+    ("t_mid_f16", 1, (131,), False, 2),                  # batch field set to 1: the single-sequence path
+])
+def test_batched_rounds_equal_sequences_alone(name, batch, lengths, perfect, n_rounds):
+    cfg = get_config(name)
+    pair = Pair(name, storage=_perfect_drafter_storage(cfg) if perfect else None, lib_over={"batch": batch})
+    ctx = pair.ctx
+    prompts = _prompts(cfg, lengths)
+    _say(f"batch {batch} of {name}, prompts {lengths}, perfect drafter {perfect}")
+    alone = [_rounds_alone(pair, p, n_rounds) for p in prompts]
+    firsts = [ctx.prefill(p, seq=b) for b, p in enumerate(prompts)]
+    assert firsts == [a[0] for a in alone]
+    for rnd in range(n_rounds):
+        tr0 = ctx.draft_tree()
+        trees = [ctx.get_tree(b).as_dict() for b in range(batch)]
+        assert _same_tree(tr0.as_dict(), trees[0])
+        ctx.verify_tree(want_argmax=False)
+        path0, m0, toks0 = ctx.accept_and_commit()
+        for b in range(batch):
+            atr, apath, am, atoks = alone[b][1][rnd]
+            assert _same_tree(trees[b], atr), f"round {rnd}, sequence {b}: tree differs"
+            path, m, toks = ctx.commit_result(b)
+            assert (path, m, toks) == (apath, am, atoks), f"round {rnd}, sequence {b}"
+            if b == 0:
+                assert (path0, m0, toks0) == (path, m, toks)
+        _say(f"  round {rnd}: accepted {[ctx.commit_result(b)[1] for b in range(batch)]}")
+    for b in range(batch):
+        assert ctx.tokens(b) == alone[b][2]
+    st = ctx.stats()
+    assert st.rounds == batch * n_rounds                               # one round per sequence and call
+    assert st.committed_tokens == sum(len(alone[b][2]) - len(prompts[b]) - 1 for b in range(batch))
+    if perfect:
+        assert [ctx.commit_result(b)[1] for b in range(batch)] == [cfg.depth] * batch
+    if cfg.dtype == 0:
+        # float32 storage: the free-running oracle gives the same stream
+        for b in range(batch):
+            o = pair.oracle()
+            want = o.generate(prompts[b], len(ctx.tokens(b)) - len(prompts[b]))
+            assert ctx.tokens(b)[:len(want)] == want[:len(ctx.tokens(b))]
+    pair.close()
+
+
+def test_batched_context_refuses_what_it_cannot_do():
+    cfg = get_config("c0_tiny_f32")
+    pair = Pair("c0_tiny_f32", lib_over={"batch": 2})
+    ctx = pair.ctx
+    p0, p1 = _prompts(cfg, (12, 20))
+    with pytest.raises(P.PossError):
+        ctx.prefill(p0, seq=2)                                         # no such sequence
+    ctx.prefill(p0, seq=0)
+    with pytest.raises(P.PossError):
+        ctx.draft_tree()                                               # sequence 1 has no prompt yet
+    with pytest.raises(P.PossError):
+        ctx.prefill(p0, seq=0)                                         # already started
+    ctx.prefill(p1, seq=1)
+    with pytest.raises(P.PossError):
+        ctx.set_sampling(1.0, [0.5])                                   # batched rounds verify greedily
+    ctx.draft_tree(want_tree=False)
+    tree = ctx.get_tree(1)
+    with pytest.raises(P.PossError):
+        ctx.verify_tree(tree)                                          # a caller's tree needs batch 1
+    ctx.verify_tree(want_argmax=False)
+    ctx.accept_and_commit()
+    with pytest.raises(P.PossError):
+        ctx.commit_result(5)
+    assert len(ctx.tokens(0)) >= len(p0) + 2 and len(ctx.tokens(1)) >= len(p1) + 2
+    ctx.reset()
+    with pytest.raises(P.PossError):
+        ctx.draft_tree()
+    pair.close()
+    # configurations whose stacked rows do not fit one launch are rejected at load
+    for over in ({"batch": 9}, {"batch": 6}):                          # 6 x 25 verification rows > 128
+        with pytest.raises(P.PossError):
+            P.Poss(cfg, pair.dev_weights, **over)
+
+
+def test_full_size_batch_of_two_equals_each_sequence_alone():
+    """The benchmark shape with two sequences per round (2 x 61 rows in the verification pass, the
+    128-row GEMM instantiations): trees, accepted paths and tokens of each sequence are the ones a
+    context of its own produces."""
+    import torch
+    from synth.gpu import make_weights_on_device
+    cfg = get_config("c1_llama3_8b_3x2")
+    _say("generating weights of c1_llama3_8b_3x2")
+    dev = make_weights_on_device(cfg)
+    prompts = _prompts(cfg, (cfg.n_prompt, 300))
+    n_rounds = 3
+    ctx = P.Poss(cfg, dev, batch=2)
+    for b, p in enumerate(prompts):
+        ctx.prefill(p, seq=b)
+    got = []
+    for rnd in range(n_rounds):
+        ctx.draft_tree(want_tree=False)
+        trees = [ctx.get_tree(b).as_dict() for b in range(2)]
+        ctx.verify_tree(want_argmax=False)
+        ctx.accept_and_commit()
+        got.append([(trees[b],) + ctx.commit_result(b) for b in range(2)])
+    tokens = [ctx.tokens(b) for b in range(2)]
+    ctx.close()
+    torch.cuda.empty_cache()
+    for b, p in enumerate(prompts):
+        one = P.Poss(cfg, dev)
+        one.prefill(p)
+        for rnd in range(n_rounds):
+            tr = one.draft_tree().as_dict()
+            one.verify_tree(want_argmax=False)
+            path, m, toks = one.accept_and_commit()
+            assert _same_tree(got[rnd][b][0], tr), f"round {rnd}, sequence {b}: tree differs"
+            assert got[rnd][b][1:] == (path, m, toks), f"round {rnd}, sequence {b}"
+        assert one.tokens() == tokens[b]
+        one.close()
+        torch.cuda.empty_cache()
+        _say(f"  sequence {b}: {n_rounds} rounds identical")
