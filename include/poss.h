@@ -6,7 +6,7 @@
  *   poss_load -> poss_prefill -> ( poss_draft_tree -> poss_verify_tree
  *                                  -> poss_accept_and_commit )*
  *
- * With poss_config.batch = B > 1 a context carries B independent sequences (greedy verification):
+ * With poss_config.batch = B > 1 a context carries B independent sequences:
  * each has its own caches, tree and token stream, every pass stacks their rows into one set of
  * weight-streaming launches, and the three round calls advance all of them; poss_prefill_seq,
  * poss_get_tree_seq, poss_get_commit_seq and poss_get_tokens_seq address one sequence (the calls
@@ -180,6 +180,9 @@ int poss_get_commit_seq(poss_ctx *ctx, int32_t seq, int32_t *path_idx_out, int32
  * returns; it stays in force until the next call.  temperature == 0 restores greedy verification
  * (u ignored).  Statistics count accepted draft tokens as before. */
 int poss_set_sampling(poss_ctx *ctx, float temperature, const float *u, int32_t n_u);
+/* With batch > 1 poss_set_sampling gives every sequence the same numbers; this call gives sequence
+ * seq its own (same rules for u and n_u; the temperature is the context's). */
+int poss_set_uniforms_seq(poss_ctx *ctx, int32_t seq, const float *u, int32_t n_u);
 
 /* Waits for queued work, then copies the statistics. */
 int poss_get_stats(poss_ctx *ctx, poss_stats *out);

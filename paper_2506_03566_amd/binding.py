@@ -16,7 +16,7 @@ MAX_ROWS, MASK_WORDS, MAX_DEPTH = 128, 2, 16
 
 EXPORTS = ["poss_workspace_bytes", "poss_load", "poss_reset", "poss_prefill", "poss_draft_tree",
            "poss_verify_tree", "poss_accept_and_commit", "poss_get_stats", "poss_get_tokens",
-           "poss_prefill_seq", "poss_get_tree_seq", "poss_get_commit_seq", "poss_get_tokens_seq",
+           "poss_prefill_seq", "poss_get_tree_seq", "poss_get_commit_seq", "poss_get_tokens_seq", "poss_set_uniforms_seq",
            "poss_last_error", "poss_free", "poss_profile_gemm", "poss_gemm_profile", "poss_set_tuning", "poss_set_sampling",
            "poss_debug_build_tree", "poss_debug_set_taps", "poss_debug_read_kv",
            "poss_debug_gemm_scratch_bytes", "poss_debug_gemm"]
@@ -88,6 +88,7 @@ def load_library():
     lib.poss_gemm_profile.argtypes = [c_vp, P(ctypes.c_int64), P(ctypes.c_double), P(ctypes.c_double)]
     lib.poss_set_tuning.argtypes = [c_vp, c_i32, c_i32]
     lib.poss_set_sampling.argtypes = [c_vp, c_f32, ctypes.POINTER(c_f32), c_i32]
+    lib.poss_set_uniforms_seq.argtypes = [c_vp, c_i32, ctypes.POINTER(c_f32), c_i32]
     lib.poss_debug_build_tree.argtypes = [c_vp, P(c_i32), P(c_f32), P(PossTree)]
     lib.poss_debug_set_taps.argtypes = [c_vp, c_vp]
     lib.poss_debug_read_kv.argtypes = [c_vp, c_i32, c_i32, c_i32, c_i32, P(c_f32), P(c_f32)]
@@ -265,6 +266,11 @@ class Poss:
             return
         u = np.ascontiguousarray(u, dtype=np.float32)
         self._check(self.lib.poss_set_sampling(self.h, float(temperature), u.ctypes.data_as(ctypes.POINTER(c_f32)), len(u)))
+
+    def set_uniforms(self, seq, u):
+        """Uniform numbers of one sequence of a batch (set_sampling gives all sequences the same ones)."""
+        u = np.ascontiguousarray(u, dtype=np.float32)
+        self._check(self.lib.poss_set_uniforms_seq(self.h, seq, u.ctypes.data_as(ctypes.POINTER(c_f32)), len(u)))
 
     def set_tuning(self, gemm_target_workgroups=0, attn_keys_per_split=0):
         self._check(self.lib.poss_set_tuning(self.h, gemm_target_workgroups, attn_keys_per_split))

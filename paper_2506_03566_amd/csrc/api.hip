@@ -91,7 +91,7 @@ struct poss_ctx {
     bool ev_pending[3];                // phase recorded, elapsed time not yet added to the statistics
     bool launch_refused;               // a GEMM launch was refused on the host (null operand): internal error
     float temperature;                 // 0: greedy verification; > 0: the target's tokens are drawn (poss_set_sampling)
-    float *u_pinned, *u_dev;           // one uniform number per tree depth, host staging and device copy
+    float *u_pinned, *u_dev;           // per sequence, one uniform number per tree depth: host staging and device copy
     int gemm_target_wgs, attn_keys_per_split;
     // gemm profiling
     int prof_on, prof_n;
@@ -241,7 +241,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     int32_t *topk_id_all = a.take_n<int32_t>((size_t)QR * 16); float *topk_logp_all = a.take_n<float>((size_t)QR * 16);
     int32_t *argmax_dev = a.take_n<int32_t>(R);
     double *inv_freq = a.take_n<double>(c.head_dim / 2);
-    float *u_dev = a.take_n<float>(POSS_MAX_DEPTH + 1);
+    float *u_dev = a.take_n<float>((size_t)B * (POSS_MAX_DEPTH + 1));
     // per sequence: tree state, token stream, feature stash, stored frontier rows
     const int k = c.top_k, L = c.depth, pool = k + (L - 1) * k * k, stride = c.total_tokens + 1;
     std::vector<Seq> seqs(B);
@@ -574,8 +574,8 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     // small host->device tables
     c->pinned_bytes = 1 << 20;
     LOAD_TRY(hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault));
-    LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->u_pinned), (POSS_MAX_DEPTH + 1) * sizeof(float), hipHostMallocDefault));
-    for (int i = 0; i <= POSS_MAX_DEPTH; ++i) c->u_pinned[i] = 0.f;
+    LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->u_pinned), (size_t)c->B * (POSS_MAX_DEPTH + 1) * sizeof(float), hipHostMallocDefault));
+    for (int i = 0; i < c->B * (POSS_MAX_DEPTH + 1); ++i) c->u_pinned[i] = 0.f;
     LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->result_pinned_all), (size_t)c->B * 64 * sizeof(int32_t), hipHostMallocDefault));
     {
         int32_t *dev = nullptr;
@@ -633,7 +633,7 @@ void poss_free(poss_ctx *c) {
 
 const char *poss_last_error(poss_ctx *c) { return c ? c->err : g_load_error; }
 
-static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth);
+static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, int seq_first, int rows_each);
 
 int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
     if (!c) return POSS_E_INVALID_ARG;
@@ -660,7 +660,7 @@ int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_
             EpiArgs pe{};
             pe.mode = EPI_PLAIN;
             GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true, pe);
-            { int rc = choose_tokens(c, g.Npad, 1, nullptr); if (rc) return rc; }
+            { int rc = choose_tokens(c, g.Npad, 1, nullptr, seq, 1); if (rc) return rc; }
             HIP_TRY(c, hipMemcpyAsync(sq.tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
         }
         HIP_TRY(c, hipStreamSynchronize(c->st));          // the staging buffer is reused by the next chunk
@@ -687,11 +687,15 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
 
 // The token the target chooses after each of `rows` rows of c->logits: the argmax, or at temperature > 0 a
 // draw by inverse CDF with the uniform number of the row's depth (depth == nullptr: all rows use u[0]).
-static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth) {
+// The rows are rows_each per sequence, starting with sequence seq_first: each sequence has its own numbers.
+static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, int seq_first, int rows_each) {
     if (c->temperature > 0.f) {
-        HIP_TRY(c, hipMemcpyAsync(c->u_dev, c->u_pinned, (POSS_MAX_DEPTH + 1) * sizeof(float), hipMemcpyHostToDevice, c->st));
-        if (!launch_sample(c->logits, ld, rows, c->cfg.vocab, c->temperature, c->u_dev, depth, c->topk_scratch, c->argmax_dev, c->st))
-            return fail(c, POSS_E_INVALID_ARG, "sampling: vocabulary too large for the sampler");
+        const int nu = POSS_MAX_DEPTH + 1;
+        HIP_TRY(c, hipMemcpyAsync(c->u_dev, c->u_pinned, (size_t)c->B * nu * sizeof(float), hipMemcpyHostToDevice, c->st));
+        for (int r0 = 0, b = seq_first; r0 < rows; r0 += rows_each, ++b)
+            if (!launch_sample(c->logits + (size_t)r0 * ld, ld, rows_each, c->cfg.vocab, c->temperature, c->u_dev + (size_t)b * nu,
+                               depth ? depth + r0 : nullptr, c->topk_scratch, c->argmax_dev + r0, c->st))
+                return fail(c, POSS_E_INVALID_ARG, "sampling: vocabulary too large for the sampler");
     } else {
         launch_argmax(c->logits, ld, rows, c->cfg.vocab, c->topk_scratch, c->argmax_dev, c->st);
     }
@@ -887,7 +891,7 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     if (B == 1) segs[0].x0 = n;
     target_forward(c, rows, c->tree_token_all, rm, segs);
     GemmShape g = run_head(c, rows);
-    { int rc = choose_tokens(c, g.Npad, rows, c->tree_depth_all); if (rc) return rc; }
+    { int rc = choose_tokens(c, g.Npad, rows, c->tree_depth_all, 0, n); if (rc) return rc; }
     (void)hipEventRecord(c->ev[3], c->st);
     c->ev_pending[1] = true;
     if (logits_out) launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
@@ -952,18 +956,32 @@ int poss_get_commit_seq(poss_ctx *c, int32_t seq, int32_t *path_idx_out, int32_t
     return POSS_OK;
 }
 
+static int check_uniforms(poss_ctx *c, const float *u, int32_t n_u) {
+    if (!u || n_u < 1 || n_u > POSS_MAX_DEPTH + 1) return fail(c, POSS_E_INVALID_ARG, "sampling: needs 1..%d uniform numbers", POSS_MAX_DEPTH + 1);
+    for (int i = 0; i < n_u; ++i)
+        if (!(u[i] >= 0.f && u[i] < 1.f)) return fail(c, POSS_E_INVALID_ARG, "sampling: u[%d] is not in [0, 1)", i);
+    return POSS_OK;
+}
+
 int poss_set_sampling(poss_ctx *c, float temperature, const float *u, int32_t n_u) {
     if (!c) return POSS_E_INVALID_ARG;
     if (!(temperature >= 0.f)) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: temperature must be >= 0");
-    if (temperature > 0.f && c->B > 1) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: batched rounds verify greedily (one set of uniform numbers serves one sequence)");
     if (temperature > 0.f) {
-        if (!u || n_u < 1 || n_u > POSS_MAX_DEPTH + 1) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: needs 1..%d uniform numbers", POSS_MAX_DEPTH + 1);
-        for (int i = 0; i < n_u; ++i)
-            if (!(u[i] >= 0.f && u[i] < 1.f)) return fail(c, POSS_E_INVALID_ARG, "poss_set_sampling: u[%d] is not in [0, 1)", i);
+        { int rc = check_uniforms(c, u, n_u); if (rc) return rc; }
         HIP_TRY(c, hipStreamSynchronize(c->st));           // a queued verification may still read the staging array
-        for (int i = 0; i <= POSS_MAX_DEPTH; ++i) c->u_pinned[i] = i < n_u ? u[i] : u[n_u - 1];
+        for (int b = 0; b < c->B; ++b)                     // every sequence; poss_set_uniforms_seq gives one its own
+            for (int i = 0; i <= POSS_MAX_DEPTH; ++i) c->u_pinned[b * (POSS_MAX_DEPTH + 1) + i] = i < n_u ? u[i] : u[n_u - 1];
     }
     c->temperature = temperature;
+    return POSS_OK;
+}
+
+int poss_set_uniforms_seq(poss_ctx *c, int32_t seq, const float *u, int32_t n_u) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (seq < 0 || seq >= c->B) return fail(c, POSS_E_INVALID_ARG, "poss_set_uniforms_seq: no sequence %d (batch %d)", seq, c->B);
+    { int rc = check_uniforms(c, u, n_u); if (rc) return rc; }
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    for (int i = 0; i <= POSS_MAX_DEPTH; ++i) c->u_pinned[seq * (POSS_MAX_DEPTH + 1) + i] = i < n_u ? u[i] : u[n_u - 1];
     return POSS_OK;
 }
 

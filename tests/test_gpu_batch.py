@@ -103,7 +103,9 @@ def test_batched_context_refuses_what_it_cannot_do():
         ctx.prefill(p0, seq=0)                                         # already started
     ctx.prefill(p1, seq=1)
     with pytest.raises(P.PossError):
-        ctx.set_sampling(1.0, [0.5])                                   # batched rounds verify greedily
+        ctx.set_uniforms(2, [0.5])                                     # no such sequence
+    with pytest.raises(P.PossError):
+        ctx.set_uniforms(1, [1.0])                                     # not in [0, 1)
     ctx.draft_tree(want_tree=False)
     tree = ctx.get_tree(1)
     with pytest.raises(P.PossError):
@@ -160,3 +162,51 @@ def test_full_size_batch_of_two_equals_each_sequence_alone():
         one.close()
         torch.cuda.empty_cache()
         _say(f"  sequence {b}: {n_rounds} rounds identical")
+
+
+@pytest.mark.parametrize("name,batch,lengths", [("c0_tiny_f32", 3, (16, 23, 40)), ("t_mid_bf16", 2, (150, 97))])
+def test_batched_sampling_equals_sequences_alone(name, batch, lengths):
+    """Verification at a temperature with a set of uniform numbers per sequence: every sequence of the
+    batch commits the tokens it commits alone with the same numbers (and, in float32 storage, the
+    tokens of the oracle's sampler)."""
+    cfg = get_config(name)
+    pair = Pair(name, lib_over={"batch": batch})
+    ctx = pair.ctx
+    prompts = _prompts(cfg, lengths)
+    n_rounds, T = 4, 0.8
+    rng = np.random.default_rng(11)
+    # U[b][position]: one number per absolute sequence position, as the oracle indexes them
+    U = [rng.random(max(lengths) + n_rounds * (cfg.depth + 1) + 2).astype(np.float32) for _ in range(batch)]
+    alone = []
+    for b, p in enumerate(prompts):
+        one = P.Poss(cfg, pair.dev_weights)
+        one.set_sampling(T, [U[b][len(p)]])
+        one.prefill(p)
+        for _ in range(n_rounds):
+            t = len(one.tokens()) - 1
+            one.set_sampling(T, U[b][t + 1:t + cfg.depth + 2])
+            one.draft_tree(want_tree=False)
+            one.verify_tree(want_argmax=False)
+            one.accept_and_commit()
+        alone.append(one.tokens())
+        one.close()
+    ctx.set_sampling(T, [0.0])
+    for b, p in enumerate(prompts):
+        ctx.set_uniforms(b, [U[b][len(p)]])
+        ctx.prefill(p, seq=b)
+    for _ in range(n_rounds):
+        for b in range(batch):
+            t = len(ctx.tokens(b)) - 1
+            ctx.set_uniforms(b, U[b][t + 1:t + cfg.depth + 2])
+        ctx.draft_tree(want_tree=False)
+        ctx.verify_tree(want_argmax=False)
+        ctx.accept_and_commit()
+    for b in range(batch):
+        assert ctx.tokens(b) == alone[b], f"sequence {b}"
+    if cfg.dtype == 0:
+        for b in range(batch):
+            o = pair.oracle()
+            n_new = len(alone[b]) - len(prompts[b])
+            want = o.generate(prompts[b], n_new, temperature=T, U=U[b].astype(np.float64))
+            assert alone[b][:len(want)] == want[:len(alone[b])], f"sequence {b} against the oracle"
+    pair.close()
