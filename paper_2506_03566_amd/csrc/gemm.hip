@@ -165,8 +165,11 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     const int ngroup = blockIdx.x * WPB + wave;
     const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCS) * (GEMM_NT * 64) + lane;
 
-    // Global->LDS staging map: unit u of a chunk covers row m = u / 32, 8 consecutive k starting at
-    // (u % 32) * 8 (coalesced along k); it lands at A-operand position [k_step][m_tile][lane].
+    // Global->LDS staging map: a wave instruction covers one A-operand block [k_step][m_tile] (64 units of 16
+    // bytes): four consecutive lanes take the four 8-element groups of one row's k-step (64 contiguous bytes in
+    // global memory), consecutive quads take consecutive rows.  In LDS the block is stored in operand order,
+    // unit (k8 & 3) * 16 + (m & 15), so the 16 rows of the wave spread over all 64 banks.  (With a wave covering
+    // 2 rows x 32 groups, contiguous along k, its 64 stores fell into 8 of the 64 banks.)
     // Loads are never predicated (a predicated load becomes a branch, and the compiler then waits
     // for every outstanding load at it): out-of-range units read a clamped, valid address and are
     // zeroed by a select.
@@ -176,11 +179,12 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
         const int u = min(tid + i * (WPB * 64), XUNITS - 1);
-        const int m = u >> 5, k8 = u & 31;
+        const int blk = u >> 6, ln = u & 63;
+        const int m = (blk % MT) * 16 + (ln >> 2), k8 = (blk / MT) * 4 + (ln & 3);
         x_row_ok[i] = m < M;
         x_src[i] = X + (size_t)(m < M ? m : M - 1) * ldx;
         x_k[i] = k8 * 8;
-        x_dst[i] = ((k8 >> 2) * MT + (m >> 4)) * 64 + ((k8 & 3) << 4) + (m & 15);
+        x_dst[i] = blk * 64 + ((ln & 3) << 4) + (ln >> 2);
     }
     auto load_x = [&](int chunk, u32x4 (&xr)[XPT]) {
 #pragma unroll
