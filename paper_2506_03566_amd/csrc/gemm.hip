@@ -263,16 +263,28 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     // D tile: lane -> column n = lane % 16, register r -> row m = 4 * (lane / 16) + r
     if constexpr (FUSE_SILU) {
         static_assert(GEMM_NT == 2, "gate and up are the two column tiles of a wave");
-        const int f = ngroup * 16 + (lane & 15);
-        if (f < F) {
+        // The waves of the workgroup own WPB * 16 consecutive columns of act.  The tile is collected in LDS (the
+        // staging memory, free after a barrier) so that a row leaves as one contiguous piece in 16-byte stores
+        // instead of 16-column fragments written two bytes per lane.
+        constexpr int TW = WPB * 16, TWP = TW + 8;       // padded row: the four row groups of a wave hit different banks
+        constexpr int EPV = 16 / (int)sizeof(T);         // elements per 16-byte store
+        static_assert((size_t)MT * 16 * TWP * sizeof(T) <= sizeof(xs), "the tile fits the staging memory");
+        T *tile = reinterpret_cast<T *>(&xs[0][0]);
+        __syncthreads();                                 // every wave has read its last operand fragments
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int m = mt * 16 + 4 * (lane >> 4) + r;
-                    const float g = acc[mt][0][r], up = acc[mt][1][r];
-                    if (m < M) act[(size_t)m * F + f] = from_f<T>(g / (1.0f + expf(-g)) * up);
-                }
+            for (int r = 0; r < 4; ++r) {
+                const float g = acc[mt][0][r], up = acc[mt][1][r];
+                tile[(mt * 16 + 4 * (lane >> 4) + r) * TWP + wave * 16 + (lane & 15)] = from_f<T>(g / (1.0f + expf(-g)) * up);
+            }
+        __syncthreads();
+        const int f0 = blockIdx.x * TW;
+        constexpr int PPR = TW / EPV;                    // 16-byte pieces per row
+        for (int p = tid; p < MT * 16 * PPR; p += WPB * 64) {
+            const int m = p / PPR, f = f0 + (p % PPR) * EPV;
+            if (m < M && f + EPV <= F)                   // F is a multiple of 8: a piece is inside or outside as a whole
+                *reinterpret_cast<u32x4 *>(act + (size_t)m * F + f) = *reinterpret_cast<const u32x4 *>(tile + m * TWP + (p % PPR) * EPV);
         }
         return;
     }
