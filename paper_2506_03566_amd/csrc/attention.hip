@@ -178,13 +178,16 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     };
     static_for([&](auto p) { load_block(p, b0 + decltype(p)::value * KW); });
     store_block(std::integral_constant<int, 0>{}, 0);
+    load_block(std::integral_constant<int, 0>{}, b0 + PFD * KW);
     __syncthreads();
     int buf = 0;
-    // iteration `it` (blocks bi .. bi+KW-1): refill ring slot it%PFD with iteration it+PFD, compute
-    // from LDS buffer `buf`, move iteration it+1 (slot (it+1)%PFD) into the other buffer.
+    // iteration `it` (blocks bi .. bi+KW-1): compute from LDS buffer `buf`, move iteration it+1 (ring
+    // slot (it+1)%PFD) into the other buffer and refill that slot at once with iteration it+1+PFD.
+    // A slot is reloaded right behind the LDS stores that read it: its registers are never free in
+    // between (used as temporaries they made the compiler wait for every load in flight at the head
+    // of the loop), and the wait for a block's loads comes after an iteration's arithmetic, not before.
     auto iteration = [&](auto slot_tag, int bi) {
         constexpr int SLOT = decltype(slot_tag)::value;
-        load_block(slot_tag, bi + PFD * KW);
         const int b = bi + kway;
         if (b < b1) {                                     // wave-uniform
         const int slot0 = b << 5;
@@ -260,6 +263,7 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
         }
         }
         store_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, buf ^ 1);
+        load_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, bi + (1 + PFD) * KW);
         __syncthreads();
         buf ^= 1;
     };
