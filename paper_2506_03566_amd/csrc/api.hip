@@ -227,7 +227,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     void *u = a.take((size_t)R * d * es), *xin = a.take((size_t)R * 2 * d * es);
     void *q = a.take((size_t)R * qd * es), *ao = a.take((size_t)R * qd * es), *act = a.take((size_t)R * F * es);
     const int G = c.n_q_heads / c.n_kv_heads;
-    const int rho_pad = round_up(R * G, 16);
+    const int rho_pad = round_up(R * G, 16) + 16 * 8;          // every sequence of a batch pads its row tiles
     const int max_splits = attention_splits(slots, 64);
     float *ao_part = a.take_n<float>((size_t)max_splits * c.n_kv_heads * rho_pad * c.head_dim);
     float *ml_part = a.take_n<float>((size_t)max_splits * c.n_kv_heads * rho_pad * 2);
@@ -316,10 +316,6 @@ EpiArgs epi_residual(poss_ctx *c, bool residual, const void *bias, float *h_copy
 // key/value-only rows [x0, x0 + nx); its cache, committed prefix and region length.
 struct Seg { int b; const KVCache *kv; int q0, nq, x0, nx, n_prefix, region_len; };
 
-char *row_ptr(void *base, size_t row, size_t row_elems, int dt) {
-    return static_cast<char *>(base) + row * row_elems * dtype_size(dt);
-}
-
 // One decoder layer on rows_all rows (all produce K/V) of which the first rows_q go through
 // attention and the MLP; the full rows of every sequence come first, each sequence attends to its
 // own cache.  On entry c->u holds T(rmsnorm(h) * attn_norm) and c->cs the rotary table of the rows;
@@ -337,20 +333,21 @@ void run_layer(poss_ctx *c, const LayerW &w, const std::vector<Seg> &segs, int r
     } else {
         // one weight stream for every sequence, then each sequence's rows go into its own cache
         const GemmShape g = run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false, e, true);
+        RopeRanges rr;
+        rr.n = 0;
         for (const Seg &sg : segs) {
-            e.kv = *sg.kv;
-            e.rows_q = sg.q0 + sg.nq;
-            if (sg.nq > 0 && !launch_rope_kv_epilogue(md.dt, g, c->part, e, sg.q0, sg.q0 + sg.nq, c->st)) c->launch_refused = true;
-            e.rows_q = 0;
-            if (sg.nx > 0 && !launch_rope_kv_epilogue(md.dt, g, c->part, e, sg.x0, sg.x0 + sg.nx, c->st)) c->launch_refused = true;
+            if (sg.nq > 0) { rr.r0[rr.n] = sg.q0; rr.r1[rr.n] = sg.q0 + sg.nq; rr.rows_q[rr.n] = sg.q0 + sg.nq; rr.kv[rr.n] = *sg.kv; ++rr.n; }
+            if (sg.nx > 0) { rr.r0[rr.n] = sg.x0; rr.r1[rr.n] = sg.x0 + sg.nx; rr.rows_q[rr.n] = 0; rr.kv[rr.n] = *sg.kv; ++rr.n; }
         }
+        if (!launch_rope_kv_epilogue(md.dt, g, c->part, e, rr, c->st)) c->launch_refused = true;
     }
     if (rows_q == 0) return;
-    for (const Seg &sg : segs) {
-        if (sg.nq == 0) continue;
-        const RowMeta srm{rm.pos + sg.q0, rm.slot + sg.q0, rm.mask + (size_t)sg.q0 * MASK_WORDS};
-        launch_attention(md, row_ptr(c->q, sg.q0, qd, md.dt), sg.nq, srm, sg.n_prefix, sg.region_len, *sg.kv,
-                         c->attn_keys_per_split, c->attn_sc, row_ptr(c->attn_out, sg.q0, qd, md.dt), c->st);
+    {
+        AttnSeg as[8];
+        int na = 0;
+        for (const Seg &sg : segs)
+            if (sg.nq > 0) as[na++] = AttnSeg{sg.q0, sg.nq, sg.n_prefix, sg.region_len, sg.kv};
+        launch_attention_batch(md, c->q, rm, as, na, c->attn_keys_per_split, c->attn_sc, c->attn_out, c->st);
     }
     run_gemm(c, w.wo, md.d, qd, c->attn_out, qd, rows_q, c->part, false, epi_residual(c, true, nullptr, nullptr, w.mlp_norm));
     EpiArgs es{};

@@ -53,8 +53,8 @@ __device__ __forceinline__ bool slot_visible(int slot, int n_prefix, int region_
 // With a single split the result is normalised and written in the storage type directly;
 // otherwise (max, sum, O) partials go to the merge kernel.
 template <typename T, int DH, int KW, int RT>
-__global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
-    const T *__restrict__ q, int rows, int hq, int hkv, const uint64_t *__restrict__ mask, int n_prefix,
+__device__ __forceinline__ void attn_mfma_body(
+    const int wg_id, const T *__restrict__ q, int rows, int hq, int hkv, const uint64_t *__restrict__ mask, int n_prefix,
     int region_len, KVCache kv, int blocks_per_split, int n_splits, int n_row_groups, float scale,
     float *__restrict__ o_part, float *__restrict__ ml_part, int rho_pad, T *__restrict__ out_direct) {
     typedef typename Vec8<T>::type V8;
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     // L2 of its own, so the row groups that read the same keys and values (same head and split) are given
     // ids that are equal modulo 8: the block is fetched from memory once and then found in that L2.
     const int n_pairs = hkv * n_splits;
-    const int xcd = blockIdx.x & 7, qid = blockIdx.x >> 3;
+    const int xcd = wg_id & 7, qid = wg_id >> 3;
     const int row_group = qid % n_row_groups, pair = (qid / n_row_groups) * 8 + xcd;
     if (pair >= n_pairs) return;                          // padding of the last round of eight
     const int G = hq / hkv, kvh = pair % hkv, split = pair / hkv;
@@ -345,16 +345,47 @@ __global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
     }
 }
 
+template <typename T, int DH, int KW, int RT>
+__global__ __launch_bounds__(256 * KW) void attn_mfma_kernel(
+    const T *__restrict__ q, int rows, int hq, int hkv, const uint64_t *__restrict__ mask, int n_prefix,
+    int region_len, KVCache kv, int blocks_per_split, int n_splits, int n_row_groups, float scale,
+    float *__restrict__ o_part, float *__restrict__ ml_part, int rho_pad, T *__restrict__ out_direct) {
+    attn_mfma_body<T, DH, KW, RT>(blockIdx.x, q, rows, hq, hkv, mask, n_prefix, region_len, kv, blocks_per_split, n_splits,
+                                  n_row_groups, scale, o_part, ml_part, rho_pad, out_direct);
+}
+
+// Several sequences in one launch: every sequence has its own rows, cache, prefix, split count and slice of the
+// partial buffers; a workgroup finds its sequence from the first workgroup id of each, then does exactly what it does
+// in a launch of its own.
+constexpr int ATTN_MAX_SEQ = 8;
+struct AttnSeq {
+    const void *q; const uint64_t *mask; void *out_direct; float *o_part, *ml_part;
+    KVCache kv;
+    int rows, n_prefix, region_len, blocks_per_split, n_splits, n_row_groups, rho_pad, wg0, row0;
+};
+struct AttnSeqs { int n; AttnSeq s[ATTN_MAX_SEQ]; };
+
+template <typename T, int DH, int KW, int RT>
+__global__ __launch_bounds__(256 * KW) void attn_mfma_batch_kernel(AttnSeqs seqs, int hq, int hkv, float scale) {
+    int i = 0;
+    for (int j = 1; j < seqs.n; ++j)
+        if ((int)blockIdx.x >= seqs.s[j].wg0) i = j;
+    const AttnSeq &a = seqs.s[i];
+    attn_mfma_body<T, DH, KW, RT>(blockIdx.x - a.wg0, static_cast<const T *>(a.q), a.rows, hq, hkv, a.mask, a.n_prefix, a.region_len,
+                                  a.kv, a.blocks_per_split, a.n_splits, a.n_row_groups, scale, a.o_part, a.ml_part, a.rho_pad,
+                                  static_cast<T *>(a.out_direct));
+}
+
 // out[m][qh][:] = sum_s e^{m_s - M} O_s / sum_s e^{m_s - M} l_s, splits in order.  The (max, sum) pairs of
 // all splits are fetched in one go and turned into weights once; the partial outputs are then read
 // four splits at a time so that their latencies overlap.
 constexpr int ATTN_MAX_SPLITS = 256;
 template <typename T>
-__global__ void attn_merge_kernel(const float *__restrict__ o_part, const float *__restrict__ ml_part, int n_splits,
-                                  int hq, int hkv, int dh, int rho_pad, T *__restrict__ out) {
+__device__ __forceinline__ void attn_merge_body(const int m, const float *__restrict__ o_part, const float *__restrict__ ml_part,
+                                                int n_splits, int hq, int hkv, int dh, int rho_pad, T *__restrict__ out) {
     __shared__ float w_lds[ATTN_MAX_SPLITS];
     __shared__ float den_lds;
-    const int m = blockIdx.x, qh = blockIdx.y, G = hq / hkv;
+    const int qh = blockIdx.y, G = hq / hkv;
     const int kvh = qh / G, rho = m * G + qh % G;
     const size_t stride = (size_t)hkv * rho_pad;          // rows between consecutive splits
     const size_t row0 = (size_t)kvh * rho_pad + rho;
@@ -389,6 +420,25 @@ __global__ void attn_merge_kernel(const float *__restrict__ o_part, const float 
         for (; s0 < n_splits; ++s0) num += w_lds[s0] * src[(size_t)s0 * stride * dh];
         out[((size_t)m * hq + qh) * dh + i] = from_f<T>(num / den);
     }
+}
+
+template <typename T>
+__global__ void attn_merge_kernel(const float *__restrict__ o_part, const float *__restrict__ ml_part, int n_splits,
+                                  int hq, int hkv, int dh, int rho_pad, T *__restrict__ out) {
+    attn_merge_body<T>(blockIdx.x, o_part, ml_part, n_splits, hq, hkv, dh, rho_pad, out);
+}
+
+// The merge of several sequences' rows in one launch (blockIdx.x = row of the pass); sequences whose keys fit one
+// split wrote their rows directly and are skipped.
+template <typename T>
+__global__ void attn_merge_batch_kernel(AttnSeqs seqs, int hq, int hkv, int dh, T *__restrict__ out) {
+    int i = 0;
+    for (int j = 1; j < seqs.n; ++j)
+        if ((int)blockIdx.x >= seqs.s[j].row0) i = j;
+    const AttnSeq &a = seqs.s[i];
+    const int m = blockIdx.x - a.row0;
+    if (m >= a.rows || a.n_splits == 1) return;          // (workgroup-uniform)
+    attn_merge_body<T>(m, a.o_part, a.ml_part, a.n_splits, hq, hkv, dh, a.rho_pad, out + (size_t)a.row0 * hq * dh);
 }
 
 // float32 storage: one wave per (row, query head); exact two-pass softmax.
@@ -478,6 +528,100 @@ static void launch_attention_t(const ModelDims &md, const void *q, int rows, con
     if (n_splits > 1)
         hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(rows, md.hq), dim3(md.dh < 64 ? 64 : md.dh), 0, st, sc.o, sc.ml,
                            n_splits, md.hq, md.hkv, md.dh, rho_pad, static_cast<T *>(out));
+}
+
+// Launch shape of one sequence's attention: the split rule, key-ways and row tiles per wave (see above).
+struct AttnShape { int bps, n_splits, kw, rt, n_row_groups, rho_pad, n_wgs; };
+static AttnShape attention_shape(const ModelDims &md, int rows, int n_prefix, int region_len, int keys_per_split) {
+    AttnShape a;
+    const int G = md.hq / md.hkv;
+    const int tiles = (rows * G + 15) / 16;
+    a.rho_pad = tiles * 16;
+    const int n_blocks = (n_prefix + region_len + 31) / 32;
+    a.bps = blocks_per_split(n_prefix, keys_per_split);
+    while ((n_blocks + a.bps - 1) / a.bps > ATTN_MAX_SPLITS) a.bps *= 2;
+    a.n_splits = (n_blocks + a.bps - 1) / a.bps;
+    a.kw = a.bps >= 4 ? 2 : 1;
+    a.rt = tiles > 4 && a.bps >= 8 ? 2 : 1;
+    a.n_row_groups = (tiles + 4 * a.rt - 1) / (4 * a.rt);
+    a.n_wgs = 8 * a.n_row_groups * ((md.hkv * a.n_splits + 7) / 8);
+    return a;
+}
+
+template <typename T>
+static void launch_attention_batch_t(const ModelDims &md, const void *q, const RowMeta &rm, const AttnSeg *segs, int n,
+                                     int keys_per_split, const AttnScratch &sc, void *out, hipStream_t st) {
+    const float scale = 1.4426950408889634f / sqrtf((float)md.dh);
+    const size_t qd = (size_t)md.hq * md.dh;
+    AttnShape shp[ATTN_MAX_SEQ];
+    AttnSeq all[ATTN_MAX_SEQ];
+    size_t o_off = 0, ml_off = 0;
+    bool any_split = false;
+    for (int i = 0; i < n; ++i) {
+        const AttnSeg &g = segs[i];
+        shp[i] = attention_shape(md, g.rows, g.n_prefix, g.region_len, keys_per_split);
+        AttnSeq &a = all[i];
+        a.q = static_cast<const T *>(q) + g.row0 * qd;
+        a.mask = rm.mask + (size_t)g.row0 * MASK_WORDS;
+        a.out_direct = shp[i].n_splits == 1 ? static_cast<T *>(out) + g.row0 * qd : nullptr;
+        a.o_part = sc.o + o_off; a.ml_part = sc.ml + ml_off;
+        o_off += (size_t)shp[i].n_splits * md.hkv * shp[i].rho_pad * md.dh;
+        ml_off += (size_t)shp[i].n_splits * md.hkv * shp[i].rho_pad * 2;
+        a.kv = *g.kv;
+        a.rows = g.rows; a.n_prefix = g.n_prefix; a.region_len = g.region_len;
+        a.blocks_per_split = shp[i].bps; a.n_splits = shp[i].n_splits; a.n_row_groups = shp[i].n_row_groups;
+        a.rho_pad = shp[i].rho_pad; a.wg0 = 0; a.row0 = g.row0;
+        any_split = any_split || shp[i].n_splits > 1;
+    }
+    // one launch per (key-ways, row tiles) instantiation that occurs: as a rule one
+    for (int kw = 1; kw <= 2; ++kw)
+        for (int rt = 1; rt <= 2; ++rt) {
+            AttnSeqs grp;
+            grp.n = 0;
+            int wgs = 0;
+            for (int i = 0; i < n; ++i)
+                if (shp[i].kw == kw && shp[i].rt == rt) {
+                    grp.s[grp.n] = all[i];
+                    grp.s[grp.n].wg0 = wgs;
+                    wgs += shp[i].n_wgs;
+                    ++grp.n;
+                }
+            if (grp.n == 0) continue;
+#define POSS_ATTNB(DH, KW, RT)                                                                                   \
+    hipLaunchKernelGGL((attn_mfma_batch_kernel<T, DH, KW, RT>), dim3(wgs), dim3(256 * KW), 0, st, grp, md.hq, md.hkv, scale)
+#define POSS_ATTNB_DH(DH)                                                                                        \
+    do {                                                                                                         \
+        if (kw == 2) { if (rt == 2) POSS_ATTNB(DH, 2, 2); else POSS_ATTNB(DH, 2, 1); }                           \
+        else         { if (rt == 2) POSS_ATTNB(DH, 1, 2); else POSS_ATTNB(DH, 1, 1); }                           \
+    } while (0)
+            if (md.dh == 128) POSS_ATTNB_DH(128); else POSS_ATTNB_DH(64);
+#undef POSS_ATTNB_DH
+#undef POSS_ATTNB
+        }
+    if (any_split) {
+        AttnSeqs grp;
+        grp.n = n;
+        for (int i = 0; i < n; ++i) grp.s[i] = all[i];
+        const int rows_span = segs[n - 1].row0 + segs[n - 1].rows;       // sequences are in row order
+        hipLaunchKernelGGL((attn_merge_batch_kernel<T>), dim3(rows_span, md.hq), dim3(md.dh < 64 ? 64 : md.dh), 0, st, grp,
+                           md.hq, md.hkv, md.dh, static_cast<T *>(out));
+    }
+}
+
+void launch_attention_batch(const ModelDims &md, const void *q, const RowMeta &rm, const AttnSeg *segs, int n,
+                            int keys_per_split, const AttnScratch &sc, void *out, hipStream_t st) {
+    if (n == 1 || md.dt == DT_F32 || n > ATTN_MAX_SEQ) {       // one sequence: the launch of its own; float32: the exact kernel
+        const size_t row_bytes = (size_t)md.hq * md.dh * dtype_size(md.dt);
+        for (int i = 0; i < n; ++i) {
+            const AttnSeg &g = segs[i];
+            const RowMeta srm{rm.pos + g.row0, rm.slot + g.row0, rm.mask + (size_t)g.row0 * MASK_WORDS};
+            launch_attention(md, static_cast<const char *>(q) + g.row0 * row_bytes, g.rows, srm, g.n_prefix, g.region_len, *g.kv,
+                             keys_per_split, sc, static_cast<char *>(out) + g.row0 * row_bytes, st);
+        }
+        return;
+    }
+    if (md.dt == DT_BF16) launch_attention_batch_t<bf16_t>(md, q, rm, segs, n, keys_per_split, sc, out, st);
+    else launch_attention_batch_t<f16_t>(md, q, rm, segs, n, keys_per_split, sc, out, st);
 }
 
 int attention_splits(int total_keys, int keys_per_split) {

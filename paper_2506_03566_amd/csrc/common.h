@@ -103,11 +103,13 @@ struct EpiArgs {
 bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
                  const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t after_stream = nullptr,
                  bool defer_epilogue = false);
-// The RoPE + KV-write epilogue over rows [row_begin, row_end) of a deferred launch.  Row indices stay
-// those of the launch (epi.cs, epi.slot, epi.q are indexed by them; rows below epi.rows_q get a query):
-// several sequences batched into one GEMM each take their own rows into their own cache.
-bool launch_rope_kv_epilogue(int dt, const GemmShape &g, const float *part, const EpiArgs &epi, int row_begin, int row_end,
-                             hipStream_t st);
+// The RoPE + KV-write epilogue of a deferred launch over row ranges [r0, r1), each into its own cache and
+// with its own query limit (rows below rows_q get a rotated query), in one launch: several sequences batched
+// into one GEMM each take their own rows into their own cache.  Row indices stay those of the GEMM launch
+// (epi.cs, epi.slot, epi.q are indexed by them); epi.kv and epi.rows_q are ignored.  blk0 is filled in here.
+constexpr int ROPE_MAX_RANGES = 16;
+struct RopeRanges { int n; int r0[ROPE_MAX_RANGES], r1[ROPE_MAX_RANGES], rows_q[ROPE_MAX_RANGES], blk0[ROPE_MAX_RANGES]; KVCache kv[ROPE_MAX_RANGES]; };
+bool launch_rope_kv_epilogue(int dt, const GemmShape &g, const float *part, const EpiArgs &epi, RopeRanges ranges, hipStream_t st);
 
 // ---------------------------------------------------------------- launchers: elementwise
 // also writes the rotary table of the rows: cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)), angle formed in float64
@@ -130,6 +132,12 @@ struct AttnScratch { float *o; float *ml; };  // partial outputs [split][Hq][row
 void launch_attention(const ModelDims &md, const void *q, int rows, const RowMeta &rm, int n_prefix,
                       int region_len, const KVCache &kv, int keys_per_split, const AttnScratch &sc,
                       void *out, hipStream_t st);
+// The same for several sequences whose rows [row0, row0 + rows) share the q / mask / out buffers (segs in row
+// order): one launch for all of them (and one merge), each sequence against its own cache with its own split count.
+// The partial buffers must hold every sequence's slices: row tiles padded per sequence.
+struct AttnSeg { int row0, rows, n_prefix, region_len; const KVCache *kv; };
+void launch_attention_batch(const ModelDims &md, const void *q, const RowMeta &rm, const AttnSeg *segs, int n,
+                            int keys_per_split, const AttnScratch &sc, void *out, hipStream_t st);
 
 // ---------------------------------------------------------------- draft-tree kernels
 struct TreeDev {            // device-resident tree state of one round

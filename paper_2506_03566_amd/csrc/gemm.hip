@@ -381,6 +381,20 @@ __global__ __launch_bounds__(256) void epilogue_kernel(const float *__restrict__
     tile_epilogue<T, EPI>(part, plane, S, Npad, N, r0, min(M, r0 + ROWS), blockIdx.x, epi);
 }
 
+// The RoPE + KV-write epilogue over several row ranges in one launch, each range into its own cache
+// (sequences batched into one GEMM); blockIdx.y runs over the 4-row blocks of all ranges.
+template <typename T>
+__global__ __launch_bounds__(256) void epilogue_rope_ranges_kernel(const float *__restrict__ part, size_t plane, int S, int Npad,
+                                                                   int N, RopeRanges rr, EpiArgs epi) {
+    int j = 0;
+    for (int i = 1; i < rr.n; ++i)
+        if ((int)blockIdx.y >= rr.blk0[i]) j = i;
+    const int r0 = rr.r0[j] + ((int)blockIdx.y - rr.blk0[j]) * EPI_ROWS_PAIR;
+    epi.kv = rr.kv[j];
+    epi.rows_q = rr.rows_q[j];
+    tile_epilogue<T, EPI_ROPE_KV>(part, plane, S, Npad, N, r0, min(rr.r1[j], r0 + EPI_ROWS_PAIR), blockIdx.x, epi);
+}
+
 // ------------------------------------------------------------------------------------------
 // Row count of a partial plane as the kernel instantiation writes it.
 static int gemm_rows_written(int mpad) {
@@ -509,18 +523,24 @@ bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int 
     return true;
 }
 
-bool launch_rope_kv_epilogue(int dt, const GemmShape &g, const float *part, const EpiArgs &epi, int row_begin, int row_end,
-                             hipStream_t st) {
-    if (!part || epi.mode != EPI_ROPE_KV || row_begin < 0 || row_end > g.M || row_begin >= row_end) return false;
-    if (!epi.q || !epi.cs || !epi.slot || !epi.kv.k || !epi.kv.vt || !epi.kv.page_table) return false;
+bool launch_rope_kv_epilogue(int dt, const GemmShape &g, const float *part, const EpiArgs &epi, RopeRanges rr, hipStream_t st) {
+    if (!part || epi.mode != EPI_ROPE_KV || rr.n < 1 || rr.n > ROPE_MAX_RANGES) return false;
+    if (!epi.q || !epi.cs || !epi.slot) return false;
+    int blocks = 0;
+    for (int i = 0; i < rr.n; ++i) {
+        if (rr.r0[i] < 0 || rr.r1[i] > g.M || rr.r0[i] >= rr.r1[i]) return false;
+        if (!rr.kv[i].k || !rr.kv[i].vt || !rr.kv[i].page_table) return false;
+        rr.blk0[i] = blocks;
+        blocks += (rr.r1[i] - rr.r0[i] + EPI_ROWS_PAIR - 1) / EPI_ROWS_PAIR;
+    }
     const size_t plane = (size_t)g.Mpad * g.Npad;
-    dim3 grid(g.Npad / GEMM_BLOCK_N, (row_end - row_begin + EPI_ROWS_PAIR - 1) / EPI_ROWS_PAIR), eb(256);
+    dim3 grid(g.Npad / GEMM_BLOCK_N, blocks), eb(256);
     if (dt == DT_F32)
-        hipLaunchKernelGGL((epilogue_kernel<float, EPI_ROPE_KV>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, row_begin, row_end, epi);
+        hipLaunchKernelGGL((epilogue_rope_ranges_kernel<float>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, rr, epi);
     else if (dt == DT_BF16)
-        hipLaunchKernelGGL((epilogue_kernel<bf16_t, EPI_ROPE_KV>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, row_begin, row_end, epi);
+        hipLaunchKernelGGL((epilogue_rope_ranges_kernel<bf16_t>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, rr, epi);
     else
-        hipLaunchKernelGGL((epilogue_kernel<f16_t, EPI_ROPE_KV>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, row_begin, row_end, epi);
+        hipLaunchKernelGGL((epilogue_rope_ranges_kernel<f16_t>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, rr, epi);
     return true;
 }
 
