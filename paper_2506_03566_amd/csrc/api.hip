@@ -1,6 +1,7 @@
 // Host side of the C ABI (include/poss.h): context, workspace carving, weight repacking, the pass
 // schedules of prefill / draft / verify / accept-and-commit.  No arithmetic of the method happens
-// here: every step is a kernel launch on the caller's stream.
+// here: every step is a kernel launch on the caller's stream.  A context carries one or several
+// sequences; a pass stacks the rows of all of them so that they share the weight streams.
 #include "../../include/poss.h"
 #include "common.h"
 
