@@ -150,8 +150,9 @@ int poss_get_tree_seq(poss_ctx *ctx, int32_t seq, poss_tree *out);
  * [n_nodes, d_model], may be NULL) receive Head(f) and f of every row (Eq. 6).  With all three
  * outputs NULL the call returns once the work is queued (no host wait), so that a round
  * draft -> verify -> accept waits for the device once, in poss_accept_and_commit; the tree
- * arrays are copied before the call returns.  With batch > 1: tree must be NULL (the drafted trees
- * of all sequences are verified in one pass); the outputs then cover sequence 0's rows. */
+ * arrays are copied before the call returns.  With batch > 1 all sequences are verified in one pass:
+ * tree is NULL (the drafted trees) or points to an array of `batch` trees, one per sequence; the
+ * outputs then cover sequence 0's rows. */
 int poss_verify_tree(poss_ctx *ctx, const poss_tree *tree, int32_t *argmax_out,
                      void *logits_out, void *feat_out);
 

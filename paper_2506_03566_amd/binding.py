@@ -223,9 +223,20 @@ class Poss:
         return tr
 
     def verify_tree(self, tree=None, logits_out=None, feat_out=None, want_argmax=True):
+        """tree: None (the drafted trees), one TreeArrays (batch 1) or a list with one TreeArrays per sequence."""
         g = np.zeros(MAX_ROWS, np.int32) if want_argmax else None
+        batch = max(1, int(self.c_cfg.batch))
+        if tree is None:
+            tp = None
+        else:
+            trees = list(tree) if isinstance(tree, (list, tuple)) else [tree]
+            if len(trees) != batch:
+                raise ValueError("verify_tree needs one tree per sequence (%d), got %d" % (batch, len(trees)))
+            arr = (PossTree * batch)(*[t.c for t in trees])
+            self._keep_trees = (arr, trees)
+            tp = ctypes.cast(arr, ctypes.POINTER(PossTree))
         self._check(self.lib.poss_verify_tree(
-            self.h, ctypes.byref(tree.c) if tree is not None else None, _iptr(g) if g is not None else None,
+            self.h, tp, _iptr(g) if g is not None else None,
             c_vp(logits_out.data_ptr()) if logits_out is not None else None,
             c_vp(feat_out.data_ptr()) if feat_out is not None else None))
         return g

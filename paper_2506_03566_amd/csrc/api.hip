@@ -49,7 +49,7 @@ struct Seq {
     int32_t *tree_slot, *tokens_dev, *walk_dev;
     void *feat_stash, *xin_tmp;
     int32_t *result_pinned, *result_dev;   // the commit kernel's result: host memory and its device address
-    int t, tree_ready, tree_n, prefilled;
+    int t, tree_ready, tree_n, tree_row0, prefilled;   // tree_row0: first row of its tree in the batch-wide arrays
     std::vector<int32_t> tokens;
     std::vector<int> spec_len, spec_tmp_depth;
     int last_m;                        // the last commit: accepted drafts, path, committed tokens
@@ -78,8 +78,9 @@ struct poss_ctx {
     AttnScratch attn_sc;
     int32_t *row_pos, *row_slot;
     uint64_t *row_mask;
-    int32_t *tree_token_all, *tree_pos_all, *tree_slot_all, *tree_depth_all;   // rows of the verification pass, all sequences
+    int32_t *tree_token_all, *tree_pos_all, *tree_slot_all, *tree_depth_all, *tree_parent_all;   // rows of the verification pass, all sequences
     uint64_t *tree_mask_all;
+    float *tree_score_all;
     int32_t *topk_id_all; float *topk_logp_all;
     int32_t *argmax_dev;
     double *inv_freq;
@@ -282,7 +283,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         ctx->attn_sc = AttnScratch{ao_part, ml_part};
         ctx->row_pos = row_pos; ctx->row_slot = row_slot; ctx->row_mask = row_mask;
         ctx->tree_token_all = token_all; ctx->tree_pos_all = pos_all; ctx->tree_slot_all = slot_all;
-        ctx->tree_depth_all = depth_all; ctx->tree_mask_all = mask_all;
+        ctx->tree_depth_all = depth_all; ctx->tree_mask_all = mask_all; ctx->tree_parent_all = parent_all; ctx->tree_score_all = score_all;
         ctx->topk_id_all = topk_id_all; ctx->topk_logp_all = topk_logp_all;
         ctx->argmax_dev = argmax_dev;
         ctx->inv_freq = inv_freq; ctx->u_dev = u_dev;
@@ -488,10 +489,21 @@ LayerW layer_view(const std::vector<void *> &v, size_t base) {
     return LayerW{v[base], v[base + 1], v[base + 2], v[base + 3], v[base + 4], v[base + 5]};
 }
 
+// The final-tree arrays of a sequence are a slice of the batch-wide row arrays: drafted trees sit at a fixed
+// stride (total_tokens + 1), caller-supplied ones back to back.
+void point_tree(poss_ctx *c, Seq &sq, int row0) {
+    sq.tree_row0 = row0;
+    sq.td.token = c->tree_token_all + row0; sq.td.parent = c->tree_parent_all + row0;
+    sq.td.depth = c->tree_depth_all + row0; sq.td.pos = c->tree_pos_all + row0;
+    sq.td.mask = c->tree_mask_all + (size_t)row0 * MASK_WORDS; sq.td.score = c->tree_score_all + row0;
+    sq.tree_slot = c->tree_slot_all + row0;
+}
+
 void reset_sequence(poss_ctx *c) {
     c->state = ST_LOADED;
     for (Seq &sq : c->seq) {
         sq.t = 0; sq.tree_ready = 0; sq.tree_n = 0; sq.prefilled = 0; sq.last_m = 0;
+        point_tree(c, sq, (int)(&sq - &c->seq[0]) * (c->cfg.total_tokens + 1));
         sq.tokens.clear();
         sq.spec_len.assign(c->cfg.n_specialists, 0);
         sq.spec_tmp_depth.assign(c->cfg.n_specialists, 0);
@@ -631,7 +643,8 @@ void poss_free(poss_ctx *c) {
 
 const char *poss_last_error(poss_ctx *c) { return c ? c->err : g_load_error; }
 
-static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, int seq_first, int rows_each);
+static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, int seq_first, int n_seq, const int *row0,
+                         const int *n_rows);
 
 int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
     if (!c) return POSS_E_INVALID_ARG;
@@ -658,7 +671,7 @@ int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_
             EpiArgs pe{};
             pe.mode = EPI_PLAIN;
             GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true, pe);
-            { int rc = choose_tokens(c, g.Npad, 1, nullptr, seq, 1); if (rc) return rc; }
+            { const int zero = 0, one = 1; int rc = choose_tokens(c, g.Npad, 1, nullptr, seq, 1, &zero, &one); if (rc) return rc; }
             HIP_TRY(c, hipMemcpyAsync(sq.tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
         }
         HIP_TRY(c, hipStreamSynchronize(c->st));          // the staging buffer is reused by the next chunk
@@ -685,14 +698,16 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
 
 // The token the target chooses after each of `rows` rows of c->logits: the argmax, or at temperature > 0 a
 // draw by inverse CDF with the uniform number of the row's depth (depth == nullptr: all rows use u[0]).
-// The rows are rows_each per sequence, starting with sequence seq_first: each sequence has its own numbers.
-static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, int seq_first, int rows_each) {
+// Sequence seq_first + i owns rows [row0[i], row0[i] + n_rows[i]) and has its own numbers.
+static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, int seq_first, int n_seq, const int *row0,
+                         const int *n_rows) {
     if (c->temperature > 0.f) {
         const int nu = POSS_MAX_DEPTH + 1;
         HIP_TRY(c, hipMemcpyAsync(c->u_dev, c->u_pinned, (size_t)c->B * nu * sizeof(float), hipMemcpyHostToDevice, c->st));
-        for (int r0 = 0, b = seq_first; r0 < rows; r0 += rows_each, ++b)
-            if (!launch_sample(c->logits + (size_t)r0 * ld, ld, rows_each, c->cfg.vocab, c->temperature, c->u_dev + (size_t)b * nu,
-                               depth ? depth + r0 : nullptr, c->topk_scratch, c->argmax_dev + r0, c->st))
+        for (int i = 0; i < n_seq; ++i)
+            if (!launch_sample(c->logits + (size_t)row0[i] * ld, ld, n_rows[i], c->cfg.vocab, c->temperature,
+                               c->u_dev + (size_t)(seq_first + i) * nu, depth ? depth + row0[i] : nullptr, c->topk_scratch,
+                               c->argmax_dev + row0[i], c->st))
                 return fail(c, POSS_E_INVALID_ARG, "sampling: vocabulary too large for the sampler");
     } else {
         launch_argmax(c->logits, ld, rows, c->cfg.vocab, c->topk_scratch, c->argmax_dev, c->st);
@@ -730,6 +745,7 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
     (void)hipEventRecord(c->ev[0], c->st);
     for (int b = 0; b < B; ++b) {
         Seq &sq = c->seq[b];
+        point_tree(c, sq, b * (cf.total_tokens + 1));
         for (int s = 0; s < cf.n_specialists; ++s) {
             sq.spec_tmp_depth[s] = 0;
             if (sq.t - 1 - sq.spec_len[s] > L) spec_catchup(c, b, s, sq.t - 1);      // only after caller-supplied trees
@@ -838,60 +854,66 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: needs a prefilled context with no pending verification");
     const poss_config &cf = c->cfg;
     const int B = c->B;
-    if (tree && B > 1) return fail(c, POSS_E_INVALID_ARG, "poss_verify_tree: a caller's tree needs batch 1; batched rounds verify the drafted trees");
-    Seq &s0 = c->seq[0];
-    int n;
-    if (tree) {
-        n = tree->n_nodes;
-        if (n < 1 || n > cf.total_tokens + 1) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: %d nodes, capacity %d", n, cf.total_tokens + 1);
-        if (!tree->token || !tree->parent) return fail(c, POSS_E_INVALID_ARG, "poss_verify_tree: null tree arrays");
-        std::vector<int> depth(n, 0);
-        if (tree->parent[0] != -1) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: parent[0] must be -1");
-        for (int i = 1; i < n; ++i) {
-            const int p = tree->parent[i];
-            if (p < 0 || p >= i) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: parent[%d] = %d does not precede the node", i, p);
-            if (tree->token[i] < 0 || tree->token[i] >= cf.vocab) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: token[%d] out of range", i);
-            depth[i] = depth[p] + 1;
-            if (depth[i] > cf.depth) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: node %d deeper than depth %d", i, cf.depth);
-            for (int j = 1; j < i; ++j)
-                if (tree->parent[j] == p && tree->token[j] == tree->token[i])
-                    return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: siblings %d and %d carry the same token", j, i);
+    int row0[8], n_rows[8], rows = 0;
+    if (tree) {                                            // one tree per sequence: tree[0 .. B-1]
+        for (int b = 0; b < B; ++b) {
+            const poss_tree &tr = tree[b];
+            const int n = tr.n_nodes;
+            if (n < 1 || n > cf.total_tokens + 1) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: %d nodes, capacity %d", n, cf.total_tokens + 1);
+            if (!tr.token || !tr.parent) return fail(c, POSS_E_INVALID_ARG, "poss_verify_tree: null tree arrays");
+            std::vector<int> depth(n, 0);
+            if (tr.parent[0] != -1) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: parent[0] must be -1");
+            for (int i = 1; i < n; ++i) {
+                const int p = tr.parent[i];
+                if (p < 0 || p >= i) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: parent[%d] = %d does not precede the node", i, p);
+                if (tr.token[i] < 0 || tr.token[i] >= cf.vocab) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: token[%d] out of range", i);
+                depth[i] = depth[p] + 1;
+                if (depth[i] > cf.depth) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: node %d deeper than depth %d", i, cf.depth);
+                for (int j = 1; j < i; ++j)
+                    if (tr.parent[j] == p && tr.token[j] == tr.token[i])
+                        return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: siblings %d and %d carry the same token", j, i);
+            }
+            row0[b] = rows; n_rows[b] = n; rows += n;       // back to back
         }
     } else {
-        for (int b = 0; b < B; ++b)
+        for (int b = 0; b < B; ++b) {
             if (!c->seq[b].tree_ready) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: no drafted tree");
-        n = s0.tree_n;                                      // drafted trees all have total_tokens + 1 nodes
+            row0[b] = c->seq[b].tree_row0; n_rows[b] = c->seq[b].tree_n; rows = row0[b] + n_rows[b];   // fixed stride, no gaps
+        }
     }
     for (int b = 0; b < B; ++b) {
         const int t = c->seq[b].t;
-        if (t + n > c->cache_slots || t + cf.depth + 1 > cf.max_seq)
+        if (t + n_rows[b] > c->cache_slots || t + cf.depth + 1 > cf.max_seq)
             return fail(c, POSS_E_CAPACITY, "poss_verify_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
     }
     (void)hipEventRecord(c->ev[2], c->st);
     if (tree) {
-        const int t = s0.t;
-        int32_t *stage = static_cast<int32_t *>(c->pinned);
-        memcpy(stage, tree->token, n * sizeof(int32_t));
-        stage[0] = s0.tokens[t];                                  // the root is always x_t
-        memcpy(stage + MAX_ROWS, tree->parent, n * sizeof(int32_t));
-        stage[2 * MAX_ROWS] = n;
-        HIP_TRY(c, hipMemcpyAsync(s0.td.token, stage, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-        HIP_TRY(c, hipMemcpyAsync(s0.td.parent, stage + MAX_ROWS, n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-        HIP_TRY(c, hipMemcpyAsync(s0.td.n_nodes, stage + 2 * MAX_ROWS, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-        launch_tree_upload_finish(n, t, s0.td.token, s0.td.parent, s0.td.depth, s0.td.pos, s0.tree_slot, s0.td.mask, c->st);
-        s0.tree_n = n; s0.tree_ready = 1;
+        int32_t *stage = static_cast<int32_t *>(c->pinned);      // [tokens | parents | node counts]
+        for (int b = 0; b < B; ++b) {
+            Seq &sq = c->seq[b];
+            const int n = n_rows[b], t = sq.t;
+            point_tree(c, sq, row0[b]);
+            memcpy(stage + row0[b], tree[b].token, n * sizeof(int32_t));
+            stage[row0[b]] = sq.tokens[t];                        // the root is always x_t
+            memcpy(stage + MAX_ROWS + row0[b], tree[b].parent, n * sizeof(int32_t));
+            stage[2 * MAX_ROWS + b] = n;
+            HIP_TRY(c, hipMemcpyAsync(sq.td.token, stage + row0[b], n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+            HIP_TRY(c, hipMemcpyAsync(sq.td.parent, stage + MAX_ROWS + row0[b], n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+            HIP_TRY(c, hipMemcpyAsync(sq.td.n_nodes, stage + 2 * MAX_ROWS + b, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+            launch_tree_upload_finish(n, t, sq.td.token, sq.td.parent, sq.td.depth, sq.td.pos, sq.tree_slot, sq.td.mask, c->st);
+            sq.tree_n = n; sq.tree_ready = 1;
+        }
     }                                     // (a drafted tree's slots were written when it was finalized)
     // the trees' rows are adjacent slices of the batch-wide arrays: one pass over all of them
-    const int rows = B * n;
     RowMeta rm{c->tree_pos_all, c->tree_slot_all, c->tree_mask_all};
     std::vector<Seg> segs;
-    for (int b = 0; b < B; ++b) segs.push_back(Seg{b, nullptr, b * n, n, rows, 0, c->seq[b].t, n});
-    if (B == 1) segs[0].x0 = n;
+    for (int b = 0; b < B; ++b) segs.push_back(Seg{b, nullptr, row0[b], n_rows[b], rows, 0, c->seq[b].t, n_rows[b]});
     target_forward(c, rows, c->tree_token_all, rm, segs);
     GemmShape g = run_head(c, rows);
-    { int rc = choose_tokens(c, g.Npad, rows, c->tree_depth_all, 0, n); if (rc) return rc; }
+    { int rc = choose_tokens(c, g.Npad, rows, c->tree_depth_all, 0, B, row0, n_rows); if (rc) return rc; }
     (void)hipEventRecord(c->ev[3], c->st);
     c->ev_pending[1] = true;
+    const int n = n_rows[0];                               // host and device outputs: sequence 0's rows
     if (logits_out) launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
     if (feat_out) launch_copy_rows_f32(c->feats, cf.d_model, static_cast<float *>(feat_out), cf.d_model, n, cf.d_model, c->st);
     HIP_TRY(c, hipGetLastError());
@@ -912,7 +934,7 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
     (void)hipEventRecord(c->ev[4], c->st);
     for (int b = 0; b < B; ++b) {
         Seq &sq = c->seq[b];
-        const int row0 = b * sq.tree_n;
+        const int row0 = sq.tree_row0;
         launch_commit(c->md, cf.n_layers, sq.target_kv_dev, sq.td.token, sq.td.parent, c->argmax_dev + row0, sq.td.n_nodes, L, sq.t,
                       c->feats + (size_t)row0 * cf.d_model, sq.feat_stash, sq.tokens_dev, sq.walk_dev, sq.result_dev, c->st);
     }

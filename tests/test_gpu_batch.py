@@ -108,8 +108,11 @@ def test_batched_context_refuses_what_it_cannot_do():
         ctx.set_uniforms(1, [1.0])                                     # not in [0, 1)
     ctx.draft_tree(want_tree=False)
     tree = ctx.get_tree(1)
+    with pytest.raises(ValueError):
+        ctx.verify_tree(tree)                                          # one tree per sequence
+    bad = P.TreeArrays.from_lists([0, 1, 1], [-1, 0, 0])               # two siblings with the same token
     with pytest.raises(P.PossError):
-        ctx.verify_tree(tree)                                          # a caller's tree needs batch 1
+        ctx.verify_tree([tree, bad])
     ctx.verify_tree(want_argmax=False)
     ctx.accept_and_commit()
     with pytest.raises(P.PossError):
@@ -209,4 +212,49 @@ def test_batched_sampling_equals_sequences_alone(name, batch, lengths):
             n_new = len(alone[b]) - len(prompts[b])
             want = o.generate(prompts[b], n_new, temperature=T, U=U[b].astype(np.float64))
             assert alone[b][:len(want)] == want[:len(alone[b])], f"sequence {b} against the oracle"
+    pair.close()
+
+
+@pytest.mark.parametrize("name,batch,lengths", [("c0_tiny_f32", 3, (16, 23, 40)), ("t_mid_bf16", 2, (150, 97))])
+def test_batched_caller_trees_equal_sequences_alone(name, batch, lengths):
+    """Trees handed in by the caller, one per sequence and of different sizes (root-only rounds are
+    vanilla decoding): the batch commits what each sequence commits alone, and a draft after such
+    rounds catches the specialists up for every sequence."""
+    cfg = get_config(name)
+    pair = Pair(name, lib_over={"batch": batch})
+    ctx = pair.ctx
+    prompts = _prompts(cfg, lengths)
+    rng = np.random.default_rng(5)
+
+    def some_tree(b, rnd):
+        if rnd % 2 == 0:
+            return P.TreeArrays.from_lists([0], [-1])                   # root only
+        n = 2 + (b + rnd) % 3                                           # a short chain under the root
+        toks = [0] + [int(x) for x in rng.integers(0, cfg.vocab, n - 1)]
+        return P.TreeArrays.from_lists(toks, [-1] + list(range(n - 1)))
+
+    n_rounds = 4
+    trees = [[some_tree(b, r) for b in range(batch)] for r in range(n_rounds)]
+    alone = []
+    for b, p in enumerate(prompts):
+        one = P.Poss(cfg, pair.dev_weights)
+        one.prefill(p)
+        res = []
+        for r in range(n_rounds):
+            one.verify_tree(trees[r][b], want_argmax=False)
+            res.append(one.accept_and_commit())
+        tr = one.draft_tree().as_dict()
+        alone.append((res, one.tokens(), tr))
+        one.close()
+    for b, p in enumerate(prompts):
+        ctx.prefill(p, seq=b)
+    for r in range(n_rounds):
+        ctx.verify_tree(trees[r], want_argmax=False)
+        ctx.accept_and_commit()
+        for b in range(batch):
+            assert ctx.commit_result(b) == alone[b][0][r], f"round {r}, sequence {b}"
+    ctx.draft_tree(want_tree=False)
+    for b in range(batch):
+        assert ctx.tokens(b) == alone[b][1]
+        assert _same_tree(ctx.get_tree(b).as_dict(), alone[b][2]), f"sequence {b}: tree after caller-tree rounds"
     pair.close()
