@@ -309,3 +309,53 @@ def test_degenerate_and_maximal_tree_shapes(over, n_prompt):
         assert ctx.tokens() == o.tokens
     _say(f"  {over}: {identical}/3 rounds with an identical tree")
     pair.close()
+
+
+def _imperfect_drafter_storage(cfg, noise):
+    """The perfect drafter with the feature half of every fc matrix filled with noise: drafts are
+    right often but not always, so rounds accept anything between nothing and the full depth."""
+    st = _perfect_drafter_storage(cfg)
+    rng = np.random.default_rng(77)
+    d = cfg.d_model
+    for s in range(cfg.n_specialists):
+        fc = to_float64(st[f"spec{s}.fc_w"], cfg.dtype)
+        fc[:, d:] = noise * rng.normal(size=(d, d)) / np.sqrt(d)
+        st[f"spec{s}.fc_w"] = to_storage(fc, cfg.dtype)
+    return st
+
+
+@pytest.mark.parametrize("name", ["c0_tiny_f32", "t_tiny_f32_6x1"])
+def test_long_run_with_mixed_acceptance_is_lossless(name):
+    """Float32 storage, a drafter that is right only some of the time, many rounds: accepted lengths
+    of every size occur, the caches are compacted and caught up in every combination, pages are
+    crossed - and the committed stream stays exactly the stream of one-token-at-a-time decoding
+    through the same library (section 2.1: verification does not change the target's output)."""
+    cfg = get_config(name)
+    pair = Pair(name, storage=_imperfect_drafter_storage(cfg, 0.1))
+    ctx = pair.ctx
+    prompt = make_prompt(cfg, n=21)
+    ctx.prefill(prompt)
+    ms = []
+    while len(ctx.tokens()) < len(prompt) + 260:
+        ctx.draft_tree(want_tree=False)
+        ctx.verify_tree(want_argmax=False)
+        _, m, _ = ctx.accept_and_commit()
+        ms.append(m)
+    spec = ctx.tokens()
+    _say(f"  {name}: {len(ms)} rounds, accepted lengths {sorted(set(ms))}, mean {np.mean(ms):.2f}")
+    assert len(set(ms)) >= 4 and 0 in ms and max(ms) >= cfg.depth - 1      # the drafter is neither useless nor perfect
+    st = ctx.stats()
+    assert st.rounds == len(ms) and st.committed_tokens == sum(ms) + len(ms)
+    c = list(st.c)
+    assert c[1:cfg.depth + 1] == [sum(1 for m in ms if m >= i) for i in range(1, cfg.depth + 1)]   # Eq. 3 counters
+    ctx.reset()
+    ctx.prefill(prompt)
+    root = P.TreeArrays.from_lists([0], [-1])
+    while len(ctx.tokens()) < len(spec):
+        ctx.verify_tree(root, want_argmax=False)
+        ctx.accept_and_commit()
+    assert ctx.tokens() == spec
+    # and the oracle, free-running, agrees on the first stretch (float32 against float64: until a near-tie)
+    want = pair.oracle().generate(prompt, 40)
+    assert spec[:len(want)] == want
+    pair.close()
