@@ -22,8 +22,51 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ e
                                                          float2 *__restrict__ cs) {
     __shared__ float red[17];
     const int row = blockIdx.x;
-    rope_table_row(pos[row], inv_freq, half, cs + (size_t)row * half);
+    // the rotary table by the last wave, so that the first ones start on the embedding row at once
+    rope_table_row(pos[row], inv_freq, half, cs + (size_t)row * half, half <= 64 && blockDim.x >= 128 ? (int)blockDim.x - 64 : 0);
     const T *e = embed + (size_t)tokens[row] * d;
+    constexpr int VE = 16 / (int)sizeof(T);               // elements per 16-byte access
+    constexpr int MAXV = 4;                                // 16-byte pieces a thread keeps (d <= 4 * 256 * VE)
+    if (d % VE == 0 && d <= MAXV * 256 * VE && blockDim.x == 256) {
+        // one trip to memory: the row and the gains are loaded in 16-byte pieces and kept in registers
+        union Piece { uint4 q; T t[VE]; };
+        Piece ev[MAXV], gv[MAXV];
+        const int nv = d / VE;
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j) {
+            const int p = threadIdx.x + j * 256;
+            if (p < nv) {
+                ev[j].q = reinterpret_cast<const uint4 *>(e)[p];
+                gv[j].q = reinterpret_cast<const uint4 *>(gain)[p];
+            }
+        }
+        float ss = 0.f;                                    // fixed order: a thread's pieces one after the other, element by element
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j) {
+            const int p = threadIdx.x + j * 256;
+            if (p < nv) {
+#pragma unroll
+                for (int x = 0; x < VE; ++x) {
+                    const float v = to_f(ev[j].t[x]);
+                    h[(size_t)row * d + (size_t)p * VE + x] = v;
+                    ss += v * v;
+                }
+            }
+        }
+        ss = block_sum(ss, red);
+        const float rs = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j) {
+            const int p = threadIdx.x + j * 256;
+            if (p < nv) {
+                Piece o;
+#pragma unroll
+                for (int x = 0; x < VE; ++x) o.t[x] = from_f<T>(to_f(ev[j].t[x]) * rs * to_f(gv[j].t[x]));
+                reinterpret_cast<uint4 *>(u + (size_t)row * d)[p] = o.q;
+            }
+        }
+        return;
+    }
     float ss = 0.f;
     for (int i = threadIdx.x; i < d; i += blockDim.x) {
         const float v = to_f(e[i]);

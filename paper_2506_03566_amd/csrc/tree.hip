@@ -255,12 +255,23 @@ constexpr int POOL_MAX = 2048;
 __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int pool_n, int n_keep, int t,
                                                              const int32_t *__restrict__ tokens_dev,
                                                              int32_t *__restrict__ slot_out) {
-    __shared__ float sc[POOL_MAX];
+    __shared__ __attribute__((aligned(16))) float sc[POOL_MAX];
     __shared__ int16_t par[POOL_MAX];                 // candidate -> parent candidate (-1: the root)
     __shared__ int16_t new_idx[POOL_MAX];             // candidate -> node index in the tree, -1 if dropped
     __shared__ int wave_cnt[2 * 16];                  // kept candidates per (pass, wave)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < pool_n; i += 1024) { sc[i] = td.pool_score[i]; par[i] = (int16_t)td.pool_parent[i]; }
+    int my_token[2], my_depth[2];                     // of candidates tid and tid + 1024: asked for with the scores
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int i = tid + p * 1024;
+        my_token[p] = 0; my_depth[p] = 0;
+        if (i < pool_n) {
+            sc[i] = td.pool_score[i]; par[i] = (int16_t)td.pool_parent[i];
+            my_token[p] = td.pool_token[i]; my_depth[p] = td.pool_depth[i];
+        } else if (i < ((pool_n + 3) & ~3)) {
+            sc[i] = -INFINITY;                        // the ranking reads the scores four at a time
+        }
+    }
     __syncthreads();
     // rank by counting; node index = 1 + number of kept candidates before this one (candidate order is
     // kept, so parents come first), from wave ballots instead of a serial scan
@@ -273,7 +284,13 @@ __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int poo
         if (i < pool_n) {
             const float s = sc[i];
             int rank = 0;
-            for (int j = 0; j < pool_n; ++j) rank += (sc[j] > s) || (sc[j] == s && j < i);
+            for (int j = 0; j < pool_n; j += 4) {
+                const float4 o = *reinterpret_cast<const float4 *>(&sc[j]);
+                rank += (o.x > s) || (o.x == s && j < i);
+                rank += (o.y > s) || (o.y == s && j + 1 < i);
+                rank += (o.z > s) || (o.z == s && j + 2 < i);
+                rank += (o.w > s) || (o.w == s && j + 3 < i);
+            }
             keep[p] = rank < n_keep;
         }
         const unsigned long long b = __ballot(keep[p]);
@@ -297,11 +314,14 @@ __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int poo
         slot_out[0] = t;
     }
     __syncthreads();
-    for (int i = tid; i < pool_n; i += 1024) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int i = tid + p * 1024;
+        if (i >= pool_n) continue;
         const int ni = new_idx[i];
         if (ni < 0) continue;
-        const int pp = par[i], dep = td.pool_depth[i];
-        td.token[ni] = td.pool_token[i];
+        const int pp = par[i], dep = my_depth[p];
+        td.token[ni] = my_token[p];
         td.parent[ni] = pp < 0 ? 0 : new_idx[pp];
         td.depth[ni] = dep;
         td.pos[ni] = t + dep;
