@@ -196,8 +196,8 @@ void poss_free(poss_ctx *ctx);
 /* ---- instrumentation -------------------------------------------------------------------- */
 
 /* Per-kernel timing of the weight-streaming GEMM (the kernel that carries the round's bytes).
- * enable != 0: every launch is bracketed by HIP events on the library's stream (slows the round
- * slightly: use a pass of its own).  poss_gemm_profile sums the launches since the last call:
+ * enable != 0: every launch carries a pair of HIP events that take the kernel's begin and end
+ * timestamps (slows the round slightly: use a pass of its own).  poss_gemm_profile sums the launches since the last call:
  * count, milliseconds, and algorithmic bytes (each launch's weight matrix once, in storage
  * dtype). */
 int poss_profile_gemm(poss_ctx *ctx, int32_t enable);

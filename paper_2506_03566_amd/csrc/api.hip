@@ -296,8 +296,8 @@ GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int
                    bool single_split, EpiArgs epi, bool defer_epilogue = false) {
     GemmShape g = gemm_plan(c->md.dt, M, N, K, single_split ? 1 : c->gemm_target_wgs);
     const bool prof = c->prof_on && c->prof_n < PROFILE_EVENTS;
-    if (prof) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], c->st);
-    if (!launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st, prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr, defer_epilogue))
+    if (!launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st, prof ? c->prof_ev[2 * c->prof_n] : nullptr,
+                     prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr, defer_epilogue))
         c->launch_refused = true;                   // reported by the next call that waits for the stream
     if (prof) {
         ++c->prof_n;

@@ -96,13 +96,13 @@ struct EpiArgs {
     // owns both factors of act[m][f] = T(silu(gate) * up); with S == 1 the stream kernel writes act itself
     void *act; int F;
 };
-// part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.  after_stream, if given, is
-// recorded between the weight-streaming kernel and its epilogue kernel (per-launch timing).
+// part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.  ev_start / ev_stop, if both
+// given, receive the begin and end timestamps of the weight-streaming kernel itself (per-launch timing).
 // Returns false, launching nothing, if a pointer the chosen epilogue writes through is null.
 // defer_epilogue (EPI_ROPE_KV only): the partial planes are left for launch_rope_kv_epilogue calls.
 bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t after_stream = nullptr,
-                 bool defer_epilogue = false);
+                 const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t ev_start = nullptr,
+                 hipEvent_t ev_stop = nullptr, bool defer_epilogue = false);
 // The RoPE + KV-write epilogue of a deferred launch over row ranges [r0, r1), each into its own cache and
 // with its own query limit (rows below rows_q get a rotated query), in one launch: several sequences batched
 // into one GEMM each take their own rows into their own cache.  Row indices stay those of the GEMM launch

@@ -21,6 +21,8 @@
 //     both factors, and the kernel writes SiLU(gate) * up in the storage type itself.
 #include "device_utils.h"
 
+#include <hip/hip_ext.h>
+
 #include <type_traits>
 
 namespace poss {
@@ -459,7 +461,7 @@ static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiAr
 
 template <typename T>
 static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                          const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream, bool defer_epilogue) {
+                          const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop, bool defer_epilogue) {
     // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
     const bool fuse_silu = epi.mode == EPI_SILU && g.S == 1;
     const bool wide = !fuse_silu && g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
@@ -470,9 +472,18 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     const T *x = static_cast<const T *>(X);
     T *act = static_cast<T *>(epi.act);
     const bool deep = !wide && (int)(grid.x * grid.y) < 256;     // fewer workgroups than CUs: deeper weight ring
+    // With a pair of events the launch itself carries them: they take the kernel's own begin and end
+    // timestamps (what a profiler reports), not the time of extra packets around it.
+    const bool timed = ev_start && ev_stop;
 #define POSS_GEMM_LAUNCH(MT, W, FUSE, PFV, FARG)                                                              \
-    hipLaunchKernelGGL((gemm_stream_kernel<T, MT, W, FUSE, PFV>), grid, block, 0, st, w, x, ldx, part, g.M,   \
-                       g.K, g.Npad, ksteps, act, FARG)
+    do {                                                                                                      \
+        if (timed)                                                                                            \
+            hipExtLaunchKernelGGL((gemm_stream_kernel<T, MT, W, FUSE, PFV>), grid, block, 0, st, ev_start,    \
+                                  ev_stop, 0, w, x, ldx, part, g.M, g.K, g.Npad, ksteps, act, FARG);          \
+        else                                                                                                  \
+            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, W, FUSE, PFV>), grid, block, 0, st, w, x, ldx, part, \
+                               g.M, g.K, g.Npad, ksteps, act, FARG);                                          \
+    } while (0)
 #define POSS_GEMM_CASE(MT)                                                                                    \
     do {                                                                                                      \
         if (fuse_silu) { if (deep) POSS_GEMM_LAUNCH(MT, 4, true, 8, epi.F); else POSS_GEMM_LAUNCH(MT, 4, true, 4, epi.F); } \
@@ -489,7 +500,6 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     }
 #undef POSS_GEMM_CASE
 #undef POSS_GEMM_LAUNCH
-    if (after_stream) (void)hipEventRecord(after_stream, st);
     if (!defer_epilogue) launch_epilogue_t<T>(g, part, epi, eps, fuse_silu, st);
 }
 
@@ -506,19 +516,22 @@ static bool gemm_args_ok(const GemmShape &g, const void *Wp, const void *X, cons
 }
 
 bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t after_stream, bool defer_epilogue) {
+                 const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop, bool defer_epilogue) {
     if (!gemm_args_ok(g, Wp, X, part, epi)) return false;
     if (defer_epilogue && epi.mode != EPI_ROPE_KV) return false;       // only that epilogue can be launched by row range
     if (dt == DT_F32) {
         dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
-        hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
-                           static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
-        if (after_stream) (void)hipEventRecord(after_stream, st);
+        if (ev_start && ev_stop)
+            hipExtLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, ev_start, ev_stop, 0, static_cast<const float *>(Wp),
+                                  static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
+        else
+            hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
+                               static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
         if (!defer_epilogue) launch_epilogue_t<float>(g, part, epi, eps, false, st);
     } else if (dt == DT_BF16) {
-        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st, after_stream, defer_epilogue);
+        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st, ev_start, ev_stop, defer_epilogue);
     } else {
-        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st, after_stream, defer_epilogue);
+        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st, ev_start, ev_stop, defer_epilogue);
     }
     return true;
 }
