@@ -105,8 +105,9 @@ typedef struct poss_tree {
 
 /* Acceptance statistics (section 3.1): c[i] = rounds that accepted at least i draft tokens,
  * so P(A_i) = c[i]/rounds, pos-acc_i = c[i]/c[i-1] (Eq. 3), and the mean number of accepted
- * draft tokens per round is sum_i c[i] / rounds (Eq. 4 summed over k).  Times are HIP-event
- * milliseconds summed over rounds. */
+ * draft tokens per round is sum_i c[i] / rounds (Eq. 4 summed over k).  With batch > 1 every
+ * sequence's round counts (rounds grows by batch per poss_accept_and_commit).  Times are HIP-event
+ * milliseconds summed over the calls. */
 typedef struct poss_stats {
     int64_t rounds, committed_tokens;
     int64_t c[POSS_MAX_DEPTH + 1];
