@@ -226,8 +226,7 @@ __device__ __forceinline__ void attn_mfma_body(
                     bm = fmaxf(bm, sv[j]);
                 }
             }
-            bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
-            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+            bm = rows_max(bm);
             const float m_new = fmaxf(m_run[rt], bm);
             float psum = 0.f;
             alpha[rt] = 1.f;

@@ -61,6 +61,22 @@ __device__ __forceinline__ void block_argmax(float &v, int &i, float *red_v, int
     v = red_v[16]; i = red_i[16];
 }
 
+// Maximum over the four 16-lane rows of a wave (lanes l, l^16, l^32, l^48), left in every lane.  The two
+// row-swap instructions of gfx950 stay in the vector ALU (v_permlane16_swap: [A.r0 B.r0 A.r2 B.r2] and
+// [A.r1 B.r1 A.r3 B.r3] from rows r0..r3 of registers A and B; v_permlane32_swap: [A.lo B.lo] and
+// [A.hi B.hi]); a shuffle would go through the LDS crossbar and wait for it.  Written as assembly with both
+// registers as in/out operands: through the builtin, this compiler reads the second result from the first
+// register.  (The s_nop covers the wait states a swap needs behind the VALU write of its operands.)
+// Every lane of the wave must be active.
+__device__ __forceinline__ float rows_max(float x) {
+    float a = x, b = x;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    x = fmaxf(a, b);
+    a = x; b = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return fmaxf(a, b);
+}
+
 // Rotary table of one row, by `half` threads of the row's workgroup starting at first_thread:
 // cs[i] = (cos, sin)(pos * theta^(-2i/dh)).  The angle is formed in float64 so that positions in the
 // thousands keep float32-accurate sines; one table serves every layer of the pass.
