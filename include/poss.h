@@ -126,6 +126,10 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace,
 
 /* Forget the sequence (back to the state after poss_load); statistics are cleared. */
 int poss_reset(poss_ctx *ctx);
+/* Forget one sequence of a batch; the others keep their state and the statistics are kept.  Rounds
+ * resume once the sequence has been given a new prompt (poss_prefill_seq): a finished sequence is
+ * replaced while the rest of the batch goes on.  Not between verify and accept. */
+int poss_reset_seq(poss_ctx *ctx, int32_t seq);
 
 /* Causal target pass over the prompt (HOST int32 ids, 1 <= n_prompt, n_prompt + 1 <= max_seq),
  * then every specialist's keys/values for the pairs [x_j ; f_{j-1}], j = 1..n_prompt-1

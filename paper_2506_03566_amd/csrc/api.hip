@@ -630,6 +630,23 @@ int poss_reset(poss_ctx *c) {
     return POSS_OK;
 }
 
+static int sync_and_harvest(poss_ctx *c);
+
+int poss_reset_seq(poss_ctx *c, int32_t seq) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (seq < 0 || seq >= c->B) return fail(c, POSS_E_INVALID_ARG, "poss_reset_seq: no sequence %d (batch %d)", seq, c->B);
+    if (c->state == ST_VERIFIED) return fail(c, POSS_E_BAD_STATE, "poss_reset_seq: a verified round is waiting for poss_accept_and_commit");
+    { int rc = sync_and_harvest(c); if (rc) return rc; }
+    Seq &sq = c->seq[seq];
+    sq.t = 0; sq.tree_ready = 0; sq.tree_n = 0; sq.prefilled = 0; sq.last_m = 0;
+    sq.tokens.clear();
+    sq.spec_len.assign(c->cfg.n_specialists, 0);
+    sq.spec_tmp_depth.assign(c->cfg.n_specialists, 0);
+    for (Seq &o : c->seq) o.tree_ready = 0;               // trees drafted for the old line-up are void
+    c->state = ST_LOADED;                                  // rounds resume once the sequence has a prompt again
+    return POSS_OK;
+}
+
 void poss_free(poss_ctx *c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->st);

@@ -258,3 +258,34 @@ def test_batched_caller_trees_equal_sequences_alone(name, batch, lengths):
         assert ctx.tokens(b) == alone[b][1]
         assert _same_tree(ctx.get_tree(b).as_dict(), alone[b][2]), f"sequence {b}: tree after caller-tree rounds"
     pair.close()
+
+
+def test_a_finished_sequence_is_replaced_while_the_others_go_on():
+    """Continuous batching: one sequence of the batch is reset and given a new prompt between
+    rounds; every sequence, old and new, commits what it commits alone."""
+    name, batch, n_rounds = "t_mid_bf16", 2, 3
+    cfg = get_config(name)
+    pair = Pair(name, lib_over={"batch": batch})
+    ctx = pair.ctx
+    p0, p1, p2 = _prompts(cfg, (150, 97, 61))
+    a0 = _rounds_alone(pair, p0, 2 * n_rounds)            # runs through both phases
+    a1 = _rounds_alone(pair, p1, n_rounds)                # finishes after the first phase
+    a2 = _rounds_alone(pair, p2, n_rounds)                # takes its place
+    ctx.prefill(p0, seq=0); ctx.prefill(p1, seq=1)
+
+    def rounds(n):
+        for _ in range(n):
+            ctx.draft_tree(want_tree=False)
+            ctx.verify_tree(want_argmax=False)
+            ctx.accept_and_commit()
+
+    rounds(n_rounds)
+    assert ctx.tokens(1) == a1[2]
+    ctx.reset(seq=1)
+    with pytest.raises(P.PossError):
+        ctx.draft_tree()                                  # sequence 1 has no prompt
+    assert ctx.prefill(p2, seq=1) == a2[0]
+    rounds(n_rounds)
+    assert ctx.tokens(0) == a0[2] and ctx.tokens(1) == a2[2]
+    assert ctx.stats().rounds == batch * 2 * n_rounds      # the statistics run on
+    pair.close()
