@@ -130,6 +130,12 @@ int poss_reset(poss_ctx *ctx);
  * resume once the sequence has been given a new prompt (poss_prefill_seq): a finished sequence is
  * replaced while the rest of the batch goes on.  Not between verify and accept. */
 int poss_reset_seq(poss_ctx *ctx, int32_t seq);
+/* Set a sequence of a batch aside (active == 0: the rounds go on without it, its tokens stay readable)
+ * or take it back in (it must still have its prompt; after poss_reset_seq use poss_prefill_seq, which
+ * activates it).  The last active sequence cannot be set aside.  Drafted trees are dropped: the rows
+ * of a round are laid out for the sequences that take part.  Not between verify and accept.  The
+ * outputs of the round calls that address "sequence 0" address the first active sequence. */
+int poss_set_active(poss_ctx *ctx, int32_t seq, int32_t active);
 
 /* Causal target pass over the prompt (HOST int32 ids, 1 <= n_prompt, n_prompt + 1 <= max_seq),
  * then every specialist's keys/values for the pairs [x_j ; f_{j-1}], j = 1..n_prompt-1

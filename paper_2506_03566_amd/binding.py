@@ -16,7 +16,7 @@ MAX_ROWS, MASK_WORDS, MAX_DEPTH = 128, 2, 16
 
 EXPORTS = ["poss_workspace_bytes", "poss_load", "poss_reset", "poss_prefill", "poss_draft_tree",
            "poss_verify_tree", "poss_accept_and_commit", "poss_get_stats", "poss_get_tokens",
-           "poss_prefill_seq", "poss_get_tree_seq", "poss_get_commit_seq", "poss_get_tokens_seq", "poss_set_uniforms_seq", "poss_reset_seq",
+           "poss_prefill_seq", "poss_get_tree_seq", "poss_get_commit_seq", "poss_get_tokens_seq", "poss_set_uniforms_seq", "poss_reset_seq", "poss_set_active",
            "poss_last_error", "poss_free", "poss_profile_gemm", "poss_gemm_profile", "poss_set_tuning", "poss_set_sampling",
            "poss_debug_build_tree", "poss_debug_set_taps", "poss_debug_read_kv",
            "poss_debug_gemm_scratch_bytes", "poss_debug_gemm"]
@@ -71,6 +71,7 @@ def load_library():
     lib.poss_load.argtypes = [P(PossConfig), P(PossWeights), c_vp, ctypes.c_size_t, c_vp, P(c_vp)]
     lib.poss_reset.argtypes = [c_vp]
     lib.poss_reset_seq.argtypes = [c_vp, c_i32]
+    lib.poss_set_active.argtypes = [c_vp, c_i32, c_i32]
     lib.poss_prefill.argtypes = [c_vp, P(c_i32), c_i32, P(c_i32)]
     lib.poss_draft_tree.argtypes = [c_vp, P(PossTree)]
     lib.poss_verify_tree.argtypes = [c_vp, P(PossTree), P(c_i32), c_vp, c_vp]
@@ -199,6 +200,10 @@ class Poss:
     def reset(self, seq=None):
         """Forget every sequence (and the statistics), or one sequence of a batch."""
         self._check(self.lib.poss_reset(self.h) if seq is None else self.lib.poss_reset_seq(self.h, seq))
+
+    def set_active(self, seq, active):
+        """Set a sequence of a batch aside (False) or take it back into the rounds (True)."""
+        self._check(self.lib.poss_set_active(self.h, seq, 1 if active else 0))
 
     def prefill(self, prompt, seq=0):
         p = np.ascontiguousarray(prompt, dtype=np.int32)

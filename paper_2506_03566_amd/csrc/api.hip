@@ -50,6 +50,7 @@ struct Seq {
     void *feat_stash, *xin_tmp;
     int32_t *result_pinned, *result_dev;   // the commit kernel's result: host memory and its device address
     int t, tree_ready, tree_n, tree_row0, prefilled;   // tree_row0: first row of its tree in the batch-wide arrays
+    int active;                        // takes part in the rounds (poss_set_active)
     std::vector<int32_t> tokens;
     std::vector<int> spec_len, spec_tmp_depth;
     int last_m;                        // the last commit: accepted drafts, path, committed tokens
@@ -502,13 +503,29 @@ void point_tree(poss_ctx *c, Seq &sq, int row0) {
 void reset_sequence(poss_ctx *c) {
     c->state = ST_LOADED;
     for (Seq &sq : c->seq) {
-        sq.t = 0; sq.tree_ready = 0; sq.tree_n = 0; sq.prefilled = 0; sq.last_m = 0;
+        sq.t = 0; sq.tree_ready = 0; sq.tree_n = 0; sq.prefilled = 0; sq.last_m = 0; sq.active = 1;
         point_tree(c, sq, (int)(&sq - &c->seq[0]) * (c->cfg.total_tokens + 1));
         sq.tokens.clear();
         sq.spec_len.assign(c->cfg.n_specialists, 0);
         sq.spec_tmp_depth.assign(c->cfg.n_specialists, 0);
     }
     memset(&c->stats, 0, sizeof(c->stats));
+}
+
+// The sequences that take part in the rounds, in order; a pass stacks their rows in this order.
+std::vector<int> active_seqs(const poss_ctx *c) {
+    std::vector<int> a;
+    for (int b = 0; b < c->B; ++b)
+        if (c->seq[b].active) a.push_back(b);
+    return a;
+}
+
+// Rounds can run when every active sequence has its prompt.
+void update_ready(poss_ctx *c) {
+    bool all = true;
+    for (const Seq &o : c->seq) all = all && (o.prefilled || !o.active);
+    if (c->state == ST_LOADED && all) c->state = ST_READY;
+    if (c->state == ST_READY && !all) c->state = ST_LOADED;
 }
 
 }  // namespace
@@ -642,8 +659,26 @@ int poss_reset_seq(poss_ctx *c, int32_t seq) {
     sq.tokens.clear();
     sq.spec_len.assign(c->cfg.n_specialists, 0);
     sq.spec_tmp_depth.assign(c->cfg.n_specialists, 0);
+    sq.active = 1;
     for (Seq &o : c->seq) o.tree_ready = 0;               // trees drafted for the old line-up are void
     c->state = ST_LOADED;                                  // rounds resume once the sequence has a prompt again
+    update_ready(c);
+    return POSS_OK;
+}
+
+int poss_set_active(poss_ctx *c, int32_t seq, int32_t active) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (seq < 0 || seq >= c->B) return fail(c, POSS_E_INVALID_ARG, "poss_set_active: no sequence %d (batch %d)", seq, c->B);
+    if (c->state == ST_VERIFIED) return fail(c, POSS_E_BAD_STATE, "poss_set_active: a verified round is waiting for poss_accept_and_commit");
+    Seq &sq = c->seq[seq];
+    if (!active) {
+        int others = 0;
+        for (const Seq &o : c->seq) others += (&o != &sq && o.active);
+        if (!others) return fail(c, POSS_E_INVALID_ARG, "poss_set_active: the last active sequence cannot be set aside");
+    }
+    sq.active = active ? 1 : 0;
+    for (Seq &o : c->seq) o.tree_ready = 0;               // the rows of a round are laid out per line-up
+    update_ready(c);
     return POSS_OK;
 }
 
@@ -660,7 +695,7 @@ void poss_free(poss_ctx *c) {
 
 const char *poss_last_error(poss_ctx *c) { return c ? c->err : g_load_error; }
 
-static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, int seq_first, int n_seq, const int *row0,
+static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, const int *seq_ids, int n_seq, const int *row0,
                          const int *n_rows);
 
 int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
@@ -688,7 +723,7 @@ int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_
             EpiArgs pe{};
             pe.mode = EPI_PLAIN;
             GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true, pe);
-            { const int zero = 0, one = 1; int rc = choose_tokens(c, g.Npad, 1, nullptr, seq, 1, &zero, &one); if (rc) return rc; }
+            { const int zero = 0, one = 1, id = seq; int rc = choose_tokens(c, g.Npad, 1, nullptr, &id, 1, &zero, &one); if (rc) return rc; }
             HIP_TRY(c, hipMemcpyAsync(sq.tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
         }
         HIP_TRY(c, hipStreamSynchronize(c->st));          // the staging buffer is reused by the next chunk
@@ -702,9 +737,8 @@ int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_
     HIP_TRY(c, hipStreamSynchronize(c->st));
     HIP_TRY(c, hipGetLastError());
     sq.prefilled = 1; sq.tree_ready = 0;
-    bool all = true;
-    for (const Seq &o : c->seq) all = all && o.prefilled;
-    if (all) c->state = ST_READY;                          // rounds start once every sequence has its prompt
+    sq.active = 1;
+    update_ready(c);                                       // rounds start once every active sequence has its prompt
     if (first_token_out) *first_token_out = first;
     return POSS_OK;
 }
@@ -715,15 +749,15 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
 
 // The token the target chooses after each of `rows` rows of c->logits: the argmax, or at temperature > 0 a
 // draw by inverse CDF with the uniform number of the row's depth (depth == nullptr: all rows use u[0]).
-// Sequence seq_first + i owns rows [row0[i], row0[i] + n_rows[i]) and has its own numbers.
-static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, int seq_first, int n_seq, const int *row0,
+// Sequence seq_ids[i] owns rows [row0[i], row0[i] + n_rows[i]) and has its own numbers.
+static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, const int *seq_ids, int n_seq, const int *row0,
                          const int *n_rows) {
     if (c->temperature > 0.f) {
         const int nu = POSS_MAX_DEPTH + 1;
         HIP_TRY(c, hipMemcpyAsync(c->u_dev, c->u_pinned, (size_t)c->B * nu * sizeof(float), hipMemcpyHostToDevice, c->st));
         for (int i = 0; i < n_seq; ++i)
             if (!launch_sample(c->logits + (size_t)row0[i] * ld, ld, n_rows[i], c->cfg.vocab, c->temperature,
-                               c->u_dev + (size_t)(seq_first + i) * nu, depth ? depth + row0[i] : nullptr, c->topk_scratch,
+                               c->u_dev + (size_t)seq_ids[i] * nu, depth ? depth + row0[i] : nullptr, c->topk_scratch,
                                c->argmax_dev + row0[i], c->st))
                 return fail(c, POSS_E_INVALID_ARG, "sampling: vocabulary too large for the sampler");
     } else {
@@ -752,17 +786,20 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
     if (!c) return POSS_E_INVALID_ARG;
     if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_draft_tree: needs a prefilled context with no pending verification");
     const poss_config &cf = c->cfg;
-    const int k = cf.top_k, L = cf.depth, B = c->B;
-    for (int b = 0; b < B; ++b) {
+    const int k = cf.top_k, L = cf.depth;
+    const std::vector<int> act = active_seqs(c);
+    const int B = (int)act.size();                         // sequences in this round
+    for (int b : act) {
         const int t = c->seq[b].t;
         if (t + cf.total_tokens + 1 > c->cache_slots || t + L + 1 > cf.max_seq)
             return fail(c, POSS_E_CAPACITY, "poss_draft_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
     }
     if (c->ev_pending[0]) { int rc = sync_and_harvest(c); if (rc) return rc; }   // a re-draft: keep the first one's time
     (void)hipEventRecord(c->ev[0], c->st);
-    for (int b = 0; b < B; ++b) {
+    for (int i = 0; i < B; ++i) {
+        const int b = act[i];
         Seq &sq = c->seq[b];
-        point_tree(c, sq, b * (cf.total_tokens + 1));
+        point_tree(c, sq, i * (cf.total_tokens + 1));
         for (int s = 0; s < cf.n_specialists; ++s) {
             sq.spec_tmp_depth[s] = 0;
             if (sq.t - 1 - sq.spec_len[s] > L) spec_catchup(c, b, s, sq.t - 1);      // only after caller-supplied trees
@@ -774,9 +811,10 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
         std::vector<SeqPlan> plans(B);
         int rows_all = 0;
         const int rows_q_each = d == 1 ? 1 : k;
-        for (int b = 0; b < B; ++b) {
+        for (int i = 0; i < B; ++i) {
+            const int b = act[i];
             Seq &sq = c->seq[b];
-            SeqPlan &sp = plans[b];
+            SeqPlan &sp = plans[i];
             DraftRowPlan &plan = sp.plan;
             const int t = sq.t;
             int n = 0;
@@ -787,12 +825,12 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
                 sp.n_prefix = sq.spec_len[s]; sp.region_len = t - sp.n_prefix;
                 plan.mask0[0] = ones(sp.region_len); plan.mask0[1] = ones(sp.region_len - 64);
                 plan.kind[n] = 0; plan.idx[n] = t - 1; plan.slot[n] = t - 1; plan.pos[n] = t - 1; ++n;
-                for (int i = sp.n_prefix; i < t - 1; ++i) { plan.kind[n] = 0; plan.idx[n] = i; plan.slot[n] = i; plan.pos[n] = i; ++n; }
+                for (int j = sp.n_prefix; j < t - 1; ++j) { plan.kind[n] = 0; plan.idx[n] = j; plan.slot[n] = j; plan.pos[n] = j; ++n; }
             } else {
                 sp.n_prefix = t; sp.region_len = (d - 1) * k;
                 plan.mask0[0] = plan.mask0[1] = 0;
                 for (int r = 0; r < k; ++r) { plan.kind[n] = 2; plan.idx[n] = r; plan.slot[n] = t + (d - 2) * k + r; plan.pos[n] = t - 1 + (d - 1); ++n; }
-                for (int i = sq.spec_len[s]; i < t; ++i) { plan.kind[n] = 0; plan.idx[n] = i; plan.slot[n] = i; plan.pos[n] = i; ++n; }
+                for (int j = sq.spec_len[s]; j < t; ++j) { plan.kind[n] = 0; plan.idx[n] = j; plan.slot[n] = j; plan.pos[n] = j; ++n; }
                 for (int dl = sq.spec_tmp_depth[s] + 1; dl <= d - 2; ++dl)
                     for (int r = 0; r < k; ++r) { plan.kind[n] = 1; plan.idx[n] = (dl - 1) * k + r; plan.slot[n] = t + (dl - 1) * k + r; plan.pos[n] = t - 1 + dl; ++n; }
             }
@@ -805,17 +843,17 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
         const int rows_q = B * rows_q_each;
         GemmShape g = run_head(c, rows_q);
         launch_topk_logsoftmax(c->logits, g.Npad, rows_q, cf.vocab, k, c->topk_scratch, c->topk_id_all, c->topk_logp_all, c->st);
-        for (int b = 0; b < B; ++b) {
-            Seq &sq = c->seq[b];
+        for (int i = 0; i < B; ++i) {
+            Seq &sq = c->seq[act[i]];
             TreeDev td = sq.td;                              // this sequence's rows of the top-k
-            td.topk_id = c->topk_id_all + (size_t)q0[b] * k; td.topk_logp = c->topk_logp_all + (size_t)q0[b] * k;
+            td.topk_id = c->topk_id_all + (size_t)q0[i] * k; td.topk_logp = c->topk_logp_all + (size_t)q0[i] * k;
             launch_tree_expand(td, d, k, L, rows_q_each, c->st);
             sq.spec_len[s] = sq.t;
             sq.spec_tmp_depth[s] = d - 1;
         }
     }
     const int pool = k + (L - 1) * k * k;
-    for (int b = 0; b < B; ++b) {
+    for (int b : act) {
         Seq &sq = c->seq[b];
         launch_tree_finalize(sq.td, k, L, cf.total_tokens, sq.t, sq.tokens_dev, sq.tree_slot, c->st);
         sq.tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
@@ -825,7 +863,7 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
     c->ev_pending[0] = true;
     HIP_TRY(c, hipGetLastError());
     if (!out) return POSS_OK;                    // nothing for the host: the work stays queued
-    int rc = copy_tree_out(c, c->seq[0], out);
+    int rc = copy_tree_out(c, c->seq[act[0]], out);             // the first active sequence's
     if (rc) return rc;
     return sync_and_harvest(c);
 }
@@ -870,53 +908,56 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     if (!c) return POSS_E_INVALID_ARG;
     if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: needs a prefilled context with no pending verification");
     const poss_config &cf = c->cfg;
-    const int B = c->B;
+    const std::vector<int> act = active_seqs(c);
+    const int B = (int)act.size();                         // sequences in this round; i-th active sequence = act[i]
     int row0[8], n_rows[8], rows = 0;
-    if (tree) {                                            // one tree per sequence: tree[0 .. B-1]
-        for (int b = 0; b < B; ++b) {
-            const poss_tree &tr = tree[b];
+    if (tree) {                                            // one tree per sequence: tree[0 .. batch-1], inactive ones ignored
+        for (int i = 0; i < B; ++i) {
+            const poss_tree &tr = tree[act[i]];
             const int n = tr.n_nodes;
             if (n < 1 || n > cf.total_tokens + 1) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: %d nodes, capacity %d", n, cf.total_tokens + 1);
             if (!tr.token || !tr.parent) return fail(c, POSS_E_INVALID_ARG, "poss_verify_tree: null tree arrays");
             std::vector<int> depth(n, 0);
             if (tr.parent[0] != -1) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: parent[0] must be -1");
-            for (int i = 1; i < n; ++i) {
-                const int p = tr.parent[i];
-                if (p < 0 || p >= i) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: parent[%d] = %d does not precede the node", i, p);
-                if (tr.token[i] < 0 || tr.token[i] >= cf.vocab) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: token[%d] out of range", i);
-                depth[i] = depth[p] + 1;
-                if (depth[i] > cf.depth) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: node %d deeper than depth %d", i, cf.depth);
-                for (int j = 1; j < i; ++j)
-                    if (tr.parent[j] == p && tr.token[j] == tr.token[i])
-                        return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: siblings %d and %d carry the same token", j, i);
+            for (int v2 = 1; v2 < n; ++v2) {
+                const int p = tr.parent[v2];
+                if (p < 0 || p >= v2) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: parent[%d] = %d does not precede the node", v2, p);
+                if (tr.token[v2] < 0 || tr.token[v2] >= cf.vocab) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: token[%d] out of range", v2);
+                depth[v2] = depth[p] + 1;
+                if (depth[v2] > cf.depth) return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: node %d deeper than depth %d", v2, cf.depth);
+                for (int j = 1; j < v2; ++j)
+                    if (tr.parent[j] == p && tr.token[j] == tr.token[v2])
+                        return fail(c, POSS_E_BAD_TREE, "poss_verify_tree: siblings %d and %d carry the same token", j, v2);
             }
-            row0[b] = rows; n_rows[b] = n; rows += n;       // back to back
+            row0[i] = rows; n_rows[i] = n; rows += n;       // back to back
         }
     } else {
-        for (int b = 0; b < B; ++b) {
-            if (!c->seq[b].tree_ready) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: no drafted tree");
-            row0[b] = c->seq[b].tree_row0; n_rows[b] = c->seq[b].tree_n; rows = row0[b] + n_rows[b];   // fixed stride, no gaps
+        for (int i = 0; i < B; ++i) {
+            const Seq &sq = c->seq[act[i]];
+            if (!sq.tree_ready) return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: no drafted tree");
+            row0[i] = sq.tree_row0; n_rows[i] = sq.tree_n; rows = row0[i] + n_rows[i];   // fixed stride, no gaps
         }
     }
-    for (int b = 0; b < B; ++b) {
-        const int t = c->seq[b].t;
-        if (t + n_rows[b] > c->cache_slots || t + cf.depth + 1 > cf.max_seq)
+    for (int i = 0; i < B; ++i) {
+        const int t = c->seq[act[i]].t;
+        if (t + n_rows[i] > c->cache_slots || t + cf.depth + 1 > cf.max_seq)
             return fail(c, POSS_E_CAPACITY, "poss_verify_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
     }
     (void)hipEventRecord(c->ev[2], c->st);
     if (tree) {
         int32_t *stage = static_cast<int32_t *>(c->pinned);      // [tokens | parents | node counts]
-        for (int b = 0; b < B; ++b) {
+        for (int i = 0; i < B; ++i) {
+            const int b = act[i];
             Seq &sq = c->seq[b];
-            const int n = n_rows[b], t = sq.t;
-            point_tree(c, sq, row0[b]);
-            memcpy(stage + row0[b], tree[b].token, n * sizeof(int32_t));
-            stage[row0[b]] = sq.tokens[t];                        // the root is always x_t
-            memcpy(stage + MAX_ROWS + row0[b], tree[b].parent, n * sizeof(int32_t));
-            stage[2 * MAX_ROWS + b] = n;
-            HIP_TRY(c, hipMemcpyAsync(sq.td.token, stage + row0[b], n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-            HIP_TRY(c, hipMemcpyAsync(sq.td.parent, stage + MAX_ROWS + row0[b], n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-            HIP_TRY(c, hipMemcpyAsync(sq.td.n_nodes, stage + 2 * MAX_ROWS + b, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+            const int n = n_rows[i], t = sq.t;
+            point_tree(c, sq, row0[i]);
+            memcpy(stage + row0[i], tree[b].token, n * sizeof(int32_t));
+            stage[row0[i]] = sq.tokens[t];                        // the root is always x_t
+            memcpy(stage + MAX_ROWS + row0[i], tree[b].parent, n * sizeof(int32_t));
+            stage[2 * MAX_ROWS + i] = n;
+            HIP_TRY(c, hipMemcpyAsync(sq.td.token, stage + row0[i], n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+            HIP_TRY(c, hipMemcpyAsync(sq.td.parent, stage + MAX_ROWS + row0[i], n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+            HIP_TRY(c, hipMemcpyAsync(sq.td.n_nodes, stage + 2 * MAX_ROWS + i, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
             launch_tree_upload_finish(n, t, sq.td.token, sq.td.parent, sq.td.depth, sq.td.pos, sq.tree_slot, sq.td.mask, c->st);
             sq.tree_n = n; sq.tree_ready = 1;
         }
@@ -924,13 +965,13 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     // the trees' rows are adjacent slices of the batch-wide arrays: one pass over all of them
     RowMeta rm{c->tree_pos_all, c->tree_slot_all, c->tree_mask_all};
     std::vector<Seg> segs;
-    for (int b = 0; b < B; ++b) segs.push_back(Seg{b, nullptr, row0[b], n_rows[b], rows, 0, c->seq[b].t, n_rows[b]});
+    for (int i = 0; i < B; ++i) segs.push_back(Seg{act[i], nullptr, row0[i], n_rows[i], rows, 0, c->seq[act[i]].t, n_rows[i]});
     target_forward(c, rows, c->tree_token_all, rm, segs);
     GemmShape g = run_head(c, rows);
-    { int rc = choose_tokens(c, g.Npad, rows, c->tree_depth_all, 0, B, row0, n_rows); if (rc) return rc; }
+    { int rc = choose_tokens(c, g.Npad, rows, c->tree_depth_all, act.data(), B, row0, n_rows); if (rc) return rc; }
     (void)hipEventRecord(c->ev[3], c->st);
     c->ev_pending[1] = true;
-    const int n = n_rows[0];                               // host and device outputs: sequence 0's rows
+    const int n = n_rows[0];                               // host and device outputs: the first active sequence's rows
     if (logits_out) launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
     if (feat_out) launch_copy_rows_f32(c->feats, cf.d_model, static_cast<float *>(feat_out), cf.d_model, n, cf.d_model, c->st);
     HIP_TRY(c, hipGetLastError());
@@ -947,9 +988,10 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
     if (!c) return POSS_E_INVALID_ARG;
     if (c->state != ST_VERIFIED) return fail(c, POSS_E_BAD_STATE, "poss_accept_and_commit: no verified tree");
     const poss_config &cf = c->cfg;
-    const int L = cf.depth, B = c->B;
+    const int L = cf.depth;
+    const std::vector<int> act = active_seqs(c);
     (void)hipEventRecord(c->ev[4], c->st);
-    for (int b = 0; b < B; ++b) {
+    for (int b : act) {
         Seq &sq = c->seq[b];
         const int row0 = sq.tree_row0;
         launch_commit(c->md, cf.n_layers, sq.target_kv_dev, sq.td.token, sq.td.parent, c->argmax_dev + row0, sq.td.n_nodes, L, sq.t,
@@ -958,7 +1000,7 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
     (void)hipEventRecord(c->ev[5], c->st);
     c->ev_pending[2] = true;
     { int rc = sync_and_harvest(c); if (rc) return rc; }
-    for (int b = 0; b < B; ++b) {
+    for (int b : act) {
         Seq &sq = c->seq[b];
         const int32_t *walk = sq.result_pinned, *toks = walk + 32;     // written by the kernel itself
         const int m = walk[0];
@@ -971,7 +1013,7 @@ int poss_accept_and_commit(poss_ctx *c, int32_t *path_idx_out, int32_t *n_accept
         c->stats.committed_tokens += m + 1;
         for (int i = 1; i <= m; ++i) c->stats.c[i] += 1;
     }
-    const Seq &s0 = c->seq[0];
+    const Seq &s0 = c->seq[act[0]];                        // the outputs of this call: the first active sequence
     if (path_idx_out) for (int j = 0; j <= s0.last_m; ++j) path_idx_out[j] = s0.last_path[j];
     if (n_accepted_out) *n_accepted_out = s0.last_m;
     if (committed_out) for (int j = 0; j <= s0.last_m; ++j) committed_out[j] = s0.last_tokens[j];

@@ -289,3 +289,44 @@ def test_a_finished_sequence_is_replaced_while_the_others_go_on():
     assert ctx.tokens(0) == a0[2] and ctx.tokens(1) == a2[2]
     assert ctx.stats().rounds == batch * 2 * n_rounds      # the statistics run on
     pair.close()
+
+
+def test_rounds_go_on_without_a_sequence_that_was_set_aside():
+    """A batch of three: the middle sequence stops after two rounds, the others go on alone (their rows
+    move up), then it comes back; every sequence commits what it commits alone over its own rounds."""
+    name, batch = "c0_tiny_f32", 3
+    cfg = get_config(name)
+    pair = Pair(name, storage=_perfect_drafter_storage(cfg), lib_over={"batch": batch})
+    ctx = pair.ctx
+    prompts = _prompts(cfg, (16, 23, 40))
+    alone = [_rounds_alone(pair, prompts[0], 6), _rounds_alone(pair, prompts[1], 4), _rounds_alone(pair, prompts[2], 6)]
+
+    def rounds(n):
+        for _ in range(n):
+            ctx.draft_tree(want_tree=False)
+            ctx.verify_tree(want_argmax=False)
+            ctx.accept_and_commit()
+
+    for b, p in enumerate(prompts):
+        ctx.prefill(p, seq=b)
+    rounds(2)
+    ctx.set_active(1, False)
+    kept = ctx.tokens(1)
+    rounds(2)                                             # sequences 0 and 2 only
+    assert ctx.tokens(1) == kept and ctx.stats().rounds == 3 * 2 + 2 * 2
+    tr = ctx.draft_tree()                                 # the tree handed back is the first active sequence's
+    assert _same_tree(tr.as_dict(), ctx.get_tree(0).as_dict())
+    ctx.set_active(1, True)                               # (drops the drafted trees)
+    with pytest.raises(P.PossError):
+        ctx.verify_tree(want_argmax=False)
+    rounds(2)
+    for b in range(batch):
+        assert ctx.tokens(b) == alone[b][2], f"sequence {b}"
+    ctx.set_active(0, False); ctx.set_active(2, False)
+    with pytest.raises(P.PossError):
+        ctx.set_active(1, False)                          # someone has to stay
+    ctx.draft_tree(want_tree=False)
+    ctx.verify_tree(want_argmax=False)
+    path, m, toks = ctx.accept_and_commit()               # outputs: the first active sequence, here sequence 1
+    assert (path, m, toks) == ctx.commit_result(1)
+    pair.close()
