@@ -9,8 +9,9 @@
  * With poss_config.batch = B > 1 a context carries B independent sequences:
  * each has its own caches, tree and token stream, every pass stacks their rows into one set of
  * weight-streaming launches, and the three round calls advance all of them; poss_prefill_seq,
- * poss_get_tree_seq, poss_get_commit_seq and poss_get_tokens_seq address one sequence (the calls
- * without _seq address sequence 0).  A sequence's tokens are the ones it gets at batch 1.
+ * poss_get_tree_seq, poss_get_commit_seq, poss_get_tokens_seq and poss_set_uniforms_seq address one
+ * sequence (the calls without _seq address sequence 0); poss_set_active and poss_reset_seq take a
+ * sequence out of the rounds or replace it.  A sequence's tokens are the ones it gets at batch 1.
  *
  * Every step runs in hand-written HIP kernels of this library.  All pointers
  * are plain addresses; each argument says whether it is HOST or DEVICE memory.
