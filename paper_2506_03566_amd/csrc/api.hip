@@ -100,7 +100,6 @@ struct poss_ctx {
     int prof_on, prof_n;
     hipEvent_t prof_ev[2 * PROFILE_EVENTS];
     double prof_bytes;
-    int64_t prof_launches; double prof_ms;
 };
 
 namespace {
@@ -177,7 +176,6 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     const int dt = c.dtype;
     const size_t es = esize(c);
     const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kd = c.n_kv_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
-    const int tw = 0;
     auto layer_slots = [&](std::vector<void *> &out) {
         out.push_back(a.take(d * es));
         out.push_back(a.take(packed_elems(dt, qd + 2 * kd, d) * es));
@@ -273,7 +271,6 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         for (int s2 = 0; s2 < c.n_specialists; ++s2)
             sq.spec_kv.push_back(KVCache{kvp[base + 2 * (c.n_layers + s2)], kvp[base + 2 * (c.n_layers + s2) + 1], pt, shift});
     }
-    (void)tw;
     if (ctx) {
         ctx->B = B;
         ctx->cache_slots = slots; ctx->n_pages = pages; ctx->page_table = pt; ctx->cache_bytes_each = cache_each;
@@ -563,7 +560,7 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     c->err[0] = 0;
     c->taps_user = nullptr;
     c->gemm_target_wgs = 0; c->attn_keys_per_split = 0;
-    c->prof_on = 0; c->prof_n = 0; c->prof_bytes = 0; c->prof_launches = 0; c->prof_ms = 0;
+    c->prof_on = 0; c->prof_n = 0; c->prof_bytes = 0;
     Arena a(workspace);
     WeightSlots ws;
     carve(*cfg, a, c, &ws);

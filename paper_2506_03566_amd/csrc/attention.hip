@@ -38,10 +38,11 @@ template <> struct Vec8<f16_t> {
 };
 
 __device__ __forceinline__ bool slot_visible(int slot, int n_prefix, int region_len, uint64_t m0, uint64_t m1) {
-    if (slot < n_prefix) return true;
+    // straight-line: a lane's eight slots would otherwise each cost a divergent branch
     const int j = slot - n_prefix;
-    if (j >= region_len) return false;
-    return ((j < 64 ? m0 >> j : m1 >> (j - 64)) & 1ull) != 0;
+    const uint64_t word = j < 64 ? m0 : m1;
+    const bool bit = ((word >> (j & 63)) & 1ull) != 0;
+    return (j < 0) | (((unsigned)j < (unsigned)region_len) & bit);
 }
 
 // One workgroup = 4 waves x RT tiles of 16 query rows of ONE KV head (times KW key-ways), over the key
@@ -69,10 +70,10 @@ __device__ __forceinline__ void attn_mfma_body(
     T *ks_lds = lds_all, *vs_lds = lds_all + 2 * KW * KBLK;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
-    const int kway = wave >> 2;                           // which of the KW blocks of an iteration this wave takes
     // staging: 256 threads per block; the block index is wave-uniform, and said to be, so that the
     // page-table reads become scalar loads that do not queue behind the key/value loads in flight
     const int stage_blk = __builtin_amdgcn_readfirstlane(tid >> 8), stid = tid & 255;
+    const int kway = stage_blk;                           // which of the KW blocks of an iteration this wave takes (wave / 4): branches on it are scalar
     // Workgroup id -> (row group, KV head, split).  Consecutive ids go to the 8 XCDs in turn, each with an
     // L2 of its own, so the row groups that read the same keys and values (same head and split) are given
     // ids that are equal modulo 8: the block is fetched from memory once and then found in that L2.
