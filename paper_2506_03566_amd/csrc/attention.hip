@@ -126,13 +126,14 @@ __device__ __forceinline__ void attn_mfma_body(
         return page_table_c[(b << 5) >> kv.page_shift];
     };
     int pg_next = page_of(b0);
-    auto load_block = [&](auto slot_tag, int bfirst) {    // this thread's share of block bfirst + stage_blk
+    // pg_after: the entry for the call that follows (bfirst + KW), read by the caller
+    auto load_block = [&](auto slot_tag, int bfirst, int pg_after) {    // this thread's share of block bfirst + stage_blk
         constexpr int SLOT = decltype(slot_tag)::value;
         int b = bfirst + stage_blk;
         if (b >= b1) b = b1 - 1;                          // never predicated: reload a valid block, it is ignored
         const int slot0 = b << 5;
         const int pg = pg_next, off = slot0 & (P - 1);
-        pg_next = page_of(bfirst + KW);
+        pg_next = pg_after;
         const size_t head_base = (size_t)(pg * hkv + kvh);
         const T *kb = kc + (head_base * P + off) * DH;
         const T *vb = vc + head_base * DH * P + off;
@@ -177,9 +178,9 @@ __device__ __forceinline__ void attn_mfma_body(
         if constexpr (PFD > 2) f(std::integral_constant<int, 2>{});
         if constexpr (PFD > 3) f(std::integral_constant<int, 3>{});
     };
-    static_for([&](auto p) { load_block(p, b0 + decltype(p)::value * KW); });
+    static_for([&](auto p) { load_block(p, b0 + decltype(p)::value * KW, page_of(b0 + (decltype(p)::value + 1) * KW)); });
     store_block(std::integral_constant<int, 0>{}, 0);
-    load_block(std::integral_constant<int, 0>{}, b0 + PFD * KW);
+    load_block(std::integral_constant<int, 0>{}, b0 + PFD * KW, page_of(b0 + (PFD + 1) * KW));
     __syncthreads();
     int buf = 0;
     // iteration `it` (blocks bi .. bi+KW-1): compute from LDS buffer `buf`, move iteration it+1 (ring
@@ -189,24 +190,37 @@ __device__ __forceinline__ void attn_mfma_body(
     // of the loop), and the wait for a block's loads comes after an iteration's arithmetic, not before.
     auto iteration = [&](auto slot_tag, int bi) {
         constexpr int SLOT = decltype(slot_tag)::value;
+        // requested here, used by this iteration's refill: at the foot of the iteration the wait for the
+        // LDS stores ahead of the barrier would wait for this scalar load as well
+        const int pg_ahead = page_of(bi + (2 + PFD) * KW);
         const int b = bi + kway;
         if (b < b1) {                                     // wave-uniform
         const int slot0 = b << 5;
         const T *kbuf = &ks_lds[(buf * KW + kway) * KBLK], *vbuf = &vs_lds[(buf * KW + kway) * VBLK];
         // S^T tiles: rows = keys slot0 + tt*16 + (0..15), columns = query rows of a tile of this wave
+        // every key fragment of the block is requested before the first MFMA, and the value fragments
+        // before the softmax: read where they are used, each pair of reads is waited for in turn
         f32x4 s[RT][2];
+        u32x4 kf[2][KS], vf[DT];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kf[tt][ks] = *reinterpret_cast<const u32x4 *>(&kbuf[(tt * 16 + lr) * KROW + ks * 32 + lg * 8]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) s[rt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const u32x4 kf = *reinterpret_cast<const u32x4 *>(&kbuf[(tt * 16 + lr) * KROW + ks * 32 + lg * 8]);
+            for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt)
-                    s[rt][tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf), qf[rt][ks], s[rt][tt]);
-            }
+                    s[rt][tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf[tt][ks]), qf[rt][ks], s[rt][tt]);
         }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) vf[dt] = *reinterpret_cast<const u32x4 *>(&vbuf[(dt * 16 + lr) * VROW + lg * 8]);
+        __builtin_amdgcn_sched_barrier(0);
         // lane holds keys slot0 + tt*16 + 4*lg + r of query row lr.  Scores are kept in the log2
         // domain (scale * log2 e folded into one factor) so that the exponentials are single
         // v_exp_f32 instructions; the softmax is VALU-bound, not MFMA-bound, at these sizes.
@@ -215,19 +229,20 @@ __device__ __forceinline__ void attn_mfma_body(
         bool rescale = false;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
+            // raw scores; the factor (positive: the maximum commutes with it) goes into the exponent's fma
             float sv[8], bm = -INFINITY;
             if (slot0 + 32 <= n_prefix) {                // whole block inside the committed prefix
 #pragma unroll
-                for (int j = 0; j < 8; ++j) { sv[j] = s[rt][j >> 2][j & 3] * scale; bm = fmaxf(bm, sv[j]); }
+                for (int j = 0; j < 8; ++j) { sv[j] = s[rt][j >> 2][j & 3]; bm = fmaxf(bm, sv[j]); }
             } else {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const int slot = slot0 + (j >> 2) * 16 + 4 * lg + (j & 3);
-                    sv[j] = slot_visible(slot, n_prefix, region_len, m0[rt], m1[rt]) ? s[rt][j >> 2][j & 3] * scale : -INFINITY;
+                    sv[j] = slot_visible(slot, n_prefix, region_len, m0[rt], m1[rt]) ? s[rt][j >> 2][j & 3] : -INFINITY;
                     bm = fmaxf(bm, sv[j]);
                 }
             }
-            bm = rows_max(bm);
+            bm = rows_max(bm) * scale;
             const float m_new = fmaxf(m_run[rt], bm);
             float psum = 0.f;
             alpha[rt] = 1.f;
@@ -238,9 +253,9 @@ __device__ __forceinline__ void attn_mfma_body(
                 alpha[rt] = __builtin_amdgcn_exp2f(m_run[rt] - m_new);   // 2^(-inf) = 0 on the first visible block
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const T pt = from_f<T>(__builtin_amdgcn_exp2f(sv[j] - m_new));
-                    pf[rt][j] = pt;
-                    psum += to_f(pt);                    // normalise by what is actually multiplied into V
+                    const float pe = __builtin_amdgcn_exp2f(fmaf(sv[j], scale, -m_new));
+                    pf[rt][j] = from_f<T>(pe);
+                    psum += pe;
                 }
             }
             l_run[rt] = l_run[rt] * alpha[rt] + psum;
@@ -255,15 +270,13 @@ __device__ __forceinline__ void attn_mfma_body(
                 for (int dt = 0; dt < DT; ++dt) acc[rt][dt] *= alpha[rt];
         }
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            const u32x4 vf = *reinterpret_cast<const u32x4 *>(&vbuf[(dt * 16 + lr) * VROW + lg * 8]);
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
-                acc[rt][dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf), pf[rt], acc[rt][dt]);
-        }
+                acc[rt][dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf[dt]), pf[rt], acc[rt][dt]);
         }
         store_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, buf ^ 1);
-        load_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, bi + (1 + PFD) * KW);
+        load_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, bi + (1 + PFD) * KW, pg_ahead);
         __syncthreads();
         buf ^= 1;
     };
