@@ -243,7 +243,11 @@ __device__ __forceinline__ void attn_mfma_body(
                 }
             }
             bm = rows_max(bm) * scale;
-            const float m_new = fmaxf(m_run[rt], bm);
+            // The reference point of the exponentials only moves when the block's maximum is more than
+            // 2^8 above it (any reference gives the same quotient; the probabilities then go up to 256
+            // instead of 1, exact in float32 and in the 16-bit operand alike): without the slack nearly
+            // every block moves some row's maximum a little and all accumulators are rescaled.
+            const float m_new = bm > m_run[rt] + 8.f ? bm : m_run[rt];
             float psum = 0.f;
             alpha[rt] = 1.f;
             if (m_new == -INFINITY) {
