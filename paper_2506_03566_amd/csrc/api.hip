@@ -840,21 +840,29 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
         const int rows_q = B * rows_q_each;
         GemmShape g = run_head(c, rows_q);
         launch_topk_logsoftmax(c->logits, g.Npad, rows_q, cf.vocab, k, c->topk_scratch, c->topk_id_all, c->topk_logp_all, c->st);
+        TreeDev tds[8];
         for (int i = 0; i < B; ++i) {
             Seq &sq = c->seq[act[i]];
-            TreeDev td = sq.td;                              // this sequence's rows of the top-k
-            td.topk_id = c->topk_id_all + (size_t)q0[i] * k; td.topk_logp = c->topk_logp_all + (size_t)q0[i] * k;
-            launch_tree_expand(td, d, k, L, rows_q_each, c->st);
+            tds[i] = sq.td;                                  // with this sequence's rows of the top-k
+            tds[i].topk_id = c->topk_id_all + (size_t)q0[i] * k; tds[i].topk_logp = c->topk_logp_all + (size_t)q0[i] * k;
             sq.spec_len[s] = sq.t;
             sq.spec_tmp_depth[s] = d - 1;
         }
+        launch_tree_expand(tds, B, d, k, L, rows_q_each, c->st);        // one launch, a workgroup per sequence
     }
     const int pool = k + (L - 1) * k * k;
-    for (int b : act) {
-        Seq &sq = c->seq[b];
-        launch_tree_finalize(sq.td, k, L, cf.total_tokens, sq.t, sq.tokens_dev, sq.tree_slot, c->st);
-        sq.tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
-        sq.tree_ready = 1;
+    {
+        TreeDev tds[8];
+        int ts[8];
+        const int32_t *toks[8];
+        int32_t *slots[8];
+        for (int i = 0; i < B; ++i) {
+            Seq &sq = c->seq[act[i]];
+            tds[i] = sq.td; ts[i] = sq.t; toks[i] = sq.tokens_dev; slots[i] = sq.tree_slot;
+            sq.tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
+            sq.tree_ready = 1;
+        }
+        launch_tree_finalize(tds, B, k, L, cf.total_tokens, ts, toks, slots, c->st);
     }
     (void)hipEventRecord(c->ev[1], c->st);
     c->ev_pending[0] = true;
@@ -889,9 +897,12 @@ int poss_debug_build_tree(poss_ctx *c, const int32_t *ids, const float *logp, po
         const int rows = d == 1 ? 1 : k;
         HIP_TRY(c, hipMemcpyAsync(sq.td.topk_id, sid + (size_t)(d - 1) * k * k, rows * k * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
         HIP_TRY(c, hipMemcpyAsync(sq.td.topk_logp, slp + (size_t)(d - 1) * k * k, rows * k * sizeof(float), hipMemcpyHostToDevice, c->st));
-        launch_tree_expand(sq.td, d, k, L, rows, c->st);
+        launch_tree_expand(&sq.td, 1, d, k, L, rows, c->st);
     }
-    launch_tree_finalize(sq.td, k, L, cf.total_tokens, sq.t, sq.tokens_dev, sq.tree_slot, c->st);
+    {
+        const int32_t *toks = sq.tokens_dev;
+        launch_tree_finalize(&sq.td, 1, k, L, cf.total_tokens, &sq.t, &toks, &sq.tree_slot, c->st);
+    }
     const int pool = k + (L - 1) * k * k;
     sq.tree_n = (cf.total_tokens < pool ? cf.total_tokens : pool) + 1;
     sq.tree_ready = 1;

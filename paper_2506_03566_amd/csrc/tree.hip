@@ -207,8 +207,17 @@ size_t topk_scratch_floats(int rows, int vocab) {
 // Children of the frontier of depth d-1 (the root for d = 1) join the candidate pool; unless d = L,
 // the k best of them become the frontier of depth d.  A frontier node's drafter row lives in temp
 // slot (d-1)*k + rank; fr_mask collects the temp slots of the node and its drafted ancestors.
-__global__ __launch_bounds__(256) void tree_expand_kernel(TreeDev td, int d, int k, int L, int rows) {
+// One workgroup per sequence of the batch.
+struct TreeBatch {
+    TreeDev td[TREE_BATCH_MAX];
+    int t[TREE_BATCH_MAX];
+    const int32_t *tokens_dev[TREE_BATCH_MAX];
+    int32_t *slot_out[TREE_BATCH_MAX];
+};
+
+__global__ __launch_bounds__(256) void tree_expand_kernel(TreeBatch tb, int d, int k, int L, int rows) {
     __shared__ float sc[256];
+    const TreeDev &td = tb.td[blockIdx.x];
     const int n_child = rows * k;
     const int base = d == 1 ? 0 : k + (d - 2) * k * k;
     const int tid = threadIdx.x;
@@ -244,17 +253,22 @@ __global__ __launch_bounds__(256) void tree_expand_kernel(TreeDev td, int d, int
     }
 }
 
-void launch_tree_expand(const TreeDev &td, int d, int k, int L, int rows, hipStream_t st) {
-    hipLaunchKernelGGL(tree_expand_kernel, dim3(1), dim3(256), 0, st, td, d, k, L, rows);
+void launch_tree_expand(const TreeDev *tds, int n_seq, int d, int k, int L, int rows, hipStream_t st) {
+    if (n_seq < 1 || n_seq > TREE_BATCH_MAX) return;
+    TreeBatch tb{};
+    for (int i = 0; i < n_seq; ++i) tb.td[i] = tds[i];
+    hipLaunchKernelGGL(tree_expand_kernel, dim3(n_seq), dim3(256), 0, st, tb, d, k, L, rows);
 }
 
 // ------------------------------------------------------------------ rerank + emit
 // Keep the n_keep best candidates; order them as candidates are ordered (parents first); node 0 is
 // the root x_t.  pos = t + depth; mask = node and its ancestors; slot = t + node index.
 constexpr int POOL_MAX = 2048;
-__global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int pool_n, int n_keep, int t,
-                                                             const int32_t *__restrict__ tokens_dev,
-                                                             int32_t *__restrict__ slot_out) {
+__global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeBatch tb, int pool_n, int n_keep) {
+    const TreeDev &td = tb.td[blockIdx.x];
+    const int t = tb.t[blockIdx.x];
+    const int32_t *__restrict__ tokens_dev = tb.tokens_dev[blockIdx.x];
+    int32_t *__restrict__ slot_out = tb.slot_out[blockIdx.x];
     __shared__ __attribute__((aligned(16))) float sc[POOL_MAX];
     __shared__ int16_t par[POOL_MAX];                 // candidate -> parent candidate (-1: the root)
     __shared__ int16_t new_idx[POOL_MAX];             // candidate -> node index in the tree, -1 if dropped
@@ -337,11 +351,13 @@ __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeDev td, int poo
     }
 }
 
-void launch_tree_finalize(const TreeDev &td, int k, int L, int n_keep, int t, const int32_t *tokens_dev,
-                          int32_t *slot_out, hipStream_t st) {
+void launch_tree_finalize(const TreeDev *tds, int n_seq, int k, int L, int n_keep, const int *t,
+                          const int32_t *const *tokens_dev, int32_t *const *slot_out, hipStream_t st) {
+    if (n_seq < 1 || n_seq > TREE_BATCH_MAX) return;
     const int pool_n = k + (L - 1) * k * k;
-    hipLaunchKernelGGL(tree_finalize_kernel, dim3(1), dim3(1024), 0, st, td, pool_n, n_keep < pool_n ? n_keep : pool_n,
-                       t, tokens_dev, slot_out);
+    TreeBatch tb{};
+    for (int i = 0; i < n_seq; ++i) { tb.td[i] = tds[i]; tb.t[i] = t[i]; tb.tokens_dev[i] = tokens_dev[i]; tb.slot_out[i] = slot_out[i]; }
+    hipLaunchKernelGGL(tree_finalize_kernel, dim3(n_seq), dim3(1024), 0, st, tb, pool_n, n_keep < pool_n ? n_keep : pool_n);
 }
 
 // ------------------------------------------------------------------ rows of one specialist pass
