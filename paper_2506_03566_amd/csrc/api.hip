@@ -525,6 +525,17 @@ void update_ready(poss_ctx *c) {
     if (c->state == ST_READY && !all) c->state = ST_LOADED;
 }
 
+// Events and pinned host memory of a context (whatever of them exists: a failed poss_load stops half way).
+void release_host(poss_ctx *c) {
+    for (int i = 0; i < 6; ++i)
+        if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+    for (int i = 0; i < 2 * PROFILE_EVENTS; ++i)
+        if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
+    if (c->pinned) (void)hipHostFree(c->pinned);
+    if (c->u_pinned) (void)hipHostFree(c->u_pinned);
+    if (c->result_pinned_all) (void)hipHostFree(c->result_pinned_all);
+}
+
 }  // namespace
 
 // ============================================================================================ C ABI
@@ -565,7 +576,7 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     WeightSlots ws;
     carve(*cfg, a, c, &ws);
 
-    auto bail = [&](int code) { g_load_error[0] = 0; strncpy(g_load_error, c->err, 511); delete c; return code; };
+    auto bail = [&](int code) { g_load_error[0] = 0; strncpy(g_load_error, c->err, 511); release_host(c); delete c; return code; };
 #define LOAD_TRY(call)                                                                    \
     do {                                                                                  \
         hipError_t e_ = (call);                                                           \
@@ -682,11 +693,7 @@ int poss_set_active(poss_ctx *c, int32_t seq, int32_t active) {
 void poss_free(poss_ctx *c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->st);
-    for (int i = 0; i < 6; ++i) (void)hipEventDestroy(c->ev[i]);
-    for (int i = 0; i < 2 * PROFILE_EVENTS; ++i) (void)hipEventDestroy(c->prof_ev[i]);
-    (void)hipHostFree(c->pinned);
-    (void)hipHostFree(c->u_pinned);
-    (void)hipHostFree(c->result_pinned_all);
+    release_host(c);
     delete c;
 }
 
