@@ -15,6 +15,9 @@ Modules
             brute-force path enumeration (section 4.1 "Implementations": width,
             depth, total tokens)
   poss      the round: draft -> verify -> accept/commit; tau and pos-acc (Eq. 3, 4)
+  sampling  verification at a temperature: the target's token drawn from softmax(logits / T) by
+            inverse CDF with a uniform number per position (section 2.1 asks only that the
+            target's distribution is kept)
 
 Pins (tests/test_oracle_*.py): layer parameter count of section 3.3,
 specialist indexing example below Eq. 7, draft-layer counts of appendix D,
@@ -23,5 +26,5 @@ brute-force top-N, perfect-drafter and S-identical-specialists special cases,
 textbook reductions (softmax rows, RoPE relativity, norm invariants).
 Parity unpinned: the specialist used beyond depth S*n (clamped to the last
 one); whether the paper's printed tau counts the bonus token; whether "total
-tokens" counts the root.
+tokens" counts the root; which acceptance rule the paper's temperature-1 runs used.
 """
