@@ -5,7 +5,8 @@ import pytest
 
 from synth import get_config, make_weights, make_prompt
 from synth.gen import to_storage
-from oracle.model import Weights, target_full, head, specialist_pass
+from oracle.model import Weights, target_full, head, specialist_pass, specialist_index, causal_allowed
+from oracle.numerics import log_softmax
 from oracle.greedy import greedy_decode
 from oracle.poss import PossOracle, topk_lowest_id
 from oracle.tree import accept_bruteforce, Tree
@@ -82,6 +83,65 @@ def test_depth_one_uses_target_features_only():
     assert tb.token[:cfg.top_k] == want
     kids = [tree.token[i] for i in range(1, tree.n) if tree.parent[i] == 0]
     assert set(kids) <= set(want)
+
+
+@pytest.mark.parametrize("name", ["c0_tiny_f32", "t_tiny_f32_6x1"])
+def test_a_root_path_of_the_tree_is_the_plain_pair_sequence(name):
+    """Eq. 2 / Eq. 9 on one path, written out without any tree bookkeeping: the committed pairs
+    [x_j ; f_{j-1}] followed by the drafted pairs [token(v_i) ; drafted feature of v_{i-1}] of a
+    root path form an ordinary sequence - consecutive positions, plain causal attention - and the
+    specialist of depth d, applied to that sequence, gives at its last row the distribution the
+    children of v_{d-1} were scored with.  Pins what the batched tree drafting must reproduce with
+    its masks and position ids (a drafted row sits right behind the committed pairs plus its
+    ancestors, and sees nothing else)."""
+    cfg, W = _setup(name)
+    o = PossOracle(W, cfg)
+    o.prefill(make_prompt(cfg, n=19))
+    tree = o.draft_tree()
+    t = o.t
+    deepest = max(range(tree.n), key=lambda i: (tree.depth[i], tree.score[i]))
+    assert tree.depth[deepest] >= 3
+    path = [deepest]
+    while path[-1] != 0:
+        path.append(tree.parent[path[-1]])
+    path.reverse()
+    tok, feat = list(o.tokens[1:t + 1]), list(o.feats[:t])
+    for d, node in enumerate(path[1:], start=1):
+        s = specialist_index(d - 1, cfg.positions_per_specialist, cfg.n_specialists)
+        rows = len(tok)
+        out = specialist_pass(W, cfg, s, tok, np.stack(feat), np.arange(rows), causal_allowed(0, rows)[-1:], [rows - 1])
+        lp = log_softmax(head(W, cfg, out))[0]
+        step = float(tree.score[node]) - float(tree.score[tree.parent[node]])
+        assert abs(step - lp[tree.token[node]]) < 1e-4, (d, step, lp[tree.token[node]])
+        tok.append(tree.token[node])
+        feat.append(out[0])
+
+
+def test_a_drafter_that_passes_the_feature_through_predicts_the_token_it_is_paired_with():
+    """Closed form for the pairing of Eq. 1: the root row is [x_t ; f_{t-1}], and f_{t-1} is the
+    feature the target chose x_t from.  A drafter whose fc keeps only the feature half and whose
+    layer adds nothing hands Head that very feature, so its best guess for the token after x_t is
+    x_t again, its k guesses are the target's top-k at position t-1, and (the drafted feature never
+    changing) every expanded node gets the same k children."""
+    cfg = get_config("c0_tiny_f32")
+    st = make_weights(cfg)
+    d = cfg.d_model
+    for s in range(cfg.n_specialists):
+        fc = np.zeros((d, 2 * d)); fc[:, d:] = np.eye(d)            # the feature half of [x ; f]
+        st[f"spec{s}.fc_w"] = to_storage(fc, cfg.dtype)
+        st[f"spec{s}.fc_b"] = to_storage(np.zeros(d), cfg.dtype)
+        for nm in ("wo", "w_down"):
+            st[f"spec{s}.{nm}"] = to_storage(np.zeros(st[f"spec{s}.{nm}"].shape), cfg.dtype)
+    W = Weights(cfg, st)
+    o = PossOracle(W, cfg)
+    o.prefill(make_prompt(cfg, n=23))
+    o.draft_tree()
+    t, k = o.t, cfg.top_k
+    want = topk_lowest_id(head(W, cfg, o.feats[t - 1][None])[0].astype(np.float32), k).tolist()
+    assert want[0] == o.tokens[t]
+    tb = o.last["builder"]
+    assert tb.token[:k] == want
+    assert all(tb.token[i:i + k] == want for i in range(0, len(tb.token), k))
 
 
 def _perfect_drafter_weights(cfg):
