@@ -5,7 +5,8 @@ import pytest
 
 from synth import get_config, make_weights, make_prompt
 from synth.gen import to_storage
-from oracle.model import Weights, target_full, head, specialist_pass, specialist_index, causal_allowed
+from oracle.model import (Weights, target_full, target_rows, empty_kv, head, specialist_pass, specialist_index,
+                          causal_allowed)
 from oracle.numerics import log_softmax
 from oracle.greedy import greedy_decode
 from oracle.poss import PossOracle, topk_lowest_id
@@ -64,6 +65,13 @@ def test_lossless_with_injected_trees_of_every_accept_length():
         f_full, logits_full = target_full(W, cfg, o.tokens[:-1])
         assert np.allclose(np.stack(o.feats), f_full, rtol=1e-9, atol=1e-11)
         assert np.allclose(logits[path], logits_full[len(prompt):], rtol=1e-9, atol=1e-11)
+        # and the committed keys / values are those of that plain pass (the accepted rows, which are
+        # not the first rows of the tree: node 1 is the decoy)
+        n_c = len(o.tokens) - 1
+        _, kv_full = target_rows(W, cfg, o.tokens[:-1], np.arange(n_c), empty_kv(cfg), causal_allowed(0, n_c))
+        for (k_o, v_o), (k_f, v_f) in zip(o.kv, kv_full):
+            assert k_o.shape == k_f.shape and np.allclose(k_o, k_f, rtol=1e-9, atol=1e-11)
+            assert np.allclose(v_o, v_f, rtol=1e-9, atol=1e-11)
 
 
 def test_depth_one_uses_target_features_only():
