@@ -8,7 +8,8 @@
  *
  * With poss_config.batch = B > 1 a context carries B independent sequences:
  * each has its own caches, tree and token stream, every pass stacks their rows into one set of
- * weight-streaming launches, and the three round calls advance all of them; poss_prefill_seq,
+ * weight-streaming launches (of at most POSS_MAX_ROWS rows: a larger batch runs its passes group by
+ * group), and the three round calls advance all of them; poss_prefill_seq,
  * poss_get_tree_seq, poss_get_commit_seq, poss_get_tokens_seq and poss_set_uniforms_seq address one
  * sequence (the calls without _seq address sequence 0); poss_set_active and poss_reset_seq take a
  * sequence out of the rounds or replace it.  A sequence's tokens are the ones it gets at batch 1.
@@ -74,8 +75,8 @@ typedef struct poss_config {
     int32_t max_seq;                         /* capacity in committed tokens (multiple of kv_page_tokens) */
     int32_t kv_page_tokens;                  /* tokens per KV page: 32, 64 or 128           */
     int32_t kv_page_order;                   /* 0: pages in order; 1: physical pages reversed (layout tests) */
-    int32_t batch;                           /* sequences per round: 0 or 1 = one; up to 8 while batch *
-                                              * (total_tokens + 1) and the widest specialist pass fit 128 rows */
+    int32_t batch;                           /* sequences per round: 0 or 1 = one; up to 8.  A pass stacks the rows of as *
+                                              * many sequences as fit 128 rows and runs group by group beyond that       */
 } poss_config;
 
 /* Weights: DEVICE pointers to row-major [out, in] tensors of `dtype`.

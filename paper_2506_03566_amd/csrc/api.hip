@@ -71,6 +71,8 @@ struct poss_ctx {
     int32_t *page_table;
     size_t cache_bytes_each;
     int B;                             // sequences per round
+    int G;                             // sequences whose rows one pass can stack (a larger batch runs group by group)
+    int rows_all;                      // rows of the batch-wide tree arrays
     std::vector<Seq> seq;
     // activations
     float *h, *part, *logits, *feats, *fhat[2], *topk_scratch, *taps_user;
@@ -145,21 +147,26 @@ const char *check_config(const poss_config &c) {
     if (c.kv_page_order < 0 || c.kv_page_order > 1) return "kv_page_order must be 0 or 1";
     if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return "rms_eps / rope_theta out of range";
     if (c.batch < 0 || c.batch > 8) return "batch must be in 0..8 (0 and 1: one sequence)";
-    if (c.batch > 1) {
-        // every pass stacks the rows of all sequences: the verification pass and the widest specialist
-        // pass (k full rows, the pairs committed by the last round, the frontier rows of the depths
-        // since that specialist last ran) must fit the 128-row launches
-        if (c.batch * (c.total_tokens + 1) > POSS_MAX_ROWS) return "batch * (total_tokens + 1) must not exceed 128 rows";
-        std::vector<int> seen(c.n_specialists, 0);
-        for (int d = 1; d <= c.depth; ++d) {
-            int s = (d - 1) / c.positions_per_specialist;
-            if (s > c.n_specialists - 1) s = c.n_specialists - 1;
-            const int earlier = d >= 2 && d - 2 > seen[s] ? (d - 2 - seen[s]) * c.top_k : 0;
-            if (c.batch * (c.top_k + c.depth + 1 + earlier) > POSS_MAX_ROWS) return "a batched specialist pass would exceed 128 rows";
-            seen[s] = d - 1;
-        }
-    }
     return nullptr;
+}
+
+// Sequences whose rows one pass can stack: the verification pass (total_tokens + 1 rows each) and the
+// widest specialist pass (k full rows, the pairs committed by the last round, the frontier rows of the
+// depths since that specialist last ran) must fit the 128-row launches.  A batch larger than this runs
+// its passes group by group.
+int group_size(const poss_config &c) {
+    int widest = c.total_tokens + 1;
+    std::vector<int> seen(c.n_specialists, 0);
+    for (int d = 1; d <= c.depth; ++d) {
+        int s = (d - 1) / c.positions_per_specialist;
+        if (s > c.n_specialists - 1) s = c.n_specialists - 1;
+        const int earlier = d >= 2 && d - 2 > seen[s] ? (d - 2 - seen[s]) * c.top_k : 0;
+        const int rows = c.top_k + c.depth + 1 + earlier;
+        if (rows > widest) widest = rows;
+        seen[s] = d - 1;
+    }
+    const int g = POSS_MAX_ROWS / widest;
+    return g < 1 ? 1 : g;
 }
 
 size_t esize(const poss_config &c) { return dtype_size(c.dtype); }
@@ -206,6 +213,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     KVCache *kv_dev = a.take_n<KVCache>((size_t)B * c.n_layers);
     // activations
     const int R = MAX_ROWS;
+    const int RA = B * (c.total_tokens + 1) > R ? B * (c.total_tokens + 1) : R;   // tree rows of all sequences (several groups)
     size_t part_floats = 0;
     const int shapes[6][2] = {{qd + 2 * kd, d}, {d, qd}, {gate_up_rows(F), d}, {d, F}, {d, 2 * d}, {V, d}};
     for (int i = 0; i < 5; ++i) {
@@ -219,7 +227,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     float2 *cs = a.take_n<float2>((size_t)R * (c.head_dim / 2));
     float *part = a.take_n<float>(part_floats);
     float *logits = a.take_n<float>((size_t)R * gemm_npad(V));
-    float *feats = a.take_n<float>((size_t)R * d);
+    float *feats = a.take_n<float>((size_t)RA * d);
     float *fhat0 = a.take_n<float>((size_t)QR * d), *fhat1 = a.take_n<float>((size_t)QR * d);
     size_t scr_floats = topk_scratch_floats(QR, V);
     if (argmax_scratch_floats(R, V) > scr_floats) scr_floats = argmax_scratch_floats(R, V);
@@ -235,12 +243,12 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     int32_t *row_pos = a.take_n<int32_t>(R), *row_slot = a.take_n<int32_t>(R);
     uint64_t *row_mask = a.take_n<uint64_t>((size_t)R * MASK_WORDS);
     // rows of the verification pass (sequence b owns rows [b * (total_tokens + 1), ...)) and of the top-k
-    int32_t *token_all = a.take_n<int32_t>(R), *pos_all = a.take_n<int32_t>(R), *slot_all = a.take_n<int32_t>(R);
-    int32_t *depth_all = a.take_n<int32_t>(R), *parent_all = a.take_n<int32_t>(R);
-    uint64_t *mask_all = a.take_n<uint64_t>((size_t)R * MASK_WORDS);
-    float *score_all = a.take_n<float>(R);
+    int32_t *token_all = a.take_n<int32_t>(RA), *pos_all = a.take_n<int32_t>(RA), *slot_all = a.take_n<int32_t>(RA);
+    int32_t *depth_all = a.take_n<int32_t>(RA), *parent_all = a.take_n<int32_t>(RA);
+    uint64_t *mask_all = a.take_n<uint64_t>((size_t)RA * MASK_WORDS);
+    float *score_all = a.take_n<float>(RA);
     int32_t *topk_id_all = a.take_n<int32_t>((size_t)QR * 16); float *topk_logp_all = a.take_n<float>((size_t)QR * 16);
-    int32_t *argmax_dev = a.take_n<int32_t>(R);
+    int32_t *argmax_dev = a.take_n<int32_t>(RA);
     double *inv_freq = a.take_n<double>(c.head_dim / 2);
     float *u_dev = a.take_n<float>((size_t)B * (POSS_MAX_DEPTH + 1));
     // per sequence: tree state, token stream, feature stash, stored frontier rows
@@ -272,7 +280,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
             sq.spec_kv.push_back(KVCache{kvp[base + 2 * (c.n_layers + s2)], kvp[base + 2 * (c.n_layers + s2) + 1], pt, shift});
     }
     if (ctx) {
-        ctx->B = B;
+        ctx->B = B; ctx->G = group_size(c); ctx->rows_all = RA;
         ctx->cache_slots = slots; ctx->n_pages = pages; ctx->page_table = pt; ctx->cache_bytes_each = cache_each;
         ctx->seq = seqs;
         ctx->cs = cs;
@@ -360,7 +368,7 @@ void run_layer(poss_ctx *c, const LayerW &w, const std::vector<Seg> &segs, int r
 // Target pass over `rows` rows (all of them full rows; segs says which belong to which sequence)
 // whose tokens / metadata are on the device.  Leaves features in c->feats and
 // T(rmsnorm_final(features)) in c->u.
-void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowMeta &rm, std::vector<Seg> segs) {
+void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowMeta &rm, std::vector<Seg> segs, float *feats_out) {
     const ModelDims &md = c->md;
     launch_embed_norm(md, c->embed, tokens_dev, rows, c->layers[0].attn_norm, c->h, c->u, rm.pos, c->inv_freq, c->cs, c->st);
     const int nl = c->cfg.n_layers;
@@ -369,7 +377,7 @@ void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowM
             launch_copy_rows_f32(c->h, md.d, c->taps_user + (size_t)l * rows * md.d, md.d, rows, md.d, c->st);
         const void *next_gain = l + 1 < nl ? c->layers[l + 1].attn_norm : c->final_norm;
         for (Seg &sg : segs) sg.kv = &c->seq[sg.b].target_kv[l];
-        run_layer(c, c->layers[l], segs, rows, rows, rm, next_gain, l + 1 == nl ? c->feats : nullptr);
+        run_layer(c, c->layers[l], segs, rows, rows, rm, next_gain, l + 1 == nl ? feats_out : nullptr);
     }
     if (c->taps_user)
         launch_copy_rows_f32(c->h, md.d, c->taps_user + (size_t)nl * rows * md.d, md.d, rows, md.d, c->st);
@@ -700,7 +708,7 @@ void poss_free(poss_ctx *c) {
 const char *poss_last_error(poss_ctx *c) { return c ? c->err : g_load_error; }
 
 static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, const int *seq_ids, int n_seq, const int *row0,
-                         const int *n_rows);
+                         const int *n_rows, int base = 0);
 
 int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
     if (!c) return POSS_E_INVALID_ARG;
@@ -719,7 +727,7 @@ int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_
         HIP_TRY(c, hipMemcpyAsync(sq.tokens_dev + c0, stage, rows * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
         hipLaunchKernelGGL(causal_meta_kernel, dim3(1), dim3(MAX_ROWS), 0, c->st, rows, c0, c->row_pos, c->row_slot, c->row_mask);
         RowMeta rm{c->row_pos, c->row_slot, c->row_mask};
-        target_forward(c, rows, sq.tokens_dev + c0, rm, {Seg{seq, nullptr, 0, rows, rows, 0, c0, rows}});
+        target_forward(c, rows, sq.tokens_dev + c0, rm, {Seg{seq, nullptr, 0, rows, rows, 0, c0, rows}}, c->feats);
         stash_rows(c, sq, rows, c0);
         if (c0 + rows == n_prompt) {
             // Head on the last row only: its normed activations sit at row rows-1 of c->u
@@ -753,19 +761,20 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
 
 // The token the target chooses after each of `rows` rows of c->logits: the argmax, or at temperature > 0 a
 // draw by inverse CDF with the uniform number of the row's depth (depth == nullptr: all rows use u[0]).
-// Sequence seq_ids[i] owns rows [row0[i], row0[i] + n_rows[i]) and has its own numbers.
+// Sequence seq_ids[i] owns rows [row0[i], row0[i] + n_rows[i]) of the logits and has its own numbers; the
+// rows' depths and results sit `base` rows further on in the batch-wide arrays (the rows of earlier groups).
 static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, const int *seq_ids, int n_seq, const int *row0,
-                         const int *n_rows) {
+                         const int *n_rows, int base) {
     if (c->temperature > 0.f) {
         const int nu = POSS_MAX_DEPTH + 1;
         HIP_TRY(c, hipMemcpyAsync(c->u_dev, c->u_pinned, (size_t)c->B * nu * sizeof(float), hipMemcpyHostToDevice, c->st));
         for (int i = 0; i < n_seq; ++i)
             if (!launch_sample(c->logits + (size_t)row0[i] * ld, ld, n_rows[i], c->cfg.vocab, c->temperature,
-                               c->u_dev + (size_t)seq_ids[i] * nu, depth ? depth + row0[i] : nullptr, c->topk_scratch,
-                               c->argmax_dev + row0[i], c->st))
+                               c->u_dev + (size_t)seq_ids[i] * nu, depth ? depth + base + row0[i] : nullptr, c->topk_scratch,
+                               c->argmax_dev + base + row0[i], c->st))
                 return fail(c, POSS_E_INVALID_ARG, "sampling: vocabulary too large for the sampler");
     } else {
-        launch_argmax(c->logits, ld, rows, c->cfg.vocab, c->topk_scratch, c->argmax_dev, c->st);
+        launch_argmax(c->logits, ld, rows, c->cfg.vocab, c->topk_scratch, c->argmax_dev + base, c->st);
     }
     return POSS_OK;
 }
@@ -791,17 +800,16 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
     if (c->state != ST_READY) return fail(c, POSS_E_BAD_STATE, "poss_draft_tree: needs a prefilled context with no pending verification");
     const poss_config &cf = c->cfg;
     const int k = cf.top_k, L = cf.depth;
-    const std::vector<int> act = active_seqs(c);
-    const int B = (int)act.size();                         // sequences in this round
-    for (int b : act) {
+    const std::vector<int> all = active_seqs(c);
+    for (int b : all) {
         const int t = c->seq[b].t;
         if (t + cf.total_tokens + 1 > c->cache_slots || t + L + 1 > cf.max_seq)
             return fail(c, POSS_E_CAPACITY, "poss_draft_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
     }
     if (c->ev_pending[0]) { int rc = sync_and_harvest(c); if (rc) return rc; }   // a re-draft: keep the first one's time
     (void)hipEventRecord(c->ev[0], c->st);
-    for (int i = 0; i < B; ++i) {
-        const int b = act[i];
+    for (int i = 0; i < (int)all.size(); ++i) {
+        const int b = all[i];
         Seq &sq = c->seq[b];
         point_tree(c, sq, i * (cf.total_tokens + 1));
         for (int s = 0; s < cf.n_specialists; ++s) {
@@ -809,6 +817,10 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
             if (sq.t - 1 - sq.spec_len[s] > L) spec_catchup(c, b, s, sq.t - 1);      // only after caller-supplied trees
         }
     }
+    // the sequences draft in groups whose stacked rows fit the launches (one group unless the batch is large)
+    for (int g0 = 0; g0 < (int)all.size(); g0 += c->G) {
+    const std::vector<int> act(all.begin() + g0, all.begin() + (g0 + c->G < (int)all.size() ? g0 + c->G : (int)all.size()));
+    const int B = (int)act.size();                         // sequences in this group
     for (int d = 1; d <= L; ++d) {
         int s = (d - 1) / cf.positions_per_specialist;
         if (s > cf.n_specialists - 1) s = cf.n_specialists - 1;
@@ -871,11 +883,12 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
         }
         launch_tree_finalize(tds, B, k, L, cf.total_tokens, ts, toks, slots, c->st);
     }
+    }   // groups
     (void)hipEventRecord(c->ev[1], c->st);
     c->ev_pending[0] = true;
     HIP_TRY(c, hipGetLastError());
     if (!out) return POSS_OK;                    // nothing for the host: the work stays queued
-    int rc = copy_tree_out(c, c->seq[act[0]], out);             // the first active sequence's
+    int rc = copy_tree_out(c, c->seq[all[0]], out);             // the first active sequence's
     if (rc) return rc;
     return sync_and_harvest(c);
 }
@@ -925,7 +938,7 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     const poss_config &cf = c->cfg;
     const std::vector<int> act = active_seqs(c);
     const int B = (int)act.size();                         // sequences in this round; i-th active sequence = act[i]
-    int row0[8], n_rows[8], rows = 0;
+    int row0[8], n_rows[8], rows = 0;                      // a sequence's rows in the batch-wide arrays
     if (tree) {                                            // one tree per sequence: tree[0 .. batch-1], inactive ones ignored
         for (int i = 0; i < B; ++i) {
             const poss_tree &tr = tree[act[i]];
@@ -961,6 +974,7 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     (void)hipEventRecord(c->ev[2], c->st);
     if (tree) {
         int32_t *stage = static_cast<int32_t *>(c->pinned);      // [tokens | parents | node counts]
+        const int RA = c->rows_all;
         for (int i = 0; i < B; ++i) {
             const int b = act[i];
             Seq &sq = c->seq[b];
@@ -968,26 +982,39 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
             point_tree(c, sq, row0[i]);
             memcpy(stage + row0[i], tree[b].token, n * sizeof(int32_t));
             stage[row0[i]] = sq.tokens[t];                        // the root is always x_t
-            memcpy(stage + MAX_ROWS + row0[i], tree[b].parent, n * sizeof(int32_t));
-            stage[2 * MAX_ROWS + i] = n;
+            memcpy(stage + RA + row0[i], tree[b].parent, n * sizeof(int32_t));
+            stage[2 * RA + i] = n;
             HIP_TRY(c, hipMemcpyAsync(sq.td.token, stage + row0[i], n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-            HIP_TRY(c, hipMemcpyAsync(sq.td.parent, stage + MAX_ROWS + row0[i], n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-            HIP_TRY(c, hipMemcpyAsync(sq.td.n_nodes, stage + 2 * MAX_ROWS + i, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+            HIP_TRY(c, hipMemcpyAsync(sq.td.parent, stage + RA + row0[i], n * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
+            HIP_TRY(c, hipMemcpyAsync(sq.td.n_nodes, stage + 2 * RA + i, sizeof(int32_t), hipMemcpyHostToDevice, c->st));
             launch_tree_upload_finish(n, t, sq.td.token, sq.td.parent, sq.td.depth, sq.td.pos, sq.tree_slot, sq.td.mask, c->st);
             sq.tree_n = n; sq.tree_ready = 1;
         }
     }                                     // (a drafted tree's slots were written when it was finalized)
-    // the trees' rows are adjacent slices of the batch-wide arrays: one pass over all of them
-    RowMeta rm{c->tree_pos_all, c->tree_slot_all, c->tree_mask_all};
-    std::vector<Seg> segs;
-    for (int i = 0; i < B; ++i) segs.push_back(Seg{act[i], nullptr, row0[i], n_rows[i], rows, 0, c->seq[act[i]].t, n_rows[i]});
-    target_forward(c, rows, c->tree_token_all, rm, segs);
-    GemmShape g = run_head(c, rows);
-    { int rc = choose_tokens(c, g.Npad, rows, c->tree_depth_all, act.data(), B, row0, n_rows); if (rc) return rc; }
+    // The trees' rows are adjacent slices of the batch-wide arrays: one pass over all of them, or, when they
+    // are more than a launch carries, one pass per group of sequences (the rows of a group are adjacent too;
+    // as many sequences as fit: eight root-only trees, vanilla decoding of a batch, share one pass).
+    const int n = n_rows[0];                               // host and device outputs: the first active sequence's rows
+    for (int i0 = 0; i0 < B;) {
+        int i1 = i0, grows = 0;
+        while (i1 < B && grows + n_rows[i1] <= MAX_ROWS) grows += n_rows[i1++];
+        const int base = row0[i0];
+        RowMeta rm{c->tree_pos_all + base, c->tree_slot_all + base, c->tree_mask_all + (size_t)base * MASK_WORDS};
+        std::vector<Seg> segs;
+        int rel0[8];
+        for (int i = i0; i < i1; ++i) {
+            rel0[i - i0] = row0[i] - base;
+            segs.push_back(Seg{act[i], nullptr, row0[i] - base, n_rows[i], grows, 0, c->seq[act[i]].t, n_rows[i]});
+        }
+        target_forward(c, grows, c->tree_token_all + base, rm, segs, c->feats + (size_t)base * cf.d_model);
+        GemmShape g = run_head(c, grows);
+        { int rc = choose_tokens(c, g.Npad, grows, c->tree_depth_all, act.data() + i0, i1 - i0, rel0, n_rows + i0, base); if (rc) return rc; }
+        if (i0 == 0 && logits_out)                         // before the next group overwrites the logits
+            launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
+        i0 = i1;
+    }
     (void)hipEventRecord(c->ev[3], c->st);
     c->ev_pending[1] = true;
-    const int n = n_rows[0];                               // host and device outputs: the first active sequence's rows
-    if (logits_out) launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
     if (feat_out) launch_copy_rows_f32(c->feats, cf.d_model, static_cast<float *>(feat_out), cf.d_model, n, cf.d_model, c->st);
     HIP_TRY(c, hipGetLastError());
     c->state = ST_VERIFIED;

@@ -49,6 +49,8 @@ def _same_tree(a, b):
     ("t_tiny_f32_6x1", 2, (70, 33), True, 3),            # six specialists, one position each
     ("t_mid_bf16", 2, (150, 97), False, 4),              # 16-bit storage, 2 x 61 rows in the verification pass
     ("t_mid_f16", 1, (131,), False, 2),                  # batch field set to 1: the single-sequence path
+    ("c0_tiny_f32", 7, (16, 23, 40, 12, 31, 18, 27), True, 3),   # more rows than a launch carries: groups of 4 and 3 sequences
+    ("t_mid_bf16", 3, (150, 97, 120), False, 3),         # 3 x 61 rows: a group of two sequences and one of one
 ])
 def test_batched_rounds_equal_sequences_alone(name, batch, lengths, perfect, n_rounds):
     cfg = get_config(name)
@@ -122,34 +124,34 @@ def test_batched_context_refuses_what_it_cannot_do():
     with pytest.raises(P.PossError):
         ctx.draft_tree()
     pair.close()
-    # configurations whose stacked rows do not fit one launch are rejected at load
-    for over in ({"batch": 9}, {"batch": 6}):                          # 6 x 25 verification rows > 128
-        with pytest.raises(P.PossError):
-            P.Poss(cfg, pair.dev_weights, **over)
+    # more than eight sequences are rejected at load (six, whose stacked rows exceed one launch, run in groups)
+    with pytest.raises(P.PossError):
+        P.Poss(cfg, pair.dev_weights, batch=9)
 
 
-def test_full_size_batch_of_two_equals_each_sequence_alone():
+@pytest.mark.parametrize("lengths", [(512, 300), (512, 300, 411)])
+def test_full_size_batch_equals_each_sequence_alone(lengths):
     """The benchmark shape with two sequences per round (2 x 61 rows in the verification pass, the
-    128-row GEMM instantiations): trees, accepted paths and tokens of each sequence are the ones a
-    context of its own produces."""
+    128-row GEMM instantiations) and with three (a group of two and a group of one): trees, accepted
+    paths and tokens of each sequence are the ones a context of its own produces."""
     import torch
     from synth.gpu import make_weights_on_device
     cfg = get_config("c1_llama3_8b_3x2")
     _say("generating weights of c1_llama3_8b_3x2")
     dev = make_weights_on_device(cfg)
-    prompts = _prompts(cfg, (cfg.n_prompt, 300))
-    n_rounds = 3
-    ctx = P.Poss(cfg, dev, batch=2)
+    prompts = _prompts(cfg, lengths)
+    n_rounds, B = 3, len(lengths)
+    ctx = P.Poss(cfg, dev, batch=B)
     for b, p in enumerate(prompts):
         ctx.prefill(p, seq=b)
     got = []
     for rnd in range(n_rounds):
         ctx.draft_tree(want_tree=False)
-        trees = [ctx.get_tree(b).as_dict() for b in range(2)]
+        trees = [ctx.get_tree(b).as_dict() for b in range(B)]
         ctx.verify_tree(want_argmax=False)
         ctx.accept_and_commit()
-        got.append([(trees[b],) + ctx.commit_result(b) for b in range(2)])
-    tokens = [ctx.tokens(b) for b in range(2)]
+        got.append([(trees[b],) + ctx.commit_result(b) for b in range(B)])
+    tokens = [ctx.tokens(b) for b in range(B)]
     ctx.close()
     torch.cuda.empty_cache()
     for b, p in enumerate(prompts):
@@ -167,7 +169,8 @@ def test_full_size_batch_of_two_equals_each_sequence_alone():
         _say(f"  sequence {b}: {n_rounds} rounds identical")
 
 
-@pytest.mark.parametrize("name,batch,lengths", [("c0_tiny_f32", 3, (16, 23, 40)), ("t_mid_bf16", 2, (150, 97))])
+@pytest.mark.parametrize("name,batch,lengths", [("c0_tiny_f32", 3, (16, 23, 40)), ("t_mid_bf16", 2, (150, 97)),
+                                                ("c0_tiny_f32", 6, (16, 23, 40, 12, 31, 18))])               # groups of 4 and 2
 def test_batched_sampling_equals_sequences_alone(name, batch, lengths):
     """Verification at a temperature with a set of uniform numbers per sequence: every sequence of the
     batch commits the tokens it commits alone with the same numbers (and, in float32 storage, the
@@ -215,7 +218,8 @@ def test_batched_sampling_equals_sequences_alone(name, batch, lengths):
     pair.close()
 
 
-@pytest.mark.parametrize("name,batch,lengths", [("c0_tiny_f32", 3, (16, 23, 40)), ("t_mid_bf16", 2, (150, 97))])
+@pytest.mark.parametrize("name,batch,lengths", [("c0_tiny_f32", 3, (16, 23, 40)), ("t_mid_bf16", 2, (150, 97)),
+                                                ("c0_tiny_f32", 8, (16, 23, 40, 12, 31, 18, 27, 21))])      # two groups
 def test_batched_caller_trees_equal_sequences_alone(name, batch, lengths):
     """Trees handed in by the caller, one per sequence and of different sizes (root-only rounds are
     vanilla decoding): the batch commits what each sequence commits alone, and a draft after such

@@ -47,17 +47,15 @@ def test_workspace_bytes_and_config_validation():
     for over in bad:
         assert lib.poss_workspace_bytes(ctypes.byref(P.make_config(base.with_(**over)))) == 0, over
     assert lib.poss_workspace_bytes(None) == 0
-    # several sequences per round: the stacked rows of every pass have to fit the 128-row launches
+    # several sequences per round: up to eight (passes whose stacked rows exceed a launch run in groups),
+    # every sequence with caches and tree state of its own
     def ws(cfg, batch):
         return lib.poss_workspace_bytes(ctypes.byref(P.make_config(cfg, batch=batch)))
     c1 = get_config("c1_llama3_8b_3x2")
     assert ws(c1, 0) == ws(c1, 1) == big                    # 0 and 1 both mean one sequence
-    assert ws(c1, 2) > big and ws(c1, 3) == 0               # 2 x 61 verification rows fit, 3 x 61 do not
-    assert ws(base, 5) > 0 and ws(base, 6) == 0             # 5 x 25 rows fit, 6 x 25 do not
+    assert big < ws(c1, 2) < ws(c1, 3) < ws(c1, 8)
+    assert 0 < ws(base, 5) < ws(base, 6)
     assert ws(base, -1) == 0 and ws(base, 9) == 0
-    # six specialists of one position: the last one catches up on four earlier frontiers (4 + 7 + 16 rows)
-    t6 = get_config("t_tiny_f32_6x1")
-    assert ws(t6, 4) > 0 and ws(t6, 5) == 0
 
 
 def test_null_arguments_are_rejected_before_any_gpu_work():
