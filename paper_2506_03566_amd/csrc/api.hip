@@ -71,7 +71,6 @@ struct poss_ctx {
     int32_t *page_table;
     size_t cache_bytes_each;
     int B;                             // sequences per round
-    int G;                             // sequences whose rows one pass can stack (a larger batch runs group by group)
     int rows_all;                      // rows of the batch-wide tree arrays
     std::vector<Seq> seq;
     // activations
@@ -148,25 +147,6 @@ const char *check_config(const poss_config &c) {
     if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return "rms_eps / rope_theta out of range";
     if (c.batch < 0 || c.batch > 8) return "batch must be in 0..8 (0 and 1: one sequence)";
     return nullptr;
-}
-
-// Sequences whose rows one pass can stack: the verification pass (total_tokens + 1 rows each) and the
-// widest specialist pass (k full rows, the pairs committed by the last round, the frontier rows of the
-// depths since that specialist last ran) must fit the 128-row launches.  A batch larger than this runs
-// its passes group by group.
-int group_size(const poss_config &c) {
-    int widest = c.total_tokens + 1;
-    std::vector<int> seen(c.n_specialists, 0);
-    for (int d = 1; d <= c.depth; ++d) {
-        int s = (d - 1) / c.positions_per_specialist;
-        if (s > c.n_specialists - 1) s = c.n_specialists - 1;
-        const int earlier = d >= 2 && d - 2 > seen[s] ? (d - 2 - seen[s]) * c.top_k : 0;
-        const int rows = c.top_k + c.depth + 1 + earlier;
-        if (rows > widest) widest = rows;
-        seen[s] = d - 1;
-    }
-    const int g = POSS_MAX_ROWS / widest;
-    return g < 1 ? 1 : g;
 }
 
 size_t esize(const poss_config &c) { return dtype_size(c.dtype); }
@@ -280,7 +260,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
             sq.spec_kv.push_back(KVCache{kvp[base + 2 * (c.n_layers + s2)], kvp[base + 2 * (c.n_layers + s2) + 1], pt, shift});
     }
     if (ctx) {
-        ctx->B = B; ctx->G = group_size(c); ctx->rows_all = RA;
+        ctx->B = B; ctx->rows_all = RA;
         ctx->cache_slots = slots; ctx->n_pages = pages; ctx->page_table = pt; ctx->cache_bytes_each = cache_each;
         ctx->seq = seqs;
         ctx->cs = cs;
@@ -817,15 +797,12 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
             if (sq.t - 1 - sq.spec_len[s] > L) spec_catchup(c, b, s, sq.t - 1);      // only after caller-supplied trees
         }
     }
-    // the sequences draft in groups whose stacked rows fit the launches (one group unless the batch is large)
-    for (int g0 = 0; g0 < (int)all.size(); g0 += c->G) {
-    const std::vector<int> act(all.begin() + g0, all.begin() + (g0 + c->G < (int)all.size() ? g0 + c->G : (int)all.size()));
-    const int B = (int)act.size();                         // sequences in this group
+    const std::vector<int> &act = all;
+    const int B = (int)act.size();                         // sequences in this round
     for (int d = 1; d <= L; ++d) {
         int s = (d - 1) / cf.positions_per_specialist;
         if (s > cf.n_specialists - 1) s = cf.n_specialists - 1;
         std::vector<SeqPlan> plans(B);
-        int rows_all = 0;
         const int rows_q_each = d == 1 ? 1 : k;
         for (int i = 0; i < B; ++i) {
             const int b = act[i];
@@ -851,23 +828,34 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
                     for (int r = 0; r < k; ++r) { plan.kind[n] = 1; plan.idx[n] = (dl - 1) * k + r; plan.slot[n] = t + (dl - 1) * k + r; plan.pos[n] = t - 1 + dl; ++n; }
             }
             plan.n_rows = n;
-            rows_all += n;
+            if (n > MAX_ROWS) return fail(c, POSS_E_CAPACITY, "poss_draft_tree: a pass of %d rows for one sequence (limit %d)", n, MAX_ROWS);
         }
-        if (rows_all > MAX_ROWS) return fail(c, POSS_E_CAPACITY, "poss_draft_tree: a pass of %d rows (limit %d)", rows_all, MAX_ROWS);
-        std::vector<int> q0;
-        spec_pass(c, s, plans, d - 1, c->fhat[(d - 1) & 1], d - 1 == 1 ? 1 : k, c->fhat[d & 1], &q0);
-        const int rows_q = B * rows_q_each;
-        GemmShape g = run_head(c, rows_q);
-        launch_topk_logsoftmax(c->logits, g.Npad, rows_q, cf.vocab, k, c->topk_scratch, c->topk_id_all, c->topk_logp_all, c->st);
-        TreeDev tds[8];
-        for (int i = 0; i < B; ++i) {
-            Seq &sq = c->seq[act[i]];
-            tds[i] = sq.td;                                  // with this sequence's rows of the top-k
-            tds[i].topk_id = c->topk_id_all + (size_t)q0[i] * k; tds[i].topk_logp = c->topk_logp_all + (size_t)q0[i] * k;
-            sq.spec_len[s] = sq.t;
-            sq.spec_tmp_depth[s] = d - 1;
+        // One pass over the rows of as many sequences as a launch carries (all of them unless the batch is
+        // large: then group by group, each depth by the rows it brings).  The drafted features of the
+        // frontier rows sit at the sequence's place in the batch (i * rows_q_each), whatever the grouping.
+        const int prev_each = d - 1 == 1 ? 1 : k;
+        for (int i0 = 0; i0 < B;) {
+            int i1 = i0, grows = 0;
+            while (i1 < B && grows + plans[i1].plan.n_rows <= MAX_ROWS) grows += plans[i1++].plan.n_rows;
+            std::vector<SeqPlan> gp(plans.begin() + i0, plans.begin() + i1);
+            const int nb = i1 - i0;
+            std::vector<int> q0;
+            spec_pass(c, s, gp, d - 1, c->fhat[(d - 1) & 1] + (size_t)i0 * prev_each * c->md.d, prev_each,
+                      c->fhat[d & 1] + (size_t)i0 * rows_q_each * c->md.d, &q0);
+            const int rows_q = nb * rows_q_each;
+            GemmShape g = run_head(c, rows_q);
+            launch_topk_logsoftmax(c->logits, g.Npad, rows_q, cf.vocab, k, c->topk_scratch, c->topk_id_all, c->topk_logp_all, c->st);
+            TreeDev tds[8];
+            for (int i = 0; i < nb; ++i) {
+                Seq &sq = c->seq[act[i0 + i]];
+                tds[i] = sq.td;                              // with this sequence's rows of the top-k
+                tds[i].topk_id = c->topk_id_all + (size_t)q0[i] * k; tds[i].topk_logp = c->topk_logp_all + (size_t)q0[i] * k;
+                sq.spec_len[s] = sq.t;
+                sq.spec_tmp_depth[s] = d - 1;
+            }
+            launch_tree_expand(tds, nb, d, k, L, rows_q_each, c->st);   // one launch, a workgroup per sequence
+            i0 = i1;
         }
-        launch_tree_expand(tds, B, d, k, L, rows_q_each, c->st);        // one launch, a workgroup per sequence
     }
     const int pool = k + (L - 1) * k * k;
     {
@@ -883,7 +871,6 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
         }
         launch_tree_finalize(tds, B, k, L, cf.total_tokens, ts, toks, slots, c->st);
     }
-    }   // groups
     (void)hipEventRecord(c->ev[1], c->st);
     c->ev_pending[0] = true;
     HIP_TRY(c, hipGetLastError());
