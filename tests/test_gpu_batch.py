@@ -334,3 +334,28 @@ def test_rounds_go_on_without_a_sequence_that_was_set_aside():
     path, m, toks = ctx.accept_and_commit()               # outputs: the first active sequence, here sequence 1
     assert (path, m, toks) == ctx.commit_result(1)
     pair.close()
+
+
+def test_a_sequence_set_aside_in_a_batch_that_runs_in_groups():
+    """Six sequences whose verification rows need two passes (6 x 25 > 128): one of the first group is
+    set aside after two rounds, so the groups are made up differently from then on; every sequence
+    still commits what it commits alone."""
+    name, batch = "c0_tiny_f32", 6
+    cfg = get_config(name)
+    pair = Pair(name, storage=_perfect_drafter_storage(cfg), lib_over={"batch": batch})
+    ctx = pair.ctx
+    prompts = _prompts(cfg, (16, 23, 40, 12, 31, 18))
+    n_rounds = [5, 2, 5, 5, 5, 5]
+    alone = [_rounds_alone(pair, p, n) for p, n in zip(prompts, n_rounds)]
+    for b, p in enumerate(prompts):
+        ctx.prefill(p, seq=b)
+    for rnd in range(5):
+        if rnd == 2:
+            ctx.set_active(1, False)
+        ctx.draft_tree(want_tree=False)
+        ctx.verify_tree(want_argmax=False)
+        ctx.accept_and_commit()
+    for b in range(batch):
+        assert ctx.tokens(b) == alone[b][2], f"sequence {b}"
+    assert ctx.stats().rounds == 6 * 2 + 5 * 3
+    pair.close()
