@@ -243,6 +243,25 @@ int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_
                     int32_t K, int32_t target_workgroups, void *scratch, void *hip_stream,
                     int32_t repeats, float *ms_per_launch_out);
 
+/* ---- for callers that cannot allocate ------------------------------------------------------ */
+
+/* poss_debug_gemm for callers that may not allocate device memory or hand over a scratch buffer:
+ * code under HIP graph capture, serving loops and harnesses that forbid hipMalloc.  Same kernels,
+ * same result (Y[M, N] DEVICE float32 = X[M, K] . W[N, K]^T, X and W DEVICE row-major of `dtype`,
+ * M <= POSS_MAX_ROWS), but the repacked weights and the split-K partial planes live in a
+ * POSS_GEMM_STATIC_BYTES array inside the library's device image (each GPU the library runs on holds
+ * its own copy until the process ends).  The call allocates nothing, creates no events and does
+ * not wait: it enqueues three kernels on hip_stream (NULL = default stream) and returns; Y is valid
+ * once the stream has been waited for.  Shapes whose packed matrix
+ * (N rounded up to 128) x (K rounded up to 256) x sizeof(dtype) plus planes
+ * splits x 128 x (N rounded up to 128) x 4 exceed the array are refused with POSS_E_CAPACITY and
+ * nothing is launched.  Every call on a GPU uses that GPU's one array, on whatever stream: calls
+ * that overlap on one GPU race, the caller serialises them.  Nothing in the array has to start at
+ * zero; a call overwrites all of it that it reads. */
+#define POSS_GEMM_STATIC_BYTES (32u << 20)
+int poss_gemm_static(int32_t dtype, const void *x, const void *w, void *y, int32_t M, int32_t N,
+                     int32_t K, int32_t target_workgroups, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

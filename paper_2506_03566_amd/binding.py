@@ -19,7 +19,7 @@ EXPORTS = ["poss_workspace_bytes", "poss_load", "poss_reset", "poss_prefill", "p
            "poss_prefill_seq", "poss_get_tree_seq", "poss_get_commit_seq", "poss_get_tokens_seq", "poss_set_uniforms_seq", "poss_reset_seq", "poss_set_active",
            "poss_last_error", "poss_free", "poss_profile_gemm", "poss_gemm_profile", "poss_set_tuning", "poss_set_sampling",
            "poss_debug_build_tree", "poss_debug_set_taps", "poss_debug_read_kv",
-           "poss_debug_gemm_scratch_bytes", "poss_debug_gemm"]
+           "poss_debug_gemm_scratch_bytes", "poss_debug_gemm", "poss_gemm_static"]
 
 c_i32, c_f32, c_vp = ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
 
@@ -97,6 +97,7 @@ def load_library():
     lib.poss_debug_gemm_scratch_bytes.restype = ctypes.c_size_t
     lib.poss_debug_gemm_scratch_bytes.argtypes = [c_i32, c_i32, c_i32, c_i32]
     lib.poss_debug_gemm.argtypes = [c_i32, c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_vp, c_i32, P(c_f32)]
+    lib.poss_gemm_static.argtypes = [c_i32, c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp]
     _lib = lib
     return lib
 
@@ -331,3 +332,18 @@ def debug_gemm(dtype, x, w, target_workgroups=0, repeats=1, stream=None):
     if rc != POSS_OK:
         raise PossError(rc, lib.poss_last_error(None).decode())
     return y, float(ms.value)
+
+
+GEMM_STATIC_BYTES = 32 << 20
+
+
+def gemm_static(dtype, x, w, y, target_workgroups=0, stream=None):
+    """Y = X W^T with the library's own static scratch array: allocates nothing, enqueues and returns.
+    x [M,K], w [N,K] torch GPU tensors of `dtype`; y [M,N] float32 GPU tensor the caller allocated."""
+    lib = load_library()
+    M, K = x.shape
+    N = w.shape[0]
+    rc = lib.poss_gemm_static(dtype, c_vp(x.data_ptr()), c_vp(w.data_ptr()), c_vp(y.data_ptr()), M, N, K,
+                              target_workgroups, c_vp(stream.cuda_stream) if stream is not None else c_vp(0))
+    if rc != POSS_OK:
+        raise PossError(rc, lib.poss_last_error(None).decode())

@@ -10,6 +10,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1222,3 +1223,65 @@ int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_
 }
 
 }  // extern "C"
+
+// ---- the same GEMM path for callers that cannot allocate device memory --------------------------
+// Packed weights and split-K planes live in a file-scope device array instead of a caller's buffer.
+// In host code the array's name is only a handle: its device address is looked up once per GPU
+// (hipGetSymbolAddress, with that GPU current) and that address is what kernels are given.
+static __device__ __align__(256) unsigned char scratch[POSS_GEMM_STATIC_BYTES];
+
+namespace {
+constexpr int STATIC_MAX_DEVICES = 64;
+void *g_scratch_ptr[STATIC_MAX_DEVICES];     // device address of `scratch` on each GPU, nullptr until looked up
+std::mutex g_scratch_mutex;
+
+// The address of the current GPU's copy of `scratch`; nullptr (and a message) on failure.
+void *static_scratch_address() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) {
+        fail(nullptr, POSS_E_HIP, "poss_gemm_static: no current device (or device index above %d)", STATIC_MAX_DEVICES - 1);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            fail(nullptr, POSS_E_HIP, "poss_gemm_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int poss_gemm_static(int32_t dtype, const void *x, const void *w, void *y, int32_t M, int32_t N, int32_t K,
+                                int32_t target_workgroups, void *hip_stream) {
+    if (!x || !w || !y) return fail(nullptr, POSS_E_INVALID_ARG, "poss_gemm_static: null argument");
+    if (dtype < 0 || dtype > 2 || M < 1 || M > MAX_ROWS || N < 1 || K < 1)
+        return fail(nullptr, POSS_E_INVALID_ARG, "poss_gemm_static: bad shape");
+    if (dtype != DT_F32 && (K % 8)) return fail(nullptr, POSS_E_INVALID_ARG, "poss_gemm_static: K must be a multiple of 8");
+    if (target_workgroups < 0 || target_workgroups > 4096) return fail(nullptr, POSS_E_INVALID_ARG, "poss_gemm_static: workgroup target out of range");
+    // sizes in 64 bits before anything is laid out: the limit is checked on the exact byte count
+    const GemmShape g = gemm_plan(dtype, M, N, K, target_workgroups);
+    const size_t w_bytes = ((size_t)g.Npad * g.Kpad * dtype_size(dtype) + 255) / 256 * 256;
+    const size_t part_bytes = (size_t)g.S * MAX_ROWS * g.Npad * sizeof(float);
+    if ((size_t)g.Npad > POSS_GEMM_STATIC_BYTES || (size_t)g.Kpad > POSS_GEMM_STATIC_BYTES || w_bytes + part_bytes > POSS_GEMM_STATIC_BYTES)
+        return fail(nullptr, POSS_E_CAPACITY, "poss_gemm_static: M=%d N=%d K=%d needs %zu bytes of scratch, the static buffer holds %zu",
+                    M, N, K, w_bytes + part_bytes, (size_t)POSS_GEMM_STATIC_BYTES);
+    unsigned char *base = static_cast<unsigned char *>(static_scratch_address());
+    if (!base) return POSS_E_HIP;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    void *wp = base;
+    float *part = reinterpret_cast<float *>(base + w_bytes);
+    EpiArgs epi{};
+    epi.mode = EPI_PLAIN; epi.out = static_cast<float *>(y); epi.ld_out = N;
+    // every byte the kernels read is written first by this call: the packed matrix including its zero
+    // padding by the pack kernel, every row of every plane by the stream kernel
+    launch_pack(dtype, PackSrc{{w, nullptr, nullptr}, {N, 0, 0}}, K, wp, st);
+    if (!launch_gemm(dtype, g, wp, x, K, part, epi, 0.f, st)) return fail(nullptr, POSS_E_INVALID_ARG, "poss_gemm_static: launch refused");
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(nullptr, POSS_E_HIP, "poss_gemm_static: %s", hipGetErrorString(e));
+    return POSS_OK;
+}
