@@ -263,6 +263,40 @@ def test_fc_bias_flag_off_ignores_the_bias_tensor():
     pair.close(); with_bias.close()
 
 
+@pytest.mark.parametrize("name", ["c0_tiny_f32", "t_mid_bf16"])
+def test_fc_bias_alone_drives_the_draft_when_everything_else_is_switched_off(name):
+    """Closed form for the fc bias (the oracle's CPU pin of the same name): fc_w = 0 and zero output
+    projections make every drafted feature the specialist's bias, so a node of depth d carries a token of
+    the top-k of Head(bias of the specialist serving depth d) and adds that token's log-probability."""
+    from oracle.model import head
+    from oracle.numerics import log_softmax
+    cfg = get_config(name)
+    st = make_weights(cfg)
+    rng = np.random.default_rng(11)
+    d_model, k = cfg.d_model, cfg.top_k
+    for s in range(cfg.n_specialists):
+        st[f"spec{s}.fc_w"] = to_storage(np.zeros((d_model, 2 * d_model)), cfg.dtype)
+        st[f"spec{s}.fc_b"] = to_storage(rng.normal(size=d_model) * (1 + s), cfg.dtype)
+        for nm in ("wo", "w_down"):
+            st[f"spec{s}.{nm}"] = to_storage(np.zeros(st[f"spec{s}.{nm}"].shape), cfg.dtype)
+    pair = Pair(name, storage=st)
+    tol = tol_for(cfg)
+    pair.ctx.prefill(make_prompt(cfg, n=14))
+    tr = pair.ctx.draft_tree().as_dict()
+    lp_of = {}
+    for s in range(cfg.n_specialists):
+        logits = head(pair.W, cfg, pair.W(f"spec{s}.fc_b")[None], pair.act)[0]
+        lp_of[s] = (log_softmax(logits), np.sort(logits)[-k])
+    assert tr["n"] == cfg.total_tokens + 1
+    for i in range(1, tr["n"]):
+        s = specialist_index(tr["depth"][i] - 1, cfg.positions_per_specialist, cfg.n_specialists)
+        lp, kth = lp_of[s]
+        step = float(tr["score"][i]) - float(tr["score"][tr["parent"][i]])
+        assert abs(step - lp[tr["token"][i]]) <= 2 * tol, (i, step, lp[tr["token"][i]])
+        assert lp[tr["token"][i]] >= np.sort(lp)[-k] - 2 * tol
+    pair.close()
+
+
 @pytest.mark.parametrize("over,n_prompt", [
     (dict(top_k=1, depth=1, total_tokens=1), 1),               # smallest everything: one-token prompt, one draft token
     (dict(top_k=1, depth=6, total_tokens=6), 2),               # a chain

@@ -232,10 +232,83 @@ def test_mixed_precision_mode_is_lossless_too():
     assert 1e-5 < np.abs(exact - mixed).max() < 2e-2
 
 
+def test_specialist_kv_of_a_copied_target_layer_is_that_layer_s_cache():
+    """Pin of specialist_kv that does not go through the specialist code: a specialist whose fc keeps the
+    embedding half of [x ; f] and whose layer is a copy of target layer 0 (with a bias of zero) turns the
+    pairs [x_j ; .] into target layer 0's own keys and values of the tokens x_j, provided it is given the
+    target's positions.  The target side is pinned against Hugging Face's Llama.  A swapped wk / wv, a
+    missing norm or rotation, or the feature half leaking in fail this."""
+    from oracle.model import specialist_kv
+    cfg = get_config("c0_tiny_f32")
+    W = Weights(cfg, _perfect_drafter_weights(cfg))
+    tokens = make_prompt(cfg, n=18)
+    n = len(tokens)
+    feats, kv = target_rows(W, cfg, tokens, np.arange(n), empty_kv(cfg), causal_allowed(0, n))
+    junk = np.random.default_rng(3).normal(size=(n - 1, cfg.d_model))        # the feature half must not matter
+    for s in range(cfg.n_specialists):
+        k, v = specialist_kv(W, cfg, s, tokens[1:], junk, np.arange(1, n))
+        assert np.allclose(k, kv[0][0][1:], rtol=1e-10, atol=1e-12), s
+        assert np.allclose(v, kv[0][1][1:], rtol=1e-10, atol=1e-12), s
+    assert np.abs(kv[0][0][1:] - kv[0][1][1:]).max() > 1e-3                      # keys and values do differ
+
+
+def test_specialist_kv_is_what_the_pass_attends_to():
+    """With ordinary random specialists (fc bias included): giving the decoder layer specialist_kv's keys
+    and values as context for the last pair reproduces specialist_pass over the whole pair sequence."""
+    from oracle.model import specialist_kv, decoder_layer
+    cfg, W = _setup("t_tiny_f32_6x1")
+    assert cfg.fc_bias and np.abs(W("spec2.fc_b")).max() > 0
+    o = PossOracle(W, cfg)
+    o.prefill(make_prompt(cfg, n=21))
+    t = o.t
+    toks, feats, pos = o.tokens[1:t + 1], np.stack(o.feats[:t]), np.arange(t)
+    for s in (0, 2, 5):
+        want = specialist_pass(W, cfg, s, toks, feats, pos, np.ones((1, t), bool), [t - 1])
+        k, v = specialist_kv(W, cfg, s, toks, feats, pos)
+        x_last = np.concatenate([W("embed")[toks[-1]], feats[-1]])
+        h_last = (W(f"spec{s}.fc_w") @ x_last + W(f"spec{s}.fc_b"))[None]
+        got, k_last, v_last = decoder_layer(W, f"spec{s}.", cfg, h_last, pos[-1:], k[:-1], v[:-1], np.ones((1, t), bool))
+        assert np.allclose(got, want, rtol=1e-9, atol=1e-11), s
+        assert np.allclose(k_last[0], k[-1], atol=1e-12) and np.allclose(v_last[0], v[-1], atol=1e-12)
+        # the context matters: the same row alone gives another feature
+        alone, _, _ = decoder_layer(W, f"spec{s}.", cfg, h_last, pos[-1:], k[:0], v[:0], np.ones((1, 1), bool))
+        assert np.abs(alone - want).max() > 1e-4
+
+
+def test_fc_bias_alone_drives_the_draft_when_everything_else_is_switched_off():
+    """Closed form for the bias of the fc layer (appendix B: the draft model's configuration has one).
+    With fc_w = 0 and the layer's two output projections zero, every drafted feature is the bias itself,
+    so every expanded node's children are the top-k of Head(bias) with the log-probabilities of
+    log_softmax(Head(bias)); without the bias the feature would be zero and the children ids 0..k-1."""
+    cfg = get_config("c0_tiny_f32")
+    st = make_weights(cfg)
+    rng = np.random.default_rng(11)
+    d, k = cfg.d_model, cfg.top_k
+    for s in range(cfg.n_specialists):
+        st[f"spec{s}.fc_w"] = to_storage(np.zeros((d, 2 * d)), cfg.dtype)
+        st[f"spec{s}.fc_b"] = to_storage(rng.normal(size=d) * (1 + s), cfg.dtype)      # a different bias per specialist
+        for nm in ("wo", "w_down"):
+            st[f"spec{s}.{nm}"] = to_storage(np.zeros(st[f"spec{s}.{nm}"].shape), cfg.dtype)
+    W = Weights(cfg, st)
+    o = PossOracle(W, cfg)
+    o.prefill(make_prompt(cfg, n=14))
+    o.draft_tree()
+    tb = o.last["builder"]
+    pool_depth = [1] * k + [dd for dd in range(2, cfg.depth + 1) for _ in range(k * k)]
+    for i0 in range(0, len(tb.token), k):
+        s = specialist_index(pool_depth[i0] - 1, cfg.positions_per_specialist, cfg.n_specialists)
+        logits = head(W, cfg, W(f"spec{s}.fc_b")[None])[0]
+        want = topk_lowest_id(logits.astype(np.float32), k)
+        assert tb.token[i0:i0 + k] == want.tolist(), (i0, s)
+        lp = log_softmax(logits)[want]
+        parent_score = 0.0 if tb.parent[i0] < 0 else float(tb.score[tb.parent[i0]])
+        assert np.allclose(np.array(tb.score[i0:i0 + k], dtype=np.float64) - parent_score, lp, atol=1e-4)
+    assert tb.token[:k] != list(range(k))
+
+
 def test_score_tree_and_specialist_kv_agree_with_the_draft():
     """Helpers used by the GPU lock-step tests: re-scoring the oracle's own tree reproduces its
-    scores, and a specialist's keys/values are what its pass attends to (checked through
-    attention over them reproducing the pass output)."""
+    scores; specialist_kv's keys are rotated by the position they are given."""
     from oracle.model import specialist_kv
     cfg, W = _setup("t_tiny_f32_6x1")
     o = PossOracle(W, cfg)
