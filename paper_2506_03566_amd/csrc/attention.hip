@@ -224,7 +224,12 @@ __device__ __forceinline__ void attn_mfma_body(
         // lane holds keys slot0 + tt*16 + 4*lg + r of query row lr.  Scores are kept in the log2
         // domain (scale * log2 e folded into one factor) so that the exponentials are single
         // v_exp_f32 instructions; the softmax is VALU-bound, not MFMA-bound, at these sizes.
-        V8 pf[RT];
+        // bf16 keeps 8 significant bits: probabilities rounded to it moved a layer's output by 2e-2 at the 8B
+        // shape (the mean of hundreds of values loses its low bits), ten times everything else.  They go into the
+        // P V product as a sum of two bf16 numbers, p = hi + lo, 16 significant bits, at the price of a second
+        // MFMA per value fragment.  fp16 (11 bits) stays single.
+        constexpr bool SPLIT_P = std::is_same<T, bf16_t>::value;
+        V8 pf[RT], pf_lo[RT];
         float alpha[RT];
         bool rescale = false;
 #pragma unroll
@@ -252,13 +257,14 @@ __device__ __forceinline__ void attn_mfma_body(
             alpha[rt] = 1.f;
             if (m_new == -INFINITY) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) pf[rt][j] = (T)0.f;
+                for (int j = 0; j < 8; ++j) { pf[rt][j] = (T)0.f; pf_lo[rt][j] = (T)0.f; }
             } else {
                 alpha[rt] = __builtin_amdgcn_exp2f(m_run[rt] - m_new);   // 2^(-inf) = 0 on the first visible block
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const float pe = __builtin_amdgcn_exp2f(fmaf(sv[j], scale, -m_new));
                     pf[rt][j] = from_f<T>(pe);
+                    if constexpr (SPLIT_P) pf_lo[rt][j] = from_f<T>(pe - to_f(pf[rt][j]));
                     psum += pe;
                 }
             }
@@ -278,6 +284,13 @@ __device__ __forceinline__ void attn_mfma_body(
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
                 acc[rt][dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf[dt]), pf[rt], acc[rt][dt]);
+        if constexpr (SPLIT_P) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    acc[rt][dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf[dt]), pf_lo[rt], acc[rt][dt]);
+        }
         }
         store_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, buf ^ 1);
         load_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, bi + (1 + PFD) * KW, pg_ahead);

@@ -42,6 +42,15 @@ def tol_for(cfg):
     return 1e-4 if cfg.dtype == 0 else 2e-2
 
 
+# End-to-end error of 16-bit logits after the whole target at the 8B / 13B shapes.  The 2e-2 bound holds per
+# layer and per Head on identical inputs; through 32-40 random-initialised layers every flipped rounding of
+# an activation is carried on and amplified, and two summation orders (the oracle's float64 sums, the
+# kernels' float32 sums; consecutive or scattered cache slots) flip different ones.  Measured against the
+# teacher-forced oracle at the 8B shape: max|dlogit| 0.20 over 12 positions (median 0.17, logit std 1.28);
+# tests allow 0.30, and two runs of the library may therefore disagree where a top-2 gap is below twice that.
+E2E_LOGIT_TOL = 0.30
+
+
 def tree_from_gpu(tr):
     from oracle.tree import Tree
     d = tr.as_dict()

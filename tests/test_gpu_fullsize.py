@@ -6,7 +6,7 @@ size (speculative stream == the library's own vanilla greedy stream, tree validi
 import numpy as np
 import pytest
 
-from gpu_util import have_gpu
+from gpu_util import have_gpu, E2E_LOGIT_TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -23,8 +23,8 @@ def _say(msg):
     print(msg, flush=True)
 
 
-@pytest.mark.parametrize("name,layer,n_ar", [("c1_llama3_8b_3x2", 17, 10), ("c3_llama2_13b_3x2", 23, 6),
-                                             ("c4_llama3_8b_long", 5, 5)])
+@pytest.mark.parametrize("name,layer,n_ar", [("c1_llama3_8b_3x2", 17, 10), ("c2_llama3_8b_6x1", 30, 6),
+                                             ("c3_llama2_13b_3x2", 23, 6), ("c4_llama3_8b_long", 5, 5)])
 def test_full_size_sampled_parity_and_losslessness(name, layer, n_ar):
     cfg = get_config(name)
     keep = [f"layer{layer}.", "lm_head", "final_norm"]
@@ -71,9 +71,16 @@ def test_full_size_sampled_parity_and_losslessness(name, layer, n_ar):
     rms = np.sqrt((h_out ** 2).mean())
     err = np.abs(o_out - h_out).max()
     _say(f"  layer {layer}: max|dh| = {err:.3e}, rms(h) = {rms:.2f}")
-    assert err <= 2e-2 * max(1.0, rms)
+    # One layer on identical inputs, in the residual stream (float32, rms ~ 6-15 at these depths): the two
+    # sides differ where a float32 and a float64 sum round an activation to different 16-bit neighbours
+    # (values up to ~8 in SiLU.up, step 2^-6 there), each flip moving one output by step x |w| ~ 3e-4 and a
+    # few hundred of them meeting in the worst element.  Measured 1.7e-2 .. 2.2e-2 (bf16), 3e-3 (fp16).
+    assert err <= 4e-2
     gk, gv = ctx.debug_read_kv(-1, layer, t, d["n"])
-    assert np.abs(gk - k_new).max() <= 2e-2 and np.abs(gv - v_new).max() <= 2e-2
+    # cache entries are 16-bit: an entry that rounds to the other neighbour differs by one step of its own
+    # size (2^-7 relative covers bf16 and fp16), which above 2.5 is more than the absolute bound
+    for got, want in ((gk, k_new), (gv, v_new)):
+        assert (np.abs(got - want) <= np.maximum(2e-2, 2.0 ** -7 * np.abs(want))).all()
     # ---- sampled Head rows: the library's features through the oracle's Head
     rows = [0, 1, 17, d["n"] - 1]
     ol = head(W, cfg, feats[rows].cpu().numpy().astype(np.float64), act=cfg.dtype)
@@ -89,8 +96,9 @@ def test_full_size_sampled_parity_and_losslessness(name, layer, n_ar):
     # weight shape only, attention splits on the committed prefix only), so as long as every round
     # commits the bonus token of the root alone the two streams are equal bit for bit.  A round that
     # accepts drafted tokens reads their keys from scattered tree slots instead of consecutive ones:
-    # another summation order, and at 32 random-init layers rounding noise is amplified to ~0.2 in
-    # the logits, so from that round on only a clear margin binds.
+    # another summation order, and through 32 random-init layers rounding noise is amplified to the
+    # end-to-end error measured against the oracle (E2E_LOGIT_TOL), so from that round on two streams
+    # may part where the top-2 gap is below twice that.
     path, m, toks = ctx.accept_and_commit()
     assert accept_bruteforce(d["token"], d["parent"], g.tolist())[0] == path
     spec, exact_upto = [first] + toks, (1 + len(toks) if m == 0 else 1)
@@ -108,7 +116,7 @@ def test_full_size_sampled_parity_and_losslessness(name, layer, n_ar):
     assert spec[:n] == ar[:n]
     for j in range(n, len(ar)):
         if spec[j] != ar[j]:
-            assert gaps[j - 1] <= 0.5, f"streams differ at {j} with a clear margin {gaps[j - 1]}"
+            assert gaps[j - 1] <= 2 * E2E_LOGIT_TOL, f"streams differ at {j} with a clear margin {gaps[j - 1]}"
             break
     st = ctx.stats()
     assert st.rounds >= 1 and st.committed_tokens == len(spec) - 1

@@ -148,17 +148,23 @@ def test_verify_parity_with_other_launch_shapes(gemm_wgs, attn_keys):
     pair.close()
 
 
-@pytest.mark.parametrize("name,layers,attn_keys", [("t_mid_bf16", 1, 0), ("t_mid_bf16", 1, 1024), ("t_mid_f16", 2, 0), ("t_mid_f16", 2, 64)])
+@pytest.mark.parametrize("name,layers,attn_keys", [("t_mid_bf16", 1, 0), ("t_mid_bf16", 1, 1024), ("t_mid_bf16", 3, 0),
+                                                   ("t_mid_bf16", 3, 1024), ("t_mid_f16", 2, 0), ("t_mid_f16", 2, 64)])
 def test_verify_parity_with_a_wide_score_range(name, layers, attn_keys):
-    """Query / key projections scaled by 16 / 2: attention scores spread over tens of binary orders
-    instead of a fraction of one, so the running reference of the online softmax is overtaken from
-    block to block, by little (kept) and by much (accumulators rescaled), within a split and across
-    the merge of splits.  400 committed tokens: several key blocks per split.
-    Such attention is close to one-hot: its output is a value row rather than the mean of hundreds,
-    twenty times larger, and so is what the 16-bit rounding of the probabilities (which the oracle
-    does not model) adds to it; with bfloat16 the usual tolerance holds when one layer is scaled
-    (0.08 with all three, in the kernel from before the reference was allowed to lag as well),
-    with float16 when all are."""
+    """Query / key projections of the first `layers` layers scaled by 16 / 2: attention scores spread over
+    tens of binary orders instead of a fraction of one, so the running reference of the online softmax is
+    overtaken from block to block, by little (kept) and by much (accumulators rescaled), within a split
+    and across the merge of splits.  400 committed tokens: several key blocks per split.
+    Such attention is close to one-hot, and a model built of it is badly conditioned in 16-bit storage: a
+    query or key element that rounds to the other neighbour moves a score by a tenth and a probability by
+    ten percent.  The bound is therefore the usual tolerance or, if larger, twice what the oracle's OWN
+    logits move when its queries and keys are disturbed by one part in a million before they are rounded
+    (what float32 instead of float64 sums do to them): with one bfloat16 layer or both float16 layers
+    scaled that is below the usual tolerance, with all three bfloat16 layers scaled it is 0.03-0.07.
+    (The kernel carries bfloat16 probabilities into the P V product as a sum of two bfloat16 numbers;
+    single ones added another 0.08 here and 2e-2 per layer at the 8B shape.)"""
+    from unittest import mock
+    import oracle.model
     cfg = get_config(name)
     storage = make_weights(cfg)
     for l in range(layers):
@@ -167,11 +173,24 @@ def test_verify_parity_with_a_wide_score_range(name, layers, attn_keys):
     pair = Pair(name, storage=storage)
     if attn_keys:
         pair.ctx.set_tuning(0, attn_keys)
-    o, first, tr, g, logits, feats, og, ologits, ofeats = _verify_both(pair, make_prompt(cfg, n=400))
-    tol = tol_for(cfg)
+    prompt = make_prompt(cfg, n=400)
+    o, first, tr, g, logits, feats, og, ologits, ofeats = _verify_both(pair, prompt)
+    # conditioning: the oracle once more on the same tokens and tree, queries and keys disturbed before rounding
+    rng = np.random.default_rng(1)
+    plain_rope = oracle.model.rope
+    with mock.patch.object(oracle.model, "rope", lambda x, pos, theta: plain_rope(x, pos, theta) * (1 + 1e-6 * rng.normal(size=x.shape))):
+        o2 = pair.oracle()
+        o2.prefill(prompt)
+        o2.tokens[-1] = o.tokens[-1]
+        _, dlogits, _ = o2.verify_tree(Tree(o.last["tree"].token, o.last["tree"].parent))
+    cond = np.abs(dlogits - ologits).max()
+    tol = max(tol_for(cfg), 2 * cond)
     err = np.abs(logits - ologits).max()
-    _say(f"  {name}, keys per split {attn_keys or 'default'}: max|dlogit| = {err:.3e} (tol {tol})")
+    _say(f"  {name}, {layers} layers scaled, keys per split {attn_keys or 'default'}: max|dlogit| = {err:.3e} "
+         f"(oracle moved by {cond:.3e} under 1e-6 noise; bound {tol:.3e})")
     assert err <= tol
+    if layers == 1 or cfg.dtype == 2:
+        assert err <= tol_for(cfg)
     pair.close()
 
 
