@@ -139,7 +139,7 @@ const char *check_config(const poss_config &c) {
     if (c.total_tokens < 1 || c.total_tokens + 1 > POSS_MAX_ROWS) return "total_tokens must be in 1..127";
     if (c.total_tokens > pool) return "total_tokens exceeds the candidate pool k + (depth-1) k^2";
     if (pool > 2048) return "candidate pool too large";
-    if ((long long)((c.vocab + 2047) / 2048) * c.top_k > 2048) return "vocab * top_k too large for the top-k merge";
+    if ((long long)head_segments_max(c.vocab) * c.top_k > 64 * 256) return "vocab * top_k too large for the top-k merge";
     if ((c.depth - 1) * c.top_k > 64 * POSS_MASK_WORDS) return "(depth-1)*top_k must fit the 128-bit ancestor mask";
     if (c.top_k + (c.depth + 1) + (c.depth - 1) * c.top_k > POSS_MAX_ROWS) return "a specialist pass would exceed 128 rows";
     if (c.kv_page_tokens != 32 && c.kv_page_tokens != 64 && c.kv_page_tokens != 128) return "kv_page_tokens must be 32, 64 or 128";
@@ -364,11 +364,34 @@ void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowM
         launch_copy_rows_f32(c->h, md.d, c->taps_user + (size_t)nl * rows * md.d, md.d, rows, md.d, c->st);
 }
 
-// logits[rows][Npad] = Head(features) for the rows whose final-normed activations are in c->u
-GemmShape run_head(poss_ctx *c, int rows) {
+// Head(features) for the rows whose final-normed activations start at x (default: c->u).  head_mode 0: the logits,
+// c->logits[rows][Npad].  HEAD_ARGMAX / HEAD_TOPK (16-bit storage): the GEMM reduces its own column tiles into
+// c->topk_scratch - per row and tile the best (value, index), or the record of the k best with the tile's maximum and
+// sum of exponentials - and writes the logits only if asked; *n_seg_out receives the number of tiles.  Float32
+// storage has no such epilogue: it always writes logits and reports 0 tiles.
+GemmShape run_head(poss_ctx *c, int rows, int head_mode, bool write_logits, int *n_seg_out, const void *x = nullptr) {
     EpiArgs e{};
     e.mode = EPI_PLAIN;
-    return run_gemm(c, c->lm_head, c->md.vocab, c->md.d, c->u, c->md.d, rows, c->logits, true, e);
+    if (n_seg_out) *n_seg_out = 0;
+    if (head_mode && c->md.dt != DT_F32) {
+        const GemmShape g0 = gemm_plan(c->md.dt, rows, c->md.vocab, c->md.d, 1);
+        const int n_seg = gemm_head_segments(g0);
+        e.mode = EPI_HEAD; e.head_mode = head_mode; e.head_k = c->cfg.top_k; e.write_logits = write_logits ? 1 : 0;
+        e.seg_out = c->topk_scratch;
+        e.pv = c->topk_scratch; e.pi = reinterpret_cast<int *>(c->topk_scratch + (size_t)rows * n_seg);
+        if (n_seg_out) *n_seg_out = n_seg;
+    }
+    return run_gemm(c, c->lm_head, c->md.vocab, c->md.d, x ? x : c->u, c->md.d, rows, c->logits, true, e);
+}
+
+// The drafter's k best next tokens and their log-probabilities for `rows` rows of final-normed activations in c->u.
+void run_head_topk(poss_ctx *c, int rows) {
+    int n_seg = 0;
+    const GemmShape g = run_head(c, rows, HEAD_TOPK, false, &n_seg);
+    if (n_seg)
+        launch_topk_merge(c->topk_scratch, n_seg, rows, c->cfg.top_k, c->topk_id_all, c->topk_logp_all, c->st);
+    else
+        launch_topk_logsoftmax(c->logits, g.Npad, rows, c->cfg.vocab, c->cfg.top_k, c->topk_scratch, c->topk_id_all, c->topk_logp_all, c->st);
 }
 
 __global__ void causal_meta_kernel(int n, int c0, int32_t *pos, int32_t *slot, uint64_t *mask) {
@@ -688,8 +711,8 @@ void poss_free(poss_ctx *c) {
 
 const char *poss_last_error(poss_ctx *c) { return c ? c->err : g_load_error; }
 
-static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, const int *seq_ids, int n_seq, const int *row0,
-                         const int *n_rows, int base = 0);
+static int head_and_choose(poss_ctx *c, const void *x, int rows, bool want_logits, const int32_t *depth, const int *seq_ids,
+                           int n_seq, const int *row0, const int *n_rows, int base, int *ld_out);
 
 int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
     if (!c) return POSS_E_INVALID_ARG;
@@ -713,10 +736,7 @@ int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_
         if (c0 + rows == n_prompt) {
             // Head on the last row only: its normed activations sit at row rows-1 of c->u
             const char *last = static_cast<const char *>(c->u) + (size_t)(rows - 1) * md.d * dtype_size(md.dt);
-            EpiArgs pe{};
-            pe.mode = EPI_PLAIN;
-            GemmShape g = run_gemm(c, c->lm_head, md.vocab, md.d, last, md.d, 1, c->logits, true, pe);
-            { const int zero = 0, one = 1, id = seq; int rc = choose_tokens(c, g.Npad, 1, nullptr, &id, 1, &zero, &one); if (rc) return rc; }
+            { const int zero = 0, one = 1, id = seq; int rc = head_and_choose(c, last, 1, false, nullptr, &id, 1, &zero, &one, 0, nullptr); if (rc) return rc; }
             HIP_TRY(c, hipMemcpyAsync(sq.tokens_dev + n_prompt, c->argmax_dev, sizeof(int32_t), hipMemcpyDeviceToDevice, c->st));
         }
         HIP_TRY(c, hipStreamSynchronize(c->st));          // the staging buffer is reused by the next chunk
@@ -740,23 +760,33 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
     return poss_prefill_seq(c, 0, prompt, n_prompt, first_token_out);
 }
 
-// The token the target chooses after each of `rows` rows of c->logits: the argmax, or at temperature > 0 a
-// draw by inverse CDF with the uniform number of the row's depth (depth == nullptr: all rows use u[0]).
-// Sequence seq_ids[i] owns rows [row0[i], row0[i] + n_rows[i]) of the logits and has its own numbers; the
-// rows' depths and results sit `base` rows further on in the batch-wide arrays (the rows of earlier groups).
-static int choose_tokens(poss_ctx *c, int ld, int rows, const int32_t *depth, const int *seq_ids, int n_seq, const int *row0,
-                         const int *n_rows, int base) {
+// Head over `rows` rows of final-normed activations at x (nullptr: c->u), then the token the target chooses after
+// each: the argmax - reduced per column tile inside the Head GEMM, the logits written only if want_logits - or at
+// temperature > 0 a draw by inverse CDF with the uniform number of the row's depth (depth == nullptr: all rows use u[0]).
+// Sequence seq_ids[i] owns rows [row0[i], row0[i] + n_rows[i]) and has its own numbers; the rows' depths and results
+// sit `base` rows further on in the batch-wide arrays (the rows of earlier groups).  *ld_out: row stride of c->logits.
+static int head_and_choose(poss_ctx *c, const void *x, int rows, bool want_logits, const int32_t *depth, const int *seq_ids,
+                           int n_seq, const int *row0, const int *n_rows, int base, int *ld_out) {
     if (c->temperature > 0.f) {
-        const int nu = POSS_MAX_DEPTH + 1;
+        const GemmShape g = run_head(c, rows, 0, true, nullptr, x);
+        if (ld_out) *ld_out = g.Npad;
+        const int nu = POSS_MAX_DEPTH + 1, ld = g.Npad;
         HIP_TRY(c, hipMemcpyAsync(c->u_dev, c->u_pinned, (size_t)c->B * nu * sizeof(float), hipMemcpyHostToDevice, c->st));
         for (int i = 0; i < n_seq; ++i)
             if (!launch_sample(c->logits + (size_t)row0[i] * ld, ld, n_rows[i], c->cfg.vocab, c->temperature,
                                c->u_dev + (size_t)seq_ids[i] * nu, depth ? depth + base + row0[i] : nullptr, c->topk_scratch,
                                c->argmax_dev + base + row0[i], c->st))
                 return fail(c, POSS_E_INVALID_ARG, "sampling: vocabulary too large for the sampler");
-    } else {
-        launch_argmax(c->logits, ld, rows, c->cfg.vocab, c->topk_scratch, c->argmax_dev + base, c->st);
+        return POSS_OK;
     }
+    int n_seg = 0;
+    const GemmShape g = run_head(c, rows, HEAD_ARGMAX, want_logits, &n_seg, x);
+    if (ld_out) *ld_out = g.Npad;
+    if (n_seg)
+        launch_argmax_merge(c->topk_scratch, reinterpret_cast<const int *>(c->topk_scratch + (size_t)rows * n_seg), n_seg, rows,
+                            c->argmax_dev + base, c->st);
+    else
+        launch_argmax(c->logits, g.Npad, rows, c->cfg.vocab, c->topk_scratch, c->argmax_dev + base, c->st);
     return POSS_OK;
 }
 
@@ -844,8 +874,7 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
             spec_pass(c, s, gp, d - 1, c->fhat[(d - 1) & 1] + (size_t)i0 * prev_each * c->md.d, prev_each,
                       c->fhat[d & 1] + (size_t)i0 * rows_q_each * c->md.d, &q0);
             const int rows_q = nb * rows_q_each;
-            GemmShape g = run_head(c, rows_q);
-            launch_topk_logsoftmax(c->logits, g.Npad, rows_q, cf.vocab, k, c->topk_scratch, c->topk_id_all, c->topk_logp_all, c->st);
+            run_head_topk(c, rows_q);
             TreeDev tds[8];
             for (int i = 0; i < nb; ++i) {
                 Seq &sq = c->seq[act[i0 + i]];
@@ -995,10 +1024,10 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
             segs.push_back(Seg{act[i], nullptr, row0[i] - base, n_rows[i], grows, 0, c->seq[act[i]].t, n_rows[i]});
         }
         target_forward(c, grows, c->tree_token_all + base, rm, segs, c->feats + (size_t)base * cf.d_model);
-        GemmShape g = run_head(c, grows);
-        { int rc = choose_tokens(c, g.Npad, grows, c->tree_depth_all, act.data() + i0, i1 - i0, rel0, n_rows + i0, base); if (rc) return rc; }
+        int ld = 0;
+        { int rc = head_and_choose(c, nullptr, grows, i0 == 0 && logits_out, c->tree_depth_all, act.data() + i0, i1 - i0, rel0, n_rows + i0, base, &ld); if (rc) return rc; }
         if (i0 == 0 && logits_out)                         // before the next group overwrites the logits
-            launch_copy_rows_f32(c->logits, g.Npad, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
+            launch_copy_rows_f32(c->logits, ld, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
         i0 = i1;
     }
     (void)hipEventRecord(c->ev[3], c->st);

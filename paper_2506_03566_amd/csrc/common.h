@@ -81,7 +81,12 @@ struct RowMeta {
 // ---------------------------------------------------------------- GEMM with fused epilogue
 // The stream kernel writes split-K partial planes; an epilogue kernel with one workgroup per
 // 128-column tile sums them in split order and applies the fused operation.
-enum { EPI_PLAIN = 0, EPI_ROPE_KV = 1, EPI_RESIDUAL = 2, EPI_SILU = 3 };
+enum { EPI_PLAIN = 0, EPI_ROPE_KV = 1, EPI_RESIDUAL = 2, EPI_SILU = 3, EPI_HEAD = 4 };
+// What the Head GEMM reduces in its own epilogue (EPI_HEAD, 16-bit types, K unsplit): every workgroup owns whole
+// columns of every row, so it leaves, per row, the winner or the k best of its columns instead of (or besides) logits.
+enum { HEAD_ARGMAX = 1, HEAD_TOPK = 2 };
+constexpr int TOPK_MAXK = 16;
+constexpr int TOPK_REC = 2 + 2 * TOPK_MAXK;    // segment record: [max, sum exp(l - max), k values, k indices (as bits)]
 struct EpiArgs {
     int mode;
     // EPI_PLAIN: out[m][n] = sum (with out == nullptr and S == 1 plane 0 is the result, row stride Npad)
@@ -92,6 +97,11 @@ struct EpiArgs {
     // EPI_RESIDUAL: h[m][n] = sum + bias[n] + (residual ? h[m][n] : 0); h_copy likewise; then, if
     // gain != nullptr, u[m][n] = T(rmsnorm(h[m]) * gain[n]) - the operand of the next GEMM
     float *h; const void *bias; int residual; float *h_copy; const void *gain; void *u;
+    // EPI_HEAD (N = vocabulary; the stream kernel's column tile is a "segment"; seg_out / pv, pi must hold
+    // gemm_head_segments() entries per row): head_mode HEAD_ARGMAX: pv/pi[row * n_seg + seg] = best (value, index) of the
+    // segment, ties to the lower index; HEAD_TOPK: seg_out[(row * n_seg + seg) * TOPK_REC ..] = the segment's record.
+    // write_logits != 0: the float32 logits are also written to the partial-plane buffer (row stride Npad).
+    int head_mode, head_k, write_logits; float *seg_out; float *pv; int *pi;
     // EPI_SILU: columns [32j, 32j+16) hold gate[16j..16j+15], the next 16 up[16j..16j+15], so one MFMA lane
     // owns both factors of act[m][f] = T(silu(gate) * up); with S == 1 the stream kernel writes act itself
     void *act; int F;
@@ -103,6 +113,10 @@ struct EpiArgs {
 bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
                  const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t ev_start = nullptr,
                  hipEvent_t ev_stop = nullptr, bool defer_epilogue = false);
+// Column tiles ("segments") of an unsplit launch of this shape, i.e. records per row an EPI_HEAD launch writes;
+// head_segments_max bounds it for any row count.
+int gemm_head_segments(const GemmShape &g);
+static inline int head_segments_max(int vocab) { return gemm_npad(vocab) / GEMM_BLOCK_N; }
 // The RoPE + KV-write epilogue of a deferred launch over row ranges [r0, r1), each into its own cache and
 // with its own query limit (rows below rows_q get a rotated query), in one launch: several sequences batched
 // into one GEMM each take their own rows into their own cache.  Row indices stay those of the GEMM launch
@@ -118,6 +132,8 @@ void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *to
                        float2 *cs, hipStream_t st);
 size_t argmax_scratch_floats(int rows, int vocab);
 void launch_argmax(const float *logits, int ld, int rows, int vocab, float *scratch, int32_t *out, hipStream_t st);
+// second stage alone: pv / pi hold n_seg partial winners per row
+void launch_argmax_merge(const float *pv, const int *pi, int n_seg, int rows, int32_t *out, hipStream_t st);
 // Temperature sampling: out[r] = first id whose cumulative probability under softmax(logits[r] / temperature)
 // exceeds u_by_depth[depth ? depth[r] : 0] (DEVICE arrays).  Returns false (nothing launched) for temperature <= 0
 // or a vocabulary beyond 4M entries.
@@ -151,6 +167,8 @@ struct TreeDev {            // device-resident tree state of one round
     int32_t *n_nodes, *token, *parent, *depth, *pos; uint64_t *mask; float *score;
 };
 size_t topk_scratch_floats(int rows, int vocab);
+// second stage alone, over n_seg segment records per row (written by topk_seg_kernel or by an EPI_HEAD launch)
+void launch_topk_merge(const float *seg_records, int n_seg, int rows, int k, int32_t *out_id, float *out_logp, hipStream_t st);
 void launch_topk_logsoftmax(const float *logits, int ld, int rows, int vocab, int k, float *seg_scratch,
                             int32_t *out_id, float *out_logp, hipStream_t st);
 // Both take the trees of n_seq <= TREE_BATCH_MAX sequences (arrays of n_seq entries): one workgroup each.

@@ -120,14 +120,18 @@ __global__ __launch_bounds__(64) void argmax_merge_kernel(const float *__restric
     if (threadIdx.x == 0) out[rowi] = bi;
 }
 
-size_t argmax_scratch_floats(int rows, int vocab) { return (size_t)2 * rows * ((vocab + ARGMAX_SEG - 1) / ARGMAX_SEG); }
+size_t argmax_scratch_floats(int rows, int vocab) { return (size_t)2 * rows * head_segments_max(vocab); }   // finest segmentation: the Head GEMM's tiles
+
+void launch_argmax_merge(const float *pv, const int *pi, int n_seg, int rows, int32_t *out, hipStream_t st) {
+    hipLaunchKernelGGL(argmax_merge_kernel, dim3(rows), dim3(64), 0, st, pv, pi, n_seg, out);
+}
 
 void launch_argmax(const float *logits, int ld, int rows, int vocab, float *scratch, int32_t *out, hipStream_t st) {
     const int n_seg = (vocab + ARGMAX_SEG - 1) / ARGMAX_SEG;
     float *pv = scratch;
     int *pi = reinterpret_cast<int *>(scratch + (size_t)rows * n_seg);
     hipLaunchKernelGGL(argmax_seg_kernel, dim3(n_seg, rows), dim3(256), 0, st, logits, ld, vocab, n_seg, pv, pi);
-    hipLaunchKernelGGL(argmax_merge_kernel, dim3(rows), dim3(64), 0, st, pv, pi, n_seg, out);
+    launch_argmax_merge(pv, pi, n_seg, rows, out, st);
 }
 
 // ------------------------------------------------------------------ temperature sampling per row

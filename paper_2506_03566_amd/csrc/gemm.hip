@@ -150,10 +150,25 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
 // slice: halves the L2 traffic per weight byte; used where N alone fills the GPU).
 // FUSE_SILU (K not split, gate/up interleaved per wave tile): the kernel applies SiLU(gate) * up to its
 // accumulators and writes the activation act[M][F] itself; no partial plane, no epilogue kernel.
-template <typename T, int MT, int WPB, bool FUSE_SILU, int PF>
+// HEAD (K not split, columns = vocabulary): the workgroup reduces its column tile per row in its own epilogue - the
+// best (value, index) for greedy verification, or maximum, sum of exponentials and the k best for the drafter's
+// log-softmax + top-k - so that no kernel has to read the logits back; they are written only on request.
+struct HeadEpi { int mode, k, vocab, write_logits; float *seg_out; float *pv; int *pi; };
+
+// (value, index) reductions over the 32 lanes of a half wave
+__device__ __forceinline__ void half_argmax(float &v, int &i) {
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(v, o, 32);
+        const int oi = __shfl_xor(i, o, 32);
+        if (better(ov, oi, v, i)) { v = ov; i = oi; }
+    }
+}
+
+template <typename T, int MT, int WPB, bool FUSE_SILU, int PF, bool HEAD = false>
 __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
-    int M, int K, int Npad, int ksteps_total, T *__restrict__ act, int F) {
+    int M, int K, int Npad, int ksteps_total, T *__restrict__ act, int F, HeadEpi he) {
     static_assert(KCS % PF == 0, "ring index must be static");
     constexpr int XUNITS = KCS * MT * 64;                 // 16-byte units of one staged chunk
     // units per thread; where 64 * WPB does not divide the units the last threads stage the last unit again
@@ -287,6 +302,78 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
             const int m = p / PPR, f = f0 + (p % PPR) * EPV;
             if (m < M && f + EPV <= F)                   // F is a multiple of 8: a piece is inside or outside as a whole
                 *reinterpret_cast<u32x4 *>(act + (size_t)m * F + f) = *reinterpret_cast<const u32x4 *>(tile + m * TWP + (p % PPR) * EPV);
+        }
+        return;
+    }
+    if constexpr (HEAD) {
+        constexpr int TW = WPB * GEMM_NT * 16;           // columns of the workgroup's tile = one segment
+        static_assert((size_t)MT * 16 * TW * sizeof(float) <= sizeof(xs), "the tile fits the staging memory");
+        if (he.write_logits) {
+            const int nl = ngroup * (GEMM_NT * 16) + (lane & 15);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < GEMM_NT; ++nt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        part[(size_t)(mt * 16 + 4 * (lane >> 4) + r) * Npad + nl + nt * 16] = acc[mt][nt][r];
+        }
+        float *tile = reinterpret_cast<float *>(&xs[0][0]);
+        __syncthreads();                                 // every wave has read its last operand fragments
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < GEMM_NT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    tile[(mt * 16 + 4 * (lane >> 4) + r) * TW + wave * (GEMM_NT * 16) + nt * 16 + (lane & 15)] = acc[mt][nt][r];
+        __syncthreads();
+        // one half wave per row (its two halves take different rows; shuffles stay inside a half)
+        constexpr int NVH = TW / 32;
+        const int hw = tid >> 5, hl = tid & 31, seg = blockIdx.x, n_seg = gridDim.x, col0 = seg * TW;
+        for (int row = hw; row < M; row += WPB * 2) {
+            float v[NVH]; int id[NVH];
+            float bv = -INFINITY; int bi = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < NVH; ++j) {
+                const int c = hl + 32 * j, n = col0 + c;
+                const bool ok = n < he.vocab;
+                v[j] = ok ? tile[row * TW + c] : -INFINITY;
+                id[j] = ok ? n : 0x7fffffff - j;         // dummies stay below every real entry
+                if (better(v[j], id[j], bv, bi)) { bv = v[j]; bi = id[j]; }
+            }
+            if (he.mode == HEAD_ARGMAX) {
+                half_argmax(bv, bi);
+                if (hl == 0) { he.pv[(size_t)row * n_seg + seg] = bv; he.pi[(size_t)row * n_seg + seg] = bi; }
+                continue;
+            }
+            // maximum, sum of exp(l - max) in a fixed order, then the k best by k rounds of (argmax, remove)
+            float mx = bv;
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 32));
+            float se = 0.f;
+#pragma unroll
+            for (int j = 0; j < NVH; ++j) se += v[j] > -INFINITY ? expf(v[j] - mx) : 0.f;
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) se += __shfl_xor(se, o, 32);
+            float *rec = he.seg_out + ((size_t)row * n_seg + seg) * TOPK_REC;
+            if (hl == 0) { rec[0] = mx; rec[1] = se; }
+            float my_v = -INFINITY; int my_i = 0x7fffffff;
+            for (int r = 0; r < he.k; ++r) {
+                float wv = -INFINITY; int wi = 0x7fffffff;
+#pragma unroll
+                for (int j = 0; j < NVH; ++j)
+                    if (better(v[j], id[j], wv, wi)) { wv = v[j]; wi = id[j]; }
+                half_argmax(wv, wi);
+                if (hl == r) { my_v = wv; my_i = wi; }
+#pragma unroll
+                for (int j = 0; j < NVH; ++j)
+                    if (id[j] == wi) v[j] = -INFINITY;   // real indices are unique: removes exactly the winner
+            }
+            if (hl < he.k) {
+                rec[2 + hl] = my_v;
+                reinterpret_cast<int *>(rec)[2 + TOPK_MAXK + hl] = my_v > -INFINITY ? my_i : 0x7fffffff;
+            }
         }
         return;
     }
@@ -430,6 +517,14 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
     return g;
 }
 
+// Two 128-column tiles per workgroup (8 waves sharing one staged activation slice) when the column count alone
+// gives every CU work and K is not split.
+static bool gemm_wide(const GemmShape &g) {
+    return g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
+}
+
+int gemm_head_segments(const GemmShape &g) { return g.Npad / (GEMM_BLOCK_N * (gemm_wide(g) ? 2 : 1)); }
+
 template <typename T>
 static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiArgs &epi, float eps, bool silu_done,
                               hipStream_t st) {
@@ -448,6 +543,7 @@ static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiAr
                                g.N, eps, epi);
             break;
         }
+        case EPI_HEAD: break;           // reduced inside the stream kernel
         case EPI_SILU:
             if (silu_done) break;       // applied inside the stream kernel
             hipLaunchKernelGGL((epilogue_kernel<T, EPI_SILU>), pair_grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, 0, g.M, epi);
@@ -464,8 +560,11 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
                           const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop, bool defer_epilogue) {
     // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
     const bool fuse_silu = epi.mode == EPI_SILU && g.S == 1;
-    const bool wide = !fuse_silu && g.S == 1 && g.Mpad <= 96 && g.Npad % (2 * GEMM_BLOCK_N) == 0 && g.Npad / (2 * GEMM_BLOCK_N) >= 256;
+    const bool head = epi.mode == EPI_HEAD;
+    const bool wide = !fuse_silu && gemm_wide(g);
     const int wpb = wide ? 8 : 4;
+    HeadEpi he{};
+    if (head) he = HeadEpi{epi.head_mode, epi.head_k, g.N, epi.write_logits, epi.seg_out, epi.pv, epi.pi};
     dim3 grid(g.Npad / (GEMM_NT * 16 * wpb), g.S), block(wpb * 64);
     const int ksteps = g.Kpad / GEMM_KSTEP;
     const u32x4 *w = static_cast<const u32x4 *>(Wp);
@@ -475,21 +574,22 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     // With a pair of events the launch itself carries them: they take the kernel's own begin and end
     // timestamps (what a profiler reports), not the time of extra packets around it.
     const bool timed = ev_start && ev_stop;
-#define POSS_GEMM_LAUNCH(MT, W, FUSE, PFV, FARG)                                                              \
+#define POSS_GEMM_LAUNCH(MT, W, FUSE, PFV, HD, FARG)                                                          \
     do {                                                                                                      \
         if (timed)                                                                                            \
-            hipExtLaunchKernelGGL((gemm_stream_kernel<T, MT, W, FUSE, PFV>), grid, block, 0, st, ev_start,    \
-                                  ev_stop, 0, w, x, ldx, part, g.M, g.K, g.Npad, ksteps, act, FARG);          \
+            hipExtLaunchKernelGGL((gemm_stream_kernel<T, MT, W, FUSE, PFV, HD>), grid, block, 0, st, ev_start, \
+                                  ev_stop, 0, w, x, ldx, part, g.M, g.K, g.Npad, ksteps, act, FARG, he);      \
         else                                                                                                  \
-            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, W, FUSE, PFV>), grid, block, 0, st, w, x, ldx, part, \
-                               g.M, g.K, g.Npad, ksteps, act, FARG);                                          \
+            hipLaunchKernelGGL((gemm_stream_kernel<T, MT, W, FUSE, PFV, HD>), grid, block, 0, st, w, x, ldx, part, \
+                               g.M, g.K, g.Npad, ksteps, act, FARG, he);                                      \
     } while (0)
 #define POSS_GEMM_CASE(MT)                                                                                    \
     do {                                                                                                      \
-        if (fuse_silu) { if (deep) POSS_GEMM_LAUNCH(MT, 4, true, 8, epi.F); else POSS_GEMM_LAUNCH(MT, 4, true, 4, epi.F); } \
-        else if (wide) POSS_GEMM_LAUNCH(MT, 8, false, 4, 0);                                                  \
-        else if (deep) POSS_GEMM_LAUNCH(MT, 4, false, 8, 0);                                                  \
-        else POSS_GEMM_LAUNCH(MT, 4, false, 4, 0);                                                            \
+        if (fuse_silu) { if (deep) POSS_GEMM_LAUNCH(MT, 4, true, 8, false, epi.F); else POSS_GEMM_LAUNCH(MT, 4, true, 4, false, epi.F); } \
+        else if (head) { if (wide) POSS_GEMM_LAUNCH(MT, 8, false, 4, true, 0); else POSS_GEMM_LAUNCH(MT, 4, false, 4, true, 0); } \
+        else if (wide) POSS_GEMM_LAUNCH(MT, 8, false, 4, false, 0);                                           \
+        else if (deep) POSS_GEMM_LAUNCH(MT, 4, false, 8, false, 0);                                           \
+        else POSS_GEMM_LAUNCH(MT, 4, false, 4, false, 0);                                                     \
     } while (0)
     switch (g.Mpad / 16) {
         case 1: POSS_GEMM_CASE(1); break;
@@ -511,6 +611,10 @@ static bool gemm_args_ok(const GemmShape &g, const void *Wp, const void *X, cons
         case EPI_ROPE_KV: return e.q && e.cs && e.slot && e.kv.k && e.kv.vt && e.kv.page_table;
         case EPI_RESIDUAL: return e.h && (!e.gain || e.u);
         case EPI_SILU: return e.act != nullptr;
+        case EPI_HEAD:
+            if (g.S != 1 || g.N < 1) return false;
+            if (e.head_mode == HEAD_ARGMAX) return e.pv && e.pi;
+            return e.head_mode == HEAD_TOPK && e.seg_out && e.head_k >= 1 && e.head_k <= TOPK_MAXK;
         default: return false;
     }
 }
@@ -520,6 +624,7 @@ bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int 
     if (!gemm_args_ok(g, Wp, X, part, epi)) return false;
     if (defer_epilogue && epi.mode != EPI_ROPE_KV) return false;       // only that epilogue can be launched by row range
     if (dt == DT_F32) {
+        if (epi.mode == EPI_HEAD) return false;          // float32 storage reduces its logits with the two-stage kernels
         dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
         if (ev_start && ev_stop)
             hipExtLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, ev_start, ev_stop, 0, static_cast<const float *>(Wp),

@@ -22,7 +22,6 @@ namespace poss {
 // the bound (long runs of equal values).
 // Either way thread r < k ends up with the r-th best, (-inf, 0x7fffffff...) where fewer than k exist.
 constexpr int TOPK_SEG = 2048;
-constexpr int TOPK_MAXK = 16;
 constexpr int TOPK_CAND = 256;
 struct __attribute__((aligned(16))) TopkLds {
     float tmax[256];
@@ -148,13 +147,15 @@ __global__ __launch_bounds__(256) void topk_seg_kernel(const float *__restrict__
 
 // stage 2: one workgroup per row merges the segments: lse over the segment records, then the k
 // best of the n_seg * k candidates; writes token ids and log-probabilities (value - lse).
-constexpr int TOPK_MERGE_NV = 8;                          // up to 2048 candidates (128 segments x 16)
+// NV candidates per thread: 8 (up to 2048: the records of topk_seg_kernel), 32 or 64 (the records of a Head GEMM,
+// one per column tile: up to 1002 x 16)
+template <int TOPK_MERGE_NV>
 __global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict__ seg_out, int n_seg, int k,
                                                          int32_t *__restrict__ out_id, float *__restrict__ out_logp) {
     __shared__ TopkLds lds;
     __shared__ float red[17];
     const int row = blockIdx.x, nc = n_seg * k;
-    constexpr int REC = 2 + 2 * TOPK_MAXK;
+    constexpr int REC = TOPK_REC;
     const float *recs = seg_out + (size_t)row * n_seg * REC;
     // Every load is issued before the first reduction, unconditionally (an entry that does not exist
     // reads slot 0 of segment 0 and is discarded afterwards): one trip to memory, not one per step.
@@ -192,15 +193,25 @@ __global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict
     }
 }
 
+void launch_topk_merge(const float *seg_records, int n_seg, int rows, int k, int32_t *out_id, float *out_logp, hipStream_t st) {
+    const int nc = n_seg * k;
+    if (nc <= 8 * 256)
+        hipLaunchKernelGGL((topk_merge_kernel<8>), dim3(rows), dim3(256), 0, st, seg_records, n_seg, k, out_id, out_logp);
+    else if (nc <= 32 * 256)
+        hipLaunchKernelGGL((topk_merge_kernel<32>), dim3(rows), dim3(256), 0, st, seg_records, n_seg, k, out_id, out_logp);
+    else                                                   // nc <= 64 * 256: checked when the context is configured
+        hipLaunchKernelGGL((topk_merge_kernel<64>), dim3(rows), dim3(256), 0, st, seg_records, n_seg, k, out_id, out_logp);
+}
+
 void launch_topk_logsoftmax(const float *logits, int ld, int rows, int vocab, int k, float *seg_scratch,
                             int32_t *out_id, float *out_logp, hipStream_t st) {
     const int n_seg = (vocab + TOPK_SEG - 1) / TOPK_SEG;
     hipLaunchKernelGGL(topk_seg_kernel, dim3(n_seg, rows), dim3(256), 0, st, logits, ld, vocab, k, n_seg, seg_scratch);
-    hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(256), 0, st, seg_scratch, n_seg, k, out_id, out_logp);
+    launch_topk_merge(seg_scratch, n_seg, rows, k, out_id, out_logp, st);
 }
 
-size_t topk_scratch_floats(int rows, int vocab) {
-    return (size_t)rows * ((vocab + TOPK_SEG - 1) / TOPK_SEG) * (2 + 2 * TOPK_MAXK);
+size_t topk_scratch_floats(int rows, int vocab) {      // the Head GEMM's column tiles are the finer segmentation
+    return (size_t)rows * head_segments_max(vocab) * TOPK_REC;
 }
 
 // ------------------------------------------------------------------ expansion of one depth
