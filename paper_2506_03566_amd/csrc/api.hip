@@ -280,11 +280,11 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
 
 // ------------------------------------------------------------------------------------------ GEMM wrapper
 GemmShape run_gemm(poss_ctx *c, const void *Wp, int N, int K, const void *X, int ldx, int M, float *part,
-                   bool single_split, EpiArgs epi, bool defer_epilogue = false) {
+                   bool single_split, EpiArgs epi, const RopeRanges *ranges = nullptr) {
     GemmShape g = gemm_plan(c->md.dt, M, N, K, single_split ? 1 : c->gemm_target_wgs);
     const bool prof = c->prof_on && c->prof_n < PROFILE_EVENTS;
     if (!launch_gemm(c->md.dt, g, Wp, X, ldx, part, epi, c->md.eps, c->st, prof ? c->prof_ev[2 * c->prof_n] : nullptr,
-                     prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr, defer_epilogue))
+                     prof ? c->prof_ev[2 * c->prof_n + 1] : nullptr, ranges))
         c->launch_refused = true;                   // reported by the next call that waits for the stream
     if (prof) {
         ++c->prof_n;
@@ -320,15 +320,14 @@ void run_layer(poss_ctx *c, const LayerW &w, const std::vector<Seg> &segs, int r
     if (one) {
         run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false, e);
     } else {
-        // one weight stream for every sequence, then each sequence's rows go into its own cache
-        const GemmShape g = run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false, e, true);
+        // one weight stream for every sequence, each sequence's rows into its own cache
         RopeRanges rr;
         rr.n = 0;
         for (const Seg &sg : segs) {
             if (sg.nq > 0) { rr.r0[rr.n] = sg.q0; rr.r1[rr.n] = sg.q0 + sg.nq; rr.rows_q[rr.n] = sg.q0 + sg.nq; rr.kv[rr.n] = *sg.kv; ++rr.n; }
             if (sg.nx > 0) { rr.r0[rr.n] = sg.x0; rr.r1[rr.n] = sg.x0 + sg.nx; rr.rows_q[rr.n] = 0; rr.kv[rr.n] = *sg.kv; ++rr.n; }
         }
-        if (!launch_rope_kv_epilogue(md.dt, g, c->part, e, rr, c->st)) c->launch_refused = true;
+        run_gemm(c, w.wqkv, qd + 2 * kd, md.d, c->u, md.d, rows_all, c->part, false, e, &rr);
     }
     if (rows_q == 0) return;
     {
@@ -488,7 +487,7 @@ void pack_layer(poss_ctx *c, const void *const *src, const std::vector<void *> &
     const int dt = cf.dtype, d = cf.d_model, qd = cf.n_q_heads * cf.head_dim, kd = cf.n_kv_heads * cf.head_dim, F = cf.d_ffn;
     const size_t es = esize(cf);
     (void)hipMemcpyAsync(dst[base + 0], src[0], d * es, hipMemcpyDeviceToDevice, c->st);
-    launch_pack(dt, PackSrc{{src[1], src[2], src[3]}, {qd, kd, kd}}, d, dst[base + 1], c->st);
+    launch_pack(dt, PackSrc{{src[1], src[2], src[3]}, {qd, kd, kd}, 0, dt == DT_F32 ? 0 : cf.head_dim}, d, dst[base + 1], c->st);
     launch_pack(dt, PackSrc{{src[4], nullptr, nullptr}, {d, 0, 0}}, qd, dst[base + 2], c->st);
     (void)hipMemcpyAsync(dst[base + 3], src[5], d * es, hipMemcpyDeviceToDevice, c->st);
     launch_pack(dt, PackSrc{{src[6], src[7], nullptr}, {F, F, 0}, 1}, d, dst[base + 4], c->st);

@@ -52,6 +52,8 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs);
 struct PackSrc {
     const void *ptr[3]; int rows[3];   // up to three matrices stacked along N
     int interleave16;                  // 1: ptr[0]/ptr[1] alternate in groups of 16 rows (gate | up per 32-column wave tile)
+    int rope_dh;                       // > 0 (16-bit types): rows are heads of rope_dh dims; inside each head the columns are permuted so
+                                       // that a 32-column wave tile holds dims [16j, 16j+16) and their rotary partners [16j + dh/2, ..)
 };
 void launch_pack(int dt, const PackSrc &src, int K, void *dst, hipStream_t st);
 static inline int gate_up_rows(int F) { return 2 * round_up(F, 16); }
@@ -94,6 +96,7 @@ struct EpiArgs {
     // EPI_ROPE_KV: columns are [q heads | k heads | v heads]; rows < rows_q get a rotated query,
     // every row its rotated key and its value written to cache slot slot[m]
     int rows_q; const float2 *cs; const int32_t *slot; void *q; KVCache kv; int hq, hkv, dh;
+    int rope_packed;   // set by the launcher: the columns of a head are in the packed order of PackSrc::rope_dh
     // EPI_RESIDUAL: h[m][n] = sum + bias[n] + (residual ? h[m][n] : 0); h_copy likewise; then, if
     // gain != nullptr, u[m][n] = T(rmsnorm(h[m]) * gain[n]) - the operand of the next GEMM
     float *h; const void *bias; int residual; float *h_copy; const void *gain; void *u;
@@ -109,21 +112,19 @@ struct EpiArgs {
 // part must hold S * Mpad * Npad floats.  X row-major [M][ldx] of dtype dt.  ev_start / ev_stop, if both
 // given, receive the begin and end timestamps of the weight-streaming kernel itself (per-launch timing).
 // Returns false, launching nothing, if a pointer the chosen epilogue writes through is null.
-// defer_epilogue (EPI_ROPE_KV only): the partial planes are left for launch_rope_kv_epilogue calls.
+// EPI_ROPE_KV (the QKV projection; 16-bit types: one kernel that needs no partial planes, weights packed with
+// PackSrc::rope_dh): `ranges`, if given, sends row ranges [r0, r1) each into its own cache with its own query limit
+// (rows below rows_q get a rotated query) - several sequences batched into one launch; row indices stay those of the
+// launch (epi.cs, epi.slot, epi.q are indexed by them), epi.kv and epi.rows_q are ignored, blk0 is filled in here.
+constexpr int ROPE_MAX_RANGES = 16;
+struct RopeRanges { int n; int r0[ROPE_MAX_RANGES], r1[ROPE_MAX_RANGES], rows_q[ROPE_MAX_RANGES], blk0[ROPE_MAX_RANGES]; KVCache kv[ROPE_MAX_RANGES]; };
 bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
                  const EpiArgs &epi, float rms_eps, hipStream_t st, hipEvent_t ev_start = nullptr,
-                 hipEvent_t ev_stop = nullptr, bool defer_epilogue = false);
+                 hipEvent_t ev_stop = nullptr, const RopeRanges *ranges = nullptr);
 // Column tiles ("segments") of an unsplit launch of this shape, i.e. records per row an EPI_HEAD launch writes;
 // head_segments_max bounds it for any row count.
 int gemm_head_segments(const GemmShape &g);
 static inline int head_segments_max(int vocab) { return gemm_npad(vocab) / GEMM_BLOCK_N; }
-// The RoPE + KV-write epilogue of a deferred launch over row ranges [r0, r1), each into its own cache and
-// with its own query limit (rows below rows_q get a rotated query), in one launch: several sequences batched
-// into one GEMM each take their own rows into their own cache.  Row indices stay those of the GEMM launch
-// (epi.cs, epi.slot, epi.q are indexed by them); epi.kv and epi.rows_q are ignored.  blk0 is filled in here.
-constexpr int ROPE_MAX_RANGES = 16;
-struct RopeRanges { int n; int r0[ROPE_MAX_RANGES], r1[ROPE_MAX_RANGES], rows_q[ROPE_MAX_RANGES], blk0[ROPE_MAX_RANGES]; KVCache kv[ROPE_MAX_RANGES]; };
-bool launch_rope_kv_epilogue(int dt, const GemmShape &g, const float *part, const EpiArgs &epi, RopeRanges ranges, hipStream_t st);
 
 // ---------------------------------------------------------------- launchers: elementwise
 // also writes the rotary table of the rows: cs[m][i] = (cos, sin)(pos[m] * theta^(-2i/dh)), angle formed in float64

@@ -101,13 +101,16 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
         const int half = e.dh >> 1, c = t & 63;
         const int hb = n0 + (c / half) * e.dh, i = c % half, gh = hb / e.dh;
         if (gh >= e.hq + 2 * e.hkv) return;
+        // columns of the pair: natural order (i, i + dh/2), or the packed order of PackSrc::rope_dh, in which a 32-column
+        // group holds dims [16j, 16j+16) followed by their partners
+        const int c1 = e.rope_packed ? hb + (i >> 4) * 32 + (i & 15) : hb + i, c2 = e.rope_packed ? c1 + 16 : c1 + half;
         T *kc = static_cast<T *>(e.kv.k), *vc = static_cast<T *>(e.kv.vt), *q = static_cast<T *>(e.q);
         for (int r = r_begin + (t >> 6); r < r_end; r += 4) {
             if (gh < e.hq && r >= e.rows_q) continue;
             const float2 cs = e.cs[r * half + i];          // requested together with the planes
             const int sl = e.slot[r];
-            const float x1 = sum_planes(part, plane, S, (size_t)r * Npad + hb + i);
-            const float x2 = sum_planes(part, plane, S, (size_t)r * Npad + hb + i + half);
+            const float x1 = sum_planes(part, plane, S, (size_t)r * Npad + c1);
+            const float x2 = sum_planes(part, plane, S, (size_t)r * Npad + c2);
             if (gh < e.hq) {
                 T *dst = q + ((size_t)r * e.hq + gh) * e.dh;
                 dst[i] = from_f<T>(x1 * cs.x - x2 * cs.y);
@@ -391,6 +394,129 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// The QKV projection with its epilogue inside: K split INSIDE the workgroup.  One 32-column tile per workgroup, the
+// k-steps dealt to its four waves in contiguous quarters; a wave loads its own operands straight into registers (an A
+// fragment of v_mfma 16x16x32 is 16 contiguous bytes of one activation row, and with K split among the waves no two of
+// them want the same fragment: no LDS hop, no barrier in the loop).  The four partial tiles meet in LDS and are added
+// in wave order, so the workgroup holds finished sums and applies the rotary embedding and writes queries, keys and
+// values itself: no partial planes, no epilogue kernel.  The weight rows are packed so that the two 16-column tiles
+// of a wave are dims [16j, 16j+16) and [16j + dh/2, ..) of one head: a lane owns both members of a rotary pair.
+// Bitwise repeatable; a row's result does not depend on the rows around it.
+struct QkvEpi { const float2 *cs; const int32_t *slot; void *q; int hq, hkv, dh; RopeRanges rr; };
+
+template <typename T, int MT, int PF>
+__global__ __launch_bounds__(256) void gemm_qkv_rope_kernel(const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx,
+                                                           int M, int K, int ksteps_total, QkvEpi e) {
+    constexpr int NTILE = MT * GEMM_NT;
+    __shared__ f32x4 red[4][NTILE][64];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, tile = blockIdx.x;
+    const int w0 = wave * ksteps_total / 4, w1 = (wave + 1) * ksteps_total / 4, n_w = w1 - w0;
+    const u32x4 *wp = Wp + ((size_t)tile * ksteps_total + w0) * (GEMM_NT * 64) + lane;      // this wave's first k-step
+    const T *xp[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 16 + (lane & 15);
+        xp[mt] = X + (size_t)(m < M ? m : M - 1) * ldx + (size_t)w0 * GEMM_KSTEP + (lane >> 4) * 8;   // rows beyond M repeat the last row
+    }
+    f32x4 acc[MT][GEMM_NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    int done = 0;
+    if (w1 * GEMM_KSTEP <= K && n_w >= PF) {             // no k-step of this wave reaches beyond K: loads need no mask
+        u32x4 wr[PF][GEMM_NT], ar[PF][MT];
+        auto load_step = [&](int p, int i) {             // k-step w0 + i into ring slot p (p static after unrolling)
+#pragma unroll
+            for (int nt = 0; nt < GEMM_NT; ++nt) wr[p][nt] = __builtin_nontemporal_load(wp + (size_t)i * (GEMM_NT * 64) + nt * 64);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) ar[p][mt] = *reinterpret_cast<const u32x4 *>(xp[mt] + (size_t)i * GEMM_KSTEP);
+        };
+#pragma unroll
+        for (int p = 0; p < PF; ++p) load_step(p, p);
+        const int groups = n_w / PF;
+        auto group = [&](auto more_tag, int g) {
+            constexpr bool MORE = decltype(more_tag)::value;
+#pragma unroll
+            for (int p = 0; p < PF; ++p) {
+                u32x4 w[GEMM_NT], a[MT];
+#pragma unroll
+                for (int nt = 0; nt < GEMM_NT; ++nt) w[nt] = wr[p][nt];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) a[mt] = ar[p][mt];
+                if constexpr (MORE) load_step(p, (g + 1) * PF + p);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[mt], w[nt], acc[mt][nt]);
+                __builtin_amdgcn_sched_barrier(0);       // one k-step at a time: loads stay in ring order
+            }
+        };
+        for (int g = 0; g + 1 < groups; ++g) group(std::true_type{}, g);
+        group(std::false_type{}, groups - 1);
+        done = groups * PF;
+    }
+    for (int i = done; i < n_w; ++i) {                   // what the ring did not cover; fragments beyond K are zero
+        const bool ok = (w0 + i) * GEMM_KSTEP + (lane >> 4) * 8 < K;
+        u32x4 w[GEMM_NT], a[MT];
+#pragma unroll
+        for (int nt = 0; nt < GEMM_NT; ++nt) w[nt] = wp[(size_t)i * (GEMM_NT * 64) + nt * 64];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(ok ? xp[mt] + (size_t)i * GEMM_KSTEP : xp[mt] - (size_t)w0 * GEMM_KSTEP - (lane >> 4) * 8);
+            a[mt] = ok ? v : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[mt], w[nt], acc[mt][nt]);
+    }
+
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < GEMM_NT; ++nt) red[wave][mt * GEMM_NT + nt][lane] = acc[mt][nt];
+    __syncthreads();
+    // D tile: lane -> column c = lane % 16, register r -> row 4 * (lane / 16) + r.  Wave w finishes row tiles w, w + 4.
+    const int half = e.dh >> 1, tph = half >> 4;          // 32-column tiles per head
+    const int gh = tile / tph, i = (tile % tph) * 16 + (lane & 15);
+    if (gh >= e.hq + 2 * e.hkv) return;                   // padding columns
+    T *q = static_cast<T *>(e.q);
+    for (int mt = wave; mt < MT; mt += 4) {
+        const f32x4 x1 = ((red[0][mt * GEMM_NT][lane] + red[1][mt * GEMM_NT][lane]) + red[2][mt * GEMM_NT][lane]) + red[3][mt * GEMM_NT][lane];
+        const f32x4 x2 = ((red[0][mt * GEMM_NT + 1][lane] + red[1][mt * GEMM_NT + 1][lane]) + red[2][mt * GEMM_NT + 1][lane]) + red[3][mt * GEMM_NT + 1][lane];
+        for (int qi = 0; qi < e.rr.n; ++qi) {             // (workgroup-uniform) the sequences that share this launch
+            const int r0 = e.rr.r0[qi], r1 = e.rr.r1[qi], rows_q = e.rr.rows_q[qi];
+            const KVCache kv = e.rr.kv[qi];
+            T *kc = static_cast<T *>(kv.k), *vc = static_cast<T *>(kv.vt);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = mt * 16 + 4 * (lane >> 4) + r;
+                if (m < r0 || m >= r1 || m >= M) continue;
+                const float a = x1[r], b = x2[r];
+                if (gh < e.hq) {
+                    if (m >= rows_q) continue;
+                    const float2 cs = e.cs[m * half + i];
+                    T *dst = q + ((size_t)m * e.hq + gh) * e.dh;
+                    dst[i] = from_f<T>(a * cs.x - b * cs.y);
+                    dst[i + half] = from_f<T>(b * cs.x + a * cs.y);
+                } else if (gh < e.hq + e.hkv) {
+                    const float2 cs = e.cs[m * half + i];
+                    T *dst = kc + k_offset(kv, e.slot[m], gh - e.hq, e.hkv, e.dh);
+                    dst[i] = from_f<T>(a * cs.x - b * cs.y);
+                    dst[i + half] = from_f<T>(b * cs.x + a * cs.y);
+                } else {
+                    const int vh = gh - e.hq - e.hkv, sl = e.slot[m];
+                    vc[vt_offset(kv, sl, vh, e.hkv, e.dh, i)] = from_f<T>(a);
+                    vc[vt_offset(kv, sl, vh, e.hkv, e.dh, i + half)] = from_f<T>(b);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Residual epilogue, one workgroup per row: h = sum of planes (+ bias) (+ h); then, because the
 // whole row is in this workgroup, the RMSNorm that feeds the next GEMM right away:
 // u = T(h / sqrt(mean(h^2) + eps) * gain).  Saves a kernel per norm.
@@ -555,9 +681,42 @@ static void launch_epilogue_t(const GemmShape &g, const float *part, const EpiAr
     }
 }
 
+// The QKV projection of 16-bit types: one kernel, rotary embedding and cache writes included.
+template <typename T>
+static void launch_qkv_rope_t(const GemmShape &g, const void *Wp, const void *X, int ldx, const EpiArgs &epi, const RopeRanges &rr,
+                              hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    QkvEpi qe{epi.cs, epi.slot, epi.q, epi.hq, epi.hkv, epi.dh, rr};
+    dim3 grid(g.Npad / (GEMM_NT * 16)), block(256);
+    const int ksteps = g.Kpad / GEMM_KSTEP;
+    const u32x4 *w = static_cast<const u32x4 *>(Wp);
+    const T *x = static_cast<const T *>(X);
+#define POSS_QKV_LAUNCH(MT, PFV)                                                                              \
+    do {                                                                                                      \
+        if (ev_start && ev_stop)                                                                              \
+            hipExtLaunchKernelGGL((gemm_qkv_rope_kernel<T, MT, PFV>), grid, block, 0, st, ev_start, ev_stop, 0, w, x, ldx, g.M, g.K, ksteps, qe); \
+        else                                                                                                  \
+            hipLaunchKernelGGL((gemm_qkv_rope_kernel<T, MT, PFV>), grid, block, 0, st, w, x, ldx, g.M, g.K, ksteps, qe); \
+    } while (0)
+    switch (g.Mpad / 16) {
+        case 1: POSS_QKV_LAUNCH(1, 8); break;
+        case 2: POSS_QKV_LAUNCH(2, 8); break;
+        case 4: POSS_QKV_LAUNCH(4, 8); break;
+        case 6: POSS_QKV_LAUNCH(6, 4); break;
+        default: POSS_QKV_LAUNCH(8, 4); break;
+    }
+#undef POSS_QKV_LAUNCH
+}
+
 template <typename T>
 static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                          const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop, bool defer_epilogue) {
+                          const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop, const RopeRanges *rr) {
+    // The QKV projection of at most 32 rows (draft passes, plain decoding) runs as one kernel with the K split inside the
+    // workgroup; with more rows that kernel's activation traffic (every workgroup reads every row over the whole K)
+    // outweighs the partial planes and the epilogue kernel it saves: 25 us against 13.6 + 4.9 us at 61 rows of the 8B shape.
+    if (epi.mode == EPI_ROPE_KV && g.Mpad <= 32) {
+        launch_qkv_rope_t<T>(g, Wp, X, ldx, epi, *rr, st, ev_start, ev_stop);
+        return;
+    }
     // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
     const bool fuse_silu = epi.mode == EPI_SILU && g.S == 1;
     const bool head = epi.mode == EPI_HEAD;
@@ -600,7 +759,16 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     }
 #undef POSS_GEMM_CASE
 #undef POSS_GEMM_LAUNCH
-    if (!defer_epilogue) launch_epilogue_t<T>(g, part, epi, eps, fuse_silu, st);
+    if (epi.mode == EPI_ROPE_KV) {                       // rotary + cache writes per row range, one launch
+        EpiArgs pe = epi;
+        pe.rope_packed = 1;
+        const size_t plane = (size_t)g.Mpad * g.Npad;
+        const int blocks = rr->blk0[rr->n - 1] + (rr->r1[rr->n - 1] - rr->r0[rr->n - 1] + EPI_ROWS_PAIR - 1) / EPI_ROWS_PAIR;
+        hipLaunchKernelGGL((epilogue_rope_ranges_kernel<T>), dim3(g.Npad / GEMM_BLOCK_N, blocks), dim3(256), 0, st, part, plane, g.S,
+                           g.Npad, g.N, *rr, pe);
+        return;
+    }
+    launch_epilogue_t<T>(g, part, epi, eps, fuse_silu, st);
 }
 
 // Refuse, on the host, argument sets that would make a kernel write through a null pointer.
@@ -608,7 +776,7 @@ static bool gemm_args_ok(const GemmShape &g, const void *Wp, const void *X, cons
     if (!Wp || !X || !part || g.M < 1 || g.M > MAX_ROWS || g.S < 1) return false;
     switch (e.mode) {
         case EPI_PLAIN: return e.out || g.S == 1;          // unsplit: plane 0 is the result
-        case EPI_ROPE_KV: return e.q && e.cs && e.slot && e.kv.k && e.kv.vt && e.kv.page_table;
+        case EPI_ROPE_KV: return e.q && e.cs && e.slot && (e.dh == 64 || e.dh == 128 || !e.dh);   // caches: checked per range
         case EPI_RESIDUAL: return e.h && (!e.gain || e.u);
         case EPI_SILU: return e.act != nullptr;
         case EPI_HEAD:
@@ -619,31 +787,8 @@ static bool gemm_args_ok(const GemmShape &g, const void *Wp, const void *X, cons
     }
 }
 
-bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
-                 const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop, bool defer_epilogue) {
-    if (!gemm_args_ok(g, Wp, X, part, epi)) return false;
-    if (defer_epilogue && epi.mode != EPI_ROPE_KV) return false;       // only that epilogue can be launched by row range
-    if (dt == DT_F32) {
-        if (epi.mode == EPI_HEAD) return false;          // float32 storage reduces its logits with the two-stage kernels
-        dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
-        if (ev_start && ev_stop)
-            hipExtLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, ev_start, ev_stop, 0, static_cast<const float *>(Wp),
-                                  static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
-        else
-            hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
-                               static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
-        if (!defer_epilogue) launch_epilogue_t<float>(g, part, epi, eps, false, st);
-    } else if (dt == DT_BF16) {
-        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st, ev_start, ev_stop, defer_epilogue);
-    } else {
-        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st, ev_start, ev_stop, defer_epilogue);
-    }
-    return true;
-}
-
-bool launch_rope_kv_epilogue(int dt, const GemmShape &g, const float *part, const EpiArgs &epi, RopeRanges rr, hipStream_t st) {
-    if (!part || epi.mode != EPI_ROPE_KV || rr.n < 1 || rr.n > ROPE_MAX_RANGES) return false;
-    if (!epi.q || !epi.cs || !epi.slot) return false;
+static bool ranges_ok(const GemmShape &g, const EpiArgs &epi, RopeRanges &rr) {
+    if (rr.n < 1 || rr.n > ROPE_MAX_RANGES) return false;
     int blocks = 0;
     for (int i = 0; i < rr.n; ++i) {
         if (rr.r0[i] < 0 || rr.r1[i] > g.M || rr.r0[i] >= rr.r1[i]) return false;
@@ -651,14 +796,43 @@ bool launch_rope_kv_epilogue(int dt, const GemmShape &g, const float *part, cons
         rr.blk0[i] = blocks;
         blocks += (rr.r1[i] - rr.r0[i] + EPI_ROWS_PAIR - 1) / EPI_ROWS_PAIR;
     }
-    const size_t plane = (size_t)g.Mpad * g.Npad;
-    dim3 grid(g.Npad / GEMM_BLOCK_N, blocks), eb(256);
-    if (dt == DT_F32)
-        hipLaunchKernelGGL((epilogue_rope_ranges_kernel<float>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, rr, epi);
-    else if (dt == DT_BF16)
-        hipLaunchKernelGGL((epilogue_rope_ranges_kernel<bf16_t>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, rr, epi);
-    else
-        hipLaunchKernelGGL((epilogue_rope_ranges_kernel<f16_t>), grid, eb, 0, st, part, plane, g.S, g.Npad, g.N, rr, epi);
+    (void)epi;
+    return true;
+}
+
+bool launch_gemm(int dt, const GemmShape &g, const void *Wp, const void *X, int ldx, float *part,
+                 const EpiArgs &epi, float eps, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop, const RopeRanges *ranges) {
+    if (!gemm_args_ok(g, Wp, X, part, epi)) return false;
+    if (ranges && epi.mode != EPI_ROPE_KV) return false;               // only that epilogue works by row range
+    RopeRanges rr;
+    if (epi.mode == EPI_ROPE_KV) {
+        if (ranges) rr = *ranges;
+        else { rr.n = 1; rr.r0[0] = 0; rr.r1[0] = g.M; rr.rows_q[0] = epi.rows_q; rr.kv[0] = epi.kv; }
+        if (!ranges_ok(g, epi, rr)) return false;
+    }
+    if (dt == DT_F32) {
+        if (epi.mode == EPI_HEAD) return false;          // float32 storage reduces its logits with the two-stage kernels
+        if (!part) return false;
+        dim3 grid((g.Npad + 127) / 128, g.Mpad), block(128);
+        if (ev_start && ev_stop)
+            hipExtLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, ev_start, ev_stop, 0, static_cast<const float *>(Wp),
+                                  static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
+        else
+            hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, static_cast<const float *>(Wp),
+                               static_cast<const float *>(X), ldx, part, g.M, g.N, g.Npad, g.K);
+        if (epi.mode == EPI_ROPE_KV) {                   // rotary + cache writes per row range, one launch
+            const size_t plane = (size_t)g.Mpad * g.Npad;
+            int blocks = rr.blk0[rr.n - 1] + (rr.r1[rr.n - 1] - rr.r0[rr.n - 1] + EPI_ROWS_PAIR - 1) / EPI_ROWS_PAIR;
+            dim3 egrid(g.Npad / GEMM_BLOCK_N, blocks), eb(256);
+            hipLaunchKernelGGL((epilogue_rope_ranges_kernel<float>), egrid, eb, 0, st, part, plane, g.S, g.Npad, g.N, rr, epi);
+        } else {
+            launch_epilogue_t<float>(g, part, epi, eps, false, st);
+        }
+    } else if (dt == DT_BF16) {
+        launch_gemm_t<bf16_t>(g, Wp, X, ldx, part, epi, eps, st, ev_start, ev_stop, epi.mode == EPI_ROPE_KV ? &rr : nullptr);
+    } else {
+        launch_gemm_t<f16_t>(g, Wp, X, ldx, part, epi, eps, st, ev_start, ev_stop, epi.mode == EPI_ROPE_KV ? &rr : nullptr);
+    }
     return true;
 }
 
@@ -670,6 +844,10 @@ __device__ __forceinline__ bool pack_source_row(const PackSrc &src, int n, int &
         const int w = n & 31;
         which = w >> 4; row = (n >> 5) * 16 + (w & 15);
         return row < src.rows[which];
+    }
+    if (src.rope_dh > 0) {           // packed column p of a head -> dim (p / 32) * 16 + p % 16 + (p / 16 % 2) * dh / 2
+        const int dh = src.rope_dh, p = n % dh;
+        n = n - p + (p >> 5) * 16 + (p & 15) + ((p >> 4) & 1) * (dh >> 1);
     }
     for (which = 0; which < 3; ++which) {
         if (n < src.rows[which]) { row = n; return true; }
