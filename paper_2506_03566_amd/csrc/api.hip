@@ -310,7 +310,7 @@ struct Seg { int b; const KVCache *kv; int q0, nq, x0, nx, n_prefix, region_len;
 // own cache.  On entry c->u holds T(rmsnorm(h) * attn_norm) and c->cs the rotary table of the rows;
 // on exit c->h is updated and c->u holds T(rmsnorm(h) * next_gain).
 void run_layer(poss_ctx *c, const LayerW &w, const std::vector<Seg> &segs, int rows_all, int rows_q, const RowMeta &rm,
-               const void *next_gain, float *h_copy) {
+               const void *next_gain, float *h_copy, bool drafter = false) {
     const ModelDims &md = c->md;
     const int qd = md.hq * md.dh, kd = md.hkv * md.dh;
     EpiArgs e{};
@@ -335,7 +335,9 @@ void run_layer(poss_ctx *c, const LayerW &w, const std::vector<Seg> &segs, int r
         int na = 0;
         for (const Seg &sg : segs)
             if (sg.nq > 0) as[na++] = AttnSeg{sg.q0, sg.nq, sg.n_prefix, sg.region_len, sg.kv};
-        launch_attention_batch(md, c->q, rm, as, na, c->attn_keys_per_split, c->attn_sc, c->attn_out, c->st);
+        // a specialist's pass: splits of at most 512 keys (few rows, its own cache); a tuning override applies to both
+        const int kps = c->attn_keys_per_split ? c->attn_keys_per_split : (drafter ? -512 : 0);
+        launch_attention_batch(md, c->q, rm, as, na, kps, c->attn_sc, c->attn_out, c->st);
     }
     run_gemm(c, w.wo, md.d, qd, c->attn_out, qd, rows_q, c->part, false, epi_residual(c, true, nullptr, nullptr, w.mlp_norm));
     EpiArgs es{};
@@ -451,7 +453,7 @@ void spec_pass(poss_ctx *c, int s, std::vector<SeqPlan> &plans, int depth_index,
     run_gemm(c, w.fc_w, md.d, 2 * md.d, c->xin, 2 * md.d, rows_all, c->part, false,
              epi_residual(c, false, c->cfg.fc_bias ? w.fc_b : nullptr, nullptr, w.layer.attn_norm));
     RowMeta rm{c->row_pos, c->row_slot, c->row_mask};
-    run_layer(c, w.layer, segs, rows_all, rows_q, rm, c->final_norm, fhat_out);
+    run_layer(c, w.layer, segs, rows_all, rows_q, rm, c->final_norm, fhat_out, true);
 }
 
 // Keys/values of committed pairs [spec_len[s], upto) of one sequence for specialist s, in chunks of MAX_ROWS rows.

@@ -109,11 +109,13 @@ __device__ __forceinline__ void attn_mfma_body(
     const T *kc = static_cast<const T *>(kv.k), *vc = static_cast<const T *>(kv.vt);
 
     // staging: K block = 32 consecutive token rows = 32*DH contiguous elements; V^T block = DH rows
-    // of 32 keys (64 bytes each, row stride P elements)
-    // ring of PFD iterations of key/value loads in flight: an iteration's arithmetic is much shorter
-    // than the latency of its loads, so one block of look-ahead would leave the loop latency-bound
-    constexpr int PFD = 2;
-    u32x4 kr[PFD][KPT], vr[PFD][VPT];
+    // of 32 keys (64 bytes each, row stride P elements).
+    // Key and value blocks travel global -> registers -> LDS in two rings of their own, two iterations deep (an
+    // iteration's arithmetic is much shorter than the latency of its loads).  Keys run one iteration AHEAD of values:
+    // the score MFMAs of iteration it + 1 are issued before the softmax of iteration it, so that the matrix pipe works
+    // while the vector ALU exponentiates (waves of a workgroup move in step from barrier to barrier: without this
+    // every wave of a SIMD would sit in its softmax at the same time, the matrix pipe idle).
+    u32x4 kr[2][KPT], vr[2][VPT];
     // The page-table entry of a block is fetched one call ahead of the block itself: read where it is
     // used, it would put a dependent trip to memory (and a wait for every load in flight) into each
     // iteration.  Calls go up in steps of KW blocks.
@@ -125,33 +127,41 @@ __device__ __forceinline__ void attn_mfma_body(
         const int b = min(bfirst + stage_blk, b1 - 1);
         return page_table_c[(b << 5) >> kv.page_shift];
     };
-    int pg_next = page_of(b0);
-    // pg_after: the entry for the call that follows (bfirst + KW), read by the caller
-    auto load_block = [&](auto slot_tag, int bfirst, int pg_after) {    // this thread's share of block bfirst + stage_blk
+    int pgk_next = page_of(b0), pgv_next = pgk_next;
+    // this thread's share of the keys / values of block bfirst + stage_blk; pg_after: the entry for the call that follows
+    auto load_k = [&](auto slot_tag, int bfirst, int pg_after) {
         constexpr int SLOT = decltype(slot_tag)::value;
         int b = bfirst + stage_blk;
         if (b >= b1) b = b1 - 1;                          // never predicated: reload a valid block, it is ignored
-        const int slot0 = b << 5;
-        const int pg = pg_next, off = slot0 & (P - 1);
-        pg_next = pg_after;
-        const size_t head_base = (size_t)(pg * hkv + kvh);
-        const T *kb = kc + (head_base * P + off) * DH;
-        const T *vb = vc + head_base * DH * P + off;
+        const int off = (b << 5) & (P - 1);
+        const T *kb = kc + ((size_t)(pgk_next * hkv + kvh) * P + off) * DH;
+        pgk_next = pg_after;
 #pragma unroll
         for (int i = 0; i < KPT; ++i) kr[SLOT][i] = *reinterpret_cast<const u32x4 *>(kb + (size_t)(stid + i * 256) * 8);
+    };
+    auto load_v = [&](auto slot_tag, int bfirst, int pg_after) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        int b = bfirst + stage_blk;
+        if (b >= b1) b = b1 - 1;
+        const int off = (b << 5) & (P - 1);
+        const T *vb = vc + (size_t)(pgv_next * hkv + kvh) * DH * P + off;
+        pgv_next = pg_after;
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             const int u = stid + i * 256;                 // unit: dh row u / 4, keys (u % 4) * 8 .. +8
             vr[SLOT][i] = *reinterpret_cast<const u32x4 *>(vb + (size_t)(u >> 2) * P + (u & 3) * 8);
         }
     };
-    auto store_block = [&](auto slot_tag, int buf) {
+    auto store_k = [&](auto slot_tag, int buf) {
         constexpr int SLOT = decltype(slot_tag)::value;
 #pragma unroll
         for (int i = 0; i < KPT; ++i) {
             const int u = stid + i * 256, row = u / (DH / 8), c8 = u % (DH / 8);
             *reinterpret_cast<u32x4 *>(&ks_lds[(buf * KW + stage_blk) * KBLK + row * KROW + c8 * 8]) = kr[SLOT][i];
         }
+    };
+    auto store_v = [&](auto slot_tag, int buf) {
+        constexpr int SLOT = decltype(slot_tag)::value;
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             // keys k0 = (u%4)*8 .. k0+7: key k sits at element (k%16)/4*8 + (k/16)*4 + k%4 of its row
@@ -172,42 +182,16 @@ __device__ __forceinline__ void attn_mfma_body(
         for (int dt = 0; dt < DT; ++dt) acc[rt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    auto static_for = [&](auto f) {                       // f(integral_constant<int, p>) for p < PFD
-        f(std::integral_constant<int, 0>{});
-        if constexpr (PFD > 1) f(std::integral_constant<int, 1>{});
-        if constexpr (PFD > 2) f(std::integral_constant<int, 2>{});
-        if constexpr (PFD > 3) f(std::integral_constant<int, 3>{});
-    };
-    static_for([&](auto p) { load_block(p, b0 + decltype(p)::value * KW, page_of(b0 + (decltype(p)::value + 1) * KW)); });
-    store_block(std::integral_constant<int, 0>{}, 0);
-    load_block(std::integral_constant<int, 0>{}, b0 + PFD * KW, page_of(b0 + (PFD + 1) * KW));
-    __syncthreads();
-    int buf = 0;
-    // iteration `it` (blocks bi .. bi+KW-1): compute from LDS buffer `buf`, move iteration it+1 (ring
-    // slot (it+1)%PFD) into the other buffer and refill that slot at once with iteration it+1+PFD.
-    // A slot is reloaded right behind the LDS stores that read it: its registers are never free in
-    // between (used as temporaries they made the compiler wait for every load in flight at the head
-    // of the loop), and the wait for a block's loads comes after an iteration's arithmetic, not before.
-    auto iteration = [&](auto slot_tag, int bi) {
-        constexpr int SLOT = decltype(slot_tag)::value;
-        // requested here, used by this iteration's refill: at the foot of the iteration the wait for the
-        // LDS stores ahead of the barrier would wait for this scalar load as well
-        const int pg_ahead = page_of(bi + (2 + PFD) * KW);
-        const int b = bi + kway;
-        if (b < b1) {                                     // wave-uniform
-        const int slot0 = b << 5;
-        const T *kbuf = &ks_lds[(buf * KW + kway) * KBLK], *vbuf = &vs_lds[(buf * KW + kway) * VBLK];
-        // S^T tiles: rows = keys slot0 + tt*16 + (0..15), columns = query rows of a tile of this wave
-        // every key fragment of the block is requested before the first MFMA, and the value fragments
-        // before the softmax: read where they are used, each pair of reads is waited for in turn
-        f32x4 s[RT][2];
-        u32x4 kf[2][KS], vf[DT];
+    // S^T tiles of one block for this wave's row tiles: rows = keys slot0 + tt*16 + (0..15), columns = query rows.
+    // Every key fragment of the block is requested before the first MFMA.
+    auto scores = [&](int buf, f32x4 (&s)[RT][2]) {
+        const T *kbuf = &ks_lds[(buf * KW + kway) * KBLK];
+        u32x4 kf[2][KS];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
                 kf[tt][ks] = *reinterpret_cast<const u32x4 *>(&kbuf[(tt * 16 + lr) * KROW + ks * 32 + lg * 8]);
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
 #pragma unroll
@@ -218,9 +202,45 @@ __device__ __forceinline__ void attn_mfma_body(
                 for (int rt = 0; rt < RT; ++rt)
                     s[rt][tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf[tt][ks]), qf[rt][ks], s[rt][tt]);
         }
+    };
+
+    typedef std::integral_constant<int, 0> S0;
+    typedef std::integral_constant<int, 1> S1;
+    // prologue: keys of iterations 0 and 1 and values of iteration 0 into LDS, the scores of iteration 0 formed,
+    // both rings refilled (keys up to iteration 3, values up to iteration 2)
+    load_k(S0{}, b0, page_of(b0 + KW));
+    load_k(S1{}, b0 + KW, page_of(b0 + 2 * KW));
+    load_v(S0{}, b0, page_of(b0 + KW));
+    load_v(S1{}, b0 + KW, page_of(b0 + 2 * KW));
+    store_k(S0{}, 0);
+    load_k(S0{}, b0 + 2 * KW, page_of(b0 + 3 * KW));
+    __syncthreads();
+    f32x4 s_cur[RT][2];
+    if (b0 + kway < b1) scores(0, s_cur);
+    store_k(S1{}, 1);
+    load_k(S1{}, b0 + 3 * KW, page_of(b0 + 4 * KW));
+    store_v(S0{}, 0);
+    load_v(S0{}, b0 + 2 * KW, page_of(b0 + 3 * KW));
+    __syncthreads();
+    // iteration `it` (blocks bi .. bi+KW-1, PAR = it % 2): scores of it + 1 (keys in LDS buffer PAR ^ 1), softmax of it,
+    // P V of it (values in buffer PAR); then keys of it + 2 go into key buffer PAR (last read by the scores of `it`, an
+    // iteration ago) and values of it + 1 into value buffer PAR ^ 1, and the two ring slots are refilled at once with
+    // iterations it + 4 (keys) and it + 3 (values).  A slot is reloaded right behind the LDS stores that read it: its
+    // registers are never free in between, and the wait for a block's loads comes after an iteration's arithmetic.
+    auto iteration = [&](auto par_tag, int bi) {
+        constexpr int PAR = decltype(par_tag)::value;
+        // requested here, used by this iteration's refills: at the foot of the iteration the wait for the
+        // LDS stores ahead of the barrier would wait for these scalar loads as well
+        const int pgk_ahead = page_of(bi + 5 * KW), pgv_ahead = page_of(bi + 4 * KW);
+        const int b = bi + kway;
+        f32x4 s_next[RT][2];
+        if (b + KW < b1) scores(PAR ^ 1, s_next);         // wave-uniform
+        if (b < b1) {                                     // wave-uniform
+        const int slot0 = b << 5;
+        const T *vbuf = &vs_lds[(PAR * KW + kway) * VBLK];
+        u32x4 vf[DT];
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) vf[dt] = *reinterpret_cast<const u32x4 *>(&vbuf[(dt * 16 + lr) * VROW + lg * 8]);
-        __builtin_amdgcn_sched_barrier(0);
         // lane holds keys slot0 + tt*16 + 4*lg + r of query row lr.  Scores are kept in the log2
         // domain (scale * log2 e folded into one factor) so that the exponentials are single
         // v_exp_f32 instructions; the softmax is VALU-bound, not MFMA-bound, at these sizes.
@@ -238,12 +258,12 @@ __device__ __forceinline__ void attn_mfma_body(
             float sv[8], bm = -INFINITY;
             if (slot0 + 32 <= n_prefix) {                // whole block inside the committed prefix
 #pragma unroll
-                for (int j = 0; j < 8; ++j) { sv[j] = s[rt][j >> 2][j & 3]; bm = fmaxf(bm, sv[j]); }
+                for (int j = 0; j < 8; ++j) { sv[j] = s_cur[rt][j >> 2][j & 3]; bm = fmaxf(bm, sv[j]); }
             } else {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const int slot = slot0 + (j >> 2) * 16 + 4 * lg + (j & 3);
-                    sv[j] = slot_visible(slot, n_prefix, region_len, m0[rt], m1[rt]) ? s[rt][j >> 2][j & 3] : -INFINITY;
+                    sv[j] = slot_visible(slot, n_prefix, region_len, m0[rt], m1[rt]) ? s_cur[rt][j >> 2][j & 3] : -INFINITY;
                     bm = fmaxf(bm, sv[j]);
                 }
             }
@@ -292,16 +312,18 @@ __device__ __forceinline__ void attn_mfma_body(
                     acc[rt][dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf[dt]), pf_lo[rt], acc[rt][dt]);
         }
         }
-        store_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, buf ^ 1);
-        load_block(std::integral_constant<int, (SLOT + 1) % PFD>{}, bi + (1 + PFD) * KW, pg_ahead);
+        store_k(std::integral_constant<int, PAR>{}, PAR);
+        load_k(std::integral_constant<int, PAR>{}, bi + 4 * KW, pgk_ahead);
+        store_v(std::integral_constant<int, PAR ^ 1>{}, PAR ^ 1);
+        load_v(std::integral_constant<int, PAR ^ 1>{}, bi + 3 * KW, pgv_ahead);
         __syncthreads();
-        buf ^= 1;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) { s_cur[rt][0] = s_next[rt][0]; s_cur[rt][1] = s_next[rt][1]; }
     };
-    for (int bi = b0; bi < b1; bi += PFD * KW)            // unrolled by PFD so that ring slots are static
-        static_for([&](auto p) {
-            constexpr int I = decltype(p)::value;
-            if (bi + I * KW < b1) iteration(p, bi + I * KW);
-        });
+    for (int bi = b0; bi < b1; bi += 2 * KW) {            // unrolled by two so that ring slots and buffers are static
+        iteration(S0{}, bi);
+        if (bi + KW < b1) iteration(S1{}, bi + KW);
+    }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         l_run[rt] += __shfl_xor(l_run[rt], 16, 64);
@@ -516,12 +538,16 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float *__restrict__ 
 // meet in which split, in which order) is then the same whether it is verified alone or among 60 others,
 // which is what makes the speculative stream reproduce the one-token-at-a-time stream bit for bit as long
 // as only bonus tokens are committed.  keys_per_split > 0 overrides.
+// keys_per_split < 0: the rule above with splits of at most -keys_per_split keys (the specialists' passes carry few
+// rows, so that only a few dozen workgroups exist per split level: at long contexts they want shorter walks than the
+// target's passes; the drafter's caches are its own, so its rule need not match the target's).
 static int blocks_per_split(int n_prefix, int keys_per_split) {
     if (keys_per_split > 0) return keys_per_split >= 32 ? keys_per_split / 32 : 1;
     const int prefix_blocks = (n_prefix + 31) / 32;
     int bps = (prefix_blocks + 3) / 4;
     if (bps < 4) bps = 4;
-    if (bps > 32) bps = 32;
+    const int cap = keys_per_split < 0 && -keys_per_split >= 128 ? -keys_per_split / 32 : 32;
+    if (bps > cap) bps = cap;
     return bps;
 }
 
