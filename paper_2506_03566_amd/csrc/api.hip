@@ -147,6 +147,9 @@ const char *check_config(const poss_config &c) {
     if (c.kv_page_order < 0 || c.kv_page_order > 1) return "kv_page_order must be 0 or 1";
     if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return "rms_eps / rope_theta out of range";
     if (c.batch < 0 || c.batch > 8) return "batch must be in 0..8 (0 and 1: one sequence)";
+    // the float32 attention kernel keeps one score per cache slot in LDS (64 KiB without opting in to more)
+    if (c.dtype == POSS_DTYPE_F32 && (size_t)(c.max_seq + POSS_MAX_ROWS + c.kv_page_tokens) * sizeof(float) > 64 * 1024)
+        return "float32 storage supports max_seq up to about 16000 (scores of one row are kept in LDS)";
     return nullptr;
 }
 
@@ -817,6 +820,21 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
         const int t = c->seq[b].t;
         if (t + cf.total_tokens + 1 > c->cache_slots || t + L + 1 > cf.max_seq)
             return fail(c, POSS_E_CAPACITY, "poss_draft_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
+    }
+    // Rows of every pass, worked out before anything is launched or any state is touched (a pass that does not fit
+    // must not leave a half-drafted round behind): specialist s catches up on the pairs and frontier rows it has not seen.
+    for (int b : all) {
+        const Seq &sq = c->seq[b];
+        std::vector<int> len = sq.spec_len, tmp(cf.n_specialists, 0);
+        for (int s = 0; s < cf.n_specialists; ++s)
+            if (sq.t - 1 - len[s] > L) len[s] = sq.t - 1;             // brought up to date in chunks of their own first
+        for (int d = 1; d <= L; ++d) {
+            int s = (d - 1) / cf.positions_per_specialist;
+            if (s > cf.n_specialists - 1) s = cf.n_specialists - 1;
+            const int n = d == 1 ? sq.t - len[s] : k + (sq.t - len[s]) + k * (d - 2 - tmp[s] > 0 ? d - 2 - tmp[s] : 0);
+            if (n > MAX_ROWS) return fail(c, POSS_E_CAPACITY, "poss_draft_tree: the pass at depth %d would carry %d rows for one sequence (limit %d)", d, n, MAX_ROWS);
+            len[s] = sq.t; tmp[s] = d - 1;
+        }
     }
     if (c->ev_pending[0]) { int rc = sync_and_harvest(c); if (rc) return rc; }   // a re-draft: keep the first one's time
     (void)hipEventRecord(c->ev[0], c->st);

@@ -134,10 +134,10 @@ def test_lockstep_rounds_16bit(name):
         score, rows = o.score_tree(otree)
         serr = np.abs(score - d["score"].astype(np.float64)).max()
         _say(f"  round {rnd}: max|dscore| {serr:.2e}")
-        assert serr <= 5 * tol
+        assert serr <= 2 * tol                            # a score sums up to `depth` log-probabilities; measured 1e-2
         own = o.draft_tree()                              # the oracle's own tree on the same state
         worst_kept = min(float(s) for s in own.score[1:])
-        assert score[1:].min() >= worst_kept - 5 * tol
+        assert score[1:].min() >= worst_kept - 2 * tol
         # children of an expanded node are among the oracle's best-k of that node, up to tolerance
         for v, lp in rows.items():
             kth = np.sort(lp)[-cfg.top_k]

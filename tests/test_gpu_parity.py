@@ -116,7 +116,9 @@ def test_verify_logits_features_and_cache(name):
     err = np.abs(logits - ologits).max()
     _say(f"  max|dlogit| = {err:.3e} (tol {tol})  max|dfeat| = {np.abs(feats - ofeats).max():.3e}")
     assert err <= tol
-    assert np.abs(feats - ofeats).max() <= tol * 5 * max(1.0, np.abs(ofeats).max())
+    # features are the residual stream itself (no final norm): the logit bound, scaled by the norm's factor, the root
+    # mean square of the row (1 .. 3 at these shapes)
+    assert np.abs(feats - ofeats).max() <= tol * max(1.0, np.sqrt((ofeats ** 2).mean(axis=1)).max())
     # greedy tokens agree wherever the oracle's top-2 gap exceeds twice the tolerance
     for i in range(len(og)):
         top2 = np.partition(ologits[i], -2)[-2:]
