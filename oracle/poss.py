@@ -19,7 +19,7 @@ from .model import (target_rows, head, causal_allowed, empty_kv, specialist_pass
                     specialist_index)
 from .numerics import log_softmax
 from .tree import TreeBuilder, Tree, accept_walk, AcceptStats
-from .sampling import sample_token
+from .sampling import sample_token, softmax_t, sample_children, reject_or_accept, draw_from
 
 
 def topk_lowest_id(row, k):
@@ -61,7 +61,11 @@ class PossOracle:
         self.margins.append(float(top2[1] - top2[0]))
 
     # ------------------------------------------------------------------ draft
-    def draft_tree(self):
+    def draft_tree(self, sampling=None):
+        """sampling = (temperature, UD): the k children of an expanded node are drawn without replacement from the
+        drafter's softmax(logits / temperature), child i of the node of frontier rank r at depth d with
+        UD[d - 1][r][i], and scored with their log-probability under it (oracle/sampling.py, second reading);
+        None: its k most probable tokens."""
         cfg, W, t = self.cfg, self.W, self.t
         k, L = cfg.top_k, cfg.depth
         n, S = cfg.positions_per_specialist, cfg.n_specialists
@@ -73,6 +77,7 @@ class PossOracle:
         fhat = {}                        # pool index (-1 = root) -> drafted feature
         tb = TreeBuilder(k, L, cfg.total_tokens)
         dbg_logp = []
+        draft_q, self.draw_margins = {}, []      # sampled children: the distribution each expanded node's children came from
         for d in range(1, L + 1):
             s = specialist_index(d - 1, n, S)
             front = tb.frontier()
@@ -102,6 +107,12 @@ class PossOracle:
             ids = np.zeros((len(front), k), dtype=np.int64)
             lp = np.zeros((len(front), k), dtype=np.float32)
             for r in range(len(front)):
+                if sampling is not None:
+                    temperature, UD = sampling
+                    cids, q = sample_children(logits[r], temperature, UD[d - 1][r][:k], self.draw_margins)
+                    ids[r], lp[r] = cids, np.log(q[cids]).astype(np.float32)
+                    draft_q[front[r]] = q
+                    continue
                 order = topk_lowest_id(logits[r], k + 1)
                 ids[r], lp[r] = order[:k], logp[r, order[:k]]
                 gaps = -np.diff(logits[r, order].astype(np.float64))
@@ -117,7 +128,7 @@ class PossOracle:
         tree = tb.finalize(t)
         tree.token[0] = self.tokens[t]
         self.margins += tb.margins
-        self.last["builder"], self.last["topk"] = tb, dbg_logp
+        self.last["builder"], self.last["topk"], self.last["draft_q"] = tb, dbg_logp, draft_q
         return tree
 
     def score_tree(self, tree):
@@ -182,6 +193,42 @@ class PossOracle:
             g = [int(np.argmax(logits[i])) for i in range(tree.n)]
         self.last.update(tree=tree, F=F, new_kv=new_kv, logits=logits, g=g)
         return g, logits, F
+
+    def verify_tree_sampled(self, tree, temperature, UA):
+        """Verification of a tree whose children were drawn (draft_tree(sampling=...)) by the rejection rule.  One
+        target pass as in verify_tree; then from the root: the k drawn children of the current node are tested in
+        the order drawn with UA[depth][0 .. k-1]; an accepted child that the tree kept becomes the current node; an
+        accepted child that the rerank dropped, the token drawn from the last residual (with UA[depth][k]) when all
+        are rejected, or - at a node that was not expanded - the token drawn from the target's own distribution,
+        ends the walk and is committed in the bonus token's place.  Returns (path, that last token)."""
+        cfg, t, k = self.cfg, self.t, self.cfg.top_k
+        if tree.pos is None:
+            tree.finish(t)
+        F, new_kv = target_rows(self.W, cfg, tree.token, tree.pos, self.kv, tree.allowed(t), self.act)
+        logits = head(self.W, cfg, F, self.act)
+        tb, dq = self.last["builder"], self.last["draft_q"]
+        node_of = {pool: i for i, pool in enumerate(tree.pool_index)}
+        self.accept_margins = []
+        cur, path = 0, [0]
+        while True:
+            d = tree.depth[cur]
+            p = softmax_t(logits[cur].astype(np.float32), temperature)
+            pv = tree.pool_index[cur]
+            if pv not in tb.expanded:
+                last = draw_from(p, UA[d][k], self.accept_margins)
+                break
+            cand = tb.expanded[pv]
+            i, resid = reject_or_accept(p, dq[pv], [tb.token[c] for c in cand], UA[d][:k], self.accept_margins)
+            if i < 0:
+                last = draw_from(resid, UA[d][k], self.accept_margins)
+                break
+            if cand[i] not in node_of:
+                last = tb.token[cand[i]]
+                break
+            cur = node_of[cand[i]]
+            path.append(cur)
+        self.last.update(tree=tree, F=F, new_kv=new_kv, logits=logits, g=None)
+        return path, int(last)
 
     # ------------------------------------------------------------------ accept + commit
     def accept_and_commit(self, path=None, bonus=None):

@@ -16,6 +16,18 @@ Random numbers are inputs: one uniform number in [0, 1) per sequence position, U
 token at position p.  The draw is by inverse CDF in vocabulary order, so a run is reproducible
 and the speculative stream can be compared token for token with vanilla sampling that uses the
 same numbers.
+
+Second reading, for the rejection-sampling rule proper ("sampled children"): the k children of an
+expanded node are DRAWN from the drafter's distribution q = softmax(drafter logits / T), one after
+the other without replacement; verification tests them in the order drawn: candidate c is accepted
+with probability min(1, p(c) / q(c)); after a rejection the target distribution is replaced by the
+normalised positive part of p - q and the drafter distribution by q without c, renormalised; if no
+candidate is accepted the token is drawn from the last residual.  The accepted or drawn token is
+distributed exactly as p (speculative sampling extended to several candidates drawn without
+replacement, the recursive form of the rule cited in section 2.1), so the committed stream keeps the
+target's distribution; here the speculative stream is NOT the vanilla stream of the same numbers,
+only equal in distribution.  Uniform numbers are again inputs: one per draw, one per test, one per
+residual draw.
 """
 import numpy as np
 
@@ -51,3 +63,53 @@ def sample_decode(W, cfg, prompt, n_new, temperature, U, act=None):
         _, logits = target_full(W, cfg, seq, act)
         seq.append(sample_token(logits[-1], temperature, U[len(seq)]))
     return seq
+
+
+# ------------------------------------------------------------------ sampled children, rejection rule
+def draw_from(p, u, margins=None):
+    """Inverse CDF in vocabulary order over a vector of non-negative masses (need not sum to 1): the first id
+    whose cumulative mass exceeds u * total; never an id of zero mass.  `margins`, if a list, receives how far
+    (as a fraction of the total) u * total is from the nearer end of the chosen id's interval."""
+    p = np.asarray(p, dtype=np.float64)
+    cdf = np.cumsum(p)
+    target = u * cdf[-1]
+    i = int(np.searchsorted(cdf, target, side="right"))
+    if i >= len(p) or p[i] <= 0.0:                    # rounding pushed the target past the total
+        i = int(np.nonzero(p > 0)[0][-1])
+    if margins is not None:
+        margins.append(float(min(target - (cdf[i - 1] if i > 0 else 0.0), cdf[i] - target) / cdf[-1]))
+    return i
+
+
+def sample_children(logits, temperature, us, margins=None):
+    """len(us) distinct ids drawn one after the other from softmax(logits / T), each from what the earlier draws
+    left (inverse CDF in vocabulary order, us[i] for draw i).  Returns (ids in draw order, q, the full
+    distribution they were drawn from)."""
+    q = softmax_t(logits, temperature)
+    left = q.copy()
+    ids = []
+    for u in us:
+        c = draw_from(left, u, margins)
+        ids.append(c)
+        left[c] = 0.0
+    return ids, q
+
+
+def reject_or_accept(p, q, candidates, us, margins=None):
+    """The candidates (distinct ids, in the order they were drawn from q without replacement) are tested one
+    after the other with us[i]: candidate c passes if us[i] < min(1, p(c) / q(c)) for the CURRENT p and q.
+    After a rejection p becomes the normalised positive part of p - q and q loses c and is renormalised.
+    Returns (index of the accepted candidate or -1, the p to draw from if none was accepted)."""
+    p = np.asarray(p, dtype=np.float64).copy()
+    q = np.asarray(q, dtype=np.float64).copy()
+    for i, c in enumerate(candidates):
+        a = min(1.0, p[c] / q[c])
+        if margins is not None and a < 1.0:
+            margins.append(abs(float(us[i]) - a))
+        if us[i] < a:
+            return i, None
+        p = np.maximum(p - q, 0.0)
+        p /= p.sum()
+        q[c] = 0.0
+        q /= q.sum()
+    return -1, p

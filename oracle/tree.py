@@ -36,6 +36,7 @@ class TreeBuilder:
         self.k, self.L, self.N = top_k, depth, total_tokens
         self.token, self.parent, self.depth, self.score = [], [], [], []
         self._frontier = [-1]
+        self.expanded = {}         # expanded node (candidate index, -1 = the root) -> candidate indices of its k children, in the order given
         self.d = 0
         self.margins = []          # score gaps at every keep/drop boundary (diagnostics)
 
@@ -49,6 +50,7 @@ class TreeBuilder:
         self.d += 1
         first = len(self.token)
         for r, v in enumerate(self._frontier):
+            self.expanded[v] = list(range(first + r * self.k, first + (r + 1) * self.k))
             for c in range(self.k):
                 self.token.append(int(ids[r][c]))
                 self.parent.append(v)

@@ -85,3 +85,108 @@ def test_acceptance_probability_of_a_child_is_its_target_probability():
             assert bonus == g[0] and bonus not in token[1:]
     want = p[3] + p[11] + p[29]
     assert abs(acc / n - want) < 5 * np.sqrt(want * (1 - want) / n)
+
+
+# ---------------------------------------------------------------------- sampled children, rejection rule
+from oracle.sampling import draw_from, sample_children, reject_or_accept
+
+
+def test_children_are_drawn_without_replacement_in_proportion_to_what_is_left():
+    rng = np.random.default_rng(4)
+    logits = rng.normal(size=9) * 1.3
+    q = softmax_t(logits, 0.8)
+    n = 30000
+    first = np.zeros(9)
+    second_given_first = np.zeros((9, 9))
+    for _ in range(n):
+        ids, qq = sample_children(logits, 0.8, rng.random(4))
+        assert len(set(ids)) == 4 and np.allclose(qq, q)
+        first[ids[0]] += 1
+        second_given_first[ids[0], ids[1]] += 1
+    assert np.all(np.abs(first - n * q) < 5 * np.sqrt(n * q * (1 - q)) + 1)
+    a = int(np.argmax(q))                              # condition on the most frequent first draw
+    cond = q.copy(); cond[a] = 0; cond /= cond.sum()
+    na = second_given_first[a].sum()
+    assert second_given_first[a, a] == 0
+    assert np.all(np.abs(second_given_first[a] - na * cond) < 5 * np.sqrt(na * cond * (1 - cond)) + 1)
+    # closed form: equal logits, u in the j-th of the remaining equal intervals picks the j-th remaining id
+    ids, _ = sample_children(np.zeros(5), 1.0, [0.5, 0.5, 0.99, 0.0])
+    assert ids == [2, 3, 4, 0]
+    assert draw_from([0.0, 2.0, 0.0, 2.0], 0.5) == 3 and draw_from([0.0, 2.0, 0.0, 2.0], 0.4999) == 1
+
+
+def test_rejection_rule_closed_forms():
+    # one candidate, two tokens: accepted with probability min(1, p/q); the residual is the positive part of p - q
+    p, q = np.array([0.3, 0.7]), np.array([0.6, 0.4])
+    assert reject_or_accept(p, q, [0], [0.4999]) == (0, None)         # p/q = 0.5
+    i, r = reject_or_accept(p, q, [0], [0.5])
+    assert i == -1 and np.allclose(r, [0.0, 1.0])                      # max(p - q, 0) = (0, 0.3) -> (0, 1)
+    assert reject_or_accept(p, q, [1], [0.999999])[0] == 0             # p/q > 1: always accepted
+    # p == q: whatever was drawn is accepted
+    assert reject_or_accept(p, p, [0], [0.999999])[0] == 0
+    # two candidates: after rejecting 0, q' = (0, 1) and p' = (0, 1): candidate 1 is accepted whatever its number
+    assert reject_or_accept(p, q, [0, 1], [0.9, 0.999999])[0] == 1
+    # acceptance probability of the first candidate over its own draw: sum_x min(p, q)
+    rng = np.random.default_rng(8)
+    n, acc = 40000, 0
+    for _ in range(n):
+        c = draw_from(q, rng.random())
+        acc += reject_or_accept(p, q, [c], [rng.random()])[0] == 0
+    want = np.minimum(p, q).sum()
+    assert abs(acc / n - want) < 5 * np.sqrt(want * (1 - want) / n)
+
+
+def test_rejection_rule_keeps_the_target_distribution():
+    """Whatever the drafter's distribution and however many candidates are drawn from it, the token that comes
+    out - an accepted candidate, else a draw from the last residual - is distributed as the target says."""
+    rng = np.random.default_rng(21)
+    for k, T in ((1, 1.0), (3, 1.0), (4, 0.7)):
+        lp, lq = rng.normal(size=7) * 1.5, rng.normal(size=7) * 1.5
+        lq[2] = -np.inf                                        # a token the drafter never proposes
+        p = softmax_t(lp, T)
+        n = 40000
+        counts = np.zeros(7)
+        accepted = 0
+        for _ in range(n):
+            cands, q = sample_children(lq, T, rng.random(k))
+            i, resid = reject_or_accept(p, q, cands, rng.random(k))
+            tok = cands[i] if i >= 0 else draw_from(resid, rng.random())
+            accepted += i >= 0
+            counts[tok] += 1
+        assert np.all(np.abs(counts - n * p) < 5 * np.sqrt(n * p * (1 - p)) + 1), (k, T)
+        assert counts[2] > 0 and 0 < accepted < n
+
+
+def test_sampled_round_on_the_tiny_model():
+    """The round with drawn children: the accepted path is a root path of the tree, every child set is distinct,
+    numbers of 0 accept every candidate with target mass (the walk then follows the first-drawn kept children),
+    the same numbers give the same round, and committing leaves the state consistent."""
+    cfg = get_config("c0_tiny_f32")
+    W = Weights(cfg, make_weights(cfg))
+    prompt = make_prompt(cfg, n=16)
+    rng = np.random.default_rng(6)
+    UD = rng.random((cfg.depth, cfg.top_k, cfg.top_k))
+    UA = rng.random((cfg.depth + 1, cfg.top_k + 1))
+    outs = []
+    for rep in range(2):
+        o = PossOracle(W, cfg)
+        o.prefill(prompt)
+        tree = o.draft_tree(sampling=(1.0, UD))
+        tb = o.last["builder"]
+        for v, kids in tb.expanded.items():
+            assert len({tb.token[c] for c in kids}) == cfg.top_k
+            assert abs(o.last["draft_q"][v].sum() - 1.0) < 1e-12
+        path, last = o.verify_tree_sampled(tree, 1.0, UA)
+        assert path[0] == 0 and all(tree.parent[b] == a for a, b in zip(path, path[1:]))
+        outs.append((tree.token, tree.parent, path, last))
+        o.accept_and_commit(path=path, bonus=last)
+        assert o.tokens[-1] == last and len(o.feats) == o.t == len(o.kv[0][0])
+    assert outs[0] == outs[1]
+    o = PossOracle(W, cfg)
+    o.prefill(prompt)
+    tree = o.draft_tree(sampling=(1.0, UD))
+    path, last = o.verify_tree_sampled(tree, 1.0, np.zeros_like(UA))
+    tb = o.last["builder"]
+    first_kids = tb.expanded[-1]
+    if tree.pool_index[1] == first_kids[0]:
+        assert path[:2] == [0, 1]                            # the first-drawn child of the root was kept and is accepted
