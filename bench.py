@@ -208,6 +208,9 @@ def main():
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0: verification draws the target's tokens at this temperature (sampler kernels "
                          "instead of argmax); the headline metric is quoted at 0")
+    ap.add_argument("--drawn-children", action="store_true",
+                    help="with --temperature: children drawn from the drafter's distribution and verified by the rejection "
+                         "rule (poss_set_draft_sampling) instead of the deterministic tree")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short measurements of the other workloads (6 specialists x 1, 13B fp16, 8192-token context) "
                          "that the default run appends as other_configs")
@@ -255,6 +258,9 @@ def main():
     def one_round():
         if args.temperature > 0:
             ctx.set_sampling(args.temperature, u_rng.random(cfg.depth + 1).astype(np.float32))
+            if args.drawn_children:
+                ctx.set_draft_sampling(u_rng.random((cfg.depth, cfg.top_k, cfg.top_k)).astype(np.float32),
+                                       u_rng.random((cfg.depth + 1, cfg.top_k + 1)).astype(np.float32))
         ctx.draft_tree(want_tree=False)
         ctx.verify_tree(None, want_argmax=False)
         return ctx.accept_and_commit()
@@ -315,6 +321,7 @@ def main():
     if args.vanilla_steps > 0:
         ctx.reset()
         if args.temperature > 0:
+            ctx.set_draft_sampling(None)
             ctx.set_sampling(0.0)
         ctx.prefill(prompt)
         for b in range(1, B):
@@ -339,6 +346,7 @@ def main():
         out["config"]["overrides"] = over
     if args.temperature > 0:
         out["config"]["temperature"] = args.temperature
+        out["config"]["drawn_children"] = bool(args.drawn_children)
     if cfg.name in PAPER_TAU and not over:
         # NOT a measurement: random-init drafters accept nothing (tau_gen = 1), so this only restates the
         # measured round latency at the acceptance length the paper reports for trained drafters.

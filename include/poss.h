@@ -194,6 +194,23 @@ int poss_get_commit_seq(poss_ctx *ctx, int32_t seq, int32_t *path_idx_out, int32
  * returns; it stays in force until the next call.  temperature == 0 restores greedy verification
  * (u ignored).  Statistics count accepted draft tokens as before. */
 int poss_set_sampling(poss_ctx *ctx, float temperature, const float *u, int32_t n_u);
+/* The rejection-sampling rule proper at a temperature (section 2.1 names the step; this is the second reading of
+ * it): with enable != 0, and a temperature set by poss_set_sampling, poss_draft_tree DRAWS the top_k children of
+ * every expanded node from the drafter's softmax(logits / temperature), one after the other without replacement
+ * (inverse CDF in vocabulary order over what is left), child i of the node of frontier rank r at depth d with
+ * u_draft[((d - 1) * top_k + r) * top_k + i], and scores them with their log-probability; poss_verify_tree
+ * (drafted tree only) tests the children of the current node in the order drawn, child i at a node of depth d
+ * with u_accept[d * (top_k + 1) + i] against min(1, p / q) - p the target's, q the drafter's probability,
+ * after a rejection p becomes the normalised positive part of p - q and q loses the candidate - and ends the
+ * walk with a token drawn from the last residual (u_accept[d * (top_k + 1) + top_k]), with an accepted child that
+ * the tree had dropped, or at a node without drawn children with a token drawn from the target's distribution.
+ * That last token takes the bonus token's place in poss_accept_and_commit; every committed token is
+ * distributed as the target's softmax(logits / temperature) given its prefix.  argmax_out of poss_verify_tree
+ * then holds, for the nodes of the accepted path, the token that follows them, and -1 elsewhere.
+ * u_draft: HOST float32 [depth][top_k][top_k]; u_accept: HOST float32 [depth + 1][top_k + 1]; all in [0, 1);
+ * copied before the call returns, in force until the next call.  One sequence per context.  enable == 0:
+ * back to the deterministic tree and the inverse-CDF coupling of poss_set_sampling. */
+int poss_set_draft_sampling(poss_ctx *ctx, int32_t enable, const float *u_draft, const float *u_accept);
 /* With batch > 1 poss_set_sampling gives every sequence the same numbers; this call gives sequence
  * seq its own (same rules for u and n_u; the temperature is the context's). */
 int poss_set_uniforms_seq(poss_ctx *ctx, int32_t seq, const float *u, int32_t n_u);

@@ -17,7 +17,7 @@ MAX_ROWS, MASK_WORDS, MAX_DEPTH = 128, 2, 16
 EXPORTS = ["poss_workspace_bytes", "poss_load", "poss_reset", "poss_prefill", "poss_draft_tree",
            "poss_verify_tree", "poss_accept_and_commit", "poss_get_stats", "poss_get_tokens",
            "poss_prefill_seq", "poss_get_tree_seq", "poss_get_commit_seq", "poss_get_tokens_seq", "poss_set_uniforms_seq", "poss_reset_seq", "poss_set_active",
-           "poss_last_error", "poss_free", "poss_profile_gemm", "poss_gemm_profile", "poss_set_tuning", "poss_set_sampling",
+           "poss_last_error", "poss_free", "poss_profile_gemm", "poss_gemm_profile", "poss_set_tuning", "poss_set_sampling", "poss_set_draft_sampling",
            "poss_debug_build_tree", "poss_debug_set_taps", "poss_debug_read_kv",
            "poss_debug_gemm_scratch_bytes", "poss_debug_gemm", "poss_gemm_static"]
 
@@ -91,6 +91,7 @@ def load_library():
     lib.poss_set_tuning.argtypes = [c_vp, c_i32, c_i32]
     lib.poss_set_sampling.argtypes = [c_vp, c_f32, ctypes.POINTER(c_f32), c_i32]
     lib.poss_set_uniforms_seq.argtypes = [c_vp, c_i32, ctypes.POINTER(c_f32), c_i32]
+    lib.poss_set_draft_sampling.argtypes = [c_vp, c_i32, ctypes.POINTER(c_f32), ctypes.POINTER(c_f32)]
     lib.poss_debug_build_tree.argtypes = [c_vp, P(c_i32), P(c_f32), P(PossTree)]
     lib.poss_debug_set_taps.argtypes = [c_vp, c_vp]
     lib.poss_debug_read_kv.argtypes = [c_vp, c_i32, c_i32, c_i32, c_i32, P(c_f32), P(c_f32)]
@@ -285,6 +286,18 @@ class Poss:
             return
         u = np.ascontiguousarray(u, dtype=np.float32)
         self._check(self.lib.poss_set_sampling(self.h, float(temperature), u.ctypes.data_as(ctypes.POINTER(c_f32)), len(u)))
+
+    def set_draft_sampling(self, u_draft=None, u_accept=None):
+        """Drawn children and the rejection rule (needs a temperature from set_sampling).  u_draft [depth][k][k], u_accept
+        [depth + 1][k + 1], all in [0, 1); both None: back to the deterministic tree."""
+        if u_draft is None:
+            self._check(self.lib.poss_set_draft_sampling(self.h, 0, None, None))
+            return
+        cfg = self.cfg
+        ud = np.ascontiguousarray(u_draft, dtype=np.float32).reshape(cfg.depth, cfg.top_k, cfg.top_k)
+        ua = np.ascontiguousarray(u_accept, dtype=np.float32).reshape(cfg.depth + 1, cfg.top_k + 1)
+        fp = ctypes.POINTER(c_f32)
+        self._check(self.lib.poss_set_draft_sampling(self.h, 1, ud.ctypes.data_as(fp), ua.ctypes.data_as(fp)))
 
     def set_uniforms(self, seq, u):
         """Uniform numbers of one sequence of a batch (set_sampling gives all sequences the same ones)."""

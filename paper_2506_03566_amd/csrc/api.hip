@@ -97,6 +97,10 @@ struct poss_ctx {
     bool launch_refused;               // a GEMM launch was refused on the host (null operand): internal error
     float temperature;                 // 0: greedy verification; > 0: the target's tokens are drawn (poss_set_sampling)
     float *u_pinned, *u_dev;           // per sequence, one uniform number per tree depth: host staging and device copy
+    // drawn children (poss_set_draft_sampling): uniform numbers of the draws [depth][k][k] and of the tests [depth + 1][k + 1]
+    // (host staging, device copies), the drafter's logits of every expanded node, the residual vector of the walk
+    int draft_sampling;
+    float *ud_pinned, *ua_pinned, *ud_dev, *ua_dev, *dlogits, *resid;
     int gemm_target_wgs, attn_keys_per_split;
     // gemm profiling
     int prof_on, prof_n;
@@ -235,6 +239,10 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     int32_t *argmax_dev = a.take_n<int32_t>(RA);
     double *inv_freq = a.take_n<double>(c.head_dim / 2);
     float *u_dev = a.take_n<float>((size_t)B * (POSS_MAX_DEPTH + 1));
+    float *ud_dev = a.take_n<float>((size_t)c.depth * c.top_k * c.top_k), *ua_dev = a.take_n<float>((size_t)(c.depth + 1) * (c.top_k + 1));
+    // one row per expanded node; a pass's Head launch writes whole 16-row tiles, so the last pass needs room beyond its rows
+    float *dlogits = a.take_n<float>((size_t)(1 + (c.depth - 1) * c.top_k + 16) * gemm_npad(V));
+    float *resid = a.take_n<float>(gemm_npad(V));
     // per sequence: tree state, token stream, feature stash, stored frontier rows
     const int k = c.top_k, L = c.depth, pool = k + (L - 1) * k * k, stride = c.total_tokens + 1;
     std::vector<Seq> seqs(B);
@@ -248,6 +256,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         td.fr_mask = a.take_n<uint64_t>((size_t)(L + 1) * k * MASK_WORDS);
         td.topk_id = topk_id_all; td.topk_logp = topk_logp_all;          // re-pointed at the sequence's rows per pass
         td.n_nodes = a.take_n<int32_t>(4);
+        td.pool_node = a.take_n<int32_t>(pool); td.node_pool = a.take_n<int32_t>(c.total_tokens + 1);
         td.token = token_all + b * stride; td.parent = parent_all + b * stride;
         td.depth = depth_all + b * stride; td.pos = pos_all + b * stride;
         td.mask = mask_all + (size_t)b * stride * MASK_WORDS; td.score = score_all + b * stride;
@@ -277,6 +286,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
         ctx->topk_id_all = topk_id_all; ctx->topk_logp_all = topk_logp_all;
         ctx->argmax_dev = argmax_dev;
         ctx->inv_freq = inv_freq; ctx->u_dev = u_dev;
+        ctx->ud_dev = ud_dev; ctx->ua_dev = ua_dev; ctx->dlogits = dlogits; ctx->resid = resid;
     }
     return a.off + 256;
 }
@@ -373,7 +383,8 @@ void target_forward(poss_ctx *c, int rows, const int32_t *tokens_dev, const RowM
 // c->topk_scratch - per row and tile the best (value, index), or the record of the k best with the tile's maximum and
 // sum of exponentials - and writes the logits only if asked; *n_seg_out receives the number of tiles.  Float32
 // storage has no such epilogue: it always writes logits and reports 0 tiles.
-GemmShape run_head(poss_ctx *c, int rows, int head_mode, bool write_logits, int *n_seg_out, const void *x = nullptr) {
+GemmShape run_head(poss_ctx *c, int rows, int head_mode, bool write_logits, int *n_seg_out, const void *x = nullptr,
+                   float *logits_dst = nullptr) {
     EpiArgs e{};
     e.mode = EPI_PLAIN;
     if (n_seg_out) *n_seg_out = 0;
@@ -385,11 +396,21 @@ GemmShape run_head(poss_ctx *c, int rows, int head_mode, bool write_logits, int 
         e.pv = c->topk_scratch; e.pi = reinterpret_cast<int *>(c->topk_scratch + (size_t)rows * n_seg);
         if (n_seg_out) *n_seg_out = n_seg;
     }
-    return run_gemm(c, c->lm_head, c->md.vocab, c->md.d, x ? x : c->u, c->md.d, rows, c->logits, true, e);
+    return run_gemm(c, c->lm_head, c->md.vocab, c->md.d, x ? x : c->u, c->md.d, rows, logits_dst ? logits_dst : c->logits, true, e);
 }
 
 // The drafter's k best next tokens and their log-probabilities for `rows` rows of final-normed activations in c->u.
-void run_head_topk(poss_ctx *c, int rows) {
+void run_head_topk(poss_ctx *c, int rows, int depth) {
+    if (c->draft_sampling) {
+        // drawn children: the logits of the pass's rows are kept (the walk needs the distribution each child came from),
+        // k children per row drawn without replacement with the caller's numbers
+        const int k = c->cfg.top_k;
+        float *dst = c->dlogits + (size_t)(depth == 1 ? 0 : 1 + (depth - 2) * k) * gemm_npad(c->cfg.vocab);
+        const GemmShape g = run_head(c, rows, 0, true, nullptr, nullptr, dst);
+        launch_sample_children(dst, g.Npad, rows, c->cfg.vocab, k, c->temperature, c->ud_dev + (size_t)(depth - 1) * k * k,
+                               c->topk_id_all, c->topk_logp_all, c->st);
+        return;
+    }
     int n_seg = 0;
     const GemmShape g = run_head(c, rows, HEAD_TOPK, false, &n_seg);
     if (n_seg)
@@ -549,6 +570,8 @@ void release_host(poss_ctx *c) {
         if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
     if (c->pinned) (void)hipHostFree(c->pinned);
     if (c->u_pinned) (void)hipHostFree(c->u_pinned);
+    if (c->ud_pinned) (void)hipHostFree(c->ud_pinned);
+    if (c->ua_pinned) (void)hipHostFree(c->ua_pinned);
     if (c->result_pinned_all) (void)hipHostFree(c->result_pinned_all);
 }
 
@@ -627,6 +650,9 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     LOAD_TRY(hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault));
     LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->u_pinned), (size_t)c->B * (POSS_MAX_DEPTH + 1) * sizeof(float), hipHostMallocDefault));
     for (int i = 0; i < c->B * (POSS_MAX_DEPTH + 1); ++i) c->u_pinned[i] = 0.f;
+    LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->ud_pinned), (size_t)cfg->depth * cfg->top_k * cfg->top_k * sizeof(float), hipHostMallocDefault));
+    LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->ua_pinned), (size_t)(cfg->depth + 1) * (cfg->top_k + 1) * sizeof(float), hipHostMallocDefault));
+    c->draft_sampling = 0;
     LOAD_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->result_pinned_all), (size_t)c->B * 64 * sizeof(int32_t), hipHostMallocDefault));
     {
         int32_t *dev = nullptr;
@@ -716,7 +742,7 @@ void poss_free(poss_ctx *c) {
 const char *poss_last_error(poss_ctx *c) { return c ? c->err : g_load_error; }
 
 static int head_and_choose(poss_ctx *c, const void *x, int rows, bool want_logits, const int32_t *depth, const int *seq_ids,
-                           int n_seq, const int *row0, const int *n_rows, int base, int *ld_out);
+                           int n_seq, const int *row0, const int *n_rows, int base, int *ld_out, bool drafted_tree = false);
 
 int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_prompt, int32_t *first_token_out) {
     if (!c) return POSS_E_INVALID_ARG;
@@ -770,7 +796,18 @@ int poss_prefill(poss_ctx *c, const int32_t *prompt, int32_t n_prompt, int32_t *
 // Sequence seq_ids[i] owns rows [row0[i], row0[i] + n_rows[i]) and has its own numbers; the rows' depths and results
 // sit `base` rows further on in the batch-wide arrays (the rows of earlier groups).  *ld_out: row stride of c->logits.
 static int head_and_choose(poss_ctx *c, const void *x, int rows, bool want_logits, const int32_t *depth, const int *seq_ids,
-                           int n_seq, const int *row0, const int *n_rows, int base, int *ld_out) {
+                           int n_seq, const int *row0, const int *n_rows, int base, int *ld_out, bool drafted_tree) {
+    if (c->temperature > 0.f && c->draft_sampling && drafted_tree) {
+        // drawn children: the rejection walk over the target's and the drafter's logits writes the path as the g[] of a
+        // greedy walk (g[node] = next token on the path), which is what the commit kernel follows
+        const GemmShape g = run_head(c, rows, 0, true, nullptr, x);
+        if (ld_out) *ld_out = g.Npad;
+        const poss_config &cf = c->cfg;
+        HIP_TRY(c, hipMemcpyAsync(c->ua_dev, c->ua_pinned, (size_t)(cf.depth + 1) * (cf.top_k + 1) * sizeof(float), hipMemcpyHostToDevice, c->st));
+        launch_rejection_walk(c->seq[seq_ids[0]].td, cf.top_k, cf.depth, cf.vocab, c->logits, c->dlogits, g.Npad, c->temperature,
+                              c->ua_dev, c->resid, c->argmax_dev + base, c->st);
+        return POSS_OK;
+    }
     if (c->temperature > 0.f) {
         const GemmShape g = run_head(c, rows, 0, true, nullptr, x);
         if (ld_out) *ld_out = g.Npad;
@@ -836,8 +873,14 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
             len[s] = sq.t; tmp[s] = d - 1;
         }
     }
+    if (c->draft_sampling) {
+        if (!(c->temperature > 0.f)) return fail(c, POSS_E_BAD_STATE, "poss_draft_tree: drawn children need a temperature (poss_set_sampling)");
+        if ((int)all.size() != 1) return fail(c, POSS_E_BAD_STATE, "poss_draft_tree: drawn children are built for one sequence per round");
+    }
     if (c->ev_pending[0]) { int rc = sync_and_harvest(c); if (rc) return rc; }   // a re-draft: keep the first one's time
     (void)hipEventRecord(c->ev[0], c->st);
+    if (c->draft_sampling)
+        HIP_TRY(c, hipMemcpyAsync(c->ud_dev, c->ud_pinned, (size_t)L * k * k * sizeof(float), hipMemcpyHostToDevice, c->st));
     for (int i = 0; i < (int)all.size(); ++i) {
         const int b = all[i];
         Seq &sq = c->seq[b];
@@ -893,7 +936,7 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
             spec_pass(c, s, gp, d - 1, c->fhat[(d - 1) & 1] + (size_t)i0 * prev_each * c->md.d, prev_each,
                       c->fhat[d & 1] + (size_t)i0 * rows_q_each * c->md.d, &q0);
             const int rows_q = nb * rows_q_each;
-            run_head_topk(c, rows_q);
+            run_head_topk(c, rows_q, d);
             TreeDev tds[8];
             for (int i = 0; i < nb; ++i) {
                 Seq &sq = c->seq[act[i0 + i]];
@@ -1007,6 +1050,8 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
         if (t + n_rows[i] > c->cache_slots || t + cf.depth + 1 > cf.max_seq)
             return fail(c, POSS_E_CAPACITY, "poss_verify_tree: %d committed tokens leave no room (max_seq %d)", t, cf.max_seq);
     }
+    if (tree && c->draft_sampling && c->temperature > 0.f)
+        return fail(c, POSS_E_BAD_STATE, "poss_verify_tree: with drawn children only the drafted tree can be verified (a caller's tree has no draft distributions)");
     (void)hipEventRecord(c->ev[2], c->st);
     if (tree) {
         int32_t *stage = static_cast<int32_t *>(c->pinned);      // [tokens | parents | node counts]
@@ -1044,7 +1089,7 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
         }
         target_forward(c, grows, c->tree_token_all + base, rm, segs, c->feats + (size_t)base * cf.d_model);
         int ld = 0;
-        { int rc = head_and_choose(c, nullptr, grows, i0 == 0 && logits_out, c->tree_depth_all, act.data() + i0, i1 - i0, rel0, n_rows + i0, base, &ld); if (rc) return rc; }
+        { int rc = head_and_choose(c, nullptr, grows, i0 == 0 && logits_out, c->tree_depth_all, act.data() + i0, i1 - i0, rel0, n_rows + i0, base, &ld, tree == nullptr); if (rc) return rc; }
         if (i0 == 0 && logits_out)                         // before the next group overwrites the logits
             launch_copy_rows_f32(c->logits, ld, static_cast<float *>(logits_out), cf.vocab, n, cf.vocab, c->st);
         i0 = i1;
@@ -1130,6 +1175,25 @@ int poss_set_sampling(poss_ctx *c, float temperature, const float *u, int32_t n_
             for (int i = 0; i <= POSS_MAX_DEPTH; ++i) c->u_pinned[b * (POSS_MAX_DEPTH + 1) + i] = i < n_u ? u[i] : u[n_u - 1];
     }
     c->temperature = temperature;
+    return POSS_OK;
+}
+
+int poss_set_draft_sampling(poss_ctx *c, int32_t enable, const float *u_draft, const float *u_accept) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (!enable) { c->draft_sampling = 0; return POSS_OK; }
+    if (c->B != 1) return fail(c, POSS_E_INVALID_ARG, "poss_set_draft_sampling: built for contexts of one sequence");
+    if (!u_draft || !u_accept) return fail(c, POSS_E_INVALID_ARG, "poss_set_draft_sampling: null argument");
+    if (c->cfg.vocab > 8192 * 256 || c->cfg.top_k > 16)   // the samplers' block sums and list of drawn ids in LDS
+        return fail(c, POSS_E_CAPACITY, "poss_set_draft_sampling: vocabulary above 2097152 or k above 16");
+    const int k = c->cfg.top_k, L = c->cfg.depth, nd = L * k * k, na = (L + 1) * (k + 1);
+    for (int i = 0; i < nd; ++i)
+        if (!(u_draft[i] >= 0.f && u_draft[i] < 1.f)) return fail(c, POSS_E_INVALID_ARG, "poss_set_draft_sampling: u_draft[%d] is not in [0, 1)", i);
+    for (int i = 0; i < na; ++i)
+        if (!(u_accept[i] >= 0.f && u_accept[i] < 1.f)) return fail(c, POSS_E_INVALID_ARG, "poss_set_draft_sampling: u_accept[%d] is not in [0, 1)", i);
+    HIP_TRY(c, hipStreamSynchronize(c->st));              // queued work may still read the staging arrays
+    memcpy(c->ud_pinned, u_draft, nd * sizeof(float));
+    memcpy(c->ua_pinned, u_accept, na * sizeof(float));
+    c->draft_sampling = 1;
     return POSS_OK;
 }
 

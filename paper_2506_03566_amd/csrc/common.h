@@ -166,7 +166,26 @@ struct TreeDev {            // device-resident tree state of one round
     int32_t *topk_id; float *topk_logp;
     // final tree
     int32_t *n_nodes, *token, *parent, *depth, *pos; uint64_t *mask; float *score;
+    // candidate <-> tree node, written with the final tree: pool_node[candidate] = node index or -1 (dropped),
+    // node_pool[node] = candidate index (-1 for the root)
+    int32_t *pool_node, *node_pool;
 };
+// Verification at a temperature with DRAWN children (the rejection-sampling rule).
+// Children: for each of `rows` logits rows, k distinct ids drawn one after the other from softmax(logits / temperature),
+// each from what the earlier draws left (inverse CDF in vocabulary order), draw i of row r with u[r * k + i]; out_logp is
+// the log-probability under the full distribution.  One workgroup per row.
+void launch_sample_children(const float *logits, int ld, int rows, int vocab, int k, float temperature, const float *u,
+                            int32_t *out_id, float *out_logp, hipStream_t st);
+// The walk: from the root, the k drawn children of the current node (candidates cbase .. cbase + k - 1 of the pool, in
+// draw order) are tested with ua[depth * (k + 1) + i] against min(1, p / q), p from the target's logits row of the node,
+// q from the drafter's logits row that produced the children (draft_logits row 0 for the root, 1 + (depth - 1) * k + rank
+// for a frontier node); after a rejection p becomes the positive part of p - q and q loses the candidate.  An accepted child
+// that the tree kept becomes the current node; otherwise the walk ends with one more token (an accepted child the tree
+// dropped, a draw from the last residual with ua[depth * (k + 1) + k], or at a node without drawn children a draw from
+// the target's distribution).  The result is written as the g[] of a greedy walk: g[node] = next token for every
+// node of the path, so that the commit kernel reproduces it.  resid: vocab floats of scratch.
+void launch_rejection_walk(const TreeDev &td, int k, int L, int vocab, const float *target_logits, const float *draft_logits,
+                           int ld, float temperature, const float *ua, float *resid, int32_t *g, hipStream_t st);
 size_t topk_scratch_floats(int rows, int vocab);
 // second stage alone, over n_seg segment records per row (written by topk_seg_kernel or by an EPI_HEAD launch)
 void launch_topk_merge(const float *seg_records, int n_seg, int rows, int k, int32_t *out_id, float *out_logp, hipStream_t st);

@@ -245,6 +245,319 @@ bool launch_sample(const float *logits, int ld, int rows, int vocab, float tempe
     return true;
 }
 
+// ------------------------------------------------------------------ drawn children and the rejection rule
+// Both kernels cut the vocabulary into blocks of 256 ids (one float4 per lane of a wave: coalesced) and find "the first id
+// whose cumulative mass exceeds the target" in two steps: the block (a scan over the block sums), then the id inside it (a
+// scan over the lanes of one wave).  Every sum is formed in one fixed order, so a run is repeatable.
+constexpr int DRAW_THREADS = 1024, DRAW_BLOCK = 256, DRAW_MAX_BLOCKS = 8192;
+typedef float f32x4e __attribute__((ext_vector_type(4)));
+
+struct DrawLds {
+    float bsum[DRAW_MAX_BLOCKS];       // mass of every block
+    float cum[DRAW_THREADS];           // inclusive scan over the threads' shares of bsum
+    float red[17];
+    float wave_off[17];
+    float f[4]; int i[4];
+    int removed[16];
+};
+
+// Inclusive scan of one value per thread over the workgroup, in a fixed order: inside a wave by shuffles, the 16 wave
+// totals by thread 0.  Returns the inclusive value; *total = the sum of all.
+__device__ __forceinline__ float block_scan(float v, DrawLds &L, float *total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    __syncthreads();
+    if (lane == 63) L.red[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float a = 0.f;
+        for (int w = 0; w < DRAW_THREADS / 64; ++w) { L.wave_off[w] = a; a += L.red[w]; }
+        L.wave_off[16] = a;
+    }
+    __syncthreads();
+    *total = L.wave_off[16];
+    return v + L.wave_off[wave];
+}
+
+// The block that holds u * (total mass): the first whose inclusive cumulative sum exceeds it; blocks without mass are never
+// chosen; if rounding pushed the target past the total, the last block with mass (*before = -inf then).  Every thread
+// gets the result.
+__device__ __forceinline__ int find_block(DrawLds &L, int nblk, float u, float *before, float *total_out) {
+    const int tid = threadIdx.x, per = (nblk + DRAW_THREADS - 1) / DRAW_THREADS, b0 = tid * per, b1 = min(nblk, b0 + per);
+    float s = 0.f;
+    int last_mass = -1;
+    for (int b = b0; b < b1; ++b) { s += L.bsum[b]; if (L.bsum[b] > 0.f) last_mass = b; }
+    float total;
+    const float incl = block_scan(s, L, &total);
+    L.cum[tid] = incl;
+    if (tid == 0) { L.i[0] = -1; L.i[1] = -1; }
+    __syncthreads();
+    const float target = u * total, prev = tid ? L.cum[tid - 1] : 0.f;
+    if (last_mass >= 0) atomicMax(&L.i[1], last_mass);
+    if (s > 0.f && prev <= target && target < incl) {
+        // (prev + the shares one by one may round differently from incl: the last share with mass takes what is left)
+        float cumb = prev;
+        for (int b = b0; b < b1; ++b) {
+            const float w = L.bsum[b];
+            if (w > 0.f && (cumb + w > target || b == last_mass)) { L.i[0] = b; L.f[0] = cumb; break; }
+            cumb += w;
+        }
+    }
+    __syncthreads();
+    *total_out = total;
+    if (L.i[0] >= 0) { *before = L.f[0]; return L.i[0]; }
+    *before = -INFINITY;
+    return L.i[1] < 0 ? 0 : L.i[1];
+}
+
+// By wave 0: the id inside block b at which the cumulative mass (mass(id), in id order) exceeds `rest`; with rest = +inf or
+// nothing crossing, the last id with mass.  The result goes to L.i[2] (every thread reads it after the barrier that follows).
+template <class Mass>
+__device__ __forceinline__ void pick_in_block(DrawLds &L, int b, float rest, bool take_last, Mass mass) {
+    if (threadIdx.x >= 64) return;
+    const int lane = threadIdx.x;
+    const f32x4e m = mass(b, lane);
+    const float ls = ((m[0] + m[1]) + m[2]) + m[3];
+    float incl = ls;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
+    }
+    const float prev = incl - ls;                         // (exclusive prefix of this lane)
+    int last = -1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) if (m[j] > 0.f) last = b * DRAW_BLOCK + lane * 4 + j;
+    int mine = -1;
+    if (!take_last && ls > 0.f && incl > rest) {          // the crossing falls into this lane's four ids
+        float c = prev;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            c += m[j];
+            if (mine < 0 && m[j] > 0.f && c > rest) mine = b * DRAW_BLOCK + lane * 4 + j;
+        }
+        if (mine < 0) mine = last;                        // (prev + the four masses rounded below incl)
+    }
+    // first crossing lane wins; otherwise the last id with mass
+    const unsigned long long crossed = __ballot(mine >= 0);
+    int pick;
+    if (crossed) {
+        const int src = __ffsll((long long)crossed) - 1;
+        pick = __shfl(mine, src, 64);
+    } else {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, 64));
+        pick = last;
+    }
+    if (lane == 0) L.i[2] = pick;
+}
+
+// the four masses exp((row[id] - mx) * inv_t) of lane's ids in block b (0 beyond the vocabulary)
+__device__ __forceinline__ f32x4e exp_masses(const float *row, int ld, int vocab, int b, int lane, float mx, float inv_t) {
+    const int id0 = b * DRAW_BLOCK + lane * 4;
+    f32x4e v = f32x4e{0.f, 0.f, 0.f, 0.f};
+    if (id0 + 3 < ld) v = *reinterpret_cast<const f32x4e *>(row + id0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = id0 + j < vocab ? expf((v[j] - mx) * inv_t) : 0.f;
+    return v;
+}
+
+__device__ __forceinline__ float draw_block_max(float v, DrawLds &L) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) L.red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float m = L.red[0];
+    for (int w = 1; w < DRAW_THREADS / 64; ++w) m = fmaxf(m, L.red[w]);
+    return m;
+}
+
+// the largest of row[0 .. vocab)
+__device__ __forceinline__ float row_max(const float *row, int ld, int vocab, int nblk, DrawLds &L) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float mx = -INFINITY;
+    for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
+        const int id0 = b * DRAW_BLOCK + lane * 4;
+        if (id0 + 3 < ld) {
+            const f32x4e v = *reinterpret_cast<const f32x4e *>(row + id0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) if (id0 + j < vocab) mx = fmaxf(mx, v[j]);
+        }
+    }
+    return draw_block_max(mx, L);
+}
+
+__global__ __launch_bounds__(DRAW_THREADS) void sample_children_kernel(const float *__restrict__ logits, int ld, int vocab, int k,
+                                                                       float inv_t, const float *__restrict__ u,
+                                                                       int32_t *__restrict__ out_id, float *__restrict__ out_logp) {
+    __shared__ DrawLds L;
+    const int rowi = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const float *row = logits + (size_t)rowi * ld;
+    const int nblk = (vocab + DRAW_BLOCK - 1) / DRAW_BLOCK;
+    const float mx = row_max(row, ld, vocab, nblk, L);
+    // masses of a block without the ids already drawn (n_removed of them)
+    auto masses = [&](int b, int ln, int n_removed) {
+        f32x4e m = exp_masses(row, ld, vocab, b, ln, mx, inv_t);
+        const int id0 = b * DRAW_BLOCK + ln * 4;
+        for (int j = 0; j < n_removed; ++j) {
+            const int r = L.removed[j] - id0;
+            if (r >= 0 && r < 4) m[r] = 0.f;
+        }
+        return m;
+    };
+    for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
+        const f32x4e m = masses(b, lane, 0);
+        const float s = wave_sum(((m[0] + m[1]) + m[2]) + m[3]);
+        if (lane == 0) L.bsum[b] = s;
+    }
+    __syncthreads();
+    float log_z = 0.f;
+    for (int d = 0; d < k; ++d) {
+        float before, total;
+        const int b = find_block(L, nblk, u[rowi * k + d], &before, &total);
+        if (d == 0) log_z = logf(total);                  // the normaliser of the full distribution
+        const float target = u[rowi * k + d] * total;
+        pick_in_block(L, b, target - before, before == -INFINITY, [&](int bb, int ln) { return masses(bb, ln, d); });
+        __syncthreads();
+        const int c = L.i[2];
+        if (tid == 0) {
+            L.removed[d] = c;
+            out_id[rowi * k + d] = c;
+            out_logp[rowi * k + d] = (row[c] - mx) * inv_t - log_z;
+        }
+        __syncthreads();
+        if (wave == 0) {                                  // the block's mass without the id just drawn, formed afresh
+            const f32x4e m = masses(b, lane, d + 1);
+            const float s = wave_sum(((m[0] + m[1]) + m[2]) + m[3]);
+            if (lane == 0) L.bsum[b] = s;
+        }
+        __syncthreads();
+    }
+}
+
+void launch_sample_children(const float *logits, int ld, int rows, int vocab, int k, float temperature, const float *u,
+                            int32_t *out_id, float *out_logp, hipStream_t st) {
+    hipLaunchKernelGGL(sample_children_kernel, dim3(rows), dim3(DRAW_THREADS), 0, st, logits, ld, vocab, k, 1.0f / temperature, u,
+                       out_id, out_logp);
+}
+
+__global__ __launch_bounds__(DRAW_THREADS) void rejection_walk_kernel(TreeDev td, int k, int L_depth, int vocab,
+                                                                      const float *__restrict__ target_logits,
+                                                                      const float *__restrict__ draft_logits, int ld, float inv_t,
+                                                                      const float *__restrict__ ua, float *__restrict__ resid,
+                                                                      int32_t *__restrict__ g) {
+    __shared__ DrawLds L;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int nblk = (vocab + DRAW_BLOCK - 1) / DRAW_BLOCK;
+    auto resid_masses = [&](int b, int ln) {
+        const int id0 = b * DRAW_BLOCK + ln * 4;
+        f32x4e v = f32x4e{0.f, 0.f, 0.f, 0.f};
+        if (id0 + 3 < ld) v = *reinterpret_cast<const f32x4e *>(resid + id0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) if (id0 + j >= vocab) v[j] = 0.f;
+        return v;
+    };
+    const int n_nodes = td.n_nodes[0];
+    for (int i = tid; i < n_nodes; i += DRAW_THREADS) g[i] = -1;
+    int cur = 0;
+    for (int step = 0; step <= L_depth; ++step) {         // at most L accepted children, then the last token
+        const int d = td.depth[cur];
+        const float *prow = target_logits + (size_t)cur * ld;
+        const float mp = row_max(prow, ld, vocab, nblk, L);
+        // which drafter row expanded this node, and where its drawn children sit in the pool
+        int e = -1, cbase = 0;
+        if (cur == 0) { e = 0; cbase = 0; }
+        else if (d < L_depth) {
+            const int pv = td.node_pool[cur];
+            for (int r = 0; r < k; ++r)
+                if (td.fr_pool[d * k + r] == pv) { e = 1 + (d - 1) * k + r; cbase = k + (d - 1) * k * k + r * k; }
+        }
+        // block sums of the target's masses P = exp((l - max) / T); zp = their total (p = P / zp)
+        for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
+            const f32x4e m = exp_masses(prow, ld, vocab, b, lane, mp, inv_t);
+            const float s = wave_sum(((m[0] + m[1]) + m[2]) + m[3]);
+            if (lane == 0) L.bsum[b] = s;
+        }
+        __syncthreads();
+        if (e < 0) {                                      // no drawn children: the target's own token ends the walk
+            float before, total;
+            const float un = ua[d * (k + 1) + k];
+            const int b = find_block(L, nblk, un, &before, &total);
+            pick_in_block(L, b, un * total - before, before == -INFINITY,
+                          [&](int bb, int ln) { return exp_masses(prow, ld, vocab, bb, ln, mp, inv_t); });
+            __syncthreads();
+            if (tid == 0) g[cur] = L.i[2];
+            return;
+        }
+        float before_unused, zp;
+        (void)find_block(L, nblk, 0.f, &before_unused, &zp);
+        const float *qrow = draft_logits + (size_t)e * ld;
+        const float mq = row_max(qrow, ld, vocab, nblk, L);
+        float sq = 0.f;                                   // zq: total of the drafter's masses, same block order
+        for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
+            const f32x4e m = exp_masses(qrow, ld, vocab, b, lane, mq, inv_t);
+            sq += ((m[0] + m[1]) + m[2]) + m[3];
+        }
+        float zq = block_sum(sq, L.red);
+        bool have_resid = false;
+        int next = -1, last_tok = -1;
+        for (int i = 0; i < k; ++i) {
+            const int c = td.pool_token[cbase + i];
+            const float pc = (have_resid ? resid[c] : expf((prow[c] - mp) * inv_t)) / zp;
+            const float ec = expf((qrow[c] - mq) * inv_t), qc = ec / zq;
+            const float a = fminf(1.f, pc / qc);
+            if (ua[d * (k + 1) + i] < a) {                // accepted (every thread takes the same decision)
+                const int node = td.pool_node[cbase + i];
+                if (tid == 0) g[cur] = c;
+                if (node >= 0) next = node; else last_tok = c;
+                break;
+            }
+            // rejected: P <- max(P / zp - Q / zq, 0) with its block sums, zp <- their total; the candidate leaves q
+            __syncthreads();                              // resid[c] has been read by every thread
+            for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
+                const int id0 = b * DRAW_BLOCK + lane * 4;
+                const f32x4e pm = have_resid ? resid_masses(b, lane) : exp_masses(prow, ld, vocab, b, lane, mp, inv_t);
+                f32x4e qm = exp_masses(qrow, ld, vocab, b, lane, mq, inv_t);
+                for (int j = 0; j < i; ++j) {
+                    const int r = L.removed[j] - id0;
+                    if (r >= 0 && r < 4) qm[r] = 0.f;
+                }
+                f32x4e r4;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) r4[j] = fmaxf(pm[j] / zp - qm[j] / zq, 0.f);
+                if (id0 + 3 < ld) *reinterpret_cast<f32x4e *>(resid + id0) = r4;
+                const float s = wave_sum(((r4[0] + r4[1]) + r4[2]) + r4[3]);
+                if (lane == 0) L.bsum[b] = s;
+            }
+            if (tid == 0) L.removed[i] = c;
+            __syncthreads();
+            (void)find_block(L, nblk, 0.f, &before_unused, &zp);   // (its barriers also publish resid[])
+            zq -= ec;
+            have_resid = true;
+        }
+        if (next >= 0) { cur = next; continue; }
+        if (last_tok < 0) {                               // every candidate rejected: draw from the last residual
+            float before, total;
+            const float un = ua[d * (k + 1) + k];
+            const int b = find_block(L, nblk, un, &before, &total);
+            pick_in_block(L, b, un * total - before, before == -INFINITY, resid_masses);
+            __syncthreads();
+            if (tid == 0) g[cur] = L.i[2];
+        }
+        return;
+    }
+}
+
+void launch_rejection_walk(const TreeDev &td, int k, int L, int vocab, const float *target_logits, const float *draft_logits,
+                           int ld, float temperature, const float *ua, float *resid, int32_t *g, hipStream_t st) {
+    hipLaunchKernelGGL(rejection_walk_kernel, dim3(1), dim3(DRAW_THREADS), 0, st, td, k, L, vocab, target_logits, draft_logits, ld,
+                       1.0f / temperature, ua, resid, g);
+}
+
 __global__ void copy_rows_f32_kernel(const float *__restrict__ src, int ld_src, float *__restrict__ dst, int ld_dst,
                                      int cols) {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;

@@ -275,6 +275,7 @@ void launch_tree_expand(const TreeDev *tds, int n_seq, int d, int k, int L, int 
 // Keep the n_keep best candidates; order them as candidates are ordered (parents first); node 0 is
 // the root x_t.  pos = t + depth; mask = node and its ancestors; slot = t + node index.
 constexpr int POOL_MAX = 2048;
+constexpr int POSS_TREE_MAX_DEPTH = 16;              // the deepest tree a context can be configured for
 __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeBatch tb, int pool_n, int n_keep) {
     const TreeDev &td = tb.td[blockIdx.x];
     const int t = tb.t[blockIdx.x];
@@ -330,12 +331,17 @@ __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeBatch tb, int p
         const int i = tid + p * 1024;
         int off = 0;
         for (int w = 0; w < p * 16 + wave; ++w) off += wave_cnt[w];
-        if (i < pool_n) new_idx[i] = keep[p] ? (int16_t)(off + before[p] + 1) : (int16_t)-1;
+        if (i < pool_n) {
+            new_idx[i] = keep[p] ? (int16_t)(off + before[p] + 1) : (int16_t)-1;
+            td.pool_node[i] = new_idx[i];
+            if (keep[p]) td.node_pool[new_idx[i]] = i;
+        }
     }
     if (tid == 0) {
         td.n_nodes[0] = total + 1;
         td.token[0] = tokens_dev[t]; td.parent[0] = -1; td.depth[0] = 0; td.pos[0] = t; td.score[0] = 0.f;
         td.mask[0] = 1ull; td.mask[1] = 0ull;
+        td.node_pool[0] = -1;
         slot_out[0] = t;
     }
     __syncthreads();
@@ -353,7 +359,7 @@ __global__ __launch_bounds__(1024) void tree_finalize_kernel(TreeBatch tb, int p
         slot_out[ni] = t + ni;
         td.score[ni] = sc[i];
         uint64_t w0 = 1ull, w1 = 0ull;               // the root
-        for (int u = i; u >= 0; u = par[u]) {
+        for (int u = i, hops = 0; u >= 0 && hops <= POSS_TREE_MAX_DEPTH; u = par[u], ++hops) {   // (bounded: a node has at most depth ancestors)
             const int bit = new_idx[u];
             if (bit < 64) w0 |= 1ull << bit; else w1 |= 1ull << (bit - 64);
         }

@@ -157,3 +157,116 @@ def test_sampling_arguments_are_checked():
     with pytest.raises(P.PossError):
         ctx.set_sampling(1.0, [0.5] * 40)
     pair.close()
+
+
+# ---------------------------------------------------------------------- drawn children, rejection rule
+def _numbers(cfg, seed):
+    rng = np.random.default_rng(seed)
+    return (rng.random((cfg.depth, cfg.top_k, cfg.top_k)).astype(np.float32),
+            rng.random((cfg.depth + 1, cfg.top_k + 1)).astype(np.float32))
+
+
+@pytest.mark.parametrize("T", [1.0, 0.6])
+def test_drawn_children_and_rejection_walk_equal_the_oracle(T):
+    """The second reading of verification at a temperature, round by round against the oracle with the same uniform
+    numbers.  A vocabulary of 96 tokens keeps every draw's interval wide: numbers are screened by the oracle so that
+    every draw and every accept test has a margin of 2e-4 (float32 sums here, float64 there), and then the drawn
+    children, the tree, the accepted path and the last token must be identical."""
+    pair = Pair("c0_tiny_f32", vocab=96)
+    cfg, ctx = pair.cfg, pair.ctx
+    o = pair.oracle()
+    prompt = make_prompt(cfg, n=24)
+    assert ctx.prefill(prompt) == o.prefill(prompt)
+    ctx.set_sampling(T, np.zeros(cfg.depth + 1, np.float32))
+    seed, rounds, lengths, kinds = 0, 0, [], set()
+    while rounds < 8 and seed < 400:
+        seed += 1
+        UD, UA = _numbers(cfg, seed)
+        snap = (list(o.tokens), list(o.feats), list(o.kv), o.stats.rounds)
+        otree = o.draft_tree(sampling=(T, UD))
+        opath, olast = o.verify_tree_sampled(otree, T, UA)
+        if min(o.draw_margins) < 2e-4 or (o.accept_margins and min(o.accept_margins) < 2e-4):
+            continue                                          # too close to call in float32: other numbers
+        _say(f"  T={T}: numbers {seed} pass the screen, round {rounds} on the GPU")
+        ctx.set_draft_sampling(UD, UA)
+        d = ctx.draft_tree().as_dict()
+        assert d["token"][1:] == otree.token[1:] and d["parent"] == otree.parent, f"seed {seed}"
+        assert np.abs(d["score"] - np.array(otree.score, dtype=np.float32)).max() < 1e-4
+        g = ctx.verify_tree()
+        path, m, toks = ctx.accept_and_commit()
+        assert path == opath and toks[-1] == olast and toks[:-1] == [otree.token[p] for p in opath[1:]], f"seed {seed}"
+        assert all(g[a] == otree.token[b] for a, b in zip(path, path[1:])) and g[path[-1]] == olast
+        o.accept_and_commit(path=opath, bonus=olast)
+        assert ctx.tokens() == o.tokens
+        rounds += 1
+        lengths.append(m)
+        tb = o.last["builder"]
+        pv = otree.pool_index[opath[-1]]
+        kinds.add("leaf" if pv not in tb.expanded else ("dropped child" if olast in [tb.token[c] for c in tb.expanded[pv]] else "residual"))
+    _say(f"  T={T}: {rounds} rounds compared ({seed} sets of numbers tried), accepted lengths {lengths}, walks ended by {sorted(kinds)}")
+    assert rounds == 8 and max(lengths) >= 1
+    # back to the deterministic tree: the coupling rule again
+    ctx.set_draft_sampling(None)
+    ctx.set_sampling(0.0)
+    tr = ctx.draft_tree().as_dict()
+    kids = [tr["token"][i] for i in range(1, tr["n"]) if tr["parent"][i] == 0]
+    assert len(set(kids)) == len(kids)
+    pair.close()
+
+
+@pytest.mark.parametrize("name", ["t_mid_bf16", "t_mid_f16"])
+def test_drawn_children_at_16_bit_shapes_give_valid_rounds(name):
+    """16-bit storage, vocabularies of thousands: draws fall too close to interval ends for a token-by-token comparison,
+    so the rounds are checked for what must hold whatever the numbers: distinct children under every node, scores that
+    are sums of log-probabilities (non-positive steps), a path that is a root path, a last token that is not a kept child
+    of the last node, a consistent token stream."""
+    pair = Pair(name)
+    cfg, ctx = pair.cfg, pair.ctx
+    ctx.prefill(make_prompt(cfg))
+    ctx.set_sampling(1.0, np.zeros(cfg.depth + 1, np.float32))
+    n_before = len(ctx.tokens())
+    total = 0
+    for rnd in range(5):
+        UD, UA = _numbers(cfg, 100 + rnd)
+        ctx.set_draft_sampling(UD, UA)
+        d = ctx.draft_tree().as_dict()
+        assert d["n"] == cfg.total_tokens + 1
+        kids = {}
+        for i in range(1, d["n"]):
+            kids.setdefault(d["parent"][i], []).append(d["token"][i])
+            assert d["score"][i] <= d["score"][d["parent"][i]] + 1e-6
+        assert all(len(set(v)) == len(v) for v in kids.values())
+        ctx.verify_tree()
+        path, m, toks = ctx.accept_and_commit()
+        assert path[0] == 0 and all(d["parent"][b] == a for a, b in zip(path, path[1:]))
+        assert toks[:-1] == [d["token"][p] for p in path[1:]] and toks[-1] not in kids.get(path[-1], [])
+        total += len(toks)
+    assert len(ctx.tokens()) == n_before + total
+    pair.close()
+
+
+def test_drawn_children_arguments_and_call_order_are_checked():
+    pair = Pair("c0_tiny_f32")
+    cfg, ctx = pair.cfg, pair.ctx
+    UD, UA = _numbers(cfg, 1)
+    bad = UD.copy(); bad[0, 0, 0] = 1.0
+    with pytest.raises(P.PossError):
+        ctx.set_draft_sampling(bad, UA)
+    ctx.prefill(make_prompt(cfg, n=12))
+    ctx.set_draft_sampling(UD, UA)
+    with pytest.raises(P.PossError) as ei:                    # no temperature set
+        ctx.draft_tree()
+    assert ei.value.code == P.E_BAD_STATE
+    ctx.set_sampling(1.0, np.zeros(cfg.depth + 1, np.float32))
+    ctx.draft_tree()
+    with pytest.raises(P.PossError) as ei:                    # a caller's tree has no draft distributions
+        ctx.verify_tree(P.TreeArrays.from_lists([0], [-1]))
+    assert ei.value.code == P.E_BAD_STATE
+    ctx.verify_tree()
+    ctx.accept_and_commit()
+    pair.close()
+    two = Pair("c0_tiny_f32", lib_over=dict(batch=2))
+    with pytest.raises(P.PossError) as ei:
+        two.ctx.set_draft_sampling(UD, UA)
+    assert ei.value.code == P.E_INVALID_ARG
+    two.close()
