@@ -8,7 +8,7 @@
  *
  * With poss_config.batch = B > 1 a context carries B independent sequences:
  * each has its own caches, tree and token stream, every pass stacks their rows into one set of
- * weight-streaming launches (of at most POSS_MAX_ROWS rows: a larger batch runs its passes group by
+ * weight-streaming launches (of at most POSS_LAUNCH_ROWS rows: a larger batch runs its passes group by
  * group), and the three round calls advance all of them; poss_prefill_seq,
  * poss_get_tree_seq, poss_get_commit_seq, poss_get_tokens_seq and poss_set_uniforms_seq address one
  * sequence (the calls without _seq address sequence 0); poss_set_active and poss_reset_seq take a
@@ -51,7 +51,8 @@ extern "C" {
 #define POSS_DTYPE_BF16 1
 #define POSS_DTYPE_F16  2
 
-#define POSS_MAX_ROWS   128     /* rows one pass can carry: tree rows, prefill chunk  */
+#define POSS_MAX_ROWS   128     /* rows of ONE sequence in a pass: tree rows           */
+#define POSS_LAUNCH_ROWS 256    /* rows one launch carries: sequences together, prefill */
 #define POSS_MASK_WORDS 2       /* 64-bit words of one ancestor mask                  */
 #define POSS_MAX_DEPTH  16
 
@@ -235,6 +236,11 @@ int poss_gemm_profile(poss_ctx *ctx, int64_t *launches, double *ms, double *weig
 
 /* Tuning knobs for sweeps: target number of workgroups per GEMM launch (0 = default). */
 int poss_set_tuning(poss_ctx *ctx, int32_t gemm_target_workgroups, int32_t attn_keys_per_split);
+
+/* Rows that one launch of a batch's pass carries at most (POSS_MAX_ROWS .. POSS_LAUNCH_ROWS, default the latter): the
+ * sequences of a pass are grouped so that a group's rows fit.  A sequence's results do not depend on it; lower values
+ * re-stream the weights more often (for sweeps of that cost). */
+int poss_set_launch_rows(poss_ctx *ctx, int32_t rows);
 
 /* ---- test hooks (same kernels, inputs injected) ----------------------------------------- */
 

@@ -17,7 +17,7 @@ MAX_ROWS, MASK_WORDS, MAX_DEPTH = 128, 2, 16
 EXPORTS = ["poss_workspace_bytes", "poss_load", "poss_reset", "poss_prefill", "poss_draft_tree",
            "poss_verify_tree", "poss_accept_and_commit", "poss_get_stats", "poss_get_tokens",
            "poss_prefill_seq", "poss_get_tree_seq", "poss_get_commit_seq", "poss_get_tokens_seq", "poss_set_uniforms_seq", "poss_reset_seq", "poss_set_active",
-           "poss_last_error", "poss_free", "poss_profile_gemm", "poss_gemm_profile", "poss_set_tuning", "poss_set_sampling", "poss_set_draft_sampling",
+           "poss_last_error", "poss_free", "poss_profile_gemm", "poss_gemm_profile", "poss_set_tuning", "poss_set_launch_rows", "poss_set_sampling", "poss_set_draft_sampling",
            "poss_debug_build_tree", "poss_debug_set_taps", "poss_debug_read_kv",
            "poss_debug_gemm_scratch_bytes", "poss_debug_gemm", "poss_gemm_static"]
 
@@ -89,6 +89,7 @@ def load_library():
     lib.poss_profile_gemm.argtypes = [c_vp, c_i32]
     lib.poss_gemm_profile.argtypes = [c_vp, P(ctypes.c_int64), P(ctypes.c_double), P(ctypes.c_double)]
     lib.poss_set_tuning.argtypes = [c_vp, c_i32, c_i32]
+    lib.poss_set_launch_rows.argtypes = [c_vp, c_i32]
     lib.poss_set_sampling.argtypes = [c_vp, c_f32, ctypes.POINTER(c_f32), c_i32]
     lib.poss_set_uniforms_seq.argtypes = [c_vp, c_i32, ctypes.POINTER(c_f32), c_i32]
     lib.poss_set_draft_sampling.argtypes = [c_vp, c_i32, ctypes.POINTER(c_f32), ctypes.POINTER(c_f32)]
@@ -306,6 +307,10 @@ class Poss:
 
     def set_tuning(self, gemm_target_workgroups=0, attn_keys_per_split=0):
         self._check(self.lib.poss_set_tuning(self.h, gemm_target_workgroups, attn_keys_per_split))
+
+    def set_launch_rows(self, rows):
+        """Rows one launch of a batch's pass carries at most (128..256)."""
+        self._check(self.lib.poss_set_launch_rows(self.h, rows))
 
     def debug_build_tree(self, ids, logp):
         ids = np.ascontiguousarray(ids, dtype=np.int32)

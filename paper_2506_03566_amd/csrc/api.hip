@@ -102,6 +102,7 @@ struct poss_ctx {
     int draft_sampling;
     float *ud_pinned, *ua_pinned, *ud_dev, *ua_dev, *dlogits, *resid;
     int gemm_target_wgs, attn_keys_per_split;
+    int launch_rows;                   // rows one launch of a batch's pass carries (POSS_LAUNCH_ROWS unless lowered for a sweep)
     // gemm profiling
     int prof_on, prof_n;
     hipEvent_t prof_ev[2 * PROFILE_EVENTS];
@@ -200,7 +201,7 @@ size_t carve(const poss_config &c, Arena &a, poss_ctx *ctx, WeightSlots *ws) {
     for (int i = 0; i < B * 2 * (c.n_layers + c.n_specialists); ++i) kvp.push_back(a.take(cache_each));
     KVCache *kv_dev = a.take_n<KVCache>((size_t)B * c.n_layers);
     // activations
-    const int R = MAX_ROWS;
+    const int R = LAUNCH_ROWS;
     const int RA = B * (c.total_tokens + 1) > R ? B * (c.total_tokens + 1) : R;   // tree rows of all sequences (several groups)
     size_t part_floats = 0;
     const int shapes[6][2] = {{qd + 2 * kd, d}, {d, qd}, {gate_up_rows(F), d}, {d, F}, {d, 2 * d}, {V, d}};
@@ -423,7 +424,7 @@ __global__ void causal_meta_kernel(int n, int c0, int32_t *pos, int32_t *slot, u
     const int i = threadIdx.x;
     if (i >= n) return;
     pos[i] = c0 + i; slot[i] = c0 + i;
-    const int bits = i + 1;
+    const int bits = i % MAX_ROWS + 1;                     // within the row's range of MAX_ROWS rows
     mask[i * MASK_WORDS] = bits >= 64 ? ~0ull : ((1ull << bits) - 1);
     mask[i * MASK_WORDS + 1] = bits <= 64 ? 0ull : (bits >= 128 ? ~0ull : ((1ull << (bits - 64)) - 1));
 }
@@ -609,7 +610,7 @@ int poss_load(const poss_config *cfg, const poss_weights *w, void *workspace, si
     c->st = static_cast<hipStream_t>(hip_stream);
     c->err[0] = 0;
     c->taps_user = nullptr;
-    c->gemm_target_wgs = 0; c->attn_keys_per_split = 0;
+    c->gemm_target_wgs = 0; c->attn_keys_per_split = 0; c->launch_rows = LAUNCH_ROWS;
     c->prof_on = 0; c->prof_n = 0; c->prof_bytes = 0;
     Arena a(workspace);
     WeightSlots ws;
@@ -755,13 +756,19 @@ int poss_prefill_seq(poss_ctx *c, int32_t seq, const int32_t *prompt, int32_t n_
         if (prompt[i] < 0 || prompt[i] >= c->cfg.vocab) return fail(c, POSS_E_INVALID_ARG, "poss_prefill: token id %d out of range at %d", prompt[i], i);
     const ModelDims &md = c->md;
     int32_t *stage = static_cast<int32_t *>(c->pinned);
-    for (int c0 = 0; c0 < n_prompt; c0 += MAX_ROWS) {
-        const int rows = n_prompt - c0 < MAX_ROWS ? n_prompt - c0 : MAX_ROWS;
+    // A launch carries LAUNCH_ROWS prompt tokens as two row ranges of at most MAX_ROWS (the width of a row's mask): the
+    // second range finds the keys of the first, written by the same layer's QKV epilogue, in its committed prefix.
+    for (int c0 = 0; c0 < n_prompt; c0 += LAUNCH_ROWS) {
+        const int rows = n_prompt - c0 < LAUNCH_ROWS ? n_prompt - c0 : LAUNCH_ROWS;
         memcpy(stage, prompt + c0, rows * sizeof(int32_t));
         HIP_TRY(c, hipMemcpyAsync(sq.tokens_dev + c0, stage, rows * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
-        hipLaunchKernelGGL(causal_meta_kernel, dim3(1), dim3(MAX_ROWS), 0, c->st, rows, c0, c->row_pos, c->row_slot, c->row_mask);
+        hipLaunchKernelGGL(causal_meta_kernel, dim3(1), dim3(LAUNCH_ROWS), 0, c->st, rows, c0, c->row_pos, c->row_slot, c->row_mask);
         RowMeta rm{c->row_pos, c->row_slot, c->row_mask};
-        target_forward(c, rows, sq.tokens_dev + c0, rm, {Seg{seq, nullptr, 0, rows, rows, 0, c0, rows}}, c->feats);
+        std::vector<Seg> segs;
+        const int ra = rows < MAX_ROWS ? rows : MAX_ROWS;
+        segs.push_back(Seg{seq, nullptr, 0, ra, rows, 0, c0, ra});
+        if (rows > ra) segs.push_back(Seg{seq, nullptr, ra, rows - ra, rows, 0, c0 + ra, rows - ra});
+        target_forward(c, rows, sq.tokens_dev + c0, rm, segs, c->feats);
         stash_rows(c, sq, rows, c0);
         if (c0 + rows == n_prompt) {
             // Head on the last row only: its normed activations sit at row rows-1 of c->u
@@ -929,7 +936,7 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
         const int prev_each = d - 1 == 1 ? 1 : k;
         for (int i0 = 0; i0 < B;) {
             int i1 = i0, grows = 0;
-            while (i1 < B && grows + plans[i1].plan.n_rows <= MAX_ROWS) grows += plans[i1++].plan.n_rows;
+            while (i1 < B && grows + plans[i1].plan.n_rows <= c->launch_rows) grows += plans[i1++].plan.n_rows;
             std::vector<SeqPlan> gp(plans.begin() + i0, plans.begin() + i1);
             const int nb = i1 - i0;
             std::vector<int> q0;
@@ -1078,7 +1085,7 @@ int poss_verify_tree(poss_ctx *c, const poss_tree *tree, int32_t *argmax_out, vo
     const int n = n_rows[0];                               // host and device outputs: the first active sequence's rows
     for (int i0 = 0; i0 < B;) {
         int i1 = i0, grows = 0;
-        while (i1 < B && grows + n_rows[i1] <= MAX_ROWS) grows += n_rows[i1++];
+        while (i1 < B && grows + n_rows[i1] <= c->launch_rows) grows += n_rows[i1++];
         const int base = row0[i0];
         RowMeta rm{c->tree_pos_all + base, c->tree_slot_all + base, c->tree_mask_all + (size_t)base * MASK_WORDS};
         std::vector<Seg> segs;
@@ -1261,6 +1268,13 @@ int poss_set_tuning(poss_ctx *c, int32_t gemm_target_workgroups, int32_t attn_ke
     return POSS_OK;
 }
 
+int poss_set_launch_rows(poss_ctx *c, int32_t rows) {
+    if (!c) return POSS_E_INVALID_ARG;
+    if (rows < MAX_ROWS || rows > LAUNCH_ROWS) return fail(c, POSS_E_INVALID_ARG, "poss_set_launch_rows: %d is outside %d..%d", rows, MAX_ROWS, LAUNCH_ROWS);
+    c->launch_rows = rows;
+    return POSS_OK;
+}
+
 int poss_debug_set_taps(poss_ctx *c, void *taps) {
     if (!c) return POSS_E_INVALID_ARG;
     c->taps_user = static_cast<float *>(taps);
@@ -1296,17 +1310,17 @@ __global__ void sum_planes_kernel(const float *__restrict__ part, int S, size_t 
 }
 
 size_t poss_debug_gemm_scratch_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K) {
-    if (dtype < 0 || dtype > 2 || M < 1 || M > MAX_ROWS || N < 1 || K < 1) return 0;
+    if (dtype < 0 || dtype > 2 || M < 1 || M > LAUNCH_ROWS || N < 1 || K < 1) return 0;
     GemmShape g = gemm_plan(dtype, M, N, K, 4096);
     return (packed_elems(dtype, N, K) * dtype_size(dtype) + 255) / 256 * 256 +
-           (size_t)g.S * MAX_ROWS * g.Npad * sizeof(float) + (size_t)(g.Npad / GEMM_BLOCK_N) * sizeof(unsigned) + 1024;
+           (size_t)g.S * LAUNCH_ROWS * g.Npad * sizeof(float) + (size_t)(g.Npad / GEMM_BLOCK_N) * sizeof(unsigned) + 1024;
 }
 
 int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_t M, int32_t N, int32_t K,
                     int32_t target_workgroups, void *scratch, void *hip_stream, int32_t repeats,
                     float *ms_per_launch_out) {
     if (!x || !w || !y || !scratch) return fail(nullptr, POSS_E_INVALID_ARG, "poss_debug_gemm: null argument");
-    if (dtype < 0 || dtype > 2 || M < 1 || M > MAX_ROWS || N < 1 || K < 1 || repeats < 1)
+    if (dtype < 0 || dtype > 2 || M < 1 || M > LAUNCH_ROWS || N < 1 || K < 1 || repeats < 1)
         return fail(nullptr, POSS_E_INVALID_ARG, "poss_debug_gemm: bad shape");
     if (dtype != DT_F32 && (K % 8)) return fail(nullptr, POSS_E_INVALID_ARG, "poss_debug_gemm: K must be a multiple of 8");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -1315,7 +1329,7 @@ int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_
     void *wp = p;
     p += (packed_elems(dtype, N, K) * dtype_size(dtype) + 255) / 256 * 256;
     float *part = reinterpret_cast<float *>(p);
-    p += ((size_t)g.S * MAX_ROWS * g.Npad * sizeof(float) + 255) / 256 * 256;
+    p += ((size_t)g.S * LAUNCH_ROWS * g.Npad * sizeof(float) + 255) / 256 * 256;
     EpiArgs epi{};
     epi.mode = EPI_PLAIN; epi.out = static_cast<float *>(y); epi.ld_out = N;
     launch_pack(dtype, PackSrc{{w, nullptr, nullptr}, {N, 0, 0}}, K, wp, st);

@@ -32,7 +32,8 @@ constexpr int GEMM_WPB     = POSS_GEMM_WPB;           // waves per workgroup
 constexpr int GEMM_BLOCK_N = GEMM_NT * 16 * GEMM_WPB; // 128 columns per workgroup
 constexpr int GEMM_KSTEP   = 32;
 constexpr int GEMM_KCHUNK  = 256;                     // K is padded to this at pack time
-constexpr int MAX_ROWS     = 128;
+constexpr int MAX_ROWS     = 128;                     // rows of one sequence in a pass (tree masks are 128 bits wide)
+constexpr int LAUNCH_ROWS  = 256;                     // rows one weight-streaming launch carries (several sequences, prefill)
 constexpr int MASK_WORDS   = 2;
 
 static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }

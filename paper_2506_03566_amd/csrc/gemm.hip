@@ -1,4 +1,4 @@
-// Weight-streaming GEMM for M <= 128 activation rows:  Y[m][n] = sum_k X[m][k] W[n][k], with the
+// Weight-streaming GEMM for M <= 256 activation rows:  Y[m][n] = sum_k X[m][k] W[n][k], with the
 // operation that follows it in a Llama decoder layer fused into its epilogue.
 //
 // The round is bound by reading every weight once (the verify pass reads the whole target, each
@@ -44,6 +44,15 @@ template <> struct Mfma<f16_t> {
                                                       __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
 };
+
+// Rotation of one rotary pair, spelt out operation by operation (two products, two fused multiply-adds): the two kernels
+// that apply it must round alike, so nothing is left to the compiler's choice of what to contract.
+__device__ __forceinline__ void rope_pair(float x1, float x2, float2 cs, float &o1, float &o2) {
+#pragma clang fp contract(off)
+    const float p = x2 * cs.y, q = x1 * cs.y;
+    o1 = __builtin_fmaf(x1, cs.x, -p);
+    o2 = __builtin_fmaf(x2, cs.x, q);
+}
 
 constexpr int KCS = GEMM_KCHUNK / GEMM_KSTEP;   // k-steps per LDS chunk (8)
 // PF = weight k-steps in flight per wave (template parameter of the stream kernel): 4, or 8 for launches
@@ -111,14 +120,16 @@ __device__ __forceinline__ void tile_epilogue(const float *__restrict__ part, si
             const int sl = e.slot[r];
             const float x1 = sum_planes(part, plane, S, (size_t)r * Npad + c1);
             const float x2 = sum_planes(part, plane, S, (size_t)r * Npad + c2);
+            float o1, o2;
+            rope_pair(x1, x2, cs, o1, o2);
             if (gh < e.hq) {
                 T *dst = q + ((size_t)r * e.hq + gh) * e.dh;
-                dst[i] = from_f<T>(x1 * cs.x - x2 * cs.y);
-                dst[i + half] = from_f<T>(x2 * cs.x + x1 * cs.y);
+                dst[i] = from_f<T>(o1);
+                dst[i + half] = from_f<T>(o2);
             } else if (gh < e.hq + e.hkv) {
                 T *dst = kc + k_offset(e.kv, sl, gh - e.hq, e.hkv, e.dh);
-                dst[i] = from_f<T>(x1 * cs.x - x2 * cs.y);
-                dst[i + half] = from_f<T>(x2 * cs.x + x1 * cs.y);
+                dst[i] = from_f<T>(o1);
+                dst[i + half] = from_f<T>(o2);
             } else {
                 const int vh = gh - e.hq - e.hkv;
                 vc[vt_offset(e.kv, sl, vh, e.hkv, e.dh, i)] = from_f<T>(x1);
@@ -168,22 +179,25 @@ __device__ __forceinline__ void half_argmax(float &v, int &i) {
     }
 }
 
-template <typename T, int MT, int WPB, bool FUSE_SILU, int PF, bool HEAD = false>
+// KCL = k-steps of one staged activation chunk: 8, or 4 above 128 rows so that two chunks of 16 row tiles fit the LDS.
+// Splits own whole groups of 8 k-steps whatever KCL is, and a wave adds its k-steps in ascending order: a row's sum
+// does not depend on the instantiation that computes it.
+template <typename T, int MT, int WPB, bool FUSE_SILU, int PF, bool HEAD = false, int KCL = (MT > 8 ? 4 : KCS)>
 __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
     int M, int K, int Npad, int ksteps_total, T *__restrict__ act, int F, HeadEpi he) {
-    static_assert(KCS % PF == 0, "ring index must be static");
-    constexpr int XUNITS = KCS * MT * 64;                 // 16-byte units of one staged chunk
+    static_assert(KCL % PF == 0 && KCS % KCL == 0, "ring index must be static");
+    constexpr int XUNITS = KCL * MT * 64;                 // 16-byte units of one staged chunk
     // units per thread; where 64 * WPB does not divide the units the last threads stage the last unit again
     constexpr int XPT    = (XUNITS + WPB * 64 - 1) / (WPB * 64);
     __shared__ u32x4 xs[2][XUNITS];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     // split y of gridDim.y owns chunks [y * n / S, (y + 1) * n / S): sizes differ by at most one chunk
     const int n_chunks_total = ksteps_total / KCS;
-    const int chunk0 = (int)blockIdx.y * n_chunks_total / (int)gridDim.y;
-    const int chunk1 = ((int)blockIdx.y + 1) * n_chunks_total / (int)gridDim.y;
+    const int chunk0 = ((int)blockIdx.y * n_chunks_total / (int)gridDim.y) * (KCS / KCL);          // in staged chunks
+    const int chunk1 = (((int)blockIdx.y + 1) * n_chunks_total / (int)gridDim.y) * (KCS / KCL);
     const int ngroup = blockIdx.x * WPB + wave;
-    const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCS) * (GEMM_NT * 64) + lane;
+    const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCL) * (GEMM_NT * 64) + lane;
 
     // Global->LDS staging map: a wave instruction covers one A-operand block [k_step][m_tile] (64 units of 16
     // bytes): four consecutive lanes take the four 8-element groups of one row's k-step (64 contiguous bytes in
@@ -209,14 +223,14 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     auto load_x = [&](int chunk, u32x4 (&xr)[XPT]) {
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const int k = chunk * GEMM_KCHUNK + x_k[i];
+            const int k = chunk * (KCL * GEMM_KSTEP) + x_k[i];
             xr[i] = *reinterpret_cast<const u32x4 *>(x_src[i] + (k < K ? k : K - 8));
         }
     };
     auto store_x = [&](int chunk, int b, const u32x4 (&xr)[XPT]) {   // the select happens here, not at the load
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const bool ok = x_row_ok[i] && chunk * GEMM_KCHUNK + x_k[i] < K;
+            const bool ok = x_row_ok[i] && chunk * (KCL * GEMM_KSTEP) + x_k[i] < K;
             xs[b][x_dst[i]] = ok ? xr[i] : u32x4{0u, 0u, 0u, 0u};
         }
     };
@@ -231,7 +245,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     load_x(chunk0, xr);
     u32x4 wr[PF][GEMM_NT];
 #pragma unroll
-    for (int p = 0; p < PF; ++p) {                   // a workgroup owns at least one chunk (KCS >= PF steps)
+    for (int p = 0; p < PF; ++p) {                   // a workgroup owns at least one chunk (KCL >= PF steps)
 #pragma unroll
         for (int nt = 0; nt < GEMM_NT; ++nt) wr[p][nt] = __builtin_nontemporal_load(wp + nt * 64);
         wp += GEMM_NT * 64;
@@ -239,7 +253,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     store_x(chunk0, 0, xr);
     __syncthreads();
 
-    // One chunk of KCS k-steps.  MORE (another chunk follows) is a compile-time flag so that the
+    // One chunk of KCL k-steps.  MORE (another chunk follows) is a compile-time flag so that the
     // body is straight-line code: the weight ring is refilled PF steps ahead, across the chunk
     // boundary when MORE, and the next chunk's activations are requested before any of it.
     int buf = 0;
@@ -252,15 +266,15 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) a[0][mt] = xs[buf][mt * 64 + lane];
 #pragma unroll
-        for (int i = 0; i < KCS; ++i) {
-            if (i + 1 < KCS) {
+        for (int i = 0; i < KCL; ++i) {
+            if (i + 1 < KCL) {
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) a[(i + 1) & 1][mt] = xs[buf][((i + 1) * MT + mt) * 64 + lane];
             }
             u32x4 w[GEMM_NT];
 #pragma unroll
             for (int nt = 0; nt < GEMM_NT; ++nt) w[nt] = wr[i % PF][nt];
-            if (MORE || i + PF < KCS) {
+            if (MORE || i + PF < KCL) {
 #pragma unroll
                 for (int nt = 0; nt < GEMM_NT; ++nt) wr[i % PF][nt] = __builtin_nontemporal_load(wp + nt * 64);
                 wp += GEMM_NT * 64;
@@ -497,15 +511,17 @@ __global__ __launch_bounds__(256) void gemm_qkv_rope_kernel(const u32x4 *__restr
                 const float a = x1[r], b = x2[r];
                 if (gh < e.hq) {
                     if (m >= rows_q) continue;
-                    const float2 cs = e.cs[m * half + i];
+                    float o1, o2;
+                    rope_pair(a, b, e.cs[m * half + i], o1, o2);
                     T *dst = q + ((size_t)m * e.hq + gh) * e.dh;
-                    dst[i] = from_f<T>(a * cs.x - b * cs.y);
-                    dst[i + half] = from_f<T>(b * cs.x + a * cs.y);
+                    dst[i] = from_f<T>(o1);
+                    dst[i + half] = from_f<T>(o2);
                 } else if (gh < e.hq + e.hkv) {
-                    const float2 cs = e.cs[m * half + i];
+                    float o1, o2;
+                    rope_pair(a, b, e.cs[m * half + i], o1, o2);
                     T *dst = kc + k_offset(kv, e.slot[m], gh - e.hq, e.hkv, e.dh);
-                    dst[i] = from_f<T>(a * cs.x - b * cs.y);
-                    dst[i + half] = from_f<T>(b * cs.x + a * cs.y);
+                    dst[i] = from_f<T>(o1);
+                    dst[i + half] = from_f<T>(o2);
                 } else {
                     const int vh = gh - e.hq - e.hkv, sl = e.slot[m];
                     vc[vt_offset(kv, sl, vh, e.hkv, e.dh, i)] = from_f<T>(a);
@@ -614,7 +630,7 @@ __global__ __launch_bounds__(256) void epilogue_rope_ranges_kernel(const float *
 // Row count of a partial plane as the kernel instantiation writes it.
 static int gemm_rows_written(int mpad) {
     const int mt = mpad / 16;
-    return (mt <= 2 ? mt : mt <= 4 ? 4 : mt <= 6 ? 6 : 8) * 16;
+    return (mt <= 2 ? mt : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : mt <= 12 ? 12 : 16) * 16;
 }
 
 GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
@@ -624,7 +640,7 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
     g.Kpad = gemm_kpad(dt, K);
     g.Mpad = round_up(M < 1 ? 1 : M, 16);
     if (dt == DT_F32) { g.S = 1; return g; }
-    g.Mpad = gemm_rows_written(g.Mpad);       // the kernel is instantiated for 1, 2, 4, 6 or 8 row tiles
+    g.Mpad = gemm_rows_written(g.Mpad);       // the kernel is instantiated for 1, 2, 4, 6, 8, 12 or 16 row tiles
     const int n_blocks = g.Npad / GEMM_BLOCK_N;
     const int n_chunks = g.Kpad / GEMM_KCHUNK;
     // One workgroup per CU (256) at most, as many as fit, chunks dealt out evenly: in every sweep more
@@ -713,7 +729,10 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     // The QKV projection of at most 32 rows (draft passes, plain decoding) runs as one kernel with the K split inside the
     // workgroup; with more rows that kernel's activation traffic (every workgroup reads every row over the whole K)
     // outweighs the partial planes and the epilogue kernel it saves: 25 us against 13.6 + 4.9 us at 61 rows of the 8B shape.
-    if (epi.mode == EPI_ROPE_KV && g.Mpad <= 32) {
+    // It is used only where its four waves own exactly the four splits the streaming kernel would take (four splits, chunk
+    // count a multiple of four) and adds them in the same order: a row then gets bit for bit the same sums from either
+    // kernel, whatever the number of rows that share its launch.
+    if (epi.mode == EPI_ROPE_KV && g.Mpad <= 32 && g.S == 4 && (g.Kpad / GEMM_KCHUNK) % 4 == 0) {
         launch_qkv_rope_t<T>(g, Wp, X, ldx, epi, *rr, st, ev_start, ev_stop);
         return;
     }
@@ -750,13 +769,23 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
         else if (deep) POSS_GEMM_LAUNCH(MT, 4, false, 8, false, 0);                                           \
         else POSS_GEMM_LAUNCH(MT, 4, false, 4, false, 0);                                                     \
     } while (0)
+    // above 128 rows: four waves, four k-steps in flight (the staged chunk is four k-steps long)
+#define POSS_GEMM_CASE_TALL(MT)                                                                               \
+    do {                                                                                                      \
+        if (fuse_silu) POSS_GEMM_LAUNCH(MT, 4, true, 4, false, epi.F);                                        \
+        else if (head) POSS_GEMM_LAUNCH(MT, 4, false, 4, true, 0);                                            \
+        else POSS_GEMM_LAUNCH(MT, 4, false, 4, false, 0);                                                     \
+    } while (0)
     switch (g.Mpad / 16) {
         case 1: POSS_GEMM_CASE(1); break;
         case 2: POSS_GEMM_CASE(2); break;
         case 4: POSS_GEMM_CASE(4); break;
         case 6: POSS_GEMM_CASE(6); break;
-        default: POSS_GEMM_CASE(8); break;
+        case 8: POSS_GEMM_CASE(8); break;
+        case 12: POSS_GEMM_CASE_TALL(12); break;
+        default: POSS_GEMM_CASE_TALL(16); break;
     }
+#undef POSS_GEMM_CASE_TALL
 #undef POSS_GEMM_CASE
 #undef POSS_GEMM_LAUNCH
     if (epi.mode == EPI_ROPE_KV) {                       // rotary + cache writes per row range, one launch
@@ -773,7 +802,7 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
 
 // Refuse, on the host, argument sets that would make a kernel write through a null pointer.
 static bool gemm_args_ok(const GemmShape &g, const void *Wp, const void *X, const float *part, const EpiArgs &e) {
-    if (!Wp || !X || !part || g.M < 1 || g.M > MAX_ROWS || g.S < 1) return false;
+    if (!Wp || !X || !part || g.M < 1 || g.M > LAUNCH_ROWS || g.S < 1) return false;
     switch (e.mode) {
         case EPI_PLAIN: return e.out || g.S == 1;          // unsplit: plane 0 is the result
         case EPI_ROPE_KV: return e.q && e.cs && e.slot && (e.dh == 64 || e.dh == 128 || !e.dh);   // caches: checked per range

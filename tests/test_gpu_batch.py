@@ -49,8 +49,10 @@ def _same_tree(a, b):
     ("t_tiny_f32_6x1", 2, (70, 33), True, 3),            # six specialists, one position each
     ("t_mid_bf16", 2, (150, 97), False, 4),              # 16-bit storage, 2 x 61 rows in the verification pass
     ("t_mid_f16", 1, (131,), False, 2),                  # batch field set to 1: the single-sequence path
-    ("c0_tiny_f32", 7, (16, 23, 40, 12, 31, 18, 27), True, 3),   # more rows than a launch carries: groups of 4 and 3 sequences
-    ("t_mid_bf16", 3, (150, 97, 120), False, 3),         # 3 x 61 rows: a group of two sequences and one of one
+    ("c0_tiny_f32", 7, (16, 23, 40, 12, 31, 18, 27), True, 3),   # 7 x 25 rows in one launch (float32 kernels)
+    ("t_mid_bf16", 3, (150, 97, 120), False, 3),         # 3 x 61 rows: the 12-row-tile instantiations
+    ("t_mid_bf16", 4, (150, 97, 120, 33), False, 3),     # 4 x 61 rows: one launch of 244 rows (16 row tiles)
+    ("t_mid_f16", 5, (150, 97, 120, 33, 64), False, 2),  # more rows than a launch carries: a group of four sequences and one of one
 ])
 def test_batched_rounds_equal_sequences_alone(name, batch, lengths, perfect, n_rounds):
     cfg = get_config(name)
@@ -129,10 +131,10 @@ def test_batched_context_refuses_what_it_cannot_do():
         P.Poss(cfg, pair.dev_weights, batch=9)
 
 
-@pytest.mark.parametrize("lengths", [(512, 300), (512, 300, 411)])
+@pytest.mark.parametrize("lengths", [(512, 300), (512, 300, 411, 77)])
 def test_full_size_batch_equals_each_sequence_alone(lengths):
     """The benchmark shape with two sequences per round (2 x 61 rows in the verification pass, the
-    128-row GEMM instantiations) and with three (a group of two and a group of one): trees, accepted
+    128-row GEMM instantiations) and with four (244 rows in one launch, 16 row tiles): trees, accepted
     paths and tokens of each sequence are the ones a context of its own produces."""
     import torch
     from synth.gpu import make_weights_on_device
@@ -337,14 +339,14 @@ def test_rounds_go_on_without_a_sequence_that_was_set_aside():
 
 
 def test_a_sequence_set_aside_in_a_batch_that_runs_in_groups():
-    """Six sequences whose verification rows need two passes (6 x 25 > 128): one of the first group is
+    """Six sequences whose verification rows need two passes (6 x 61 > 256): one of the first group is
     set aside after two rounds, so the groups are made up differently from then on; every sequence
     still commits what it commits alone."""
-    name, batch = "c0_tiny_f32", 6
+    name, batch = "t_mid_bf16", 6
     cfg = get_config(name)
-    pair = Pair(name, storage=_perfect_drafter_storage(cfg), lib_over={"batch": batch})
+    pair = Pair(name, lib_over={"batch": batch})
     ctx = pair.ctx
-    prompts = _prompts(cfg, (16, 23, 40, 12, 31, 18))
+    prompts = _prompts(cfg, (150, 97, 120, 33, 64, 141))
     n_rounds = [5, 2, 5, 5, 5, 5]
     alone = [_rounds_alone(pair, p, n) for p, n in zip(prompts, n_rounds)]
     for b, p in enumerate(prompts):

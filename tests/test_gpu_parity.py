@@ -29,7 +29,9 @@ def _say(msg):
 @pytest.mark.parametrize("dtype,M,N,K,twg", [
     (1, 61, 1000, 1408, 0), (2, 10, 520, 512, 0), (1, 81, 256, 768, 0), (1, 128, 384, 256, 0),
     (0, 25, 688, 256, 0), (1, 1, 128, 256, 0), (2, 33, 128, 1024, 0), (1, 61, 6144, 4096, 512),
-    (1, 16, 4096, 14336, 1024), (2, 96, 2000, 5120, 300), (1, 17, 130, 8, 0)])
+    (1, 16, 4096, 14336, 1024), (2, 96, 2000, 5120, 300), (1, 17, 130, 8, 0),
+    (1, 129, 384, 512, 0), (2, 200, 1000, 1408, 0), (1, 256, 6144, 4096, 512), (1, 244, 4096, 14336, 1024),
+    (2, 177, 130, 8, 0), (0, 150, 688, 256, 0)])
 def test_gemm_against_float64_matmul(dtype, M, N, K, twg):
     _say(f"gemm dtype={dtype} M={M} N={N} K={K} twg={twg}")
     rng = np.random.default_rng(M * 7 + N)
@@ -39,6 +41,21 @@ def test_gemm_against_float64_matmul(dtype, M, N, K, twg):
     ref = to_float64(x, dtype) @ to_float64(w, dtype).T
     err = np.abs(y.cpu().numpy().astype(np.float64) - ref).max()
     assert err < 2e-5 * np.sqrt(K / 256.0), err          # float32 accumulation of exact products
+
+
+@pytest.mark.parametrize("dtype,N,K,twg", [(1, 1000, 1408, 0), (2, 4096, 4096, 256), (1, 512, 14336, 0)])
+def test_a_gemm_row_does_not_depend_on_the_rows_around_it(dtype, N, K, twg):
+    """The same activation row in launches of 1, 10, 61, 122, 183 and 244 rows (every row-tile instantiation, the staged
+    chunks of 8 and of 4 k-steps): bit for bit the same result, which is what lets sequences share a launch."""
+    rng = np.random.default_rng(N + K)
+    x = to_storage(rng.normal(size=(244, K)), dtype)
+    w = to_device(to_storage(rng.normal(size=(N, K)) * 0.02, dtype), dtype)
+    full, _ = P.debug_gemm(dtype, to_device(x, dtype), w, twg)
+    full = full.cpu().numpy()
+    for M in (1, 10, 61, 122, 183):
+        _say(f"gemm rows dtype={dtype} M={M} N={N} K={K}")
+        y, _ = P.debug_gemm(dtype, to_device(x[:M], dtype), w, twg)
+        assert np.array_equal(y.cpu().numpy(), full[:M]), M
 
 
 # --------------------------------------------------------------------------- whole path, float32, strict

@@ -74,5 +74,5 @@ def test_null_arguments_are_rejected_before_any_gpu_work():
     assert lib.poss_accept_and_commit(None, None, None, None, None) == P.E_INVALID_ARG
     assert lib.poss_get_stats(None, None) == P.E_INVALID_ARG
     assert lib.poss_debug_gemm_scratch_bytes(1, 0, 10, 10) == 0
-    assert lib.poss_debug_gemm_scratch_bytes(1, 129, 10, 16) == 0
+    assert lib.poss_debug_gemm_scratch_bytes(1, 257, 10, 16) == 0
     lib.poss_free(None)
