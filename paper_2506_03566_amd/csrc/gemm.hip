@@ -179,31 +179,99 @@ __device__ __forceinline__ void half_argmax(float &v, int &i) {
     }
 }
 
-// KCL = k-steps of one staged activation chunk: 8, or 4 above 128 rows so that two chunks of 16 row tiles fit the LDS.
-// Splits own whole groups of 8 k-steps whatever KCL is, and a wave adds its k-steps in ascending order: a row's sum
-// does not depend on the instantiation that computes it.
-template <typename T, int MT, int WPB, bool FUSE_SILU, int PF, bool HEAD = false, int KCL = (MT > 8 ? 4 : KCS)>
+
+// ---- epilogues on a finished output tile, shared by the stream kernel and the tall kernel --------------------------
+// SiLU(gate) * up of a workgroup's rows x TW activation columns, collected in LDS (row stride TW + 8 elements: the four
+// row groups of a wave hit different banks) and written out so that a row leaves as one contiguous piece in 16-byte
+// stores instead of 16-column fragments of two bytes per lane.
+template <typename T, int ROWS, int TW, int NTHREADS>
+__device__ __forceinline__ void silu_tile_store(const T *tile, T *__restrict__ act, int M, int F, int f0, int tid) {
+    constexpr int TWP = TW + 8, EPV = 16 / (int)sizeof(T), PPR = TW / EPV;   // elements per 16-byte store, pieces per row
+    for (int p = tid; p < ROWS * PPR; p += NTHREADS) {
+        const int m = p / PPR, f = f0 + (p % PPR) * EPV;
+        if (m < M && f + EPV <= F)                       // F is a multiple of 8: a piece is inside or outside as a whole
+            *reinterpret_cast<u32x4 *>(act + (size_t)m * F + f) = *reinterpret_cast<const u32x4 *>(tile + m * TWP + (p % PPR) * EPV);
+    }
+}
+
+// The Head's reduction of a tile of logits in LDS, tile[row][TW] = columns [col0, col0 + TW): one half wave per row (NHW
+// of them; shuffles stay inside a half).  HEAD_ARGMAX: the best (value, index) of the row's segment; HEAD_TOPK: maximum,
+// sum of exp(l - max) in a fixed order, and the k best by k rounds of (argmax, remove).
+template <int TW, int NHW>
+__device__ __forceinline__ void head_tile_reduce(const float *tile, int M, const HeadEpi &he, int seg, int n_seg, int tid) {
+    constexpr int NVH = TW / 32;
+    const int hw = tid >> 5, hl = tid & 31, col0 = seg * TW;
+    for (int row = hw; row < M; row += NHW) {
+        float v[NVH]; int id[NVH];
+        float bv = -INFINITY; int bi = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < NVH; ++j) {
+            const int c = hl + 32 * j, n = col0 + c;
+            const bool ok = n < he.vocab;
+            v[j] = ok ? tile[row * TW + c] : -INFINITY;
+            id[j] = ok ? n : 0x7fffffff - j;         // dummies stay below every real entry
+            if (better(v[j], id[j], bv, bi)) { bv = v[j]; bi = id[j]; }
+        }
+        if (he.mode == HEAD_ARGMAX) {
+            half_argmax(bv, bi);
+            if (hl == 0) { he.pv[(size_t)row * n_seg + seg] = bv; he.pi[(size_t)row * n_seg + seg] = bi; }
+            continue;
+        }
+        float mx = bv;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 32));
+        float se = 0.f;
+#pragma unroll
+        for (int j = 0; j < NVH; ++j) se += v[j] > -INFINITY ? expf(v[j] - mx) : 0.f;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) se += __shfl_xor(se, o, 32);
+        float *rec = he.seg_out + ((size_t)row * n_seg + seg) * TOPK_REC;
+        if (hl == 0) { rec[0] = mx; rec[1] = se; }
+        float my_v = -INFINITY; int my_i = 0x7fffffff;
+        for (int r = 0; r < he.k; ++r) {
+            float wv = -INFINITY; int wi = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < NVH; ++j)
+                if (better(v[j], id[j], wv, wi)) { wv = v[j]; wi = id[j]; }
+            half_argmax(wv, wi);
+            if (hl == r) { my_v = wv; my_i = wi; }
+#pragma unroll
+            for (int j = 0; j < NVH; ++j)
+                if (id[j] == wi) v[j] = -INFINITY;   // real indices are unique: removes exactly the winner
+        }
+        if (hl < he.k) {
+            rec[2 + hl] = my_v;
+            reinterpret_cast<int *>(rec)[2 + TOPK_MAXK + hl] = my_v > -INFINITY ? my_i : 0x7fffffff;
+        }
+    }
+}
+
+__device__ __forceinline__ int xs_swizzle(int g) { return (0xea40 >> (4 * g)) & 15; }   // f(g) = 0, 4, 10, 14
+
+template <typename T, int MT, int WPB, bool FUSE_SILU, int PF, bool HEAD = false>
 __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
     int M, int K, int Npad, int ksteps_total, T *__restrict__ act, int F, HeadEpi he) {
-    static_assert(KCL % PF == 0 && KCS % KCL == 0, "ring index must be static");
-    constexpr int XUNITS = KCL * MT * 64;                 // 16-byte units of one staged chunk
+    static_assert(KCS % PF == 0, "ring index must be static");
+    constexpr int XUNITS = KCS * MT * 64;                 // 16-byte units of one staged chunk
     // units per thread; where 64 * WPB does not divide the units the last threads stage the last unit again
     constexpr int XPT    = (XUNITS + WPB * 64 - 1) / (WPB * 64);
     __shared__ u32x4 xs[2][XUNITS];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     // split y of gridDim.y owns chunks [y * n / S, (y + 1) * n / S): sizes differ by at most one chunk
     const int n_chunks_total = ksteps_total / KCS;
-    const int chunk0 = ((int)blockIdx.y * n_chunks_total / (int)gridDim.y) * (KCS / KCL);          // in staged chunks
-    const int chunk1 = (((int)blockIdx.y + 1) * n_chunks_total / (int)gridDim.y) * (KCS / KCL);
+    const int chunk0 = (int)blockIdx.y * n_chunks_total / (int)gridDim.y;
+    const int chunk1 = ((int)blockIdx.y + 1) * n_chunks_total / (int)gridDim.y;
     const int ngroup = blockIdx.x * WPB + wave;
-    const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCL) * (GEMM_NT * 64) + lane;
+    const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCS) * (GEMM_NT * 64) + lane;
 
     // Global->LDS staging map: a wave instruction covers one A-operand block [k_step][m_tile] (64 units of 16
     // bytes): four consecutive lanes take the four 8-element groups of one row's k-step (64 contiguous bytes in
-    // global memory), consecutive quads take consecutive rows.  In LDS the block is stored in operand order,
-    // unit (k8 & 3) * 16 + (m & 15), so the 16 rows of the wave spread over all 64 banks.  (With a wave covering
-    // 2 rows x 32 groups, contiguous along k, its 64 stores fell into 8 of the 64 banks.)
+    // global memory), consecutive quads take consecutive rows.  In LDS the block is stored in operand order with the
+    // row index swizzled by the k-group, unit g * 16 + (m ^ f(g)), f = {0, 4, 10, 14}: the four units a quad stores
+    // (same row, g = 0..3) would otherwise lie 256 bytes apart, in the same banks; with f the 8 and the 16 lanes that
+    // the LDS takes together always store to 8 and 16 different 16-byte columns, and a read (16 lanes of one g, all rows)
+    // still covers one contiguous 256 bytes.
     // Loads are never predicated (a predicated load becomes a branch, and the compiler then waits
     // for every outstanding load at it): out-of-range units read a clamped, valid address and are
     // zeroed by a select.
@@ -218,19 +286,19 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
         x_row_ok[i] = m < M;
         x_src[i] = X + (size_t)(m < M ? m : M - 1) * ldx;
         x_k[i] = k8 * 8;
-        x_dst[i] = blk * 64 + ((ln & 3) << 4) + (ln >> 2);
+        x_dst[i] = blk * 64 + ((ln & 3) << 4) + ((ln >> 2) ^ xs_swizzle(ln & 3));
     }
     auto load_x = [&](int chunk, u32x4 (&xr)[XPT]) {
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const int k = chunk * (KCL * GEMM_KSTEP) + x_k[i];
+            const int k = chunk * GEMM_KCHUNK + x_k[i];
             xr[i] = *reinterpret_cast<const u32x4 *>(x_src[i] + (k < K ? k : K - 8));
         }
     };
     auto store_x = [&](int chunk, int b, const u32x4 (&xr)[XPT]) {   // the select happens here, not at the load
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const bool ok = x_row_ok[i] && chunk * (KCL * GEMM_KSTEP) + x_k[i] < K;
+            const bool ok = x_row_ok[i] && chunk * GEMM_KCHUNK + x_k[i] < K;
             xs[b][x_dst[i]] = ok ? xr[i] : u32x4{0u, 0u, 0u, 0u};
         }
     };
@@ -245,7 +313,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     load_x(chunk0, xr);
     u32x4 wr[PF][GEMM_NT];
 #pragma unroll
-    for (int p = 0; p < PF; ++p) {                   // a workgroup owns at least one chunk (KCL >= PF steps)
+    for (int p = 0; p < PF; ++p) {                   // a workgroup owns at least one chunk (KCS >= PF steps)
 #pragma unroll
         for (int nt = 0; nt < GEMM_NT; ++nt) wr[p][nt] = __builtin_nontemporal_load(wp + nt * 64);
         wp += GEMM_NT * 64;
@@ -253,10 +321,11 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
     store_x(chunk0, 0, xr);
     __syncthreads();
 
-    // One chunk of KCL k-steps.  MORE (another chunk follows) is a compile-time flag so that the
+    // One chunk of KCS k-steps.  MORE (another chunk follows) is a compile-time flag so that the
     // body is straight-line code: the weight ring is refilled PF steps ahead, across the chunk
     // boundary when MORE, and the next chunk's activations are requested before any of it.
     int buf = 0;
+    const int lane_sw = (lane & 48) + ((lane & 15) ^ xs_swizzle(lane >> 4));   // this lane's A fragment inside a block
     auto chunk_body = [&](auto more_tag, int chunk) {
         constexpr bool MORE = decltype(more_tag)::value;
         if constexpr (MORE) load_x(chunk + 1, xr);
@@ -264,17 +333,17 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
         // A fragments of k-step i + 1 are requested from LDS before the MFMAs of k-step i are issued
         u32x4 a[2][MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) a[0][mt] = xs[buf][mt * 64 + lane];
+        for (int mt = 0; mt < MT; ++mt) a[0][mt] = xs[buf][mt * 64 + lane_sw];
 #pragma unroll
-        for (int i = 0; i < KCL; ++i) {
-            if (i + 1 < KCL) {
+        for (int i = 0; i < KCS; ++i) {
+            if (i + 1 < KCS) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) a[(i + 1) & 1][mt] = xs[buf][((i + 1) * MT + mt) * 64 + lane];
+                for (int mt = 0; mt < MT; ++mt) a[(i + 1) & 1][mt] = xs[buf][((i + 1) * MT + mt) * 64 + lane_sw];
             }
             u32x4 w[GEMM_NT];
 #pragma unroll
             for (int nt = 0; nt < GEMM_NT; ++nt) w[nt] = wr[i % PF][nt];
-            if (MORE || i + PF < KCL) {
+            if (MORE || i + PF < KCS) {
 #pragma unroll
                 for (int nt = 0; nt < GEMM_NT; ++nt) wr[i % PF][nt] = __builtin_nontemporal_load(wp + nt * 64);
                 wp += GEMM_NT * 64;
@@ -301,7 +370,6 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
         // staging memory, free after a barrier) so that a row leaves as one contiguous piece in 16-byte stores
         // instead of 16-column fragments written two bytes per lane.
         constexpr int TW = WPB * 16, TWP = TW + 8;       // padded row: the four row groups of a wave hit different banks
-        constexpr int EPV = 16 / (int)sizeof(T);         // elements per 16-byte store
         static_assert((size_t)MT * 16 * TWP * sizeof(T) <= sizeof(xs), "the tile fits the staging memory");
         T *tile = reinterpret_cast<T *>(&xs[0][0]);
         __syncthreads();                                 // every wave has read its last operand fragments
@@ -313,13 +381,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
                 tile[(mt * 16 + 4 * (lane >> 4) + r) * TWP + wave * 16 + (lane & 15)] = from_f<T>(g / (1.0f + expf(-g)) * up);
             }
         __syncthreads();
-        const int f0 = blockIdx.x * TW;
-        constexpr int PPR = TW / EPV;                    // 16-byte pieces per row
-        for (int p = tid; p < MT * 16 * PPR; p += WPB * 64) {
-            const int m = p / PPR, f = f0 + (p % PPR) * EPV;
-            if (m < M && f + EPV <= F)                   // F is a multiple of 8: a piece is inside or outside as a whole
-                *reinterpret_cast<u32x4 *>(act + (size_t)m * F + f) = *reinterpret_cast<const u32x4 *>(tile + m * TWP + (p % PPR) * EPV);
-        }
+        silu_tile_store<T, MT * 16, TW, WPB * 64>(tile, act, M, F, blockIdx.x * TW, tid);
         return;
     }
     if constexpr (HEAD) {
@@ -345,53 +407,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
                 for (int r = 0; r < 4; ++r)
                     tile[(mt * 16 + 4 * (lane >> 4) + r) * TW + wave * (GEMM_NT * 16) + nt * 16 + (lane & 15)] = acc[mt][nt][r];
         __syncthreads();
-        // one half wave per row (its two halves take different rows; shuffles stay inside a half)
-        constexpr int NVH = TW / 32;
-        const int hw = tid >> 5, hl = tid & 31, seg = blockIdx.x, n_seg = gridDim.x, col0 = seg * TW;
-        for (int row = hw; row < M; row += WPB * 2) {
-            float v[NVH]; int id[NVH];
-            float bv = -INFINITY; int bi = 0x7fffffff;
-#pragma unroll
-            for (int j = 0; j < NVH; ++j) {
-                const int c = hl + 32 * j, n = col0 + c;
-                const bool ok = n < he.vocab;
-                v[j] = ok ? tile[row * TW + c] : -INFINITY;
-                id[j] = ok ? n : 0x7fffffff - j;         // dummies stay below every real entry
-                if (better(v[j], id[j], bv, bi)) { bv = v[j]; bi = id[j]; }
-            }
-            if (he.mode == HEAD_ARGMAX) {
-                half_argmax(bv, bi);
-                if (hl == 0) { he.pv[(size_t)row * n_seg + seg] = bv; he.pi[(size_t)row * n_seg + seg] = bi; }
-                continue;
-            }
-            // maximum, sum of exp(l - max) in a fixed order, then the k best by k rounds of (argmax, remove)
-            float mx = bv;
-#pragma unroll
-            for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 32));
-            float se = 0.f;
-#pragma unroll
-            for (int j = 0; j < NVH; ++j) se += v[j] > -INFINITY ? expf(v[j] - mx) : 0.f;
-#pragma unroll
-            for (int o = 16; o > 0; o >>= 1) se += __shfl_xor(se, o, 32);
-            float *rec = he.seg_out + ((size_t)row * n_seg + seg) * TOPK_REC;
-            if (hl == 0) { rec[0] = mx; rec[1] = se; }
-            float my_v = -INFINITY; int my_i = 0x7fffffff;
-            for (int r = 0; r < he.k; ++r) {
-                float wv = -INFINITY; int wi = 0x7fffffff;
-#pragma unroll
-                for (int j = 0; j < NVH; ++j)
-                    if (better(v[j], id[j], wv, wi)) { wv = v[j]; wi = id[j]; }
-                half_argmax(wv, wi);
-                if (hl == r) { my_v = wv; my_i = wi; }
-#pragma unroll
-                for (int j = 0; j < NVH; ++j)
-                    if (id[j] == wi) v[j] = -INFINITY;   // real indices are unique: removes exactly the winner
-            }
-            if (hl < he.k) {
-                rec[2 + hl] = my_v;
-                reinterpret_cast<int *>(rec)[2 + TOPK_MAXK + hl] = my_v > -INFINITY ? my_i : 0x7fffffff;
-            }
-        }
+        head_tile_reduce<TW, WPB * 2>(tile, M, he, blockIdx.x, gridDim.x, tid);
         return;
     }
     float *out = part + (size_t)blockIdx.y * (MT * 16) * Npad;
@@ -405,6 +421,186 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
                 const int m = mt * 16 + 4 * (lane >> 4) + r;
                 out[(size_t)m * Npad + n0 + nt * 16] = acc[mt][nt][r];
             }
+}
+
+// ------------------------------------------------------------------------------------------
+// The same product for 129..256 rows (several sequences verified in one weight stream, prefill): at that height the
+// kernel is bound by the matrix pipe, not by the weight stream, and one wave per SIMD cannot keep that pipe busy (a
+// single wave reaches about 60 % of the MFMA rate).  Eight waves per workgroup, two per SIMD: wave (wm, wn) owns the
+// rows [128 wm, 128 wm + 128) of the 32 columns wn of the workgroup's 128-column tile; the two waves of a column group
+// read the same weights (the second read is served by the caches), the activations are staged as above in chunks of four
+// k-steps (two chunks of 256 rows fill the LDS).  The chunk's A fragments pass through a window of AW registers, each
+// refilled as soon as its two MFMAs are issued, AW fragments ahead of its use; that order is given to the scheduler
+// as it stands (left alone it moves every LDS read next to its use and waits for it there).
+// Splits own whole groups of 8 k-steps as in the stream kernel and a wave adds its k-steps in ascending order, so a
+// row's sums are bit for bit those of the stream kernel.
+constexpr int TALL_MT = 16, TALL_KCL = 4, TALL_PF = 4, TALL_AW = 8;
+
+template <typename T, bool FUSE_SILU, bool HEAD>
+__global__ __launch_bounds__(512) void gemm_tall_kernel(
+    const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
+    int M, int K, int Npad, int ksteps_total, T *__restrict__ act, int F, HeadEpi he) {
+    constexpr int MT = TALL_MT, KCL = TALL_KCL, PF = TALL_PF, AW = TALL_AW, MTW = MT / 2;
+    static_assert(KCL % PF == 0 && KCS % KCL == 0, "ring index must be static");
+    constexpr int XUNITS = KCL * MT * 64, XPT = XUNITS / 512, RJ = MT / 8;
+    __shared__ u32x4 xs[2][XUNITS];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, wn = wave & 3, wm = wave >> 2;
+    const int n_chunks_total = ksteps_total / KCS;
+    const int chunk0 = ((int)blockIdx.y * n_chunks_total / (int)gridDim.y) * (KCS / KCL);          // in staged chunks
+    const int chunk1 = (((int)blockIdx.y + 1) * n_chunks_total / (int)gridDim.y) * (KCS / KCL);
+    const int ngroup = blockIdx.x * 4 + wn;
+    const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCL) * (GEMM_NT * 64) + lane;
+
+    // Staging: wave w takes the row tiles w and w + 8 of every k-step, so that a thread's units are one lane-dependent
+    // base plus compile-time steps; unit layout and swizzle as in the stream kernel.  Loads are never predicated:
+    // out-of-range units read a clamped, valid address and are zeroed by a mask (given a condition the compiler moves
+    // the load itself behind a branch).
+    const T *x_row[RJ];
+    uint32_t x_rmask[RJ];
+    const int x_kl = (lane & 3) * 8;
+    const int x_dst0 = wave * 64 + ((lane & 3) << 4) + ((lane >> 2) ^ xs_swizzle(lane & 3));
+#pragma unroll
+    for (int j = 0; j < RJ; ++j) {
+        const int m = (j * 8 + wave) * 16 + (lane >> 2);
+        x_rmask[j] = 0u - (uint32_t)(m < M);
+        x_row[j] = X + (size_t)(m < M ? m : M - 1) * ldx + x_kl;
+    }
+    auto load_x = [&](int chunk, u32x4 (&xr)[XPT]) {
+#pragma unroll
+        for (int ks = 0; ks < KCL; ++ks) {
+            const int k = (chunk * KCL + ks) * GEMM_KSTEP;
+            const int koff = k + x_kl < K ? k : K - 8 - x_kl;
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) xr[ks * RJ + j] = *reinterpret_cast<const u32x4 *>(x_row[j] + koff);
+        }
+    };
+    auto store_x = [&](int chunk, int b, const u32x4 (&xr)[XPT]) {
+#pragma unroll
+        for (int ks = 0; ks < KCL; ++ks) {
+            const uint32_t kmask = 0u - (uint32_t)((chunk * KCL + ks) * GEMM_KSTEP + x_kl < K);
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) {
+                const uint32_t mk = kmask & x_rmask[j];
+                const u32x4 v = xr[ks * RJ + j];
+                xs[b][x_dst0 + (ks * MT + 8 * j) * 64] = u32x4{v[0] & mk, v[1] & mk, v[2] & mk, v[3] & mk};
+            }
+        }
+    };
+
+    f32x4 acc[MTW][GEMM_NT];
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 xr[XPT];
+    load_x(chunk0, xr);
+    u32x4 wr[PF][GEMM_NT];
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+#pragma unroll
+        for (int nt = 0; nt < GEMM_NT; ++nt) wr[p][nt] = wp[nt * 64];
+        wp += GEMM_NT * 64;
+    }
+    store_x(chunk0, 0, xr);
+    __syncthreads();
+
+    int buf = 0;
+    const int lane_sw = wm * (MTW * 64) + (lane & 48) + ((lane & 15) ^ xs_swizzle(lane >> 4));   // first fragment of this wave's rows
+    auto chunk_body = [&](auto more_tag, int chunk) {
+        constexpr bool MORE = decltype(more_tag)::value;
+        constexpr int NF = KCL * MTW;                     // fragments of the chunk for this wave: (k-step i, row tile mt)
+        if constexpr (MORE) load_x(chunk + 1, xr);
+        __builtin_amdgcn_sched_barrier(0);               // keep these loads older than the weight loads below
+        u32x4 a[AW], w[GEMM_NT];
+#pragma unroll
+        for (int f = 0; f < AW; ++f) a[f] = xs[buf][((f / MTW) * MT + f % MTW) * 64 + lane_sw];
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            const int i = f / MTW, mt = f % MTW;
+            if (mt == 0) {
+#pragma unroll
+                for (int nt = 0; nt < GEMM_NT; ++nt) w[nt] = wr[i % PF][nt];
+                if (MORE || i + PF < KCL) {
+#pragma unroll
+                    for (int nt = 0; nt < GEMM_NT; ++nt) wr[i % PF][nt] = wp[nt * 64];
+                    wp += GEMM_NT * 64;
+                }
+            }
+#pragma unroll
+            for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[f % AW], w[nt], acc[mt][nt]);
+            if (f + AW < NF) a[f % AW] = xs[buf][(((f + AW) / MTW) * MT + (f + AW) % MTW) * 64 + lane_sw];
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, AW, 0);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            const int i = f / MTW, mt = f % MTW;
+            if (mt == 0 && (MORE || i + PF < KCL)) __builtin_amdgcn_sched_group_barrier(0x020, GEMM_NT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, GEMM_NT, 0);
+            if (f + AW < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (MORE) {
+            store_x(chunk + 1, buf ^ 1, xr);
+            __syncthreads();
+            buf ^= 1;
+        }
+    };
+    for (int chunk = chunk0; chunk + 1 < chunk1; ++chunk) chunk_body(std::true_type{}, chunk);
+    chunk_body(std::false_type{}, chunk1 - 1);
+
+    // D tile: lane -> column n = lane % 16, register r -> row m = 4 * (lane / 16) + r of row tile wm * MTW + mt
+    const int row0 = wm * (MTW * 16) + 4 * (lane >> 4);
+    if constexpr (FUSE_SILU) {
+        constexpr int TW = 4 * 16, TWP = TW + 8;
+        static_assert((size_t)MT * 16 * TWP * sizeof(T) <= sizeof(xs), "the tile fits the staging memory");
+        T *tile = reinterpret_cast<T *>(&xs[0][0]);
+        __syncthreads();                                 // every wave has read its last operand fragments
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float g = acc[mt][0][r], up = acc[mt][1][r];
+                tile[(row0 + mt * 16 + r) * TWP + wn * 16 + (lane & 15)] = from_f<T>(g / (1.0f + expf(-g)) * up);
+            }
+        __syncthreads();
+        silu_tile_store<T, MT * 16, TW, 512>(tile, act, M, F, blockIdx.x * TW, tid);
+        return;
+    }
+    if constexpr (HEAD) {
+        constexpr int TW = 4 * GEMM_NT * 16;
+        static_assert((size_t)MT * 16 * TW * sizeof(float) <= sizeof(xs), "the tile fits the staging memory");
+        if (he.write_logits) {
+            const int nl = ngroup * (GEMM_NT * 16) + (lane & 15);
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < GEMM_NT; ++nt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        part[(size_t)(row0 + mt * 16 + r) * Npad + nl + nt * 16] = acc[mt][nt][r];
+        }
+        float *tile = reinterpret_cast<float *>(&xs[0][0]);
+        __syncthreads();
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < GEMM_NT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    tile[(row0 + mt * 16 + r) * TW + wn * (GEMM_NT * 16) + nt * 16 + (lane & 15)] = acc[mt][nt][r];
+        __syncthreads();
+        head_tile_reduce<TW, 16>(tile, M, he, blockIdx.x, gridDim.x, tid);
+        return;
+    }
+    float *out = part + (size_t)blockIdx.y * (MT * 16) * Npad;
+    const int n0 = ngroup * (GEMM_NT * 16) + (lane & 15);
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < GEMM_NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out[(size_t)(row0 + mt * 16 + r) * Npad + n0 + nt * 16] = acc[mt][nt][r];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -630,7 +826,7 @@ __global__ __launch_bounds__(256) void epilogue_rope_ranges_kernel(const float *
 // Row count of a partial plane as the kernel instantiation writes it.
 static int gemm_rows_written(int mpad) {
     const int mt = mpad / 16;
-    return (mt <= 2 ? mt : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : mt <= 12 ? 12 : 16) * 16;
+    return (mt <= 2 ? mt : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : 16) * 16;
 }
 
 GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
@@ -640,7 +836,7 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
     g.Kpad = gemm_kpad(dt, K);
     g.Mpad = round_up(M < 1 ? 1 : M, 16);
     if (dt == DT_F32) { g.S = 1; return g; }
-    g.Mpad = gemm_rows_written(g.Mpad);       // the kernel is instantiated for 1, 2, 4, 6, 8, 12 or 16 row tiles
+    g.Mpad = gemm_rows_written(g.Mpad);       // the kernels are instantiated for 1, 2, 4, 6, 8 or (tall kernel) 16 row tiles
     const int n_blocks = g.Npad / GEMM_BLOCK_N;
     const int n_chunks = g.Kpad / GEMM_KCHUNK;
     // One workgroup per CU (256) at most, as many as fit, chunks dealt out evenly: in every sweep more
@@ -736,9 +932,42 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
         launch_qkv_rope_t<T>(g, Wp, X, ldx, epi, *rr, st, ev_start, ev_stop);
         return;
     }
-    // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
     const bool fuse_silu = epi.mode == EPI_SILU && g.S == 1;
     const bool head = epi.mode == EPI_HEAD;
+    if (g.Mpad > 128) {                                  // the tall kernel: eight waves, one 128-column tile
+        HeadEpi he{};
+        if (head) he = HeadEpi{epi.head_mode, epi.head_k, g.N, epi.write_logits, epi.seg_out, epi.pv, epi.pi};
+        dim3 grid(g.Npad / GEMM_BLOCK_N, g.S), block(512);
+        const int ksteps = g.Kpad / GEMM_KSTEP;
+        const u32x4 *w = static_cast<const u32x4 *>(Wp);
+        const T *x = static_cast<const T *>(X);
+        T *act = static_cast<T *>(epi.act);
+#define POSS_TALL_LAUNCH(FUSE, HD, FARG)                                                                      \
+    do {                                                                                                      \
+        if (ev_start && ev_stop)                                                                              \
+            hipExtLaunchKernelGGL((gemm_tall_kernel<T, FUSE, HD>), grid, block, 0, st, ev_start, ev_stop, 0, w, x, ldx, part, \
+                                  g.M, g.K, g.Npad, ksteps, act, FARG, he);                                   \
+        else                                                                                                  \
+            hipLaunchKernelGGL((gemm_tall_kernel<T, FUSE, HD>), grid, block, 0, st, w, x, ldx, part, g.M, g.K, g.Npad, \
+                               ksteps, act, FARG, he);                                                        \
+    } while (0)
+        if (fuse_silu) POSS_TALL_LAUNCH(true, false, epi.F);
+        else if (head) POSS_TALL_LAUNCH(false, true, 0);
+        else POSS_TALL_LAUNCH(false, false, 0);
+#undef POSS_TALL_LAUNCH
+        if (epi.mode == EPI_ROPE_KV) {
+            EpiArgs pe = epi;
+            pe.rope_packed = 1;
+            const size_t plane = (size_t)g.Mpad * g.Npad;
+            const int blocks = rr->blk0[rr->n - 1] + (rr->r1[rr->n - 1] - rr->r0[rr->n - 1] + EPI_ROWS_PAIR - 1) / EPI_ROWS_PAIR;
+            hipLaunchKernelGGL((epilogue_rope_ranges_kernel<T>), dim3(g.Npad / GEMM_BLOCK_N, blocks), dim3(256), 0, st, part, plane, g.S,
+                               g.Npad, g.N, *rr, pe);
+            return;
+        }
+        launch_epilogue_t<T>(g, part, epi, eps, fuse_silu, st);
+        return;
+    }
+    // Two tiles per workgroup when the column count alone gives every CU work and K is not split.
     const bool wide = !fuse_silu && gemm_wide(g);
     const int wpb = wide ? 8 : 4;
     HeadEpi he{};
@@ -769,23 +998,13 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
         else if (deep) POSS_GEMM_LAUNCH(MT, 4, false, 8, false, 0);                                           \
         else POSS_GEMM_LAUNCH(MT, 4, false, 4, false, 0);                                                     \
     } while (0)
-    // above 128 rows: four waves, four k-steps in flight (the staged chunk is four k-steps long)
-#define POSS_GEMM_CASE_TALL(MT)                                                                               \
-    do {                                                                                                      \
-        if (fuse_silu) POSS_GEMM_LAUNCH(MT, 4, true, 4, false, epi.F);                                        \
-        else if (head) POSS_GEMM_LAUNCH(MT, 4, false, 4, true, 0);                                            \
-        else POSS_GEMM_LAUNCH(MT, 4, false, 4, false, 0);                                                     \
-    } while (0)
     switch (g.Mpad / 16) {
         case 1: POSS_GEMM_CASE(1); break;
         case 2: POSS_GEMM_CASE(2); break;
         case 4: POSS_GEMM_CASE(4); break;
         case 6: POSS_GEMM_CASE(6); break;
-        case 8: POSS_GEMM_CASE(8); break;
-        case 12: POSS_GEMM_CASE_TALL(12); break;
-        default: POSS_GEMM_CASE_TALL(16); break;
+        default: POSS_GEMM_CASE(8); break;
     }
-#undef POSS_GEMM_CASE_TALL
 #undef POSS_GEMM_CASE
 #undef POSS_GEMM_LAUNCH
     if (epi.mode == EPI_ROPE_KV) {                       // rotary + cache writes per row range, one launch
