@@ -129,20 +129,24 @@ def cpu_baseline(cfg, n_layers_sample=16):
                 ms_per_round=round_s * 1e3)
 
 
-def quick_measure(name, steps=10, warmup=3, vanilla_steps=10):
+def quick_measure(name, steps=10, warmup=3, vanilla_steps=10, batch=1):
     """Round latency, achieved fraction of the HBM peak and the plain-decoding step of another workload of
-    the benchmark spec (same library, same timing rules as the headline: inputs resident, synchronised on both sides)."""
+    the benchmark spec (same library, same timing rules as the headline: inputs resident, synchronised on both sides).
+    batch > 1: that many sequences per round (other prompts of the same length), tokens/s over all of them; the
+    bytes of the fraction are one round's weights, streamed once for all sequences."""
     import torch
     import paper_2506_03566_amd as P
     from synth import get_config, make_prompt
     from synth.gpu import make_weights_on_device
     cfg = get_config(name)
     weights = make_weights_on_device(cfg)
-    ctx = P.Poss(cfg, weights)
+    ctx = P.Poss(cfg, weights, batch=batch)
     del weights
     torch.cuda.empty_cache()
     prompt = make_prompt(cfg)
     ctx.prefill(prompt)
+    for b in range(1, batch):
+        ctx.prefill(make_prompt(cfg.with_(prompt_seed=cfg.prompt_seed + 17 * b)), seq=b)
 
     def one_round():
         ctx.draft_tree(want_tree=False)
@@ -161,12 +165,16 @@ def quick_measure(name, steps=10, warmup=3, vanilla_steps=10):
     ms_round = (time.perf_counter() - t0) * 1e3 / steps
     s1 = ctx.stats()
     committed = s1.committed_tokens - s0.committed_tokens
-    gbps = round_bytes(cfg, t_begin + committed // 2, 1) / (ms_round * 1e-3) / 1e9
+    t_mid = t_begin + committed // (2 * batch)
+    bytes_round = round_bytes(cfg, t_mid, 1) + (batch - 1) * (round_bytes(cfg, t_mid, 1) - round_bytes(cfg, 0, 1))   # weights once, KV per sequence
+    gbps = bytes_round / (ms_round * 1e-3) / 1e9
     out = dict(ms_per_round=round(ms_round, 4), hbm_frac=round(gbps / HBM_PEAK_GBPS, 4),
                draft_ms=round((s1.ms_draft - s0.ms_draft) / steps, 4), verify_ms=round((s1.ms_verify - s0.ms_verify) / steps, 4),
                tokens_per_s=round(committed / (ms_round * 1e-3 * steps), 2), steps=steps, n_prompt=cfg.n_prompt,
                depth=cfg.depth, total_tokens=cfg.total_tokens, dtype={0: "f32", 1: "bf16", 2: "f16"}[cfg.dtype])
-    if vanilla_steps > 0:
+    if batch > 1:
+        out["batch"] = batch
+    if vanilla_steps > 0 and batch == 1:
         ctx.reset()
         ctx.prefill(prompt)
         root = P.TreeArrays.from_lists([0], [-1])
@@ -364,6 +372,8 @@ def main():
     if (not args.no_other_configs and args.config == "c1_llama3_8b_3x2" and not over and B == 1 and args.temperature == 0
             and not args.gemm_wgs and not args.attn_split):
         out["other_configs"] = {n: quick_measure(n) for n in ("c2_llama3_8b_6x1", "c3_llama2_13b_3x2", "c4_llama3_8b_long")}
+        # four sequences per round at the headline shape: 4 x 61 rows verified in one weight stream
+        out["other_configs"]["c1_llama3_8b_3x2_batch4"] = quick_measure("c1_llama3_8b_3x2", batch=4)
     if args.pmc_calibration:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)

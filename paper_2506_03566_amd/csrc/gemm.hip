@@ -340,18 +340,18 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) a[(i + 1) & 1][mt] = xs[buf][((i + 1) * MT + mt) * 64 + lane_sw];
             }
-            u32x4 w[GEMM_NT];
+            // The MFMAs read the ring slot itself and the slot is refilled after them: with a copy taken first (so that
+            // the refill could be issued ahead of the MFMAs) the compiler gathers the copies of all slots at the top of
+            // the chunk and waits there for the whole ring, which empties the memory pipeline once per chunk.
 #pragma unroll
-            for (int nt = 0; nt < GEMM_NT; ++nt) w[nt] = wr[i % PF][nt];
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[i & 1][mt], wr[i % PF][nt], acc[mt][nt]);
             if (MORE || i + PF < KCS) {
 #pragma unroll
                 for (int nt = 0; nt < GEMM_NT; ++nt) wr[i % PF][nt] = __builtin_nontemporal_load(wp + nt * 64);
                 wp += GEMM_NT * 64;
             }
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[i & 1][mt], w[nt], acc[mt][nt]);
             __builtin_amdgcn_sched_barrier(0);       // one k-step at a time: loads stay in ring order
         }
         if constexpr (MORE) {
