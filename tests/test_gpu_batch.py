@@ -172,6 +172,7 @@ def test_full_size_batch_equals_each_sequence_alone(lengths):
 
 
 @pytest.mark.parametrize("name,batch,lengths", [("c0_tiny_f32", 3, (16, 23, 40)), ("t_mid_bf16", 2, (150, 97)),
+                                                ("t_mid_bf16", 4, (150, 97, 120, 33)),       # 244 rows: the tall kernel writes the logits
                                                 ("c0_tiny_f32", 6, (16, 23, 40, 12, 31, 18))])               # groups of 4 and 2
 def test_batched_sampling_equals_sequences_alone(name, batch, lengths):
     """Verification at a temperature with a set of uniform numbers per sequence: every sequence of the
@@ -221,6 +222,7 @@ def test_batched_sampling_equals_sequences_alone(name, batch, lengths):
 
 
 @pytest.mark.parametrize("name,batch,lengths", [("c0_tiny_f32", 3, (16, 23, 40)), ("t_mid_bf16", 2, (150, 97)),
+                                                ("t_mid_bf16", 4, (150, 97, 120, 33)),       # 244 rows: the tall kernel writes the logits
                                                 ("c0_tiny_f32", 8, (16, 23, 40, 12, 31, 18, 27, 21))])      # two groups
 def test_batched_caller_trees_equal_sequences_alone(name, batch, lengths):
     """Trees handed in by the caller, one per sequence and of different sizes (root-only rounds are
@@ -360,4 +362,38 @@ def test_a_sequence_set_aside_in_a_batch_that_runs_in_groups():
     for b in range(batch):
         assert ctx.tokens(b) == alone[b][2], f"sequence {b}"
     assert ctx.stats().rounds == 6 * 2 + 5 * 3
+    pair.close()
+
+
+def test_the_rows_a_launch_carries_do_not_change_any_sequence():
+    """Four sequences of a 16-bit shape with launches of at most 256 rows (one verification pass of 244 rows,
+    the tall kernel) and of at most 128 rows (two groups of two, the stream kernel): the same trees, paths and
+    tokens, which are those of every sequence alone."""
+    name, batch, lengths, n_rounds = "t_mid_f16", 4, (131, 64, 150, 97), 3
+    cfg = get_config(name)
+    pair = Pair(name, lib_over={"batch": batch})
+    prompts = _prompts(cfg, lengths)
+    alone = [_rounds_alone(pair, p, n_rounds) for p in prompts]
+    with pytest.raises(P.PossError):
+        pair.ctx.set_launch_rows(64)
+    with pytest.raises(P.PossError):
+        pair.ctx.set_launch_rows(257)
+    for rows in (256, 128):
+        ctx = pair.ctx if rows == 256 else P.Poss(cfg, pair.dev_weights, batch=batch)
+        ctx.set_launch_rows(rows)
+        firsts = [ctx.prefill(p, seq=b) for b, p in enumerate(prompts)]
+        assert firsts == [a[0] for a in alone]
+        for rnd in range(n_rounds):
+            ctx.draft_tree(want_tree=False)
+            trees = [ctx.get_tree(b).as_dict() for b in range(batch)]
+            ctx.verify_tree(want_argmax=False)
+            ctx.accept_and_commit()
+            for b in range(batch):
+                atr, apath, am, atoks = alone[b][1][rnd]
+                assert _same_tree(trees[b], atr), f"launch rows {rows}, round {rnd}, sequence {b}: tree differs"
+                assert ctx.commit_result(b) == (apath, am, atoks), f"launch rows {rows}, round {rnd}, sequence {b}"
+        for b in range(batch):
+            assert ctx.tokens(b) == alone[b][2]
+        if rows != 256:
+            ctx.close()
     pair.close()
