@@ -31,14 +31,7 @@ if have_gpu():
 
 
 def _say(msg):
-    """Progress line: to stdout, and (long oracle passes run silently under pytest's capture) appended to a
-    log under gpurun_out/ when that folder exists."""
     print(msg, flush=True)
-    import os
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
-        with open(os.path.join(d, "test_progress.log"), "a") as f:
-            f.write(msg + "\n")
 
 
 def test_committed_stream_teacher_forced_through_the_oracle():
