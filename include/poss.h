@@ -77,7 +77,7 @@ typedef struct poss_config {
     int32_t kv_page_tokens;                  /* tokens per KV page: 32, 64 or 128           */
     int32_t kv_page_order;                   /* 0: pages in order; 1: physical pages reversed (layout tests) */
     int32_t batch;                           /* sequences per round: 0 or 1 = one; up to 8.  A pass stacks the rows of as *
-                                              * many sequences as fit 128 rows and runs group by group beyond that       */
+                                              * many sequences as fit POSS_LAUNCH_ROWS and runs group by group beyond it */
 } poss_config;
 
 /* Weights: DEVICE pointers to row-major [out, in] tensors of `dtype`.
@@ -260,7 +260,8 @@ int poss_debug_read_kv(poss_ctx *ctx, int32_t which, int32_t layer, int32_t slot
                        float *k_out, float *v_out);
 
 /* Y[M, N] (DEVICE float32) = X[M, K] . W[N, K]^T through the library's GEMM path; X and W DEVICE
- * row-major of `dtype`; scratch DEVICE of at least poss_debug_gemm_scratch_bytes bytes. */
+ * row-major of `dtype`, M <= POSS_LAUNCH_ROWS (up to 128 rows the stream kernel, above it the tall kernel);
+ * scratch DEVICE of at least poss_debug_gemm_scratch_bytes bytes (0 for a shape that is refused). */
 size_t poss_debug_gemm_scratch_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K);
 int poss_debug_gemm(int32_t dtype, const void *x, const void *w, void *y, int32_t M, int32_t N,
                     int32_t K, int32_t target_workgroups, void *scratch, void *hip_stream,
