@@ -441,6 +441,38 @@ __device__ __forceinline__ void attn_merge_body(const int m, const float *__rest
     const int kvh = qh / G, rho = m * G + qh % G;
     const size_t stride = (size_t)hkv * rho_pad;          // rows between consecutive splits
     const size_t row0 = (size_t)kvh * rho_pad + rho;
+    // Up to 12 splits (the usual case): everything in registers and every load requested before the first use - one
+    // trip to memory, no barrier.  Each thread forms the weights itself (the (max, sum) pairs are the same addresses
+    // for the whole workgroup); sums run in split order, as in the general path.  Slots beyond n_splits re-read the
+    // last split and are not used.
+    auto in_registers = [&](auto nr_tag) {
+        constexpr int NR = decltype(nr_tag)::value;
+        const int i = (int)threadIdx.x < dh ? (int)threadIdx.x : dh - 1;
+        const float *src = o_part + row0 * dh + i;
+        float ms[NR], ls[NR], v[NR];
+#pragma unroll
+        for (int s0 = 0; s0 < NR; ++s0) {
+            const int sc = s0 < n_splits ? s0 : n_splits - 1;
+            const float2 ml = *reinterpret_cast<const float2 *>(ml_part + (row0 + sc * stride) * 2);
+            ms[s0] = ml.x; ls[s0] = ml.y;
+            v[s0] = src[(size_t)sc * stride * dh];
+        }
+        float M = -INFINITY;
+#pragma unroll
+        for (int s0 = 0; s0 < NR; ++s0) if (s0 < n_splits) M = fmaxf(M, ms[s0]);
+        float den = 0.f, num = 0.f;
+#pragma unroll
+        for (int s0 = 0; s0 < NR; ++s0)
+            if (s0 < n_splits) {
+                const float w = ms[s0] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms[s0] - M);   // maxima are in the log2 domain
+                den += w * ls[s0];
+                num += w * v[s0];                         // a split without visible keys has weight 0 and O = 0
+            }
+        if ((int)threadIdx.x < dh) out[((size_t)m * hq + qh) * dh + i] = from_f<T>(num / den);
+    };
+    if (n_splits <= 4) { in_registers(std::integral_constant<int, 4>{}); return; }     // (workgroup-uniform)
+    if (n_splits <= 8) { in_registers(std::integral_constant<int, 8>{}); return; }
+    if (n_splits <= 12) { in_registers(std::integral_constant<int, 12>{}); return; }
     for (int s0 = threadIdx.x; s0 < n_splits; s0 += blockDim.x) w_lds[s0] = ml_part[(row0 + s0 * stride) * 2];
     __syncthreads();
     float M = -INFINITY;
