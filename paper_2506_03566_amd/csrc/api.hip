@@ -125,7 +125,6 @@ int fail(poss_ctx *c, int code, const char *fmt, ...) {
         if (e_ != hipSuccess) return fail(c, POSS_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
     } while (0)
 
-bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 const char *check_config(const poss_config &c) {
     if (c.n_layers < 1 || c.d_model < 8 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.d_ffn < 8 || c.vocab < 2)
