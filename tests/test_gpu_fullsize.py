@@ -151,3 +151,39 @@ def test_sampler_at_full_vocabulary():
         ctx.draft_tree(want_tree=True)
     _say(f"  {same}/{2 * len(rows)} draws identical to the float64 inverse CDF")
     ctx.close()
+
+
+def test_drawn_children_at_full_vocabulary():
+    """Drawn children and the rejection walk over the 128256-entry vocabulary of the benchmark shape (501 blocks of
+    256 ids per draw): what must hold whatever the numbers - distinct children under every node, non-positive score
+    steps, a committed path that is a root path of the tree, a last token that is not a kept child of the last node
+    unless that node's children were all rejected, a consistent token stream."""
+    cfg = get_config("c1_llama3_8b_3x2", n_prompt=64)
+    dev = make_weights_on_device(cfg)
+    ctx = P.Poss(cfg, dev)
+    del dev
+    torch.cuda.empty_cache()
+    ctx.prefill(make_prompt(cfg))
+    ctx.set_sampling(1.0, np.zeros(cfg.depth + 1, np.float32))
+    n_before, total, accepted = len(ctx.tokens()), 0, 0
+    for rnd in range(8):
+        rng = np.random.default_rng(500 + rnd)
+        ctx.set_draft_sampling(rng.random((cfg.depth, cfg.top_k, cfg.top_k)).astype(np.float32),
+                               rng.random((cfg.depth + 1, cfg.top_k + 1)).astype(np.float32))
+        d = ctx.draft_tree().as_dict()
+        assert d["n"] == cfg.total_tokens + 1 and validate_tree(d["token"], d["parent"])
+        kids = {}
+        for i in range(1, d["n"]):
+            kids.setdefault(d["parent"][i], []).append(d["token"][i])
+            assert 0 <= d["token"][i] < cfg.vocab
+            assert d["score"][i] <= d["score"][d["parent"][i]] + 1e-6
+        assert all(len(set(v)) == len(v) for v in kids.values())
+        ctx.verify_tree()
+        path, m, toks = ctx.accept_and_commit()
+        assert path[0] == 0 and all(d["parent"][b] == a for a, b in zip(path, path[1:]))
+        assert toks[:-1] == [d["token"][p] for p in path[1:]] and 0 <= toks[-1] < cfg.vocab
+        total += len(toks)
+        accepted += m
+    _say(f"  8 rounds with drawn children: {accepted} drafted tokens accepted, {total} committed")
+    assert len(ctx.tokens()) == n_before + total
+    ctx.close()
