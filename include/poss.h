@@ -254,6 +254,11 @@ int poss_debug_build_tree(poss_ctx *ctx, const int32_t *ids, const float *logp, 
  * [n_layers + 1][rows][d_model] (entry l = input of layer l; last = features). */
 int poss_debug_set_taps(poss_ctx *ctx, void *taps_dev_or_null);
 
+/* With drawn children (poss_set_draft_sampling), after poss_draft_tree: the drafter's logits of the expanded nodes
+ * row0 .. row0+n-1 (row 0: the root; row 1 + (d-1) * top_k + r: the frontier node of rank r at depth d) into out,
+ * DEVICE float32 [n][vocab]: the distributions the children were drawn from.  Waits for the stream. */
+int poss_debug_draft_logits(poss_ctx *ctx, int32_t row0, int32_t n, float *out);
+
 /* Read keys/values of logical slots [slot0, slot0+n) of one cache into HOST float32 arrays
  * [n][n_kv_heads][head_dim].  which = -1: target layer `layer`; which = s >= 0: specialist s. */
 int poss_debug_read_kv(poss_ctx *ctx, int32_t which, int32_t layer, int32_t slot0, int32_t n,

@@ -18,7 +18,7 @@ EXPORTS = ["poss_workspace_bytes", "poss_load", "poss_reset", "poss_prefill", "p
            "poss_verify_tree", "poss_accept_and_commit", "poss_get_stats", "poss_get_tokens",
            "poss_prefill_seq", "poss_get_tree_seq", "poss_get_commit_seq", "poss_get_tokens_seq", "poss_set_uniforms_seq", "poss_reset_seq", "poss_set_active",
            "poss_last_error", "poss_free", "poss_profile_gemm", "poss_gemm_profile", "poss_set_tuning", "poss_set_launch_rows", "poss_set_sampling", "poss_set_draft_sampling",
-           "poss_debug_build_tree", "poss_debug_set_taps", "poss_debug_read_kv",
+           "poss_debug_build_tree", "poss_debug_set_taps", "poss_debug_read_kv", "poss_debug_draft_logits",
            "poss_debug_gemm_scratch_bytes", "poss_debug_gemm", "poss_gemm_static"]
 
 c_i32, c_f32, c_vp = ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
@@ -95,6 +95,7 @@ def load_library():
     lib.poss_set_draft_sampling.argtypes = [c_vp, c_i32, ctypes.POINTER(c_f32), ctypes.POINTER(c_f32)]
     lib.poss_debug_build_tree.argtypes = [c_vp, P(c_i32), P(c_f32), P(PossTree)]
     lib.poss_debug_set_taps.argtypes = [c_vp, c_vp]
+    lib.poss_debug_draft_logits.argtypes = [c_vp, c_i32, c_i32, c_vp]
     lib.poss_debug_read_kv.argtypes = [c_vp, c_i32, c_i32, c_i32, c_i32, P(c_f32), P(c_f32)]
     lib.poss_debug_gemm_scratch_bytes.restype = ctypes.c_size_t
     lib.poss_debug_gemm_scratch_bytes.argtypes = [c_i32, c_i32, c_i32, c_i32]
@@ -322,6 +323,13 @@ class Poss:
 
     def debug_set_taps(self, taps):
         self._check(self.lib.poss_debug_set_taps(self.h, c_vp(taps.data_ptr()) if taps is not None else None))
+
+    def debug_draft_logits(self, row0, n):
+        """Drafter logits of expanded nodes row0 .. row0+n-1 of a tree drafted with drawn children: GPU tensor [n, vocab]."""
+        import torch
+        out = torch.empty(n, self.cfg.vocab, dtype=torch.float32, device="cuda")
+        self._check(self.lib.poss_debug_draft_logits(self.h, row0, n, c_vp(out.data_ptr())))
+        return out
 
     def debug_read_kv(self, which, layer, slot0, n):
         cfg = self.cfg

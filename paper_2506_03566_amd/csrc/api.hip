@@ -1280,6 +1280,18 @@ int poss_debug_set_taps(poss_ctx *c, void *taps) {
     return POSS_OK;
 }
 
+int poss_debug_draft_logits(poss_ctx *c, int32_t row0, int32_t n, float *out) {
+    if (!c || !out) return POSS_E_INVALID_ARG;
+    const poss_config &cf = c->cfg;
+    const int rows = 1 + (cf.depth - 1) * cf.top_k;
+    if (!c->draft_sampling || !c->seq[0].tree_ready)
+        return fail(c, POSS_E_BAD_STATE, "poss_debug_draft_logits: needs a tree drafted with drawn children");
+    if (row0 < 0 || n < 1 || row0 + n > rows) return fail(c, POSS_E_INVALID_ARG, "poss_debug_draft_logits: rows out of range (%d expanded nodes)", rows);
+    const int ld = gemm_npad(cf.vocab);
+    launch_copy_rows_f32(c->dlogits + (size_t)row0 * ld, ld, out, cf.vocab, n, cf.vocab, c->st);
+    return sync_and_harvest(c);
+}
+
 int poss_debug_read_kv(poss_ctx *c, int32_t which, int32_t layer, int32_t slot0, int32_t n, float *k_out, float *v_out) {
     if (!c || !k_out || !v_out) return POSS_E_INVALID_ARG;
     if (n < 1 || slot0 < 0 || slot0 + n > c->cache_slots) return fail(c, POSS_E_INVALID_ARG, "poss_debug_read_kv: slots out of range");

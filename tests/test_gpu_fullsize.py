@@ -155,21 +155,28 @@ def test_sampler_at_full_vocabulary():
 
 def test_drawn_children_at_full_vocabulary():
     """Drawn children and the rejection walk over the 128256-entry vocabulary of the benchmark shape (501 blocks of
-    256 ids per draw): what must hold whatever the numbers - distinct children under every node, non-positive score
-    steps, a committed path that is a root path of the tree, a last token that is not a kept child of the last node
-    unless that node's children were all rejected, a consistent token stream."""
+    256 ids per draw).  Every round: what must hold whatever the numbers (distinct children under every node,
+    non-positive score steps, a committed path that is a root path of the tree, a consistent token stream); and the
+    root against the oracle on the library's own logits: each of its k children lies where its uniform number falls
+    in the float64 CDF of what the earlier draws left (float32 sums over 128K masses: within 3e-5 of the interval),
+    its score is its log-probability, and the walk's decision at the root is the oracle's rejection rule wherever
+    the acceptance test has a margin."""
+    from oracle.sampling import softmax_t, reject_or_accept
     cfg = get_config("c1_llama3_8b_3x2", n_prompt=64)
+    k, T = cfg.top_k, 1.0
     dev = make_weights_on_device(cfg)
     ctx = P.Poss(cfg, dev)
     del dev
     torch.cuda.empty_cache()
     ctx.prefill(make_prompt(cfg))
-    ctx.set_sampling(1.0, np.zeros(cfg.depth + 1, np.float32))
-    n_before, total, accepted = len(ctx.tokens()), 0, 0
+    ctx.set_sampling(T, np.zeros(cfg.depth + 1, np.float32))
+    logits = torch.zeros(cfg.total_tokens + 1, cfg.vocab, device="cuda")
+    n_before, total, accepted, judged = len(ctx.tokens()), 0, 0, 0
     for rnd in range(8):
         rng = np.random.default_rng(500 + rnd)
-        ctx.set_draft_sampling(rng.random((cfg.depth, cfg.top_k, cfg.top_k)).astype(np.float32),
-                               rng.random((cfg.depth + 1, cfg.top_k + 1)).astype(np.float32))
+        UD = rng.random((cfg.depth, k, k)).astype(np.float32)
+        UA = rng.random((cfg.depth + 1, k + 1)).astype(np.float32)
+        ctx.set_draft_sampling(UD, UA)
         d = ctx.draft_tree().as_dict()
         assert d["n"] == cfg.total_tokens + 1 and validate_tree(d["token"], d["parent"])
         kids = {}
@@ -178,12 +185,37 @@ def test_drawn_children_at_full_vocabulary():
             assert 0 <= d["token"][i] < cfg.vocab
             assert d["score"][i] <= d["score"][d["parent"][i]] + 1e-6
         assert all(len(set(v)) == len(v) for v in kids.values())
-        ctx.verify_tree()
+        # ---- the root's children against the float64 inverse CDF of the library's own drafter logits
+        q = softmax_t(ctx.debug_draft_logits(0, 1)[0].cpu().numpy().astype(np.float64), T)
+        root_nodes = [i for i in range(1, d["n"]) if d["parent"][i] == 0]
+        assert len(root_nodes) == k                       # single log-probabilities outrank every deeper sum
+        left = q.copy()
+        for j, node in enumerate(root_nodes):             # node order is draw order
+            c = d["token"][node]
+            cdf = np.cumsum(left) / left.sum()
+            lo, hi = (cdf[c - 1] if c else 0.0), cdf[c]
+            assert lo - 3e-5 <= float(UD[0, 0, j]) < hi + 3e-5, (rnd, j, c, float(UD[0, 0, j]), lo, hi)
+            assert abs(d["score"][node] - np.log(q[c])) <= 1e-3
+            left[c] = 0.0
+        ctx.verify_tree(None, logits_out=logits)
         path, m, toks = ctx.accept_and_commit()
         assert path[0] == 0 and all(d["parent"][b] == a for a, b in zip(path, path[1:]))
         assert toks[:-1] == [d["token"][p] for p in path[1:]] and 0 <= toks[-1] < cfg.vocab
+        # ---- the walk's decision at the root against the oracle's rejection rule
+        p_root = softmax_t(logits[0].cpu().numpy().astype(np.float64), T)
+        margins = []
+        idx, resid = reject_or_accept(p_root, q, [d["token"][n] for n in root_nodes], UA[0, :k], margins)
+        if not margins or min(margins) > 1e-3:
+            judged += 1
+            if idx >= 0:
+                assert m >= 1 and path[1] == root_nodes[idx], (rnd, idx, path)
+            else:
+                assert m == 0
+                cdf = np.cumsum(resid)
+                c = toks[0]
+                assert (cdf[c - 1] if c else 0.0) - 3e-5 <= float(UA[0, k]) < cdf[c] + 3e-5
         total += len(toks)
         accepted += m
-    _say(f"  8 rounds with drawn children: {accepted} drafted tokens accepted, {total} committed")
-    assert len(ctx.tokens()) == n_before + total
+    _say(f"  8 rounds with drawn children: {accepted} drafted tokens accepted, {total} committed, root decision judged in {judged}")
+    assert len(ctx.tokens()) == n_before + total and judged >= 4
     ctx.close()
