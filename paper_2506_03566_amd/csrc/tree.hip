@@ -145,6 +145,82 @@ __global__ __launch_bounds__(256) void topk_seg_kernel(const float *__restrict__
     }
 }
 
+// The merge in two trips, tried first: a segment's values are sorted, so its first value decides whether anything of it
+// can be among the k best.  Trip 1 fetches (max, sum of exponentials, best value) of every segment, up to NT per thread;
+// the threshold is formed as in block_topk, from the threads' best values; trip 2 fetches the k values of the few
+// segments whose best value reaches it.  Returns false, with nothing written, when more than TOPK_CAND candidates sit at
+// the threshold (long runs of equal values): the caller then merges in full.  *lse_out: the row's log-sum-exp.
+template <int NT>
+__device__ __forceinline__ bool topk_merge_heads(const float *__restrict__ recs, int n_seg, int k, TopkLds &L, float *red,
+                                                 float &ov, int &oi, float &lse_out) {
+    constexpr int REC = TOPK_REC;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float m_s[NT], z_s[NT], v0[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {                        // unconditional loads: a segment that does not exist reads segment 0
+        const int sg = tid + j * 256;
+        const float *r = recs + (sg < n_seg ? (size_t)sg * REC : 0);
+        m_s[j] = r[0]; z_s[j] = r[1]; v0[j] = r[2];
+        const int i0 = reinterpret_cast<const int *>(r)[2 + TOPK_MAXK];
+        if (sg >= n_seg) { m_s[j] = -INFINITY; z_s[j] = 0.f; v0[j] = -INFINITY; }
+        else if (i0 == 0x7fffffff) v0[j] = -INFINITY;     // a segment without a valid entry
+    }
+    float mx = -INFINITY, tm = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) { mx = fmaxf(mx, m_s[j]); tm = fmaxf(tm, v0[j]); }
+    mx = wave_max(mx);
+    L.tmax[tid] = tm;
+    if (tid == 0) L.cnt = 0;
+    if (tid < 4) L.thr_w[tid] = -INFINITY;
+    if (tid < TOPK_MAXK) { L.out_v[tid] = -INFINITY; L.out_i[tid] = 0x7fffffff; }
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float se = 0.f;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) se += m_s[j] > -INFINITY ? z_s[j] * expf(m_s[j] - mx) : 0.f;
+    int rank = 0;                                         // of this thread's best value within its wave, ties to the lower lane
+    for (int j = 0; j < 64; j += 4) {
+        const float4 o = *reinterpret_cast<const float4 *>(&L.tmax[wave * 64 + j]);
+        rank += (o.x > tm) || (o.x == tm && j < lane);
+        rank += (o.y > tm) || (o.y == tm && j + 1 < lane);
+        rank += (o.z > tm) || (o.z == tm && j + 2 < lane);
+        rank += (o.w > tm) || (o.w == tm && j + 3 < lane);
+    }
+    if (rank == k - 1) L.thr_w[wave] = tm;
+    se = block_sum(se, red);                              // (its barriers also publish thr_w)
+    lse_out = mx + logf(se);
+    const float thr = fmaxf(fmaxf(L.thr_w[0], L.thr_w[1]), fmaxf(L.thr_w[2], L.thr_w[3]));
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        if (!(v0[j] > -INFINITY && v0[j] >= thr)) continue;
+        const float *r = recs + (size_t)(tid + j * 256) * REC;
+        float cv[TOPK_MAXK]; int ci[TOPK_MAXK];           // the whole record at once: one more trip, not k
+#pragma unroll
+        for (int q = 0; q < TOPK_MAXK; ++q) { cv[q] = r[2 + q]; ci[q] = reinterpret_cast<const int *>(r)[2 + TOPK_MAXK + q]; }
+#pragma unroll
+        for (int q = 0; q < TOPK_MAXK; ++q) {
+            if (q < k && cv[q] >= thr && ci[q] != 0x7fffffff) {
+                const int p = atomicAdd(&L.cnt, 1);       // arrival order does not matter: ranks are by (value, index)
+                if (p < TOPK_CAND) { L.cand_v[p] = cv[q]; L.cand_i[p] = ci[q]; }
+            }
+        }
+    }
+    __syncthreads();
+    const int cnt = L.cnt;
+    if (cnt > TOPK_CAND) { __syncthreads(); return false; }   // (workgroup-uniform; L is reused by the full merge)
+    if (tid < cnt) {
+        const float cv = L.cand_v[tid]; const int ci = L.cand_i[tid];
+        int r = 0;
+        for (int j = 0; j < cnt; ++j) r += better(L.cand_v[j], L.cand_i[j], cv, ci);
+        if (r < k) { L.out_v[r] = cv; L.out_i[r] = ci; }
+    }
+    __syncthreads();
+    ov = -INFINITY; oi = 0x7fffffff;
+    if (tid < k) { ov = L.out_v[tid]; oi = L.out_i[tid]; }
+    return true;
+}
+
 // stage 2: one workgroup per row merges the segments: lse over the segment records, then the k
 // best of the n_seg * k candidates; writes token ids and log-probabilities (value - lse).
 // NV candidates per thread: 8 (up to 2048: the records of topk_seg_kernel), 32 or 64 (the records of a Head GEMM,
@@ -157,7 +233,17 @@ __global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict
     const int row = blockIdx.x, nc = n_seg * k;
     constexpr int REC = TOPK_REC;
     const float *recs = seg_out + (size_t)row * n_seg * REC;
-    // Every load is issued before the first reduction, unconditionally (an entry that does not exist
+    if (n_seg <= 4 * 256) {                               // (workgroup-uniform) the short way first
+        float hv, hl; int hi;
+        if (topk_merge_heads<4>(recs, n_seg, k, lds, red, hv, hi, hl)) {
+            if ((int)threadIdx.x < k) {
+                out_id[row * k + threadIdx.x] = hi;
+                out_logp[row * k + threadIdx.x] = hv - hl;
+            }
+            return;
+        }
+    }
+    // The full merge.  Every load is issued before the first reduction, unconditionally (an entry that does not exist
     // reads slot 0 of segment 0 and is discarded afterwards): one trip to memory, not one per step.
     float v[TOPK_MERGE_NV]; int id[TOPK_MERGE_NV];
 #pragma unroll
