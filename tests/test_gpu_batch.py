@@ -397,3 +397,30 @@ def test_the_rows_a_launch_carries_do_not_change_any_sequence():
         if rows != 256:
             ctx.close()
     pair.close()
+
+
+def test_two_maximal_trees_fill_a_launch():
+    """Two sequences whose trees have the largest size a sequence can carry (127 draft tokens + root = 128 rows):
+    their verification pass is one launch of exactly 256 rows, no ragged tile anywhere; every sequence still
+    drafts, verifies and commits what it does alone."""
+    name, batch, lengths, n_rounds = "t_mid_bf16", 2, (150, 97), 3
+    cfg = get_config(name, total_tokens=127)
+    pair = Pair(name, lib_over={"batch": batch}, total_tokens=127)
+    ctx = pair.ctx
+    prompts = _prompts(cfg, lengths)
+    alone = [_rounds_alone(pair, p, n_rounds) for p in prompts]
+    for b, p in enumerate(prompts):
+        ctx.prefill(p, seq=b)
+    for rnd in range(n_rounds):
+        ctx.draft_tree(want_tree=False)
+        trees = [ctx.get_tree(b).as_dict() for b in range(batch)]
+        assert all(t["n"] == 128 for t in trees)
+        ctx.verify_tree(want_argmax=False)
+        ctx.accept_and_commit()
+        for b in range(batch):
+            atr, apath, am, atoks = alone[b][1][rnd]
+            assert _same_tree(trees[b], atr), f"round {rnd}, sequence {b}: tree differs"
+            assert ctx.commit_result(b) == (apath, am, atoks), f"round {rnd}, sequence {b}"
+    for b in range(batch):
+        assert ctx.tokens(b) == alone[b][2]
+    pair.close()
