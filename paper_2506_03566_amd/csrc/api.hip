@@ -148,6 +148,8 @@ const char *check_config(const poss_config &c) {
     if (c.top_k + (c.depth + 1) + (c.depth - 1) * c.top_k > POSS_MAX_ROWS) return "a specialist pass would exceed 128 rows";
     if (c.kv_page_tokens != 32 && c.kv_page_tokens != 64 && c.kv_page_tokens != 128) return "kv_page_tokens must be 32, 64 or 128";
     if (c.max_seq < 2 || c.max_seq % c.kv_page_tokens) return "max_seq must be a positive multiple of kv_page_tokens";
+    // attention cuts the keys into at most 256 splits of at most 64 blocks of 32
+    if (c.max_seq > 500000) return "max_seq above 500000 is not supported";
     if (c.kv_page_order < 0 || c.kv_page_order > 1) return "kv_page_order must be 0 or 1";
     if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return "rms_eps / rope_theta out of range";
     if (c.batch < 0 || c.batch > 8) return "batch must be in 0..8 (0 and 1: one sequence)";
@@ -951,7 +953,7 @@ int poss_draft_tree(poss_ctx *c, poss_tree *out) {
                 sq.spec_len[s] = sq.t;
                 sq.spec_tmp_depth[s] = d - 1;
             }
-            launch_tree_expand(tds, nb, d, k, L, rows_q_each, c->st);   // one launch, a workgroup per sequence
+            launch_tree_expand(tds, nb, d, k, L, rows_q_each, cf.vocab, c->st);   // one launch, a workgroup per sequence
             i0 = i1;
         }
     }
@@ -1002,7 +1004,7 @@ int poss_debug_build_tree(poss_ctx *c, const int32_t *ids, const float *logp, po
         const int rows = d == 1 ? 1 : k;
         HIP_TRY(c, hipMemcpyAsync(sq.td.topk_id, sid + (size_t)(d - 1) * k * k, rows * k * sizeof(int32_t), hipMemcpyHostToDevice, c->st));
         HIP_TRY(c, hipMemcpyAsync(sq.td.topk_logp, slp + (size_t)(d - 1) * k * k, rows * k * sizeof(float), hipMemcpyHostToDevice, c->st));
-        launch_tree_expand(&sq.td, 1, d, k, L, rows, c->st);
+        launch_tree_expand(&sq.td, 1, d, k, L, rows, cf.vocab, c->st);
     }
     {
         const int32_t *toks = sq.tokens_dev;

@@ -194,7 +194,7 @@ void launch_topk_logsoftmax(const float *logits, int ld, int rows, int vocab, in
                             int32_t *out_id, float *out_logp, hipStream_t st);
 // Both take the trees of n_seq <= TREE_BATCH_MAX sequences (arrays of n_seq entries): one workgroup each.
 constexpr int TREE_BATCH_MAX = 8;
-void launch_tree_expand(const TreeDev *tds, int n_seq, int d, int k, int L, int rows, hipStream_t st);
+void launch_tree_expand(const TreeDev *tds, int n_seq, int d, int k, int L, int rows, int vocab, hipStream_t st);
 // also writes the KV slot of every node (slot_out[s][i] = t[s] + i), which the verification pass reads
 void launch_tree_finalize(const TreeDev *tds, int n_seq, int k, int L, int n_keep, const int *t,
                           const int32_t *const *tokens_dev, int32_t *const *slot_out, hipStream_t st);

@@ -30,6 +30,11 @@ __device__ __forceinline__ float block_sum(float v, float *red /* >= 17 floats o
     return s;
 }
 
+// A token id that came out of arithmetic indexes the embedding table only through this: an argmax over a row of
+// logits that are all NaN finds no entry that compares and leaves the id of "no entry" (0x7fffffff) - a bad number
+// must not become a bad address.  Such a row reads token 0.
+__device__ __forceinline__ int embedding_row(int token, int vocab) { return (unsigned)token < (unsigned)vocab ? token : 0; }
+
 // (value, index) ordering used by every argmax / top-k here: larger value first, then lower index.
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
     return (v > bv) || (v == bv && i < bi);

@@ -15,7 +15,7 @@ namespace poss {
 // (and the row's rotary table, which every layer of the pass uses)
 template <typename T>
 __global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ embed, const int32_t *__restrict__ tokens,
-                                                         int d, float eps, const T *__restrict__ gain,
+                                                         int vocab, int d, float eps, const T *__restrict__ gain,
                                                          float *__restrict__ h, T *__restrict__ u,
                                                          const int32_t *__restrict__ pos,
                                                          const double *__restrict__ inv_freq, int half,
@@ -24,7 +24,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const T *__restrict__ e
     const int row = blockIdx.x;
     // the rotary table by the last wave, so that the first ones start on the embedding row at once
     rope_table_row(pos[row], inv_freq, half, cs + (size_t)row * half, half <= 64 && blockDim.x >= 128 ? (int)blockDim.x - 64 : 0);
-    const T *e = embed + (size_t)tokens[row] * d;
+    const T *e = embed + (size_t)embedding_row(tokens[row], vocab) * d;
     constexpr int VE = 16 / (int)sizeof(T);               // elements per 16-byte access
     constexpr int MAXV = 4;                                // 16-byte pieces a thread keeps (d <= 4 * 256 * VE)
     if (d % VE == 0 && d <= MAXV * 256 * VE && blockDim.x == 256) {
@@ -83,7 +83,7 @@ void launch_embed_norm(const ModelDims &md, const void *embed, const int32_t *to
                        const void *gain, float *h, void *u, const int32_t *pos, const double *inv_freq,
                        float2 *cs, hipStream_t st) {
     POSS_DISPATCH(md.dt, hipLaunchKernelGGL((embed_norm_kernel<T>), dim3(rows), dim3(256), 0, st,
-                                            static_cast<const T *>(embed), tokens, md.d, md.eps,
+                                            static_cast<const T *>(embed), tokens, md.vocab, md.d, md.eps,
                                             static_cast<const T *>(gain), h, static_cast<T *>(u), pos, inv_freq,
                                             md.dh / 2, cs));
 }
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(64) void argmax_merge_kernel(const float *__restric
         if (better(v, i, bv, bi)) { bv = v; bi = i; }
     }
     wave_argmax(bv, bi);
-    if (threadIdx.x == 0) out[rowi] = bi;
+    if (threadIdx.x == 0) out[rowi] = bi == 0x7fffffff ? 0 : bi;        // no logit of the row compared (all NaN): token 0, not an id outside the vocabulary
 }
 
 size_t argmax_scratch_floats(int rows, int vocab) { return (size_t)2 * rows * head_segments_max(vocab); }   // finest segmentation: the Head GEMM's tiles

@@ -312,7 +312,7 @@ struct TreeBatch {
     int32_t *slot_out[TREE_BATCH_MAX];
 };
 
-__global__ __launch_bounds__(256) void tree_expand_kernel(TreeBatch tb, int d, int k, int L, int rows) {
+__global__ __launch_bounds__(256) void tree_expand_kernel(TreeBatch tb, int d, int k, int L, int rows, int vocab) {
     __shared__ float sc[256];
     const TreeDev &td = tb.td[blockIdx.x];
     const int n_child = rows * k;
@@ -323,9 +323,14 @@ __global__ __launch_bounds__(256) void tree_expand_kernel(TreeBatch tb, int d, i
         const int r = tid / k;
         const float ps = d == 1 ? 0.f : td.fr_score[(d - 1) * k + r];
         if (d > 1 && d < L) { pw0 = td.fr_mask[((d - 1) * k + r) * MASK_WORDS]; pw1 = td.fr_mask[((d - 1) * k + r) * MASK_WORDS + 1]; }
-        const float s = ps + td.topk_logp[tid];
+        // A score that is not a number (a drafter fed NaN) would compare false with everything: every child would rank
+        // first here and every candidate be kept by the final ranking, beyond the tree's arrays.  It counts as -inf
+        // (ties go by index), and an id that is no vocabulary entry as token 0.
+        float s = ps + td.topk_logp[tid];
+        if (!(s == s)) s = -INFINITY;
         sc[tid] = s;
-        td.pool_token[base + tid] = td.topk_id[tid];
+        const int tok = embedding_row(td.topk_id[tid], vocab);
+        td.pool_token[base + tid] = tok;
         td.pool_parent[base + tid] = d == 1 ? -1 : td.fr_pool[(d - 1) * k + r];
         td.pool_depth[base + tid] = d;
         td.pool_score[base + tid] = s;
@@ -338,7 +343,7 @@ __global__ __launch_bounds__(256) void tree_expand_kernel(TreeBatch tb, int d, i
         if (rank < k) {
             const int r = tid / k, o = d * k + rank;
             td.fr_pool[o] = base + tid;
-            td.fr_token[o] = td.topk_id[tid];
+            td.fr_token[o] = embedding_row(td.topk_id[tid], vocab);
             td.fr_parent_rank[o] = r;
             td.fr_score[o] = s;
             const int bit = (d - 1) * k + rank;
@@ -350,11 +355,11 @@ __global__ __launch_bounds__(256) void tree_expand_kernel(TreeBatch tb, int d, i
     }
 }
 
-void launch_tree_expand(const TreeDev *tds, int n_seq, int d, int k, int L, int rows, hipStream_t st) {
+void launch_tree_expand(const TreeDev *tds, int n_seq, int d, int k, int L, int rows, int vocab, hipStream_t st) {
     if (n_seq < 1 || n_seq > TREE_BATCH_MAX) return;
     TreeBatch tb{};
     for (int i = 0; i < n_seq; ++i) tb.td[i] = tds[i];
-    hipLaunchKernelGGL(tree_expand_kernel, dim3(n_seq), dim3(256), 0, st, tb, d, k, L, rows);
+    hipLaunchKernelGGL(tree_expand_kernel, dim3(n_seq), dim3(256), 0, st, tb, d, k, L, rows, vocab);
 }
 
 // ------------------------------------------------------------------ rerank + emit
@@ -466,7 +471,7 @@ void launch_tree_finalize(const TreeDev *tds, int n_seq, int k, int L, int n_kee
 // ------------------------------------------------------------------ rows of one specialist pass
 template <typename T>
 __global__ __launch_bounds__(256) void draft_assemble_kernel(
-    DraftRowPlan plan, int depth_index, int k, int d_model, const T *__restrict__ embed,
+    DraftRowPlan plan, int depth_index, int k, int d_model, int vocab, const T *__restrict__ embed,
     const int32_t *__restrict__ tokens_dev, const T *__restrict__ feat_stash, TreeDev td,
     const float *__restrict__ fhat_prev, T *__restrict__ xin_tmp, T *__restrict__ x_out,
     int32_t *__restrict__ pos_out, int32_t *__restrict__ slot_out, uint64_t *__restrict__ mask_out,
@@ -480,7 +485,7 @@ __global__ __launch_bounds__(256) void draft_assemble_kernel(
     const bool vec = d_model % VE == 0;
     const int nv = d_model / VE;
     if (kind == 0) {                    // committed pair [x_{i+1} ; f_i]
-        const T *e = embed + (size_t)tokens_dev[idx + 1] * d_model, *f = feat_stash + (size_t)idx * d_model;
+        const T *e = embed + (size_t)embedding_row(tokens_dev[idx + 1], vocab) * d_model, *f = feat_stash + (size_t)idx * d_model;
         if (vec) {
             const uint4 *e4 = reinterpret_cast<const uint4 *>(e), *f4 = reinterpret_cast<const uint4 *>(f);
             uint4 *d4 = reinterpret_cast<uint4 *>(dst);
@@ -499,7 +504,7 @@ __global__ __launch_bounds__(256) void draft_assemble_kernel(
         }
     } else {                            // new frontier row: [emb(token_v) ; drafted feature of parent(v)]
         const int o = depth_index * k + idx;
-        const T *e = embed + (size_t)td.fr_token[o] * d_model;
+        const T *e = embed + (size_t)embedding_row(td.fr_token[o], vocab) * d_model;
         const float *f = fhat_prev + (size_t)td.fr_parent_rank[o] * d_model;
         T *keep = xin_tmp + (size_t)((depth_index - 1) * k + idx) * 2 * d_model;
         if (vec) {
@@ -540,7 +545,7 @@ void launch_draft_assemble(const ModelDims &md, const DraftRowPlan &plan, int de
                            float2 *cs, hipStream_t st) {
 #define POSS_ASM(T)                                                                                          \
     hipLaunchKernelGGL((draft_assemble_kernel<T>), dim3(plan.n_rows), dim3(256), 0, st, plan, depth_index, k,   \
-                       md.d, static_cast<const T *>(embed), tokens_dev, static_cast<const T *>(feat_stash), td, \
+                       md.d, md.vocab, static_cast<const T *>(embed), tokens_dev, static_cast<const T *>(feat_stash), td, \
                        fhat_prev, static_cast<T *>(xin_tmp), static_cast<T *>(x_out), pos_out, slot_out, mask_out, \
                        inv_freq, md.dh / 2, cs)
     if (md.dt == DT_F32) POSS_ASM(float); else if (md.dt == DT_BF16) POSS_ASM(bf16_t); else POSS_ASM(f16_t);
