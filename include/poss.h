@@ -73,7 +73,7 @@ typedef struct poss_config {
     int32_t dtype;                           /* POSS_DTYPE_*                               */
     int32_t n_specialists, positions_per_specialist, fc_bias;
     int32_t top_k, depth, total_tokens;
-    int32_t max_seq;                         /* capacity in committed tokens (multiple of kv_page_tokens) */
+    int32_t max_seq;                         /* capacity in committed tokens (multiple of kv_page_tokens, at most 500000) */
     int32_t kv_page_tokens;                  /* tokens per KV page: 32, 64 or 128           */
     int32_t kv_page_order;                   /* 0: pages in order; 1: physical pages reversed (layout tests) */
     int32_t batch;                           /* sequences per round: 0 or 1 = one; up to 8.  A pass stacks the rows of as *

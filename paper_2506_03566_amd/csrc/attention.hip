@@ -4,13 +4,15 @@
 // that follow them (the rows of this round: tree nodes in verification, drafted ancestors in a
 // specialist pass, the chunk itself in prefill), those whose bit is set in the row's mask.
 //
-// 16-bit types: one wave per 16 query rows, four waves (one KV head) per workgroup sharing the
-// key/value blocks through LDS, on v_mfma_f32_16x16x32.
+// 16-bit types: one wave per 16 (or 32) query rows, four waves (one KV head) per key-way and workgroup
+// sharing the key/value blocks through LDS, on v_mfma_f32_16x16x32.
 // Query rows of the G = Hq/Hkv heads that share a KV head are stacked (rho = m*G + g) so a wave's
 // 16 rows reuse every key it loads.  Scores are formed transposed, S^T = K Q^T (keys as MFMA rows):
 // a lane then holds 8 scores of ONE query row per 32-key block, which is already the B-operand
 // layout of O^T = V^T P^T as long as the keys of a block are contracted in the order the score
-// tiles deliver them; V is cached transposed ([dh][token]) so that order costs two 8-byte loads.
+// tiles deliver them; the key rows are dealt to the two score tiles so that this order is the
+// natural one of V^T, which is cached transposed ([dh][token]).  Blocks go from memory straight
+// into LDS (LDS-direct loads), swizzled so that operand reads run at the full LDS rate.
 // Softmax is online (running max / sum per query row, float32); partial (max, sum, O) per split
 // are merged by a second kernel in fixed order.
 #include "device_utils.h"
@@ -45,12 +47,43 @@ __device__ __forceinline__ bool slot_visible(int slot, int n_prefix, int region_
     return (j < 0) | (((unsigned)j < (unsigned)region_len) & bit);
 }
 
+// Swizzles of the staged blocks.  A block reaches LDS through 16-byte LDS-direct loads: lane l of a wave
+// writes base + 16 l, so a row cannot be padded; instead the 16-byte chunk c of row r is kept at position
+// c ^ swz(r) of the row (the loading lane simply fetches the chunk that belongs at its position).
+// An operand read has its 64 lanes read one row each (lane % 16 picks the row, lane / 16 the chunk).  Measured
+// on this GPU with every wave of a CU reading: these two patterns run at 4.0 cycles per ds_read_b128 (256 bytes
+// per cycle, the same as consecutive addresses), rows padded by 16 bytes instead (272- or 80-byte strides), a
+// three-bit key swizzle, or a value swizzle that also folds in row bit 3, at 8.2 - 8.9 cycles.
+// Keys: row kappa of a block (bits 0, 1 and 3, 4 vary over the lanes of a read; bit 2 is the score tile).
+template <int DH>
+__device__ __forceinline__ int key_swizzle(int kappa) {
+    const int l0 = kappa & 1, l1 = (kappa >> 1) & 1, l2 = (kappa >> 3) & 1, l3 = (kappa >> 4) & 1;
+    if (DH >= 128) return l0 | (l1 << 1) | (l2 << 2) | (l3 << 3);     // 16 chunks per row: the reading lane's row number
+    return l1 | (l2 << 1) | (l3 << 2);                                // 8 chunks per row, two rows per 256 bytes: half of it
+}
+// Values: row rho of V^T (a dh index; 4 chunks of 8 keys per row, four rows per 256 bytes).
+__device__ __forceinline__ int value_swizzle(int rho) { return (rho >> 1) & 3; }
+
+// One 16-byte LDS-direct load per lane: lane l's 16 bytes from `g` land at LDS byte address lds_base + 16 l
+// (lds_base wave-uniform).  Written as assembly because the compiler, which cannot tell which LDS reads a
+// load it knows of may alias, would wait for ALL such loads before every LDS read; counted waits
+// (dma_wait) are placed by hand instead.  M0 is set in the same statement and nothing else here uses it.
+__device__ __forceinline__ void lds_dma16(unsigned lds_base, const void *g) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(g) : "memory");
+}
+// Wait until at most N of this wave's vector-memory loads are outstanding (they complete in order).
+template <int N>
+__device__ __forceinline__ void dma_wait() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // One workgroup = 4 waves x RT tiles of 16 query rows of ONE KV head (times KW key-ways), over the key
 // blocks of one split.  RT = 2 halves the LDS operand reads per MFMA (every key / value fragment
-// feeds two row tiles): long contexts are bound by exactly those reads.  Key / value blocks (32 slots) go global -> registers -> LDS one block ahead of the
-// arithmetic and are shared by the four waves.  LDS layouts: K rows padded to DH+8 elements (row
-// stride 272 B: conflict-free 16-byte operand reads); V^T rows hold their 32 keys permuted so that
-// the 8 keys a lane contracts (4 of each 16-key half) are one 16-byte chunk.
+// feeds two row tiles): long contexts are bound by exactly those reads.
+// Key / value blocks (32 slots) go from memory straight into LDS (no registers, no LDS stores), four stages
+// deep, shared by the four waves of a key-way.  The 16 key rows of score tile tt are rows 8(i/4) + 4tt + i%4
+// of the block, so that the 8 scores a lane holds of a query row belong to 8 CONSECUTIVE keys
+// (8 lg .. 8 lg + 7): its slice of P^T then pairs with one natural 16-byte chunk of a V^T row.
 // With a single split the result is normalised and written in the storage type directly;
 // otherwise (max, sum, O) partials go to the merge kernel.
 template <typename T, int DH, int KW, int RT>
@@ -59,21 +92,26 @@ __device__ __forceinline__ void attn_mfma_body(
     int region_len, KVCache kv, int blocks_per_split, int n_splits, int n_row_groups, float scale,
     float *__restrict__ o_part, float *__restrict__ ml_part, int rho_pad, T *__restrict__ out_direct) {
     typedef typename Vec8<T>::type V8;
+    typedef __attribute__((address_space(3))) void *LdsPtr;
     constexpr int KS = DH / 32, DT = DH / 16;
-    constexpr int KROW = DH + 8;                          // padded K row, elements
-    constexpr int K_UNITS = 32 * DH / 8;                  // 16-byte units of one K block
-    constexpr int KPT = K_UNITS / 256, VPT = K_UNITS / 256;
-    constexpr int VROW = 32 + 8;                          // padded V^T row (80 B stride: conflict-free operand reads)
-    constexpr int KBLK = 32 * KROW, VBLK = DH * VROW;     // elements of one staged K / V^T block
-    // [2 buffers][KW blocks]; after the last block the same memory carries the KW-way merge
-    __shared__ __attribute__((aligned(16))) T lds_all[2 * KW * (KBLK + VBLK)];
-    T *ks_lds = lds_all, *vs_lds = lds_all + 2 * KW * KBLK;
+    constexpr int CPR = DH / 8;                           // 16-byte chunks of a key row
+    constexpr int UNITS = 32 * CPR;                       // 16-byte units of a key block (and of a value block)
+    constexpr int WPW = 4;                                // waves per key-way
+    constexpr int STG = 64 * WPW;                         // threads of a key-way: they load its blocks
+    constexpr int UPT = UNITS / STG;                      // loads per thread and block
+    static_assert(UPT >= 1, "a block must give every thread of its key-way a load");
+    constexpr int BLK = 32 * DH;                          // elements of a staged block
+    constexpr int NST = 4;                                // stages
+    // [stage][key-way] blocks of keys, then of values; after the last block the same memory carries the KW-way merge
+    __shared__ __attribute__((aligned(1024))) T lds_all[2 * NST * KW * BLK];
+    T *ks_lds = lds_all, *vs_lds = lds_all + NST * KW * BLK;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
-    // staging: 256 threads per block; the block index is wave-uniform, and said to be, so that the
-    // page-table reads become scalar loads that do not queue behind the key/value loads in flight
-    const int stage_blk = __builtin_amdgcn_readfirstlane(tid >> 8), stid = tid & 255;
-    const int kway = stage_blk;                           // which of the KW blocks of an iteration this wave takes (wave / 4): branches on it are scalar
+    // which of the KW blocks of an iteration this wave takes (wave / 4; wave-uniform: branches on it are scalar) and
+    // which of the four groups of row tiles.  (Waves w and w + 4, the two key-ways of a tile group, are the pair the
+    // text below places on one SIMD; giving the pairs (2w, 2w + 1) the two ways instead measured the same.)
+    const int kway = __builtin_amdgcn_readfirstlane(tid / STG), wq = wave % WPW;
+    const int stid = tid % STG;
     // Workgroup id -> (row group, KV head, split).  Consecutive ids go to the 8 XCDs in turn, each with an
     // L2 of its own, so the row groups that read the same keys and values (same head and split) are given
     // ids that are equal modulo 8: the block is fetched from memory once and then found in that L2.
@@ -82,95 +120,70 @@ __device__ __forceinline__ void attn_mfma_body(
     const int row_group = qid % n_row_groups, pair = (qid / n_row_groups) * 8 + xcd;
     if (pair >= n_pairs) return;                          // padding of the last round of eight
     const int G = hq / hkv, kvh = pair % hkv, split = pair / hkv;
-    const int tile0 = (row_group * 4 + (wave & 3)) * RT;  // this wave's tiles: tile0 .. tile0 + RT - 1
-    bool valid[RT];
-    int m[RT], qh[RT];
+    const int tile0 = (row_group * WPW + wq) * RT;        // this wave's tiles: tile0 .. tile0 + RT - 1
+    // query row of lane lr in row tile rt: (valid, row of the pass, query head).  Recomputed where it is needed
+    // (the masked blocks at the end of the keys, the final stores) rather than kept in registers over the loop.
+    auto row_of = [&](int rt, bool &valid, int &m, int &qh) {
+        const int rho = (tile0 + rt) * 16 + lr;
+        valid = rho < rows * G;
+        m = valid ? rho / G : 0;
+        qh = kvh * G + (valid ? rho % G : 0);
+    };
     V8 qf[RT][KS];
-    uint64_t m0[RT], m1[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-        const int rho = (tile0 + rt) * 16 + lr;
-        valid[rt] = rho < rows * G;
-        m[rt] = valid[rt] ? rho / G : 0;
-        qh[rt] = kvh * G + (valid[rt] ? rho % G : 0);
+        bool valid; int m, qh;
+        row_of(rt, valid, m, qh);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(q + ((size_t)m[rt] * hq + qh[rt]) * DH + ks * 32 + lg * 8);
-            qf[rt][ks] = __builtin_bit_cast(V8, valid[rt] ? v : u32x4{0u, 0u, 0u, 0u});
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(q + ((size_t)m * hq + qh) * DH + ks * 32 + lg * 8);
+            qf[rt][ks] = __builtin_bit_cast(V8, valid ? v : u32x4{0u, 0u, 0u, 0u});
         }
-        m0[rt] = valid[rt] ? mask[(size_t)m[rt] * MASK_WORDS] : 0ull;
-        m1[rt] = valid[rt] ? mask[(size_t)m[rt] * MASK_WORDS + 1] : 0ull;
     }
 
     const int total = n_prefix + region_len;
     const int n_blocks = (total + 31) >> 5;
     const int b0 = split * blocks_per_split, b1 = min(n_blocks, b0 + blocks_per_split);
+    const int n_it = (b1 - b0 + KW - 1) / KW;             // iteration `it` takes blocks b0 + it KW .. + KW - 1, one per key-way
     const int P = 1 << kv.page_shift;
     const T *kc = static_cast<const T *>(kv.k), *vc = static_cast<const T *>(kv.vt);
 
-    // staging: K block = 32 consecutive token rows = 32*DH contiguous elements; V^T block = DH rows
-    // of 32 keys (64 bytes each, row stride P elements).
-    // Key and value blocks travel global -> registers -> LDS in two rings of their own, two iterations deep (an
-    // iteration's arithmetic is much shorter than the latency of its loads).  Keys run one iteration AHEAD of values:
-    // the score MFMAs of iteration it + 1 are issued before the softmax of iteration it, so that the matrix pipe works
-    // while the vector ALU exponentiates (waves of a workgroup move in step from barrier to barrier: without this
-    // every wave of a SIMD would sit in its softmax at the same time, the matrix pipe idle).
-    u32x4 kr[2][KPT], vr[2][VPT];
-    // The page-table entry of a block is fetched one call ahead of the block itself: read where it is
-    // used, it would put a dependent trip to memory (and a wait for every load in flight) into each
-    // iteration.  Calls go up in steps of KW blocks.
-    // (The table is read through the constant address space: nothing writes it while a kernel runs,
-    // and a wave-uniform read from there is a scalar load, outside the vector-memory queue.)
-    typedef const __attribute__((address_space(4))) int32_t *ConstTable;
-    const ConstTable page_table_c = (ConstTable)(uintptr_t)kv.page_table;
-    auto page_of = [&](int bfirst) {
-        const int b = min(bfirst + stage_blk, b1 - 1);
-        return page_table_c[(b << 5) >> kv.page_shift];
-    };
-    int pgk_next = page_of(b0), pgv_next = pgk_next;
-    // this thread's share of the keys / values of block bfirst + stage_blk; pg_after: the entry for the call that follows
-    auto load_k = [&](auto slot_tag, int bfirst, int pg_after) {
-        constexpr int SLOT = decltype(slot_tag)::value;
-        int b = bfirst + stage_blk;
-        if (b >= b1) b = b1 - 1;                          // never predicated: reload a valid block, it is ignored
-        const int off = (b << 5) & (P - 1);
-        const T *kb = kc + ((size_t)(pgk_next * hkv + kvh) * P + off) * DH;
-        pgk_next = pg_after;
+    // Staging.  K block = 32 consecutive token rows = 32*DH contiguous elements; V^T block = DH rows of 32 keys
+    // (64 bytes each, row stride P elements).  Thread stid of a block's 256 owns LDS units stid + 256 i and fetches
+    // the chunk that belongs there under the swizzle.  Stage it % NST holds iteration it's blocks.
+    // (Page-table entries: lane j of pg_vec holds the entry of block b0 + j - a split has at most ATTN_MAX_BPS = 64
+    // blocks - fetched with one vector load before the loads to LDS start and picked with v_readlane afterwards.  A
+    // scalar load per block would sit in the same counter as the LDS reads and, returning out of order, turn every
+    // wait for an operand fragment into a wait for a trip to memory; a vector load inside the loop would make the
+    // compiler wait for every load in flight.)
+    auto block_of = [&](int it) { return min(b0 + it * KW + kway, b1 - 1); };   // never predicated: past the end a valid block is loaded again and ignored
+    const int pg_vec = kv.page_table[(min(b0 + lane, b1 - 1) << 5) >> kv.page_shift];
+    auto page_of_block = [&](int b) { return __builtin_amdgcn_readlane(pg_vec, (b - b0) & 63); };   // b wave-uniform
+    int k_goff[UPT], v_goff[UPT];                         // element offsets of this thread's chunks inside a block
 #pragma unroll
-        for (int i = 0; i < KPT; ++i) kr[SLOT][i] = *reinterpret_cast<const u32x4 *>(kb + (size_t)(stid + i * 256) * 8);
-    };
-    auto load_v = [&](auto slot_tag, int bfirst, int pg_after) {
-        constexpr int SLOT = decltype(slot_tag)::value;
-        int b = bfirst + stage_blk;
-        if (b >= b1) b = b1 - 1;
-        const int off = (b << 5) & (P - 1);
-        const T *vb = vc + (size_t)(pgv_next * hkv + kvh) * DH * P + off;
-        pgv_next = pg_after;
+    for (int i = 0; i < UPT; ++i) {
+        const int u = stid + i * STG;
+        const int krow = u / CPR, kpos = u % CPR;
+        k_goff[i] = krow * DH + (kpos ^ key_swizzle<DH>(krow)) * 8;
+        const int vrow = u >> 2, vpos = u & 3;
+        v_goff[i] = vrow * P + (vpos ^ value_swizzle(vrow)) * 8;
+    }
+    const unsigned lds_k0 = (unsigned)(uintptr_t)(LdsPtr)ks_lds, lds_v0 = (unsigned)(uintptr_t)(LdsPtr)vs_lds;
+    // byte offset of this wave's 64 units of load 0 inside a stage, wave-uniform
+    const unsigned wave_units = __builtin_amdgcn_readfirstlane(kway * BLK * (int)sizeof(T) + wq * 1024);
+    auto issue_k = [&](int it) {
+        const int b = block_of(it), off = (b << 5) & (P - 1);
+        const T *kb = kc + ((size_t)(page_of_block(b) * hkv + kvh) * P + off) * DH;
+        const unsigned base = lds_k0 + (unsigned)((it & (NST - 1)) * KW * BLK * (int)sizeof(T)) + wave_units;
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int u = stid + i * 256;                 // unit: dh row u / 4, keys (u % 4) * 8 .. +8
-            vr[SLOT][i] = *reinterpret_cast<const u32x4 *>(vb + (size_t)(u >> 2) * P + (u & 3) * 8);
-        }
+        for (int i = 0; i < UPT; ++i) lds_dma16(base + i * STG * 16, kb + k_goff[i]);
     };
-    auto store_k = [&](auto slot_tag, int buf) {
-        constexpr int SLOT = decltype(slot_tag)::value;
+    auto issue_v = [&](int it) {
+        const int b = block_of(it), off = (b << 5) & (P - 1);
+        const T *vb = vc + (size_t)(page_of_block(b) * hkv + kvh) * DH * P + off;
+        const unsigned base = lds_v0 + (unsigned)((it & (NST - 1)) * KW * BLK * (int)sizeof(T)) + wave_units;
 #pragma unroll
-        for (int i = 0; i < KPT; ++i) {
-            const int u = stid + i * 256, row = u / (DH / 8), c8 = u % (DH / 8);
-            *reinterpret_cast<u32x4 *>(&ks_lds[(buf * KW + stage_blk) * KBLK + row * KROW + c8 * 8]) = kr[SLOT][i];
-        }
-    };
-    auto store_v = [&](auto slot_tag, int buf) {
-        constexpr int SLOT = decltype(slot_tag)::value;
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            // keys k0 = (u%4)*8 .. k0+7: key k sits at element (k%16)/4*8 + (k/16)*4 + k%4 of its row
-            const int u = stid + i * 256, row = u >> 2, k0 = (u & 3) * 8;
-            const int half = k0 >> 4, g0 = (k0 & 15) >> 2;                 // k0..k0+3 -> group g0, k0+4..k0+7 -> g0+1
-            T *dst = &vs_lds[(buf * KW + stage_blk) * VBLK + row * VROW];
-            *reinterpret_cast<u32x2 *>(dst + g0 * 8 + half * 4) = u32x2{vr[SLOT][i].x, vr[SLOT][i].y};
-            *reinterpret_cast<u32x2 *>(dst + (g0 + 1) * 8 + half * 4) = u32x2{vr[SLOT][i].z, vr[SLOT][i].w};
-        }
+        for (int i = 0; i < UPT; ++i) lds_dma16(base + i * STG * 16, vb + v_goff[i]);
     };
 
     f32x4 acc[RT][DT];
@@ -182,16 +195,23 @@ __device__ __forceinline__ void attn_mfma_body(
         for (int dt = 0; dt < DT; ++dt) acc[rt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // S^T tiles of one block for this wave's row tiles: rows = keys slot0 + tt*16 + (0..15), columns = query rows.
+    // operand reads: element offsets of this lane inside a staged block
+    const int kappa0 = 8 * (lr >> 2) + (lr & 3), kswz = key_swizzle<DH>(kappa0);
+    int k_rd[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k_rd[ks] = kappa0 * DH + ((ks * 4 + lg) ^ kswz) * 8;
+    const int v_rd = lr * 32 + (lg ^ value_swizzle(lr)) * 8;
+
+    // S^T tiles of iteration it's block for this wave's row tiles: rows = keys 8(i/4) + 4tt + i%4, columns = query rows.
     // Every key fragment of the block is requested before the first MFMA.
-    auto scores = [&](int buf, f32x4 (&s)[RT][2]) {
-        const T *kbuf = &ks_lds[(buf * KW + kway) * KBLK];
-        u32x4 kf[2][KS];
+    auto key_fragments = [&](int it, u32x4 (&kf)[2][KS]) {
+        const T *kbuf = &ks_lds[((it & (NST - 1)) * KW + kway) * BLK];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                kf[tt][ks] = *reinterpret_cast<const u32x4 *>(&kbuf[(tt * 16 + lr) * KROW + ks * 32 + lg * 8]);
+            for (int ks = 0; ks < KS; ++ks) kf[tt][ks] = *reinterpret_cast<const u32x4 *>(&kbuf[tt * 4 * DH + k_rd[ks]]);
+    };
+    auto scores_of = [&](const u32x4 (&kf)[2][KS], f32x4 (&s)[RT][2]) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
 #pragma unroll
@@ -203,67 +223,66 @@ __device__ __forceinline__ void attn_mfma_body(
                     s[rt][tt] = Vec8<T>::mfma(__builtin_bit_cast(V8, kf[tt][ks]), qf[rt][ks], s[rt][tt]);
         }
     };
-
-    typedef std::integral_constant<int, 0> S0;
-    typedef std::integral_constant<int, 1> S1;
-    // prologue: keys of iterations 0 and 1 and values of iteration 0 into LDS, the scores of iteration 0 formed,
-    // both rings refilled (keys up to iteration 3, values up to iteration 2)
-    load_k(S0{}, b0, page_of(b0 + KW));
-    load_k(S1{}, b0 + KW, page_of(b0 + 2 * KW));
-    load_v(S0{}, b0, page_of(b0 + KW));
-    load_v(S1{}, b0 + KW, page_of(b0 + 2 * KW));
-    store_k(S0{}, 0);
-    load_k(S0{}, b0 + 2 * KW, page_of(b0 + 3 * KW));
-    __syncthreads();
-    f32x4 s_cur[RT][2];
-    if (b0 + kway < b1) scores(0, s_cur);
-    store_k(S1{}, 1);
-    load_k(S1{}, b0 + 3 * KW, page_of(b0 + 4 * KW));
-    store_v(S0{}, 0);
-    load_v(S0{}, b0 + 2 * KW, page_of(b0 + 3 * KW));
-    __syncthreads();
-    // iteration `it` (blocks bi .. bi+KW-1, PAR = it % 2): scores of it + 1 (keys in LDS buffer PAR ^ 1), softmax of it,
-    // P V of it (values in buffer PAR); then keys of it + 2 go into key buffer PAR (last read by the scores of `it`, an
-    // iteration ago) and values of it + 1 into value buffer PAR ^ 1, and the two ring slots are refilled at once with
-    // iterations it + 4 (keys) and it + 3 (values).  A slot is reloaded right behind the LDS stores that read it: its
-    // registers are never free in between, and the wait for a block's loads comes after an iteration's arithmetic.
-    auto iteration = [&](auto par_tag, int bi) {
-        constexpr int PAR = decltype(par_tag)::value;
-        // requested here, used by this iteration's refills: at the foot of the iteration the wait for the
-        // LDS stores ahead of the barrier would wait for these scalar loads as well
-        const int pgk_ahead = page_of(bi + 5 * KW), pgv_ahead = page_of(bi + 4 * KW);
-        const int b = bi + kway;
-        f32x4 s_next[RT][2];
-        if (b + KW < b1) scores(PAR ^ 1, s_next);         // wave-uniform
-        if (b < b1) {                                     // wave-uniform
-        const int slot0 = b << 5;
-        const T *vbuf = &vs_lds[(PAR * KW + kway) * VBLK];
-        u32x4 vf[DT];
+    auto scores = [&](int it, f32x4 (&s)[RT][2]) {
+        u32x4 kf[2][KS];
+        key_fragments(it, kf);
+        scores_of(kf, s);
+    };
+    // bf16 keeps 8 significant bits: probabilities rounded to it moved a layer's output by 2e-2 at the 8B
+    // shape (the mean of hundreds of values loses its low bits), ten times everything else.  They go into the
+    // P V product as a sum of two bf16 numbers, p = hi + lo, 16 significant bits, at the price of a second
+    // MFMA per value fragment.  fp16 (11 bits) stays single.
+    constexpr bool SPLIT_P = std::is_same<T, bf16_t>::value;
+    // acc += V^T P^T of iteration it's block, in two halves of the value fragments (h = 0, 1) so that only half of them
+    // need registers at a time
+    auto pv_half = [&](int it, auto h_tag, const V8 (&p_hi)[RT], const V8 (&p_lo)[RT]) {
+        constexpr int HD = DT / 2, H = decltype(h_tag)::value;
+        const T *vbuf = &vs_lds[((it & (NST - 1)) * KW + kway) * BLK];
+        u32x4 vf[HD];
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[dt] = *reinterpret_cast<const u32x4 *>(&vbuf[(dt * 16 + lr) * VROW + lg * 8]);
-        // lane holds keys slot0 + tt*16 + 4*lg + r of query row lr.  Scores are kept in the log2
-        // domain (scale * log2 e folded into one factor) so that the exponentials are single
-        // v_exp_f32 instructions; the softmax is VALU-bound, not MFMA-bound, at these sizes.
-        // bf16 keeps 8 significant bits: probabilities rounded to it moved a layer's output by 2e-2 at the 8B
-        // shape (the mean of hundreds of values loses its low bits), ten times everything else.  They go into the
-        // P V product as a sum of two bf16 numbers, p = hi + lo, 16 significant bits, at the price of a second
-        // MFMA per value fragment.  fp16 (11 bits) stays single.
-        constexpr bool SPLIT_P = std::is_same<T, bf16_t>::value;
-        V8 pf[RT], pf_lo[RT];
-        float alpha[RT];
-        bool rescale = false;
+        for (int d = 0; d < HD; ++d) vf[d] = *reinterpret_cast<const u32x4 *>(&vbuf[(H * HD + d) * 16 * 32 + v_rd]);
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
+        for (int d = 0; d < HD; ++d)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+                acc[rt][H * HD + d] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf[d]), p_hi[rt], acc[rt][H * HD + d]);
+        if constexpr (SPLIT_P) {
+#pragma unroll
+            for (int d = 0; d < HD; ++d)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    acc[rt][H * HD + d] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf[d]), p_lo[rt], acc[rt][H * HD + d]);
+        }
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    auto pv = [&](int it, const V8 (&p_hi)[RT], const V8 (&p_lo)[RT]) {
+        pv_half(it, I0{}, p_hi, p_lo);
+        pv_half(it, I1{}, p_hi, p_lo);
+    };
+    // Online softmax of one block's scores: running maximum and sum updated, the probabilities left in MFMA operand
+    // form, alpha = the factor the accumulators are to be multiplied by; returns whether any lane's alpha differs from 1.
+    // A lane holds keys slot0 + 8 lg + j (j = 4 tt + r) of query row lr.  Scores are kept in the log2
+    // domain (scale * log2 e folded into one factor) so that the exponentials are single v_exp_f32 instructions.
+    // INSIDE: the whole block lies in the committed prefix (no mask, and some key is visible to every row).
+    auto softmax_tile = [&](auto inside_tag, auto rt_tag, int slot0, const f32x4 (&s)[RT][2], V8 (&p_hi)[RT], V8 (&p_lo)[RT], float (&alpha)[RT]) {
+        constexpr bool INSIDE = decltype(inside_tag)::value;
+        constexpr int rt = decltype(rt_tag)::value;
+        {
             // raw scores; the factor (positive: the maximum commutes with it) goes into the exponent's fma
             float sv[8], bm = -INFINITY;
-            if (slot0 + 32 <= n_prefix) {                // whole block inside the committed prefix
+            if (INSIDE || slot0 + 32 <= n_prefix) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) { sv[j] = s_cur[rt][j >> 2][j & 3]; bm = fmaxf(bm, sv[j]); }
+                for (int j = 0; j < 8; ++j) { sv[j] = s[rt][j >> 2][j & 3]; bm = fmaxf(bm, sv[j]); }
             } else {
+                // the row's mask words come from memory here: few blocks reach into the region
+                bool valid; int m, qh;
+                row_of(rt, valid, m, qh);
+                const uint64_t m0 = valid ? mask[(size_t)m * MASK_WORDS] : 0ull, m1 = valid ? mask[(size_t)m * MASK_WORDS + 1] : 0ull;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const int slot = slot0 + (j >> 2) * 16 + 4 * lg + (j & 3);
-                    sv[j] = slot_visible(slot, n_prefix, region_len, m0[rt], m1[rt]) ? s_cur[rt][j >> 2][j & 3] : -INFINITY;
+                    const int slot = slot0 + 8 * lg + j;
+                    sv[j] = slot_visible(slot, n_prefix, region_len, m0, m1) ? s[rt][j >> 2][j & 3] : -INFINITY;
                     bm = fmaxf(bm, sv[j]);
                 }
             }
@@ -275,54 +294,120 @@ __device__ __forceinline__ void attn_mfma_body(
             const float m_new = bm > m_run[rt] + 8.f ? bm : m_run[rt];
             float psum = 0.f;
             alpha[rt] = 1.f;
-            if (m_new == -INFINITY) {
+            if (!INSIDE && m_new == -INFINITY) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) { pf[rt][j] = (T)0.f; pf_lo[rt][j] = (T)0.f; }
+                for (int j = 0; j < 8; ++j) { p_hi[rt][j] = (T)0.f; p_lo[rt][j] = (T)0.f; }
             } else {
                 alpha[rt] = __builtin_amdgcn_exp2f(m_run[rt] - m_new);   // 2^(-inf) = 0 on the first visible block
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const float pe = __builtin_amdgcn_exp2f(fmaf(sv[j], scale, -m_new));
-                    pf[rt][j] = from_f<T>(pe);
-                    if constexpr (SPLIT_P) pf_lo[rt][j] = from_f<T>(pe - to_f(pf[rt][j]));
+                    p_hi[rt][j] = from_f<T>(pe);
+                    if constexpr (SPLIT_P) p_lo[rt][j] = from_f<T>(pe - to_f(p_hi[rt][j]));
                     psum += pe;
                 }
             }
             l_run[rt] = l_run[rt] * alpha[rt] + psum;
             m_run[rt] = m_new;
-            rescale = rescale || __builtin_amdgcn_ballot_w64(alpha[rt] != 1.f) != 0;   // rare once the maximum has settled
+            return __builtin_amdgcn_ballot_w64(alpha[rt] != 1.f) != 0;   // rare once the maximum has settled
         }
-        if (rescale) {                                   // wave-uniform: a real branch, taken rarely
-            asm volatile("" ::: "memory");               // (keeps the compiler from turning it into 64 selects)
+    };
+    auto softmax = [&](auto inside_tag, int slot0, const f32x4 (&s)[RT][2], V8 (&p_hi)[RT], V8 (&p_lo)[RT], float (&alpha)[RT]) {
+        bool rescale = softmax_tile(inside_tag, I0{}, slot0, s, p_hi, p_lo, alpha);
+        if constexpr (RT > 1) rescale = rescale | softmax_tile(inside_tag, I1{}, slot0, s, p_hi, p_lo, alpha);   // (no short circuit: it would cut the block in two)
+        return rescale;
+    };
+    auto rescale_acc = [&](const float (&alpha)[RT]) {   // behind a wave-uniform branch that is rarely taken
+        asm volatile("" ::: "memory");                   // (keeps the compiler from turning it into 64 selects)
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
+        for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) acc[rt][dt] *= alpha[rt];
+            for (int dt = 0; dt < DT; ++dt) acc[rt][dt] *= alpha[rt];
+    };
+
+    // Schedule.  The loads of an iteration are issued two iterations before the first wave reads them: at the top of
+    // iteration `it` go the keys of it + 3 (stage last read by the scores of it - 1, at least one barrier ago) and the
+    // values of it + 2 (stage last read by the P V of it - 2, at least one barrier ago); at its foot every wave waits
+    // until only those are outstanding, and the barrier then publishes the keys of it + 2 and the values of it + 1.
+    // The waves of a workgroup move in step from barrier to barrier, and with two key-ways a SIMD holds one wave of
+    // each.  The two key-ways take an iteration in opposite order, so that one wave of a SIMD has vector work while the
+    // other has matrix work:
+    //   way 0: softmax of it (scores formed an iteration ago), then P V of it and scores of it + 1      vector, matrix
+    //   way 1: scores of it + 1 and P V of it (probabilities formed an iteration ago), then softmax of it + 1
+    // The accumulators of a key-way see the same operations in the same order either way.  (One key-way: the order of
+    // way 0.)  Measured against both ways in way 0's order with the next scores ahead of the softmax: 35.5 against
+    // 35.9 us at 8192 tokens - timestamps taken inside the kernel show each wave's own chain (LDS reads, a run of
+    // dependent MFMAs, the softmax) at about 3000 of an iteration's 4200 cycles whatever the other wave does.
+    // The P V product of an iteration is unconditional (a conditional one made the compiler keep two copies of the
+    // accumulators): way 1's block beyond an odd end gets zero probabilities against the valid block staged in its place.
+    typedef std::integral_constant<bool, true> Inside;
+    typedef std::integral_constant<bool, false> Anywhere;
+    const bool matrix_first = KW == 2 && kway == 1;        // wave-uniform
+    issue_k(0);
+    issue_k(1);
+    issue_v(0);
+    issue_k(2);
+    issue_v(1);
+    dma_wait<2 * UPT>();                                  // keys of iterations 0 and 1 and values of iteration 0 have landed
+    __syncthreads();
+    // softmax of block b's scores -> probabilities; accumulators rescaled
+    auto softmax_block = [&](int b, const f32x4 (&s)[RT][2], V8 (&p_hi)[RT], V8 (&p_lo)[RT]) {
+        float alpha[RT];
+        const bool rescale = (b << 5) + 32 <= n_prefix ? softmax(Inside{}, b << 5, s, p_hi, p_lo, alpha)
+                                                       : softmax(Anywhere{}, b << 5, s, p_hi, p_lo, alpha);
+        if (rescale) rescale_acc(alpha);
+    };
+    auto top = [&](int it) {
+        if (it + 3 < n_it) issue_k(it + 3);               // workgroup-uniform, like the waits at the foot
+        if (it + 2 < n_it) issue_v(it + 2);
+    };
+    auto foot = [&](int it) {
+        if (it + 3 < n_it) dma_wait<2 * UPT>();
+        else if (it + 2 < n_it) dma_wait<UPT>();
+        else dma_wait<0>();
+        __syncthreads();
+    };
+    // (one loop per order, each with the state of its own order only: scores kept from iteration to iteration in
+    // the first, probabilities in the second.  Branches on block indices are wave-uniform.)
+    if (!matrix_first) {
+        f32x4 s[RT][2];
+        scores(0, s);                                     // way 0's block of an iteration always exists
+        for (int it = 0; it < n_it; ++it) {
+            top(it);
+            const int b = b0 + it * KW + kway;
+            V8 p_hi[RT], p_lo[RT];
+            softmax_block(b, s, p_hi, p_lo);
+            __builtin_amdgcn_sched_barrier(0);            // (operand reads hoisted above the softmax would not fit the registers)
+            pv(it, p_hi, p_lo);
+            if (b + KW < b1) scores(it + 1, s);
+            foot(it);
         }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
-                acc[rt][dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf[dt]), pf[rt], acc[rt][dt]);
-        if constexpr (SPLIT_P) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+    } else {
+        V8 p_hi[RT], p_lo[RT];
+        f32x4 s[RT][2];
+        auto probabilities = [&](int b) {                 // of block b from its scores in s; zero beyond the end
+            if (b < b1) {
+                softmax_block(b, s, p_hi, p_lo);
+            } else {
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt)
-                    acc[rt][dt] = Vec8<T>::mfma(__builtin_bit_cast(V8, vf[dt]), pf_lo[rt], acc[rt][dt]);
-        }
-        }
-        store_k(std::integral_constant<int, PAR>{}, PAR);
-        load_k(std::integral_constant<int, PAR>{}, bi + 4 * KW, pgk_ahead);
-        store_v(std::integral_constant<int, PAR ^ 1>{}, PAR ^ 1);
-        load_v(std::integral_constant<int, PAR ^ 1>{}, bi + 3 * KW, pgv_ahead);
-        __syncthreads();
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) { s_cur[rt][0] = s_next[rt][0]; s_cur[rt][1] = s_next[rt][1]; }
-    };
-    for (int bi = b0; bi < b1; bi += 2 * KW) {            // unrolled by two so that ring slots and buffers are static
-        iteration(S0{}, bi);
-        if (bi + KW < b1) iteration(S1{}, bi + KW);
+                    for (int j = 0; j < 8; ++j) { p_hi[rt][j] = (T)0.f; p_lo[rt][j] = (T)0.f; }
+            }
+        };
+        if (b0 + kway < b1) scores(0, s);
+        probabilities(b0 + kway);
+        for (int it = 0; it < n_it; ++it) {
+            const int b_next = b0 + (it + 1) * KW + kway;
+            // The next block's scores lead the matrix part: by the time the P V products are issued they are complete,
+            // and the softmax behind them starts at once (and needs the matrix pipe no more while way 0 fills it).
+            top(it);
+            if (b_next < b1) scores(it + 1, s);
+            pv(it, p_hi, p_lo);
+            __builtin_amdgcn_sched_barrier(0);
+            probabilities(b_next);
+            foot(it);
+        }
     }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -332,12 +417,13 @@ __device__ __forceinline__ void attn_mfma_body(
 
     if constexpr (KW > 1) {
         // Merge the KW partial (max, sum, O) of each row tile in key-way order: ways 1.. park theirs
-        // in LDS (the staging buffers are free after the loop's final barrier), way 0 folds them in;
-        // one tile of each wave at a time, so that the records fit the staging memory.
+        // in LDS (the stages are free once every wave has read its last values), way 0 folds them in;
+        // one tile of each wave at a time.
         float *xch = reinterpret_cast<float *>(lds_all);  // per (way-1, wave): 64 lanes x (DT*4 + 2) floats
         constexpr int REC = DT * 4 + 2;
-        static_assert((size_t)(KW - 1) * 4 * 64 * REC * sizeof(float) <= sizeof(lds_all), "merge records must fit");
-        float *mine = xch + ((size_t)((kway - 1) * 4 + (wave & 3)) * 64 + lane) * REC;
+        static_assert((size_t)(KW - 1) * WPW * 64 * REC * sizeof(float) <= sizeof(lds_all), "merge records must fit");
+        float *mine = xch + ((size_t)((kway - 1) * WPW + wq) * 64 + lane) * REC;
+        __syncthreads();
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             if (rt > 0) __syncthreads();                  // way 0 has read the previous tile's records
@@ -352,7 +438,7 @@ __device__ __forceinline__ void attn_mfma_body(
             if (kway == 0) {
 #pragma unroll
                 for (int w = 1; w < KW; ++w) {
-                    const float *o = xch + ((size_t)((w - 1) * 4 + (wave & 3)) * 64 + lane) * REC;
+                    const float *o = xch + ((size_t)((w - 1) * WPW + wq) * 64 + lane) * REC;
                     const float mo = o[0], lo = o[1];
                     const float mn = fmaxf(m_run[rt], mo);
                     if (mn == -INFINITY) continue;
@@ -373,9 +459,11 @@ __device__ __forceinline__ void attn_mfma_body(
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         if (out_direct) {
-            if (valid[rt]) {
+            bool valid; int m, qh;
+            row_of(rt, valid, m, qh);
+            if (valid) {
                 const float inv = 1.0f / l_run[rt];
-                T *dst = out_direct + ((size_t)m[rt] * hq + qh[rt]) * DH + 4 * lg;
+                T *dst = out_direct + ((size_t)m * hq + qh) * DH + 4 * lg;
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -573,8 +661,9 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float *__restrict__ 
 // keys_per_split < 0: the rule above with splits of at most -keys_per_split keys (the specialists' passes carry few
 // rows, so that only a few dozen workgroups exist per split level: at long contexts they want shorter walks than the
 // target's passes; the drafter's caches are its own, so its rule need not match the target's).
+constexpr int ATTN_MAX_BPS = 64;                         // blocks per split the kernel can address (one page-table entry per lane)
 static int blocks_per_split(int n_prefix, int keys_per_split) {
-    if (keys_per_split > 0) return keys_per_split >= 32 ? keys_per_split / 32 : 1;
+    if (keys_per_split > 0) return keys_per_split >= 32 ? (keys_per_split / 32 < ATTN_MAX_BPS ? keys_per_split / 32 : ATTN_MAX_BPS) : 1;
     const int prefix_blocks = (n_prefix + 31) / 32;
     int bps = (prefix_blocks + 3) / 4;
     if (bps < 4) bps = 4;
@@ -583,42 +672,11 @@ static int blocks_per_split(int n_prefix, int keys_per_split) {
     return bps;
 }
 
-template <typename T>
-static void launch_attention_t(const ModelDims &md, const void *q, int rows, const RowMeta &rm, int n_prefix,
-                               int region_len, const KVCache &kv, int keys_per_split, const AttnScratch &sc,
-                               void *out, hipStream_t st) {
-    const int G = md.hq / md.hkv;
-    const int tiles = (rows * G + 15) / 16, rho_pad = tiles * 16;
-    const int n_blocks = (n_prefix + region_len + 31) / 32;
-    int bps = blocks_per_split(n_prefix, keys_per_split);
-    while ((n_blocks + bps - 1) / bps > ATTN_MAX_SPLITS) bps *= 2;     // only with a tiny split override on a very long context
-    const int n_splits = (n_blocks + bps - 1) / bps;
-    const float scale = 1.4426950408889634f / sqrtf((float)md.dh);     // log2(e) / sqrt(dh): scores in the log2 domain
-    T *direct = n_splits == 1 ? static_cast<T *>(out) : nullptr;
-    // Key-ways follow the split size (so, like it, the committed prefix only); the number of row tiles per
-    // wave may follow the row count: it does not change any row's arithmetic.
-    const int kw = bps >= 4 ? 2 : 1;
-    const int rt = tiles > 4 && bps >= 8 ? 2 : 1;         // pays only where the walk is long
-    const int n_row_groups = (tiles + 4 * rt - 1) / (4 * rt), n_pairs = md.hkv * n_splits;
-    dim3 grid(8 * n_row_groups * ((n_pairs + 7) / 8));
-#define POSS_ATTN(DH, KW, RT)                                                                                    \
-    hipLaunchKernelGGL((attn_mfma_kernel<T, DH, KW, RT>), grid, dim3(256 * KW), 0, st, static_cast<const T *>(q),   \
-                       rows, md.hq, md.hkv, rm.mask, n_prefix, region_len, kv, bps, n_splits, n_row_groups, scale,  \
-                       sc.o, sc.ml, rho_pad, direct)
-#define POSS_ATTN_DH(DH)                                                                                         \
-    do {                                                                                                         \
-        if (kw == 2) { if (rt == 2) POSS_ATTN(DH, 2, 2); else POSS_ATTN(DH, 2, 1); }                             \
-        else         { if (rt == 2) POSS_ATTN(DH, 1, 2); else POSS_ATTN(DH, 1, 1); }                             \
-    } while (0)
-    if (md.dh == 128) POSS_ATTN_DH(128); else POSS_ATTN_DH(64);
-#undef POSS_ATTN_DH
-#undef POSS_ATTN
-    if (n_splits > 1)
-        hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(rows, md.hq), dim3(md.dh < 64 ? 64 : md.dh), 0, st, sc.o, sc.ml,
-                           n_splits, md.hq, md.hkv, md.dh, rho_pad, static_cast<T *>(out));
-}
-
-// Launch shape of one sequence's attention: the split rule, key-ways and row tiles per wave (see above).
+// Launch shape of one sequence's attention: the split rule, key-ways and row tiles per wave.
+// Key-ways follow the split size (so, like it, the committed prefix only); the number of row tiles per wave may follow
+// the row count: it does not change any row's arithmetic.  Eight tiles per workgroup where the walk is long (every key /
+// value block staged once for eight tiles), as 4 waves x 2 tiles per key-way; 8 waves x 1 tile (sixteen waves per
+// workgroup, four per SIMD) measured the same.
 struct AttnShape { int bps, n_splits, kw, rt, n_row_groups, rho_pad, n_wgs; };
 static AttnShape attention_shape(const ModelDims &md, int rows, int n_prefix, int region_len, int keys_per_split) {
     AttnShape a;
@@ -627,13 +685,37 @@ static AttnShape attention_shape(const ModelDims &md, int rows, int n_prefix, in
     a.rho_pad = tiles * 16;
     const int n_blocks = (n_prefix + region_len + 31) / 32;
     a.bps = blocks_per_split(n_prefix, keys_per_split);
-    while ((n_blocks + a.bps - 1) / a.bps > ATTN_MAX_SPLITS) a.bps *= 2;
+    while ((n_blocks + a.bps - 1) / a.bps > ATTN_MAX_SPLITS) a.bps *= 2;     // only with a tiny split override on a very long context
     a.n_splits = (n_blocks + a.bps - 1) / a.bps;
     a.kw = a.bps >= 4 ? 2 : 1;
-    a.rt = tiles > 4 && a.bps >= 8 ? 2 : 1;
+    a.rt = tiles > 4 && a.bps >= 8 ? 2 : 1;               // pays only where the walk is long
     a.n_row_groups = (tiles + 4 * a.rt - 1) / (4 * a.rt);
     a.n_wgs = 8 * a.n_row_groups * ((md.hkv * a.n_splits + 7) / 8);
     return a;
+}
+
+template <typename T>
+static void launch_attention_t(const ModelDims &md, const void *q, int rows, const RowMeta &rm, int n_prefix,
+                               int region_len, const KVCache &kv, int keys_per_split, const AttnScratch &sc,
+                               void *out, hipStream_t st) {
+    const AttnShape a = attention_shape(md, rows, n_prefix, region_len, keys_per_split);
+    const float scale = 1.4426950408889634f / sqrtf((float)md.dh);     // log2(e) / sqrt(dh): scores in the log2 domain
+    T *direct = a.n_splits == 1 ? static_cast<T *>(out) : nullptr;
+#define POSS_ATTN(DH, KW, RT)                                                                                     \
+    hipLaunchKernelGGL((attn_mfma_kernel<T, DH, KW, RT>), dim3(a.n_wgs), dim3(256 * KW), 0, st,                  \
+                       static_cast<const T *>(q), rows, md.hq, md.hkv, rm.mask, n_prefix, region_len, kv, a.bps,  \
+                       a.n_splits, a.n_row_groups, scale, sc.o, sc.ml, a.rho_pad, direct)
+#define POSS_ATTN_DH(DH)                                                                                         \
+    do {                                                                                                         \
+        if (a.kw == 2) { if (a.rt == 2) POSS_ATTN(DH, 2, 2); else POSS_ATTN(DH, 2, 1); }                         \
+        else           { if (a.rt == 2) POSS_ATTN(DH, 1, 2); else POSS_ATTN(DH, 1, 1); }                         \
+    } while (0)
+    if (md.dh == 128) POSS_ATTN_DH(128); else POSS_ATTN_DH(64);
+#undef POSS_ATTN_DH
+#undef POSS_ATTN
+    if (a.n_splits > 1)
+        hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(rows, md.hq), dim3(md.dh < 64 ? 64 : md.dh), 0, st, sc.o, sc.ml,
+                           a.n_splits, md.hq, md.hkv, md.dh, a.rho_pad, static_cast<T *>(out));
 }
 
 template <typename T>
@@ -664,17 +746,17 @@ static void launch_attention_batch_t(const ModelDims &md, const void *q, const R
     // one launch per (key-ways, row tiles) instantiation that occurs: as a rule one
     for (int kw = 1; kw <= 2; ++kw)
         for (int rt = 1; rt <= 2; ++rt) {
-            AttnSeqs grp;
-            grp.n = 0;
-            int wgs = 0;
-            for (int i = 0; i < n; ++i)
-                if (shp[i].kw == kw && shp[i].rt == rt) {
-                    grp.s[grp.n] = all[i];
-                    grp.s[grp.n].wg0 = wgs;
-                    wgs += shp[i].n_wgs;
-                    ++grp.n;
-                }
-            if (grp.n == 0) continue;
+                AttnSeqs grp;
+                grp.n = 0;
+                int wgs = 0;
+                for (int i = 0; i < n; ++i)
+                    if (shp[i].kw == kw && shp[i].rt == rt) {
+                        grp.s[grp.n] = all[i];
+                        grp.s[grp.n].wg0 = wgs;
+                        wgs += shp[i].n_wgs;
+                        ++grp.n;
+                    }
+                if (grp.n == 0) continue;
 #define POSS_ATTNB(DH, KW, RT)                                                                                   \
     hipLaunchKernelGGL((attn_mfma_batch_kernel<T, DH, KW, RT>), dim3(wgs), dim3(256 * KW), 0, st, grp, md.hq, md.hkv, scale)
 #define POSS_ATTNB_DH(DH)                                                                                        \
@@ -682,10 +764,10 @@ static void launch_attention_batch_t(const ModelDims &md, const void *q, const R
         if (kw == 2) { if (rt == 2) POSS_ATTNB(DH, 2, 2); else POSS_ATTNB(DH, 2, 1); }                           \
         else         { if (rt == 2) POSS_ATTNB(DH, 1, 2); else POSS_ATTNB(DH, 1, 1); }                           \
     } while (0)
-            if (md.dh == 128) POSS_ATTNB_DH(128); else POSS_ATTNB_DH(64);
+                if (md.dh == 128) POSS_ATTNB_DH(128); else POSS_ATTNB_DH(64);
 #undef POSS_ATTNB_DH
 #undef POSS_ATTNB
-        }
+            }
     if (any_split) {
         AttnSeqs grp;
         grp.n = n;

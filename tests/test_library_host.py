@@ -43,9 +43,11 @@ def test_workspace_bytes_and_config_validation():
     bad = [dict(top_k=0), dict(top_k=17), dict(depth=0), dict(depth=17), dict(total_tokens=0),
            dict(total_tokens=128), dict(total_tokens=85), dict(kv_page_tokens=48), dict(max_seq=100),
            dict(n_kv_heads=3), dict(dtype=3), dict(n_specialists=0), dict(positions_per_specialist=0),
-           dict(top_k=4096), dict(dtype=1, head_dim=32), dict(dtype=1, d_model=260), dict(kv_page_order=2)]
+           dict(top_k=4096), dict(dtype=1, head_dim=32), dict(dtype=1, d_model=260), dict(kv_page_order=2),
+           dict(dtype=1, max_seq=500096)]          # beyond 256 attention splits of 64 blocks of 32 keys
     for over in bad:
         assert lib.poss_workspace_bytes(ctypes.byref(P.make_config(base.with_(**over)))) == 0, over
+    assert lib.poss_workspace_bytes(ctypes.byref(P.make_config(base.with_(dtype=1, max_seq=499968)))) > 0
     assert lib.poss_workspace_bytes(None) == 0
     # several sequences per round: up to eight (passes whose stacked rows exceed a launch run in groups),
     # every sequence with caches and tree state of its own
