@@ -64,19 +64,6 @@ __device__ __forceinline__ int key_swizzle(int kappa) {
 // Values: row rho of V^T (a dh index; 4 chunks of 8 keys per row, four rows per 256 bytes).
 __device__ __forceinline__ int value_swizzle(int rho) { return (rho >> 1) & 3; }
 
-// One 16-byte LDS-direct load per lane: lane l's 16 bytes from `g` land at LDS byte address lds_base + 16 l
-// (lds_base wave-uniform).  Written as assembly because the compiler, which cannot tell which LDS reads a
-// load it knows of may alias, would wait for ALL such loads before every LDS read; counted waits
-// (dma_wait) are placed by hand instead.  M0 is set in the same statement and nothing else here uses it.
-__device__ __forceinline__ void lds_dma16(unsigned lds_base, const void *g) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(g) : "memory");
-}
-// Wait until at most N of this wave's vector-memory loads are outstanding (they complete in order).
-template <int N>
-__device__ __forceinline__ void dma_wait() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 // One workgroup = 4 waves x RT tiles of 16 query rows of ONE KV head (times KW key-ways), over the key
 // blocks of one split.  RT = 2 halves the LDS operand reads per MFMA (every key / value fragment
 // feeds two row tiles): long contexts are bound by exactly those reads.

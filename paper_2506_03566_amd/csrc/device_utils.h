@@ -30,6 +30,19 @@ __device__ __forceinline__ float block_sum(float v, float *red /* >= 17 floats o
     return s;
 }
 
+// One 16-byte LDS-direct load per lane: lane l's 16 bytes from `g` land at LDS byte address lds_base + 16 l
+// (lds_base wave-uniform).  Written as assembly because the compiler, which cannot tell which LDS reads a
+// load it knows of may alias, would wait for ALL such loads before every LDS read; counted waits
+// (dma_wait) are placed by hand instead.  M0 is set in the same statement and nothing else in these kernels uses it.
+__device__ __forceinline__ void lds_dma16(unsigned lds_base, const void *g) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(g) : "memory");
+}
+// Wait until at most N of this wave's vector-memory loads are outstanding (they complete in order).
+template <int N>
+__device__ __forceinline__ void dma_wait() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // A token id that came out of arithmetic indexes the embedding table only through this: an argmax over a row of
 // logits that are all NaN finds no entry that compares and leaves the id of "no entry" (0x7fffffff) - a bad number
 // must not become a bad address.  Such a row reads token 0.

@@ -428,68 +428,52 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// The same product for 129..256 rows (several sequences verified in one weight stream, prefill): at that height the
-// kernel is bound by the matrix pipe, not by the weight stream, and one wave per SIMD cannot keep that pipe busy (a
-// single wave reaches about 60 % of the MFMA rate).  Eight waves per workgroup, two per SIMD: wave (wm, wn) owns the
-// rows [128 wm, 128 wm + 128) of the 32 columns wn of the workgroup's 128-column tile; the two waves of a column group
-// read the same weights (the second read is served by the caches), the activations are staged as above in chunks of four
-// k-steps (two chunks of 256 rows fill the LDS).  The chunk's A fragments pass through a window of AW registers, each
-// refilled as soon as its two MFMAs are issued, AW fragments ahead of its use; that order is given to the scheduler
-// as it stands (left alone it moves every LDS read next to its use and waits for it there).
+// The same product for 129..256 rows (several sequences verified in one weight stream, prefill).  At that height a
+// workgroup's 256 x 128 tile needs 16 KB of activations and 8 KB of weights per k-step and every workgroup re-reads the
+// whole activation matrix.  Counters and timestamps of earlier versions of this kernel: with operands fetched by the
+// waves that multiply (weights into registers, activations through registers into LDS) the matrix pipe was busy 29 % of
+// the time, the waves waiting for loads 53 %, and 963 MB went through the L1s for 235 MB of weights, because the two
+// waves that share a column group each fetched its weights; with both operands staged in LDS by LDS-direct loads, each
+// fetched once, a wave still sat 450 - 1300 cycles of a 2600-cycle stage in the ISSUE of its six loads (the CU's vector
+// memory pipe takes in about 64 bytes a cycle, and a wave issues in order: while it waits to issue a load it issues no
+// MFMA), wherever in the stage the loads were put.  So the work is split by wave:
+//   eight consumer waves, two per SIMD: wave (wm, wn) owns the rows [128 wm, 128 wm + 128) of the 32 columns wn of the
+//       tile, reads its operand fragments from LDS and issues MFMAs, nothing else;
+//   four producer waves, one per SIMD, issue the loads, three stages of two k-steps (48 KB each) deep, and wait for them.
+// Staging, by 16-byte LDS-direct loads (no staging registers, no masks):
+//   activations: a stage holds 256 rows x 64 k, a row's 128 bytes (both k-steps) contiguous, its eight 16-byte units
+//       xor-swizzled by a function of the row - eight consecutive lanes fetch one row's 128 bytes, a whole line of the
+//       L2 (four lanes and 64 bytes, one k-step, made twice the requests), and an operand read (lane % 16 the row,
+//       lane / 16 the k-group) runs at the full LDS rate;
+//   weights: the packed layout is already the B-operand image, 1 KB per (k-step, column tile), copied as it is.
+// Rows >= M and k >= K are not zeroed: such a lane fetches a valid element of the matrix instead (row M - 1, k = 0);
+// the rows are never read back and the packed weights are zero beyond K.
 // Splits own whole groups of 8 k-steps as in the stream kernel and a wave adds its k-steps in ascending order, so a
 // row's sums are bit for bit those of the stream kernel.
-constexpr int TALL_MT = 16, TALL_KCL = 4, TALL_PF = 4, TALL_AW = 8;
+constexpr int TALL_MT = 16, TALL_KCL = 2, TALL_NST = 3, TALL_THREADS = 1024;
+
+// position of 16-byte unit u of row r (of a 16-row tile) inside the row's 128 bytes: u ^ tall_x_swizzle(r)
+__device__ __forceinline__ int tall_x_swizzle(int r) { return (((r >> 1) & 1) << 2) | ((r >> 1) & 3); }
 
 template <typename T, bool FUSE_SILU, bool HEAD>
-__global__ __launch_bounds__(512) void gemm_tall_kernel(
+__global__ __launch_bounds__(TALL_THREADS) void gemm_tall_kernel(
     const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
     int M, int K, int Npad, int ksteps_total, T *__restrict__ act, int F, HeadEpi he) {
-    constexpr int MT = TALL_MT, KCL = TALL_KCL, PF = TALL_PF, AW = TALL_AW, MTW = MT / 2;
-    static_assert(KCL % PF == 0 && KCS % KCL == 0, "ring index must be static");
-    constexpr int XUNITS = KCL * MT * 64, XPT = XUNITS / 512, RJ = MT / 8;
-    __shared__ u32x4 xs[2][XUNITS];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, wn = wave & 3, wm = wave >> 2;
+    typedef __attribute__((address_space(3))) void *LdsPtr;
+    constexpr int MT = TALL_MT, KCL = TALL_KCL, NST = TALL_NST, MTW = MT / 2;
+    static_assert(KCS % KCL == 0, "a split's k-steps are whole stages");
+    static_assert(KCL == 2 && MTW == 8 && GEMM_NT == 2 && MT == 16, "the schedules below are written for these");
+    constexpr int XBLKS = KCL * MT, WBLKS = KCL * 4 * GEMM_NT;           // 1 KB blocks of a stage: activations, weights
+    constexpr int STAGE_UNITS = (XBLKS + WBLKS) * 64;
+    constexpr int LPS = (XBLKS + WBLKS) / 8;                             // loads of a producer wave per stage
+    __shared__ __attribute__((aligned(1024))) u32x4 xs[NST * STAGE_UNITS];
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const bool producer = wave >= 8;                      // wave-uniform
+    const int wn = wave & 3, wm = (wave >> 2) & 1;
     const int n_chunks_total = ksteps_total / KCS;
-    const int chunk0 = ((int)blockIdx.y * n_chunks_total / (int)gridDim.y) * (KCS / KCL);          // in staged chunks
+    const int chunk0 = ((int)blockIdx.y * n_chunks_total / (int)gridDim.y) * (KCS / KCL);          // in stages
     const int chunk1 = (((int)blockIdx.y + 1) * n_chunks_total / (int)gridDim.y) * (KCS / KCL);
     const int ngroup = blockIdx.x * 4 + wn;
-    const u32x4 *wp = Wp + ((size_t)ngroup * ksteps_total + (size_t)chunk0 * KCL) * (GEMM_NT * 64) + lane;
-
-    // Staging: wave w takes the row tiles w and w + 8 of every k-step, so that a thread's units are one lane-dependent
-    // base plus compile-time steps; unit layout and swizzle as in the stream kernel.  Loads are never predicated:
-    // out-of-range units read a clamped, valid address and are zeroed by a mask (given a condition the compiler moves
-    // the load itself behind a branch).
-    const T *x_row[RJ];
-    uint32_t x_rmask[RJ];
-    const int x_kl = (lane & 3) * 8;
-    const int x_dst0 = wave * 64 + ((lane & 3) << 4) + ((lane >> 2) ^ xs_swizzle(lane & 3));
-#pragma unroll
-    for (int j = 0; j < RJ; ++j) {
-        const int m = (j * 8 + wave) * 16 + (lane >> 2);
-        x_rmask[j] = 0u - (uint32_t)(m < M);
-        x_row[j] = X + (size_t)(m < M ? m : M - 1) * ldx + x_kl;
-    }
-    auto load_x = [&](int chunk, u32x4 (&xr)[XPT]) {
-#pragma unroll
-        for (int ks = 0; ks < KCL; ++ks) {
-            const int k = (chunk * KCL + ks) * GEMM_KSTEP;
-            const int koff = k + x_kl < K ? k : K - 8 - x_kl;
-#pragma unroll
-            for (int j = 0; j < RJ; ++j) xr[ks * RJ + j] = *reinterpret_cast<const u32x4 *>(x_row[j] + koff);
-        }
-    };
-    auto store_x = [&](int chunk, int b, const u32x4 (&xr)[XPT]) {
-#pragma unroll
-        for (int ks = 0; ks < KCL; ++ks) {
-            const uint32_t kmask = 0u - (uint32_t)((chunk * KCL + ks) * GEMM_KSTEP + x_kl < K);
-#pragma unroll
-            for (int j = 0; j < RJ; ++j) {
-                const uint32_t mk = kmask & x_rmask[j];
-                const u32x4 v = xr[ks * RJ + j];
-                xs[b][x_dst0 + (ks * MT + 8 * j) * 64] = u32x4{v[0] & mk, v[1] & mk, v[2] & mk, v[3] & mk};
-            }
-        }
-    };
 
     f32x4 acc[MTW][GEMM_NT];
 #pragma unroll
@@ -497,84 +481,113 @@ __global__ __launch_bounds__(512) void gemm_tall_kernel(
 #pragma unroll
         for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 xr[XPT];
-    load_x(chunk0, xr);
-    u32x4 wr[PF][GEMM_NT];
+    if (producer) {
+        // Producer p = wave - 8 brings the blocks p, p + 8, p + 16, p + 24 of the stage's activations (block b = rows
+        // 8 b .. 8 b + 7, eight lanes per row: the unit that belongs at the lane's position under the swizzle) and the two
+        // column tiles of (k-step p / 4, column group p % 4).
+        const int pw = wave - 8;
+        const int f_row = lane >> 3;
+        const T *x_row[4];
+        int f_k[4];
 #pragma unroll
-    for (int p = 0; p < PF; ++p) {
+        for (int j = 0; j < 4; ++j) {
+            const int m = (pw + 8 * j) * 8 + f_row;
+            x_row[j] = X + (size_t)(m < M ? m : M - 1) * ldx;
+            f_k[j] = ((lane & 7) ^ tall_x_swizzle(m & 15)) * 8;
+        }
+        const u32x4 *w_src = Wp + ((size_t)(blockIdx.x * 4 + (pw & 3)) * ksteps_total + (pw >> 2)) * (GEMM_NT * 64) + lane;
+        const unsigned lds0 = (unsigned)(uintptr_t)(LdsPtr)&xs[0];
+        auto fetch = [&](int chunk, int st) {             // stage st <- k-steps chunk KCL .. + KCL - 1
+            const unsigned base = lds0 + (unsigned)(st * STAGE_UNITS * 16);
 #pragma unroll
-        for (int nt = 0; nt < GEMM_NT; ++nt) wr[p][nt] = wp[nt * 64];
-        wp += GEMM_NT * 64;
-    }
-    store_x(chunk0, 0, xr);
-    __syncthreads();
-
-    int buf = 0;
-    const int lane_sw = wm * (MTW * 64) + (lane & 48) + ((lane & 15) ^ xs_swizzle(lane >> 4));   // first fragment of this wave's rows
-    auto chunk_body = [&](auto more_tag, int chunk) {
-        constexpr bool MORE = decltype(more_tag)::value;
-        constexpr int NF = KCL * MTW;                     // fragments of the chunk for this wave: (k-step i, row tile mt)
-        if constexpr (MORE) load_x(chunk + 1, xr);
-        __builtin_amdgcn_sched_barrier(0);               // keep these loads older than the weight loads below
-        u32x4 a[AW], w[GEMM_NT];
-#pragma unroll
-        for (int f = 0; f < AW; ++f) a[f] = xs[buf][((f / MTW) * MT + f % MTW) * 64 + lane_sw];
-#pragma unroll
-        for (int f = 0; f < NF; ++f) {
-            const int i = f / MTW, mt = f % MTW;
-            if (mt == 0) {
-#pragma unroll
-                for (int nt = 0; nt < GEMM_NT; ++nt) w[nt] = wr[i % PF][nt];
-                if (MORE || i + PF < KCL) {
-#pragma unroll
-                    for (int nt = 0; nt < GEMM_NT; ++nt) wr[i % PF][nt] = wp[nt * 64];
-                    wp += GEMM_NT * 64;
-                }
+            for (int j = 0; j < 4; ++j) {
+                const int k = chunk * (KCL * GEMM_KSTEP) + f_k[j];
+                lds_dma16(base + (unsigned)((pw + 8 * j) * 1024), x_row[j] + (k < K ? k : 0));
             }
 #pragma unroll
-            for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[f % AW], w[nt], acc[mt][nt]);
-            if (f + AW < NF) a[f % AW] = xs[buf][(((f + AW) / MTW) * MT + (f + AW) % MTW) * 64 + lane_sw];
-        }
-        __builtin_amdgcn_sched_group_barrier(0x100, AW, 0);
-#pragma unroll
-        for (int f = 0; f < NF; ++f) {
-            const int i = f / MTW, mt = f % MTW;
-            if (mt == 0 && (MORE || i + PF < KCL)) __builtin_amdgcn_sched_group_barrier(0x020, GEMM_NT, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, GEMM_NT, 0);
-            if (f + AW < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (MORE) {
-            store_x(chunk + 1, buf ^ 1, xr);
+            for (int nt = 0; nt < GEMM_NT; ++nt)
+                lds_dma16(base + (unsigned)((XBLKS + ((pw >> 2) * 4 + (pw & 3)) * GEMM_NT + nt) * 1024),
+                          w_src + (size_t)chunk * KCL * (GEMM_NT * 64) + nt * 64);
+        };
+        static_assert(LPS == 4 + GEMM_NT && XBLKS == 32, "the fetch above brings exactly one stage");
+        fetch(chunk0, 0);
+        if (chunk0 + 1 < chunk1) { fetch(chunk0 + 1, 1); dma_wait<LPS>(); } else dma_wait<0>();
+        __syncthreads();
+        int st = 0;
+        for (int chunk = chunk0; chunk < chunk1; ++chunk) {
+            // stage (st + 2) % 3 was read last in the iteration before this one: every wave is past that barrier;
+            // the next stage has landed once only the loads just issued are outstanding
+            if (chunk + 2 < chunk1) { fetch(chunk + 2, st == 0 ? 2 : st - 1); dma_wait<LPS>(); } else dma_wait<0>();
             __syncthreads();
-            buf ^= 1;
+            st = st == NST - 1 ? 0 : st + 1;
         }
-    };
-    for (int chunk = chunk0; chunk + 1 < chunk1; ++chunk) chunk_body(std::true_type{}, chunk);
-    chunk_body(std::false_type{}, chunk1 - 1);
+    } else {
+        // operand reads of this wave inside a stage, in 16-byte units
+        const int a_row = (wm * MTW) * 128 + (lane & 15) * 8, a_swz = tall_x_swizzle(lane & 15), lg = lane >> 4;
+        const int b_unit = XBLKS * 64 + wn * GEMM_NT * 64 + lane;
+        __syncthreads();
+        int st = 0;
+        for (int chunk = chunk0; chunk < chunk1; ++chunk) {
+            // The fragments of the stage's first k-step are asked for at once - the only LDS wait of the stage; those of the
+            // second follow one by one behind the first k-step's MFMAs.  (The order is given to the scheduler as it stands:
+            // left alone it puts every read next to its use and waits for it there.)
+            const u32x4 *xa = &xs[st * STAGE_UNITS + a_row], *wb = &xs[st * STAGE_UNITS + b_unit];
+            u32x4 w[KCL][GEMM_NT], a[KCL][MTW];
+#pragma unroll
+            for (int ks = 0; ks < KCL; ++ks) {
+#pragma unroll
+                for (int nt = 0; nt < GEMM_NT; ++nt) w[ks][nt] = wb[(ks * 4 * GEMM_NT + nt) * 64];
+#pragma unroll
+                for (int mt = 0; mt < MTW; ++mt) a[ks][mt] = xa[mt * 128 + ((ks * 4 + lg) ^ a_swz)];
+            }
+#pragma unroll
+            for (int ks = 0; ks < KCL; ++ks)
+#pragma unroll
+                for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[ks][mt], w[ks][nt], acc[mt][nt]);
+            __builtin_amdgcn_sched_group_barrier(0x100, GEMM_NT + MTW, 0);
+#pragma unroll
+            for (int i = 0; i < 6; ++i) {                 // 16 MFMAs of the first k-step spread over the 10 reads of the second
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, MTW * GEMM_NT, 0);
+            __syncthreads();
+            st = st == NST - 1 ? 0 : st + 1;
+        }
+    }
 
-    // D tile: lane -> column n = lane % 16, register r -> row m = 4 * (lane / 16) + r of row tile wm * MTW + mt
+    // D tile: lane -> column n = lane % 16, register r -> row m = 4 * (lane / 16) + r of row tile wm * MTW + mt.
+    // (The producer waves take part in the barriers below and in nothing else.)
     const int row0 = wm * (MTW * 16) + 4 * (lane >> 4);
     if constexpr (FUSE_SILU) {
         constexpr int TW = 4 * 16, TWP = TW + 8;
         static_assert((size_t)MT * 16 * TWP * sizeof(T) <= sizeof(xs), "the tile fits the staging memory");
-        T *tile = reinterpret_cast<T *>(&xs[0][0]);
+        T *tile = reinterpret_cast<T *>(&xs[0]);
         __syncthreads();                                 // every wave has read its last operand fragments
+        if (!producer) {
 #pragma unroll
-        for (int mt = 0; mt < MTW; ++mt)
+            for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float g = acc[mt][0][r], up = acc[mt][1][r];
-                tile[(row0 + mt * 16 + r) * TWP + wn * 16 + (lane & 15)] = from_f<T>(g / (1.0f + expf(-g)) * up);
-            }
+                for (int r = 0; r < 4; ++r) {
+                    const float g = acc[mt][0][r], up = acc[mt][1][r];
+                    tile[(row0 + mt * 16 + r) * TWP + wn * 16 + (lane & 15)] = from_f<T>(g / (1.0f + expf(-g)) * up);
+                }
+        }
         __syncthreads();
-        silu_tile_store<T, MT * 16, TW, 512>(tile, act, M, F, blockIdx.x * TW, tid);
+        if (!producer) silu_tile_store<T, MT * 16, TW, 512>(tile, act, M, F, blockIdx.x * TW, tid);
         return;
     }
     if constexpr (HEAD) {
         constexpr int TW = 4 * GEMM_NT * 16;
         static_assert((size_t)MT * 16 * TW * sizeof(float) <= sizeof(xs), "the tile fits the staging memory");
-        if (he.write_logits) {
+        if (he.write_logits && !producer) {
             const int nl = ngroup * (GEMM_NT * 16) + (lane & 15);
 #pragma unroll
             for (int mt = 0; mt < MTW; ++mt)
@@ -584,19 +597,22 @@ __global__ __launch_bounds__(512) void gemm_tall_kernel(
                     for (int r = 0; r < 4; ++r)
                         part[(size_t)(row0 + mt * 16 + r) * Npad + nl + nt * 16] = acc[mt][nt][r];
         }
-        float *tile = reinterpret_cast<float *>(&xs[0][0]);
+        float *tile = reinterpret_cast<float *>(&xs[0]);
         __syncthreads();
+        if (!producer) {
 #pragma unroll
-        for (int mt = 0; mt < MTW; ++mt)
+            for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
-            for (int nt = 0; nt < GEMM_NT; ++nt)
+                for (int nt = 0; nt < GEMM_NT; ++nt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    tile[(row0 + mt * 16 + r) * TW + wn * (GEMM_NT * 16) + nt * 16 + (lane & 15)] = acc[mt][nt][r];
+                    for (int r = 0; r < 4; ++r)
+                        tile[(row0 + mt * 16 + r) * TW + wn * (GEMM_NT * 16) + nt * 16 + (lane & 15)] = acc[mt][nt][r];
+        }
         __syncthreads();
-        head_tile_reduce<TW, 16>(tile, M, he, blockIdx.x, gridDim.x, tid);
+        if (!producer) head_tile_reduce<TW, 16>(tile, M, he, blockIdx.x, gridDim.x, tid);
         return;
     }
+    if (producer) return;
     float *out = part + (size_t)blockIdx.y * (MT * 16) * Npad;
     const int n0 = ngroup * (GEMM_NT * 16) + (lane & 15);
 #pragma unroll
@@ -941,7 +957,7 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     if (g.Mpad > 128) {                                  // the tall kernel: eight waves, one 128-column tile
         HeadEpi he{};
         if (head) he = HeadEpi{epi.head_mode, epi.head_k, g.N, epi.write_logits, epi.seg_out, epi.pv, epi.pi};
-        dim3 grid(g.Npad / GEMM_BLOCK_N, g.S), block(512);
+        dim3 grid(g.Npad / GEMM_BLOCK_N, g.S), block(TALL_THREADS);
         const int ksteps = g.Kpad / GEMM_KSTEP;
         const u32x4 *w = static_cast<const u32x4 *>(Wp);
         const T *x = static_cast<const T *>(X);
