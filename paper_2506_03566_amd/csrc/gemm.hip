@@ -439,7 +439,8 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
 // MFMA), wherever in the stage the loads were put.  So the work is split by wave:
 //   eight consumer waves, two per SIMD: wave (wm, wn) owns the rows [128 wm, 128 wm + 128) of the 32 columns wn of the
 //       tile, reads its operand fragments from LDS and issues MFMAs, nothing else;
-//   four producer waves, one per SIMD, issue the loads, three stages of two k-steps (48 KB each) deep, and wait for them.
+//   eight producer waves, two per SIMD, issue the loads, three stages of two k-steps (48 KB each) deep, and wait for
+//       them (four of them were slower: a wave issues an LDS-direct load only every 100 - 250 cycles).
 // Staging, by 16-byte LDS-direct loads (no staging registers, no masks):
 //   activations: a stage holds 256 rows x 64 k, a row's 128 bytes (both k-steps) contiguous, its eight 16-byte units
 //       xor-swizzled by a function of the row - eight consecutive lanes fetch one row's 128 bytes, a whole line of the
