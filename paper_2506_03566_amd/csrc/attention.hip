@@ -665,7 +665,8 @@ static int blocks_per_split(int n_prefix, int keys_per_split) {
 // value block staged once for eight tiles), as 4 waves x 2 tiles per key-way; 8 waves x 1 tile (sixteen waves per
 // workgroup, four per SIMD) measured the same.
 struct AttnShape { int bps, n_splits, kw, rt, n_row_groups, rho_pad, n_wgs; };
-static AttnShape attention_shape(const ModelDims &md, int rows, int n_prefix, int region_len, int keys_per_split) {
+static AttnShape attention_shape(const ModelDims &md, int rows, int n_prefix, int region_len, int keys_per_split,
+                                 bool crowded = false) {
     AttnShape a;
     const int G = md.hq / md.hkv;
     const int tiles = (rows * G + 15) / 16;
@@ -675,7 +676,9 @@ static AttnShape attention_shape(const ModelDims &md, int rows, int n_prefix, in
     while ((n_blocks + a.bps - 1) / a.bps > ATTN_MAX_SPLITS) a.bps *= 2;     // only with a tiny split override on a very long context
     a.n_splits = (n_blocks + a.bps - 1) / a.bps;
     a.kw = a.bps >= 4 ? 2 : 1;
-    a.rt = tiles > 4 && a.bps >= 8 ? 2 : 1;               // pays only where the walk is long
+    // pays where the walk is long - or where the launch would otherwise hold more workgroups than the chip has CUs
+    // (a workgroup fills a CU's LDS: the surplus would run as a second round)
+    a.rt = tiles > 4 && (a.bps >= 8 || crowded) ? 2 : 1;
     a.n_row_groups = (tiles + 4 * a.rt - 1) / (4 * a.rt);
     a.n_wgs = 8 * a.n_row_groups * ((md.hkv * a.n_splits + 7) / 8);
     return a;
@@ -714,9 +717,13 @@ static void launch_attention_batch_t(const ModelDims &md, const void *q, const R
     AttnSeq all[ATTN_MAX_SEQ];
     size_t o_off = 0, ml_off = 0;
     bool any_split = false;
+    int wgs_all = 0;
+    for (int i = 0; i < n; ++i)
+        wgs_all += attention_shape(md, segs[i].rows, segs[i].n_prefix, segs[i].region_len, keys_per_split).n_wgs;
+    const bool crowded = wgs_all > 256;
     for (int i = 0; i < n; ++i) {
         const AttnSeg &g = segs[i];
-        shp[i] = attention_shape(md, g.rows, g.n_prefix, g.region_len, keys_per_split);
+        shp[i] = attention_shape(md, g.rows, g.n_prefix, g.region_len, keys_per_split, crowded);
         AttnSeq &a = all[i];
         a.q = static_cast<const T *>(q) + g.row0 * qd;
         a.mask = rm.mask + (size_t)g.row0 * MASK_WORDS;
