@@ -451,20 +451,21 @@ __global__ __launch_bounds__(WPB * 64) void gemm_stream_kernel(
 // the rows are never read back and the packed weights are zero beyond K.
 // Splits own whole groups of 8 k-steps as in the stream kernel and a wave adds its k-steps in ascending order, so a
 // row's sums are bit for bit those of the stream kernel.
-constexpr int TALL_MT = 16, TALL_KCL = 2, TALL_NST = 3, TALL_THREADS = 1024;
+constexpr int TALL_KCL = 2, TALL_NST = 3, TALL_THREADS = 1024;   // (row tiles per workgroup, MT: 16, or 12 for up to 192 rows)
 
 // position of 16-byte unit u of row r (of a 16-row tile) inside the row's 128 bytes: u ^ tall_x_swizzle(r)
 __device__ __forceinline__ int tall_x_swizzle(int r) { return (((r >> 1) & 1) << 2) | ((r >> 1) & 3); }
 
-template <typename T, bool FUSE_SILU, bool HEAD>
+template <typename T, int MT, bool FUSE_SILU, bool HEAD>
 __global__ __launch_bounds__(TALL_THREADS) void gemm_tall_kernel(
     const u32x4 *__restrict__ Wp, const T *__restrict__ X, int ldx, float *__restrict__ part,
     int M, int K, int Npad, int ksteps_total, T *__restrict__ act, int F, HeadEpi he) {
     typedef __attribute__((address_space(3))) void *LdsPtr;
-    constexpr int MT = TALL_MT, KCL = TALL_KCL, NST = TALL_NST, MTW = MT / 2;
+    constexpr int KCL = TALL_KCL, NST = TALL_NST, MTW = MT / 2;
     static_assert(KCS % KCL == 0, "a split's k-steps are whole stages");
-    static_assert(KCL == 2 && MTW == 8 && GEMM_NT == 2 && MT == 16, "the schedules below are written for these");
+    static_assert(KCL == 2 && GEMM_NT == 2 && (MT == 16 || MT == 12), "the schedules below are written for these");
     constexpr int XBLKS = KCL * MT, WBLKS = KCL * 4 * GEMM_NT;           // 1 KB blocks of a stage: activations, weights
+    constexpr int XPP = XBLKS / 8;                                       // activation blocks per producer wave
     constexpr int STAGE_UNITS = (XBLKS + WBLKS) * 64;
     constexpr int LPS = (XBLKS + WBLKS) / 8;                             // loads of a producer wave per stage
     __shared__ __attribute__((aligned(1024))) u32x4 xs[NST * STAGE_UNITS];
@@ -483,15 +484,15 @@ __global__ __launch_bounds__(TALL_THREADS) void gemm_tall_kernel(
         for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     if (producer) {
-        // Producer p = wave - 8 brings the blocks p, p + 8, p + 16, p + 24 of the stage's activations (block b = rows
+        // Producer p = wave - 8 brings the blocks p, p + 8, p + 16 (, p + 24) of the stage's activations (block b = rows
         // 8 b .. 8 b + 7, eight lanes per row: the unit that belongs at the lane's position under the swizzle) and the two
         // column tiles of (k-step p / 4, column group p % 4).
         const int pw = wave - 8;
         const int f_row = lane >> 3;
-        const T *x_row[4];
-        int f_k[4];
+        const T *x_row[XPP];
+        int f_k[XPP];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < XPP; ++j) {
             const int m = (pw + 8 * j) * 8 + f_row;
             x_row[j] = X + (size_t)(m < M ? m : M - 1) * ldx;
             f_k[j] = ((lane & 7) ^ tall_x_swizzle(m & 15)) * 8;
@@ -501,7 +502,7 @@ __global__ __launch_bounds__(TALL_THREADS) void gemm_tall_kernel(
         auto fetch = [&](int chunk, int st) {             // stage st <- k-steps chunk KCL .. + KCL - 1
             const unsigned base = lds0 + (unsigned)(st * STAGE_UNITS * 16);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < XPP; ++j) {
                 const int k = chunk * (KCL * GEMM_KSTEP) + f_k[j];
                 lds_dma16(base + (unsigned)((pw + 8 * j) * 1024), x_row[j] + (k < K ? k : 0));
             }
@@ -510,7 +511,7 @@ __global__ __launch_bounds__(TALL_THREADS) void gemm_tall_kernel(
                 lds_dma16(base + (unsigned)((XBLKS + ((pw >> 2) * 4 + (pw & 3)) * GEMM_NT + nt) * 1024),
                           w_src + (size_t)chunk * KCL * (GEMM_NT * 64) + nt * 64);
         };
-        static_assert(LPS == 4 + GEMM_NT && XBLKS == 32, "the fetch above brings exactly one stage");
+        static_assert(LPS == XPP + GEMM_NT && XBLKS == 8 * XPP, "the fetch above brings exactly one stage");
         fetch(chunk0, 0);
         if (chunk0 + 1 < chunk1) { fetch(chunk0 + 1, 1); dma_wait<LPS>(); } else dma_wait<0>();
         __syncthreads();
@@ -547,14 +548,16 @@ __global__ __launch_bounds__(TALL_THREADS) void gemm_tall_kernel(
                 for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < GEMM_NT; ++nt) acc[mt][nt] = Mfma<T>::run(a[ks][mt], w[ks][nt], acc[mt][nt]);
-            __builtin_amdgcn_sched_group_barrier(0x100, GEMM_NT + MTW, 0);
+            constexpr int FR = GEMM_NT + MTW, MF = MTW * GEMM_NT;          // fragments and MFMAs of a k-step
+            static_assert(MF >= FR && MF <= 2 * FR, "one or two MFMAs of the first k-step ahead of every read of the second");
+            __builtin_amdgcn_sched_group_barrier(0x100, FR, 0);
 #pragma unroll
-            for (int i = 0; i < 6; ++i) {                 // 16 MFMAs of the first k-step spread over the 10 reads of the second
+            for (int i = 0; i < MF - FR; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 2 * FR - MF; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
@@ -847,7 +850,7 @@ __global__ __launch_bounds__(256) void epilogue_rope_ranges_kernel(const float *
 // Row count of a partial plane as the kernel instantiation writes it.
 static int gemm_rows_written(int mpad) {
     const int mt = mpad / 16;
-    return (mt <= 2 ? mt : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : 16) * 16;
+    return (mt <= 2 ? mt : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : mt <= 12 ? 12 : 16) * 16;
 }
 
 GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
@@ -857,7 +860,7 @@ GemmShape gemm_plan(int dt, int M, int N, int K, int target_wgs) {
     g.Kpad = gemm_kpad(dt, K);
     g.Mpad = round_up(M < 1 ? 1 : M, 16);
     if (dt == DT_F32) { g.S = 1; return g; }
-    g.Mpad = gemm_rows_written(g.Mpad);       // the kernels are instantiated for 1, 2, 4, 6, 8 or (tall kernel) 16 row tiles
+    g.Mpad = gemm_rows_written(g.Mpad);       // the kernels are instantiated for 1, 2, 4, 6, 8 or (tall kernel) 12, 16 row tiles
     const int n_blocks = g.Npad / GEMM_BLOCK_N;
     const int n_chunks = g.Kpad / GEMM_KCHUNK;
     // One workgroup per CU (256) at most, as many as fit, chunks dealt out evenly: in every sweep more
@@ -955,7 +958,7 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
     }
     const bool fuse_silu = epi.mode == EPI_SILU && g.S == 1;
     const bool head = epi.mode == EPI_HEAD;
-    if (g.Mpad > 128) {                                  // the tall kernel: eight waves, one 128-column tile
+    if (g.Mpad > 128) {                                  // the tall kernel: one 128-column tile of 192 or 256 rows
         HeadEpi he{};
         if (head) he = HeadEpi{epi.head_mode, epi.head_k, g.N, epi.write_logits, epi.seg_out, epi.pv, epi.pi};
         dim3 grid(g.Npad / GEMM_BLOCK_N, g.S), block(TALL_THREADS);
@@ -963,18 +966,21 @@ static void launch_gemm_t(const GemmShape &g, const void *Wp, const void *X, int
         const u32x4 *w = static_cast<const u32x4 *>(Wp);
         const T *x = static_cast<const T *>(X);
         T *act = static_cast<T *>(epi.act);
-#define POSS_TALL_LAUNCH(FUSE, HD, FARG)                                                                      \
+#define POSS_TALL_LAUNCH_MT(MT, FUSE, HD, FARG)                                                               \
     do {                                                                                                      \
         if (ev_start && ev_stop)                                                                              \
-            hipExtLaunchKernelGGL((gemm_tall_kernel<T, FUSE, HD>), grid, block, 0, st, ev_start, ev_stop, 0, w, x, ldx, part, \
+            hipExtLaunchKernelGGL((gemm_tall_kernel<T, MT, FUSE, HD>), grid, block, 0, st, ev_start, ev_stop, 0, w, x, ldx, part, \
                                   g.M, g.K, g.Npad, ksteps, act, FARG, he);                                   \
         else                                                                                                  \
-            hipLaunchKernelGGL((gemm_tall_kernel<T, FUSE, HD>), grid, block, 0, st, w, x, ldx, part, g.M, g.K, g.Npad, \
+            hipLaunchKernelGGL((gemm_tall_kernel<T, MT, FUSE, HD>), grid, block, 0, st, w, x, ldx, part, g.M, g.K, g.Npad, \
                                ksteps, act, FARG, he);                                                        \
     } while (0)
+#define POSS_TALL_LAUNCH(FUSE, HD, FARG)                                                                      \
+    do { if (g.Mpad <= 192) POSS_TALL_LAUNCH_MT(12, FUSE, HD, FARG); else POSS_TALL_LAUNCH_MT(16, FUSE, HD, FARG); } while (0)
         if (fuse_silu) POSS_TALL_LAUNCH(true, false, epi.F);
         else if (head) POSS_TALL_LAUNCH(false, true, 0);
         else POSS_TALL_LAUNCH(false, false, 0);
+#undef POSS_TALL_LAUNCH_MT
 #undef POSS_TALL_LAUNCH
         if (epi.mode == EPI_ROPE_KV) {
             EpiArgs pe = epi;
