@@ -21,8 +21,8 @@
 //     both factors, and the kernel writes SiLU(gate) * up in the storage type itself;
 //   * three kernels share the packed weights, the split rule and the order of every sum, so a row gets bit for bit
 //     the same result from each: the stream kernel (up to 128 rows, bound by the weight stream), the tall kernel
-//     (129..256 rows: several sequences in one stream, prefill; bound by the matrix pipe and the L1/L2 traffic of
-//     its activations) and the QKV kernel with its epilogue inside (up to 32 rows).
+//     (129..256 rows: several sequences in one stream, prefill; bound by what the L2s hand to the CUs, every
+//     workgroup reading all rows of the activations) and the QKV kernel with its epilogue inside (up to 32 rows).
 #include "device_utils.h"
 
 #include <hip/hip_ext.h>
