@@ -213,7 +213,7 @@ def main():
     ap.add_argument("--positions", type=int, default=0, help="override positions per specialist n (sweeps)")
     ap.add_argument("--batch", type=int, default=1,
                     help="sequences per round, up to 8 (the headline metric is quoted at 1); rows of the sequences share the weight "
-                         "streams, 128 rows per launch (beyond that the passes run group by group)")
+                         "streams, 256 rows per launch (beyond that the passes run group by group)")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0: verification draws the target's tokens at this temperature (sampler kernels "
                          "instead of argmax); the headline metric is quoted at 0")

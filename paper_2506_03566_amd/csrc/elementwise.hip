@@ -356,15 +356,27 @@ __device__ __forceinline__ void pick_in_block(DrawLds &L, int b, float rest, boo
     if (lane == 0) L.i[2] = pick;
 }
 
-// the four masses exp((row[id] - mx) * inv_t) of lane's ids in block b (0 beyond the vocabulary)
-__device__ __forceinline__ f32x4e exp_masses(const float *row, int ld, int vocab, int b, int lane, float mx, float inv_t) {
+// the four values row[id] of lane's ids in block b (0 where the row ends)
+__device__ __forceinline__ f32x4e load_ids(const float *row, int ld, int b, int lane) {
     const int id0 = b * DRAW_BLOCK + lane * 4;
     f32x4e v = f32x4e{0.f, 0.f, 0.f, 0.f};
     if (id0 + 3 < ld) v = *reinterpret_cast<const f32x4e *>(row + id0);
+    return v;
+}
+// their masses exp((l - mx) * inv_t) (0 beyond the vocabulary)
+__device__ __forceinline__ f32x4e masses_of(f32x4e v, int vocab, int b, int lane, float mx, float inv_t) {
+    const int id0 = b * DRAW_BLOCK + lane * 4;
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] = id0 + j < vocab ? expf((v[j] - mx) * inv_t) : 0.f;
     return v;
 }
+// the four masses exp((row[id] - mx) * inv_t) of lane's ids in block b
+__device__ __forceinline__ f32x4e exp_masses(const float *row, int ld, int vocab, int b, int lane, float mx, float inv_t) {
+    return masses_of(load_ids(row, ld, b, lane), vocab, b, lane, mx, inv_t);
+}
+// A wave walks the blocks wave, wave + 16, ...: DRAW_UNROLL of them at a time, their loads asked for together (one block
+// after the other, each load waited for, the walk over a 128K-entry row is 31 trips to memory in a row).
+constexpr int DRAW_UNROLL = 4, DRAW_WAVES = DRAW_THREADS / 64;
 
 __device__ __forceinline__ float draw_block_max(float v, DrawLds &L) {
     v = wave_max(v);
@@ -380,12 +392,17 @@ __device__ __forceinline__ float draw_block_max(float v, DrawLds &L) {
 __device__ __forceinline__ float row_max(const float *row, int ld, int vocab, int nblk, DrawLds &L) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     float mx = -INFINITY;
-    for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
-        const int id0 = b * DRAW_BLOCK + lane * 4;
-        if (id0 + 3 < ld) {
-            const f32x4e v = *reinterpret_cast<const f32x4e *>(row + id0);
+    for (int b0 = wave; b0 < nblk; b0 += DRAW_WAVES * DRAW_UNROLL) {
+        f32x4e v[DRAW_UNROLL];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) if (id0 + j < vocab) mx = fmaxf(mx, v[j]);
+        for (int u = 0; u < DRAW_UNROLL; ++u) v[u] = load_ids(row, ld, min(b0 + u * DRAW_WAVES, nblk - 1), lane);
+#pragma unroll
+        for (int u = 0; u < DRAW_UNROLL; ++u) {
+            const int b = b0 + u * DRAW_WAVES, id0 = b * DRAW_BLOCK + lane * 4;
+            if (b < nblk && id0 + 3 < ld) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) if (id0 + j < vocab) mx = fmaxf(mx, v[u][j]);
+            }
         }
     }
     return draw_block_max(mx, L);
@@ -409,10 +426,18 @@ __global__ __launch_bounds__(DRAW_THREADS) void sample_children_kernel(const flo
         }
         return m;
     };
-    for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
-        const f32x4e m = masses(b, lane, 0);
-        const float s = wave_sum(((m[0] + m[1]) + m[2]) + m[3]);
-        if (lane == 0) L.bsum[b] = s;
+    for (int b0 = wave; b0 < nblk; b0 += DRAW_WAVES * DRAW_UNROLL) {
+        f32x4e v[DRAW_UNROLL];
+#pragma unroll
+        for (int u = 0; u < DRAW_UNROLL; ++u) v[u] = load_ids(row, ld, min(b0 + u * DRAW_WAVES, nblk - 1), lane);
+#pragma unroll
+        for (int u = 0; u < DRAW_UNROLL; ++u) {
+            const int b = b0 + u * DRAW_WAVES;
+            if (b >= nblk) break;                         // wave-uniform
+            const f32x4e m = masses_of(v[u], vocab, b, lane, mx, inv_t);
+            const float s = wave_sum(((m[0] + m[1]) + m[2]) + m[3]);
+            if (lane == 0) L.bsum[b] = s;
+        }
     }
     __syncthreads();
     float log_z = 0.f;
@@ -477,10 +502,18 @@ __global__ __launch_bounds__(DRAW_THREADS) void rejection_walk_kernel(TreeDev td
                 if (td.fr_pool[d * k + r] == pv) { e = 1 + (d - 1) * k + r; cbase = k + (d - 1) * k * k + r * k; }
         }
         // block sums of the target's masses P = exp((l - max) / T); zp = their total (p = P / zp)
-        for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
-            const f32x4e m = exp_masses(prow, ld, vocab, b, lane, mp, inv_t);
-            const float s = wave_sum(((m[0] + m[1]) + m[2]) + m[3]);
-            if (lane == 0) L.bsum[b] = s;
+        for (int b0 = wave; b0 < nblk; b0 += DRAW_WAVES * DRAW_UNROLL) {
+            f32x4e v[DRAW_UNROLL];
+#pragma unroll
+            for (int u = 0; u < DRAW_UNROLL; ++u) v[u] = load_ids(prow, ld, min(b0 + u * DRAW_WAVES, nblk - 1), lane);
+#pragma unroll
+            for (int u = 0; u < DRAW_UNROLL; ++u) {
+                const int b = b0 + u * DRAW_WAVES;
+                if (b >= nblk) break;                     // wave-uniform
+                const f32x4e m = masses_of(v[u], vocab, b, lane, mp, inv_t);
+                const float s = wave_sum(((m[0] + m[1]) + m[2]) + m[3]);
+                if (lane == 0) L.bsum[b] = s;
+            }
         }
         __syncthreads();
         if (e < 0) {                                      // no drawn children: the target's own token ends the walk
@@ -498,9 +531,17 @@ __global__ __launch_bounds__(DRAW_THREADS) void rejection_walk_kernel(TreeDev td
         const float *qrow = draft_logits + (size_t)e * ld;
         const float mq = row_max(qrow, ld, vocab, nblk, L);
         float sq = 0.f;                                   // zq: total of the drafter's masses, same block order
-        for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
-            const f32x4e m = exp_masses(qrow, ld, vocab, b, lane, mq, inv_t);
-            sq += ((m[0] + m[1]) + m[2]) + m[3];
+        for (int b0 = wave; b0 < nblk; b0 += DRAW_WAVES * DRAW_UNROLL) {
+            f32x4e v[DRAW_UNROLL];
+#pragma unroll
+            for (int u = 0; u < DRAW_UNROLL; ++u) v[u] = load_ids(qrow, ld, min(b0 + u * DRAW_WAVES, nblk - 1), lane);
+#pragma unroll
+            for (int u = 0; u < DRAW_UNROLL; ++u) {
+                const int b = b0 + u * DRAW_WAVES;
+                if (b >= nblk) break;                     // wave-uniform
+                const f32x4e m = masses_of(v[u], vocab, b, lane, mq, inv_t);
+                sq += ((m[0] + m[1]) + m[2]) + m[3];
+            }
         }
         float zq = block_sum(sq, L.red);
         bool have_resid = false;
@@ -518,20 +559,38 @@ __global__ __launch_bounds__(DRAW_THREADS) void rejection_walk_kernel(TreeDev td
             }
             // rejected: P <- max(P / zp - Q / zq, 0) with its block sums, zp <- their total; the candidate leaves q
             __syncthreads();                              // resid[c] has been read by every thread
-            for (int b = wave; b < nblk; b += DRAW_THREADS / 64) {
-                const int id0 = b * DRAW_BLOCK + lane * 4;
-                const f32x4e pm = have_resid ? resid_masses(b, lane) : exp_masses(prow, ld, vocab, b, lane, mp, inv_t);
-                f32x4e qm = exp_masses(qrow, ld, vocab, b, lane, mq, inv_t);
-                for (int j = 0; j < i; ++j) {
-                    const int r = L.removed[j] - id0;
-                    if (r >= 0 && r < 4) qm[r] = 0.f;
-                }
-                f32x4e r4;
+            for (int b0 = wave; b0 < nblk; b0 += DRAW_WAVES * DRAW_UNROLL) {
+                f32x4e pv[DRAW_UNROLL], qv[DRAW_UNROLL];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) r4[j] = fmaxf(pm[j] / zp - qm[j] / zq, 0.f);
-                if (id0 + 3 < ld) *reinterpret_cast<f32x4e *>(resid + id0) = r4;
-                const float s = wave_sum(((r4[0] + r4[1]) + r4[2]) + r4[3]);
-                if (lane == 0) L.bsum[b] = s;
+                for (int u = 0; u < DRAW_UNROLL; ++u) {
+                    const int b = min(b0 + u * DRAW_WAVES, nblk - 1);
+                    pv[u] = load_ids(have_resid ? resid : prow, ld, b, lane);
+                    qv[u] = load_ids(qrow, ld, b, lane);
+                }
+#pragma unroll
+                for (int u = 0; u < DRAW_UNROLL; ++u) {
+                    const int b = b0 + u * DRAW_WAVES;
+                    if (b >= nblk) break;                 // wave-uniform
+                    const int id0 = b * DRAW_BLOCK + lane * 4;
+                    f32x4e pm = pv[u];
+                    if (have_resid) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) if (id0 + j >= vocab) pm[j] = 0.f;
+                    } else {
+                        pm = masses_of(pm, vocab, b, lane, mp, inv_t);
+                    }
+                    f32x4e qm = masses_of(qv[u], vocab, b, lane, mq, inv_t);
+                    for (int j = 0; j < i; ++j) {
+                        const int r = L.removed[j] - id0;
+                        if (r >= 0 && r < 4) qm[r] = 0.f;
+                    }
+                    f32x4e r4;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) r4[j] = fmaxf(pm[j] / zp - qm[j] / zq, 0.f);
+                    if (id0 + 3 < ld) *reinterpret_cast<f32x4e *>(resid + id0) = r4;
+                    const float s = wave_sum(((r4[0] + r4[1]) + r4[2]) + r4[3]);
+                    if (lane == 0) L.bsum[b] = s;
+                }
             }
             if (tid == 0) L.removed[i] = c;
             __syncthreads();
